@@ -1,0 +1,115 @@
+"""Pins for the oracle's codebook builders and format arithmetic against values the paper prints."""
+import numpy as np
+import pytest
+
+from conftest import load_golden
+from oracle import atoms as A
+import sop_inputs as si
+
+
+def test_nf4_structure_and_ratio():
+    g = load_golden("hosting_ratios.txt")
+    L = A.nf(4)
+    assert L.size == 16 and np.all(np.diff(L) > 0)
+    assert (L < 0).sum() == g["NF4_negative_entries"] and (L > 0).sum() == g["NF4_positive_entries"]
+    assert L[0] == -1.0 and L[-1] == 1.0 and 0.0 in L            # equal endpoints, exact zero
+    assert round(A.hosting_ratio(L), 1) == g["NF4_ratio"]
+    # not closed under negation: negating interior entries does not give entries
+    assert not np.allclose(np.sort(-L), L)
+
+
+def test_nf4_is_gaussian_quantile_grid():
+    # independent statement of the construction: every non-zero entry, un-normalised, is a standard
+    # normal quantile whose probabilities are evenly spaced on each side of 1/2
+    from scipy.stats import norm
+    L = A.nf(4)
+    zmax = norm.ppf(0.5 * ((1 - 1 / 32) + (1 - 1 / 30)))
+    p = norm.cdf(L * zmax)
+    assert np.allclose(np.diff(p[8:]), np.diff(p[8:])[0], rtol=1e-9)      # 0.5 ... delta, 8 steps
+    assert np.allclose(np.diff(p[:8]), np.diff(p[:8])[0], rtol=1e-9)      # 1-delta ... 0.5, 7 steps
+    assert abs(p[7] - 0.5) < 1e-15
+
+
+def test_nf5_ratio():
+    g = load_golden("hosting_ratios.txt")
+    L = A.nf(5)
+    assert L.size == 32 and (L < 0).sum() == 15 and (L > 0).sum() == 16
+    assert round(A.hosting_ratio(L), 1) == g["NF5_ratio"]
+
+
+def test_sh_ratios_and_asymmetry():
+    g = load_golden("hosting_ratios.txt")
+    for n, key in ((4, "SH4_ratio"), (5, "SH5_ratio")):
+        L = A.sh(n)
+        assert L.size == 2 ** n and np.all(np.diff(L) > 0)
+        assert round(A.hosting_ratio(L), 1) == g[key]
+    L = A.sh(4)
+    assert L[0] == -1.0 and abs(L[-1] - (np.sinh(1.5) - 0.02) / (np.sinh(1.5) + 0.02)) < 1e-15
+    # un-normalised grid is exactly sinh(1.5 t) - 0.02 on uniform t
+    t = np.arcsinh(L * (np.sinh(1.5) + 0.02) + 0.02) / 1.5
+    assert np.allclose(np.diff(t), 2 / 15, rtol=1e-9)
+
+
+def test_exmy_grids():
+    g = load_golden("hosting_ratios.txt")
+    e2m3 = A.exmy_grid(2, 3)
+    assert e2m3.size == g["E2M3_distinct_values"]
+    m = A.exmy_magnitudes(2, 3)
+    normals = m[m >= 1.0]
+    assert normals.max() / normals.min() == g["E2M3_normal_ratio"]
+    assert m.max() / m[m > 0].min() == g["E2M3_subnormal_ratio"]
+    assert round(A.exmy_magnitudes(2, 5, reserve_top=True).max(), 2) == g["E2M5_max"]
+
+
+def test_hif_grid_counts():
+    g = load_golden("hosting_ratios.txt")
+    for shifts, nkey, rkey in ((4, "HIF7_values", "HIF7_ratio"), (5, "HIF8_values", "HIF8_ratio")):
+        vals = sorted({c * 2 ** s for c in range(-16, 16) for s in range(shifts)})
+        assert len(vals) == g[nkey]
+        mags = [abs(v) for v in vals if v != 0]
+        assert max(mags) / min(mags) >= g[rkey]      # 16*2^3 = 128 >= 120: ratio quoted on the normal range
+        assert max(v for v in vals) == 15 * 2 ** (shifts - 1) == g[rkey]
+
+
+def test_bpw_identity():
+    for key, val in load_golden("bpw.txt").items():
+        s, g_, b = (int(t) for t in key.split("_"))
+        assert A.bits_per_weight(s, g_, b) == val
+
+
+def test_metabit_count():
+    for key, m in load_golden("scale_words.txt").items():
+        _, b, w, x, y = key.split("_")
+        assert int(b) - int(w) - int(x) - int(y) == m
+
+
+def test_negate():
+    L = A.sh(4)
+    Ln = A.negate(L)
+    assert np.all(np.diff(Ln) > 0) and Ln[0] == -L[-1] and Ln[-1] == 1.0
+    assert np.array_equal(A.negate(Ln), L)
+
+
+def test_lloyd_fixed_point_and_bof_invariants():
+    draws = si.normal_draws(1 << 18, 77)
+    x = A.block_normalise(draws, 16)
+    assert np.isclose(x.reshape(-1, 16).max(axis=1), 1.0).all() and np.abs(x).max() == 1.0
+    cent = A.lloyd_1d(x, None, A.nf(4), 200)
+    # fixed point: each centroid is the mean of its cell
+    mids = 0.5 * (cent[:-1] + cent[1:])
+    cell = np.searchsorted(mids, x, side="left")
+    means = np.bincount(cell, weights=x, minlength=16) / np.bincount(cell, minlength=16)
+    assert np.allclose(cent, means, atol=2e-4)
+    # Lloyd lowers the quantisation MSE of its own training set relative to the start grid
+    def mse(c):
+        m_ = 0.5 * (c[:-1] + c[1:])
+        return np.mean((x - c[np.searchsorted(m_, x, side="left")]) ** 2)
+    assert mse(cent) < mse(A.nf(4))
+    L = A.bof(4, draws)
+    assert L.size == 16 and np.all(np.diff(L) > 0) and L[0] == -1 and L[-1] == 1 and 0.0 in L
+    # weighted Lloyd with weights = integer multiplicities equals unweighted Lloyd on repeated samples
+    xs = x[:4096]
+    wts = (np.arange(xs.size) % 3 + 1).astype(float)
+    a = A.lloyd_1d(xs, wts, A.nf(4), 5)
+    b = A.lloyd_1d(np.repeat(xs, wts.astype(int)), None, A.nf(4), 5)
+    assert np.allclose(a, b, atol=1e-12)
