@@ -1,0 +1,141 @@
+"""Benchmark of the pair-search hot path on one MI355X.
+
+One step = one sop_pair_search call over one synthetic layer (block statistics, scale encode,
+nearest-entry search for every atom, block scores, selector bits of every pair, layer reduction),
+with weights, channel norms and codebook tables already resident in HBM.  The codebook tables are
+built and uploaded once per alphabet before the timed region (they do not depend on the layer).
+
+Workload: the headline configuration -- MLP down-projection 4096 x 11008, bf16 Student-t(4)
+weights, log-normal channel norms, g = 16, UE4M4 block scale, atoms NF4 / SH4 / BOF4 and their sign
+negations, all 15 pairs, selector bits and per-atom / per-pair ACos out.  The layer rotates through
+several distinct weight buffers so consecutive steps cannot be served from the 256 MB last-level
+cache.
+
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+VALU_PEAK_TLOPS = 39.3          # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, one fp32 lane-op per lane per clock
+
+
+def parse_traffic():
+    """Measured HBM bytes per launch from the committed rocprofv3 counter summary, when present."""
+    path = os.path.join(ROOT, "profiles", "search_kernel_c3down_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        line = line.split("#", 1)[0]
+        if "=" in line:
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v)
+            except ValueError:
+                pass
+    if "hbm_bytes_per_launch" in vals:
+        return vals["hbm_bytes_per_launch"]
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--buffers", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2605_14929_amd as sop
+    import sop_inputs as si
+
+    W, c, cfg = si.make_config("C3_down")
+    M, K, g = cfg["M"], cfg["K"], cfg["g"]
+    A = len(cfg["atoms"])
+    P = A * (A - 1) // 2
+    Nb = M * K // g
+    tabs = sop.build_alphabet(cfg["atoms"], bof_draws=si.normal_draws(1 << 20, 4242))
+    fmt = sop.fmt_by_name(cfg["fmt"])
+
+    dev = torch.device("cuda", 0)
+    w0 = torch.from_numpy(W).to(dev).to(torch.bfloat16)
+    bufs = [w0] + [torch.roll(w0, shifts=17 * i, dims=0).contiguous() for i in range(1, args.buffers)]
+    ct = torch.from_numpy(c).to(dev)
+    ctx = sop.Context(0)
+    t0 = time.perf_counter()
+    ctx.set_alphabet(tabs)
+    alphabet_upload_ms = (time.perf_counter() - t0) * 1e3
+    out = ctx.alloc_outputs(M, K, g, emit=False)
+
+    for i in range(args.warmup):
+        ctx.pair_search(bufs[i % len(bufs)], ct, g, fmt, out=out)
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        ctx.pair_search(bufs[i % len(bufs)], ct, g, fmt, out=out)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall / args.steps * 1e3
+    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ev_min_ms = float(np.min([a.elapsed_time(b) for a, b in ev]))
+
+    # algorithmic HBM bytes of one launch: every weight once, the channel norms once, selector
+    # bit planes and the ACos vectors out
+    Wr = (K // g + 31) // 32
+    alg_bytes = M * K * 2 + K * 4 + P * M * Wr * 4 + (A + P) * 8
+    achieved = alg_bytes / (ev_ms * 1e-3) / 1e9
+
+    # last step ran on buffer (steps-1) % n: check it against the oracle when that is buffer 0
+    gpu_pair = out.acos_pair.cpu().numpy()[:P].copy()
+    result = {
+        "metric": "block x atom evaluations/sec", "value": Nb * A / (ms_step * 1e-3), "unit": "block*atom evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C3 down-projection 4096x11008 bf16, g=16, UE4M4, 6 atoms (NF4,SH4,BOF4 and negations), 15 pairs, search mode",
+                   "M": M, "K": K, "g": g, "scale_format": cfg["fmt"], "atoms": list(cfg["atoms"]), "pairs": P,
+                   "weight_dtype": "bf16", "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
+        "layer_latency_ms": ev_ms, "layer_latency_min_ms": ev_min_ms,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": parse_traffic(),
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel": "sopk::search_kernel (+ reduce_kernel)",
+                     "event_ms_per_launch": ev_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import pairsearch as ops
+        rows = M
+        ofmt = ops.make_fmt(fmt.sign_bits, fmt.exp_bits, fmt.man_bits, fmt.container_bits, fmt.bias, fmt.max_code)
+        t0 = time.perf_counter()
+        ref = ops.pair_search(W[:rows], c, tabs, g, ofmt, want_codes=False)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": rows * (K // g) * A / dt, "unit": "block*atom evals/s", "cores": ops.num_threads(),
+                                  "kind": "oracle", "sample": f"the whole layer ({rows} rows), OpenMP over rows, {dt:.2f} s wall"}
+        # parity of the benchmarked configuration in the same run (buffer 0)
+        chk = ctx.pair_search(bufs[0], ct, g, fmt, out=out)
+        torch.cuda.synchronize()
+        d_acos = float(np.max(np.abs(chk.acos_pair.cpu().numpy()[:P] - ref.acos_pair)))
+        sel_ok = bool(np.array_equal(chk.sel_bits.cpu().numpy().view(np.uint32), ref.sel_bits))
+        result["parity_in_run"] = {"max_abs_dACos": d_acos, "selector_bits_equal": sel_ok}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

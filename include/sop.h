@@ -1,0 +1,155 @@
+/*
+ * sop.h -- C boundary of the MI355X pair-search library (libsop_hip.so).
+ *
+ * The library runs the data-parallel core of the per-layer pair search of "Scaled Outer Product"
+ * on one gfx950 GPU: for every block of g consecutive weights along K it derives the absmax block
+ * scale, rounds it into a narrow floating-point scale word, quantises the block to the nearest
+ * entry of every candidate codebook ("atom"), scores the channel-norm-weighted error, sets the
+ * per-block selector bit of every candidate pair and reduces to the per-layer activation-weighted
+ * cosine (ACos) of every atom and pair.
+ *
+ * Conventions common to all calls
+ *   - Every function returns a sop_status; SOP_OK is 0.  Nothing throws or aborts.  After a
+ *     non-zero status sop_last_error() returns a text describing it.
+ *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are memory of the GPU the
+ *     context was created on.  The library never allocates or frees memory the caller sees; it
+ *     owns only a small image of the codebook tables inside the context.
+ *   - sop_pair_search() is asynchronous on the given HIP stream and does no host synchronisation.
+ *     Inputs are read-only; requested outputs are completely overwritten.
+ *   - Block index: block j of row m has index m*(K/g) + j.
+ *   - Weights and channel norms must be finite.
+ */
+#ifndef SOP_H
+#define SOP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SOP_MAX_ATOMS   8     /* atoms in one alphabet                       */
+#define SOP_MAX_ENTRIES 64    /* entries in one atom (n <= 6 bits)           */
+
+typedef enum {
+    SOP_OK = 0,
+    SOP_EINVAL = 1,   /* null pointer, bad enum, misaligned buffer, bad pair list            */
+    SOP_ESHAPE = 2,   /* M or K <= 0, g not in {8,16,32,64}, g does not divide K, ldw < K    */
+    SOP_EATOM  = 3,   /* atom not strictly ascending, < 2 or > 64 entries, not two-sided, NaN*/
+    SOP_EFMT   = 4,   /* scale format or layer shift outside the supported range             */
+    SOP_ENOMEM = 5,   /* workspace too small                                                 */
+    SOP_EHIP   = 6    /* a HIP runtime call failed; see sop_last_error()                     */
+} sop_status;
+
+typedef enum { SOP_F32 = 0, SOP_BF16 = 1 } sop_dtype;
+
+/* Metric of the per-block finishing reassignment (Section "Per-Layer Pair Search", design axis
+ * (ii): block error or ACos).  SOP_SEL_WSE: channel-norm-weighted squared error sum_i c_i (w_i -
+ * w^_i)^2 (default).  SOP_SEL_MSE: unweighted squared error.  SOP_SEL_COS: per-block weighted
+ * cosine. */
+typedef enum { SOP_SEL_WSE = 0, SOP_SEL_COS = 1, SOP_SEL_MSE = 2 } sop_metric;
+
+/* Scale word SwExMy in a b-bit container (Section "Scale Format and Metabit Allocation"): w sign
+ * bits (0 or 1), x exponent bits, y mantissa bits.  Magnitude code q = (e << y) | f has the value
+ * f/2^y * 2^(1-bias) when e == 0 and (1 + f/2^y) * 2^(e-bias) otherwise; every code is finite.
+ * bias < 0 selects the default 2^(x-1)-1; max_code < 0 selects 2^(x+y)-1.  A signed format makes
+ * the search try both signs of the block scale. */
+typedef struct {
+    int sign_bits, exp_bits, man_bits, container_bits;
+    int bias;
+    int max_code;
+} sop_scale_fmt;
+
+/* One codebook: n_entries values, strictly ascending, first negative and last positive.
+ * `values` is a HOST pointer; the table is copied by sop_set_alphabet(). */
+typedef struct {
+    int n_entries;
+    const float* values;
+} sop_atom;
+
+/* Output buffers, all DEVICE memory owned by the caller; a NULL member is not produced.
+ * A = number of atoms, P = number of pairs, N_b = M*K/g, Wr = ceil((K/g)/32). */
+typedef struct {
+    double*   acos_pair;   /* [P]   layer ACos with the per-block selector applied              */
+    double*   acos_atom;   /* [A]   layer ACos of each atom alone                               */
+    uint32_t* sel_bits;    /* [P][M][Wr]  bit (j%32) of word j/32 of row m: 1 = second atom of the
+                              pair reconstructs block j of row m; padding bits are 0            */
+    uint16_t* scale_code;  /* [A][N_b]  bit 15 = negative scale sign taken, low bits = code q   */
+    uint8_t*  codes;       /* one plane per atom, back to back: M*K/2 bytes when the atom has
+                              <= 16 entries (two codes per byte, even element in the low nibble),
+                              M*K bytes otherwise                                               */
+    float*    blk_cos;     /* [A][N_b]  per-block weighted cosine (value, fp32 accuracy)        */
+    float*    blk_err;     /* [A][N_b]  per-block decision score (weighted error; unweighted in
+                              mode SOP_SEL_MSE)                                                 */
+} sop_outputs;
+
+typedef struct sop_ctx sop_ctx;
+
+/* Create a context on GPU `device_ordinal`.  Allocates the device table image (a few KB).
+ * Fails with SOP_EHIP when no usable GPU or HIP runtime is present: there is no CPU fallback. */
+sop_status sop_create(sop_ctx** ctx, int device_ordinal);
+sop_status sop_destroy(sop_ctx* ctx);
+
+/* Install the alphabet (Section "Per-Layer Pair Search": the search runs over an alphabet of
+ * candidate codebooks, each atom and its sign negation being separate candidates).  atoms is a
+ * HOST array of n_atoms <= SOP_MAX_ATOMS descriptors.  Builds value and midpoint tables (midpoint
+ * = binary64 mean of neighbours rounded once to binary32) and uploads them synchronously.
+ * Resets the pair list to all pairs a < b in lexicographic order. */
+sop_status sop_set_alphabet(sop_ctx* ctx, const sop_atom* atoms, int n_atoms);
+
+/* Choose the candidate pairs: HOST array of P pairs (a, b) with a < b, no duplicates.
+ * P = 0 (or pair_ab NULL) restores the default of all pairs.  Output index = position here. */
+sop_status sop_set_pairs(sop_ctx* ctx, const int* pair_ab, int n_pairs);
+
+/* Bytes of DEVICE workspace sop_pair_search() needs for this shape (partial sums of the layer
+ * reduction).  The workspace needs no initialisation and 256-byte alignment. */
+sop_status sop_workspace_bytes(sop_ctx* ctx, int64_t M, int64_t K, int g, size_t* bytes);
+
+/* The per-layer search (Section "Block Scaling": absmax scale and round_q; Section "Scale Format
+ * and Metabit Allocation": scale word and per-layer shift; Section "Activation-Weighted Cosine
+ * Similarity": ACos; Section "Per-Layer Pair Search", step 4: finishing reassignment).
+ *   W_dev       DEVICE, M rows of K elements, row stride ldw elements, dtype fp32 or bf16;
+ *               base pointer and row stride must be multiples of 16 bytes
+ *   c_dev       DEVICE, K channel norms (fp32, >= 0), 16-byte aligned
+ *   g           block size along K: 8, 16, 32 or 64; must divide K
+ *   fmt         scale word format; layer_shift_k multiplies every ideal block scale by 2^k before
+ *               rounding and divides the decoded scale by it (|k| <= 64)
+ *   metric      SOP_SEL_WSE or SOP_SEL_MSE (SOP_SEL_COS is reported as SOP_EINVAL by this build)
+ *   workspace   DEVICE, at least sop_workspace_bytes() bytes
+ *   out         HOST pointer to the struct of DEVICE output pointers
+ *   hip_stream  a hipStream_t (NULL = the default stream)
+ * Arguments are validated before anything is launched.  Calls on one context must not overlap
+ * with sop_set_alphabet / sop_set_pairs; calls on different streams need different workspaces. */
+sop_status sop_pair_search(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                           const float* c_dev, int g, sop_scale_fmt fmt, int layer_shift_k, sop_metric metric,
+                           void* workspace_dev, size_t workspace_bytes, const sop_outputs* out, void* hip_stream);
+
+/* Text of the last error on this context (or of the last failed sop_create when ctx is NULL). */
+const char* sop_last_error(sop_ctx* ctx);
+
+/* ---- host-side atom builders (Section "Per-Layer Pair Search", alphabet list; Section "Primary
+ * Formats" for the sinh grid).  `out` is a HOST array of 2^n_bits floats, ascending. ---- */
+
+/* NormalFloat grid: Gaussian quantiles, 2^(n-1) positive and 2^(n-1)-1 negative entries plus an
+ * exact zero, endpoints -1 and +1.  n_bits in 2..6. */
+sop_status sop_atom_nf(int n_bits, float* out);
+/* Sinh grid sinh(alpha t) + c on 2^n uniform t in [-1,1], divided by its largest magnitude
+ * (the paper uses alpha = 1.5, c = -0.02). */
+sop_status sop_atom_sh(int n_bits, double alpha, double c, float* out);
+/* Sign-negated atom, re-sorted ascending.  in and out may not overlap. */
+sop_status sop_atom_negate(const float* in, int n_entries, float* out);
+/* Weighted 1-D Lloyd iteration on HOST samples (weights may be NULL = uniform): each sample goes
+ * to its nearest centroid (ties to the lower), every centroid moves to the weighted mean of its
+ * cell, empty cells stay; `centroids` holds the start grid on entry and the result on return. */
+sop_status sop_lloyd_1d(const double* samples, const double* weights, int64_t n_samples,
+                        double* centroids, int n_centroids, int iters);
+/* Block-optimum-fitted grid: the n_draws HOST N(0,1) draws are cut into blocks of g, each block
+ * is divided by its signed absmax element, Lloyd runs from the NormalFloat grid; afterwards the
+ * endpoints are set to -1 and +1 and the entry nearest zero to 0. */
+sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g, int iters, float* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOP_H */

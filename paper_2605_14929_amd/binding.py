@@ -1,0 +1,270 @@
+"""ctypes binding of include/sop.h.  Names follow the C entry points; no arithmetic lives here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+F32, BF16 = 0, 1
+SEL_WSE, SEL_COS, SEL_MSE = 0, 1, 2
+MAX_ATOMS, MAX_ENTRIES = 8, 64
+_STATUS = {1: "SOP_EINVAL", 2: "SOP_ESHAPE", 3: "SOP_EATOM", 4: "SOP_EFMT", 5: "SOP_ENOMEM", 6: "SOP_EHIP"}
+
+
+class SopError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {text}")
+        self.status = status
+
+
+class ScaleFmt(C.Structure):
+    """sop_scale_fmt: SwExMy scale word in a b-bit container."""
+    _fields_ = [("sign_bits", C.c_int), ("exp_bits", C.c_int), ("man_bits", C.c_int), ("container_bits", C.c_int),
+                ("bias", C.c_int), ("max_code", C.c_int)]
+
+
+class _Atom(C.Structure):
+    _fields_ = [("n_entries", C.c_int), ("values", C.POINTER(C.c_float))]
+
+
+class _Outputs(C.Structure):
+    _fields_ = [("acos_pair", C.c_void_p), ("acos_atom", C.c_void_p), ("sel_bits", C.c_void_p),
+                ("scale_code", C.c_void_p), ("codes", C.c_void_p), ("blk_cos", C.c_void_p), ("blk_err", C.c_void_p)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libsop_hip.so")
+
+
+_lib = None
+
+
+def lib():
+    """Load libsop_hip.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise SopError(6, f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(the pair search has no CPU fallback)")
+        # PyTorch ships its own HIP runtime; two HIP runtimes in one process cannot both own the GPU.
+        # Importing torch first makes the loader resolve this library's libamdhip64.so.7 dependency
+        # to the copy torch already mapped (same soname), so both sides share one runtime.
+        import torch  # noqa: F401
+        L = C.CDLL(path)
+        L.sop_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
+        L.sop_destroy.argtypes = [C.c_void_p]
+        L.sop_set_alphabet.argtypes = [C.c_void_p, C.POINTER(_Atom), C.c_int]
+        L.sop_set_pairs.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.c_int]
+        L.sop_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
+        L.sop_pair_search.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
+                                      ScaleFmt, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(_Outputs), C.c_void_p]
+        L.sop_last_error.argtypes = [C.c_void_p]
+        L.sop_last_error.restype = C.c_char_p
+        L.sop_atom_nf.argtypes = [C.c_int, C.POINTER(C.c_float)]
+        L.sop_atom_sh.argtypes = [C.c_int, C.c_double, C.c_double, C.POINTER(C.c_float)]
+        L.sop_atom_negate.argtypes = [C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_float)]
+        L.sop_lloyd_1d.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int64, C.POINTER(C.c_double), C.c_int, C.c_int]
+        L.sop_atom_bof.argtypes = [C.c_int, C.POINTER(C.c_double), C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float)]
+        _lib = L
+    return _lib
+
+
+def _fp(a, t=C.c_float):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+def _check(status, ctx=None):
+    if status != 0:
+        raise SopError(status, (lib().sop_last_error(ctx) or b"").decode())
+
+
+# ---- host atom builders (C implementations) ----
+def sop_atom_nf(n_bits: int) -> np.ndarray:
+    out = np.empty(2 ** n_bits, dtype=np.float32)
+    _check(lib().sop_atom_nf(n_bits, _fp(out)))
+    return out
+
+
+def sop_atom_sh(n_bits: int, alpha: float = 1.5, c: float = -0.02) -> np.ndarray:
+    out = np.empty(2 ** n_bits, dtype=np.float32)
+    _check(lib().sop_atom_sh(n_bits, alpha, c, _fp(out)))
+    return out
+
+
+def sop_atom_negate(values: np.ndarray) -> np.ndarray:
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    out = np.empty_like(v)
+    _check(lib().sop_atom_negate(_fp(v), v.size, _fp(out)))
+    return out
+
+
+def sop_lloyd_1d(samples: np.ndarray, weights, init: np.ndarray, iters: int) -> np.ndarray:
+    x = np.ascontiguousarray(samples, dtype=np.float64)
+    w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float64)
+    cent = np.array(init, dtype=np.float64).copy()
+    _check(lib().sop_lloyd_1d(_fp(x, C.c_double), None if w is None else _fp(w, C.c_double), x.size, _fp(cent, C.c_double), cent.size, iters))
+    return cent
+
+
+def sop_atom_bof(n_bits: int, draws: np.ndarray, g: int = 16, iters: int = 50) -> np.ndarray:
+    d = np.ascontiguousarray(draws, dtype=np.float64)
+    out = np.empty(2 ** n_bits, dtype=np.float32)
+    _check(lib().sop_atom_bof(n_bits, _fp(d, C.c_double), d.size, g, iters, _fp(out)))
+    return out
+
+
+_FMTS = {
+    "UE4M4": (0, 4, 4, 8, -1, -1), "E4M3": (1, 4, 3, 8, -1, -1), "UE4M3": (0, 4, 3, 8, -1, -1),
+    "UE4M6": (0, 4, 6, 10, -1, -1), "E4M5": (1, 4, 5, 10, -1, -1), "UE5M7": (0, 5, 7, 12, -1, -1),
+    "E5M6": (1, 5, 6, 12, -1, -1), "E4M7": (1, 4, 7, 12, -1, -1), "S1E5M5": (1, 5, 5, 12, -1, -1),
+    "S0E6M5": (0, 6, 5, 12, -1, -1), "UE5M3": (0, 5, 3, 8, -1, -1),
+    # bf16-like 16-bit scale kept inside binary32's normal range (values 2^-125 .. < 2^126)
+    "E8M7": (1, 8, 7, 16, 119, 244 * 128 + 127),
+}
+
+
+def fmt_by_name(name: str) -> ScaleFmt:
+    return ScaleFmt(*_FMTS[name])
+
+
+def build_alphabet(names, bof_draws=None) -> list:
+    """Tables for names such as "NF4", "SH5", "BOF4", "-NF4" using the library's own builders."""
+    out = []
+    for nm in names:
+        neg = nm.startswith("-")
+        base = nm[1:] if neg else nm
+        kind, n = base[:-1], int(base[-1])
+        if kind == "NF":
+            t = sop_atom_nf(n)
+        elif kind == "SH":
+            t = sop_atom_sh(n)
+        elif kind == "BOF":
+            if bof_draws is None:
+                raise ValueError("BOF atoms need N(0,1) draws")
+            t = sop_atom_bof(n, bof_draws)
+        else:
+            raise ValueError(f"unknown atom {nm}")
+        out.append(sop_atom_negate(t) if neg else t)
+    return out
+
+
+@dataclass
+class Outputs:
+    """Device tensors produced by Context.pair_search (None when not requested)."""
+    acos_pair: object = None
+    acos_atom: object = None
+    sel_bits: object = None
+    scale_code: object = None
+    codes: object = None
+    code_planes: list = None
+    blk_cos: object = None
+    blk_err: object = None
+
+
+class Context:
+    """sop_ctx with PyTorch tensors for device memory and the current stream."""
+
+    def __init__(self, device: int = 0):
+        self._h = C.c_void_p()
+        _check(lib().sop_create(C.byref(self._h), device))
+        self.device = device
+        self.n_atoms = 0
+        self.n_entries = []
+        self.n_pairs = 0
+        self._ws = None
+
+    def close(self):
+        if self._h:
+            lib().sop_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_alphabet(self, tables):
+        tabs = [np.ascontiguousarray(t, dtype=np.float32) for t in tables]
+        arr = (_Atom * len(tabs))()
+        for i, t in enumerate(tabs):
+            arr[i].n_entries = t.size
+            arr[i].values = _fp(t)
+        _check(lib().sop_set_alphabet(self._h, arr, len(tabs)), self._h)
+        self.n_atoms = len(tabs)
+        self.n_entries = [t.size for t in tabs]
+        self.n_pairs = self.n_atoms * (self.n_atoms - 1) // 2
+
+    def set_pairs(self, pairs):
+        if pairs is None or len(pairs) == 0:
+            _check(lib().sop_set_pairs(self._h, None, 0), self._h)
+            self.n_pairs = self.n_atoms * (self.n_atoms - 1) // 2
+            return
+        p = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        _check(lib().sop_set_pairs(self._h, _fp(p, C.c_int), p.shape[0]), self._h)
+        self.n_pairs = p.shape[0]
+
+    def workspace_bytes(self, M, K, g) -> int:
+        n = C.c_size_t()
+        _check(lib().sop_workspace_bytes(self._h, M, K, g, C.byref(n)), self._h)
+        return n.value
+
+    def alloc_outputs(self, M, K, g, emit=False, sel=True) -> Outputs:
+        """Allocate output tensors for a layer (device memory comes from PyTorch)."""
+        import torch
+        dev = torch.device("cuda", self.device)
+        A, P, Bk = self.n_atoms, self.n_pairs, K // g
+        Nb, Wr = M * Bk, (Bk + 31) // 32
+        o = Outputs()
+        o.acos_atom = torch.empty(A, dtype=torch.float64, device=dev)
+        o.acos_pair = torch.empty(max(P, 1), dtype=torch.float64, device=dev)
+        if sel and P:
+            o.sel_bits = torch.empty((P, M, Wr), dtype=torch.int32, device=dev)
+        if emit:
+            o.scale_code = torch.empty((A, Nb), dtype=torch.int16, device=dev)
+            planes = [M * K // 2 if n <= 16 else M * K for n in self.n_entries]
+            o.codes = torch.empty(sum(planes), dtype=torch.uint8, device=dev)
+            offs = np.concatenate([[0], np.cumsum(planes)])
+            o.code_planes = [o.codes[int(offs[a]):int(offs[a + 1])] for a in range(A)]
+            o.blk_cos = torch.empty((A, Nb), dtype=torch.float32, device=dev)
+            o.blk_err = torch.empty((A, Nb), dtype=torch.float32, device=dev)
+        return o
+
+    def pair_search(self, W, c, g, fmt: ScaleFmt, k: int = 0, metric: int = SEL_WSE, out: Outputs = None,
+                    emit: bool = False, stream=None) -> Outputs:
+        """sop_pair_search on torch CUDA tensors: W [M,K] float32 or bfloat16 (row stride = W.stride(0)),
+        c [K] float32.  Asynchronous on the current (or given) stream."""
+        import torch
+        if not (W.is_cuda and c.is_cuda):
+            raise SopError(1, "W and c must be CUDA tensors (no CPU fallback)")
+        if W.dim() != 2 or W.stride(1) != 1:
+            raise SopError(2, "W must be a 2-D tensor with contiguous rows")
+        if W.dtype == torch.bfloat16:
+            dt = BF16
+        elif W.dtype == torch.float32:
+            dt = F32
+        else:
+            raise SopError(1, "W must be float32 or bfloat16")
+        if c.dtype != torch.float32 or not c.is_contiguous():
+            raise SopError(1, "c must be a contiguous float32 tensor")
+        M, K = W.shape
+        if out is None:
+            out = self.alloc_outputs(M, K, g, emit=emit)
+        need = self.workspace_bytes(M, K, g)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=W.device)
+        st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
+
+        def ptr(t):
+            return None if t is None else C.c_void_p(t.data_ptr())
+
+        o = _Outputs(ptr(out.acos_pair), ptr(out.acos_atom), ptr(out.sel_bits), ptr(out.scale_code), ptr(out.codes),
+                     ptr(out.blk_cos), ptr(out.blk_err))
+        _check(lib().sop_pair_search(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
+                                     fmt, k, metric, C.c_void_p(self._ws.data_ptr()), self._ws.numel(), C.byref(o),
+                                     C.c_void_p(st)), self._h)
+        return out

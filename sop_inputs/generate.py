@@ -71,8 +71,8 @@ E5M6 = (1, 5, 6, 12, -1, -1)
 E4M7 = (1, 4, 7, 12, -1, -1)
 S1E5M5 = (1, 5, 5, 12, -1, -1)
 # bf16-like 16-bit signed scale.  Bias and top code are chosen so that every scale value and its
-# reciprocal stay inside fp32's normal range (values 2^-125 .. just under 2^127).
-E8M7 = (1, 8, 7, 16, 119, 245 * 128 + 127)
+# reciprocal stay inside fp32's normal range (values 2^-125 .. just under 2^126).
+E8M7 = (1, 8, 7, 16, 119, 244 * 128 + 127)
 
 SCALE_FORMATS = {
     "UE4M4": UE4M4, "E4M3": E4M3, "UE4M6": UE4M6, "E4M5": E4M5, "UE5M7": UE5M7,

@@ -1,0 +1,60 @@
+"""CPU-side checks of the C boundary: the library loads, exports what include/sop.h declares,
+rejects work when no GPU is present, and its host atom builders agree with the oracle's."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_14929_amd as sop
+from oracle import atoms as OA
+import sop_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sop_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert {"sop_create", "sop_destroy", "sop_set_alphabet", "sop_set_pairs", "sop_workspace_bytes",
+            "sop_pair_search", "sop_last_error"} <= set(names)
+    L = sop.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_create_without_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(sop.SopError) as e:
+        sop.Context(0)
+    assert e.value.status == 6 and "no CPU fallback" in str(e.value)
+
+
+def test_host_atom_builders_match_oracle_builders():
+    for n in (3, 4, 5, 6):
+        assert np.array_equal(sop.sop_atom_nf(n), OA.to_f32(OA.nf(n)))
+        assert np.array_equal(sop.sop_atom_sh(n), OA.to_f32(OA.sh(n)))
+    L = sop.sop_atom_sh(4)
+    assert np.array_equal(sop.sop_atom_negate(L), OA.to_f32(OA.negate(L)))
+    draws = si.normal_draws(1 << 16, 9)
+    assert np.allclose(sop.sop_atom_bof(4, draws, 16, 20), OA.to_f32(OA.bof(4, draws, 16, 20)), rtol=0, atol=1e-6)
+    x = OA.block_normalise(draws, 16)
+    w = np.abs(si.normal_draws(x.size, 10)) + 0.1
+    a = sop.sop_lloyd_1d(x, w, OA.nf(4), 7)
+    b = OA.lloyd_1d(x, w, OA.nf(4), 7)
+    assert np.allclose(a, b, rtol=0, atol=1e-9)
+
+
+def test_builder_argument_errors():
+    out = (C.c_float * 16)()
+    assert sop.lib().sop_atom_nf(9, out) == 1
+    assert sop.lib().sop_atom_nf(4, None) == 1
+    assert sop.lib().sop_atom_sh(4, -1.0, 0.0, out) == 1

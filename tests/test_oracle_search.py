@@ -9,8 +9,8 @@ import pytest
 from oracle import atoms as A, pairsearch as ps
 import sop_inputs as si
 
-WIDE = ps.make_fmt(1, 8, 7, bias=119, max_code=245 * 128 + 127)     # fine scale grid, signed
-WIDE_U = ps.make_fmt(0, 8, 7, bias=119, max_code=245 * 128 + 127)
+WIDE = ps.make_fmt(1, 8, 7, bias=119, max_code=244 * 128 + 127)     # fine scale grid, signed
+WIDE_U = ps.make_fmt(0, 8, 7, bias=119, max_code=244 * 128 + 127)
 UE4M4 = ps.make_fmt(0, 4, 4)
 E4M3 = ps.make_fmt(1, 4, 3)
 
