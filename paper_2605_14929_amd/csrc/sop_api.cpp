@@ -1,4 +1,4 @@
-// Host side of libsop_hip.so: context, argument validation, table image, launch parameters, and
+// Host side of libsop_hip.so: context, argument validation, table images, launch parameters, and
 // the host atom builders.  See include/sop.h for the contract of every entry point.
 #include "../../include/sop.h"
 
@@ -9,22 +9,47 @@
 #include <cstdio>
 #include <cstring>
 #include <limits>
+#include <map>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "sop_kparams.h"
 
-extern "C" hipError_t sopk_launch(const KParams* p, int is_bf16, int g, int is_signed, int metric, int emit, void* stream);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int metric, int emit);
+extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit);
+extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
+
+namespace {
+
+struct ScaleTab { float2* dev = nullptr; int n = 0; };
+
+uint32_t f2u(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+float u2f(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
+// order-preserving map between finite floats and integers
+int64_t ford(float f) { const uint32_t u = f2u(f); return (u & 0x80000000u) ? -(int64_t)(u & 0x7FFFFFFFu) : (int64_t)u; }
+float funord(int64_t k) { return k < 0 ? u2f(0x80000000u | (uint32_t)(-k)) : u2f((uint32_t)k); }
+
+}  // namespace
 
 struct sop_ctx {
     int device = 0;
+    int n_cu = 0;
     int n_atoms = 0, n_pairs = 0;
-    int nent[SOP_K_MAXA] = {0};
-    float tpos[SOP_K_MAXA] = {0}, tneg[SOP_K_MAXA] = {0};
-    int half0[SOP_K_MAXA] = {0};
+    // caller's order
+    std::vector<std::vector<float>> tables;
     int pairs[2 * SOP_K_MAXP] = {0};
-    float* d_tab = nullptr;          // [2][MAXA][TAB]: midpoints then values
-    long long target_waves = 0;
+    // internal order: atoms of one scale group (equal endpoints) adjacent
+    int order[SOP_K_MAXA] = {0};          // internal index -> caller's index
+    int grp_first[SOP_K_MAXA] = {0};
+    float tpos[SOP_K_MAXA] = {0}, tneg[SOP_K_MAXA] = {0}, bin_sc[SOP_K_MAXA] = {0}, bin_off[SOP_K_MAXA] = {0};
+    int nent[SOP_K_MAXA] = {0};
+    int n_bins = 0;
+    BinRec* d_bins = nullptr;             // [MAXA][MAXBINS] capacity
+    std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
+    int occ_blocks[128];                  // resident workgroups per CU of each kernel variant (0 = unknown)
+    size_t occ_lds[128];
+    long long waves_override = 0;
     std::string err;
 };
 
@@ -40,6 +65,16 @@ static sop_status hipfail(sop_ctx* c, hipError_t e, const char* what)
     return fail(c, SOP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+namespace {
+struct DeviceGuard {
+    int prev = 0;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceGuard(int dev) { (void)hipGetDevice(&prev); if (prev != dev) { err = hipSetDevice(dev); switched = err == hipSuccess; } }
+    ~DeviceGuard() { if (switched) (void)hipSetDevice(prev); }
+};
+}  // namespace
+
 extern "C" const char* sop_last_error(sop_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
 
 extern "C" sop_status sop_create(sop_ctx** out, int device)
@@ -50,19 +85,17 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess || n <= 0) return fail(nullptr, SOP_EHIP, "sop_create: no HIP device available (there is no CPU fallback)");
     if (device < 0 || device >= n) return fail(nullptr, SOP_EINVAL, "sop_create: device ordinal out of range");
-    int prev = 0;
-    (void)hipGetDevice(&prev);
-    if ((e = hipSetDevice(device)) != hipSuccess) return hipfail(nullptr, e, "hipSetDevice");
+    DeviceGuard guard(device);
+    if (guard.err != hipSuccess) return hipfail(nullptr, guard.err, "hipSetDevice");
     sop_ctx* c = new sop_ctx();
     c->device = device;
+    std::memset(c->occ_blocks, 0, sizeof(c->occ_blocks));
+    std::memset(c->occ_lds, 0, sizeof(c->occ_lds));
     hipDeviceProp_t prop;
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipGetDeviceProperties"); }
-    // one range of (strip,row) steps per resident wavefront: 4 SIMDs per CU, a few waves per SIMD
-    long long wps = 4;
-    if (const char* s = getenv("SOP_WAVES_PER_SIMD")) { long long v = atoll(s); if (v >= 1 && v <= 16) wps = v; }
-    c->target_waves = (long long)prop.multiProcessorCount * 4 * wps;
-    if ((e = hipMalloc((void**)&c->d_tab, sizeof(float) * 2 * SOP_K_MAXA * SOP_K_TAB)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
-    (void)hipSetDevice(prev);
+    c->n_cu = prop.multiProcessorCount;
+    if (const char* s = getenv("SOP_WAVES_PER_SIMD")) { long long v = atoll(s); if (v >= 1 && v <= 8) c->waves_override = v; }
+    if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXA * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
     *out = c;
     return SOP_OK;
 }
@@ -70,7 +103,11 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
 extern "C" sop_status sop_destroy(sop_ctx* c)
 {
     if (!c) return SOP_OK;
-    if (c->d_tab) (void)hipFree(c->d_tab);
+    {
+        DeviceGuard guard(c->device);
+        if (c->d_bins) (void)hipFree(c->d_bins);
+        for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
+    }
     delete c;
     return SOP_OK;
 }
@@ -83,15 +120,63 @@ static void default_pairs(sop_ctx* c)
     c->n_pairs = p;
 }
 
+// Bin of a scaled weight, exactly as the kernel computes it (clamp, one fma, mask of the bits above
+// the four fraction bits of the magic-number sum).
+static int bin_of(float x, float xl, float xh, float sc, float off, int n_bins)
+{
+    const float xc = std::fmin(std::fmax(x, xl), xh);
+    const float t = std::fmaf(xc, sc, off);
+    return (int)((f2u(t) >> 4) & (uint32_t)(n_bins - 1));
+}
+
+// Build the bin records of one atom; false when some bin would hold two code boundaries.
+static bool build_bins(const std::vector<float>& L, float xl, float xh, float sc, float off, int n_bins, BinRec* rec)
+{
+    const int N = (int)L.size();
+    std::vector<float> mid(N - 1);
+    for (int j = 0; j + 1 < N; ++j) mid[j] = (float)(((double)L[j] + (double)L[j + 1]) * 0.5);
+    auto code_of = [&](float x) { int c = 0; for (int j = 0; j + 1 < N; ++j) c += x > mid[j]; return c; };
+    // first[j] = smallest float in [xl, xh] whose bin is >= j (bins are monotone in x)
+    std::vector<float> first(n_bins + 1);
+    first[0] = xl;
+    for (int j = 1; j <= n_bins; ++j) {
+        if (bin_of(xh, xl, xh, sc, off, n_bins) < j) { first[j] = std::numeric_limits<float>::infinity(); continue; }
+        int64_t lo = ford(first[j - 1]), hi = ford(xh);              // bin(lo) may be < j, bin(hi) >= j
+        if (bin_of(funord(lo), xl, xh, sc, off, n_bins) >= j) { first[j] = funord(lo); continue; }
+        while (hi - lo > 1) {
+            const int64_t m = lo + (hi - lo) / 2;
+            if (bin_of(funord(m), xl, xh, sc, off, n_bins) >= j) hi = m; else lo = m;
+        }
+        first[j] = funord(hi);
+    }
+    for (int j = 0; j < n_bins; ++j) {
+        // floats of bin j: [first[j], pred(first[j+1])]; below xl everything falls in the first bin,
+        // above xh in the bin of xh
+        int c0, c1;
+        const bool empty = !(first[j] < first[j + 1]);
+        if (empty) { c0 = c1 = code_of(std::isinf(first[j]) ? xh : first[j]); }
+        else {
+            c0 = j == 0 ? 0 : code_of(first[j]);
+            const float last = std::isinf(first[j + 1]) ? std::numeric_limits<float>::infinity()
+                                                         : std::nextafter(first[j + 1], -std::numeric_limits<float>::infinity());
+            c1 = std::isinf(last) ? N - 1 : code_of(last);
+            if (bin_of(xh, xl, xh, sc, off, n_bins) == j) c1 = N - 1;       // the bin of xh also receives everything above
+        }
+        if (c1 - c0 > 1) return false;
+        rec[j].thr = c1 > c0 ? mid[c0] : std::numeric_limits<float>::infinity();
+        rec[j].ylo = L[c0];
+        rec[j].yhi = L[c1];
+        rec[j].code_lo = c0;
+    }
+    return true;
+}
+
 extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms)
 {
     if (!c) return SOP_EINVAL;
     if (!atoms) return fail(c, SOP_EINVAL, "sop_set_alphabet: atoms is NULL");
     if (n_atoms < 1 || n_atoms > SOP_K_MAXA) return fail(c, SOP_EATOM, "sop_set_alphabet: 1..8 atoms supported");
-    std::vector<float> img(2 * SOP_K_MAXA * SOP_K_TAB, 0.0f);
-    float* mid = img.data();
-    float* val = img.data() + SOP_K_MAXA * SOP_K_TAB;
-    for (int i = 0; i < SOP_K_MAXA * SOP_K_TAB; ++i) mid[i] = std::numeric_limits<float>::infinity();
+    std::vector<std::vector<float>> tabs(n_atoms);
     for (int a = 0; a < n_atoms; ++a) {
         const int N = atoms[a].n_entries;
         const float* L = atoms[a].values;
@@ -102,23 +187,51 @@ extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_
             if (j && !(L[j - 1] < L[j])) return fail(c, SOP_EATOM, "sop_set_alphabet: atom entries must be strictly ascending");
         }
         if (!(L[0] < 0.0f && L[N - 1] > 0.0f)) return fail(c, SOP_EATOM, "sop_set_alphabet: an atom must have a negative first and a positive last entry");
-        int npad = 2;
-        while (npad < N) npad <<= 1;
-        for (int j = 0; j < N; ++j) val[a * SOP_K_TAB + j] = L[j];
-        for (int j = N; j < SOP_K_TAB; ++j) val[a * SOP_K_TAB + j] = L[N - 1];
-        for (int j = 0; j + 1 < N; ++j) mid[a * SOP_K_TAB + j] = (float)(((double)L[j] + (double)L[j + 1]) * 0.5);
-        c->nent[a] = N;
-        c->half0[a] = npad / 2;
-        c->tpos[a] = L[N - 1];
-        c->tneg[a] = -L[0];
+        tabs[a].assign(L, L + N);
     }
-    int prev = 0;
-    (void)hipGetDevice(&prev);
-    hipError_t e = hipSetDevice(c->device);
-    if (e == hipSuccess) e = hipMemcpy(c->d_tab, img.data(), img.size() * sizeof(float), hipMemcpyHostToDevice);
-    (void)hipSetDevice(prev);
-    if (e != hipSuccess) return hipfail(c, e, "upload of the table image");
+    // scale groups: equal endpoints; internal order = groups by first appearance
+    int order[SOP_K_MAXA], grp_first[SOP_K_MAXA], n = 0;
+    bool used[SOP_K_MAXA] = {false};
+    for (int a = 0; a < n_atoms; ++a) {
+        if (used[a]) continue;
+        for (int b = a; b < n_atoms; ++b)
+            if (!used[b] && tabs[b].front() == tabs[a].front() && tabs[b].back() == tabs[a].back()) {
+                used[b] = true; grp_first[n] = (b == a); order[n++] = b;
+            }
+    }
+    // smallest bin count for which every bin of every atom holds at most one code boundary
+    std::vector<BinRec> img;
+    int n_bins = 0;
+    float sc[SOP_K_MAXA], off[SOP_K_MAXA];
+    for (int nb = 16; nb <= SOP_K_MAXBINS && !n_bins; nb <<= 1) {
+        img.assign((size_t)n_atoms * nb, BinRec{});
+        bool ok = true;
+        for (int i = 0; i < n_atoms && ok; ++i) {
+            const std::vector<float>& L = tabs[order[i]];
+            const float xl = L.front(), xh = L.back();
+            sc[i] = (float)(((double)nb - 0.5) / ((double)xh - (double)xl));
+            off[i] = (float)((double)SOP_K_BIN_MAGIC + 0.25 - (double)xl * (double)sc[i]);
+            ok = build_bins(L, xl, xh, sc[i], off[i], nb, img.data() + (size_t)i * nb);
+        }
+        if (ok) n_bins = nb;
+    }
+    if (!n_bins) return fail(c, SOP_EATOM, "sop_set_alphabet: atom entries are too closely spaced (two code boundaries within 1/1024 of the atom's range)");
+    {
+        DeviceGuard guard(c->device);
+        hipError_t e = guard.err;
+        if (e == hipSuccess) e = hipMemcpy(c->d_bins, img.data(), img.size() * sizeof(BinRec), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return hipfail(c, e, "upload of the table image");
+    }
+    c->tables.swap(tabs);
     c->n_atoms = n_atoms;
+    c->n_bins = n_bins;
+    for (int i = 0; i < n_atoms; ++i) {
+        const std::vector<float>& L = c->tables[order[i]];
+        c->order[i] = order[i]; c->grp_first[i] = grp_first[i];
+        c->tpos[i] = L.back(); c->tneg[i] = -L.front(); c->nent[i] = (int)L.size();
+        c->bin_sc[i] = sc[i]; c->bin_off[i] = off[i];
+    }
+    std::memset(c->occ_blocks, 0, sizeof(c->occ_blocks));
     default_pairs(c);
     return SOP_OK;
 }
@@ -149,25 +262,44 @@ static sop_status shape_check(sop_ctx* c, int64_t M, int64_t K, int g)
     return SOP_OK;
 }
 
-static long long plan_waves(const sop_ctx* c, int64_t M, int64_t K, int g)
-{
-    const int epl = g < 16 ? g : 16;
-    const long long lanes = K / epl, strips = (lanes + 63) / 64, units = strips * M;
-    long long w = std::min<long long>(c->target_waves, units);
-    w = (w + 3) / 4 * 4;
-    return std::max<long long>(w, 4);
-}
+// upper bound of the workgroups one launch uses: 8 resident wavefronts per SIMD
+static long long max_workgroups(const sop_ctx* c) { return (long long)c->n_cu * 8; }
 
 extern "C" sop_status sop_workspace_bytes(sop_ctx* c, int64_t M, int64_t K, int g, size_t* bytes)
 {
     if (!c) return SOP_EINVAL;
     if (!bytes) return fail(c, SOP_EINVAL, "sop_workspace_bytes: bytes is NULL");
     if (sop_status s = shape_check(c, M, K, g)) return s;
-    *bytes = (size_t)plan_waves(c, M, K, g) * (SOP_K_MAXA + SOP_K_MAXP) * sizeof(float);
+    *bytes = (size_t)max_workgroups(c) * SOP_K_NCOL * sizeof(float);
     return SOP_OK;
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// (scale * 2^-k, reciprocal) of every code of a scale word; built and uploaded on first use
+static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, int k, ScaleTab* out)
+{
+    const auto key = std::make_tuple(x, y, bias, max_code, k);
+    auto it = c->stabs.find(key);
+    if (it != c->stabs.end()) { *out = it->second; return SOP_OK; }
+    const int n = max_code + 1;
+    std::vector<float2> img(n);
+    for (int q = 0; q < n; ++q) {
+        const int e = q >> y, f = q & ((1 << y) - 1);
+        const double v = e == 0 ? std::ldexp((double)f, 1 - bias - y) : std::ldexp((double)((1 << y) + f), e - bias - y);
+        const float s = (float)std::ldexp(v, -k);
+        img[q].x = s;
+        img[q].y = s > 0.0f ? 1.0f / s : 0.0f;
+    }
+    ScaleTab t;
+    t.n = n;
+    hipError_t e = hipMalloc((void**)&t.dev, sizeof(float2) * n);
+    if (e == hipSuccess) e = hipMemcpy(t.dev, img.data(), sizeof(float2) * n, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hipfail(c, e, "upload of the scale table");
+    c->stabs[key] = t;
+    *out = t;
+    return SOP_OK;
+}
 
 extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                                       const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
@@ -202,35 +334,43 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     if (1 - bias - y - k < -126 || 1 - bias - k > 126 || std::max(emax, 1) - bias - k > 125)
         return fail(c, SOP_EFMT, "scale format with this layer shift leaves binary32's normal range (choose bias / max_code / k accordingly)");
 
+    const size_t need = (size_t)max_workgroups(c) * SOP_K_NCOL * sizeof(float);
+    if (!ws || ws_bytes < need) return fail(c, SOP_ENOMEM, "workspace is NULL or smaller than sop_workspace_bytes()");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(c, SOP_EINVAL, "workspace must be 256-byte aligned");
+
     const int epl = g < 16 ? g : 16, lpb = g / epl;
+    const int A = c->n_atoms;
     KParams p;
     std::memset(&p, 0, sizeof(p));
     p.W = W; p.c = cn;
-    p.tab_mid = c->d_tab; p.tab_val = c->d_tab + SOP_K_MAXA * SOP_K_TAB;
+    p.bins = c->d_bins;
     p.M = M; p.K = K; p.ldw = ldw;
     p.Bk = K / g; p.Nb = M * p.Bk; p.Wr = (p.Bk + 31) / 32;
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * M;
-    p.n_waves = plan_waves(c, M, K, g);
-    p.A = c->n_atoms; p.P = c->n_pairs; p.lpb = lpb;
+    p.A = A; p.P = c->n_pairs; p.lpb = lpb;
+    p.n_bins = c->n_bins;
     p.man_bits = y; p.bias = bias; p.max_code = max_code; p.k = k;
     p.pow2k = std::ldexp(1.0f, k);
     p.sub_quantum = std::ldexp(1.0f, 1 - bias - y - k);
-    long long off = 0;
-    for (int a = 0; a < c->n_atoms; ++a) {
-        p.tpos[a] = c->tpos[a]; p.tneg[a] = c->tneg[a]; p.half0[a] = c->half0[a]; p.nent[a] = c->nent[a];
-        p.code_off[a] = off;
-        off += c->nent[a] <= 16 ? M * K / 2 : M * K;
+    // code planes are laid out in the caller's atom order
+    long long plane_off[SOP_K_MAXA], off = 0;
+    for (int a = 0; a < A; ++a) { plane_off[a] = off; off += c->tables[a].size() <= 16 ? M * K / 2 : M * K; }
+    int internal_of[SOP_K_MAXA];
+    for (int i = 0; i < A; ++i) {
+        p.tpos[i] = c->tpos[i]; p.tneg[i] = c->tneg[i]; p.bin_sc[i] = c->bin_sc[i]; p.bin_off[i] = c->bin_off[i];
+        p.nent[i] = c->nent[i]; p.grp_first[i] = (unsigned char)c->grp_first[i]; p.uidx[i] = (unsigned char)c->order[i];
+        p.code_off[i] = plane_off[c->order[i]];
+        internal_of[c->order[i]] = i;
     }
     std::memset(p.pair_slot, -1, sizeof(p.pair_slot));
     for (int q = 0; q < c->n_pairs; ++q) {
-        const int a = c->pairs[2 * q], b = c->pairs[2 * q + 1];
-        p.pair_slot[a * SOP_K_MAXA + b] = (signed char)q;
-        p.pair_col[q] = (unsigned char)pair_index(a, b);
+        const int ia = internal_of[c->pairs[2 * q]], ib = internal_of[c->pairs[2 * q + 1]];
+        const int i = std::min(ia, ib), j = std::max(ia, ib);
+        p.pair_slot[i * SOP_K_MAXA + j] = (signed char)q;
+        p.pair_flip[i * SOP_K_MAXA + j] = (unsigned char)(ia > ib);
+        p.pair_col[q] = (unsigned char)pair_index(i, j);
     }
-    const size_t need = (size_t)p.n_waves * (SOP_K_MAXA + SOP_K_MAXP) * sizeof(float);
-    if (!ws || ws_bytes < need) return fail(c, SOP_ENOMEM, "workspace is NULL or smaller than sop_workspace_bytes()");
-    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(c, SOP_EINVAL, "workspace must be 256-byte aligned");
     p.partial = static_cast<float*>(ws);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
     p.acos_atom = out->acos_atom;
@@ -238,12 +378,36 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     p.scale_code = out->scale_code; p.codes = out->codes; p.blk_cos = out->blk_cos; p.blk_err = out->blk_err;
     const int emit = (p.scale_code || p.codes || p.blk_cos || p.blk_err) ? 1 : 0;
 
-    int prev = 0;
-    (void)hipGetDevice(&prev);
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    if (max_code < SOP_K_MAXTABCODES) {
+        ScaleTab t;
+        if (sop_status s = scale_table(c, x, y, bias, max_code, k, &t)) return s;
+        p.stab = t.dev;
+        p.n_tab_codes = t.n;
+    }
+    const size_t dyn_lds = (size_t)A * p.n_bins * sizeof(BinRec) + (size_t)p.n_tab_codes * sizeof(float2);
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, w, (int)metric, emit);
+    const int vi = sopk_variant_index(dtype == SOP_BF16, g, w, (int)metric, emit);
     hipError_t e = hipSuccess;
-    if (prev != c->device) e = hipSetDevice(c->device);
-    if (e == hipSuccess) e = sopk_launch(&p, dtype == SOP_BF16, g, w, (int)metric, emit, stream);
-    if (prev != c->device) (void)hipSetDevice(prev);
+    if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
+        if (dyn_lds > 48 * 1024) {
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds);
+            if (e != hipSuccess) return hipfail(c, e, "hipFuncSetAttribute(dynamic LDS)");
+        }
+        int nb = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256, dyn_lds);
+        if (e != hipSuccess) return hipfail(c, e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+        if (nb < 1) return fail(c, SOP_EHIP, "the kernel does not fit on a compute unit with this alphabet and scale format");
+        c->occ_blocks[vi] = std::min(nb, 8);
+        c->occ_lds[vi] = dyn_lds;
+    }
+    // one contiguous range of (strip,row) steps per resident wavefront
+    long long wg = (long long)c->n_cu * (c->waves_override ? std::min<long long>(c->waves_override, c->occ_blocks[vi]) : c->occ_blocks[vi]);
+    wg = std::min(wg, (p.total_units + 3) / 4);
+    wg = std::max<long long>(std::min(wg, max_workgroups(c)), 1);
+    p.n_waves = wg * 4;
+    e = sopk_launch(fn, &p, dyn_lds, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }

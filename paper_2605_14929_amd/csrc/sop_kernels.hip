@@ -5,10 +5,15 @@
 // cross-lane exchanges).  A wavefront covers a "strip" of 64*EPL consecutive columns of one row
 // per step and walks down the rows of that strip, so the channel norms of the strip stay in
 // registers.  The (strip,row) steps of the whole layer are cut into equal contiguous ranges, one
-// per wavefront, so every SIMD gets the same amount of work whatever the shape.
+// per resident wavefront, so every SIMD gets the same amount of work whatever the shape.
 //
-// Every block is read from HBM exactly once.  Codebook values and midpoints sit in LDS (16- and
-// 32-entry tables occupy distinct banks, so the binary search reads are conflict free).
+// Every block is read from HBM exactly once.  LDS holds, per atom, a table over uniform bins of
+// the scaled weight x: each bin contains at most one code boundary, so the nearest entry is one
+// table read and one compare; and, for scale words of up to 11 magnitude bits, the (scale,
+// reciprocal) pair of every scale code.
+//
+// Atoms with equal endpoints form a scale group: they share the ideal scale, the scale code and the
+// scaled weights, which are computed once per group.
 //
 // Arithmetic contract (what makes the integer outputs reproducible on any implementation):
 //   scale      s* = max(pmax/t+, nmax/-t-)  (IEEE division), times 2^k, rounded to the scale word
@@ -52,114 +57,148 @@ __device__ __forceinline__ int encode_scale(float sp, const KParams& p)
     const int y = p.man_bits;
     // normal range of the target: rebias the exponent, round the 23-bit mantissa to y bits
     const uint32_t ut = u - ((uint32_t)(127 - p.bias) << 23);
-    uint32_t qn = (ut + ((1u << (22 - y)) - 1u)) >> (23 - y);
-    // subnormal range of the target: quantum 2^(1-bias-y)
-    const int Ee = E > 0 ? E : 1;
-    const uint32_t m = (u & 0x7FFFFFu) | (E > 0 ? 0x800000u : 0u);
-    int S = 151 - p.bias - y - Ee;
-    S = S > 31 ? 31 : S;
-    uint32_t qs = S > 0 ? ((m + ((1u << (S - 1)) - 1u)) >> S) : 0u;
-    uint32_t q = (E >= 128 - p.bias) ? qn : qs;
+    uint32_t q = (ut + ((1u << (22 - y)) - 1u)) >> (23 - y);
+    const bool sub = E < 128 - p.bias;
+    if (__any(sub)) {
+        // subnormal range of the target (or zero): quantum 2^(1-bias-y)
+        const int Ee = E > 0 ? E : 1;
+        const uint32_t m = (u & 0x7FFFFFu) | (E > 0 ? 0x800000u : 0u);
+        int S = 151 - p.bias - y - Ee;
+        S = S > 31 ? 31 : S;
+        const uint32_t qs = S > 0 ? ((m + ((1u << (S - 1)) - 1u)) >> S) : 0u;
+        q = sub ? qs : q;
+    }
     return (int)(q > (uint32_t)p.max_code ? (uint32_t)p.max_code : q);
 }
 
-// value(q) * 2^-k, exact
-__device__ __forceinline__ float decode_scale(int q, const KParams& p)
+// value(q) * 2^-k (exact) and its IEEE reciprocal (0 for the zero scale)
+__device__ __forceinline__ void decode_scale(int q, const KParams& p, const float2* __restrict__ s_tab, float& s, float& rinv)
 {
-    const int y = p.man_bits;
-    const int e = q >> y, f = q & ((1 << y) - 1);
-    const float nrm = __uint_as_float(((uint32_t)(e - p.bias - p.k + 127) << 23) | ((uint32_t)f << (23 - y)));
-    const float sub = (float)f * p.sub_quantum;
-    return e > 0 ? nrm : sub;
+    if (p.n_tab_codes) {
+        const float2 t = s_tab[q];
+        s = t.x;
+        rinv = t.y;
+    } else {
+        const int y = p.man_bits;
+        const int e = q >> y, f = q & ((1 << y) - 1);
+        const float nrm = __uint_as_float(((uint32_t)(e - p.bias - p.k + 127) << 23) | ((uint32_t)f << (23 - y)));
+        const float sub = (float)f * p.sub_quantum;
+        s = e > 0 ? nrm : sub;
+        rinv = s > 0.0f ? 1.0f / s : 0.0f;
+    }
+}
+
+// ideal scale of a block against endpoints (tp, -tn); a unit endpoint needs no division
+__device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, float tn)
+{
+    float s1 = pmax, s2 = nmax;
+    if (tp != 1.0f) s1 = pmax / tp;
+    if (tn != 1.0f) s2 = nmax / tn;
+    return fmaxf(s1, s2);
+}
+
+// Scale of one (group, sign): code q, signed scale ss, scaled weights x and their bin offsets.
+template <int EPL>
+__device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, float nmax, bool negative, int a,
+                                             const KParams& p, const float2* __restrict__ s_tab,
+                                             int& q, float& ss, bool& nonzero, float (&x)[EPL], uint32_t (&boff)[EPL])
+{
+    const float tp = p.tpos[a], tn = p.tneg[a];
+    const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp) : ideal_scale(pmax, nmax, tp, tn);
+    q = encode_scale(sstar * p.pow2k, p);
+    float s, rinv;
+    decode_scale(q, p, s_tab, s, rinv);
+    ss = negative ? -s : s;
+    nonzero = s > 0.0f;
+    const float rr = negative ? -rinv : rinv;
+    const float sc = p.bin_sc[a], off = p.bin_off[a];
+    const uint32_t mask = (uint32_t)(p.n_bins - 1) << 4;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        x[i] = w[i] * rr;
+        const float xc = fminf(fmaxf(x[i], -tn), tp);
+        boff[i] = __float_as_uint(__fmaf_rn(xc, sc, off)) & mask;     // byte offset of the bin record
+    }
 }
 
 struct Cand {
     float err;    // decision score
     float ny;     // c-weighted <w,y>, signed by the scale sign
     float dy;     // c-weighted ||y||^2 (0 when the scale is 0: the reconstruction vanishes)
-    int   q;
 };
 
-// Evaluate one (atom, scale sign) candidate on the lane's EPL elements.
+// Element pass of one (atom, sign) candidate on the lane's EPL elements.
 template <int EPL, int LPB, int METRIC, bool CODES>
-__device__ __forceinline__ Cand eval_candidate(const float (&w)[EPL], const float (&cb)[EPL], const float (&cw)[EPL],
-                                               float pmax, float nmax, bool negative, int a, const KParams& p,
-                                               const float* __restrict__ s_mid, const float* __restrict__ s_val,
-                                               const float* __restrict__ s_vsq, uint32_t (&codes)[EPL / 4])
+__device__ __forceinline__ Cand eval_elements(const float (&w)[EPL], const float (&cb)[EPL], const float (&cw)[EPL],
+                                              const float (&x)[EPL], const uint32_t (&boff)[EPL], float ss, bool nonzero,
+                                              bool negative, const char* __restrict__ bins_a, bool wide_codes,
+                                              uint32_t (&codes)[EPL / 4])
 {
-    const float tp = p.tpos[a], tn = p.tneg[a];
-    const float s1 = negative ? pmax / tn : pmax / tp;
-    const float s2 = negative ? nmax / tp : nmax / tn;
-    const float sp = fmaxf(s1, s2) * p.pow2k;
-    Cand r;
-    r.q = encode_scale(sp, p);
-    const float s = decode_scale(r.q, p);
-    const float rinv = s > 0.0f ? 1.0f / s : 0.0f;
-    const float ss = negative ? -s : s;
-    const float rr = negative ? -rinv : rinv;
-
-    const float* mid = s_mid + a * SOP_K_TAB;
-    const float* val = s_val + a * SOP_K_TAB;
-    const float* vsq = s_vsq + a * SOP_K_TAB;
-    int idx[EPL];
-    float x[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) { x[i] = w[i] * rr; idx[i] = 0; }
-    for (int h = p.half0[a]; h >= 1; h >>= 1) {          // binary search over the padded midpoint table
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) idx[i] += (x[i] > mid[idx[i] + h - 1]) ? h : 0;
-    }
     float e0 = 0.0f, e1 = 0.0f, ny = 0.0f, dy = 0.0f;
+    if (CODES) {
+#pragma unroll
+        for (int j = 0; j < EPL / 4; ++j) codes[j] = 0;
+    }
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        const float yv = val[idx[i]];
+        float thr, ylo, yhi;
+        int clo = 0;
+        if (CODES) {
+            const BinRec rec = *reinterpret_cast<const BinRec*>(__builtin_assume_aligned(bins_a + boff[i], 16));
+            thr = rec.thr; ylo = rec.ylo; yhi = rec.yhi; clo = rec.code_lo;
+        } else {
+            // the first three words of the 16-byte record in one 96-bit LDS read
+            typedef float f3 __attribute__((ext_vector_type(3)));
+            const f3 rp = *reinterpret_cast<const f3*>(__builtin_assume_aligned(bins_a + boff[i], 16));
+            thr = rp.x; ylo = rp.y; yhi = rp.z;
+        }
+        const bool up = x[i] > thr;
+        const float yv = up ? yhi : ylo;
         const float d = __fmaf_rn(-ss, yv, w[i]);
         const float cd = METRIC == 2 ? d : cb[i] * d;
         if (i < 8) e0 = __fmaf_rn(cd, d, e0); else e1 = __fmaf_rn(cd, d, e1);
         ny = __fmaf_rn(cw[i], yv, ny);
-        dy = __fmaf_rn(cb[i], vsq[idx[i]], dy);
-    }
-    if (CODES) {
-#pragma unroll
-        for (int j = 0; j < EPL / 4; ++j) codes[j] = 0;
-        if (p.nent[a] <= 16) {
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) codes[i / 8] |= (uint32_t)idx[i] << (4 * (i % 8));
-        } else {
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) codes[i / 4] |= (uint32_t)idx[i] << (8 * (i % 4));
+        dy = __fmaf_rn(cb[i], yv * yv, dy);
+        if (CODES) {
+            const uint32_t code = (uint32_t)clo + (up ? 1u : 0u);
+            if (wide_codes) codes[i / 4] |= code << (8 * (i % 4));
+            else codes[i / 8] |= code << (4 * (i % 8));
         }
     }
-    float err = EPL == 16 ? e0 + e1 : e0;
+    Cand r;
+    const float err = EPL == 16 ? e0 + e1 : e0;
     r.err = group_sum<LPB>(err);
     r.ny = group_sum<LPB>(negative ? -ny : ny);
     const float dsum = group_sum<LPB>(dy);
-    r.dy = s > 0.0f ? dsum : 0.0f;
+    r.dy = nonzero ? dsum : 0.0f;
     return r;
 }
 
 template <bool BF16, int EPL, int LPB, bool SIGNED, int METRIC, bool EMIT>
 __global__ __launch_bounds__(256) void search_kernel(const KParams p)
 {
-    __shared__ float s_mid[SOP_K_MAXA * SOP_K_TAB];
-    __shared__ float s_val[SOP_K_MAXA * SOP_K_TAB];
-    __shared__ float s_vsq[SOP_K_MAXA * SOP_K_TAB];
-    for (int i = threadIdx.x; i < SOP_K_MAXA * SOP_K_TAB; i += 256) {
-        s_mid[i] = p.tab_mid[i];
-        const float v = p.tab_val[i];
-        s_val[i] = v;
-        s_vsq[i] = v * v;
+    extern __shared__ __align__(16) char s_mem[];
+    char* s_bins = s_mem;                                                         // [A][n_bins] BinRec
+    float2* s_tab = reinterpret_cast<float2*>(s_mem + (size_t)p.A * p.n_bins * sizeof(BinRec));
+    __shared__ float s_red[4][SOP_K_NCOL];
+    {
+        const int n4 = p.A * p.n_bins;
+        const float4* src = reinterpret_cast<const float4*>(p.bins);
+        float4* dst = reinterpret_cast<float4*>(s_bins);
+        for (int i = threadIdx.x; i < n4; i += 256) dst[i] = src[i];
+        for (int i = threadIdx.x; i < p.n_tab_codes; i += 256) s_tab[i] = p.stab[i];
     }
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
-    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int wv = threadIdx.x >> 6;
+    const long long wave = (long long)blockIdx.x * 4 + wv;
     const long long u0 = p.total_units * wave / p.n_waves;
     const long long u1 = p.total_units * (wave + 1) / p.n_waves;
 
-    float acc[SOP_K_MAXA + SOP_K_MAXP];
+    float acc[SOP_K_NCOL];
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXA + SOP_K_MAXP; ++i) acc[i] = 0.0f;
+    for (int i = 0; i < SOP_K_NCOL; ++i) acc[i] = 0.0f;
 
     long long strip = u0 / p.M;
     long long m = u0 - strip * p.M;
@@ -219,21 +258,38 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
         const bool leader = valid && (lane % LPB == 0);
 
         float err[SOP_K_MAXA], dlt[SOP_K_MAXA];
+        // state of the current scale group (positive sign)
+        int gq = 0;
+        float gss = 0.0f;
+        bool gnz = false;
+        float gx[EPL];
+        uint32_t gboff[EPL];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) { gx[i] = 0.0f; gboff[i] = 0; }
+
 #pragma unroll
         for (int a = 0; a < SOP_K_MAXA; ++a) {
             err[a] = 0.0f; dlt[a] = 0.0f;
             if (a < p.A) {
+                if (p.grp_first[a]) prepare_sign<EPL>(w, pmax, nmax, false, a, p, s_tab, gq, gss, gnz, gx, gboff);
+                const char* bins_a = s_bins + (size_t)a * p.n_bins * sizeof(BinRec);
+                const bool wide = p.nent[a] > 16;
                 uint32_t codes[EPL / 4];
-                Cand best = eval_candidate<EPL, LPB, METRIC, EMIT>(w, cb, cw, pmax, nmax, false, a, p, s_mid, s_val, s_vsq, codes);
+                Cand best = eval_elements<EPL, LPB, METRIC, EMIT>(w, cb, cw, gx, gboff, gss, gnz, false, bins_a, wide, codes);
+                int q = gq;
                 bool neg = false;
                 if (SIGNED) {
-                    uint32_t codes2[EPL / 4];
-                    Cand c2 = eval_candidate<EPL, LPB, METRIC, EMIT>(w, cb, cw, pmax, nmax, true, a, p, s_mid, s_val, s_vsq, codes2);
+                    int q2;
+                    float ss2, x2[EPL];
+                    bool nz2;
+                    uint32_t boff2[EPL], codes2[EPL / 4];
+                    prepare_sign<EPL>(w, pmax, nmax, true, a, p, s_tab, q2, ss2, nz2, x2, boff2);
+                    const Cand c2 = eval_elements<EPL, LPB, METRIC, EMIT>(w, cb, cw, x2, boff2, ss2, nz2, true, bins_a, wide, codes2);
                     neg = c2.err < best.err;
                     best.err = neg ? c2.err : best.err;
                     best.ny = neg ? c2.ny : best.ny;
                     best.dy = neg ? c2.dy : best.dy;
-                    best.q = neg ? c2.q : best.q;
+                    q = neg ? q2 : q;
                     if (EMIT) {
 #pragma unroll
                         for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codes2[j] : codes[j];
@@ -246,11 +302,12 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                 dlt[a] = wn > 0.0f ? 1.0f - cosv : 0.0f;
                 acc[a] += dlt[a];
                 if (EMIT) {
-                    if (p.scale_code && leader) p.scale_code[(long long)a * p.Nb + blk] = (uint16_t)(best.q | (neg ? 0x8000 : 0));
-                    if (p.blk_err && leader) p.blk_err[(long long)a * p.Nb + blk] = best.err;
-                    if (p.blk_cos && leader) p.blk_cos[(long long)a * p.Nb + blk] = 1.0f - dlt[a];
+                    const long long ua = p.uidx[a];
+                    if (p.scale_code && leader) p.scale_code[ua * p.Nb + blk] = (uint16_t)(q | (neg ? 0x8000 : 0));
+                    if (p.blk_err && leader) p.blk_err[ua * p.Nb + blk] = best.err;
+                    if (p.blk_cos && leader) p.blk_cos[ua * p.Nb + blk] = 1.0f - dlt[a];
                     if (p.codes && valid) {
-                        if (p.nent[a] <= 16) {
+                        if (!wide) {
                             uint8_t* dst = p.codes + p.code_off[a] + (m * p.K + col0) / 2;
 #pragma unroll
                             for (int j = 0; j < EPL / 8; ++j) reinterpret_cast<uint32_t*>(dst)[j] = codes[j];
@@ -263,15 +320,18 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                 }
             }
         }
-        // ---- selector of every requested pair ----
+        // ---- selector of every requested pair (i < j in internal order) ----
 #pragma unroll
-        for (int a = 0; a < SOP_K_MAXA; ++a) {
+        for (int i = 0; i < SOP_K_MAXA; ++i) {
 #pragma unroll
-            for (int b = a + 1; b < SOP_K_MAXA; ++b) {
-                const int slot = p.pair_slot[a * SOP_K_MAXA + b];
+            for (int j = i + 1; j < SOP_K_MAXA; ++j) {
+                const int slot = p.pair_slot[i * SOP_K_MAXA + j];
                 if (slot >= 0) {
-                    const bool sel = err[b] < err[a];
-                    acc[SOP_K_MAXA + pair_index(a, b)] += sel ? dlt[b] : dlt[a];
+                    // caller's pair (a,b): selector = "b strictly better than a"
+                    const bool flip = p.pair_flip[i * SOP_K_MAXA + j] != 0;      // a is internal j
+                    const bool sel = flip ? (err[i] < err[j]) : (err[j] < err[i]);
+                    const bool take_j = sel != flip;
+                    acc[SOP_K_MAXA + pair_index(i, j)] += take_j ? dlt[j] : dlt[i];
                     if (p.sel_bits) {
                         unsigned long long mask = __ballot(sel);
                         if (LPB == 2) {            // keep one bit per block: bits of even lanes
@@ -306,18 +366,19 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
         if (++m == p.M) { m = 0; ++strip; }
     }
 
-    // ---- per-wavefront partial sums (deficits 1-cos), summed over lanes ----
+    // ---- per-workgroup partial sums (deficits 1-cos): lanes, then the four wavefronts in order ----
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXA + SOP_K_MAXP; ++i) {
+    for (int i = 0; i < SOP_K_NCOL; ++i) {
         float v = acc[i];
 #pragma unroll
         for (int s = 1; s < 64; s <<= 1) v += __shfl_xor(v, s, 64);
-        acc[i] = v;
+        if (lane == 0) s_red[wv][i] = v;
     }
-    if (lane == 0) {
-        float* dst = p.partial + wave * (SOP_K_MAXA + SOP_K_MAXP);
-#pragma unroll
-        for (int i = 0; i < SOP_K_MAXA + SOP_K_MAXP; ++i) dst[i] = acc[i];
+    __syncthreads();
+    if (threadIdx.x < SOP_K_NCOL) {
+        const int i = threadIdx.x;
+        const float v = (s_red[0][i] + s_red[1][i]) + (s_red[2][i] + s_red[3][i]);
+        p.partial[(long long)i * (p.n_waves / 4) + blockIdx.x] = v;
     }
 }
 
@@ -325,13 +386,14 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
 __global__ __launch_bounds__(256) void reduce_kernel(const KParams p)
 {
     __shared__ double s[256];
-    const int o = blockIdx.x;                      // 0..A-1 atoms, A..A+P-1 pairs (output order)
+    const int o = blockIdx.x;                      // 0..A-1 atoms (internal order), then pairs by output index
     int col;
     double* dst;
-    if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + o : nullptr; }
+    if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + p.uidx[o] : nullptr; }
     else { col = SOP_K_MAXA + p.pair_col[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
+    const long long n_wg = p.n_waves / 4;
     double t = 0.0;
-    for (long long wv = threadIdx.x; wv < p.n_waves; wv += 256) t += (double)p.partial[wv * (SOP_K_MAXA + SOP_K_MAXP) + col];
+    for (long long g = threadIdx.x; g < n_wg; g += 256) t += (double)p.partial[(long long)col * n_wg + g];
     s[threadIdx.x] = t;
     __syncthreads();
     for (int h = 128; h >= 1; h >>= 1) {
@@ -343,43 +405,50 @@ __global__ __launch_bounds__(256) void reduce_kernel(const KParams p)
 
 }  // namespace sopk
 
-// ---- launch table ----
+// ---- kernel table ----
 template <bool BF16, int EPL, int LPB>
-static hipError_t launch_geom(const KParams& p, bool is_signed, int metric, bool emit, dim3 grid, hipStream_t st)
+static const void* pick_geom(bool is_signed, int metric, bool emit)
 {
-#define SOPK_GO(S, MT, E) hipLaunchKernelGGL((sopk::search_kernel<BF16, EPL, LPB, S, MT, E>), grid, dim3(256), 0, st, p)
+#define SOPK_FN(S, MT, E) reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E>)
     if (metric == 0) {
-        if (is_signed) { if (emit) SOPK_GO(true, 0, true); else SOPK_GO(true, 0, false); }
-        else           { if (emit) SOPK_GO(false, 0, true); else SOPK_GO(false, 0, false); }
-    } else {
-        if (is_signed) { if (emit) SOPK_GO(true, 2, true); else SOPK_GO(true, 2, false); }
-        else           { if (emit) SOPK_GO(false, 2, true); else SOPK_GO(false, 2, false); }
+        if (is_signed) return emit ? SOPK_FN(true, 0, true) : SOPK_FN(true, 0, false);
+        return emit ? SOPK_FN(false, 0, true) : SOPK_FN(false, 0, false);
     }
-#undef SOPK_GO
-    return hipGetLastError();
+    if (is_signed) return emit ? SOPK_FN(true, 2, true) : SOPK_FN(true, 2, false);
+    return emit ? SOPK_FN(false, 2, true) : SOPK_FN(false, 2, false);
+#undef SOPK_FN
 }
 
-extern "C" hipError_t sopk_launch(const KParams* pp, int is_bf16, int g, int is_signed, int metric, int emit, void* stream)
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int metric, int emit)
 {
-    const KParams& p = *pp;
-    hipStream_t st = (hipStream_t)stream;
-    dim3 grid((unsigned)(p.n_waves / 4));
-    hipError_t e;
     if (is_bf16) {
         switch (g) {
-            case 8:  e = launch_geom<true, 8, 1>(p, is_signed, metric, emit, grid, st); break;
-            case 16: e = launch_geom<true, 16, 1>(p, is_signed, metric, emit, grid, st); break;
-            case 32: e = launch_geom<true, 16, 2>(p, is_signed, metric, emit, grid, st); break;
-            default: e = launch_geom<true, 16, 4>(p, is_signed, metric, emit, grid, st); break;
-        }
-    } else {
-        switch (g) {
-            case 8:  e = launch_geom<false, 8, 1>(p, is_signed, metric, emit, grid, st); break;
-            case 16: e = launch_geom<false, 16, 1>(p, is_signed, metric, emit, grid, st); break;
-            case 32: e = launch_geom<false, 16, 2>(p, is_signed, metric, emit, grid, st); break;
-            default: e = launch_geom<false, 16, 4>(p, is_signed, metric, emit, grid, st); break;
+            case 8:  return pick_geom<true, 8, 1>(is_signed, metric, emit);
+            case 16: return pick_geom<true, 16, 1>(is_signed, metric, emit);
+            case 32: return pick_geom<true, 16, 2>(is_signed, metric, emit);
+            default: return pick_geom<true, 16, 4>(is_signed, metric, emit);
         }
     }
+    switch (g) {
+        case 8:  return pick_geom<false, 8, 1>(is_signed, metric, emit);
+        case 16: return pick_geom<false, 16, 1>(is_signed, metric, emit);
+        case 32: return pick_geom<false, 16, 2>(is_signed, metric, emit);
+        default: return pick_geom<false, 16, 4>(is_signed, metric, emit);
+    }
+}
+
+extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit)
+{
+    const int gi = g == 8 ? 0 : g == 16 ? 1 : g == 32 ? 2 : 3;
+    return (((is_bf16 ? 1 : 0) * 4 + gi) * 2 + (is_signed ? 1 : 0)) * 4 + (metric == 0 ? 0 : 2) + (emit ? 1 : 0);
+}
+
+extern "C" hipError_t sopk_launch(const void* fn, const KParams* pp, size_t dyn_lds, void* stream)
+{
+    KParams p = *pp;
+    hipStream_t st = (hipStream_t)stream;
+    void* args[] = {&p};
+    hipError_t e = hipLaunchKernel(fn, dim3((unsigned)(p.n_waves / 4)), dim3(256), args, dyn_lds, st);
     if (e != hipSuccess) return e;
     if (p.acos_atom || p.acos_pair) {
         hipLaunchKernelGGL(sopk::reduce_kernel, dim3((unsigned)(p.A + p.P)), dim3(256), 0, st, p);
