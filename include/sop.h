@@ -98,6 +98,13 @@ sop_status sop_destroy(sop_ctx* ctx);
  * Resets the pair list to all pairs a < b in lexicographic order. */
 sop_status sop_set_alphabet(sop_ctx* ctx, const sop_atom* atoms, int n_atoms);
 
+/* Host-only self check of the element-search table the library would build for this alphabet
+ * (no GPU needed): builds the table, then compares table lookups with the direct count of
+ * midpoints below x on every float near each code boundary and on dense sweeps of the range.
+ * Returns SOP_OK when they agree; *n_bins receives the table's bin count, *n_checked the number of
+ * values compared (either may be NULL). */
+sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int* n_bins, int64_t* n_checked);
+
 /* Choose the candidate pairs: HOST array of P pairs (a, b) with a < b, no duplicates.
  * P = 0 (or pair_ab NULL) restores the default of all pairs.  Output index = position here. */
 sop_status sop_set_pairs(sop_ctx* ctx, const int* pair_ab, int n_pairs);

@@ -58,6 +58,7 @@ def lib():
         L.sop_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
         L.sop_destroy.argtypes = [C.c_void_p]
         L.sop_set_alphabet.argtypes = [C.c_void_p, C.POINTER(_Atom), C.c_int]
+        L.sop_check_alphabet.argtypes = [C.POINTER(_Atom), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.sop_set_pairs.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.c_int]
         L.sop_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
         L.sop_pair_search.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
@@ -115,6 +116,18 @@ def sop_atom_bof(n_bits: int, draws: np.ndarray, g: int = 16, iters: int = 50) -
     out = np.empty(2 ** n_bits, dtype=np.float32)
     _check(lib().sop_atom_bof(n_bits, _fp(d, C.c_double), d.size, g, iters, _fp(out)))
     return out
+
+
+def sop_check_alphabet(tables):
+    """Host-only check of the search table built for these atoms; returns (n_bins, n_checked)."""
+    tabs = [np.ascontiguousarray(t, dtype=np.float32) for t in tables]
+    arr = (_Atom * len(tabs))()
+    for i, t in enumerate(tabs):
+        arr[i].n_entries = t.size
+        arr[i].values = _fp(t)
+    nb, nc = C.c_int(), C.c_int64()
+    _check(lib().sop_check_alphabet(arr, len(tabs), C.byref(nb), C.byref(nc)))
+    return nb.value, nc.value
 
 
 _FMTS = {

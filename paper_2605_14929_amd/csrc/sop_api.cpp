@@ -95,7 +95,7 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipGetDeviceProperties"); }
     c->n_cu = prop.multiProcessorCount;
     if (const char* s = getenv("SOP_WAVES_PER_SIMD")) { long long v = atoll(s); if (v >= 1 && v <= 8) c->waves_override = v; }
-    if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXA * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
+    if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
     *out = c;
     return SOP_OK;
 }
@@ -120,119 +120,180 @@ static void default_pairs(sop_ctx* c)
     c->n_pairs = p;
 }
 
-// Bin of a scaled weight, exactly as the kernel computes it (clamp, one fma, mask of the bits above
-// the four fraction bits of the magic-number sum).
-static int bin_of(float x, float xl, float xh, float sc, float off, int n_bins)
+// Bin of a scaled weight, exactly as the kernel computes it: clamp to the atom's range, one fma
+// whose constant term carries 1.5*2^23 (so the sum is rounded to an integer), bin = low bits.
+static int bin_of(float x, float xl, float xh, float sc, float off)
 {
     const float xc = std::fmin(std::fmax(x, xl), xh);
     const float t = std::fmaf(xc, sc, off);
-    return (int)((f2u(t) >> 4) & (uint32_t)(n_bins - 1));
+    return (int)(f2u(t) - f2u(SOP_K_BIN_MAGIC));
 }
 
-// Build the bin records of one atom; false when some bin would hold two code boundaries.
-static bool build_bins(const std::vector<float>& L, float xl, float xh, float sc, float off, int n_bins, BinRec* rec)
+// Fill atom slot `ia` of the bin records; false when some bin would hold two code boundaries or the
+// binning leaves [0, n_bins).
+static bool build_bins(const std::vector<float>& L, float xl, float xh, float sc, float off, int n_bins, int ia, BinRec* rec)
 {
     const int N = (int)L.size();
+    const float inf = std::numeric_limits<float>::infinity();
     std::vector<float> mid(N - 1);
     for (int j = 0; j + 1 < N; ++j) mid[j] = (float)(((double)L[j] + (double)L[j + 1]) * 0.5);
     auto code_of = [&](float x) { int c = 0; for (int j = 0; j + 1 < N; ++j) c += x > mid[j]; return c; };
-    // first[j] = smallest float in [xl, xh] whose bin is >= j (bins are monotone in x)
-    std::vector<float> first(n_bins + 1);
-    first[0] = xl;
-    for (int j = 1; j <= n_bins; ++j) {
-        if (bin_of(xh, xl, xh, sc, off, n_bins) < j) { first[j] = std::numeric_limits<float>::infinity(); continue; }
-        int64_t lo = ford(first[j - 1]), hi = ford(xh);              // bin(lo) may be < j, bin(hi) >= j
-        if (bin_of(funord(lo), xl, xh, sc, off, n_bins) >= j) { first[j] = funord(lo); continue; }
+    const int b_lo = bin_of(xl, xl, xh, sc, off), b_hi = bin_of(xh, xl, xh, sc, off);
+    if (b_lo < 0 || b_hi >= n_bins || b_lo > b_hi) return false;
+    // first[j] = smallest float in [xl, xh] whose bin is >= j (the binning is monotone in x)
+    std::vector<float> first(n_bins + 1, inf);
+    for (int j = 0; j <= b_lo; ++j) first[j] = xl;
+    for (int j = b_lo + 1; j <= b_hi; ++j) {
+        int64_t lo = ford(first[j - 1]), hi = ford(xh);              // bin(lo) < j <= bin(hi)
+        if (bin_of(funord(lo), xl, xh, sc, off) >= j) { first[j] = funord(lo); continue; }
         while (hi - lo > 1) {
             const int64_t m = lo + (hi - lo) / 2;
-            if (bin_of(funord(m), xl, xh, sc, off, n_bins) >= j) hi = m; else lo = m;
+            if (bin_of(funord(m), xl, xh, sc, off) >= j) hi = m; else lo = m;
         }
         first[j] = funord(hi);
     }
     for (int j = 0; j < n_bins; ++j) {
-        // floats of bin j: [first[j], pred(first[j+1])]; below xl everything falls in the first bin,
-        // above xh in the bin of xh
-        int c0, c1;
-        const bool empty = !(first[j] < first[j + 1]);
-        if (empty) { c0 = c1 = code_of(std::isinf(first[j]) ? xh : first[j]); }
-        else {
-            c0 = j == 0 ? 0 : code_of(first[j]);
-            const float last = std::isinf(first[j + 1]) ? std::numeric_limits<float>::infinity()
-                                                         : std::nextafter(first[j + 1], -std::numeric_limits<float>::infinity());
-            c1 = std::isinf(last) ? N - 1 : code_of(last);
-            if (bin_of(xh, xl, xh, sc, off, n_bins) == j) c1 = N - 1;       // the bin of xh also receives everything above
+        // floats of bin j: [first[j], pred(first[j+1])]; everything below xl falls into bin(xl),
+        // everything above xh into bin(xh)
+        int c0 = 0, c1 = 0;
+        if (j < b_lo || j > b_hi || !(first[j] < first[j + 1])) {     // never addressed
+            c0 = c1 = 0;
+        } else {
+            c0 = j == b_lo ? 0 : code_of(first[j]);
+            c1 = j == b_hi ? N - 1 : code_of(std::nextafter(first[j + 1], -inf));
         }
         if (c1 - c0 > 1) return false;
-        rec[j].thr = c1 > c0 ? mid[c0] : std::numeric_limits<float>::infinity();
-        rec[j].ylo = L[c0];
-        rec[j].yhi = L[c1];
-        rec[j].code_lo = c0;
+        rec[j].thr[ia] = c1 > c0 ? mid[c0] : inf;
+        rec[j].ylo[ia] = L[c0];
+        rec[j].yhi[ia] = L[c1];
+        rec[j].code_lo[ia] = c0;
     }
     return true;
+}
+
+namespace {
+struct AlphabetPlan {
+    std::vector<std::vector<float>> tabs;      // caller's order
+    int n_atoms = 0;
+    int order[SOP_K_MAXA] = {0}, grp_first[SOP_K_MAXA] = {0};
+    float sc[SOP_K_MAXA] = {0}, off[SOP_K_MAXA] = {0};
+    int n_bins = 0;
+    std::vector<BinRec> img;
+};
+}  // namespace
+
+// Validate the atoms, form the scale groups and build the bin table (host only).
+static sop_status plan_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms, AlphabetPlan& pl)
+{
+    if (!atoms) return fail(c, SOP_EINVAL, "atoms is NULL");
+    if (n_atoms < 1 || n_atoms > SOP_K_MAXA) return fail(c, SOP_EATOM, "1..8 atoms supported");
+    pl.tabs.assign(n_atoms, {});
+    pl.n_atoms = n_atoms;
+    for (int a = 0; a < n_atoms; ++a) {
+        const int N = atoms[a].n_entries;
+        const float* L = atoms[a].values;
+        if (!L) return fail(c, SOP_EINVAL, "atom values pointer is NULL");
+        if (N < 2 || N > SOP_MAX_ENTRIES) return fail(c, SOP_EATOM, "an atom needs 2..64 entries");
+        for (int j = 0; j < N; ++j) {
+            if (!std::isfinite(L[j])) return fail(c, SOP_EATOM, "atom entry is not finite");
+            if (j && !(L[j - 1] < L[j])) return fail(c, SOP_EATOM, "atom entries must be strictly ascending");
+        }
+        if (!(L[0] < 0.0f && L[N - 1] > 0.0f)) return fail(c, SOP_EATOM, "an atom must have a negative first and a positive last entry");
+        pl.tabs[a].assign(L, L + N);
+    }
+    // scale groups: equal endpoints; internal order = groups by first appearance
+    int n = 0;
+    bool used[SOP_K_MAXA] = {false};
+    for (int a = 0; a < n_atoms; ++a) {
+        if (used[a]) continue;
+        for (int b = a; b < n_atoms; ++b)
+            if (!used[b] && pl.tabs[b].front() == pl.tabs[a].front() && pl.tabs[b].back() == pl.tabs[a].back()) {
+                used[b] = true; pl.grp_first[n] = (b == a); pl.order[n++] = b;
+            }
+    }
+    // smallest bin count for which every bin of every atom holds at most one code boundary
+    // (up to 64 bins the table reads are free of bank conflicts)
+    static const int kBinCounts[] = {16, 24, 32, 40, 48, 56, 64, 96, 128, 192, 256, 384, 512};
+    for (int nb : kBinCounts) {
+        pl.img.assign((size_t)nb, BinRec{});
+        bool ok = true;
+        for (int i = 0; i < n_atoms && ok; ++i) {
+            const std::vector<float>& L = pl.tabs[pl.order[i]];
+            const float xl = L.front(), xh = L.back();
+            // the additive constant is an integer-valued float, so the rounded sum lies within
+            // [-0.5, nb-1] of 1.5*2^23: bins 0 .. nb-1
+            pl.sc[i] = (float)(((double)nb - 1.5) / ((double)xh - (double)xl));
+            pl.off[i] = (float)((double)SOP_K_BIN_MAGIC - (double)xl * (double)pl.sc[i]);
+            ok = build_bins(L, xl, xh, pl.sc[i], pl.off[i], nb, i, pl.img.data());
+        }
+        if (ok) { pl.n_bins = nb; break; }
+    }
+    if (!pl.n_bins) return fail(c, SOP_EATOM, "atom entries are too closely spaced (two code boundaries within 1/512 of the atom's range)");
+    return SOP_OK;
 }
 
 extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms)
 {
     if (!c) return SOP_EINVAL;
-    if (!atoms) return fail(c, SOP_EINVAL, "sop_set_alphabet: atoms is NULL");
-    if (n_atoms < 1 || n_atoms > SOP_K_MAXA) return fail(c, SOP_EATOM, "sop_set_alphabet: 1..8 atoms supported");
-    std::vector<std::vector<float>> tabs(n_atoms);
-    for (int a = 0; a < n_atoms; ++a) {
-        const int N = atoms[a].n_entries;
-        const float* L = atoms[a].values;
-        if (!L) return fail(c, SOP_EINVAL, "sop_set_alphabet: atom values pointer is NULL");
-        if (N < 2 || N > SOP_MAX_ENTRIES) return fail(c, SOP_EATOM, "sop_set_alphabet: an atom needs 2..64 entries");
-        for (int j = 0; j < N; ++j) {
-            if (!std::isfinite(L[j])) return fail(c, SOP_EATOM, "sop_set_alphabet: atom entry is not finite");
-            if (j && !(L[j - 1] < L[j])) return fail(c, SOP_EATOM, "sop_set_alphabet: atom entries must be strictly ascending");
-        }
-        if (!(L[0] < 0.0f && L[N - 1] > 0.0f)) return fail(c, SOP_EATOM, "sop_set_alphabet: an atom must have a negative first and a positive last entry");
-        tabs[a].assign(L, L + N);
-    }
-    // scale groups: equal endpoints; internal order = groups by first appearance
-    int order[SOP_K_MAXA], grp_first[SOP_K_MAXA], n = 0;
-    bool used[SOP_K_MAXA] = {false};
-    for (int a = 0; a < n_atoms; ++a) {
-        if (used[a]) continue;
-        for (int b = a; b < n_atoms; ++b)
-            if (!used[b] && tabs[b].front() == tabs[a].front() && tabs[b].back() == tabs[a].back()) {
-                used[b] = true; grp_first[n] = (b == a); order[n++] = b;
-            }
-    }
-    // smallest bin count for which every bin of every atom holds at most one code boundary
-    std::vector<BinRec> img;
-    int n_bins = 0;
-    float sc[SOP_K_MAXA], off[SOP_K_MAXA];
-    for (int nb = 16; nb <= SOP_K_MAXBINS && !n_bins; nb <<= 1) {
-        img.assign((size_t)n_atoms * nb, BinRec{});
-        bool ok = true;
-        for (int i = 0; i < n_atoms && ok; ++i) {
-            const std::vector<float>& L = tabs[order[i]];
-            const float xl = L.front(), xh = L.back();
-            sc[i] = (float)(((double)nb - 0.5) / ((double)xh - (double)xl));
-            off[i] = (float)((double)SOP_K_BIN_MAGIC + 0.25 - (double)xl * (double)sc[i]);
-            ok = build_bins(L, xl, xh, sc[i], off[i], nb, img.data() + (size_t)i * nb);
-        }
-        if (ok) n_bins = nb;
-    }
-    if (!n_bins) return fail(c, SOP_EATOM, "sop_set_alphabet: atom entries are too closely spaced (two code boundaries within 1/1024 of the atom's range)");
+    AlphabetPlan pl;
+    if (sop_status s = plan_alphabet(c, atoms, n_atoms, pl)) return s;
     {
         DeviceGuard guard(c->device);
         hipError_t e = guard.err;
-        if (e == hipSuccess) e = hipMemcpy(c->d_bins, img.data(), img.size() * sizeof(BinRec), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->d_bins, pl.img.data(), pl.img.size() * sizeof(BinRec), hipMemcpyHostToDevice);
         if (e != hipSuccess) return hipfail(c, e, "upload of the table image");
     }
-    c->tables.swap(tabs);
+    c->tables.swap(pl.tabs);
     c->n_atoms = n_atoms;
-    c->n_bins = n_bins;
+    c->n_bins = pl.n_bins;
     for (int i = 0; i < n_atoms; ++i) {
-        const std::vector<float>& L = c->tables[order[i]];
-        c->order[i] = order[i]; c->grp_first[i] = grp_first[i];
+        const std::vector<float>& L = c->tables[pl.order[i]];
+        c->order[i] = pl.order[i]; c->grp_first[i] = pl.grp_first[i];
         c->tpos[i] = L.back(); c->tneg[i] = -L.front(); c->nent[i] = (int)L.size();
-        c->bin_sc[i] = sc[i]; c->bin_off[i] = off[i];
+        c->bin_sc[i] = pl.sc[i]; c->bin_off[i] = pl.off[i];
     }
     std::memset(c->occ_blocks, 0, sizeof(c->occ_blocks));
     default_pairs(c);
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int* n_bins, int64_t* n_checked)
+{
+    AlphabetPlan pl;
+    if (sop_status s = plan_alphabet(nullptr, atoms, n_atoms, pl)) return s;
+    int64_t checked = 0;
+    const float inf = std::numeric_limits<float>::infinity();
+    for (int i = 0; i < n_atoms; ++i) {
+        const std::vector<float>& L = pl.tabs[pl.order[i]];
+        const int N = (int)L.size();
+        const float xl = L.front(), xh = L.back();
+        std::vector<float> mid(N - 1);
+        for (int j = 0; j + 1 < N; ++j) mid[j] = (float)(((double)L[j] + (double)L[j + 1]) * 0.5);
+        auto check = [&](float x) {
+            int code = 0;
+            for (int j = 0; j + 1 < N; ++j) code += x > mid[j];
+            const int b = bin_of(x, xl, xh, pl.sc[i], pl.off[i]);
+            if (b < 0 || b >= pl.n_bins) return false;
+            const BinRec& r = pl.img[b];
+            const bool up = x > r.thr[i];
+            ++checked;
+            return r.code_lo[i] + (up ? 1 : 0) == code && (up ? r.yhi[i] : r.ylo[i]) == L[code];
+        };
+        bool ok = true;
+        // every float within 64 steps of a code boundary or of an endpoint, a uniform sweep, and
+        // values far outside the range
+        for (int j = 0; j < N + 1 && ok; ++j) {
+            const float centre = j == 0 ? xl : (j == N ? xh : mid[j - 1]);
+            float lo = centre, hi = centre;
+            for (int t = 0; t < 64 && ok; ++t) { ok = check(lo) && check(hi); lo = std::nextafter(lo, -inf); hi = std::nextafter(hi, inf); }
+        }
+        for (int t = 0; t <= 200000 && ok; ++t) ok = check(xl * 1.25f + (xh - xl) * 1.25f * (float)t / 200000.0f);
+        for (int64_t k = ford(xl); k <= ford(xh) && ok; k += 4099) ok = check(funord(k));
+        ok = ok && check(-inf) && check(inf) && check(-3.0e38f) && check(3.0e38f) && check(0.0f) && check(-0.0f);
+        if (!ok) return fail(nullptr, SOP_EATOM, "sop_check_alphabet: the bin table disagrees with the direct search");
+    }
+    if (n_bins) *n_bins = pl.n_bins;
+    if (n_checked) *n_checked = checked;
     return SOP_OK;
 }
 
@@ -359,17 +420,26 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     int internal_of[SOP_K_MAXA];
     for (int i = 0; i < A; ++i) {
         p.tpos[i] = c->tpos[i]; p.tneg[i] = c->tneg[i]; p.bin_sc[i] = c->bin_sc[i]; p.bin_off[i] = c->bin_off[i];
-        p.nent[i] = c->nent[i]; p.grp_first[i] = (unsigned char)c->grp_first[i]; p.uidx[i] = (unsigned char)c->order[i];
+        if (c->grp_first[i]) p.grp_first_mask |= 1u << i;
+        if (c->tpos[i] == 1.0f) p.unit_tpos |= 1u << i;
+        if (c->tneg[i] == 1.0f) p.unit_tneg |= 1u << i;
+        if (c->nent[i] > 16) p.wide_mask |= 1u << i;
+        p.uidx[i] = (unsigned char)c->order[i];
         p.code_off[i] = plane_off[c->order[i]];
         internal_of[c->order[i]] = i;
     }
     std::memset(p.pair_slot, -1, sizeof(p.pair_slot));
     for (int q = 0; q < c->n_pairs; ++q) {
         const int ia = internal_of[c->pairs[2 * q]], ib = internal_of[c->pairs[2 * q + 1]];
-        const int i = std::min(ia, ib), j = std::max(ia, ib);
-        p.pair_slot[i * SOP_K_MAXA + j] = (signed char)q;
-        p.pair_flip[i * SOP_K_MAXA + j] = (unsigned char)(ia > ib);
-        p.pair_col[q] = (unsigned char)pair_index(i, j);
+        const int i = std::min(ia, ib), j = std::max(ia, ib), pi = pair_index(i, j);
+        p.pair_mask |= 1u << pi;
+        if (ia > ib) p.flip_mask |= 1u << pi;
+        p.pair_slot[pi] = (signed char)q;
+    }
+    for (int q = 0; q < c->n_pairs; ++q) {
+        const int ia = internal_of[c->pairs[2 * q]], ib = internal_of[c->pairs[2 * q + 1]];
+        const int pi = pair_index(std::min(ia, ib), std::max(ia, ib));
+        p.pair_col[q] = (unsigned char)__builtin_popcount(p.pair_mask & ((1u << pi) - 1u));
     }
     p.partial = static_cast<float*>(ws);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
@@ -386,7 +456,8 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
         p.stab = t.dev;
         p.n_tab_codes = t.n;
     }
-    const size_t dyn_lds = (size_t)A * p.n_bins * sizeof(BinRec) + (size_t)p.n_tab_codes * sizeof(float2);
+    const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
+                           SOP_K_MAXA * sizeof(float4) + (size_t)(A + c->n_pairs) * 256 * sizeof(float);
     const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, w, (int)metric, emit);
     const int vi = sopk_variant_index(dtype == SOP_BF16, g, w, (int)metric, emit);
     hipError_t e = hipSuccess;

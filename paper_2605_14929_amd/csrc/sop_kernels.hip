@@ -7,10 +7,13 @@
 // registers.  The (strip,row) steps of the whole layer are cut into equal contiguous ranges, one
 // per resident wavefront, so every SIMD gets the same amount of work whatever the shape.
 //
-// Every block is read from HBM exactly once.  LDS holds, per atom, a table over uniform bins of
-// the scaled weight x: each bin contains at most one code boundary, so the nearest entry is one
-// table read and one compare; and, for scale words of up to 11 magnitude bits, the (scale,
-// reciprocal) pair of every scale code.
+// Every block is read from HBM exactly once.  LDS holds a table over uniform bins of the scaled
+// weight x: for every atom each bin contains at most one code boundary, so the nearest entry is a
+// table read and one compare.  A bin is a record of 33 words (boundary, lower value, upper value
+// and lower code of each of the 8 atoms, one word of padding): the odd stride puts the same field
+// of 64 consecutive bins into 64 different banks, so lanes reading different bins do not conflict.
+// For scale words of up to 11 magnitude bits LDS also holds the (scale, reciprocal) pair of every
+// scale code.
 //
 // Atoms with equal endpoints form a scale group: they share the ideal scale, the scale code and the
 // scaled weights, which are computed once per group.
@@ -47,6 +50,30 @@ template <int LPB> __device__ __forceinline__ float group_sum(float v)
     if (LPB >= 2) v = v + xor_lanes(v, 1);
     if (LPB >= 4) v = v + xor_lanes(v, 2);
     return v;
+}
+
+// write a wave-uniform 32-bit value into lane LANE of a register (other lanes keep `old`).
+// gfx950 needs two wait states between a vector instruction that writes a scalar register (the
+// compare producing the ballot) and a vector instruction that reads it; the compiler inserts them
+// for its own code but not inside inline assembly, hence the s_nop.
+template <int LANE> __device__ __forceinline__ uint32_t put_lane(uint32_t value, uint32_t old)
+{
+    const uint32_t s = __builtin_amdgcn_readfirstlane(value);
+    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(s), "n"(LANE));
+    return old;
+}
+
+// wave-uniform switches of the row loop
+struct Switches {
+    int A;
+    uint32_t pair_mask, flip_mask, grp_first, unit_tpos, unit_tneg, wide;
+};
+
+// per-lane running sum kept in LDS (each lane owns its address: plain read-add-write, no atomics,
+// which on this chip serialise the lanes of the wavefront)
+__device__ __forceinline__ void lds_accumulate(float* slot, float v)
+{
+    *slot = *slot + v;
 }
 
 // round a non-negative fp32 to the scale word: nearest, ties to the lower code, saturating
@@ -89,35 +116,39 @@ __device__ __forceinline__ void decode_scale(int q, const KParams& p, const floa
 }
 
 // ideal scale of a block against endpoints (tp, -tn); a unit endpoint needs no division
-__device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, float tn)
+__device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, float tn, bool unit_p, bool unit_n)
 {
     float s1 = pmax, s2 = nmax;
-    if (tp != 1.0f) s1 = pmax / tp;
-    if (tn != 1.0f) s2 = nmax / tn;
+    if (!unit_p) s1 = pmax / tp;
+    if (!unit_n) s2 = nmax / tn;
     return fmaxf(s1, s2);
 }
 
 // Scale of one (group, sign): code q, signed scale ss, scaled weights x and their bin offsets.
 template <int EPL>
 __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, float nmax, bool negative, int a,
-                                             const KParams& p, const float2* __restrict__ s_tab,
+                                             const KParams& p, const Switches& sw, const float2* __restrict__ s_tab,
+                                             const float4* __restrict__ s_gpar,
                                              int& q, float& ss, bool& nonzero, float (&x)[EPL], uint32_t (&boff)[EPL])
 {
-    const float tp = p.tpos[a], tn = p.tneg[a];
-    const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp) : ideal_scale(pmax, nmax, tp, tn);
+    const float4 gp = s_gpar[a];                       // (t+, -t-, bin scale, bin offset): same address in every lane
+    const float tp = gp.x, tn = gp.y;
+    const bool unit_p = (sw.unit_tpos >> a) & 1u, unit_n = (sw.unit_tneg >> a) & 1u;
+    const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp, unit_n, unit_p) : ideal_scale(pmax, nmax, tp, tn, unit_p, unit_n);
     q = encode_scale(sstar * p.pow2k, p);
     float s, rinv;
     decode_scale(q, p, s_tab, s, rinv);
     ss = negative ? -s : s;
     nonzero = s > 0.0f;
     const float rr = negative ? -rinv : rinv;
-    const float sc = p.bin_sc[a], off = p.bin_off[a];
-    const uint32_t mask = (uint32_t)(p.n_bins - 1) << 4;
+    const float sc = gp.z, off = gp.w;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
         x[i] = w[i] * rr;
-        const float xc = fminf(fmaxf(x[i], -tn), tp);
-        boff[i] = __float_as_uint(__fmaf_rn(xc, sc, off)) & mask;     // byte offset of the bin record
+        const float xc = __builtin_amdgcn_fmed3f(x[i], -tn, tp);
+        // off carries 1.5*2^23, so the low mantissa bits of the sum are the bin number; one 24-bit
+        // multiply-add turns them into the byte offset of the bin record
+        boff[i] = __umul24(__float_as_uint(__fmaf_rn(xc, sc, off)), SOP_K_BIN_BYTES) + SOP_K_BIN_NEGC;
     }
 }
 
@@ -141,17 +172,10 @@ __device__ __forceinline__ Cand eval_elements(const float (&w)[EPL], const float
     }
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        float thr, ylo, yhi;
+        const float* rp = reinterpret_cast<const float*>(bins_a + boff[i]);      // bins_a = table + 4*a
+        const float thr = rp[0], ylo = rp[SOP_K_MAXA], yhi = rp[2 * SOP_K_MAXA];
         int clo = 0;
-        if (CODES) {
-            const BinRec rec = *reinterpret_cast<const BinRec*>(__builtin_assume_aligned(bins_a + boff[i], 16));
-            thr = rec.thr; ylo = rec.ylo; yhi = rec.yhi; clo = rec.code_lo;
-        } else {
-            // the first three words of the 16-byte record in one 96-bit LDS read
-            typedef float f3 __attribute__((ext_vector_type(3)));
-            const f3 rp = *reinterpret_cast<const f3*>(__builtin_assume_aligned(bins_a + boff[i], 16));
-            thr = rp.x; ylo = rp.y; yhi = rp.z;
-        }
+        if (CODES) clo = reinterpret_cast<const int*>(rp)[3 * SOP_K_MAXA];
         const bool up = x[i] > thr;
         const float yv = up ? yhi : ylo;
         const float d = __fmaf_rn(-ss, yv, w[i]);
@@ -174,21 +198,80 @@ __device__ __forceinline__ Cand eval_elements(const float (&w)[EPL], const float
     return r;
 }
 
+
+// first / second atom of the pair with lexicographic position pi among all pairs of SOP_K_MAXA atoms
+__host__ __device__ constexpr int pair_first(int pi) { int i = 0; while (pi >= SOP_K_MAXA - 1 - i) { pi -= SOP_K_MAXA - 1 - i; ++i; } return i; }
+__host__ __device__ constexpr int pair_second(int pi) { const int i = pair_first(pi); return pi - pair_index(i, i + 1) + i + 1; }
+
+// Selector of pair PI and of all following pairs (i < j in internal order).  The pair's ballot (one
+// bit per block) is dropped into fixed lanes of `piece`; the caller stores those lanes afterwards.
+template <int PI, int LPB>
+__device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, const float (&err)[SOP_K_MAXA],
+                                          const float (&dlt)[SOP_K_MAXA], float* __restrict__ acc_lane, uint32_t& piece)
+{
+    constexpr int i = pair_first(PI), j = pair_second(PI);
+    static_assert(pair_index(i, j) == PI, "pair enumeration");
+    if ((sw.pair_mask >> PI) & 1u) {
+        // caller's pair (a,b): selector = "b strictly better than a"; when the internal order
+        // swapped the two, b is internal i
+        const float ei = err[i], ej = err[j], di = dlt[i], dj = dlt[j];
+        bool sel;
+        float chosen;
+        // the empty asm statements keep this a real (scalar) branch: one compare per pair
+        if ((sw.flip_mask >> PI) & 1u) { asm volatile(""); sel = ei < ej; chosen = sel ? di : dj; }
+        else                           { asm volatile(""); sel = ej < ei; chosen = sel ? dj : di; }
+        // column of this pair among the requested ones
+        const int col = sw.A + __builtin_popcount(sw.pair_mask & ((1u << PI) - 1u));
+        lds_accumulate(acc_lane + col * 256, chosen);
+        if (p.sel_bits) {
+            unsigned long long mask = __ballot(sel);
+            if (LPB == 1) {
+                piece = put_lane<2 * PI>((uint32_t)mask, piece);
+                piece = put_lane<2 * PI + 1>((uint32_t)(mask >> 32), piece);
+            } else if (LPB == 2) {     // keep one bit per block: bits of even lanes
+                mask &= 0x5555555555555555ull;
+                mask = (mask | (mask >> 1)) & 0x3333333333333333ull;
+                mask = (mask | (mask >> 2)) & 0x0F0F0F0F0F0F0F0Full;
+                mask = (mask | (mask >> 4)) & 0x00FF00FF00FF00FFull;
+                mask = (mask | (mask >> 8)) & 0x0000FFFF0000FFFFull;
+                mask = (mask | (mask >> 16)) & 0x00000000FFFFFFFFull;
+                piece = put_lane<PI>((uint32_t)mask, piece);
+            } else {                   // bits of lanes 0,4,8,...
+                mask &= 0x1111111111111111ull;
+                mask = (mask | (mask >> 3)) & 0x0303030303030303ull;
+                mask = (mask | (mask >> 6)) & 0x000F000F000F000Full;
+                mask = (mask | (mask >> 12)) & 0x000000FF000000FFull;
+                mask = (mask | (mask >> 24)) & 0x000000000000FFFFull;
+                piece = put_lane<PI>((uint32_t)mask, piece);
+            }
+        }
+    }
+    if constexpr (PI + 1 < SOP_K_MAXP) all_pairs<PI + 1, LPB>(p, sw, err, dlt, acc_lane, piece);
+}
+
 template <bool BF16, int EPL, int LPB, bool SIGNED, int METRIC, bool EMIT>
 __global__ __launch_bounds__(256) void search_kernel(const KParams p)
 {
     extern __shared__ __align__(16) char s_mem[];
-    char* s_bins = s_mem;                                                         // [A][n_bins] BinRec
-    float2* s_tab = reinterpret_cast<float2*>(s_mem + (size_t)p.A * p.n_bins * sizeof(BinRec));
+    // LDS: bin table | (scale, reciprocal) table | group parameters | per-lane ACos accumulators
+    char* s_bins = s_mem;                                                         // [n_bins] records of 33 words
+    const size_t bins_bytes = ((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15;
+    float2* s_tab = reinterpret_cast<float2*>(s_mem + bins_bytes);
+    float4* s_gpar = reinterpret_cast<float4*>(s_mem + bins_bytes + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15));
+    float* s_acc = reinterpret_cast<float*>(s_gpar + SOP_K_MAXA);                  // [n_cols][256]
     __shared__ float s_red[4][SOP_K_NCOL];
+    const int n_cols = p.A + p.P;
     {
-        const int n4 = p.A * p.n_bins;
-        const float4* src = reinterpret_cast<const float4*>(p.bins);
-        float4* dst = reinterpret_cast<float4*>(s_bins);
-        for (int i = threadIdx.x; i < n4; i += 256) dst[i] = src[i];
+        const int nw = p.n_bins * (SOP_K_BIN_BYTES / 4);
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(p.bins);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(s_bins);
+        for (int i = threadIdx.x; i < nw; i += 256) dst[i] = src[i];
         for (int i = threadIdx.x; i < p.n_tab_codes; i += 256) s_tab[i] = p.stab[i];
+        if (threadIdx.x < SOP_K_MAXA) s_gpar[threadIdx.x] = make_float4(p.tpos[threadIdx.x], p.tneg[threadIdx.x], p.bin_sc[threadIdx.x], p.bin_off[threadIdx.x]);
+        for (int i = 0; i < n_cols; ++i) s_acc[i * 256 + threadIdx.x] = 0.0f;
     }
     __syncthreads();
+    float* acc_lane = s_acc + threadIdx.x;
 
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
@@ -196,9 +279,17 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
     const long long u0 = p.total_units * wave / p.n_waves;
     const long long u1 = p.total_units * (wave + 1) / p.n_waves;
 
-    float acc[SOP_K_NCOL];
+    // selector output: which pair's bit plane this lane stores into (-1: none)
+    int sel_slot = -1;
+    {
+        const int my_pi = LPB == 1 ? (lane >> 1) : (LPB == 2 ? lane : (lane & 31));
 #pragma unroll
-    for (int i = 0; i < SOP_K_NCOL; ++i) acc[i] = 0.0f;
+        for (int pi = 0; pi < SOP_K_MAXP; ++pi)
+            if (my_pi == pi && ((p.pair_mask >> pi) & 1u)) sel_slot = p.pair_slot[pi];
+        if (LPB == 1 && lane >= 2 * SOP_K_MAXP) sel_slot = -1;
+        if (LPB == 2 && lane >= SOP_K_MAXP) sel_slot = -1;
+        if (LPB == 4 && (lane & 31) >= SOP_K_MAXP) sel_slot = -1;
+    }
 
     long long strip = u0 / p.M;
     long long m = u0 - strip * p.M;
@@ -208,6 +299,10 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
     long long col0 = 0;
 
     for (long long u = u0; u < u1; ++u) {
+        // The uniform switches below are re-read every row.  Left loop-invariant, each test would be
+        // hoisted out of the loop as a 64-bit lane mask and the hundred-odd masks would spill.
+        Switches sw = {p.A, p.pair_mask, p.flip_mask, p.grp_first_mask, p.unit_tpos, p.unit_tneg, p.wide_mask};
+        asm volatile("" : "+s"(sw.A), "+s"(sw.pair_mask), "+s"(sw.flip_mask), "+s"(sw.grp_first), "+s"(sw.unit_tpos), "+s"(sw.unit_tneg), "+s"(sw.wide));
         if (strip != cur_strip) {
             cur_strip = strip;
             col0 = (strip * 64 + lane) * EPL;
@@ -270,10 +365,10 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
 #pragma unroll
         for (int a = 0; a < SOP_K_MAXA; ++a) {
             err[a] = 0.0f; dlt[a] = 0.0f;
-            if (a < p.A) {
-                if (p.grp_first[a]) prepare_sign<EPL>(w, pmax, nmax, false, a, p, s_tab, gq, gss, gnz, gx, gboff);
-                const char* bins_a = s_bins + (size_t)a * p.n_bins * sizeof(BinRec);
-                const bool wide = p.nent[a] > 16;
+            if (a < sw.A) {
+                if ((sw.grp_first >> a) & 1u) prepare_sign<EPL>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, gq, gss, gnz, gx, gboff);
+                const char* bins_a = s_bins + 4 * a;
+                const bool wide = EMIT && ((sw.wide >> a) & 1u);
                 uint32_t codes[EPL / 4];
                 Cand best = eval_elements<EPL, LPB, METRIC, EMIT>(w, cb, cw, gx, gboff, gss, gnz, false, bins_a, wide, codes);
                 int q = gq;
@@ -283,7 +378,7 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                     float ss2, x2[EPL];
                     bool nz2;
                     uint32_t boff2[EPL], codes2[EPL / 4];
-                    prepare_sign<EPL>(w, pmax, nmax, true, a, p, s_tab, q2, ss2, nz2, x2, boff2);
+                    prepare_sign<EPL>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, q2, ss2, nz2, x2, boff2);
                     const Cand c2 = eval_elements<EPL, LPB, METRIC, EMIT>(w, cb, cw, x2, boff2, ss2, nz2, true, bins_a, wide, codes2);
                     neg = c2.err < best.err;
                     best.err = neg ? c2.err : best.err;
@@ -300,7 +395,7 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                 const float cosv = prod > 0.0f ? fminf(fmaxf(best.ny * __frsqrt_rn(prod), -1.0f), 1.0f) : 0.0f;
                 err[a] = best.err;
                 dlt[a] = wn > 0.0f ? 1.0f - cosv : 0.0f;
-                acc[a] += dlt[a];
+                lds_accumulate(acc_lane + a * 256, dlt[a]);
                 if (EMIT) {
                     const long long ua = p.uidx[a];
                     if (p.scale_code && leader) p.scale_code[ua * p.Nb + blk] = (uint16_t)(q | (neg ? 0x8000 : 0));
@@ -320,46 +415,20 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                 }
             }
         }
-        // ---- selector of every requested pair (i < j in internal order) ----
-#pragma unroll
-        for (int i = 0; i < SOP_K_MAXA; ++i) {
-#pragma unroll
-            for (int j = i + 1; j < SOP_K_MAXA; ++j) {
-                const int slot = p.pair_slot[i * SOP_K_MAXA + j];
-                if (slot >= 0) {
-                    // caller's pair (a,b): selector = "b strictly better than a"
-                    const bool flip = p.pair_flip[i * SOP_K_MAXA + j] != 0;      // a is internal j
-                    const bool sel = flip ? (err[i] < err[j]) : (err[j] < err[i]);
-                    const bool take_j = sel != flip;
-                    acc[SOP_K_MAXA + pair_index(i, j)] += take_j ? dlt[j] : dlt[i];
-                    if (p.sel_bits) {
-                        unsigned long long mask = __ballot(sel);
-                        if (LPB == 2) {            // keep one bit per block: bits of even lanes
-                            mask &= 0x5555555555555555ull;
-                            mask = (mask | (mask >> 1)) & 0x3333333333333333ull;
-                            mask = (mask | (mask >> 2)) & 0x0F0F0F0F0F0F0F0Full;
-                            mask = (mask | (mask >> 4)) & 0x00FF00FF00FF00FFull;
-                            mask = (mask | (mask >> 8)) & 0x0000FFFF0000FFFFull;
-                            mask = (mask | (mask >> 16)) & 0x00000000FFFFFFFFull;
-                        } else if (LPB == 4) {     // bits of lanes 0,4,8,...
-                            mask &= 0x1111111111111111ull;
-                            mask = (mask | (mask >> 3)) & 0x0303030303030303ull;
-                            mask = (mask | (mask >> 6)) & 0x000F000F000F000Full;
-                            mask = (mask | (mask >> 12)) & 0x000000FF000000FFull;
-                            mask = (mask | (mask >> 24)) & 0x000000000000FFFFull;
-                        }
-                        // the strip owns U = 4/LPB 16-bit pieces of the row's bit plane; the last
-                        // strip also clears the padding piece of the last word
-                        const int U = 4 / LPB;
-                        const long long first = strip * U;
-                        const long long n16 = (strip == p.strips - 1) ? (2 * p.Wr - first) : U;
-                        if (lane < n16) {
-                            const uint16_t piece = lane < 4 ? (uint16_t)(mask >> (16 * lane)) : (uint16_t)0;
-                            uint16_t* plane = reinterpret_cast<uint16_t*>(p.sel_bits) + ((long long)slot * p.M + m) * (2 * p.Wr);
-                            plane[first + lane] = piece;
-                        }
-                    }
-                }
+        // ---- selector of every requested pair; afterwards the lanes that received a ballot store
+        //      their piece of the bit planes in a single instruction ----
+        uint32_t piece = 0;
+        all_pairs<0, LPB>(p, sw, err, dlt, acc_lane, piece);
+        if (p.sel_bits && sel_slot >= 0) {
+            if (LPB == 1) {                        // lane 2*pi+h holds word 2*strip+h of the row
+                const long long widx = strip * 2 + (lane & 1);
+                if (widx < p.Wr) p.sel_bits[((long long)sel_slot * p.M + m) * p.Wr + widx] = piece;
+            } else if (LPB == 2) {                 // lane pi holds word `strip` of the row
+                p.sel_bits[((long long)sel_slot * p.M + m) * p.Wr + strip] = piece;
+            } else {                               // lane pi holds 16-bit piece `strip`; lanes 32+pi clear the padding piece
+                uint16_t* plane = reinterpret_cast<uint16_t*>(p.sel_bits) + ((long long)sel_slot * p.M + m) * (2 * p.Wr);
+                if (lane < 32) plane[strip] = (uint16_t)piece;
+                else if (strip == p.strips - 1 && p.strips < 2 * p.Wr) plane[p.strips] = 0;
             }
         }
         // next step of the range
@@ -367,15 +436,14 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
     }
 
     // ---- per-workgroup partial sums (deficits 1-cos): lanes, then the four wavefronts in order ----
+    for (int i = 0; i < n_cols; ++i) {
+        float v = acc_lane[i * 256];
 #pragma unroll
-    for (int i = 0; i < SOP_K_NCOL; ++i) {
-        float v = acc[i];
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) v += __shfl_xor(v, s, 64);
+        for (int st = 1; st < 64; st <<= 1) v += __shfl_xor(v, st, 64);
         if (lane == 0) s_red[wv][i] = v;
     }
     __syncthreads();
-    if (threadIdx.x < SOP_K_NCOL) {
+    if ((int)threadIdx.x < n_cols) {
         const int i = threadIdx.x;
         const float v = (s_red[0][i] + s_red[1][i]) + (s_red[2][i] + s_red[3][i]);
         p.partial[(long long)i * (p.n_waves / 4) + blockIdx.x] = v;
@@ -390,7 +458,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const KParams p)
     int col;
     double* dst;
     if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + p.uidx[o] : nullptr; }
-    else { col = SOP_K_MAXA + p.pair_col[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
+    else { col = p.A + p.pair_col[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
     const long long n_wg = p.n_waves / 4;
     double t = 0.0;
     for (long long g = threadIdx.x; g < n_wg; g += 256) t += (double)p.partial[(long long)col * n_wg + g];

@@ -58,3 +58,27 @@ def test_builder_argument_errors():
     assert sop.lib().sop_atom_nf(9, out) == 1
     assert sop.lib().sop_atom_nf(4, None) == 1
     assert sop.lib().sop_atom_sh(4, -1.0, 0.0, out) == 1
+
+
+def test_search_table_matches_direct_search():
+    # host logic of the library: the binned search table must reproduce the midpoint count for
+    # every float near every code boundary, for each alphabet the GPU tests use
+    draws = si.normal_draws(1 << 16, 4242)
+    sets = [
+        ["NF4", "SH4", "BOF4", "-NF4", "-SH4", "-BOF4"],
+        ["NF5", "SH5", "BOF5", "-NF5", "-SH5", "-BOF5"],
+        ["NF4", "SH5", "BOF4", "-NF5"],
+        ["NF3", "SH6", "NF6"],
+    ]
+    for names in sets:
+        nb, nc = sop.sop_check_alphabet(sop.build_alphabet(names, bof_draws=draws))
+        assert 16 <= nb <= 512 and nc > 100000
+    nb, _ = sop.sop_check_alphabet(sop.build_alphabet(["NF4", "SH4", "-NF4", "-SH4"]))
+    assert nb <= 64                                                   # conflict-free table for the 4-bit atoms
+    e2m3 = OA.to_f32(OA.exmy_grid(2, 3))
+    three = np.array([-1.0, 0.0, 0.5], dtype=np.float32)
+    odd = np.array([-3.0, -2.9, -0.1, 0.0, 0.7, 5.0], dtype=np.float32)
+    sop.sop_check_alphabet([e2m3, sop.sop_atom_nf(4), three, sop.sop_atom_negate(three), odd])
+    with pytest.raises(sop.SopError) as e:                            # boundaries closer than the finest table
+        sop.sop_check_alphabet([np.array([-1.0, 0.0, 1e-4, 2e-4, 1.0], dtype=np.float32)])
+    assert e.value.status == 3
