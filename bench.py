@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain copy kernel of known size (1 GiB read, 1 GiB written) a few times: the "
+                         "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -79,6 +82,14 @@ def main():
     ctx.set_alphabet(tabs)
     alphabet_upload_ms = (time.perf_counter() - t0) * 1e3
     out = ctx.alloc_outputs(M, K, g, emit=False)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            torch.add(src, 1.0, out=dst)                                  # reads 2^30 B, writes 2^30 B
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         ctx.pair_search(bufs[i % len(bufs)], ct, g, fmt, out=out)

@@ -33,6 +33,10 @@
 
 #include "sop_kparams.h"
 
+#ifndef SOP_K_SEARCH_OCC
+#define SOP_K_SEARCH_OCC 4          /* resident workgroups per compute unit the search-mode kernels are built for */
+#endif
+
 namespace sopk {
 
 __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
@@ -154,18 +158,23 @@ __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, 
 
 struct Cand {
     float err;    // decision score
-    float ny;     // c-weighted <w,y>, signed by the scale sign
-    float dy;     // c-weighted ||y||^2 (0 when the scale is 0: the reconstruction vanishes)
+    float ny;     // numerator of the block cosine, up to a power of the scale that cancels
+    float dy;     // squared c-norm of the reconstruction, same convention: cos = ny / sqrt(||w||^2 dy)
 };
 
 // Element pass of one (atom, sign) candidate on the lane's EPL elements.
-template <int EPL, int LPB, int METRIC, bool CODES>
+// FAST: the cosine inputs come from the residual sums through
+//   <w,w^> = ||w||^2 - <w,d>,   ||w^||^2 = ||w||^2 - 2<w,d> + ||d||^2      (all c-weighted),
+// which saves two operations per element but cancels when the reconstruction is much smaller than
+// the block (saturated or vanished scale); the caller checks dy against ||w||^2 and falls back to
+// direct_cosine_sums() for the wavefront in that case.
+template <int EPL, int LPB, int METRIC, bool CODES, bool FAST>
 __device__ __forceinline__ Cand eval_elements(const float (&w)[EPL], const float (&cb)[EPL], const float (&cw)[EPL],
                                               const float (&x)[EPL], const uint32_t (&boff)[EPL], float ss, bool nonzero,
-                                              bool negative, const char* __restrict__ bins_a, bool wide_codes,
+                                              bool negative, float wn, const char* __restrict__ bins_a, bool wide_codes,
                                               uint32_t (&codes)[EPL / 4])
 {
-    float e0 = 0.0f, e1 = 0.0f, ny = 0.0f, dy = 0.0f;
+    float e0 = 0.0f, e1 = 0.0f, ny = 0.0f, dy = 0.0f, ew = 0.0f;
     if (CODES) {
 #pragma unroll
         for (int j = 0; j < EPL / 4; ++j) codes[j] = 0;
@@ -179,10 +188,16 @@ __device__ __forceinline__ Cand eval_elements(const float (&w)[EPL], const float
         const bool up = x[i] > thr;
         const float yv = up ? yhi : ylo;
         const float d = __fmaf_rn(-ss, yv, w[i]);
-        const float cd = METRIC == 2 ? d : cb[i] * d;
-        if (i < 8) e0 = __fmaf_rn(cd, d, e0); else e1 = __fmaf_rn(cd, d, e1);
-        ny = __fmaf_rn(cw[i], yv, ny);
-        dy = __fmaf_rn(cb[i], yv * yv, dy);
+        const float cd = (METRIC == 2 && !FAST) ? d : cb[i] * d;     // MSE+FAST also needs c*d for the cosine
+        const float dd = METRIC == 2 ? d : cd;
+        if (i < 8) e0 = __fmaf_rn(dd, d, e0); else e1 = __fmaf_rn(dd, d, e1);
+        if (FAST) {
+            ny = __fmaf_rn(cd, w[i], ny);                               // <w,d>, from c*d which is at hand
+            if (METRIC == 2) ew = __fmaf_rn(cd, d, ew);                   // weighted ||d||^2 beside the unweighted score
+        } else {
+            ny = __fmaf_rn(cw[i], yv, ny);
+            dy = __fmaf_rn(cb[i], yv * yv, dy);
+        }
         if (CODES) {
             const uint32_t code = (uint32_t)clo + (up ? 1u : 0u);
             if (wide_codes) codes[i / 4] |= code << (8 * (i % 4));
@@ -192,12 +207,39 @@ __device__ __forceinline__ Cand eval_elements(const float (&w)[EPL], const float
     Cand r;
     const float err = EPL == 16 ? e0 + e1 : e0;
     r.err = group_sum<LPB>(err);
-    r.ny = group_sum<LPB>(negative ? -ny : ny);
-    const float dsum = group_sum<LPB>(dy);
-    r.dy = nonzero ? dsum : 0.0f;
+    if (FAST) {
+        const float wd = group_sum<LPB>(ny);
+        const float errw = METRIC == 2 ? group_sum<LPB>(ew) : r.err;
+        r.ny = wn - wd;
+        r.dy = __fmaf_rn(-2.0f, wd, wn) + errw;
+    } else {
+        const float nsum = group_sum<LPB>(negative ? -ny : ny);
+        const float dsum = group_sum<LPB>(dy);
+        r.ny = nonzero ? nsum : 0.0f;                                  // a zero scale reconstructs nothing
+        r.dy = nonzero ? dsum : 0.0f;
+    }
     return r;
 }
 
+// Cosine inputs straight from the codebook values (positive scale sign), used when the residual
+// form above would cancel.
+template <int EPL, int LPB>
+__device__ __forceinline__ void direct_cosine_sums(const float (&cb)[EPL], const float (&w)[EPL], const float (&x)[EPL],
+                                                   const uint32_t (&boff)[EPL], bool nonzero,
+                                                   const char* __restrict__ bins_a, float& ny_out, float& dy_out)
+{
+    float ny = 0.0f, dy = 0.0f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        const float* rp = reinterpret_cast<const float*>(bins_a + boff[i]);
+        const float yv = x[i] > rp[0] ? rp[2 * SOP_K_MAXA] : rp[SOP_K_MAXA];
+        ny = __fmaf_rn(cb[i] * w[i], yv, ny);
+        dy = __fmaf_rn(cb[i], yv * yv, dy);
+    }
+    const float nsum = group_sum<LPB>(ny), dsum = group_sum<LPB>(dy);
+    ny_out = nonzero ? nsum : 0.0f;
+    dy_out = nonzero ? dsum : 0.0f;
+}
 
 // first / second atom of the pair with lexicographic position pi among all pairs of SOP_K_MAXA atoms
 __host__ __device__ constexpr int pair_first(int pi) { int i = 0; while (pi >= SOP_K_MAXA - 1 - i) { pi -= SOP_K_MAXA - 1 - i; ++i; } return i; }
@@ -249,8 +291,10 @@ __device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, 
     if constexpr (PI + 1 < SOP_K_MAXP) all_pairs<PI + 1, LPB>(p, sw, err, dlt, acc_lane, piece);
 }
 
+// The search-mode kernels are kept within 128 registers so that four workgroups (16 wavefronts)
+// stay resident per compute unit; the variants with two scale signs or per-block outputs need more.
 template <bool BF16, int EPL, int LPB, bool SIGNED, int METRIC, bool EMIT>
-__global__ __launch_bounds__(256) void search_kernel(const KParams p)
+__global__ __launch_bounds__(256, (SIGNED || EMIT) ? 1 : SOP_K_SEARCH_OCC) void search_kernel(const KParams p)
 {
     extern __shared__ __align__(16) char s_mem[];
     // LDS: bin table | (scale, reciprocal) table | group parameters | per-lane ACos accumulators
@@ -370,7 +414,14 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                 const char* bins_a = s_bins + 4 * a;
                 const bool wide = EMIT && ((sw.wide >> a) & 1u);
                 uint32_t codes[EPL / 4];
-                Cand best = eval_elements<EPL, LPB, METRIC, EMIT>(w, cb, cw, gx, gboff, gss, gnz, false, bins_a, wide, codes);
+                constexpr bool FAST = !SIGNED;      // with two scale signs per atom the direct sums are used
+                Cand best = eval_elements<EPL, LPB, METRIC, EMIT, FAST>(w, cb, cw, gx, gboff, gss, gnz, false, wn, bins_a, wide, codes);
+                if (FAST) {
+                    // the residual form is accurate while the reconstruction carries a fair share of
+                    // the block's norm; otherwise the whole wavefront recomputes this atom directly
+                    const bool weak = !(best.dy >= 0.25f * wn);
+                    if (__builtin_expect(__any(weak) != 0, 0)) direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, bins_a, best.ny, best.dy);
+                }
                 int q = gq;
                 bool neg = false;
                 if (SIGNED) {
@@ -379,7 +430,7 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                     bool nz2;
                     uint32_t boff2[EPL], codes2[EPL / 4];
                     prepare_sign<EPL>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, q2, ss2, nz2, x2, boff2);
-                    const Cand c2 = eval_elements<EPL, LPB, METRIC, EMIT>(w, cb, cw, x2, boff2, ss2, nz2, true, bins_a, wide, codes2);
+                    const Cand c2 = eval_elements<EPL, LPB, METRIC, EMIT, false>(w, cb, cw, x2, boff2, ss2, nz2, true, wn, bins_a, wide, codes2);
                     neg = c2.err < best.err;
                     best.err = neg ? c2.err : best.err;
                     best.ny = neg ? c2.ny : best.ny;
@@ -390,9 +441,8 @@ __global__ __launch_bounds__(256) void search_kernel(const KParams p)
                         for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codes2[j] : codes[j];
                     }
                 }
-                // cosine value; a vanishing reconstruction gives 0, a zero-norm block counts as 1
-                const float prod = wn * best.dy;
-                const float cosv = prod > 0.0f ? fminf(fmaxf(best.ny * __frsqrt_rn(prod), -1.0f), 1.0f) : 0.0f;
+                // cosine value; a vanishing reconstruction has ny = 0 and gives 0, a zero-norm block counts as 1
+                const float cosv = best.ny * __frsqrt_rn(fmaxf(wn * best.dy, 1.0e-37f));
                 err[a] = best.err;
                 dlt[a] = wn > 0.0f ? 1.0f - cosv : 0.0f;
                 lds_accumulate(acc_lane + a * 256, dlt[a]);
