@@ -125,10 +125,10 @@ def main():
     ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
     ev_min_ms = float(np.min([a.elapsed_time(b) for a, b in ev]))
 
-    # algorithmic HBM bytes of one launch: every weight once, the channel norms once, selector
-    # bit planes and the ACos vectors out
-    Wr = (K // g + 31) // 32
-    alg_bytes = M * K * 2 + K * 4 + P * M * Wr * 4 + (A + P) * 8
+    # algorithmic HBM bytes of one launch: every weight once, the channel norms once, the
+    # per-block selector words and the ACos vectors out
+    sel_bytes = 2 if P <= 16 else 4                                       # one selector word per block
+    alg_bytes = M * K * 2 + K * 4 + Nb * sel_bytes + (A + P) * 8
     achieved = alg_bytes / (ev_ms * 1e-3) / 1e9
     n_groups = len({(float(t[0]), float(t[-1])) for t in tabs})           # atoms with equal endpoints share a scale
     alg_ops = algorithmic_lane_ops(M * K, g, A, n_groups, P)
@@ -167,7 +167,7 @@ def main():
         chk = ctx.pair_search(bufs[0], ct, g, fmt, out=out)
         torch.cuda.synchronize()
         d_acos = float(np.max(np.abs(chk.acos_pair.cpu().numpy()[:P] - ref.acos_pair)))
-        sel_ok = bool(np.array_equal(chk.sel_bits.cpu().numpy().view(np.uint32), ref.sel_bits))
+        sel_ok = bool(np.array_equal(chk.sel_words.cpu().numpy().view(np.uint16).astype(np.uint32), ref.sel_words))
         result["parity_in_run"] = {"max_abs_dACos": d_acos, "selector_bits_equal": sel_ok}
     print(json.dumps(result))
 

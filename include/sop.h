@@ -47,7 +47,9 @@ typedef enum { SOP_F32 = 0, SOP_BF16 = 1 } sop_dtype;
 /* Metric of the per-block finishing reassignment (Section "Per-Layer Pair Search", design axis
  * (ii): block error or ACos).  SOP_SEL_WSE: channel-norm-weighted squared error sum_i c_i (w_i -
  * w^_i)^2 (default).  SOP_SEL_MSE: unweighted squared error.  SOP_SEL_COS: per-block weighted
- * cosine. */
+ * cosine, compared without a division: with num = sum_i c_i w_i w^_i, den = sum_i c_i w^_i^2 and
+ * q = num*|num|, candidate b beats candidate a when q_b*den_a > q_a*den_b (a zero reconstruction
+ * counts as q = 0, den = 1). */
 typedef enum { SOP_SEL_WSE = 0, SOP_SEL_COS = 1, SOP_SEL_MSE = 2 } sop_metric;
 
 /* Scale word SwExMy in a b-bit container (Section "Scale Format and Metabit Allocation"): w sign
@@ -69,12 +71,14 @@ typedef struct {
 } sop_atom;
 
 /* Output buffers, all DEVICE memory owned by the caller; a NULL member is not produced.
- * A = number of atoms, P = number of pairs, N_b = M*K/g, Wr = ceil((K/g)/32). */
+ * A = number of atoms, P = number of pairs, N_b = M*K/g. */
 typedef struct {
     double*   acos_pair;   /* [P]   layer ACos with the per-block selector applied              */
     double*   acos_atom;   /* [A]   layer ACos of each atom alone                               */
-    uint32_t* sel_bits;    /* [P][M][Wr]  bit (j%32) of word j/32 of row m: 1 = second atom of the
-                              pair reconstructs block j of row m; padding bits are 0            */
+    void*     sel_words;   /* [N_b] one selector word per block (the paper keeps the selector as a
+                              per-block metabit): bit q = 1 when the second atom of pair q (index
+                              in the pair list) reconstructs the block.  uint16_t words when
+                              P <= 16, uint32_t words otherwise; 4-byte aligned                  */
     uint16_t* scale_code;  /* [A][N_b]  bit 15 = negative scale sign taken, low bits = code q   */
     uint8_t*  codes;       /* one plane per atom, back to back: M*K/2 bytes when the atom has
                               <= 16 entries (two codes per byte, even element in the low nibble),
@@ -122,7 +126,7 @@ sop_status sop_workspace_bytes(sop_ctx* ctx, int64_t M, int64_t K, int g, size_t
  *   g           block size along K: 8, 16, 32 or 64; must divide K
  *   fmt         scale word format; layer_shift_k multiplies every ideal block scale by 2^k before
  *               rounding and divides the decoded scale by it (|k| <= 64)
- *   metric      SOP_SEL_WSE or SOP_SEL_MSE (SOP_SEL_COS is reported as SOP_EINVAL by this build)
+ *   metric      SOP_SEL_WSE, SOP_SEL_MSE or SOP_SEL_COS
  *   workspace   DEVICE, at least sop_workspace_bytes() bytes
  *   out         HOST pointer to the struct of DEVICE output pointers
  *   hip_stream  a hipStream_t (NULL = the default stream)

@@ -71,7 +71,7 @@ def all_pairs(n_atoms: int) -> np.ndarray:
 class Result:
     acos_pair: np.ndarray
     acos_atom: np.ndarray
-    sel_bits: np.ndarray     # [P][M][ceil((K/g)/32)] u32
+    sel_words: np.ndarray    # [M*K/g] u32, bit p = selector of pair p
     scale_code: np.ndarray   # [A][M*K/g] u16
     codes: list              # per atom: packed code plane (u8)
     blk_err: np.ndarray      # [A][M*K/g] f32
@@ -95,11 +95,10 @@ def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k:
     P = pairs.shape[0]
     Bk = K // g
     Nb = M * Bk
-    Wr = (Bk + 31) // 32
     plane = [M * K // 2 if t.size <= 16 else M * K for t in tabs]
     acos_pair = np.zeros(max(P, 1), dtype=np.float64)
     acos_atom = np.zeros(A, dtype=np.float64)
-    sel = np.zeros((max(P, 1), M, Wr), dtype=np.uint32)
+    sel = np.zeros(Nb, dtype=np.uint32)
     sc = np.zeros((A, Nb), dtype=np.uint16)
     # one code plane per atom, back to back: half a byte per element up to 16 entries, else a byte
     codes = np.zeros(sum(plane), dtype=np.uint8) if want_codes else None
@@ -121,7 +120,7 @@ def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k:
     if codes is not None:
         offs = np.concatenate([[0], np.cumsum(plane)])
         code_list = [codes[offs[a]:offs[a + 1]] for a in range(A)]
-    return Result(acos_pair[:P], acos_atom, sel[:P], sc, code_list, be, bc)
+    return Result(acos_pair[:P], acos_atom, sel, sc, code_list, be, bc)
 
 
 def unpack_codes(plane: np.ndarray, n_entries: int, M: int, K: int) -> np.ndarray:

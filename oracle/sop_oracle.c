@@ -193,7 +193,7 @@ static void eval_candidate(const float* w, const float* c, int g, const float* L
  *   atoms      concatenated ascending tables, n_entries[a] values each
  *   pair_ab    [2*P] atom indices (a,b) of each pair
  *   acos_pair  [P], acos_atom [A]                       binary64
- *   sel_bits   [P][M][ceil((K/g)/32)] u32, bit j%32 of word j/32 of row m = selector of block j
+ *   sel_words  [M*K/g] u32, one word per block: bit p = selector of pair p (1: the pair's second atom)
  *   scale_code [A][M*K/g] u16, bit 15 = negative sign taken, low bits = magnitude code
  *   codes      one plane per atom, planes back to back: M*K/2 bytes when n_entries <= 16 (two
  *              codes per byte, even element in the low nibble), otherwise M*K bytes
@@ -205,11 +205,12 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
                      int n_atoms, const int* n_entries, const float* atoms,
                      int n_pairs, const int* pair_ab,
                      const sopo_fmt* fmt, int k, int metric,
-                     double* acos_pair, double* acos_atom, uint32_t* sel_bits, uint16_t* scale_code,
+                     double* acos_pair, double* acos_atom, uint32_t* sel_words, uint16_t* scale_code,
                      uint8_t* codes, float* blk_err, float* blk_cos, int n_threads)
 {
     if (M <= 0 || K <= 0 || g <= 0 || g > 64 || K % g != 0 || ldw < K) return -1;
     if (n_atoms < 1 || n_atoms > SOPO_MAX_ATOMS) return -2;
+    if (n_pairs < 0 || n_pairs > 32) return -4;
     int chunk = g < 8 ? g : 8;
     if (g % chunk != 0 || ((g / chunk) & (g / chunk - 1)) != 0) return -1;
     if (fmt->max_code < 1 || fmt->max_code >= (1 << (fmt->exp_bits + fmt->man_bits))) return -3;
@@ -234,14 +235,14 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
         if (pair_ab[2 * p] < 0 || pair_ab[2 * p] >= n_atoms || pair_ab[2 * p + 1] < 0 || pair_ab[2 * p + 1] >= n_atoms)
             return -4;
 
-    const int64_t Bk = K / g, Nb = M * Bk, Wr = (Bk + 31) / 32;
+    const int64_t Bk = K / g, Nb = M * Bk;
     int64_t code_off[SOPO_MAX_ATOMS + 1];
     code_off[0] = 0;
     for (int a = 0; a < n_atoms; ++a) code_off[a + 1] = code_off[a] + (n_entries[a] <= 16 ? M * K / 2 : M * K);
     const int is_signed = fmt->sign_bits != 0;
     double* row_sum = (double*)calloc((size_t)M * (size_t)(n_atoms + n_pairs), sizeof(double));
     if (!row_sum) return -5;
-    if (sel_bits) memset(sel_bits, 0, (size_t)n_pairs * (size_t)M * (size_t)Wr * sizeof(uint32_t));
+    if (sel_words) memset(sel_words, 0, (size_t)Nb * sizeof(uint32_t));
 
 #ifdef _OPENMP
     if (n_threads > 0) omp_set_num_threads(n_threads);
@@ -290,7 +291,7 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
                 const cand* cb2 = &best[pair_ab[2 * p + 1]];
                 int sel = better(cb2, ca, metric);
                 rs[n_atoms + p] += sel ? cb2->cosv : ca->cosv;
-                if (sel && sel_bits) sel_bits[((int64_t)p * M + m) * Wr + j / 32] |= (uint32_t)1 << (j % 32);
+                if (sel && sel_words) sel_words[m * Bk + j] |= (uint32_t)1 << p;
             }
         }
     }

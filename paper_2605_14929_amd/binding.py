@@ -31,7 +31,7 @@ class _Atom(C.Structure):
 
 
 class _Outputs(C.Structure):
-    _fields_ = [("acos_pair", C.c_void_p), ("acos_atom", C.c_void_p), ("sel_bits", C.c_void_p),
+    _fields_ = [("acos_pair", C.c_void_p), ("acos_atom", C.c_void_p), ("sel_words", C.c_void_p),
                 ("scale_code", C.c_void_p), ("codes", C.c_void_p), ("blk_cos", C.c_void_p), ("blk_err", C.c_void_p)]
 
 
@@ -170,7 +170,7 @@ class Outputs:
     """Device tensors produced by Context.pair_search (None when not requested)."""
     acos_pair: object = None
     acos_atom: object = None
-    sel_bits: object = None
+    sel_words: object = None
     scale_code: object = None
     codes: object = None
     code_planes: list = None
@@ -231,12 +231,13 @@ class Context:
         import torch
         dev = torch.device("cuda", self.device)
         A, P, Bk = self.n_atoms, self.n_pairs, K // g
-        Nb, Wr = M * Bk, (Bk + 31) // 32
+        Nb = M * Bk
         o = Outputs()
         o.acos_atom = torch.empty(A, dtype=torch.float64, device=dev)
         o.acos_pair = torch.empty(max(P, 1), dtype=torch.float64, device=dev)
         if sel and P:
-            o.sel_bits = torch.empty((P, M, Wr), dtype=torch.int32, device=dev)
+            # one selector word per block: 16-bit words up to 16 pairs, 32-bit words beyond
+            o.sel_words = torch.empty(Nb, dtype=torch.int16 if P <= 16 else torch.int32, device=dev)
         if emit:
             o.scale_code = torch.empty((A, Nb), dtype=torch.int16, device=dev)
             planes = [M * K // 2 if n <= 16 else M * K for n in self.n_entries]
@@ -275,7 +276,7 @@ class Context:
         def ptr(t):
             return None if t is None else C.c_void_p(t.data_ptr())
 
-        o = _Outputs(ptr(out.acos_pair), ptr(out.acos_atom), ptr(out.sel_bits), ptr(out.scale_code), ptr(out.codes),
+        o = _Outputs(ptr(out.acos_pair), ptr(out.acos_atom), ptr(out.sel_words), ptr(out.scale_code), ptr(out.codes),
                      ptr(out.blk_cos), ptr(out.blk_err))
         _check(lib().sop_pair_search(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
                                      fmt, k, metric, C.c_void_p(self._ws.data_ptr()), self._ws.numel(), C.byref(o),

@@ -16,8 +16,8 @@
 
 #include "sop_kparams.h"
 
-extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int metric, int emit);
-extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
+extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
 
 namespace {
@@ -43,12 +43,13 @@ struct sop_ctx {
     int order[SOP_K_MAXA] = {0};          // internal index -> caller's index
     int grp_first[SOP_K_MAXA] = {0};
     float tpos[SOP_K_MAXA] = {0}, tneg[SOP_K_MAXA] = {0}, bin_sc[SOP_K_MAXA] = {0}, bin_off[SOP_K_MAXA] = {0};
+    float bin_lo[SOP_K_MAXA] = {0}, bin_hi[SOP_K_MAXA] = {0};
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
     BinRec* d_bins = nullptr;             // [MAXA][MAXBINS] capacity
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
-    int occ_blocks[128];                  // resident workgroups per CU of each kernel variant (0 = unknown)
-    size_t occ_lds[128];
+    int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
+    size_t occ_lds[192];
     long long waves_override = 0;
     std::string err;
 };
@@ -120,8 +121,9 @@ static void default_pairs(sop_ctx* c)
     c->n_pairs = p;
 }
 
-// Bin of a scaled weight, exactly as the kernel computes it: clamp to the atom's range, one fma
-// whose constant term carries 1.5*2^23 (so the sum is rounded to an integer), bin = low bits.
+// Bin of a scaled weight, exactly as the kernel computes it: clamp to the range the table covers
+// (the kernel skips the clamp when it knows the value is inside), one fma whose constant term
+// carries 1.5*2^23 (so the sum is rounded to an integer), bin = low bits.
 static int bin_of(float x, float xl, float xh, float sc, float off)
 {
     const float xc = std::fmin(std::fmax(x, xl), xh);
@@ -129,8 +131,9 @@ static int bin_of(float x, float xl, float xh, float sc, float off)
     return (int)(f2u(t) - f2u(SOP_K_BIN_MAGIC));
 }
 
-// Fill atom slot `ia` of the bin records; false when some bin would hold two code boundaries or the
-// binning leaves [0, n_bins).
+// Fill atom slot `ia` of the bin records for the table range [xl, xh] (wider than the atom: values
+// beyond the atom's endpoints take its first / last entry); false when some bin would hold two code
+// boundaries or the binning leaves [0, n_bins).
 static bool build_bins(const std::vector<float>& L, float xl, float xh, float sc, float off, int n_bins, int ia, BinRec* rec)
 {
     const int N = (int)L.size();
@@ -176,7 +179,7 @@ struct AlphabetPlan {
     std::vector<std::vector<float>> tabs;      // caller's order
     int n_atoms = 0;
     int order[SOP_K_MAXA] = {0}, grp_first[SOP_K_MAXA] = {0};
-    float sc[SOP_K_MAXA] = {0}, off[SOP_K_MAXA] = {0};
+    float sc[SOP_K_MAXA] = {0}, off[SOP_K_MAXA] = {0}, lo[SOP_K_MAXA] = {0}, hi[SOP_K_MAXA] = {0};
     int n_bins = 0;
     std::vector<BinRec> img;
 };
@@ -211,24 +214,26 @@ static sop_status plan_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms, 
                 used[b] = true; pl.grp_first[n] = (b == a); pl.order[n++] = b;
             }
     }
-    // smallest bin count for which every bin of every atom holds at most one code boundary
-    // (up to 64 bins the table reads are free of bank conflicts)
-    static const int kBinCounts[] = {16, 24, 32, 40, 48, 56, 64, 96, 128, 192, 256, 384, 512};
+    // smallest bin count for which every bin of every atom holds at most one code boundary.  The
+    // table spans SOP_K_BIN_EXT times the atom's range, so that a block whose scale was rounded down
+    // needs no clamp.
+    static const int kBinCounts[] = {16, 24, 32, 40, 48, 56, 64, 80, 96, 112, 128, 160, 192, 256, 384, 512, 768, 1024};
     for (int nb : kBinCounts) {
         pl.img.assign((size_t)nb, BinRec{});
         bool ok = true;
         for (int i = 0; i < n_atoms && ok; ++i) {
             const std::vector<float>& L = pl.tabs[pl.order[i]];
-            const float xl = L.front(), xh = L.back();
+            const float xl = L.front() * SOP_K_BIN_EXT, xh = L.back() * SOP_K_BIN_EXT;
             // the additive constant is an integer-valued float, so the rounded sum lies within
             // [-0.5, nb-1] of 1.5*2^23: bins 0 .. nb-1
             pl.sc[i] = (float)(((double)nb - 1.5) / ((double)xh - (double)xl));
             pl.off[i] = (float)((double)SOP_K_BIN_MAGIC - (double)xl * (double)pl.sc[i]);
+            pl.lo[i] = xl; pl.hi[i] = xh;
             ok = build_bins(L, xl, xh, pl.sc[i], pl.off[i], nb, i, pl.img.data());
         }
         if (ok) { pl.n_bins = nb; break; }
     }
-    if (!pl.n_bins) return fail(c, SOP_EATOM, "atom entries are too closely spaced (two code boundaries within 1/512 of the atom's range)");
+    if (!pl.n_bins) return fail(c, SOP_EATOM, "atom entries are too closely spaced (two code boundaries within 1/650 of the atom's range)");
     return SOP_OK;
 }
 
@@ -250,7 +255,7 @@ extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_
         const std::vector<float>& L = c->tables[pl.order[i]];
         c->order[i] = pl.order[i]; c->grp_first[i] = pl.grp_first[i];
         c->tpos[i] = L.back(); c->tneg[i] = -L.front(); c->nent[i] = (int)L.size();
-        c->bin_sc[i] = pl.sc[i]; c->bin_off[i] = pl.off[i];
+        c->bin_sc[i] = pl.sc[i]; c->bin_off[i] = pl.off[i]; c->bin_lo[i] = pl.lo[i]; c->bin_hi[i] = pl.hi[i];
     }
     std::memset(c->occ_blocks, 0, sizeof(c->occ_blocks));
     default_pairs(c);
@@ -272,7 +277,7 @@ extern "C" sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int
         auto check = [&](float x) {
             int code = 0;
             for (int j = 0; j + 1 < N; ++j) code += x > mid[j];
-            const int b = bin_of(x, xl, xh, pl.sc[i], pl.off[i]);
+            const int b = bin_of(x, pl.lo[i], pl.hi[i], pl.sc[i], pl.off[i]);
             if (b < 0 || b >= pl.n_bins) return false;
             const BinRec& r = pl.img[b];
             const bool up = x > r.thr[i];
@@ -287,8 +292,9 @@ extern "C" sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int
             float lo = centre, hi = centre;
             for (int t = 0; t < 64 && ok; ++t) { ok = check(lo) && check(hi); lo = std::nextafter(lo, -inf); hi = std::nextafter(hi, inf); }
         }
-        for (int t = 0; t <= 200000 && ok; ++t) ok = check(xl * 1.25f + (xh - xl) * 1.25f * (float)t / 200000.0f);
-        for (int64_t k = ford(xl); k <= ford(xh) && ok; k += 4099) ok = check(funord(k));
+        for (int t = 0; t <= 200000 && ok; ++t) ok = check(xl * 2.0f + (xh - xl) * 2.0f * (float)t / 200000.0f);
+        for (int64_t k = ford(pl.lo[i]); k <= ford(pl.hi[i]) && ok; k += 4099) ok = check(funord(k));
+        ok = ok && check(pl.lo[i]) && check(pl.hi[i]) && check(std::nextafter(pl.lo[i], -inf)) && check(std::nextafter(pl.hi[i], inf));
         ok = ok && check(-inf) && check(inf) && check(-3.0e38f) && check(3.0e38f) && check(0.0f) && check(-0.0f);
         if (!ok) return fail(nullptr, SOP_EATOM, "sop_check_alphabet: the bin table disagrees with the direct search");
     }
@@ -370,14 +376,13 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     if (!W || !cn || !out) return fail(c, SOP_EINVAL, "sop_pair_search: W, c and out must not be NULL");
     if (c->n_atoms < 1) return fail(c, SOP_EINVAL, "sop_pair_search: no alphabet set");
     if (dtype != SOP_F32 && dtype != SOP_BF16) return fail(c, SOP_EINVAL, "sop_pair_search: dtype must be SOP_F32 or SOP_BF16");
-    if (metric == SOP_SEL_COS) return fail(c, SOP_EINVAL, "sop_pair_search: SOP_SEL_COS is not available in this build");
-    if (metric != SOP_SEL_WSE && metric != SOP_SEL_MSE) return fail(c, SOP_EINVAL, "sop_pair_search: unknown metric");
+    if (metric != SOP_SEL_WSE && metric != SOP_SEL_MSE && metric != SOP_SEL_COS) return fail(c, SOP_EINVAL, "sop_pair_search: unknown metric");
     if (sop_status s = shape_check(c, M, K, g)) return s;
     if (ldw < K) return fail(c, SOP_ESHAPE, "ldw must be at least K");
     const int esz = dtype == SOP_BF16 ? 2 : 4;
     if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
     if (!aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
-    if ((out->sel_bits && (reinterpret_cast<uintptr_t>(out->sel_bits) & 3u)) || (out->codes && (reinterpret_cast<uintptr_t>(out->codes) & 3u)) ||
+    if ((out->sel_words && (reinterpret_cast<uintptr_t>(out->sel_words) & 3u)) || (out->codes && (reinterpret_cast<uintptr_t>(out->codes) & 3u)) ||
         (out->scale_code && (reinterpret_cast<uintptr_t>(out->scale_code) & 1u)))
         return fail(c, SOP_EINVAL, "output buffers must be naturally aligned");
 
@@ -406,7 +411,7 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     p.W = W; p.c = cn;
     p.bins = c->d_bins;
     p.M = M; p.K = K; p.ldw = ldw;
-    p.Bk = K / g; p.Nb = M * p.Bk; p.Wr = (p.Bk + 31) / 32;
+    p.Bk = K / g; p.Nb = M * p.Bk;
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * M;
     p.A = A; p.P = c->n_pairs; p.lpb = lpb;
@@ -420,6 +425,7 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     int internal_of[SOP_K_MAXA];
     for (int i = 0; i < A; ++i) {
         p.tpos[i] = c->tpos[i]; p.tneg[i] = c->tneg[i]; p.bin_sc[i] = c->bin_sc[i]; p.bin_off[i] = c->bin_off[i];
+        p.bin_lo[i] = c->bin_lo[i]; p.bin_hi[i] = c->bin_hi[i];
         if (c->grp_first[i]) p.grp_first_mask |= 1u << i;
         if (c->tpos[i] == 1.0f) p.unit_tpos |= 1u << i;
         if (c->tneg[i] == 1.0f) p.unit_tneg |= 1u << i;
@@ -433,18 +439,15 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
         const int ia = internal_of[c->pairs[2 * q]], ib = internal_of[c->pairs[2 * q + 1]];
         const int i = std::min(ia, ib), j = std::max(ia, ib), pi = pair_index(i, j);
         p.pair_mask |= 1u << pi;
-        if (ia > ib) p.flip_mask |= 1u << pi;
+        if (ia > ib) { p.flip_mask |= 1u << pi; p.flip_slots |= 1u << q; }
         p.pair_slot[pi] = (signed char)q;
-    }
-    for (int q = 0; q < c->n_pairs; ++q) {
-        const int ia = internal_of[c->pairs[2 * q]], ib = internal_of[c->pairs[2 * q + 1]];
-        const int pi = pair_index(std::min(ia, ib), std::max(ia, ib));
-        p.pair_col[q] = (unsigned char)__builtin_popcount(p.pair_mask & ((1u << pi) - 1u));
+        p.pair_pi[q] = (unsigned char)pi;
     }
     p.partial = static_cast<float*>(ws);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
     p.acos_atom = out->acos_atom;
-    p.sel_bits = c->n_pairs ? out->sel_bits : nullptr;
+    p.sel_words = c->n_pairs ? out->sel_words : nullptr;
+    p.sel_u32 = c->n_pairs > 16 ? 1 : 0;
     p.scale_code = out->scale_code; p.codes = out->codes; p.blk_cos = out->blk_cos; p.blk_err = out->blk_err;
     const int emit = (p.scale_code || p.codes || p.blk_cos || p.blk_err) ? 1 : 0;
 
@@ -457,9 +460,10 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
         p.n_tab_codes = t.n;
     }
     const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
-                           SOP_K_MAXA * sizeof(float4) + (size_t)(A + c->n_pairs) * 256 * sizeof(float);
-    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, w, (int)metric, emit);
-    const int vi = sopk_variant_index(dtype == SOP_BF16, g, w, (int)metric, emit);
+                           2 * SOP_K_MAXA * sizeof(float4) + 4 * SOP_K_NCOL * sizeof(float);
+    const int na8 = A > 6 ? 1 : 0;
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, w, (int)metric, emit, na8);
+    const int vi = sopk_variant_index(dtype == SOP_BF16, g, w, (int)metric, emit, na8);
     hipError_t e = hipSuccess;
     if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
         if (dyn_lds > 48 * 1024) {

@@ -5,14 +5,21 @@
 
 #define SOP_K_MAXA 8                 /* atoms                                        */
 #define SOP_K_MAXP 28                /* pairs i < j among SOP_K_MAXA atoms           */
-#define SOP_K_NCOL (SOP_K_MAXA + SOP_K_MAXP)
-#define SOP_K_MAXBINS 512            /* bins of the element-search table                        */
+#define SOP_K_NCOL (SOP_K_MAXA + SOP_K_MAXP + 1)   /* sum columns: atoms, pairs, zero-norm lane count */
+#define SOP_K_ZCOL (SOP_K_MAXA + SOP_K_MAXP)
+#define SOP_K_MAXBINS 1024           /* bins of the element-search table                        */
 #define SOP_K_MAXTABCODES 2048       /* scale codes whose (scale, reciprocal) pair is tabulated */
 #define SOP_K_BIN_WORDS (4 * SOP_K_MAXA + 1)   /* words of one bin record (odd: conflict-free banks)  */
 #define SOP_K_BIN_BYTES (4 * SOP_K_BIN_WORDS)
 #define SOP_K_BIN_MAGIC 12582912.0f  /* 1.5 * 2^23: one unit in the last place is 1               */
 /* bits(MAGIC + v) = 0x4B400000 + v; the 24-bit multiply sees 0x400000 + v: subtract its product */
 #define SOP_K_BIN_NEGC (0u - 0x400000u * (unsigned)SOP_K_BIN_BYTES)
+/* The bin table covers scaled weights from BIN_EXT * L[0] to BIN_EXT * L[N-1]: a block scale that
+ * was rounded down (by at most a factor 1.5, in the subnormal range of the scale word) leaves every
+ * scaled weight inside the table without a clamp.  Blocks whose scale saturated take a clamped path,
+ * selected when ideal scale / rounded scale exceeds BIN_SAFE. */
+#define SOP_K_BIN_EXT 1.5625f
+#define SOP_K_BIN_SAFE 1.55f
 
 #if defined(__HIPCC__)
 #define SOP_K_HD __host__ __device__
@@ -43,7 +50,6 @@ struct KParams {
     long long M, K, ldw;
     long long Bk;                    // blocks per row
     long long Nb;                    // blocks in the layer
-    long long Wr;                    // selector words per row
     long long strips;                // 64-lane strips per row
     long long total_units;           // strips * M
     long long n_waves;               // wavefronts launched (multiple of 4)
@@ -56,7 +62,8 @@ struct KParams {
     float sub_quantum;               // 2^(1-bias-man_bits-k)
     // atoms, internal order
     float tpos[SOP_K_MAXA], tneg[SOP_K_MAXA];      // t+ and -t-
-    float bin_sc[SOP_K_MAXA], bin_off[SOP_K_MAXA]; // bin = bits(fma(clamp(x), sc, off)) - bits(magic)
+    float bin_sc[SOP_K_MAXA], bin_off[SOP_K_MAXA]; // bin = bits(fma(x, sc, off)) - bits(magic)
+    float bin_lo[SOP_K_MAXA], bin_hi[SOP_K_MAXA];  // range of x the table covers (clamped path)
     unsigned int grp_first_mask;                   // bit a: first atom of its scale group
     unsigned int unit_tpos, unit_tneg;             // bit a: the endpoint is exactly 1 (no division needed)
     unsigned int wide_mask;                        // bit a: more than 16 entries (one byte per code)
@@ -64,13 +71,15 @@ struct KParams {
     long long code_off[SOP_K_MAXA];                // byte offset of the atom's code plane
     unsigned int pair_mask;                           // bit pair_index(i,j): the pair is requested
     unsigned int flip_mask;                           // bit pair_index(i,j): the caller's first atom is internal j
+    unsigned int flip_slots;                          // bit q: output pair q is such a swapped pair
     signed char pair_slot[SOP_K_MAXP];                // output index of pair pair_index(i,j), or -1
-    unsigned char pair_col[SOP_K_MAXP];               // rank of output o's pair among the requested pairs, by pair_index
+    unsigned char pair_pi[SOP_K_MAXP];                // pair_index(i,j) of output o
     // outputs
-    float*    partial;               // [NCOL][n_waves/4] per-workgroup sums of 1-cos
+    float*    partial;               // [SOP_K_NCOL][n_waves/4] per-workgroup sums of 1-cos
     double*   acos_pair;
     double*   acos_atom;
-    uint32_t* sel_bits;
+    void*     sel_words;             // [Nb] selector word of every block
+    int       sel_u32;               // 1: 32-bit selector words, 0: 16-bit
     uint16_t* scale_code;
     uint8_t*  codes;
     float*    blk_cos;

@@ -1,0 +1,656 @@
+// Pair-search kernel for gfx950 (MI355X).  This file is compiled once per (weight dtype, metric)
+// part; SOPK_PART_BF16 and SOPK_PART_METRIC select which instantiations the object holds.
+//
+// Work mapping.  A lane owns EPL = min(g,16) consecutive elements of one row (one block when
+// g <= 16, a half or a quarter of a block when g = 32 / 64: LPB = g/EPL lanes cooperate through
+// cross-lane exchanges).  A wavefront covers a "strip" of 64*EPL consecutive columns of one row
+// per step and walks down the rows of that strip, so the channel norms of the strip stay in
+// registers.  The (strip,row) steps of the whole layer are cut into equal contiguous ranges, one
+// per resident wavefront, so every SIMD gets the same amount of work whatever the shape.  The
+// weights of the next step are requested before the current step is evaluated.
+//
+// Every block is read from HBM exactly once.  LDS holds a table over uniform bins of the scaled
+// weight x: for every atom each bin contains at most one code boundary, so the nearest entry is a
+// table read and one compare.  A bin is a record of 33 words (boundary, lower value, upper value
+// and lower code of each of the 8 atoms, one word of padding): the odd stride puts the same field
+// of 32 consecutive bins into 32 different banks.  For scale words of up to 11 magnitude bits LDS
+// also holds the (scale, reciprocal) pair of every scale code.
+//
+// Atoms with equal endpoints form a scale group: they share the ideal scale, the scale code and the
+// scaled weights, which are computed once per group.
+//
+// Arithmetic contract (what makes the integer outputs reproducible on any implementation):
+//   scale      s* = max(pmax/t+, nmax/-t-)  (IEEE division), times 2^k, rounded to the scale word
+//              (nearest, ties to the lower code, saturating), s = value(q) * 2^-k, r = 1/s (IEEE)
+//   element    x = fl(w*r); code = number of midpoints strictly below x
+//   error      d = fma(-s, L[code], w);  err = sum fma(fl(c*d), d, .) over chunks of 8 consecutive
+//              elements, chunk partials added in a balanced tree in index order
+//   cosine     (metric COS only) w^ = fl(s*L[code]); num = sum fma(fl(c*w), w^, .),
+//              den = sum fma(fl(c*w^), w^, .), same chunks and tree
+//   selection  metrics WSE / MSE: strictly smaller err wins (second atom of a pair, negative scale
+//              sign); metric COS: b beats a when fl(q_b*den_a) > fl(q_a*den_b), q = fl(num*|num|),
+//              a zero reconstruction counting as q = 0, den = 1
+// The cosine values are not decisions; they are evaluated in fp32 and accumulated per lane as the
+// deficit 1 - cos, reduced in binary64 by the second kernel.  A lane whose block has zero weighted
+// norm adds exactly 1 to every column and 1 to a count column that the second kernel subtracts.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sop_kparams.h"
+
+#ifndef SOPK_PART_BF16
+#error "compile with -DSOPK_PART_BF16=0|1 -DSOPK_PART_METRIC=0|1|2"
+#endif
+
+namespace sopk {
+
+__device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+template <int LPB> __device__ __forceinline__ float group_max(float v)
+{
+    if (LPB >= 2) v = fmaxf(v, xor_lanes(v, 1));
+    if (LPB >= 4) v = fmaxf(v, xor_lanes(v, 2));
+    return v;
+}
+// balanced tree over the lanes of a block, in lane (= index) order; both partners compute the
+// same rounded sum because addition commutes
+template <int LPB> __device__ __forceinline__ float group_sum(float v)
+{
+    if (LPB >= 2) v = v + xor_lanes(v, 1);
+    if (LPB >= 4) v = v + xor_lanes(v, 2);
+    return v;
+}
+
+// wave-uniform switches of the row loop
+struct Switches {
+    int A;
+    uint32_t pair_mask, flip_mask, grp_first, unit_tpos, unit_tneg, wide;
+};
+
+// round a non-negative fp32 to the scale word: nearest, ties to the lower code, saturating
+__device__ __forceinline__ int encode_scale(float sp, const KParams& p)
+{
+    const uint32_t u = __float_as_uint(sp);
+    const int E = (int)(u >> 23);
+    const int y = p.man_bits;
+    // normal range of the target: rebias the exponent, round the 23-bit mantissa to y bits
+    const uint32_t ut = u - ((uint32_t)(127 - p.bias) << 23);
+    uint32_t q = (ut + ((1u << (22 - y)) - 1u)) >> (23 - y);
+    const bool sub = E < 128 - p.bias;
+    if (__any(sub)) {
+        // subnormal range of the target (or zero): quantum 2^(1-bias-y)
+        const int Ee = E > 0 ? E : 1;
+        const uint32_t m = (u & 0x7FFFFFu) | (E > 0 ? 0x800000u : 0u);
+        int S = 151 - p.bias - y - Ee;
+        S = S > 31 ? 31 : S;
+        const uint32_t qs = S > 0 ? ((m + ((1u << (S - 1)) - 1u)) >> S) : 0u;
+        q = sub ? qs : q;
+    }
+    return (int)(q > (uint32_t)p.max_code ? (uint32_t)p.max_code : q);
+}
+
+// value(q) * 2^-k (exact) and its IEEE reciprocal (0 for the zero scale)
+__device__ __forceinline__ void decode_scale(int q, const KParams& p, const float2* __restrict__ s_tab, float& s, float& rinv)
+{
+    if (p.n_tab_codes) {
+        const float2 t = s_tab[q];
+        s = t.x;
+        rinv = t.y;
+    } else {
+        const int y = p.man_bits;
+        const int e = q >> y, f = q & ((1 << y) - 1);
+        const float nrm = __uint_as_float(((uint32_t)(e - p.bias - p.k + 127) << 23) | ((uint32_t)f << (23 - y)));
+        const float sub = (float)f * p.sub_quantum;
+        s = e > 0 ? nrm : sub;
+        rinv = s > 0.0f ? 1.0f / s : 0.0f;
+    }
+}
+
+// ideal scale of a block against endpoints (tp, -tn); a unit endpoint needs no division
+__device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, float tn, bool unit_p, bool unit_n)
+{
+    float s1 = pmax, s2 = nmax;
+    if (!unit_p) s1 = pmax / tp;
+    if (!unit_n) s2 = nmax / tn;
+    return fmaxf(s1, s2);
+}
+
+// Scale of one (group, sign): code q, signed scale ss, scaled weights x and their bin offsets.
+// boff receives the LDS byte address of each element's bin record (lds_neg = table address minus the
+// product the 24-bit multiply adds for the constant's exponent bits).
+template <int EPL>
+__device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, float nmax, bool negative, int a,
+                                             const KParams& p, const Switches& sw, const float2* __restrict__ s_tab,
+                                             const float4* __restrict__ s_gpar, uint32_t lds_neg,
+                                             int& q, float& ss, bool& nonzero, float (&x)[EPL], uint32_t (&boff)[EPL])
+{
+    const float4 gp = s_gpar[2 * a];                   // (t+, -t-, bin scale, bin offset): same address in every lane
+    const float tp = gp.x, tn = gp.y;
+    const bool unit_p = (sw.unit_tpos >> a) & 1u, unit_n = (sw.unit_tneg >> a) & 1u;
+    const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp, unit_n, unit_p) : ideal_scale(pmax, nmax, tp, tn, unit_p, unit_n);
+    q = encode_scale(sstar * p.pow2k, p);
+    float s, rinv;
+    decode_scale(q, p, s_tab, s, rinv);
+    ss = negative ? -s : s;
+    nonzero = s > 0.0f;
+    const float rr = negative ? -rinv : rinv;
+    const float sc = gp.z, off = gp.w;
+    // the table covers a scale rounded down by up to the factor SOP_K_BIN_SAFE; beyond it (the scale
+    // word saturated) the whole wavefront clamps its scaled weights into the table's range
+    const bool beyond = !(sstar * rinv <= SOP_K_BIN_SAFE);
+    if (__builtin_expect(__any(beyond) != 0, 0)) {
+        const float4 g2 = s_gpar[2 * a + 1];           // (table range low, high, -, -)
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            x[i] = w[i] * rr;
+            const float xc = __builtin_amdgcn_fmed3f(x[i], g2.x, g2.y);
+            boff[i] = __umul24(__float_as_uint(__fmaf_rn(xc, sc, off)), SOP_K_BIN_BYTES) + lds_neg;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            x[i] = w[i] * rr;
+            // off carries 1.5*2^23, so the low mantissa bits of the sum are the bin number; one 24-bit
+            // multiply-add turns them into the byte offset of the bin record
+            boff[i] = __umul24(__float_as_uint(__fmaf_rn(x[i], sc, off)), SOP_K_BIN_BYTES) + lds_neg;
+        }
+    }
+}
+
+// Sums of one (atom, sign) candidate over the lane's elements, before the cross-lane tree.
+struct Sums {
+    float err;    // decision score of metrics WSE / MSE (and the blk_err output)
+    float wd;     // RESIDUAL form: <w,d>_c;  DIRECT form: numerator sum
+    float ew;     // RESIDUAL form with metric MSE: c-weighted ||d||^2;  DIRECT form: denominator sum
+};
+
+// One bin record read: boundary, value below, value above (and the lower code when codes are wanted).
+// `addr` is the LDS byte address of the record and A the atom's slot in it: all four reads are
+// register + immediate offset.
+typedef __attribute__((address_space(3))) const float lds_cfloat;
+typedef __attribute__((address_space(3))) const int lds_cint;
+struct Rec { float thr, ylo, yhi; int clo; };
+template <bool CODES>
+__device__ __forceinline__ Rec read_rec(uint32_t addr, int a)
+{
+    lds_cfloat* rp = (lds_cfloat*)(size_t)addr;
+    Rec r;
+    r.thr = rp[a]; r.ylo = rp[SOP_K_MAXA + a]; r.yhi = rp[2 * SOP_K_MAXA + a];
+    r.clo = CODES ? ((lds_cint*)(size_t)addr)[3 * SOP_K_MAXA + a] : 0;
+    return r;
+}
+
+template <int EPL, bool CODES>
+__device__ __forceinline__ void put_code(uint32_t (&codes)[EPL / 4], int i, uint32_t code, bool wide_codes)
+{
+    if (CODES) {
+        if (wide_codes) codes[i / 4] |= code << (8 * (i % 4));
+        else codes[i / 8] |= code << (4 * (i % 8));
+    }
+}
+
+// Element pass, RESIDUAL form (metrics WSE and MSE): the cosine inputs come from the residual sums
+//   <w,w^> = ||w||^2 - <w,d>,   ||w^||^2 = ||w||^2 - 2<w,d> + ||d||^2      (all c-weighted),
+// which shares c*d with the error sum.  The form cancels when the reconstruction is much smaller
+// than the block (saturated or vanished scale); the caller checks that and falls back to
+// direct_cosine_sums() for the wavefront.
+template <int EPL, int METRIC, bool CODES>
+__device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float (&cb)[EPL], const float (&x)[EPL],
+                                              const uint32_t (&boff)[EPL], float ss, int a,
+                                              bool wide_codes, uint32_t (&codes)[EPL / 4])
+{
+    float e0 = 0.0f, e1 = 0.0f, wd = 0.0f, ew = 0.0f;
+    if (CODES) {
+#pragma unroll
+        for (int j = 0; j < EPL / 4; ++j) codes[j] = 0;
+    }
+#pragma unroll
+    for (int i0 = 0; i0 < EPL; i0 += 4) {
+        Rec r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = read_rec<CODES>(boff[i0 + j], a);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = i0 + j;
+            const bool up = x[i] > r[j].thr;
+            const float yv = up ? r[j].yhi : r[j].ylo;
+            const float d = __fmaf_rn(-ss, yv, w[i]);
+            const float cd = cb[i] * d;
+            const float dd = METRIC == 2 ? d : cd;
+            if (i < 8) e0 = __fmaf_rn(dd, d, e0); else e1 = __fmaf_rn(dd, d, e1);
+            wd = __fmaf_rn(cd, w[i], wd);
+            if (METRIC == 2) ew = __fmaf_rn(cd, d, ew);
+            put_code<EPL, CODES>(codes, i, (uint32_t)r[j].clo + (up ? 1u : 0u), wide_codes);
+        }
+    }
+    Sums s;
+    s.err = EPL == 16 ? e0 + e1 : e0;
+    s.wd = wd;
+    s.ew = ew;
+    return s;
+}
+
+// Element pass, DIRECT form with the decision sums of metric COS:
+//   w^ = fl(ss*y), num = sum fma(fl(c*w), w^), den = sum fma(fl(c*w^), w^), chunks of 8 and the tree;
+// err is formed as well when WANT_ERR (the blk_err output).
+template <int EPL, bool CODES, bool WANT_ERR>
+__device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (&cb)[EPL], const float (&x)[EPL],
+                                            const uint32_t (&boff)[EPL], float ss, int a,
+                                            bool wide_codes, uint32_t (&codes)[EPL / 4])
+{
+    float e0 = 0.0f, e1 = 0.0f, n0 = 0.0f, n1 = 0.0f, d0 = 0.0f, d1 = 0.0f;
+    if (CODES) {
+#pragma unroll
+        for (int j = 0; j < EPL / 4; ++j) codes[j] = 0;
+    }
+#pragma unroll
+    for (int i0 = 0; i0 < EPL; i0 += 4) {
+        Rec r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = read_rec<CODES>(boff[i0 + j], a);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = i0 + j;
+            const bool up = x[i] > r[j].thr;
+            const float yv = up ? r[j].yhi : r[j].ylo;
+            const float what = ss * yv;
+            const float cw = cb[i] * w[i];
+            const float cwh = cb[i] * what;
+            if (i < 8) { n0 = __fmaf_rn(cw, what, n0); d0 = __fmaf_rn(cwh, what, d0); }
+            else       { n1 = __fmaf_rn(cw, what, n1); d1 = __fmaf_rn(cwh, what, d1); }
+            if (WANT_ERR) {
+                const float d = __fmaf_rn(-ss, yv, w[i]);
+                const float cd = cb[i] * d;
+                if (i < 8) e0 = __fmaf_rn(cd, d, e0); else e1 = __fmaf_rn(cd, d, e1);
+            }
+            put_code<EPL, CODES>(codes, i, (uint32_t)r[j].clo + (up ? 1u : 0u), wide_codes);
+        }
+    }
+    Sums s;
+    s.err = EPL == 16 ? e0 + e1 : e0;
+    s.wd = EPL == 16 ? n0 + n1 : n0;
+    s.ew = EPL == 16 ? d0 + d1 : d0;
+    return s;
+}
+
+// Cosine inputs straight from the codebook values in the scaled domain, where the block scale
+// cancels: cos = sign(s) <w,y>_c / sqrt(||w||_c^2 ||y||_c^2).  Used when the residual form would cancel.
+template <int EPL, int LPB>
+__device__ __forceinline__ void direct_cosine_sums(const float (&cb)[EPL], const float (&w)[EPL], const float (&x)[EPL],
+                                                   const uint32_t (&boff)[EPL], bool nonzero, bool negative,
+                                                   int a, float& ny_out, float& dy_out)
+{
+    float ny = 0.0f, dy = 0.0f;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        const Rec r = read_rec<false>(boff[i], a);
+        const float yv = x[i] > r.thr ? r.yhi : r.ylo;
+        ny = __fmaf_rn(cb[i] * w[i], yv, ny);
+        dy = __fmaf_rn(cb[i], yv * yv, dy);
+    }
+    const float nsum = group_sum<LPB>(negative ? -ny : ny), dsum = group_sum<LPB>(dy);
+    ny_out = nonzero ? nsum : 0.0f;                    // a zero scale reconstructs nothing
+    dy_out = nonzero ? dsum : 0.0f;
+}
+
+// Candidate after the cross-lane tree
+struct Cand {
+    float err;    // decision score of WSE / MSE; the weighted error in COS mode when wanted
+    float ny;     // cosine numerator   (cos = ny / sqrt(||w||^2 dy))
+    float dy;     // cosine denominator part
+    bool weak;    // residual form not trustworthy for this block
+};
+
+template <int LPB, int METRIC>
+__device__ __forceinline__ Cand finish_residual(const Sums& s, float wn, float qwn)
+{
+    Cand c;
+    c.err = group_sum<LPB>(s.err);
+    const float wd = group_sum<LPB>(s.wd);
+    const float errw = METRIC == 2 ? group_sum<LPB>(s.ew) : c.err;
+    c.ny = wn - wd;
+    c.dy = __fmaf_rn(-2.0f, wd, wn) + errw;
+    c.weak = !(c.dy >= qwn);
+    return c;
+}
+
+template <int LPB>
+__device__ __forceinline__ Cand finish_direct(const Sums& s)
+{
+    Cand c;
+    c.err = group_sum<LPB>(s.err);
+    c.ny = group_sum<LPB>(s.wd);
+    c.dy = group_sum<LPB>(s.ew);
+    c.weak = false;
+    return c;
+}
+
+// first / second atom of the pair with lexicographic position pi among all pairs of SOP_K_MAXA atoms
+__host__ __device__ constexpr int pair_first(int pi) { int i = 0; while (pi >= SOP_K_MAXA - 1 - i) { pi -= SOP_K_MAXA - 1 - i; ++i; } return i; }
+__host__ __device__ constexpr int pair_second(int pi) { const int i = pair_first(pi); return pi - pair_index(i, i + 1) + i + 1; }
+
+// Selector of pair PI and of all following pairs (i < j in internal order): bit `slot` of the
+// block's selector word, and the chosen atom's deficit into the pair's running sum.
+template <int PI, int NA, int METRIC>
+__device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, const float (&score)[SOP_K_MAXA],
+                                          const float (&den)[SOP_K_MAXA], const float (&dlt)[SOP_K_MAXA],
+                                          float (&accp)[SOP_K_MAXP], uint32_t& bits)
+{
+    constexpr int i = pair_first(PI), j = pair_second(PI);
+    static_assert(pair_index(i, j) == PI, "pair enumeration");
+    if constexpr (j < NA) {
+        if ((sw.pair_mask >> PI) & 1u) {
+            // caller's pair (a,b): selector = "b strictly better than a" (ties keep a).  The internal
+            // order may have swapped the two (b is internal i): then internal j keeps the block on a tie.
+            const float si = score[i], sj = score[j], ni = den[i], nj = den[j], di = dlt[i], dj = dlt[j];
+            const bool flip = (sw.flip_mask >> PI) & 1u;
+            // both comparisons are formed and the wave-uniform flag picks one (no branch)
+            const float lhs = METRIC == 1 ? sj * ni : sj, rhs = METRIC == 1 ? si * nj : si;
+            const bool lt = METRIC == 1 ? lhs > rhs : lhs < rhs;
+            const bool le = METRIC == 1 ? lhs >= rhs : lhs <= rhs;
+            const bool pick_j = flip ? le : lt;
+            const float chosen = pick_j ? dj : di;
+            accp[PI] += chosen;
+            // bit = "internal j taken"; for swapped pairs the caller's selector is its complement, put
+            // right by one xor with the mask of swapped pairs after the last pair
+            const int slot = p.pair_slot[PI];
+            bits |= (pick_j ? 1u : 0u) << slot;
+        }
+    }
+    if constexpr (PI + 1 < SOP_K_MAXP) all_pairs<PI + 1, NA, METRIC>(p, sw, score, den, dlt, accp, bits);
+}
+
+// The weights one lane reads per step, as they come from memory
+template <bool BF16, int EPL> struct RawBlk { uint4 v[BF16 ? EPL / 8 : EPL / 4]; };
+
+template <bool BF16, int EPL>
+__device__ __forceinline__ RawBlk<BF16, EPL> load_raw(const KParams& p, long long strip, long long m, int lane)
+{
+    RawBlk<BF16, EPL> r;
+    const long long col0 = (strip * 64 + lane) * EPL;
+    const bool valid = col0 < p.K;
+    constexpr int NV = BF16 ? EPL / 8 : EPL / 4;
+    const char* src = reinterpret_cast<const char*>(p.W) + (m * p.ldw + col0) * (BF16 ? 2 : 4);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) r.v[i] = valid ? reinterpret_cast<const uint4*>(src)[i] : make_uint4(0, 0, 0, 0);
+    return r;
+}
+
+template <bool BF16, int EPL>
+__device__ __forceinline__ void widen(const RawBlk<BF16, EPL>& r, float (&w)[EPL])
+{
+    if (BF16) {
+#pragma unroll
+        for (int i = 0; i < EPL / 8; ++i) {
+            const uint32_t v[4] = {r.v[i].x, r.v[i].y, r.v[i].z, r.v[i].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                w[8 * i + 2 * j] = __uint_as_float(v[j] << 16);
+                w[8 * i + 2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) {
+            w[4 * i] = __uint_as_float(r.v[i].x); w[4 * i + 1] = __uint_as_float(r.v[i].y);
+            w[4 * i + 2] = __uint_as_float(r.v[i].z); w[4 * i + 3] = __uint_as_float(r.v[i].w);
+        }
+    }
+}
+
+// NA: atoms the kernel is unrolled for (6 or 8).  OCC: resident workgroups per compute unit the
+// register budget is set for.
+template <bool BF16, int EPL, int LPB, bool SIGNED, int METRIC, bool EMIT, int NA, int OCC>
+__global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
+{
+    extern __shared__ __align__(16) char s_mem[];
+    // LDS: bin table | (scale, reciprocal) table | group parameters | reduction scratch
+    char* s_bins = s_mem;                                                         // [n_bins] records of 33 words
+    const size_t bins_bytes = ((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15;
+    float2* s_tab = reinterpret_cast<float2*>(s_mem + bins_bytes);
+    float4* s_gpar = reinterpret_cast<float4*>(s_mem + bins_bytes + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15));
+    float* s_red = reinterpret_cast<float*>(s_gpar + 2 * SOP_K_MAXA);              // [4][SOP_K_NCOL]
+    {
+        const int nw = p.n_bins * (SOP_K_BIN_BYTES / 4);
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(p.bins);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(s_bins);
+        for (int i = threadIdx.x; i < nw; i += 256) dst[i] = src[i];
+        for (int i = threadIdx.x; i < p.n_tab_codes; i += 256) s_tab[i] = p.stab[i];
+        // (static indices: a lane-dependent index into the kernel arguments would copy them to scratch memory)
+#pragma unroll
+        for (int a = 0; a < SOP_K_MAXA; ++a)
+            if ((int)threadIdx.x == a) {
+                s_gpar[2 * a] = make_float4(p.tpos[a], p.tneg[a], p.bin_sc[a], p.bin_off[a]);
+                s_gpar[2 * a + 1] = make_float4(p.bin_lo[a], p.bin_hi[a], 0.0f, 0.0f);
+            }
+    }
+    __syncthreads();
+    const uint32_t lds_neg = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_bins + SOP_K_BIN_NEGC;
+
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const long long wave = (long long)blockIdx.x * 4 + wv;
+    const long long u0 = p.total_units * wave / p.n_waves;
+    const long long u1 = p.total_units * (wave + 1) / p.n_waves;
+
+    // running sums of 1 - cos: atoms, pairs, and the count of lanes whose block has zero norm
+    float acca[SOP_K_MAXA], accp[SOP_K_MAXP], accz = 0.0f;
+#pragma unroll
+    for (int i = 0; i < SOP_K_MAXA; ++i) acca[i] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < SOP_K_MAXP; ++i) accp[i] = 0.0f;
+
+    long long strip = u0 / p.M;
+    long long m = u0 - strip * p.M;
+    long long cur_strip = -1;
+    float cb[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) cb[i] = 0.0f;
+    RawBlk<BF16, EPL> nxt;
+    if (u0 < u1) nxt = load_raw<BF16, EPL>(p, strip, m, lane);
+
+    for (long long u = u0; u < u1; ++u) {
+        // The uniform switches below are re-read every row.  Left loop-invariant, each test would be
+        // hoisted out of the loop as a 64-bit lane mask and the hundred-odd masks would spill.
+        Switches sw = {p.A, p.pair_mask, p.flip_mask, p.grp_first_mask, p.unit_tpos, p.unit_tneg, p.wide_mask};
+        asm volatile("" : "+s"(sw.A), "+s"(sw.pair_mask), "+s"(sw.flip_mask), "+s"(sw.grp_first), "+s"(sw.unit_tpos), "+s"(sw.unit_tneg), "+s"(sw.wide));
+        const long long cm = m, cs = strip;
+        const long long col0 = (cs * 64 + lane) * EPL;
+        const bool valid = col0 < p.K;
+        if (cs != cur_strip) {
+            cur_strip = cs;
+#pragma unroll
+            for (int i = 0; i < EPL; i += 4) {
+                float4 t = valid ? *reinterpret_cast<const float4*>(p.c + col0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                cb[i] = t.x; cb[i + 1] = t.y; cb[i + 2] = t.z; cb[i + 3] = t.w;
+            }
+        }
+        // ---- the block: one read from HBM, requested one step ahead ----
+        float w[EPL];
+        widen<BF16, EPL>(nxt, w);
+        if (++m == p.M) { m = 0; ++strip; }
+        if (u + 1 < u1) nxt = load_raw<BF16, EPL>(p, strip, m, lane);
+
+        // ---- block statistics ----
+        float pmax = 0.0f, nmin = 0.0f, wn0 = 0.0f, wn1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPL; i += 2) {
+            pmax = fmaxf(fmaxf(pmax, w[i]), w[i + 1]);
+            nmin = fminf(fminf(nmin, w[i]), w[i + 1]);
+        }
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            const float cw = cb[i] * w[i];
+            if (i < 8) wn0 = __fmaf_rn(cw, w[i], wn0); else wn1 = __fmaf_rn(cw, w[i], wn1);
+        }
+        pmax = group_max<LPB>(pmax);
+        const float nmax = group_max<LPB>(-nmin);
+        const float wn = group_sum<LPB>(EPL == 16 ? wn0 + wn1 : wn0);
+        const float qwn = 0.25f * wn;
+        accz += wn > 0.0f ? 0.0f : 1.0f;
+
+        const long long blk_in_row = (cs * 64 + lane) / LPB;
+        const long long blk = cm * p.Bk + blk_in_row;
+        const bool leader = valid && (lane % LPB == 0);
+
+        // per-block results of every atom that the pair stage needs: score = err (WSE / MSE) or
+        // q = num*|num| (COS, 0 for a zero reconstruction), den (COS only, 1 for a zero reconstruction), 1 - cos
+        float score[SOP_K_MAXA], den[SOP_K_MAXA], dlt[SOP_K_MAXA];
+        // state of the current scale group: positive sign, and negative sign for signed scale words
+        int gq = 0, gq2 = 0;
+        float gss = 0.0f, gss2 = 0.0f;
+        bool gnz = false, gnz2 = false;
+        float gx[EPL], gx2[SIGNED ? EPL : 1];
+        uint32_t gboff[EPL], gboff2[SIGNED ? EPL : 1];
+
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+            score[a] = 0.0f; den[a] = 1.0f; dlt[a] = 0.0f;
+            if (a < sw.A) {
+                if (a == 0 || ((sw.grp_first >> a) & 1u)) {       // atom 0 always opens a group
+                    prepare_sign<EPL>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff);
+                    if constexpr (SIGNED) prepare_sign<EPL>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, gq2, gss2, gnz2, gx2, gboff2);
+                }
+                const bool wide = EMIT && ((sw.wide >> a) & 1u);
+                uint32_t codes[EPL / 4];
+                Cand best;
+                int q = gq;
+                bool neg = false;
+                if constexpr (METRIC == 1) {
+                    best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, gx, gboff, gss, a, wide, codes));
+                    float bq = best.dy > 0.0f ? best.ny * fabsf(best.ny) : 0.0f;
+                    float bd = best.dy > 0.0f ? best.dy : 1.0f;
+                    if constexpr (SIGNED) {
+                        uint32_t codes2[EPL / 4];
+                        const Cand c2 = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, gx2, gboff2, gss2, a, wide, codes2));
+                        const float q2 = c2.dy > 0.0f ? c2.ny * fabsf(c2.ny) : 0.0f;
+                        const float d2 = c2.dy > 0.0f ? c2.dy : 1.0f;
+                        neg = q2 * bd > bq * d2;
+                        best.err = neg ? c2.err : best.err;
+                        best.ny = neg ? c2.ny : best.ny;
+                        best.dy = neg ? c2.dy : best.dy;
+                        bq = neg ? q2 : bq;
+                        bd = neg ? d2 : bd;
+                        q = neg ? gq2 : q;
+                        if (EMIT) {
+#pragma unroll
+                            for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codes2[j] : codes[j];
+                        }
+                    }
+                    score[a] = bq;
+                    den[a] = bd;
+                } else {
+                    best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, gx, gboff, gss, a, wide, codes), wn, qwn);
+                    if constexpr (SIGNED) {
+                        uint32_t codes2[EPL / 4];
+                        const Cand c2 = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, gx2, gboff2, gss2, a, wide, codes2), wn, qwn);
+                        neg = c2.err < best.err;
+                        best.err = neg ? c2.err : best.err;
+                        best.ny = neg ? c2.ny : best.ny;
+                        best.dy = neg ? c2.dy : best.dy;
+                        best.weak = neg ? c2.weak : best.weak;
+                        q = neg ? gq2 : q;
+                        if (EMIT) {
+#pragma unroll
+                            for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codes2[j] : codes[j];
+                        }
+                    }
+                    // the residual form is accurate while the reconstruction carries a fair share of
+                    // the block's norm; otherwise the whole wavefront recomputes this atom directly
+                    if (__builtin_expect(__any(best.weak) != 0, 0)) {
+                        float ny1, dy1;
+                        direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, false, a, ny1, dy1);
+                        if constexpr (SIGNED) {
+                            float ny2, dy2;
+                            direct_cosine_sums<EPL, LPB>(cb, w, gx2, gboff2, gnz2, true, a, ny2, dy2);
+                            ny1 = neg ? ny2 : ny1;
+                            dy1 = neg ? dy2 : dy1;
+                        }
+                        best.ny = ny1;
+                        best.dy = dy1;
+                    }
+                    score[a] = best.err;
+                }
+                // cosine value; a vanishing reconstruction has ny = 0 and gives cos 0; a zero-norm block
+                // gives exactly 1 - 0 here and is corrected through the count column
+                const float da = __fmaf_rn(-best.ny, __frsqrt_rn(__fmaf_rn(wn, best.dy, 1.0e-37f)), 1.0f);
+                dlt[a] = da;
+                acca[a] += da;
+                if (EMIT) {
+                    const long long ua = p.uidx[a];
+                    if (p.scale_code && leader) p.scale_code[ua * p.Nb + blk] = (uint16_t)(q | (neg ? 0x8000 : 0));
+                    if (p.blk_err && leader) p.blk_err[ua * p.Nb + blk] = best.err;
+                    if (p.blk_cos && leader) p.blk_cos[ua * p.Nb + blk] = wn > 0.0f ? 1.0f - da : 1.0f;
+                    if (p.codes && valid) {
+                        if (!wide) {
+                            uint8_t* dst = p.codes + p.code_off[a] + (cm * p.K + col0) / 2;
+#pragma unroll
+                            for (int j = 0; j < EPL / 8; ++j) reinterpret_cast<uint32_t*>(dst)[j] = codes[j];
+                        } else {
+                            uint8_t* dst = p.codes + p.code_off[a] + cm * p.K + col0;
+#pragma unroll
+                            for (int j = 0; j < EPL / 4; ++j) reinterpret_cast<uint32_t*>(dst)[j] = codes[j];
+                        }
+                    }
+                }
+            }
+        }
+        // ---- selector of every requested pair: one word per block ----
+        uint32_t bits = 0;
+        all_pairs<0, NA, METRIC>(p, sw, score, den, dlt, accp, bits);
+        bits ^= p.flip_slots;
+        if (p.sel_words && leader) {
+            if (p.sel_u32) reinterpret_cast<uint32_t*>(p.sel_words)[blk] = bits;
+            else reinterpret_cast<uint16_t*>(p.sel_words)[blk] = (uint16_t)bits;
+        }
+    }
+
+    // ---- per-workgroup partial sums: lanes, then the four wavefronts in order ----
+    auto wave_sum = [&](float v, int col) {
+#pragma unroll
+        for (int st = 1; st < 64; st <<= 1) v += __shfl_xor(v, st, 64);
+        if (lane == 0) s_red[wv * SOP_K_NCOL + col] = v;
+    };
+#pragma unroll
+    for (int i = 0; i < SOP_K_MAXA; ++i) wave_sum(i < NA ? acca[i] : 0.0f, i);
+#pragma unroll
+    for (int i = 0; i < SOP_K_MAXP; ++i) wave_sum(pair_second(i) < NA ? accp[i] : 0.0f, SOP_K_MAXA + i);
+    wave_sum(accz, SOP_K_ZCOL);
+    __syncthreads();
+    if ((int)threadIdx.x < SOP_K_NCOL) {
+        const int i = threadIdx.x;
+        const float v = (s_red[i] + s_red[SOP_K_NCOL + i]) + (s_red[2 * SOP_K_NCOL + i] + s_red[3 * SOP_K_NCOL + i]);
+        p.partial[(long long)i * (p.n_waves / 4) + blockIdx.x] = v;
+    }
+}
+
+}  // namespace sopk
+
+// ---- kernel table of this part ----
+namespace {
+template <bool BF16, int EPL, int LPB>
+const void* pick_geom(bool is_signed, bool emit, bool na8)
+{
+    constexpr int MT = SOPK_PART_METRIC;
+#define SOPK_FN(S, E, NA, OCC) reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, OCC>)
+    if (emit) return is_signed ? SOPK_FN(true, true, 8, 1) : SOPK_FN(false, true, 8, 1);
+    if (is_signed) return na8 ? SOPK_FN(true, false, 8, 1) : SOPK_FN(true, false, 6, 2);
+    return na8 ? SOPK_FN(false, false, 8, 2) : SOPK_FN(false, false, 6, 3);
+#undef SOPK_FN
+}
+}  // namespace
+
+#define SOPK_CAT2(a, b, c) a##b##_##c
+#define SOPK_CAT(a, b, c) SOPK_CAT2(a, b, c)
+
+// g: block size; na8: more than six atoms in the alphabet
+extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int is_signed, int emit, int na8)
+{
+    constexpr bool B = SOPK_PART_BF16 != 0;
+    switch (g) {
+        case 8:  return pick_geom<B, 8, 1>(is_signed, emit, na8);
+        case 16: return pick_geom<B, 16, 1>(is_signed, emit, na8);
+        case 32: return pick_geom<B, 16, 2>(is_signed, emit, na8);
+        default: return pick_geom<B, 16, 4>(is_signed, emit, na8);
+    }
+}

@@ -35,8 +35,9 @@ def run_gpu(W, c, tabs, g, fmt, k=0, metric=0, pairs=None, bf16=False, emit=True
     out = cx.pair_search(Wt, ct, g, fmt, k=k, metric=metric, emit=emit)
     torch.cuda.synchronize()
     r = dict(acos_pair=out.acos_pair.cpu().numpy()[:cx.n_pairs], acos_atom=out.acos_atom.cpu().numpy())
-    if out.sel_bits is not None:
-        r["sel_bits"] = out.sel_bits.cpu().numpy().view(np.uint32)
+    if out.sel_words is not None:
+        sw = out.sel_words.cpu().numpy()
+        r["sel_words"] = sw.view(np.uint16 if sw.dtype == np.int16 else np.uint32).astype(np.uint32)
     if emit:
         r["scale_code"] = out.scale_code.cpu().numpy().view(np.uint16)
         r["codes"] = [p.cpu().numpy() for p in out.code_planes]
@@ -48,7 +49,7 @@ def run_gpu(W, c, tabs, g, fmt, k=0, metric=0, pairs=None, bf16=False, emit=True
 def compare(gpu, ref, n_pairs, emit=True, acos_tol=1e-6, cos_tol=2e-5):
     """Bit-exact on every integer output and on the decision scores; ACos within 1e-6 absolute."""
     if n_pairs:
-        assert np.array_equal(gpu["sel_bits"], ref.sel_bits), "selector bits differ"
+        assert np.array_equal(gpu["sel_words"], ref.sel_words), "selector bits differ"
         assert np.max(np.abs(gpu["acos_pair"] - ref.acos_pair)) <= acos_tol, (gpu["acos_pair"], ref.acos_pair)
     assert np.max(np.abs(gpu["acos_atom"] - ref.acos_atom)) <= acos_tol, (gpu["acos_atom"], ref.acos_atom)
     if emit:

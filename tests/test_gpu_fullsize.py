@@ -20,7 +20,7 @@ def _sample_rows_check(W, c, tabs, g, fmt, gpu_full, rows, bf16):
     M, K = W.shape
     Bk = K // g
     ref = ops.pair_search(W[rows], c, tabs, g, oracle_fmt(fmt))
-    assert np.array_equal(gpu_full["sel_bits"][:, rows], ref.sel_bits)
+    assert np.array_equal(gpu_full["sel_words"].reshape(M, Bk)[rows].reshape(-1), ref.sel_words)
     if "scale_code" in gpu_full:
         sc = gpu_full["scale_code"].reshape(len(tabs), M, Bk)[:, rows].reshape(len(tabs), -1)
         assert np.array_equal(sc, ref.scale_code)

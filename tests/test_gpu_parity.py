@@ -87,6 +87,22 @@ def test_unweighted_metric_and_layer_shift():
     check(W, c, t, 32, sop.fmt_by_name("E4M3"), k=-3, metric=sop.SEL_MSE, bf16=True)
 
 
+@pytest.mark.parametrize("g,fmt", [(8, "UE4M4"), (16, "UE4M4"), (16, "E4M3"), (32, "E4M3"), (64, "UE4M6")])
+def test_cosine_metric(g, fmt):
+    # finishing reassignment by per-block cosine: decisions from the binary32 numerator / denominator sums
+    M, K = 33, 1088
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 650 + g, row_sigma=0.5, outlier_frac=0.002))
+    W[3, 64:96] = 0.0
+    c = si.channel_norms(K, 1.0, 651)
+    c[128:160] = 0.0
+    t = tabs_for(["NF4", "SH4", "BOF4", "-NF4", "-SH4", "-BOF4"])
+    gpu, ref = check(W, c, t, g, sop.fmt_by_name(fmt), metric=sop.SEL_COS, bf16=True)
+    # selecting by cosine, a pair is never worse than either of its atoms
+    pairs = [(a, b) for a in range(6) for b in range(a + 1, 6)]
+    for p, (a, b) in enumerate(pairs):
+        assert gpu["acos_pair"][p] >= max(gpu["acos_atom"][a], gpu["acos_atom"][b]) - 1e-6
+
+
 def test_row_stride():
     M, K = 16, 512
     W = si.student_t_weights(M, K, 4.0, 701)
@@ -139,7 +155,7 @@ def test_vanishing_weights_integer_outputs():
         ref = ops.pair_search(W, c, t, g, oracle_fmt(f), k=k)
         assert np.array_equal(gpu["scale_code"], ref.scale_code)
         assert all(np.array_equal(x, y) for x, y in zip(gpu["codes"], ref.codes))
-        assert np.array_equal(gpu["blk_err"], ref.blk_err) and np.array_equal(gpu["sel_bits"], ref.sel_bits)
+        assert np.array_equal(gpu["blk_err"], ref.blk_err) and np.array_equal(gpu["sel_words"], ref.sel_words)
 
 
 def test_midpoint_ties():
@@ -164,7 +180,7 @@ def test_deterministic():
     t = tabs_for(cfg["atoms"])
     a = run_gpu(W, c, t, 16, sop.fmt_by_name("UE4M4"))
     b = run_gpu(W, c, t, 16, sop.fmt_by_name("UE4M4"))
-    assert np.array_equal(a["acos_pair"], b["acos_pair"]) and np.array_equal(a["sel_bits"], b["sel_bits"])
+    assert np.array_equal(a["acos_pair"], b["acos_pair"]) and np.array_equal(a["sel_words"], b["sel_words"])
     assert np.array_equal(a["blk_cos"], b["blk_cos"])
 
 
@@ -189,7 +205,7 @@ def test_argument_errors():
         cx.pair_search(W, c, 16, sop.fmt_by_name("UE4M4"), k=100)
     assert e.value.status == 4
     with pytest.raises(sop.SopError) as e:
-        cx.pair_search(W, c, 16, f, metric=sop.SEL_COS)
+        cx.pair_search(W, c, 16, f, metric=7)
     assert e.value.status == 1
     with pytest.raises(sop.SopError) as e:
         cx.set_alphabet([np.array([0.5, -0.5], dtype=np.float32)])

@@ -83,7 +83,7 @@ def test_ties_go_to_the_lower_index_and_the_positive_sign():
     assert np.all(r.scale_code[0] >> 15 == 0)
     # in a pair of identical atoms the selector stays 0
     r = ps.pair_search(W, np.ones(64, dtype=np.float32), [L, L], 16, WIDE)
-    assert not r.sel_bits.any()
+    assert not r.sel_words.any()
 
 
 def test_zero_blocks():
@@ -240,7 +240,7 @@ def test_selector_takes_the_smaller_error():
         r = ps.pair_search(W, c, at, 16, UE4M4, metric=metric)
         Bk = W.shape[1] // 16
         for p, (a, b) in enumerate(ps.all_pairs(4)):
-            bits = ((r.sel_bits[p][:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(W.shape[0], -1)[:, :Bk].reshape(-1)
+            bits = (r.sel_words >> np.uint32(p)) & 1
             assert np.array_equal(bits.astype(bool), r.blk_err[b] < r.blk_err[a])
             chosen = np.where(bits.astype(bool), r.blk_err[b], r.blk_err[a])
             assert np.array_equal(chosen, np.minimum(r.blk_err[a], r.blk_err[b]))
@@ -254,7 +254,7 @@ def test_mse_metric_ignores_channel_norms_in_the_score():
     at = _alphabet()[:2]
     r1 = ps.pair_search(W, c, at, 16, UE4M4, metric=ps.MSE)
     r2 = ps.pair_search(W, np.ones_like(c), at, 16, UE4M4, metric=ps.WSE)
-    assert np.array_equal(r1.blk_err, r2.blk_err) and np.array_equal(r1.sel_bits, r2.sel_bits)
+    assert np.array_equal(r1.blk_err, r2.blk_err) and np.array_equal(r1.sel_words, r2.sel_words)
     assert not np.array_equal(r1.acos_pair, r2.acos_pair)          # the cosine still uses c
 
 
@@ -264,7 +264,7 @@ def test_cos_metric_pair_dominates_singles():
     r = ps.pair_search(W, c, at, 16, UE4M4, metric=ps.COS)
     for p, (a, b) in enumerate(ps.all_pairs(4)):
         assert r.acos_pair[p] >= max(r.acos_atom[a], r.acos_atom[b]) - 1e-9
-        bits = ((r.sel_bits[p][:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(W.shape[0], -1)[:, :W.shape[1] // 16].reshape(-1)
+        bits = (r.sel_words >> np.uint32(p)) & 1
         agree = bits.astype(bool) == (r.blk_cos[b] > r.blk_cos[a])
         assert agree.mean() > 0.995                                 # binary32 cosines tie occasionally
 
@@ -274,13 +274,13 @@ def test_power_of_two_invariances():
     at = _alphabet()
     r0 = ps.pair_search(W, c, at, 16, UE4M4, k=0)
     r1 = ps.pair_search(W, c * np.float32(8.0), at, 16, UE4M4, k=0)
-    assert np.array_equal(r0.acos_pair, r1.acos_pair) and np.array_equal(r0.sel_bits, r1.sel_bits)
+    assert np.array_equal(r0.acos_pair, r1.acos_pair) and np.array_equal(r0.sel_words, r1.sel_words)
     assert all(np.array_equal(x, y) for x, y in zip(r0.codes, r1.codes))
     # scaling W by 2^-9 and shifting the block scales by k = +9 changes no code and no cosine
     r2 = ps.pair_search(W * np.float32(2.0 ** -9), c, at, 16, UE4M4, k=9)
     assert np.array_equal(r0.scale_code, r2.scale_code)
     assert all(np.array_equal(x, y) for x, y in zip(r0.codes, r2.codes))
-    assert np.array_equal(r0.sel_bits, r2.sel_bits) and np.array_equal(r0.acos_pair, r2.acos_pair)
+    assert np.array_equal(r0.sel_words, r2.sel_words) and np.array_equal(r0.acos_pair, r2.acos_pair)
     # without the shift the small layer falls into the format's subnormal range and loses fidelity
     r3 = ps.pair_search(W * np.float32(2.0 ** -9), c, at, 16, UE4M4, k=0)
     assert r3.acos_atom[0] < r0.acos_atom[0]
@@ -294,7 +294,7 @@ def test_row_permutation_and_thread_count():
     r1 = ps.pair_search(W[perm], c, at, 16, E4M3, n_threads=4)
     Bk = W.shape[1] // 16
     assert np.array_equal(r0.scale_code.reshape(4, -1, Bk)[:, perm], r1.scale_code.reshape(4, -1, Bk))
-    assert np.array_equal(r0.sel_bits[:, perm], r1.sel_bits)
+    assert np.array_equal(r0.sel_words.reshape(W.shape[0], -1)[perm].reshape(-1), r1.sel_words)
     assert np.allclose(r0.acos_pair, r1.acos_pair, rtol=0, atol=1e-13)
     r2 = ps.pair_search(W, c, at, 16, E4M3, n_threads=3)
     assert np.array_equal(r0.acos_pair, r2.acos_pair) and np.array_equal(r0.blk_err, r2.blk_err)
