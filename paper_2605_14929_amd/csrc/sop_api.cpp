@@ -434,13 +434,12 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
         p.code_off[i] = plane_off[c->order[i]];
         internal_of[c->order[i]] = i;
     }
-    std::memset(p.pair_slot, -1, sizeof(p.pair_slot));
     for (int q = 0; q < c->n_pairs; ++q) {
         const int ia = internal_of[c->pairs[2 * q]], ib = internal_of[c->pairs[2 * q + 1]];
         const int i = std::min(ia, ib), j = std::max(ia, ib), pi = pair_index(i, j);
         p.pair_mask |= 1u << pi;
         if (ia > ib) { p.flip_mask |= 1u << pi; p.flip_slots |= 1u << q; }
-        p.pair_slot[pi] = (signed char)q;
+        p.pair_slot_w[pi / 4] |= (unsigned)q << (8 * (pi % 4));
         p.pair_pi[q] = (unsigned char)pi;
     }
     p.partial = static_cast<float*>(ws);

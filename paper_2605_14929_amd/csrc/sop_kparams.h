@@ -67,13 +67,14 @@ struct KParams {
     unsigned int grp_first_mask;                   // bit a: first atom of its scale group
     unsigned int unit_tpos, unit_tneg;             // bit a: the endpoint is exactly 1 (no division needed)
     unsigned int wide_mask;                        // bit a: more than 16 entries (one byte per code)
-    unsigned char uidx[SOP_K_MAXA];                // caller's index of the atom
+    alignas(8) unsigned char uidx[SOP_K_MAXA];     // caller's index of the atom
     long long code_off[SOP_K_MAXA];                // byte offset of the atom's code plane
     unsigned int pair_mask;                           // bit pair_index(i,j): the pair is requested
     unsigned int flip_mask;                           // bit pair_index(i,j): the caller's first atom is internal j
     unsigned int flip_slots;                          // bit q: output pair q is such a swapped pair
-    signed char pair_slot[SOP_K_MAXP];                // output index of pair pair_index(i,j), or -1
-    unsigned char pair_pi[SOP_K_MAXP];                // pair_index(i,j) of output o
+    // (byte arrays sit on 8-byte boundaries so that the kernels fetch them with scalar loads)
+    unsigned int pair_slot_w[SOP_K_MAXP / 4];          // byte pi%4 of word pi/4: output index of pair pi = pair_index(i,j)
+    alignas(8) unsigned char pair_pi[SOP_K_MAXP + 4];  // pair_index(i,j) of output o
     // outputs
     float*    partial;               // [SOP_K_NCOL][n_waves/4] per-workgroup sums of 1-cos
     double*   acos_pair;

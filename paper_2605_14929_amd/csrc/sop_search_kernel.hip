@@ -326,8 +326,17 @@ __device__ __forceinline__ Cand finish_direct(const Sums& s)
 }
 
 // first / second atom of the pair with lexicographic position pi among all pairs of SOP_K_MAXA atoms
-__host__ __device__ constexpr int pair_first(int pi) { int i = 0; while (pi >= SOP_K_MAXA - 1 - i) { pi -= SOP_K_MAXA - 1 - i; ++i; } return i; }
-__host__ __device__ constexpr int pair_second(int pi) { const int i = pair_first(pi); return pi - pair_index(i, i + 1) + i + 1; }
+struct PairTab { int first[SOP_K_MAXP], second[SOP_K_MAXP]; };
+constexpr PairTab make_pair_tab()
+{
+    PairTab t{};
+    int pi = 0;
+    for (int i = 0; i < SOP_K_MAXA; ++i)
+        for (int j = i + 1; j < SOP_K_MAXA; ++j) { t.first[pi] = i; t.second[pi] = j; ++pi; }
+    return t;
+}
+constexpr PairTab kPairTab = make_pair_tab();
+template <int PI> struct PairOf { static constexpr int i = kPairTab.first[PI], j = kPairTab.second[PI]; };
 
 // Selector of pair PI and of all following pairs (i < j in internal order): bit `slot` of the
 // block's selector word, and the chosen atom's deficit into the pair's running sum.
@@ -336,24 +345,25 @@ __device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, 
                                           const float (&den)[SOP_K_MAXA], const float (&dlt)[SOP_K_MAXA],
                                           float (&accp)[SOP_K_MAXP], uint32_t& bits)
 {
-    constexpr int i = pair_first(PI), j = pair_second(PI);
+    constexpr int i = PairOf<PI>::i, j = PairOf<PI>::j;
     static_assert(pair_index(i, j) == PI, "pair enumeration");
     if constexpr (j < NA) {
-        if ((sw.pair_mask >> PI) & 1u) {
+        if (__builtin_expect((sw.pair_mask >> PI) & 1u, 1)) {
             // caller's pair (a,b): selector = "b strictly better than a" (ties keep a).  The internal
             // order may have swapped the two (b is internal i): then internal j keeps the block on a tie.
             const float si = score[i], sj = score[j], ni = den[i], nj = den[j], di = dlt[i], dj = dlt[j];
             const bool flip = (sw.flip_mask >> PI) & 1u;
-            // both comparisons are formed and the wave-uniform flag picks one (no branch)
+            // both comparisons are formed as lane masks; the wave-uniform flag picks one of them in
+            // scalar registers (no branch, no per-lane select of booleans)
             const float lhs = METRIC == 1 ? sj * ni : sj, rhs = METRIC == 1 ? si * nj : si;
-            const bool lt = METRIC == 1 ? lhs > rhs : lhs < rhs;
-            const bool le = METRIC == 1 ? lhs >= rhs : lhs <= rhs;
-            const bool pick_j = flip ? le : lt;
+            const unsigned long long lt = __builtin_amdgcn_ballot_w64(METRIC == 1 ? lhs > rhs : lhs < rhs);
+            const unsigned long long le = __builtin_amdgcn_ballot_w64(METRIC == 1 ? lhs >= rhs : lhs <= rhs);
+            const bool pick_j = __builtin_amdgcn_inverse_ballot_w64(flip ? le : lt);
             const float chosen = pick_j ? dj : di;
             accp[PI] += chosen;
             // bit = "internal j taken"; for swapped pairs the caller's selector is its complement, put
             // right by one xor with the mask of swapped pairs after the last pair
-            const int slot = p.pair_slot[PI];
+            const int slot = (p.pair_slot_w[PI / 4] >> (8 * (PI % 4))) & 0xFF;
             bits |= (pick_j ? 1u : 0u) << slot;
         }
     }
@@ -428,7 +438,9 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
     const uint32_t lds_neg = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_bins + SOP_K_BIN_NEGC;
 
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    // the wavefront's number is the same in all its lanes: saying so keeps the row loop's counters
+    // and tests in scalar registers
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const long long wave = (long long)blockIdx.x * 4 + wv;
     const long long u0 = p.total_units * wave / p.n_waves;
     const long long u1 = p.total_units * (wave + 1) / p.n_waves;
@@ -506,7 +518,7 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
             score[a] = 0.0f; den[a] = 1.0f; dlt[a] = 0.0f;
-            if (a < sw.A) {
+            if (__builtin_expect(a < sw.A, 1)) {
                 if (a == 0 || ((sw.grp_first >> a) & 1u)) {       // atom 0 always opens a group
                     prepare_sign<EPL>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff);
                     if constexpr (SIGNED) prepare_sign<EPL>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, gq2, gss2, gnz2, gx2, gboff2);
@@ -614,7 +626,7 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
 #pragma unroll
     for (int i = 0; i < SOP_K_MAXA; ++i) wave_sum(i < NA ? acca[i] : 0.0f, i);
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXP; ++i) wave_sum(pair_second(i) < NA ? accp[i] : 0.0f, SOP_K_MAXA + i);
+    for (int i = 0; i < SOP_K_MAXP; ++i) wave_sum(accp[i], SOP_K_MAXA + i);     // never-touched columns are plain zeros
     wave_sum(accz, SOP_K_ZCOL);
     __syncthreads();
     if ((int)threadIdx.x < SOP_K_NCOL) {
