@@ -13,7 +13,8 @@
  *     non-zero status sop_last_error() returns a text describing it.
  *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are memory of the GPU the
  *     context was created on.  The library never allocates or frees memory the caller sees; it
- *     owns only a small image of the codebook tables inside the context.
+ *     owns only a small image of the codebook tables and the layer reduction's sums inside the
+ *     context (allocated by sop_create, scale tables on first use of a scale format).
  *   - sop_pair_search() is asynchronous on the given HIP stream and does no host synchronisation.
  *     Inputs are read-only; requested outputs are completely overwritten.
  *   - Block index: block j of row m has index m*(K/g) + j.
@@ -113,8 +114,10 @@ sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int* n_bins, i
  * P = 0 (or pair_ab NULL) restores the default of all pairs.  Output index = position here. */
 sop_status sop_set_pairs(sop_ctx* ctx, const int* pair_ab, int n_pairs);
 
-/* Bytes of DEVICE workspace sop_pair_search() needs for this shape (partial sums of the layer
- * reduction).  The workspace needs no initialisation and 256-byte alignment. */
+/* Bytes of DEVICE workspace sop_pair_search() needs for this shape.  This version needs none and
+ * reports 0 (the layer reduction keeps a few words inside the context); the workspace arguments of
+ * sop_pair_search() are accepted for callers written against a version that did, and may be
+ * NULL / 0. */
 sop_status sop_workspace_bytes(sop_ctx* ctx, int64_t M, int64_t K, int g, size_t* bytes);
 
 /* The per-layer search (Section "Block Scaling": absmax scale and round_q; Section "Scale Format
@@ -127,11 +130,12 @@ sop_status sop_workspace_bytes(sop_ctx* ctx, int64_t M, int64_t K, int g, size_t
  *   fmt         scale word format; layer_shift_k multiplies every ideal block scale by 2^k before
  *               rounding and divides the decoded scale by it (|k| <= 64)
  *   metric      SOP_SEL_WSE, SOP_SEL_MSE or SOP_SEL_COS
- *   workspace   DEVICE, at least sop_workspace_bytes() bytes
+ *   workspace   DEVICE, at least sop_workspace_bytes() bytes (0: may be NULL)
  *   out         HOST pointer to the struct of DEVICE output pointers
  *   hip_stream  a hipStream_t (NULL = the default stream)
  * Arguments are validated before anything is launched.  Calls on one context must not overlap
- * with sop_set_alphabet / sop_set_pairs; calls on different streams need different workspaces. */
+ * with sop_set_alphabet / sop_set_pairs, nor with each other on the GPU (the context holds the
+ * running sums of the layer reduction): issue them on one stream, or use one context per stream. */
 sop_status sop_pair_search(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                            const float* c_dev, int g, sop_scale_fmt fmt, int layer_shift_k, sop_metric metric,
                            void* workspace_dev, size_t workspace_bytes, const sop_outputs* out, void* hip_stream);

@@ -269,7 +269,7 @@ class Context:
         if out is None:
             out = self.alloc_outputs(M, K, g, emit=emit)
         need = self.workspace_bytes(M, K, g)
-        if self._ws is None or self._ws.numel() < need:
+        if need and (self._ws is None or self._ws.numel() < need):
             self._ws = torch.empty(need, dtype=torch.uint8, device=W.device)
         st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
 
@@ -279,6 +279,7 @@ class Context:
         o = _Outputs(ptr(out.acos_pair), ptr(out.acos_atom), ptr(out.sel_words), ptr(out.scale_code), ptr(out.codes),
                      ptr(out.blk_cos), ptr(out.blk_err))
         _check(lib().sop_pair_search(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
-                                     fmt, k, metric, C.c_void_p(self._ws.data_ptr()), self._ws.numel(), C.byref(o),
+                                     fmt, k, metric, None if self._ws is None else C.c_void_p(self._ws.data_ptr()),
+                                     0 if self._ws is None else self._ws.numel(), C.byref(o),
                                      C.c_void_p(st)), self._h)
         return out

@@ -46,7 +46,8 @@ struct sop_ctx {
     float bin_lo[SOP_K_MAXA] = {0}, bin_hi[SOP_K_MAXA] = {0};
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
-    BinRec* d_bins = nullptr;             // [MAXA][MAXBINS] capacity
+    BinRec* d_bins = nullptr;             // [MAXBINS] capacity
+    unsigned long long* d_sums = nullptr; // [SOP_K_NCOL] layer sums + (one word further) the finished-workgroup counter; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
     size_t occ_lds[192];
@@ -97,6 +98,12 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     c->n_cu = prop.multiProcessorCount;
     if (const char* s = getenv("SOP_WAVES_PER_SIMD")) { long long v = atoll(s); if (v >= 1 && v <= 8) c->waves_override = v; }
     if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
+    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * (SOP_K_NCOL + 1))) != hipSuccess ||
+        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * (SOP_K_NCOL + 1))) != hipSuccess) {
+        (void)hipFree(c->d_bins); if (c->d_sums) (void)hipFree(c->d_sums);
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(layer sums)");
+    }
     *out = c;
     return SOP_OK;
 }
@@ -107,6 +114,7 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
     {
         DeviceGuard guard(c->device);
         if (c->d_bins) (void)hipFree(c->d_bins);
+        if (c->d_sums) (void)hipFree(c->d_sums);
         for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
     }
     delete c;
@@ -337,7 +345,7 @@ extern "C" sop_status sop_workspace_bytes(sop_ctx* c, int64_t M, int64_t K, int 
     if (!c) return SOP_EINVAL;
     if (!bytes) return fail(c, SOP_EINVAL, "sop_workspace_bytes: bytes is NULL");
     if (sop_status s = shape_check(c, M, K, g)) return s;
-    *bytes = (size_t)max_workgroups(c) * SOP_K_NCOL * sizeof(float);
+    *bytes = 0;                      // the layer reduction keeps its few words inside the context
     return SOP_OK;
 }
 
@@ -400,9 +408,7 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     if (1 - bias - y - k < -126 || 1 - bias - k > 126 || std::max(emax, 1) - bias - k > 125)
         return fail(c, SOP_EFMT, "scale format with this layer shift leaves binary32's normal range (choose bias / max_code / k accordingly)");
 
-    const size_t need = (size_t)max_workgroups(c) * SOP_K_NCOL * sizeof(float);
-    if (!ws || ws_bytes < need) return fail(c, SOP_ENOMEM, "workspace is NULL or smaller than sop_workspace_bytes()");
-    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(c, SOP_EINVAL, "workspace must be 256-byte aligned");
+    (void)ws; (void)ws_bytes;         // no workspace is needed (sop_workspace_bytes reports 0)
 
     const int epl = g < 16 ? g : 16, lpb = g / epl;
     const int A = c->n_atoms;
@@ -442,7 +448,8 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
         p.pair_slot_w[pi / 4] |= (unsigned)q << (8 * (pi % 4));
         p.pair_pi[q] = (unsigned char)pi;
     }
-    p.partial = static_cast<float*>(ws);
+    p.sums = c->d_sums;
+    p.done = reinterpret_cast<unsigned int*>(c->d_sums + SOP_K_NCOL);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
     p.acos_atom = out->acos_atom;
     p.sel_words = c->n_pairs ? out->sel_words : nullptr;

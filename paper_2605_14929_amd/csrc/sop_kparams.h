@@ -76,7 +76,11 @@ struct KParams {
     unsigned int pair_slot_w[SOP_K_MAXP / 4];          // byte pi%4 of word pi/4: output index of pair pi = pair_index(i,j)
     alignas(8) unsigned char pair_pi[SOP_K_MAXP + 4];  // pair_index(i,j) of output o
     // outputs
-    float*    partial;               // [SOP_K_NCOL][n_waves/4] per-workgroup sums of 1-cos
+    // layer sums of 1-cos in fixed point (2^-32 units): every workgroup adds its share with integer
+    // atomics (order-independent, so the result is reproducible); the workgroup that finishes last
+    // turns them into the ACos outputs and leaves sums and counter at zero for the next call
+    unsigned long long* sums;        // [SOP_K_NCOL]
+    unsigned int* done;              // workgroups finished
     double*   acos_pair;
     double*   acos_atom;
     void*     sel_words;             // [Nb] selector word of every block

@@ -31,8 +31,9 @@
 //              sign); metric COS: b beats a when fl(q_b*den_a) > fl(q_a*den_b), q = fl(num*|num|),
 //              a zero reconstruction counting as q = 0, den = 1
 // The cosine values are not decisions; they are evaluated in fp32 and accumulated per lane as the
-// deficit 1 - cos, reduced in binary64 by the second kernel.  A lane whose block has zero weighted
-// norm adds exactly 1 to every column and 1 to a count column that the second kernel subtracts.
+// deficit 1 - cos; workgroup sums enter the layer sums as 64-bit fixed-point integers.  A lane whose
+// block has zero weighted norm adds exactly 1 to every column and 1 to a count column that is
+// subtracted at the end.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -110,8 +111,10 @@ __device__ __forceinline__ void decode_scale(int q, const KParams& p, const floa
 __device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, float tn, bool unit_p, bool unit_n)
 {
     float s1 = pmax, s2 = nmax;
-    if (!unit_p) s1 = pmax / tp;
-    if (!unit_n) s2 = nmax / tn;
+    // the flags are wave-uniform; the empty asm statements keep these real branches (a division is a
+    // dozen instructions, and the common codebooks have unit endpoints)
+    if (!unit_p) { asm volatile(""); s1 = pmax / tp; }
+    if (!unit_n) { asm volatile(""); s2 = nmax / tn; }
     return fmaxf(s1, s2);
 }
 
@@ -632,7 +635,35 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
     if ((int)threadIdx.x < SOP_K_NCOL) {
         const int i = threadIdx.x;
         const float v = (s_red[i] + s_red[SOP_K_NCOL + i]) + (s_red[2 * SOP_K_NCOL + i] + s_red[3 * SOP_K_NCOL + i]);
-        p.partial[(long long)i * (p.n_waves / 4) + blockIdx.x] = v;
+        // 2^32 * v is exact in binary32 and far inside the 64-bit range (a workgroup's share is < 2^20)
+        if (v != 0.0f) {
+            // the returned value is consumed so that the add has completed at the memory side before
+            // this workgroup announces itself below (all traffic here is atomic: no cache write-back,
+            // which a fence would cost on every workgroup, is needed)
+            const unsigned long long before = atomicAdd(p.sums + i, (unsigned long long)__float2ll_rn(v * 4294967296.0f));
+            asm volatile("" :: "v"(before) : "memory");
+        }
+    }
+    // ---- layer reduction: the last workgroup to arrive finishes the layer ----
+    __syncthreads();
+    unsigned int* s_flag = reinterpret_cast<unsigned int*>(s_red);
+    if (threadIdx.x == 0) *s_flag = atomicAdd(p.done, 1u) == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    if (*s_flag) {
+        // lanes whose block had zero weighted norm (and lanes past the end of a row) added exactly 1
+        // to every column; the count column takes them out again
+        const long long z = (long long)__hip_atomic_load(p.sums + SOP_K_ZCOL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int o = threadIdx.x;                 // 0..A-1 atoms (internal order), then pairs by output index
+        if (o < p.A + p.P) {
+            int col;
+            double* dst;
+            if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + p.uidx[o] : nullptr; }
+            else { col = SOP_K_MAXA + p.pair_pi[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
+            const long long t = (long long)atomicExch(p.sums + col, 0ull);
+            if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 4294967296.0)) / ((double)p.Nb * (double)p.lpb);
+        }
+        if (threadIdx.x == 255) { atomicExch(p.sums + SOP_K_ZCOL, 0ull); atomicExch(p.done, 0u); }
     }
 }
 
