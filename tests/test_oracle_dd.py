@@ -1,0 +1,134 @@
+"""Pins of the oracle's data-derived codebook (oracle/dd.py): the histogram arithmetic against a
+one-weight-at-a-time version and against conservation laws, the fit against scikit-learn's weighted
+k-means and the plain Lloyd iteration on the raw samples, exact-recovery and fixed-point cases, and
+the library's host fit (sop_dd_fit) against the oracle's."""
+import numpy as np
+import pytest
+
+import paper_2605_14929_amd as sop
+from oracle import atoms as OA, dd as DD
+import sop_inputs as si
+
+
+def _layer(M=48, K=512, seed=11, bf16=True):
+    W = si.student_t_weights(M, K, 4.0, seed, row_sigma=0.5, outlier_frac=0.002)
+    if bf16:
+        W = si.bf16_round(W)
+    c = si.channel_norms(K, 1.0, seed + 1)
+    return W, c
+
+
+@pytest.mark.parametrize("g", [8, 16, 32, 64])
+def test_vectorised_histogram_equals_the_loop_version(g):
+    W, c = _layer(M=6, K=256, seed=3 + g)
+    W[1, :g] = 0.0                                                   # an all-zero block is skipped
+    W[2, g:2 * g] = -np.abs(W[2, g:2 * g])                            # one-signed block
+    for cc in (c, None):
+        assert np.array_equal(DD.histogram(W, cc, g, 256), DD.histogram_loops(W, cc, g, 256))
+
+
+def test_histogram_conserves_weight_and_first_moment():
+    W, c = _layer()
+    H = 1024
+    h = DD.histogram(W, c, 16, H)
+    x, wt = DD.samples(W, c, 16)
+    cs = 2.0 ** 20 / float(c.max())
+    # every sample adds rint(c*cs): the total is within half a unit per sample of sum(c)*cs
+    assert abs(h[0].sum() - wt.sum() * cs) <= 0.5 * x.size + 1e-3 * wt.sum() * cs * 2.0 ** -20
+    # first moment: sum(c*x) in units of 2^-30 max(c), within half a unit per sample plus binary32 rounding
+    assert abs(h[1].sum() - (wt * x).sum() * cs * 1024.0) <= 0.5 * x.size + 2.0 ** -22 * np.abs(wt * x).sum() * cs * 1024.0
+    # each bin's mean lies inside the bin (moments belong to the samples of that bin)
+    occupied = h[0] > 0
+    mean = (h[1][occupied] / 1024.0) / h[0][occupied]
+    lo = -1.0 + np.flatnonzero(occupied) * (2.0 / H)
+    assert np.all(mean >= lo - 1e-3) and np.all(mean <= lo + 2.0 / H + 1e-3)
+    # every block contributes its largest-magnitude element at |x| = 1: the end bins hold them
+    assert h[0][0] > 0 and h[0][H - 1] > 0
+
+
+def test_power_of_two_rescaling_of_c_and_w_changes_nothing():
+    W, c = _layer(seed=21)
+    h = DD.histogram(W, c, 16, 512)
+    assert np.array_equal(h, DD.histogram(W, c * np.float32(8.0), 16, 512))
+    assert np.array_equal(h, DD.histogram(W * np.float32(2.0 ** -7), c, 16, 512))
+    # negating the layer mirrors the histogram (moments change sign); bin edges make this exact
+    # only away from them, so compare the totals
+    hn = DD.histogram(-W, c, 16, 512)
+    assert hn[0].sum() == h[0].sum() and hn[1].sum() == -h[1].sum()
+
+
+@pytest.mark.parametrize("weighted", [False, True])
+def test_fit_matches_sample_based_clustering(weighted):
+    from sklearn.cluster import KMeans
+    W, c = _layer(M=96, K=1024, seed=31)
+    cc = c if weighted else None
+    H, iters = 4096, 12
+    init = OA.nf(4)
+    cent = DD.fit(DD.histogram(W, cc, 16, H), 16, iters, init)
+    x, wt = DD.samples(W, cc, 16)
+    # (a) the oracle's plain weighted Lloyd iteration on the raw samples
+    ref = OA.lloyd_1d(x, wt if weighted else None, init, iters)
+    assert np.max(np.abs(cent - ref)) < 2.5 * (2.0 / H)
+    # (b) scikit-learn's Lloyd k-means, same start, same number of rounds
+    km = KMeans(n_clusters=16, init=init.reshape(-1, 1), n_init=1, max_iter=iters, tol=0.0, algorithm="lloyd")
+    km.fit(x.reshape(-1, 1), sample_weight=wt if weighted else None)
+    sk = np.sort(km.cluster_centers_.ravel())
+    assert np.max(np.abs(cent - sk)) < 2.5 * (2.0 / H)
+    # the channel-norm weighting matters: the two fits differ by far more than the tolerance
+    if weighted:
+        plain = DD.fit(DD.histogram(W, None, 16, H), 16, iters, init)
+        assert np.max(np.abs(cent - plain)) > 5 * (2.0 / H)
+
+
+def test_fit_recovers_levels_that_are_exactly_there():
+    rng = np.random.default_rng(5)
+    levels = np.array([-1.0, -0.75, -0.5, -0.375, -0.25, -0.125, -0.0625, 0.0, 0.0625, 0.1875, 0.25,
+                       0.4375, 0.5, 0.625, 0.875, 1.0])
+    M, K, g = 32, 256, 16
+    idx = rng.integers(0, 16, size=(M, K // g, g))
+    idx[:, :, 0] = 15                                                 # every block holds +1 (its largest magnitude)
+    scale = 2.0 ** rng.integers(-4, 4, size=(M, K // g, 1))
+    W = (levels[idx] * scale).reshape(M, K).astype(np.float32)
+    c = si.channel_norms(K, 1.0, 6)
+    h = DD.histogram(W, c, g, 2048)
+    assert np.count_nonzero(h[0]) == 16
+    start = levels + rng.uniform(-0.02, 0.02, size=16)
+    cent = DD.fit(h, 16, 3, np.sort(start))
+    assert np.max(np.abs(cent - levels)) < 1e-6
+
+
+def test_fit_reaches_a_fixed_point_and_lowers_the_distortion():
+    W, c = _layer(M=64, K=1024, seed=41)
+    h = DD.histogram(W, c, 16, 2048)
+    H = 2048
+    centres = -1.0 + (np.arange(H) + 0.5) * (2.0 / H)
+
+    def distortion(cent):
+        d = np.abs(centres[:, None] - cent[None, :]).min(axis=1)
+        return float((h[0] * d * d).sum())
+
+    prev = OA.nf(4)
+    values = [distortion(prev)]
+    for _ in range(6):
+        prev = DD.fit(h, 16, 1, prev)
+        values.append(distortion(prev))
+    assert all(b <= a * (1 + 1e-9) for a, b in zip(values, values[1:])) and values[-1] < 0.95 * values[0]
+    far = DD.fit(h, 16, 400, OA.nf(4))
+    assert np.array_equal(far, DD.fit(h, 16, 1, far))                # one more round changes nothing
+    assert far[0] < 0 < far[-1] and np.all(np.diff(far) > 0)
+
+
+def test_library_host_fit_equals_the_oracle_fit():
+    W, c = _layer(M=64, K=1024, seed=51)
+    for H, n_bits, iters in ((1024, 4, 20), (4096, 5, 7), (256, 3, 50)):
+        h = DD.histogram(W, c, 16, H)
+        init = OA.to_f32(OA.nf(n_bits))
+        mine = sop.sop_dd_fit(h, 2 ** n_bits, iters, init)
+        ref = DD.fit(h, 2 ** n_bits, iters, init.astype(np.float64))
+        assert np.array_equal(mine, ref.astype(np.float32))
+    with pytest.raises(sop.SopError) as e:                            # a one-sided result cannot be an atom
+        hh = np.zeros((2, 256), dtype=np.int64)
+        hh[0, 200:] = 5
+        hh[1, 200:] = (5 * 1024 * (-1.0 + (np.arange(200, 256) + 0.5) / 128)).astype(np.int64)
+        sop.sop_dd_fit(hh, 4, 5, np.array([0.55, 0.6, 0.7, 0.9], dtype=np.float32))
+    assert e.value.status == 3
