@@ -164,6 +164,37 @@ sop_status sop_lloyd_1d(const double* samples, const double* weights, int64_t n_
  * endpoints are set to -1 and +1 and the entry nearest zero to 0. */
 sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g, int iters, float* out);
 
+/* ---- data-derived codebook ("DD" atom; Section "Per-Layer Pair Search", steps 1 and 3: a
+ * data-adaptive atom is fitted per layer from a histogram of the layer's weights; design axis (iii):
+ * uniform or channel-norm-weighted updates).  Two steps: a statistics pass on the GPU and a
+ * weighted Lloyd fit on the histogram on the host. ----
+ *
+ * Histogram, in exact integer arithmetic (binary32 operations, one rounding each):
+ *   cmax = max_k c_k, cs = 2^20 / cmax (c_dev NULL: every c_k = 1);
+ *   per block of g weights: a = max |w_i| (blocks with a = 0 are skipped), r = 1 / a;
+ *   per weight: x = w_i * r, u = c_i * cs, mass = rint(u), moment = rint((u * 1024) * x),
+ *               bin = clamp(floor(x * H/2 + H/2), 0, H-1);
+ *   hist[bin] += mass (units 2^-20 cmax), hist[H + bin] += moment (units 2^-30 cmax).
+ * The result does not depend on the order of addition. */
+
+/* Bytes of DEVICE workspace sop_dd_histogram() needs (256-byte aligned, no initialisation). */
+sop_status sop_dd_workspace_bytes(sop_ctx* ctx, int n_bins, size_t* bytes);
+
+/* W_dev, dtype, M, K, ldw, c_dev (may be NULL), g as in sop_pair_search(); n_bins = H, a power of
+ * two within 64..4096; hist_dev: DEVICE, 2*H 64-bit integers, overwritten.  Asynchronous on the
+ * stream; calls sharing a workspace must not overlap. */
+sop_status sop_dd_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                            const float* c_dev, int g, int n_bins, int64_t* hist_dev,
+                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Weighted Lloyd iteration on a histogram (all HOST memory, binary64): each bin goes, whole, to the
+ * cell of its centre -1 + (b + 1/2) * 2/H (cell = number of midpoints of the current grid strictly
+ * below the centre); every non-empty cell's entry moves to (sum of moments / 1024) / (sum of
+ * masses); the grid is re-sorted; `iters` rounds from the ascending start grid `init`.  `out`
+ * receives n_entries binary32 values.  SOP_EATOM when the result is not strictly ascending or not
+ * two-sided (it could not serve as an atom). */
+sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries, int iters, const float* init, float* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@
 extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
 extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
+extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 
 namespace {
 
@@ -600,5 +601,84 @@ extern "C" sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_dr
     cent[z] = 0.0;
     std::sort(cent.begin(), cent.end());
     for (int j = 0; j < N; ++j) out[j] = (float)cent[j];
+    return SOP_OK;
+}
+
+// ------------------------------------------------------------------ data-derived codebook (DD atom)
+static bool dd_bins_ok(int n_bins) { return n_bins >= 64 && n_bins <= 4096 && (n_bins & (n_bins - 1)) == 0; }
+
+extern "C" sop_status sop_dd_workspace_bytes(sop_ctx* c, int n_bins, size_t* bytes)
+{
+    if (!c) return SOP_EINVAL;
+    if (!bytes) return fail(c, SOP_EINVAL, "sop_dd_workspace_bytes: bytes is NULL");
+    if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..4096");
+    *bytes = 256 + (size_t)c->n_cu * 2 * (size_t)n_bins * sizeof(unsigned long long);
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                       const float* cn, int g, int n_bins, int64_t* hist, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!W || !hist) return fail(c, SOP_EINVAL, "sop_dd_histogram: W and hist must not be NULL");
+    if (dtype != SOP_F32 && dtype != SOP_BF16) return fail(c, SOP_EINVAL, "sop_dd_histogram: dtype must be SOP_F32 or SOP_BF16");
+    if (sop_status s = shape_check(c, M, K, g)) return s;
+    if (ldw < K) return fail(c, SOP_ESHAPE, "ldw must be at least K");
+    const int esz = dtype == SOP_BF16 ? 2 : 4;
+    if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
+    if (cn && !aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
+    if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..4096");
+    if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
+    const size_t need = 256 + (size_t)c->n_cu * 2 * (size_t)n_bins * sizeof(unsigned long long);
+    if (!ws || ws_bytes < need) return fail(c, SOP_ENOMEM, "workspace is NULL or smaller than sop_dd_workspace_bytes()");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(c, SOP_EINVAL, "workspace must be 256-byte aligned");
+    const int epl = g < 16 ? g : 16;
+    DdParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.W = W; p.c = cn; p.M = M; p.K = K; p.ldw = ldw;
+    p.strips = (K / epl + 63) / 64;
+    p.total_units = p.strips * M;
+    const long long waves_per_wg = SOP_K_DD_THREADS / 64;
+    long long wg = std::min<long long>(c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    p.n_waves = std::max<long long>(wg, 1) * waves_per_wg;
+    p.n_bins = n_bins;
+    p.cmax = static_cast<float*>(ws);
+    p.partial = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
+    p.hist = reinterpret_cast<long long*>(hist);
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_dd_launch(&p, dtype == SOP_BF16, g, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries, int iters, const float* init, float* out)
+{
+    if (!hist || !init || !out) return fail(nullptr, SOP_EINVAL, "sop_dd_fit: NULL argument");
+    if (!dd_bins_ok(n_bins) || n_entries < 2 || n_entries > SOP_MAX_ENTRIES || iters < 0) return fail(nullptr, SOP_EINVAL, "sop_dd_fit: bad n_bins, n_entries or iters");
+    std::vector<double> cent(init, init + n_entries), mids(n_entries - 1);
+    for (int j = 0; j + 1 < n_entries; ++j)
+        if (!(cent[j] < cent[j + 1])) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the start grid must be strictly ascending");
+    std::vector<long long> mass(n_entries), mom(n_entries);
+    for (int it = 0; it < iters; ++it) {
+        for (int j = 0; j + 1 < n_entries; ++j) mids[j] = 0.5 * (cent[j] + cent[j + 1]);
+        std::fill(mass.begin(), mass.end(), 0LL);
+        std::fill(mom.begin(), mom.end(), 0LL);
+        int cell = 0;
+        for (int b = 0; b < n_bins; ++b) {
+            // a bin goes, whole, to the cell of its centre: cell = number of midpoints strictly below it
+            const double xc = -1.0 + ((double)b + 0.5) * (2.0 / (double)n_bins);
+            while (cell < n_entries - 1 && mids[cell] < xc) ++cell;
+            mass[cell] += hist[b];
+            mom[cell] += hist[n_bins + b];
+        }
+        for (int j = 0; j < n_entries; ++j)
+            if (mass[j] > 0) cent[j] = ((double)mom[j] / 1024.0) / (double)mass[j];
+        std::sort(cent.begin(), cent.end());
+    }
+    for (int j = 0; j < n_entries; ++j) out[j] = (float)cent[j];
+    for (int j = 0; j + 1 < n_entries; ++j)
+        if (!(out[j] < out[j + 1])) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the fitted grid is not strictly ascending in binary32 (too little data)");
+    if (!(out[0] < 0.0f && out[n_entries - 1] > 0.0f)) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the fitted grid is one-sided");
     return SOP_OK;
 }

@@ -90,4 +90,17 @@ struct KParams {
     float*    blk_cos;
     float*    blk_err;
 };
+
+/* Statistics pass of the data-derived codebook */
+#define SOP_K_DD_THREADS 1024
+struct DdParams {
+    const void*  W;
+    const float* c;                  // null: uniform weights
+    long long M, K, ldw;
+    long long strips, total_units, n_waves;
+    int n_bins;
+    float* cmax;                     // workspace: largest channel norm
+    unsigned long long* partial;     // workspace: [workgroups][2][n_bins]
+    long long* hist;                 // [2][n_bins] output
+};
 #endif

@@ -1,0 +1,87 @@
+"""GPU parity of the data-derived codebook: the integer histogram of the HIP path against the
+oracle's (bit-exact), the fitted table, and the pair search with the fitted atom appended."""
+import numpy as np
+import pytest
+
+import paper_2605_14929_amd as sop
+from oracle import atoms as OA, dd as DD, pairsearch as ops
+import sop_inputs as si
+from gpu_util import run_gpu, compare, oracle_fmt, ctx
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_hist(W, c, g, H, bf16, ldw=None):
+    import torch
+    Wt = torch.from_numpy(W).cuda()
+    if bf16:
+        Wt = Wt.to(torch.bfloat16)
+    if ldw is not None:
+        buf = torch.zeros((W.shape[0], ldw), dtype=Wt.dtype, device="cuda")
+        buf[:, :W.shape[1]] = Wt
+        Wt = buf[:, :W.shape[1]]
+    ct = None if c is None else torch.from_numpy(c).cuda()
+    h = ctx().dd_histogram(Wt, ct, g, H)
+    torch.cuda.synchronize()
+    return h.cpu().numpy()
+
+
+@pytest.mark.parametrize("g", [8, 16, 32, 64])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_histogram_block_sizes_dtypes_ragged(g, bf16):
+    M, K = 37, 1088                                                   # ragged last strip, uneven row ranges
+    W = si.student_t_weights(M, K, 4.0, 900 + g, row_sigma=0.5, outlier_frac=0.002)
+    if bf16:
+        W = si.bf16_round(W)
+    W[3, :] = 0.0                                                     # zero blocks are skipped
+    W[5, 64:128] = -np.abs(W[5, 64:128])
+    c = si.channel_norms(K, 1.0, 901)
+    c[200:216] = 0.0
+    for H in (256, 1024):
+        assert np.array_equal(gpu_hist(W, c, g, H, bf16), DD.histogram(W, c, g, H))
+    assert np.array_equal(gpu_hist(W, None, g, 512, bf16), DD.histogram(W, None, g, 512))
+
+
+def test_histogram_row_stride_and_bin_counts():
+    M, K = 16, 512
+    W = si.student_t_weights(M, K, 4.0, 911)
+    c = si.channel_norms(K, 1.0, 912)
+    assert np.array_equal(gpu_hist(W, c, 16, 64, False, ldw=K + 64), DD.histogram(W, c, 16, 64))
+    assert np.array_equal(gpu_hist(W, c, 16, 4096, False), DD.histogram(W, c, 16, 4096))
+    import torch
+    with pytest.raises(sop.SopError) as e:
+        ctx().dd_histogram(torch.from_numpy(W).cuda(), torch.from_numpy(c).cuda(), 16, 1000)
+    assert e.value.status == 1
+    with pytest.raises(sop.SopError) as e:
+        ctx().dd_histogram(torch.from_numpy(W).cuda(), torch.from_numpy(c).cuda(), 12, 1024)
+    assert e.value.status == 2
+
+
+def test_histogram_is_reproducible_and_full_layer():
+    W, c, cfg = si.make_config("C3_down")
+    a = gpu_hist(W, c, 16, 1024, True)
+    b = gpu_hist(W, c, 16, 1024, True)
+    assert np.array_equal(a, b)
+    assert np.array_equal(a, DD.histogram(W, c, 16, 1024))
+
+
+def test_dd4_joins_the_alphabet_config5_shape():
+    # 70B-shaped MLP layer 28672 x 8192: histogram and fit on the whole layer, then the seven-atom
+    # search (21 pairs, 32-bit selector words); oracle search on sampled rows
+    W, c, cfg = si.make_config("C5")
+    g, H = 16, 1024
+    hist = gpu_hist(W, c, g, H, True)
+    assert np.array_equal(hist, DD.histogram(W, c, g, H))
+    init = sop.sop_atom_nf(4)
+    dd4 = sop.sop_dd_fit(hist, 16, 20, init)                          # 16 centroids, 20 rounds, from NF4
+    assert np.array_equal(dd4, DD.fit(hist, 16, 20, OA.to_f32(OA.nf(4)).astype(np.float64)).astype(np.float32))
+    tabs = sop.build_alphabet(cfg["atoms"], bof_draws=si.normal_draws(1 << 20, 4242)) + [dd4]
+    fmt = sop.fmt_by_name(cfg["fmt"])
+    gpu = run_gpu(W, c, tabs, g, fmt, bf16=True, emit=False)
+    rows = np.sort(np.random.default_rng(7).choice(W.shape[0], 192, replace=False))
+    ref = ops.pair_search(W[rows], c, tabs, g, oracle_fmt(fmt), want_codes=False)
+    Bk = W.shape[1] // g
+    assert np.array_equal(gpu["sel_words"].reshape(W.shape[0], Bk)[rows].reshape(-1), ref.sel_words)
+    assert np.max(np.abs(gpu["acos_atom"] - ref.acos_atom)) < 2e-4     # sampled rows estimate the layer mean
+    # the atom fitted to this layer beats every fixed atom on it
+    assert gpu["acos_atom"][6] > gpu["acos_atom"][:6].max()
