@@ -172,27 +172,27 @@ sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g,
  * Histogram, in exact integer arithmetic (binary32 operations, one rounding each):
  *   cmax = max_k c_k, cs = 2^20 / cmax (c_dev NULL: every c_k = 1);
  *   per block of g weights: a = max |w_i| (blocks with a = 0 are skipped), r = 1 / a;
- *   per weight: x = w_i * r, u = c_i * cs, mass = rint(u), moment = rint((u * 1024) * x),
- *               bin = clamp(floor(x * H/2 + H/2), 0, H-1);
- *   hist[bin] += mass (units 2^-20 cmax), hist[H + bin] += moment (units 2^-30 cmax).
+ *   per weight: x = w_i * r, mass = rint(c_i * cs)  (units of 2^-20 cmax),
+ *               bin = clamp(floor(x * H/2 + H/2), 0, H-1);    hist[bin] += mass.
  * The result does not depend on the order of addition. */
 
-/* Bytes of DEVICE workspace sop_dd_histogram() needs (256-byte aligned, no initialisation). */
-sop_status sop_dd_workspace_bytes(sop_ctx* ctx, int n_bins, size_t* bytes);
-
 /* W_dev, dtype, M, K, ldw, c_dev (may be NULL), g as in sop_pair_search(); n_bins = H, a power of
- * two within 64..4096; hist_dev: DEVICE, 2*H 64-bit integers, overwritten.  Asynchronous on the
- * stream; calls sharing a workspace must not overlap. */
+ * two within 64..8192; row_step >= 1: only rows 0, row_step, 2*row_step, ... enter the histogram
+ * (1 = the whole layer; the pass is bound by LDS atomics, not by HBM, so a sample of the rows is
+ * the cheap way to a fit of the same quality); hist_dev: DEVICE, H 64-bit integers, overwritten.
+ * Asynchronous on the stream; needs no workspace.  Calls on one context must not overlap on the
+ * GPU (the context holds the running histogram). */
 sop_status sop_dd_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
-                            const float* c_dev, int g, int n_bins, int64_t* hist_dev,
-                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+                            const float* c_dev, int g, int n_bins, int64_t row_step, int64_t* hist_dev,
+                            void* hip_stream);
 
-/* Weighted Lloyd iteration on a histogram (all HOST memory, binary64): each bin goes, whole, to the
- * cell of its centre -1 + (b + 1/2) * 2/H (cell = number of midpoints of the current grid strictly
- * below the centre); every non-empty cell's entry moves to (sum of moments / 1024) / (sum of
- * masses); the grid is re-sorted; `iters` rounds from the ascending start grid `init`.  `out`
- * receives n_entries binary32 values.  SOP_EATOM when the result is not strictly ascending or not
- * two-sided (it could not serve as an atom). */
+/* Weighted Lloyd iteration on a histogram (all HOST memory): bin b stands for its centre
+ * -1 + (2b+1)/H and goes, whole, to that centre's cell (cell = number of midpoints of the current
+ * grid strictly below the centre); every non-empty cell's entry moves to the mass-weighted mean of
+ * its bins' centres (exact integer sums, one binary64 division); the grid is re-sorted; `iters`
+ * rounds from the ascending start grid `init`.  `out` receives n_entries binary32 values.
+ * SOP_EATOM when the result is not strictly ascending or not two-sided (it could not serve as an
+ * atom). */
 sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries, int iters, const float* init, float* out);
 
 #ifdef __cplusplus

@@ -10,12 +10,12 @@ grid trained per layer).  The paper gives no recipe beyond that; the reading tak
   - every block of g weights is normalised by its largest magnitude, x = w / max|w|, so that x
     lies in [-1, 1] whatever the block's scale (the codebooks are used on scaled weights);
   - weight i counts with its channel norm c_i (or 1);
-  - the samples are collected into H uniform bins over [-1, 1] holding the summed weight and the
-    summed weight * x of their samples, as exact integers (weights in units of 2^-20 max(c),
-    first moments in units of 2^-30 max(c)), every binary32 operation rounded once;
-  - Lloyd: a bin goes, whole, to the cell of its centre; a cell's entry moves to the weighted
-    mean of its bins' samples (sum of moments / sum of weights); 16 entries, start grid and number
-    of rounds given by the caller.
+  - the samples are collected into a histogram of H uniform bins over [-1, 1] (the paper builds
+    its data-adaptive atoms from a histogram), each bin holding the summed weight of its samples as
+    an exact integer (units of 2^-20 max(c)), every binary32 operation rounded once;
+  - Lloyd on the histogram: a bin stands for its centre; it goes, whole, to the cell of that
+    centre, and a cell's entry moves to the weighted mean of its bins' centres; number of entries,
+    start grid and number of rounds are given by the caller.
 Parity unpinned for the choice of recipe (the paper prints no DD4 table); the arithmetic of the
 recipe is pinned against scikit-learn's weighted k-means on the raw samples, against the plain
 Lloyd iteration of oracle/atoms.py and by exact-recovery cases (tests/test_oracle_dd.py).
@@ -28,18 +28,16 @@ F32 = np.float32
 
 
 def histogram(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int) -> np.ndarray:
-    """[2, H] int64: row 0 = summed integer weights, row 1 = summed integer first moments."""
+    """[H] int64: summed integer weights of the samples of every bin."""
     W = np.ascontiguousarray(W, dtype=F32)
     M, K = W.shape
     assert K % g == 0
     cv = np.ones(K, dtype=F32) if c is None else np.ascontiguousarray(c, dtype=F32)
     cmax = cv.max()
     cs = F32(1048576.0) / cmax if cmax > 0 else F32(0.0)             # binary32 division
-    u = (cv * cs).astype(F32)                                        # fl(c * cs)
-    mass_col = np.rint(u).astype(np.int64)                           # round half to even
-    u1024 = (u * F32(1024.0)).astype(F32)                            # exact scaling
+    mass_col = np.rint((cv * cs).astype(F32)).astype(np.int64)       # rint(fl(c * cs)), half to even
     half = F32(0.5 * n_bins)
-    hist = np.zeros((2, n_bins), dtype=np.int64)
+    hist = np.zeros(n_bins, dtype=np.int64)
     rows = max(1, (1 << 22) // K)
     for r0 in range(0, M, rows):                                     # chunks bound the temporaries
         blk = W[r0:r0 + rows].reshape(-1, K // g, g)
@@ -48,13 +46,11 @@ def histogram(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int) -> np.nd
         r = np.zeros_like(a)
         r[live] = F32(1.0) / a[live]                                 # fl(1 / a)
         x = (blk * r[:, :, None]).astype(F32)                        # fl(w * r)
-        mom = np.rint((u1024.reshape(1, K // g, g) * x).astype(F32)).astype(np.int64)
         b = np.floor(((x * half).astype(F32) + half).astype(F32)).astype(np.int64)
         b = np.clip(b, 0, n_bins - 1)
         sel = np.broadcast_to(live[:, :, None], x.shape)
         mass = np.broadcast_to(mass_col.reshape(1, K // g, g), x.shape)
-        np.add.at(hist[0], b[sel], mass[sel])
-        np.add.at(hist[1], b[sel], mom[sel])
+        np.add.at(hist, b[sel], mass[sel])
     return hist
 
 
@@ -67,7 +63,6 @@ def histogram_loops(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int) ->
     cs = F32(1048576.0) / cmax if cmax > 0 else F32(0.0)
     half = F32(0.5 * n_bins)
     mass = [0] * n_bins
-    mom = [0] * n_bins
     for m in range(M):
         for j in range(K // g):
             w = [F32(v) for v in W[m, j * g:(j + 1) * g]]
@@ -77,31 +72,29 @@ def histogram_loops(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int) ->
             r = F32(1.0) / a
             for i, wi in enumerate(w):
                 x = F32(wi * r)
-                u = F32(cv[j * g + i] * cs)
-                t = F32(F32(u * F32(1024.0)) * x)
                 b = int(np.floor(F32(F32(x * half) + half)))
                 b = min(max(b, 0), n_bins - 1)
-                mass[b] += int(np.rint(u))
-                mom[b] += int(np.rint(t))
-    return np.array([mass, mom], dtype=np.int64)
+                mass[b] += int(np.rint(F32(cv[j * g + i] * cs)))
+    return np.array(mass, dtype=np.int64)
 
 
 def fit(hist: np.ndarray, n_entries: int, iters: int, init: np.ndarray) -> np.ndarray:
-    """Weighted Lloyd rounds on the histogram, binary64; returns the ascending grid (float64)."""
-    h = np.asarray(hist, dtype=np.int64).reshape(2, -1)
-    H = h.shape[1]
+    """Weighted Lloyd rounds on the histogram, binary64; returns the ascending grid (float64).
+    Bin b stands for its centre -1 + (2b+1)/H; a cell's mean is formed from exact integer sums."""
+    h = [int(v) for v in np.asarray(hist, dtype=np.int64).reshape(-1)]
+    H = len(h)
     cent = np.array(init, dtype=np.float64).copy()
     assert cent.size == n_entries and np.all(np.diff(cent) > 0)
-    centres = -1.0 + (np.arange(H, dtype=np.float64) + 0.5) * (2.0 / H)
+    centres = -1.0 + (2.0 * np.arange(H, dtype=np.float64) + 1.0) / H
     for _ in range(iters):
         mids = 0.5 * (cent[:-1] + cent[1:])
         cell = np.searchsorted(mids, centres, side="left")           # midpoints strictly below the centre
         for j in range(n_entries):
-            in_cell = cell == j
-            mass = int(h[0][in_cell].sum(dtype=np.int64))
+            bins = np.flatnonzero(cell == j)
+            mass = sum(h[b] for b in bins)
             if mass > 0:
-                mom = int(h[1][in_cell].sum(dtype=np.int64))
-                cent[j] = (float(mom) / 1024.0) / float(mass)
+                first = sum(h[b] * (2 * int(b) + 1) for b in bins)    # exact
+                cent[j] = (float(first) / float(mass)) / H - 1.0
         cent = np.sort(cent)
     return cent
 

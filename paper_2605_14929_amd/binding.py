@@ -70,9 +70,8 @@ def lib():
         L.sop_atom_negate.argtypes = [C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_float)]
         L.sop_lloyd_1d.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int64, C.POINTER(C.c_double), C.c_int, C.c_int]
         L.sop_atom_bof.argtypes = [C.c_int, C.POINTER(C.c_double), C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float)]
-        L.sop_dd_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
         L.sop_dd_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_int,
-                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+                                       C.c_int64, C.c_void_p, C.c_void_p]
         L.sop_dd_fit.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         _lib = L
     return _lib
@@ -123,11 +122,11 @@ def sop_atom_bof(n_bits: int, draws: np.ndarray, g: int = 16, iters: int = 50) -
 
 
 def sop_dd_fit(hist: np.ndarray, n_entries: int, iters: int, init: np.ndarray) -> np.ndarray:
-    """Weighted Lloyd fit on a [2, H] int64 histogram (host)."""
-    h = np.ascontiguousarray(hist, dtype=np.int64).reshape(2, -1)
+    """Weighted Lloyd fit on an [H] int64 histogram (host)."""
+    h = np.ascontiguousarray(hist, dtype=np.int64).reshape(-1)
     ini = np.ascontiguousarray(init, dtype=np.float32)
     out = np.empty(n_entries, dtype=np.float32)
-    _check(lib().sop_dd_fit(_fp(h, C.c_int64), h.shape[1], n_entries, iters, _fp(ini), _fp(out)))
+    _check(lib().sop_dd_fit(_fp(h, C.c_int64), h.size, n_entries, iters, _fp(ini), _fp(out)))
     return out
 
 
@@ -261,8 +260,8 @@ class Context:
             o.blk_err = torch.empty((A, Nb), dtype=torch.float32, device=dev)
         return o
 
-    def dd_histogram(self, W, c, g, n_bins: int = 1024, stream=None):
-        """sop_dd_histogram on torch CUDA tensors; returns a [2, n_bins] int64 device tensor."""
+    def dd_histogram(self, W, c, g, n_bins: int = 1024, row_step: int = 1, stream=None):
+        """sop_dd_histogram on torch CUDA tensors; returns an [n_bins] int64 device tensor."""
         import torch
         if not W.is_cuda or (c is not None and not c.is_cuda):
             raise SopError(1, "W and c must be CUDA tensors (no CPU fallback)")
@@ -272,15 +271,11 @@ class Context:
         if dt is None:
             raise SopError(1, "W must be float32 or bfloat16")
         M, K = W.shape
-        n = C.c_size_t()
-        _check(lib().sop_dd_workspace_bytes(self._h, n_bins, C.byref(n)), self._h)
-        if getattr(self, "_dd_ws", None) is None or self._dd_ws.numel() < n.value:
-            self._dd_ws = torch.empty(n.value, dtype=torch.uint8, device=W.device)
-        hist = torch.empty((2, n_bins), dtype=torch.int64, device=W.device)
+        hist = torch.empty(n_bins, dtype=torch.int64, device=W.device)
         st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
         _check(lib().sop_dd_histogram(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0),
-                                      None if c is None else C.c_void_p(c.data_ptr()), g, n_bins, C.c_void_p(hist.data_ptr()),
-                                      C.c_void_p(self._dd_ws.data_ptr()), self._dd_ws.numel(), C.c_void_p(st)), self._h)
+                                      None if c is None else C.c_void_p(c.data_ptr()), g, n_bins, row_step, C.c_void_p(hist.data_ptr()),
+                                      C.c_void_p(st)), self._h)
         return hist
 
     def pair_search(self, W, c, g, fmt: ScaleFmt, k: int = 0, metric: int = SEL_WSE, out: Outputs = None,

@@ -48,6 +48,7 @@ struct sop_ctx {
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
+    unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned long long* d_sums = nullptr; // [SOP_K_NCOL] layer sums + (one word further) the finished-workgroup counter; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
@@ -105,6 +106,12 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(layer sums)");
     }
+    if ((e = hipMalloc((void**)&c->d_ddacc, sizeof(unsigned long long) * (SOP_K_DD_MAXBINS + 1))) != hipSuccess ||
+        (e = hipMemset(c->d_ddacc, 0, sizeof(unsigned long long) * (SOP_K_DD_MAXBINS + 1))) != hipSuccess) {
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); if (c->d_ddacc) (void)hipFree(c->d_ddacc);
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(histogram)");
+    }
     *out = c;
     return SOP_OK;
 }
@@ -116,6 +123,7 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         DeviceGuard guard(c->device);
         if (c->d_bins) (void)hipFree(c->d_bins);
         if (c->d_sums) (void)hipFree(c->d_sums);
+        if (c->d_ddacc) (void)hipFree(c->d_ddacc);
         for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
     }
     delete c;
@@ -605,19 +613,10 @@ extern "C" sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_dr
 }
 
 // ------------------------------------------------------------------ data-derived codebook (DD atom)
-static bool dd_bins_ok(int n_bins) { return n_bins >= 64 && n_bins <= 4096 && (n_bins & (n_bins - 1)) == 0; }
-
-extern "C" sop_status sop_dd_workspace_bytes(sop_ctx* c, int n_bins, size_t* bytes)
-{
-    if (!c) return SOP_EINVAL;
-    if (!bytes) return fail(c, SOP_EINVAL, "sop_dd_workspace_bytes: bytes is NULL");
-    if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..4096");
-    *bytes = 256 + (size_t)c->n_cu * 2 * (size_t)n_bins * sizeof(unsigned long long);
-    return SOP_OK;
-}
+static bool dd_bins_ok(int n_bins) { return n_bins >= 64 && n_bins <= SOP_K_DD_MAXBINS && (n_bins & (n_bins - 1)) == 0; }
 
 extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
-                                       const float* cn, int g, int n_bins, int64_t* hist, void* ws, size_t ws_bytes, void* stream)
+                                       const float* cn, int g, int n_bins, int64_t row_step, int64_t* hist, void* stream)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !hist) return fail(c, SOP_EINVAL, "sop_dd_histogram: W and hist must not be NULL");
@@ -627,23 +626,22 @@ extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtyp
     const int esz = dtype == SOP_BF16 ? 2 : 4;
     if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
     if (cn && !aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
-    if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..4096");
+    if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..8192");
     if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
-    const size_t need = 256 + (size_t)c->n_cu * 2 * (size_t)n_bins * sizeof(unsigned long long);
-    if (!ws || ws_bytes < need) return fail(c, SOP_ENOMEM, "workspace is NULL or smaller than sop_dd_workspace_bytes()");
-    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(c, SOP_EINVAL, "workspace must be 256-byte aligned");
+    if (row_step < 1) return fail(c, SOP_EINVAL, "row_step must be at least 1");
     const int epl = g < 16 ? g : 16;
     DdParams p;
     std::memset(&p, 0, sizeof(p));
     p.W = W; p.c = cn; p.M = M; p.K = K; p.ldw = ldw;
+    p.row_step = row_step; p.Ms = (M + row_step - 1) / row_step;
     p.strips = (K / epl + 63) / 64;
-    p.total_units = p.strips * M;
+    p.total_units = p.strips * p.Ms;
     const long long waves_per_wg = SOP_K_DD_THREADS / 64;
     long long wg = std::min<long long>(c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
     p.n_waves = std::max<long long>(wg, 1) * waves_per_wg;
     p.n_bins = n_bins;
-    p.cmax = static_cast<float*>(ws);
-    p.partial = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
+    p.acc = c->d_ddacc;
+    p.done = reinterpret_cast<unsigned int*>(c->d_ddacc + SOP_K_DD_MAXBINS);
     p.hist = reinterpret_cast<long long*>(hist);
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
@@ -656,24 +654,26 @@ extern "C" sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries,
 {
     if (!hist || !init || !out) return fail(nullptr, SOP_EINVAL, "sop_dd_fit: NULL argument");
     if (!dd_bins_ok(n_bins) || n_entries < 2 || n_entries > SOP_MAX_ENTRIES || iters < 0) return fail(nullptr, SOP_EINVAL, "sop_dd_fit: bad n_bins, n_entries or iters");
+    for (int b = 0; b < n_bins; ++b) if (hist[b] < 0) return fail(nullptr, SOP_EINVAL, "sop_dd_fit: negative histogram entry");
     std::vector<double> cent(init, init + n_entries), mids(n_entries - 1);
     for (int j = 0; j + 1 < n_entries; ++j)
         if (!(cent[j] < cent[j + 1])) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the start grid must be strictly ascending");
-    std::vector<long long> mass(n_entries), mom(n_entries);
+    std::vector<unsigned __int128> mass(n_entries), first(n_entries);
     for (int it = 0; it < iters; ++it) {
         for (int j = 0; j + 1 < n_entries; ++j) mids[j] = 0.5 * (cent[j] + cent[j + 1]);
-        std::fill(mass.begin(), mass.end(), 0LL);
-        std::fill(mom.begin(), mom.end(), 0LL);
+        std::fill(mass.begin(), mass.end(), (unsigned __int128)0);
+        std::fill(first.begin(), first.end(), (unsigned __int128)0);
         int cell = 0;
         for (int b = 0; b < n_bins; ++b) {
-            // a bin goes, whole, to the cell of its centre: cell = number of midpoints strictly below it
-            const double xc = -1.0 + ((double)b + 0.5) * (2.0 / (double)n_bins);
+            // a bin stands for its centre -1 + (2b+1)/H and goes, whole, to that centre's cell
+            // (cell = number of midpoints strictly below the centre)
+            const double xc = -1.0 + (2.0 * (double)b + 1.0) / (double)n_bins;
             while (cell < n_entries - 1 && mids[cell] < xc) ++cell;
-            mass[cell] += hist[b];
-            mom[cell] += hist[n_bins + b];
+            mass[cell] += (unsigned __int128)hist[b];
+            first[cell] += (unsigned __int128)hist[b] * (unsigned)(2 * b + 1);
         }
         for (int j = 0; j < n_entries; ++j)
-            if (mass[j] > 0) cent[j] = ((double)mom[j] / 1024.0) / (double)mass[j];
+            if (mass[j] > 0) cent[j] = ((double)first[j] / (double)mass[j]) / (double)n_bins - 1.0;
         std::sort(cent.begin(), cent.end());
     }
     for (int j = 0; j < n_entries; ++j) out[j] = (float)cent[j];

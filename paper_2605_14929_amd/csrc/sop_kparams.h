@@ -93,14 +93,16 @@ struct KParams {
 
 /* Statistics pass of the data-derived codebook */
 #define SOP_K_DD_THREADS 1024
+#define SOP_K_DD_MAXBINS 8192
 struct DdParams {
     const void*  W;
     const float* c;                  // null: uniform weights
     long long M, K, ldw;
-    long long strips, total_units, n_waves;
+    long long row_step, Ms;          // every row_step-th row is used: Ms = ceil(M / row_step) rows
+    long long strips, total_units, n_waves;  // total_units = strips * Ms
     int n_bins;
-    float* cmax;                     // workspace: largest channel norm
-    unsigned long long* partial;     // workspace: [workgroups][2][n_bins]
-    long long* hist;                 // [2][n_bins] output
+    unsigned long long* acc;         // [n_bins] running histogram of the layer (zero between calls)
+    unsigned int* done;              // workgroups finished
+    long long* hist;                 // [n_bins] output
 };
 #endif

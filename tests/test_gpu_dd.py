@@ -11,7 +11,7 @@ from gpu_util import run_gpu, compare, oracle_fmt, ctx
 pytestmark = pytest.mark.gpu
 
 
-def gpu_hist(W, c, g, H, bf16, ldw=None):
+def gpu_hist(W, c, g, H, bf16, ldw=None, row_step=1):
     import torch
     Wt = torch.from_numpy(W).cuda()
     if bf16:
@@ -21,7 +21,7 @@ def gpu_hist(W, c, g, H, bf16, ldw=None):
         buf[:, :W.shape[1]] = Wt
         Wt = buf[:, :W.shape[1]]
     ct = None if c is None else torch.from_numpy(c).cuda()
-    h = ctx().dd_histogram(Wt, ct, g, H)
+    h = ctx().dd_histogram(Wt, ct, g, H, row_step)
     torch.cuda.synchronize()
     return h.cpu().numpy()
 
@@ -40,6 +40,8 @@ def test_histogram_block_sizes_dtypes_ragged(g, bf16):
     for H in (256, 1024):
         assert np.array_equal(gpu_hist(W, c, g, H, bf16), DD.histogram(W, c, g, H))
     assert np.array_equal(gpu_hist(W, None, g, 512, bf16), DD.histogram(W, None, g, 512))
+    for step in (2, 5, 64):                                           # a sample of the rows: 0, step, 2*step, ...
+        assert np.array_equal(gpu_hist(W, c, g, 256, bf16, row_step=step), DD.histogram(W[::step], c, g, 256))
 
 
 def test_histogram_row_stride_and_bin_counts():
@@ -47,7 +49,7 @@ def test_histogram_row_stride_and_bin_counts():
     W = si.student_t_weights(M, K, 4.0, 911)
     c = si.channel_norms(K, 1.0, 912)
     assert np.array_equal(gpu_hist(W, c, 16, 64, False, ldw=K + 64), DD.histogram(W, c, 16, 64))
-    assert np.array_equal(gpu_hist(W, c, 16, 4096, False), DD.histogram(W, c, 16, 4096))
+    assert np.array_equal(gpu_hist(W, c, 16, 8192, False), DD.histogram(W, c, 16, 8192))
     import torch
     with pytest.raises(sop.SopError) as e:
         ctx().dd_histogram(torch.from_numpy(W).cuda(), torch.from_numpy(c).cuda(), 16, 1000)
@@ -69,7 +71,7 @@ def test_dd4_joins_the_alphabet_config5_shape():
     # 70B-shaped MLP layer 28672 x 8192: histogram and fit on the whole layer, then the seven-atom
     # search (21 pairs, 32-bit selector words); oracle search on sampled rows
     W, c, cfg = si.make_config("C5")
-    g, H = 16, 1024
+    g, H = 16, 4096
     hist = gpu_hist(W, c, g, H, True)
     assert np.array_equal(hist, DD.histogram(W, c, g, H))
     init = sop.sop_atom_nf(4)
@@ -85,3 +87,7 @@ def test_dd4_joins_the_alphabet_config5_shape():
     assert np.max(np.abs(gpu["acos_atom"] - ref.acos_atom)) < 2e-4     # sampled rows estimate the layer mean
     # the atom fitted to this layer beats every fixed atom on it
     assert gpu["acos_atom"][6] > gpu["acos_atom"][:6].max()
+    # a fit from every 16th row is the same grid to within two histogram bins
+    h16 = gpu_hist(W, c, g, H, True, row_step=16)
+    assert np.array_equal(h16, DD.histogram(W[::16], c, g, H))
+    assert np.max(np.abs(sop.sop_dd_fit(h16, 16, 20, init) - dd4)) < 4e-3
