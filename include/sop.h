@@ -195,6 +195,28 @@ sop_status sop_dd_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, in
  * atom). */
 sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries, int iters, const float* init, float* out);
 
+/* ---- per-layer scale shift (Section "Scale Format and Metabit Allocation", paragraph "Per-layer
+ * scale shift": all block scales of a layer are multiplied by 2^k before they are rounded into the
+ * scale word, k* maximising the fraction of block scales in the format's normal range).  Two steps:
+ * a statistics pass on the GPU and the choice of k* on the host; k* is then passed to
+ * sop_pair_search() as layer_shift_k. ----
+ *
+ * Histogram of the ideal block scales sc = max(pmax / t_pos, nmax / t_neg) (the absmax rule against
+ * a codebook with last entry t_pos and first entry -t_neg; IEEE binary32 divisions): writing
+ * sc = m * 2^e with 1/2 <= m < 1, hist[e + 160] counts the blocks with that e, and
+ * hist[320 + e + 160] those among them whose m exceeds the m of the format's largest value.
+ * Blocks with sc = 0 are not counted.  hist_dev: DEVICE, 640 64-bit integers, overwritten.
+ * Asynchronous; needs no workspace; calls on one context must not overlap on the GPU. */
+sop_status sop_scale_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw, int g,
+                               float t_pos, float t_neg, sop_scale_fmt fmt, int64_t* hist_dev, void* hip_stream);
+
+/* k* from such a histogram (HOST memory).  Normal range = [2^(1-bias), value(max_code)], both ends
+ * included; n_blocks = M*K/g is the denominator of the fraction (zero scales are in no range);
+ * candidates are the shifts within [-64, 64] that sop_pair_search() accepts for the format; among
+ * equally good shifts the smallest |k| wins, then the non-negative one.  *fraction (may be NULL)
+ * receives the fraction reached. */
+sop_status sop_layer_shift(const int64_t* hist, int64_t n_blocks, sop_scale_fmt fmt, int* k_star, double* fraction);
+
 #ifdef __cplusplus
 }
 #endif

@@ -73,6 +73,9 @@ def lib():
         L.sop_dd_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_int,
                                        C.c_int64, C.c_void_p, C.c_void_p]
         L.sop_dd_fit.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        L.sop_scale_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_float,
+                                          ScaleFmt, C.c_void_p, C.c_void_p]
+        L.sop_layer_shift.argtypes = [C.POINTER(C.c_int64), C.c_int64, ScaleFmt, C.POINTER(C.c_int), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -128,6 +131,16 @@ def sop_dd_fit(hist: np.ndarray, n_entries: int, iters: int, init: np.ndarray) -
     out = np.empty(n_entries, dtype=np.float32)
     _check(lib().sop_dd_fit(_fp(h, C.c_int64), h.size, n_entries, iters, _fp(ini), _fp(out)))
     return out
+
+
+def sop_layer_shift(hist: np.ndarray, n_blocks: int, fmt: "ScaleFmt"):
+    """(k*, fraction of block scales in the normal range) from a [2, 320] int64 exponent histogram (host)."""
+    h = np.ascontiguousarray(hist, dtype=np.int64).reshape(-1)
+    if h.size != 640:
+        raise SopError(1, "the exponent histogram has 2 x 320 entries")
+    k, frac = C.c_int(), C.c_double()
+    _check(lib().sop_layer_shift(_fp(h, C.c_int64), n_blocks, fmt, C.byref(k), C.byref(frac)))
+    return k.value, frac.value
 
 
 def sop_check_alphabet(tables):
@@ -259,6 +272,23 @@ class Context:
             o.blk_cos = torch.empty((A, Nb), dtype=torch.float32, device=dev)
             o.blk_err = torch.empty((A, Nb), dtype=torch.float32, device=dev)
         return o
+
+    def scale_histogram(self, W, g, t_pos: float, t_neg: float, fmt: ScaleFmt, stream=None):
+        """sop_scale_histogram on a torch CUDA tensor; returns a [2, 320] int64 device tensor."""
+        import torch
+        if not W.is_cuda:
+            raise SopError(1, "W must be a CUDA tensor (no CPU fallback)")
+        if W.dim() != 2 or W.stride(1) != 1:
+            raise SopError(2, "W must be a 2-D tensor with contiguous rows")
+        dt = BF16 if W.dtype == torch.bfloat16 else (F32 if W.dtype == torch.float32 else None)
+        if dt is None:
+            raise SopError(1, "W must be float32 or bfloat16")
+        M, K = W.shape
+        hist = torch.empty((2, 320), dtype=torch.int64, device=W.device)
+        st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
+        _check(lib().sop_scale_histogram(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), g, t_pos, t_neg, fmt,
+                                         C.c_void_p(hist.data_ptr()), C.c_void_p(st)), self._h)
+        return hist
 
     def dd_histogram(self, W, c, g, n_bins: int = 1024, row_step: int = 1, stream=None):
         """sop_dd_histogram on torch CUDA tensors; returns an [n_bins] int64 device tensor."""

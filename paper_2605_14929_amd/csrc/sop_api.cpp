@@ -20,6 +20,7 @@ extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int
 extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
+extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
 
 namespace {
 
@@ -680,5 +681,95 @@ extern "C" sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries,
     for (int j = 0; j + 1 < n_entries; ++j)
         if (!(out[j] < out[j + 1])) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the fitted grid is not strictly ascending in binary32 (too little data)");
     if (!(out[0] < 0.0f && out[n_entries - 1] > 0.0f)) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the fitted grid is one-sided");
+    return SOP_OK;
+}
+
+// ------------------------------------------------------------------ per-layer scale shift
+namespace {
+struct FmtRange { int x, y, bias, max_code; double lo, hi; };
+// resolves the defaults and checks the format as sop_pair_search() does
+bool resolve_fmt(const sop_scale_fmt& fmt, FmtRange& r)
+{
+    const int x = fmt.exp_bits, y = fmt.man_bits, w = fmt.sign_bits;
+    if ((w != 0 && w != 1) || x < 1 || x > 8 || y < 0 || y > 10 || x + y > 15) return false;
+    r.x = x; r.y = y;
+    r.bias = fmt.bias < 0 ? (1 << (x - 1)) - 1 : fmt.bias;
+    r.max_code = fmt.max_code < 0 ? (1 << (x + y)) - 1 : fmt.max_code;
+    if (r.max_code < 1 || r.max_code >= (1 << (x + y)) || r.bias < 0 || r.bias > 126) return false;
+    const int e = r.max_code >> y, f = r.max_code & ((1 << y) - 1);
+    r.lo = std::ldexp(1.0, 1 - r.bias);
+    r.hi = e == 0 ? std::ldexp((double)f, 1 - r.bias - y) : std::ldexp((double)((1 << y) + f), e - r.bias - y);
+    return true;
+}
+}  // namespace
+
+extern "C" sop_status sop_scale_histogram(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw, int g,
+                                          float t_pos, float t_neg, sop_scale_fmt fmt, int64_t* hist, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!W || !hist) return fail(c, SOP_EINVAL, "sop_scale_histogram: W and hist must not be NULL");
+    if (dtype != SOP_F32 && dtype != SOP_BF16) return fail(c, SOP_EINVAL, "sop_scale_histogram: dtype must be SOP_F32 or SOP_BF16");
+    if (sop_status s = shape_check(c, M, K, g)) return s;
+    if (ldw < K) return fail(c, SOP_ESHAPE, "ldw must be at least K");
+    const int esz = dtype == SOP_BF16 ? 2 : 4;
+    if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
+    if (!(t_pos > 0.0f) || !(t_neg > 0.0f) || !std::isfinite(t_pos) || !std::isfinite(t_neg)) return fail(c, SOP_EATOM, "endpoints must be positive and finite (t_neg is the magnitude of the first entry)");
+    FmtRange r;
+    if (!resolve_fmt(fmt, r)) return fail(c, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15, valid bias and max_code");
+    if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
+    const int epl = g < 16 ? g : 16;
+    FlParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.W = W; p.M = M; p.K = K; p.ldw = ldw;
+    p.strips = (K / epl + 63) / 64;
+    p.total_units = p.strips * M;
+    const long long waves_per_wg = SOP_K_FL_THREADS / 64;
+    long long wg = std::min<long long>((long long)c->n_cu * 8, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    p.n_waves = std::max<long long>(wg, 1) * waves_per_wg;
+    p.t_pos = t_pos; p.t_neg = t_neg;
+    int e_top;
+    p.m_top = std::frexp((float)r.hi, &e_top);
+    p.acc = c->d_ddacc;              // the context's running-histogram words serve both statistics passes
+    p.done = reinterpret_cast<unsigned int*>(c->d_ddacc + SOP_K_DD_MAXBINS);
+    p.hist = reinterpret_cast<long long*>(hist);
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_fl_launch(&p, dtype == SOP_BF16, g, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_layer_shift(const int64_t* hist, int64_t n_blocks, sop_scale_fmt fmt, int* k_star, double* fraction)
+{
+    if (!hist || !k_star) return fail(nullptr, SOP_EINVAL, "sop_layer_shift: NULL argument");
+    if (n_blocks < 1) return fail(nullptr, SOP_EINVAL, "sop_layer_shift: n_blocks must be positive");
+    FmtRange r;
+    if (!resolve_fmt(fmt, r)) return fail(nullptr, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15, valid bias and max_code");
+    // block scale m * 2^e (1/2 <= m < 1) times 2^k lies in [lo, hi = m_top * 2^e_top] exactly when
+    //   e + k >= e_lo  and  ( e + k < e_top  or  ( e + k == e_top and m <= m_top ) )
+    int e_lo, e_top;
+    (void)std::frexp(r.lo, &e_lo);
+    (void)std::frexp((float)r.hi, &e_top);
+    const int emax = std::max(r.max_code >> r.y, 1);
+    long long best_count = -1;
+    int best_k = 0;
+    for (int mag = 0; mag <= 64; ++mag) {
+        for (int sgn = 0; sgn < 2; ++sgn) {             // candidates by |k|, the non-negative one first
+            if (mag == 0 && sgn == 1) continue;
+            const int k = sgn ? -mag : mag;
+            // the shifts sop_pair_search() accepts for this format
+            if (1 - r.bias - r.y - k < -126 || 1 - r.bias - k > 126 || emax - r.bias - k > 125) continue;
+            long long count = 0;
+            for (int b = 0; b < SOP_K_FL_BINS; ++b) {
+                const int e = b - 160 + k;
+                if (e < e_lo || e > e_top) continue;
+                count += hist[b];
+                if (e == e_top) count -= hist[SOP_K_FL_BINS + b];
+            }
+            if (count > best_count) { best_count = count; best_k = k; }
+        }
+    }
+    *k_star = best_k;
+    if (fraction) *fraction = (double)best_count / (double)n_blocks;
     return SOP_OK;
 }

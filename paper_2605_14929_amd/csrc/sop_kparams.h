@@ -105,4 +105,18 @@ struct DdParams {
     unsigned int* done;              // workgroups finished
     long long* hist;                 // [n_bins] output
 };
+
+/* Statistics pass of the per-layer scale shift */
+#define SOP_K_FL_THREADS 256
+#define SOP_K_FL_BINS 320            /* binary exponents -160 .. 159 of sc = m * 2^e, 1/2 <= m < 1 */
+struct FlParams {
+    const void* W;
+    long long M, K, ldw;
+    long long strips, total_units, n_waves;
+    float t_pos, t_neg;              // endpoints t+ and -t- of the codebook
+    float m_top;                     // m of the scale format's largest value
+    unsigned long long* acc;         // [2 * SOP_K_FL_BINS] running counts (zero between calls)
+    unsigned int* done;
+    long long* hist;                 // [2][SOP_K_FL_BINS] output
+};
 #endif
