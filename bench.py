@@ -116,6 +116,61 @@ def bench_dd(args):
     print(json.dumps(result))
 
 
+def bench_fl(args):
+    """Statistics pass of the per-layer scale shift on the headline layer: every weight is read once,
+    one counter update per block."""
+    import numpy as np
+    import torch
+    import paper_2605_14929_amd as sop
+    import sop_inputs as si
+    W, c, cfg = si.make_config("C3_down")
+    M, K, g = cfg["M"], cfg["K"], cfg["g"]
+    fmt = sop.fmt_by_name(cfg["fmt"])
+    dev = torch.device("cuda", 0)
+    w0 = torch.from_numpy(W).to(dev).to(torch.bfloat16)
+    bufs = [w0] + [torch.roll(w0, shifts=17 * i, dims=0).contiguous() for i in range(1, args.buffers)]
+    ctx = sop.Context(0)
+    for i in range(args.warmup):
+        ctx.scale_histogram(bufs[i % len(bufs)], g, 1.0, 1.0, fmt)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        hist = ctx.scale_histogram(bufs[i % len(bufs)], g, 1.0, 1.0, fmt)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
+    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    alg_bytes = M * K * 2 + 640 * 8
+    result = {
+        "metric": "blocks scanned/sec", "value": M * K // g / (ms_step * 1e-3), "unit": "blocks/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "block-scale exponent histogram of the C3 down-projection 4096x11008 bf16, g=16, UE4M4, unit endpoints",
+                   "M": M, "K": K, "g": g},
+        "layer_latency_ms": ev_ms,
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel": "sopk::scale_hist_kernel", "event_ms_per_launch": ev_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import flayer as FL
+        t0 = time.perf_counter()
+        sc = FL.block_scales(W, g, 1.0, 1.0)
+        ref = FL.exponent_histogram(sc, fmt.exp_bits, fmt.man_bits, fmt.bias, fmt.max_code)
+        k_ref = FL.layer_shift(sc, fmt.exp_bits, fmt.man_bits, fmt.bias, fmt.max_code)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": M * K // g / dt, "unit": "blocks/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the whole layer, numpy on one core (scales, histogram and the search over k), {dt:.2f} s wall"}
+        chk = ctx.scale_histogram(bufs[0], g, 1.0, 1.0, fmt)
+        torch.cuda.synchronize()
+        h = chk.cpu().numpy()
+        result["parity_in_run"] = {"histogram_equal": bool(np.array_equal(h, ref)),
+                                   "k_star": sop.sop_layer_shift(h, M * K // g, fmt)[0], "k_star_oracle": k_ref[0]}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,9 +178,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram"],
+    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram"],
                     help="pair_search (default): the headline six-atom search; dd_histogram: the statistics pass of the "
-                         "data-derived codebook on the same layer")
+                         "data-derived codebook on the same layer; scale_histogram: the statistics pass of the per-layer "
+                         "scale shift on the same layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (1 GiB read, 1 GiB written) a few times: the "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -141,6 +197,8 @@ def main():
 
     if args.workload == "dd_histogram":
         return bench_dd(args)
+    if args.workload == "scale_histogram":
+        return bench_fl(args)
 
     W, c, cfg = si.make_config("C3_down")
     M, K, g = cfg["M"], cfg["K"], cfg["g"]

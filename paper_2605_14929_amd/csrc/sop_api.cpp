@@ -717,7 +717,7 @@ extern "C" sop_status sop_scale_histogram(sop_ctx* c, const void* W, sop_dtype d
     FmtRange r;
     if (!resolve_fmt(fmt, r)) return fail(c, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15, valid bias and max_code");
     if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
-    const int epl = g < 16 ? g : 16;
+    const int epl = dtype == SOP_BF16 ? 8 : 4;            // 16 bytes per lane and step
     FlParams p;
     std::memset(&p, 0, sizeof(p));
     p.W = W; p.M = M; p.K = K; p.ldw = ldw;

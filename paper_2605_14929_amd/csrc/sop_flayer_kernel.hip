@@ -31,59 +31,86 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
     const long long wave = (long long)blockIdx.x * (SOP_K_FL_THREADS / 64) + wv;
     const long long u0 = p.total_units * wave / p.n_waves;
     const long long u1 = p.total_units * (wave + 1) / p.n_waves;
-    long long strip = u0 / p.M;
-    long long m = u0 - strip * p.M;
-
-    // two rows in flight per wavefront: the next row is requested before the current one is used
-    auto load = [&](long long st, long long row, uint4 (&raw)[BF16 ? EPL / 8 : EPL / 4]) {
+    // row-major order: a wavefront's steps and neighbouring wavefronts cover consecutive memory.
+    // Steps are taken four at a time and the next four are requested before the current four are
+    // used, so that a wavefront keeps up to 8 KiB in flight (one load in flight per wavefront leaves
+    // the memory system three quarters idle).
+    constexpr int NV = BF16 ? EPL / 8 : EPL / 4;     // 16-byte pieces per lane and step
+    constexpr int UNR = 4;
+    auto load = [&](long long u, uint4 (&raw)[NV], bool& valid) {
+        const long long row = u / p.strips, st = u - row * p.strips;
         const long long col0 = (st * 64 + lane) * EPL;
-        const bool valid = col0 < p.K;
+        valid = u < u1 && col0 < p.K;
         const char* src = reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4);
 #pragma unroll
-        for (int i = 0; i < (BF16 ? EPL / 8 : EPL / 4); ++i)
-            raw[i] = valid ? reinterpret_cast<const uint4*>(src)[i] : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < NV; ++i) raw[i] = valid ? reinterpret_cast<const uint4*>(src)[i] : make_uint4(0, 0, 0, 0);
     };
-    uint4 nxt[BF16 ? EPL / 8 : EPL / 4];
-    if (u0 < u1) load(strip, m, nxt);
+    uint4 nxt[UNR][NV];
+    bool nxt_valid[UNR];
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) load(u0 + j, nxt[j], nxt_valid[j]);
 
-    for (long long u = u0; u < u1; ++u) {
-        const bool valid = (strip * 64 + lane) * EPL < p.K;
-        float w[EPL];
-        if (BF16) {
+    for (long long ub = u0; ub < u1; ub += UNR) {
+        uint4 cur[UNR][NV];
+        bool cur_valid[UNR];
 #pragma unroll
-            for (int i = 0; i < EPL / 8; ++i) {
-                const uint32_t v[4] = {nxt[i].x, nxt[i].y, nxt[i].z, nxt[i].w};
+        for (int j = 0; j < UNR; ++j) {
+            cur_valid[j] = nxt_valid[j];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    w[8 * i + 2 * j] = __uint_as_float(v[j] << 16);
-                    w[8 * i + 2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u);
+            for (int i = 0; i < NV; ++i) cur[j][i] = nxt[j][i];
+        }
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) load(ub + UNR + j, nxt[j], nxt_valid[j]);
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const bool valid = cur_valid[j];
+            float w[EPL];
+            if (BF16) {
+#pragma unroll
+                for (int i = 0; i < EPL / 8; ++i) {
+                    const uint32_t v[4] = {cur[j][i].x, cur[j][i].y, cur[j][i].z, cur[j][i].w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        w[8 * i + 2 * q] = __uint_as_float(v[q] << 16);
+                        w[8 * i + 2 * q + 1] = __uint_as_float(v[q] & 0xFFFF0000u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPL / 4; ++i) {
+                    w[4 * i] = __uint_as_float(cur[j][i].x); w[4 * i + 1] = __uint_as_float(cur[j][i].y);
+                    w[4 * i + 2] = __uint_as_float(cur[j][i].z); w[4 * i + 3] = __uint_as_float(cur[j][i].w);
                 }
             }
-        } else {
+            float pmax = 0.0f, nmin = 0.0f;
 #pragma unroll
-            for (int i = 0; i < EPL / 4; ++i) {
-                w[4 * i] = __uint_as_float(nxt[i].x); w[4 * i + 1] = __uint_as_float(nxt[i].y);
-                w[4 * i + 2] = __uint_as_float(nxt[i].z); w[4 * i + 3] = __uint_as_float(nxt[i].w);
+            for (int i = 0; i < EPL; i += 2) {
+                pmax = fmaxf(fmaxf(pmax, w[i]), w[i + 1]);
+                nmin = fminf(fminf(nmin, w[i]), w[i + 1]);
             }
-        }
-        if (++m == p.M) { m = 0; ++strip; }
-        if (u + 1 < u1) load(strip, m, nxt);
-
-        float pmax = 0.0f, nmin = 0.0f;
+            float nmax = -nmin;
 #pragma unroll
-        for (int i = 0; i < EPL; i += 2) {
-            pmax = fmaxf(fmaxf(pmax, w[i]), w[i + 1]);
-            nmin = fminf(fminf(nmin, w[i]), w[i + 1]);
-        }
-        float nmax = -nmin;
-        if (LPB >= 2) { pmax = fmaxf(pmax, __shfl_xor(pmax, 1, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, 1, 64)); }
-        if (LPB >= 4) { pmax = fmaxf(pmax, __shfl_xor(pmax, 2, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, 2, 64)); }
-        const float sc = fmaxf(pmax / p.t_pos, nmax / p.t_neg);
-        if (valid && (lane % LPB == 0) && sc > 0.0f && sc <= 3.4028235e38f) {   // an overflowed quotient is not counted
-            int e;
-            const float mant = frexpf(sc, &e);              // sc = mant * 2^e, 1/2 <= mant < 1 (subnormals included)
-            atomicAdd(&s_hist[e + 160], 1u);
-            if (mant > p.m_top) atomicAdd(&s_hist[SOP_K_FL_BINS + e + 160], 1u);
+            for (int st = 1; st < LPB; st <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, st, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, st, 64)); }
+            const float sc = fmaxf(pmax / p.t_pos, nmax / p.t_neg);
+            const bool counted = valid && (lane % LPB == 0) && sc > 0.0f && sc <= 3.4028235e38f;   // an overflowed quotient is not counted
+            int e = 0;
+            const float mant = frexpf(counted ? sc : 1.0f, &e);   // sc = mant * 2^e, 1/2 <= mant < 1 (subnormals included)
+            const bool above = counted && mant > p.m_top;
+            // the scales of a layer share a handful of exponents: the wavefront counts its lanes per
+            // distinct exponent with ballots and one lane adds the count (64 lanes adding to one LDS
+            // word would be served one after the other)
+            unsigned long long todo = __ballot(counted);
+            while (todo) {
+                const int first = __builtin_ctzll(todo);
+                const int e0 = __builtin_amdgcn_readlane(e, first);
+                const unsigned long long same = __ballot(counted && e == e0);
+                const unsigned long long same_above = __ballot(above && e == e0);
+                if (lane == first) {
+                    atomicAdd(&s_hist[e0 + 160], (unsigned int)__builtin_popcountll(same));
+                    if (same_above) atomicAdd(&s_hist[SOP_K_FL_BINS + e0 + 160], (unsigned int)__builtin_popcountll(same_above));
+                }
+                todo &= ~same;
+            }
         }
     }
     __syncthreads();
@@ -111,10 +138,12 @@ extern "C" hipError_t sopk_fl_launch(const FlParams* pp, int is_bf16, int g, voi
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((unsigned)(p.n_waves / (SOP_K_FL_THREADS / 64))), block(SOP_K_FL_THREADS);
 #define SOPK_FL(B, E, L) hipLaunchKernelGGL((sopk::scale_hist_kernel<B, E, L>), grid, block, 0, st, p)
+    // a lane reads 16 bytes per step (8 bf16 or 4 fp32 weights): every load instruction of a wavefront
+    // covers 1 KiB of consecutive memory; g / (weights per lane) lanes share a block
     if (is_bf16) {
-        if (g == 8) SOPK_FL(true, 8, 1); else if (g == 16) SOPK_FL(true, 16, 1); else if (g == 32) SOPK_FL(true, 16, 2); else SOPK_FL(true, 16, 4);
+        if (g == 8) SOPK_FL(true, 8, 1); else if (g == 16) SOPK_FL(true, 8, 2); else if (g == 32) SOPK_FL(true, 8, 4); else SOPK_FL(true, 8, 8);
     } else {
-        if (g == 8) SOPK_FL(false, 8, 1); else if (g == 16) SOPK_FL(false, 16, 1); else if (g == 32) SOPK_FL(false, 16, 2); else SOPK_FL(false, 16, 4);
+        if (g == 8) SOPK_FL(false, 4, 2); else if (g == 16) SOPK_FL(false, 4, 4); else if (g == 32) SOPK_FL(false, 4, 8); else SOPK_FL(false, 4, 16);
     }
 #undef SOPK_FL
     return hipGetLastError();
