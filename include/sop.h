@@ -217,6 +217,34 @@ sop_status sop_scale_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype,
  * receives the fraction reached. */
 sop_status sop_layer_shift(const int64_t* hist, int64_t n_blocks, sop_scale_fmt fmt, int* k_star, double* fraction);
 
+/* ---- layer-scope weight formats (Section "Primary Formats", paragraph "Block-scaled FP6 versus
+ * POT-scaled FP8": the baseline E4M3^0sUE8M0 is bare E4M3 weights with one power-of-two scale per
+ * layer; Appendix "Format string grammar": ^0 = layer-max scope).  The block-scaled side of that
+ * comparison is sop_pair_search() with the E2M3 grid as an atom; its layer error is the sum of the
+ * blk_err plane (sop_sum_f32). ---- */
+
+/* An ExMy weight grid: magnitudes value(q), q = 0..max_code (bias < 0: 2^(x-1)-1; max_code < 0:
+ * 2^(x+y)-1, every code finite), both signs, one zero: 2*max_code+1 values. */
+typedef struct { int exp_bits, man_bits, bias, max_code; } sop_weight_fmt;
+
+/* One scale for the whole layer by the block rule with the layer as the block: s* = max(pmax, nmax)
+ * / value(max_code), times 2^k, rounded into the scale word `sfmt` (nearest, ties to the lower
+ * code), s = value(q) * 2^-k; every weight goes to the nearest grid value of x = w / s (ties to the
+ * lower value); d = w - s*y.
+ *   out_dev    DEVICE, 4 doubles: sum c_k d^2, sum d^2, sum c_k w^2, scale code q
+ *   codes_dev  DEVICE or NULL: [M*K] uint16 index of every weight's value in the ascending grid
+ *   c_dev      DEVICE or NULL (c = 1); K must be a multiple of 8 (bf16) or 4 (fp32)
+ * The products and the sums over the 8 (bf16) or 4 (fp32) weights a lane reads at a time are
+ * binary32; these enter binary64 sums in an order fixed by the GPU's size (reproducible on one GPU;
+ * within about 1e-7 relative of the exact sums).  Asynchronous; no workspace; calls on
+ * one context must not overlap on the GPU. */
+sop_status sop_layer_scope_error(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                 const float* c_dev, sop_weight_fmt wfmt, sop_scale_fmt sfmt, int layer_shift_k,
+                                 double* out_dev, uint16_t* codes_dev, void* hip_stream);
+
+/* out_dev[0] = sum of the n binary32 values at x_dev, accumulated in binary64 in a fixed order. */
+sop_status sop_sum_f32(sop_ctx* ctx, const float* x_dev, int64_t n, double* out_dev, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,7 +5,7 @@ it, marshals arguments and hands PyTorch device pointers and streams across the 
 There is no CPU fallback: importing works anywhere, calling needs the built library and a GPU.
 """
 from .binding import (  # noqa: F401
-    SopError, lib, lib_path, Context, ScaleFmt, Outputs,
+    SopError, lib, lib_path, Context, ScaleFmt, WeightFmt, Outputs,
     sop_check_alphabet, sop_atom_nf, sop_atom_sh, sop_atom_negate, sop_atom_bof, sop_lloyd_1d, sop_dd_fit, sop_layer_shift,
     F32, BF16, SEL_WSE, SEL_COS, SEL_MSE, fmt_by_name, build_alphabet,
 )

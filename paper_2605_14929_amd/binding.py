@@ -26,6 +26,11 @@ class ScaleFmt(C.Structure):
                 ("bias", C.c_int), ("max_code", C.c_int)]
 
 
+class WeightFmt(C.Structure):
+    """sop_weight_fmt: ExMy weight grid."""
+    _fields_ = [("exp_bits", C.c_int), ("man_bits", C.c_int), ("bias", C.c_int), ("max_code", C.c_int)]
+
+
 class _Atom(C.Structure):
     _fields_ = [("n_entries", C.c_int), ("values", C.POINTER(C.c_float))]
 
@@ -75,6 +80,9 @@ def lib():
         L.sop_dd_fit.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.sop_scale_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_float,
                                           ScaleFmt, C.c_void_p, C.c_void_p]
+        L.sop_layer_scope_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, WeightFmt, ScaleFmt,
+                                            C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sop_sum_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.sop_layer_shift.argtypes = [C.POINTER(C.c_int64), C.c_int64, ScaleFmt, C.POINTER(C.c_int), C.POINTER(C.c_double)]
         _lib = L
     return _lib
@@ -272,6 +280,35 @@ class Context:
             o.blk_cos = torch.empty((A, Nb), dtype=torch.float32, device=dev)
             o.blk_err = torch.empty((A, Nb), dtype=torch.float32, device=dev)
         return o
+
+    def layer_scope_error(self, W, c, wfmt: WeightFmt, sfmt: ScaleFmt, k: int = 0, want_codes: bool = False, stream=None):
+        """sop_layer_scope_error on torch CUDA tensors; returns (out [4] float64 device tensor, codes or None)."""
+        import torch
+        if not W.is_cuda or (c is not None and not c.is_cuda):
+            raise SopError(1, "W and c must be CUDA tensors (no CPU fallback)")
+        if W.dim() != 2 or W.stride(1) != 1:
+            raise SopError(2, "W must be a 2-D tensor with contiguous rows")
+        dt = BF16 if W.dtype == torch.bfloat16 else (F32 if W.dtype == torch.float32 else None)
+        if dt is None:
+            raise SopError(1, "W must be float32 or bfloat16")
+        M, K = W.shape
+        out = torch.empty(4, dtype=torch.float64, device=W.device)
+        codes = torch.empty((M, K), dtype=torch.int16, device=W.device) if want_codes else None
+        st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
+        _check(lib().sop_layer_scope_error(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0),
+                                           None if c is None else C.c_void_p(c.data_ptr()), wfmt, sfmt, k, C.c_void_p(out.data_ptr()),
+                                           None if codes is None else C.c_void_p(codes.data_ptr()), C.c_void_p(st)), self._h)
+        return out, codes
+
+    def sum_f32(self, x, stream=None):
+        """sop_sum_f32 on a contiguous float32 CUDA tensor; returns a [1] float64 device tensor."""
+        import torch
+        if not x.is_cuda or x.dtype != torch.float32 or not x.is_contiguous():
+            raise SopError(1, "x must be a contiguous float32 CUDA tensor")
+        out = torch.empty(1, dtype=torch.float64, device=x.device)
+        st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
+        _check(lib().sop_sum_f32(self._h, C.c_void_p(x.data_ptr()), x.numel(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
+        return out
 
     def scale_histogram(self, W, g, t_pos: float, t_neg: float, fmt: ScaleFmt, stream=None):
         """sop_scale_histogram on a torch CUDA tensor; returns a [2, 320] int64 device tensor."""

@@ -21,6 +21,8 @@ extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric,
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
+extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
+extern "C" hipError_t sopk_sum_launch(const LsParams* p, void* stream);
 
 namespace {
 
@@ -49,6 +51,7 @@ struct sop_ctx {
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
+    unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and a finished-workgroup counter; zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned long long* d_sums = nullptr; // [SOP_K_NCOL] layer sums + (one word further) the finished-workgroup counter; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
@@ -113,6 +116,12 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(histogram)");
     }
+    if ((e = hipMalloc((void**)&c->d_ls, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2))) != hipSuccess ||
+        (e = hipMemset(c->d_ls, 0, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2))) != hipSuccess) {
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); if (c->d_ls) (void)hipFree(c->d_ls);
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(partials)");
+    }
     *out = c;
     return SOP_OK;
 }
@@ -125,6 +134,7 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_bins) (void)hipFree(c->d_bins);
         if (c->d_sums) (void)hipFree(c->d_sums);
         if (c->d_ddacc) (void)hipFree(c->d_ddacc);
+        if (c->d_ls) (void)hipFree(c->d_ls);
         for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
     }
     delete c;
@@ -412,7 +422,7 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     const int max_code = fmt.max_code < 0 ? (1 << (x + y)) - 1 : fmt.max_code;
     if (max_code < 1 || max_code >= (1 << (x + y))) return fail(c, SOP_EFMT, "scale format: max_code out of range");
     if (k < -64 || k > 64) return fail(c, SOP_EFMT, "layer shift k must be within [-64, 64]");
-    if (bias < 0 || bias > 126) return fail(c, SOP_EFMT, "scale format: bias must be within [0, 126]");
+    if (bias < 0 || bias > 127) return fail(c, SOP_EFMT, "scale format: bias must be within [0, 127]");
     const int emax = max_code >> y;
     // every scale value, the subnormal quantum and every reciprocal must be normal binary32 numbers
     if (1 - bias - y - k < -126 || 1 - bias - k > 126 || std::max(emax, 1) - bias - k > 125)
@@ -695,7 +705,7 @@ bool resolve_fmt(const sop_scale_fmt& fmt, FmtRange& r)
     r.x = x; r.y = y;
     r.bias = fmt.bias < 0 ? (1 << (x - 1)) - 1 : fmt.bias;
     r.max_code = fmt.max_code < 0 ? (1 << (x + y)) - 1 : fmt.max_code;
-    if (r.max_code < 1 || r.max_code >= (1 << (x + y)) || r.bias < 0 || r.bias > 126) return false;
+    if (r.max_code < 1 || r.max_code >= (1 << (x + y)) || r.bias < 0 || r.bias > 127) return false;
     const int e = r.max_code >> y, f = r.max_code & ((1 << y) - 1);
     r.lo = std::ldexp(1.0, 1 - r.bias);
     r.hi = e == 0 ? std::ldexp((double)f, 1 - r.bias - y) : std::ldexp((double)((1 << y) + f), e - r.bias - y);
@@ -771,5 +781,69 @@ extern "C" sop_status sop_layer_shift(const int64_t* hist, int64_t n_blocks, sop
     }
     *k_star = best_k;
     if (fraction) *fraction = (double)best_count / (double)n_blocks;
+    return SOP_OK;
+}
+
+// ------------------------------------------------------------------ layer-scope weight formats
+extern "C" sop_status sop_layer_scope_error(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw, const float* cn,
+                                            sop_weight_fmt wfmt, sop_scale_fmt sfmt, int k, double* out, uint16_t* codes, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!W || !out) return fail(c, SOP_EINVAL, "sop_layer_scope_error: W and out must not be NULL");
+    if (dtype != SOP_F32 && dtype != SOP_BF16) return fail(c, SOP_EINVAL, "sop_layer_scope_error: dtype must be SOP_F32 or SOP_BF16");
+    if (M <= 0 || K <= 0) return fail(c, SOP_ESHAPE, "M and K must be positive");
+    const int epl = dtype == SOP_BF16 ? 8 : 4, esz = dtype == SOP_BF16 ? 2 : 4;
+    if (K % epl != 0) return fail(c, SOP_ESHAPE, "K must be a multiple of 16 bytes of weights");
+    if (ldw < K) return fail(c, SOP_ESHAPE, "ldw must be at least K");
+    if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
+    if (cn && !aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(out) & 7u) || (codes && (reinterpret_cast<uintptr_t>(codes) & 3u))) return fail(c, SOP_EINVAL, "out must be 8-byte aligned, codes 4-byte aligned");
+    FmtRange rs, rw;
+    if (!resolve_fmt(sfmt, rs)) return fail(c, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15, valid bias and max_code");
+    sop_scale_fmt wf = {0, wfmt.exp_bits, wfmt.man_bits, 0, wfmt.bias, wfmt.max_code};
+    if (!resolve_fmt(wf, rw)) return fail(c, SOP_EFMT, "weight format: need 1<=x<=8, 0<=y<=10, x+y<=15, valid bias and max_code");
+    if (k < -64 || k > 64) return fail(c, SOP_EFMT, "layer shift k must be within [-64, 64]");
+    const int semax = std::max(rs.max_code >> rs.y, 1), wemax = std::max(rw.max_code >> rw.y, 1);
+    if (1 - rs.bias - rs.y - k < -126 || 1 - rs.bias - k > 126 || semax - rs.bias - k > 125)
+        return fail(c, SOP_EFMT, "scale format with this layer shift leaves binary32's normal range");
+    if (1 - rw.bias - rw.y < -126 || wemax - rw.bias > 125) return fail(c, SOP_EFMT, "weight format leaves binary32's normal range");
+    LsParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.W = W; p.c = cn; p.M = M; p.K = K; p.ldw = ldw;
+    p.strips = (K / epl + 63) / 64;
+    p.total_units = p.strips * M;
+    long long wg = std::min<long long>(std::min<long long>((long long)c->n_cu * 8, SOP_K_LS_MAXWG), (p.total_units + 3) / 4);
+    p.n_waves = std::max<long long>(wg, 1) * 4;
+    p.w_man = rw.y; p.w_bias = rw.bias; p.w_max_code = rw.max_code;
+    p.s_man = rs.y; p.s_bias = rs.bias; p.s_max_code = rs.max_code;
+    p.k = k; p.pow2k = std::ldexp(1.0f, k);
+    p.part = c->d_ls;
+    p.maxbits = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG);
+    p.done = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG + 1);
+    p.out = out; p.codes = codes;
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_ls_launch(&p, dtype == SOP_BF16, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_sum_f32(sop_ctx* c, const float* x, int64_t n, double* out, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!x || !out || n < 1) return fail(c, SOP_EINVAL, "sop_sum_f32: x and out must not be NULL, n positive");
+    if ((reinterpret_cast<uintptr_t>(x) & 3u) || (reinterpret_cast<uintptr_t>(out) & 7u)) return fail(c, SOP_EINVAL, "sop_sum_f32: misaligned pointer");
+    LsParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.W = x; p.total_units = n;
+    long long wg = std::min<long long>(std::min<long long>((long long)c->n_cu * 8, SOP_K_LS_MAXWG), (n + 255) / 256);
+    p.n_waves = std::max<long long>(wg, 1) * 4;
+    p.part = c->d_ls;
+    p.done = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG + 1);
+    p.out = out;
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_sum_launch(&p, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }

@@ -119,4 +119,22 @@ struct FlParams {
     unsigned int* done;
     long long* hist;                 // [2][SOP_K_FL_BINS] output
 };
+
+/* Layer-scope weight formats and the binary64 sum */
+#define SOP_K_LS_MAXWG 2048
+struct LsParams {
+    const void*  W;                  // weights (or the binary32 array of the sum kernel)
+    const float* c;                  // null: c = 1
+    long long M, K, ldw;
+    long long strips, total_units, n_waves;   // sum kernel: total_units = number of elements
+    int w_man, w_bias, w_max_code;   // weight grid ExMy
+    int s_man, s_bias, s_max_code;   // scale word
+    int k;
+    float pow2k;
+    unsigned int* maxbits;           // [2] bit patterns of the largest positive / negative weight (zero between calls)
+    unsigned long long* part;        // [SOP_K_LS_MAXWG][3] workgroup partials (bit patterns of doubles)
+    unsigned int* done;
+    double* out;                     // [4] weighted error, plain error, ||W||_c^2, scale code   (sum kernel: [1])
+    uint16_t* codes;                 // optional [M*K] index into the ascending signed grid
+};
 #endif

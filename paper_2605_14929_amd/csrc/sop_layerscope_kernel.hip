@@ -1,0 +1,233 @@
+// Layer-scope floating-point weight formats: one scale for the whole layer, weights rounded to an
+// ExMy grid, reconstruction error out.  Three kernels:
+//   layer_max_kernel    largest positive and largest negative weight of the layer (integer atomic
+//                       max on the bit patterns: order-independent)
+//   layer_scope_kernel  scale from those maxima exactly as for a block (absmax rule against the grid's
+//                       end values, times 2^k, nearest scale-word value with ties to the lower code),
+//                       then per weight x = fl(w*r), nearest grid value with ties to the lower value by
+//                       arithmetic on the bit pattern, d = fma(-s, y, w), sums of c*d^2, d^2 and c*w^2
+//   sum_kernel          sum of a binary32 array in binary64 (used for the per-block error plane of a
+//                       block-scaled format)
+// Sums: per lane binary32 within a step, binary64 across steps, lanes and wavefronts; every
+// workgroup hands its binary64 partial over through an atomic exchange and the workgroup that
+// finishes last adds the partials in workgroup order: the result is reproducible for a given GPU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sop_kparams.h"
+
+namespace sopk {
+
+// nearest code of a non-negative binary32 in an ExMy grid (every code finite, subnormals kept);
+// ties go to the lower code, or to the upper one when tie_up; saturating at max_code
+__device__ __forceinline__ int exmy_encode(float a, int y, int bias, int max_code, bool tie_up)
+{
+    const uint32_t u = __float_as_uint(a);
+    const int E = (int)(u >> 23);
+    const uint32_t dn = tie_up ? 0u : 1u;
+    const uint32_t ut = u - ((uint32_t)(127 - bias) << 23);
+    uint32_t q = (ut + ((1u << (22 - y)) - dn)) >> (23 - y);
+    if (E < 128 - bias) {                              // below the smallest normal value: quantum 2^(1-bias-y)
+        const int Ee = E > 0 ? E : 1;
+        const uint32_t m = (u & 0x7FFFFFu) | (E > 0 ? 0x800000u : 0u);
+        int S = 151 - bias - y - Ee;
+        S = S > 31 ? 31 : S;
+        q = (m + ((1u << (S - 1)) - dn)) >> S;
+    }
+    return (int)(q > (uint32_t)max_code ? (uint32_t)max_code : q);
+}
+
+// value(q) * 2^-k
+__device__ __forceinline__ float exmy_decode(int q, int y, int bias, int k)
+{
+    const int e = q >> y, f = q & ((1 << y) - 1);
+    const float nrm = __uint_as_float(((uint32_t)(e - bias - k + 127) << 23) | ((uint32_t)f << (23 - y)));
+    const float sub = (float)f * __uint_as_float((uint32_t)(1 - bias - y - k + 127) << 23);
+    return e > 0 ? nrm : sub;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int st = 1; st < 64; st <<= 1) v += __shfl_xor(v, st, 64);
+    return v;
+}
+
+// hands NV binary64 partials of this workgroup over and, in the last workgroup, adds all workgroups'
+// partials in order into out[0..NV).  Returns true in the last workgroup.  s_buf: LDS, >= 4*NV + 1 doubles.
+template <int NV>
+__device__ __forceinline__ bool finish_sums(const double (&v)[NV], unsigned long long* part, unsigned int* done, double* out, double* s_buf)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const double t = wave_sum_f64(v[i]);
+        if (lane == 0) s_buf[wv * NV + i] = t;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < NV) {
+        const int i = threadIdx.x;
+        const double t = (s_buf[i] + s_buf[NV + i]) + (s_buf[2 * NV + i] + s_buf[3 * NV + i]);
+        // an atomic exchange (not a plain store): it completes at the memory side, where the last
+        // workgroup's atomic reads find it
+        const unsigned long long before = atomicExch(part + (long long)blockIdx.x * NV + i, (unsigned long long)__double_as_longlong(t));
+        asm volatile("" :: "v"(before) : "memory");
+    }
+    __syncthreads();
+    unsigned int* s_flag = reinterpret_cast<unsigned int*>(s_buf + 4 * NV);
+    if (threadIdx.x == 0) *s_flag = atomicAdd(done, 1u) == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!*s_flag) return false;
+    if ((int)threadIdx.x < NV) {
+        double t = 0.0;
+        for (unsigned int g = 0; g < gridDim.x; ++g)
+            t += __longlong_as_double((long long)__hip_atomic_load(part + (long long)g * NV + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        out[threadIdx.x] = t;
+    }
+    if (threadIdx.x == 255) atomicExch(done, 0u);
+    return true;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
+{
+    constexpr int EPL = BF16 ? 8 : 4;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long wave = (long long)blockIdx.x * 4 + wv;
+    const long long u0 = p.total_units * wave / p.n_waves, u1 = p.total_units * (wave + 1) / p.n_waves;
+    float pmax = 0.0f, nmin = 0.0f;
+    for (long long u = u0; u < u1; ++u) {
+        const long long row = u / p.strips, st = u - row * p.strips;
+        const long long col0 = (st * 64 + lane) * EPL;
+        if (col0 < p.K) {
+            const uint4 t = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4));
+            const uint32_t v[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float a = BF16 ? __uint_as_float(v[j] << 16) : __uint_as_float(v[j]);
+                const float b = BF16 ? __uint_as_float(v[j] & 0xFFFF0000u) : a;
+                pmax = fmaxf(fmaxf(pmax, a), b);
+                nmin = fminf(fminf(nmin, a), b);
+            }
+        }
+    }
+    float nmax = -nmin;
+#pragma unroll
+    for (int st = 1; st < 64; st <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, st, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, st, 64)); }
+    if (lane == 0) {                                   // non-negative floats order like their bit patterns
+        atomicMax(p.maxbits, __float_as_uint(pmax));
+        atomicMax(p.maxbits + 1, __float_as_uint(nmax));
+    }
+}
+
+template <bool BF16, bool CODES>
+__global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
+{
+    __shared__ double s_buf[4 * 3 + 1];
+    constexpr int EPL = BF16 ? 8 : 4;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long wave = (long long)blockIdx.x * 4 + wv;
+    const long long u0 = p.total_units * wave / p.n_waves, u1 = p.total_units * (wave + 1) / p.n_waves;
+
+    // ---- the layer's scale: the block rule with the whole layer as the block ----
+    const float pmax = __uint_as_float(__hip_atomic_load(p.maxbits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const float nmax = __uint_as_float(__hip_atomic_load(p.maxbits + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const float tp = exmy_decode(p.w_max_code, p.w_man, p.w_bias, 0);            // the grid is symmetric: t+ = -t-
+    const float sstar = fmaxf(pmax / tp, nmax / tp);
+    const int q = exmy_encode(sstar * p.pow2k, p.s_man, p.s_bias, p.s_max_code, false);
+    const float s = exmy_decode(q, p.s_man, p.s_bias, p.k);
+    const float r = s > 0.0f ? 1.0f / s : 0.0f;
+
+    double acc_w = 0.0, acc_u = 0.0, acc_n = 0.0;
+    for (long long u = u0; u < u1; ++u) {
+        const long long row = u / p.strips, st = u - row * p.strips;
+        const long long col0 = (st * 64 + lane) * EPL;
+        if (col0 >= p.K) continue;
+        const uint4 t = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4));
+        const uint32_t v[4] = {t.x, t.y, t.z, t.w};
+        float w[EPL], c[EPL];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (BF16) { w[2 * j] = __uint_as_float(v[j] << 16); w[2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u); }
+            else w[j] = __uint_as_float(v[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < EPL; j += 4) {
+            float4 cc = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (p.c) cc = *reinterpret_cast<const float4*>(p.c + col0 + j);
+            c[j] = cc.x; c[j + 1] = cc.y; c[j + 2] = cc.z; c[j + 3] = cc.w;
+        }
+        float ew = 0.0f, eu = 0.0f, wn = 0.0f;
+        uint32_t packed[EPL / 2];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const float x = w[j] * r;
+            const bool negv = x < 0.0f;
+            // nearest grid value, ties to the lower value: for a negative x that is the larger magnitude
+            const int m = exmy_encode(fabsf(x), p.w_man, p.w_bias, p.w_max_code, negv);
+            const float ym = exmy_decode(m, p.w_man, p.w_bias, 0);
+            const float y = negv ? -ym : ym;
+            const float d = __fmaf_rn(-s, y, w[j]);
+            const float cd = c[j] * d;
+            ew = __fmaf_rn(cd, d, ew);
+            eu = __fmaf_rn(d, d, eu);
+            wn = __fmaf_rn(c[j] * w[j], w[j], wn);
+            if (CODES) {
+                const uint32_t idx = (uint32_t)(negv ? p.w_max_code - m : p.w_max_code + m);   // index in the ascending signed grid
+                if (j % 2 == 0) packed[j / 2] = idx; else packed[j / 2] |= idx << 16;
+            }
+        }
+        acc_w += (double)ew; acc_u += (double)eu; acc_n += (double)wn;
+        if (CODES) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(p.codes + row * p.K + col0);
+#pragma unroll
+            for (int j = 0; j < EPL / 2; ++j) dst[j] = packed[j];
+        }
+    }
+    const double v3[3] = {acc_w, acc_u, acc_n};
+    if (finish_sums<3>(v3, p.part, p.done, p.out, s_buf)) {
+        if (threadIdx.x == 0) p.out[3] = (double)q;
+        if (threadIdx.x == 1) { atomicExch(p.maxbits, 0u); atomicExch(p.maxbits + 1, 0u); }   // zero for the next call
+    }
+}
+
+__global__ __launch_bounds__(256) void sum_kernel(const LsParams p)
+{
+    __shared__ double s_buf[4 * 1 + 1];
+    const float* x = reinterpret_cast<const float*>(p.W);
+    const long long n = p.total_units;                 // elements
+    const long long per = (n + gridDim.x - 1) / gridDim.x;
+    const long long b0 = (long long)blockIdx.x * per, b1 = b0 + per < n ? b0 + per : n;
+    double acc = 0.0;
+    for (long long i = b0 + threadIdx.x; i < b1; i += 256) acc += (double)x[i];
+    const double v1[1] = {acc};
+    finish_sums<1>(v1, p.part, p.done, p.out, s_buf);
+}
+
+}  // namespace sopk
+
+extern "C" hipError_t sopk_ls_launch(const LsParams* pp, int is_bf16, void* stream)
+{
+    LsParams p = *pp;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)(p.n_waves / 4)), block(256);
+    if (is_bf16) hipLaunchKernelGGL(sopk::layer_max_kernel<true>, grid, block, 0, st, p);
+    else hipLaunchKernelGGL(sopk::layer_max_kernel<false>, grid, block, 0, st, p);
+    if (is_bf16) {
+        if (p.codes) hipLaunchKernelGGL((sopk::layer_scope_kernel<true, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((sopk::layer_scope_kernel<true, false>), grid, block, 0, st, p);
+    } else {
+        if (p.codes) hipLaunchKernelGGL((sopk::layer_scope_kernel<false, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((sopk::layer_scope_kernel<false, false>), grid, block, 0, st, p);
+    }
+    return hipGetLastError();
+}
+
+extern "C" hipError_t sopk_sum_launch(const LsParams* pp, void* stream)
+{
+    LsParams p = *pp;
+    hipLaunchKernelGGL(sopk::sum_kernel, dim3((unsigned)(p.n_waves / 4)), dim3(256), 0, (hipStream_t)stream, p);
+    return hipGetLastError();
+}
