@@ -171,6 +171,60 @@ def bench_fl(args):
     print(json.dumps(result))
 
 
+def bench_ls(args):
+    """Layer-scope FP8 baseline (E4M3 weights, one power-of-two scale per layer) on the headline layer:
+    one pass for the layer maxima, one pass rounding every weight and summing the errors."""
+    import numpy as np
+    import torch
+    import paper_2605_14929_amd as sop
+    import sop_inputs as si
+    W, c, cfg = si.make_config("C3_down")
+    M, K = cfg["M"], cfg["K"]
+    wf, sf = sop.WeightFmt(4, 3, -1, -1), sop.ScaleFmt(0, 8, 0, 8, 127, 252)
+    dev = torch.device("cuda", 0)
+    w0 = torch.from_numpy(W).to(dev).to(torch.bfloat16)
+    bufs = [w0] + [torch.roll(w0, shifts=17 * i, dims=0).contiguous() for i in range(1, args.buffers)]
+    ct = torch.from_numpy(c).to(dev)
+    ctx = sop.Context(0)
+    for i in range(args.warmup):
+        ctx.layer_scope_error(bufs[i % len(bufs)], ct, wf, sf)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        out, _ = ctx.layer_scope_error(bufs[i % len(bufs)], ct, wf, sf)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
+    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    alg_bytes = 2 * (M * K * 2) + K * 4 + 32                        # the layer is read twice: maxima, then rounding
+    result = {
+        "metric": "weights rounded/sec", "value": M * K / (ms_step * 1e-3), "unit": "weights/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "E4M3^0sUE8M0 reconstruction error of the C3 down-projection 4096x11008 bf16 (layer maxima pass + rounding pass)",
+                   "M": M, "K": K},
+        "layer_latency_ms": ev_ms,
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel": "sopk::layer_max_kernel + sopk::layer_scope_kernel",
+                     "event_ms_per_launch": ev_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import layerscope as LS, pairsearch as ops
+        t0 = time.perf_counter()
+        ref = LS.layer_scope(W, c, LS.exmy_table(4, 3), ops.make_fmt(0, 8, 0, 8, 127, 252))
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": M * K / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the whole layer, numpy on one core, {dt:.2f} s wall"}
+        chk, _ = ctx.layer_scope_error(bufs[0], ct, wf, sf)
+        torch.cuda.synchronize()
+        o = chk.cpu().numpy()
+        result["parity_in_run"] = {"scale_code_equal": int(o[3]) == ref["q"], "rel_err_weighted_error": abs(o[0] - ref["err_w"]) / ref["err_w"]}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -178,10 +232,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram"],
+    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope"],
                     help="pair_search (default): the headline six-atom search; dd_histogram: the statistics pass of the "
                          "data-derived codebook on the same layer; scale_histogram: the statistics pass of the per-layer "
-                         "scale shift on the same layer")
+                         "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (1 GiB read, 1 GiB written) a few times: the "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -199,6 +253,8 @@ def main():
         return bench_dd(args)
     if args.workload == "scale_histogram":
         return bench_fl(args)
+    if args.workload == "layer_scope":
+        return bench_ls(args)
 
     W, c, cfg = si.make_config("C3_down")
     M, K, g = cfg["M"], cfg["K"], cfg["g"]

@@ -53,7 +53,7 @@ struct sop_ctx {
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
     unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and a finished-workgroup counter; zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
-    unsigned long long* d_sums = nullptr; // [SOP_K_NCOL] layer sums + (one word further) the finished-workgroup counter; zero between calls
+    unsigned long long* d_sums = nullptr; // [SOP_K_REPL][SOP_K_NCOL] layer sums, then the ticket counters; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
     size_t occ_lds[192];
@@ -104,8 +104,8 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     c->n_cu = prop.multiProcessorCount;
     if (const char* s = getenv("SOP_WAVES_PER_SIMD")) { long long v = atoll(s); if (v >= 1 && v <= 8) c->waves_override = v; }
     if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
-    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * (SOP_K_NCOL + 1))) != hipSuccess ||
-        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * (SOP_K_NCOL + 1))) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * (SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1))) != hipSuccess ||
+        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * (SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1))) != hipSuccess) {
         (void)hipFree(c->d_bins); if (c->d_sums) (void)hipFree(c->d_sums);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(layer sums)");
@@ -469,7 +469,7 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
         p.pair_pi[q] = (unsigned char)pi;
     }
     p.sums = c->d_sums;
-    p.done = reinterpret_cast<unsigned int*>(c->d_sums + SOP_K_NCOL);
+    p.done = reinterpret_cast<unsigned int*>(c->d_sums + SOP_K_REPL * SOP_K_NCOL);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
     p.acos_atom = out->acos_atom;
     p.sel_words = c->n_pairs ? out->sel_words : nullptr;
@@ -734,7 +734,7 @@ extern "C" sop_status sop_scale_histogram(sop_ctx* c, const void* W, sop_dtype d
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * M;
     const long long waves_per_wg = SOP_K_FL_THREADS / 64;
-    long long wg = std::min<long long>((long long)c->n_cu * 8, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    long long wg = std::min<long long>((long long)c->n_cu * 4, (p.total_units + waves_per_wg - 1) / waves_per_wg);
     p.n_waves = std::max<long long>(wg, 1) * waves_per_wg;
     p.t_pos = t_pos; p.t_neg = t_neg;
     int e_top;
@@ -812,7 +812,7 @@ extern "C" sop_status sop_layer_scope_error(sop_ctx* c, const void* W, sop_dtype
     p.W = W; p.c = cn; p.M = M; p.K = K; p.ldw = ldw;
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * M;
-    long long wg = std::min<long long>(std::min<long long>((long long)c->n_cu * 8, SOP_K_LS_MAXWG), (p.total_units + 3) / 4);
+    long long wg = std::min<long long>(std::min<long long>((long long)c->n_cu * 4, SOP_K_LS_MAXWG), (p.total_units + 3) / 4);
     p.n_waves = std::max<long long>(wg, 1) * 4;
     p.w_man = rw.y; p.w_bias = rw.bias; p.w_max_code = rw.max_code;
     p.s_man = rs.y; p.s_bias = rs.bias; p.s_max_code = rs.max_code;
@@ -836,7 +836,7 @@ extern "C" sop_status sop_sum_f32(sop_ctx* c, const float* x, int64_t n, double*
     LsParams p;
     std::memset(&p, 0, sizeof(p));
     p.W = x; p.total_units = n;
-    long long wg = std::min<long long>(std::min<long long>((long long)c->n_cu * 8, SOP_K_LS_MAXWG), (n + 255) / 256);
+    long long wg = std::min<long long>(std::min<long long>((long long)c->n_cu * 4, SOP_K_LS_MAXWG), (n + 255) / 256);
     p.n_waves = std::max<long long>(wg, 1) * 4;
     p.part = c->d_ls;
     p.done = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG + 1);

@@ -78,11 +78,22 @@ __device__ __forceinline__ bool finish_sums(const double (&v)[NV], unsigned long
     if (threadIdx.x == 0) *s_flag = atomicAdd(done, 1u) == gridDim.x - 1 ? 1u : 0u;
     __syncthreads();
     if (!*s_flag) return false;
-    if ((int)threadIdx.x < NV) {
+    // last workgroup: every thread adds the partials of workgroups t, t+256, ... in that order, then a
+    // fixed tree over the 256 threads (s_tree: 256 doubles of LDS)
+    __shared__ double s_tree[256];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
         double t = 0.0;
-        for (unsigned int g = 0; g < gridDim.x; ++g)
-            t += __longlong_as_double((long long)__hip_atomic_load(part + (long long)g * NV + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        out[threadIdx.x] = t;
+        for (unsigned int g = threadIdx.x; g < gridDim.x; g += 256)
+            t += __longlong_as_double((long long)__hip_atomic_load(part + (long long)g * NV + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        s_tree[threadIdx.x] = t;
+        __syncthreads();
+        for (int h = 128; h >= 1; h >>= 1) {
+            if ((int)threadIdx.x < h) s_tree[threadIdx.x] += s_tree[threadIdx.x + h];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) out[i] = s_tree[0];
+        __syncthreads();
     }
     if (threadIdx.x == 255) atomicExch(done, 0u);
     return true;
@@ -115,9 +126,16 @@ __global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
     float nmax = -nmin;
 #pragma unroll
     for (int st = 1; st < 64; st <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, st, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, st, 64)); }
-    if (lane == 0) {                                   // non-negative floats order like their bit patterns
-        atomicMax(p.maxbits, __float_as_uint(pmax));
-        atomicMax(p.maxbits + 1, __float_as_uint(nmax));
+    // workgroup maximum in LDS, then at most one atomic per workgroup and value, and only when it
+    // would raise the running maximum (atomics to one address are served one after the other, about
+    // 25 ns each: thousands of them would cost more than the pass over the layer)
+    __shared__ float s_m[2][4];
+    if (lane == 0) { s_m[0][wv] = pmax; s_m[1][wv] = nmax; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        const float v = fmaxf(fmaxf(s_m[threadIdx.x][0], s_m[threadIdx.x][1]), fmaxf(s_m[threadIdx.x][2], s_m[threadIdx.x][3]));
+        const unsigned int bits = __float_as_uint(v);          // non-negative floats order like their bit patterns
+        if (bits > __hip_atomic_load(p.maxbits + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p.maxbits + threadIdx.x, bits);
     }
 }
 

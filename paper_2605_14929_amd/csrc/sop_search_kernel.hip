@@ -637,33 +637,55 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
         const float v = (s_red[i] + s_red[SOP_K_NCOL + i]) + (s_red[2 * SOP_K_NCOL + i] + s_red[3 * SOP_K_NCOL + i]);
         // 2^32 * v is exact in binary32 and far inside the 64-bit range (a workgroup's share is < 2^20)
         if (v != 0.0f) {
-            // the returned value is consumed so that the add has completed at the memory side before
-            // this workgroup announces itself below (all traffic here is atomic: no cache write-back,
-            // which a fence would cost on every workgroup, is needed)
-            const unsigned long long before = atomicAdd(p.sums + i, (unsigned long long)__float2ll_rn(v * 4294967296.0f));
+            // Atomics to one address are served one after the other (about 20 ns each), so the sums
+            // are kept in SOP_K_REPL replicas chosen by workgroup number.  The returned value is
+            // consumed so that the add has completed at the memory side before this workgroup
+            // announces itself below (all traffic here is atomic: no cache write-back, which a fence
+            // would cost on every workgroup, is needed).
+            const unsigned long long before = atomicAdd(p.sums + (blockIdx.x % SOP_K_REPL) * SOP_K_NCOL + i,
+                                                        (unsigned long long)__float2ll_rn(v * 4294967296.0f));
             asm volatile("" :: "v"(before) : "memory");
         }
     }
-    // ---- layer reduction: the last workgroup to arrive finishes the layer ----
+    // ---- layer reduction: tickets in two levels (per replica, then over the replicas); the
+    //      workgroup that takes the very last ticket finishes the layer ----
     __syncthreads();
     unsigned int* s_flag = reinterpret_cast<unsigned int*>(s_red);
-    if (threadIdx.x == 0) *s_flag = atomicAdd(p.done, 1u) == gridDim.x - 1 ? 1u : 0u;
+    if (threadIdx.x == 0) {
+        const unsigned int r = blockIdx.x % SOP_K_REPL;
+        const unsigned int in_group = (gridDim.x - r + SOP_K_REPL - 1) / SOP_K_REPL;
+        const unsigned int groups = gridDim.x < SOP_K_REPL ? gridDim.x : SOP_K_REPL;
+        unsigned int last = 0u;
+        if (atomicAdd(p.done + 1 + r, 1u) == in_group - 1) {
+            atomicExch(p.done + 1 + r, 0u);
+            if (atomicAdd(p.done, 1u) == groups - 1) { atomicExch(p.done, 0u); last = 1u; }
+        }
+        *s_flag = last;
+    }
     __syncthreads();
     if (*s_flag) {
+        // gather the replicas (exact integer adds in LDS; the exchanges leave zeros for the next call)
+        unsigned long long* s_tot = reinterpret_cast<unsigned long long*>(s_red) + 1;
+        __syncthreads();
+        if ((int)threadIdx.x < SOP_K_NCOL) s_tot[threadIdx.x] = 0ull;
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < SOP_K_REPL * SOP_K_NCOL; idx += 256) {
+            const unsigned long long v = atomicExch(p.sums + idx, 0ull);
+            if (v) atomicAdd(&s_tot[idx % SOP_K_NCOL], v);
+        }
+        __syncthreads();
         // lanes whose block had zero weighted norm (and lanes past the end of a row) added exactly 1
         // to every column; the count column takes them out again
-        const long long z = (long long)__hip_atomic_load(p.sums + SOP_K_ZCOL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
+        const long long z = (long long)s_tot[SOP_K_ZCOL];
         const int o = threadIdx.x;                 // 0..A-1 atoms (internal order), then pairs by output index
         if (o < p.A + p.P) {
             int col;
             double* dst;
             if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + p.uidx[o] : nullptr; }
             else { col = SOP_K_MAXA + p.pair_pi[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
-            const long long t = (long long)atomicExch(p.sums + col, 0ull);
+            const long long t = (long long)s_tot[col];
             if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 4294967296.0)) / ((double)p.Nb * (double)p.lpb);
         }
-        if (threadIdx.x == 255) { atomicExch(p.sums + SOP_K_ZCOL, 0ull); atomicExch(p.done, 0u); }
     }
 }
 
