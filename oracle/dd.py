@@ -27,8 +27,10 @@ import numpy as np
 F32 = np.float32
 
 
-def histogram(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int) -> np.ndarray:
-    """[H] int64: summed integer weights of the samples of every bin."""
+def histogram(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int, block_mask: np.ndarray | None = None) -> np.ndarray:
+    """[H] int64: summed integer weights of the samples of every bin.  block_mask ([M*K/g], non-zero =
+    take the block) restricts the samples to a pool of blocks (step 3 of the pair search fits the
+    second codebook on the blocks the first one serves worst)."""
     W = np.ascontiguousarray(W, dtype=F32)
     M, K = W.shape
     assert K % g == 0
@@ -43,6 +45,8 @@ def histogram(W: np.ndarray, c: np.ndarray | None, g: int, n_bins: int) -> np.nd
         blk = W[r0:r0 + rows].reshape(-1, K // g, g)
         a = np.abs(blk).max(axis=2)                                  # exact
         live = a > 0
+        if block_mask is not None:
+            live &= np.asarray(block_mask).reshape(M, K // g)[r0:r0 + rows] != 0
         r = np.zeros_like(a)
         r[live] = F32(1.0) / a[live]                                 # fl(1 / a)
         x = (blk * r[:, :, None]).astype(F32)                        # fl(w * r)

@@ -130,3 +130,40 @@ def test_library_host_fit_equals_the_oracle_fit():
         hh[200:] = 5
         sop.sop_dd_fit(hh, 4, 5, np.array([0.55, 0.6, 0.7, 0.9], dtype=np.float32))
     assert e.value.status == 3
+
+
+def test_block_mask_equals_zeroing_the_other_blocks():
+    W, c = _layer(M=40, K=512, seed=61)
+    g = 16
+    rng = np.random.default_rng(62)
+    mask = (rng.random(40 * 512 // g) < 0.3).astype(np.uint8)
+    Wz = (W.reshape(-1, g) * mask[:, None]).reshape(W.shape).astype(np.float32)
+    h = DD.histogram(W, c, g, 512, block_mask=mask)
+    assert np.array_equal(h, DD.histogram(Wz, c, g, 512))
+    assert 0 < h.sum() < DD.histogram(W, c, g, 512).sum()
+    assert np.array_equal(DD.histogram(W, c, g, 512, block_mask=np.ones_like(mask)), DD.histogram(W, c, g, 512))
+    assert DD.histogram(W, c, g, 512, block_mask=np.zeros_like(mask)).sum() == 0
+
+
+def test_steps_one_to_four_refit_on_the_worst_blocks_helps():
+    """Step 2 ranks by block cosine under L_a, step 3 fits L_b on the rest, step 4 picks per block."""
+    from oracle import partition as PT, pairsearch as ps
+    W, c = _layer(M=64, K=1024, seed=71)
+    g = 16
+    fmt = ps.make_fmt(0, 4, 4)
+    La = OA.to_f32(OA.nf(4))
+    r1 = ps.pair_search(W, c, [La], g, fmt)
+    n_top = PT.top_count(60.0, r1.blk_cos.shape[1])
+    tau, pool_b, n_a = PT.partition(r1.blk_cos[0], n_top, True)
+    assert n_a >= n_top and pool_b.sum() == pool_b.size - n_a
+    # the fitting pool holds the blocks L_a serves worst
+    assert r1.blk_cos[0][pool_b == 1].max() < tau <= r1.blk_cos[0][pool_b == 0].min()
+    Lb = OA.to_f32(DD.fit(DD.histogram(W, c, g, 1024, block_mask=pool_b), 16, 12, OA.nf(4)))
+    r2 = ps.pair_search(W, c, [La, Lb], g, fmt)
+    assert r2.acos_pair[0] > r2.acos_atom[0] and r2.acos_pair[0] > r2.acos_atom[1]
+    # fitted on its own pool, L_b beats a fit on all blocks there (in the scale-free block cosine:
+    # the fit works on block-normalised weights, so every block counts alike)
+    Lall = OA.to_f32(DD.fit(DD.histogram(W, c, g, 1024), 16, 12, OA.nf(4)))
+    r3 = ps.pair_search(W, c, [Lb, Lall], g, fmt)
+    pool = pool_b == 1
+    assert r3.blk_cos[0][pool].mean(dtype=np.float64) > r3.blk_cos[1][pool].mean(dtype=np.float64)
