@@ -179,12 +179,14 @@ sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g,
 /* W_dev, dtype, M, K, ldw, c_dev (may be NULL), g as in sop_pair_search(); n_bins = H, a power of
  * two within 64..8192; row_step >= 1: only rows 0, row_step, 2*row_step, ... enter the histogram
  * (1 = the whole layer; the pass is bound by LDS atomics, not by HBM, so a sample of the rows is
- * the cheap way to a fit of the same quality); hist_dev: DEVICE, H 64-bit integers, overwritten.
+ * the cheap way to a fit of the same quality); block_mask_dev: DEVICE or NULL, one byte per block
+ * (index m*(K/g) + j): only blocks with a non-zero byte enter (the fitting pool of step 3 of the pair
+ * search); hist_dev: DEVICE, H 64-bit integers, overwritten.
  * Asynchronous on the stream; needs no workspace.  Calls on one context must not overlap on the
  * GPU (the context holds the running histogram). */
 sop_status sop_dd_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
-                            const float* c_dev, int g, int n_bins, int64_t row_step, int64_t* hist_dev,
-                            void* hip_stream);
+                            const float* c_dev, int g, int n_bins, int64_t row_step, const uint8_t* block_mask_dev,
+                            int64_t* hist_dev, void* hip_stream);
 
 /* Weighted Lloyd iteration on a histogram (all HOST memory): bin b stands for its centre
  * -1 + (2b+1)/H and goes, whole, to that centre's cell (cell = number of midpoints of the current
@@ -244,6 +246,46 @@ sop_status sop_layer_scope_error(sop_ctx* ctx, const void* W_dev, sop_dtype dtyp
 
 /* out_dev[0] = sum of the n binary32 values at x_dev, accumulated in binary64 in a fixed order. */
 sop_status sop_sum_f32(sop_ctx* ctx, const float* x_dev, int64_t n, double* out_dev, void* hip_stream);
+
+/* ---- block ranking and pools (Section "Per-Layer Pair Search", step 2: every block is scored
+ * against L_a under its own scale and ranked, the best-ranked p% stay with L_a; step 3: the rest is
+ * the pool L_b is fitted on; design axes (i) ranking score = block cosine or unweighted block error,
+ * (iv) pool defined by a rank). ----
+ *   score_dev   DEVICE, n_blocks binary32 scores, no NaN (a blk_cos or blk_err plane of an emitting
+ *               sop_pair_search() call), 16-byte aligned
+ *   n_top       size asked of the first pool, 0 .. n_blocks (the caller turns p% into a count)
+ *   higher_is_better  non-zero for a cosine, zero for an error
+ *   pool_b_dev  DEVICE, n_blocks bytes, 4-byte aligned: 1 = the block ranks strictly worse than tau
+ *               (fitting pool of L_b; feeds sop_dd_histogram as block mask), 0 = it stays with L_a
+ *   tau_dev     DEVICE, 1 float: the score of the block of rank n_top (+inf / -inf when n_top = 0)
+ *   n_a_dev     DEVICE, 1 int64: blocks at least as good as tau (>= n_top: blocks that tie with tau
+ *               all stay; +0 and -0 tie)
+ * Exact (integer counting), reproducible, asynchronous, no workspace; calls on one context must not
+ * overlap on the GPU. */
+sop_status sop_partition(sop_ctx* ctx, const float* score_dev, int64_t n_blocks, int64_t n_top, int higher_is_better,
+                         uint8_t* pool_b_dev, float* tau_dev, int64_t* n_a_dev, void* hip_stream);
+
+/* ---- materialisation (Section "Scale Format and Metabit Allocation", paragraphs "The SwExMy
+ * notation", "Bit placement" and "Worked examples"; Section "Per-Layer Pair Search": one metabit per
+ * block names the codebook; introduction: a block of g n-bit codes is g*n/8 bytes). ----
+ * Per block: the scale word in its container of fmt.container_bits <= 16 bits, one uint16 per block:
+ * sign at bit b-1 when fmt.sign_bits = 1; magnitude code (exponent then mantissa) above the low-end
+ * metabits; the selector in the first metabit (bit b-1 without a sign bit, bit m-1 with one, m = b -
+ * w - x - y); remaining metabits zero.  And the block's codes as a little-endian string of n-bit
+ * fields (code i in bits i*n .. i*n+n-1; n = bits needed for the larger codebook).
+ *   scale_a_dev / codes_a_dev / entries_a   one atom's plane of an emitting search: scale_code
+ *               [N_b] (bit 15 = sign) and code plane (layout as in sop_outputs.codes), 8-byte aligned
+ *   scale_b_dev / codes_b_dev / entries_b   the second atom, or NULL, NULL, 0: single codebook
+ *   sel_words_dev, sel_word_bytes, pair_q   the search's selector words (2 or 4 bytes each) and the
+ *               pair's bit; selector 1 = the block takes atom b.  NULL with a single codebook
+ *   words_dev   DEVICE, N_b uint16;   payload_dev  DEVICE, N_b * g*n/8 bytes, 8-byte aligned
+ *   n_bits_out  HOST, may be NULL: receives n
+ * SOP_EFMT when two codebooks meet a format without a metabit.  Asynchronous; no workspace. */
+sop_status sop_pack_blocks(sop_ctx* ctx, int64_t M, int64_t K, int g, sop_scale_fmt fmt,
+                           const uint16_t* scale_a_dev, const uint8_t* codes_a_dev, int entries_a,
+                           const uint16_t* scale_b_dev, const uint8_t* codes_b_dev, int entries_b,
+                           const void* sel_words_dev, int sel_word_bytes, int pair_q,
+                           uint16_t* words_dev, uint8_t* payload_dev, int* n_bits_out, void* hip_stream);
 
 #ifdef __cplusplus
 }

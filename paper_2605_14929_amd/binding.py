@@ -76,13 +76,17 @@ def lib():
         L.sop_lloyd_1d.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int64, C.POINTER(C.c_double), C.c_int, C.c_int]
         L.sop_atom_bof.argtypes = [C.c_int, C.POINTER(C.c_double), C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float)]
         L.sop_dd_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_int,
-                                       C.c_int64, C.c_void_p, C.c_void_p]
+                                       C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_dd_fit.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.sop_scale_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_float,
                                           ScaleFmt, C.c_void_p, C.c_void_p]
         L.sop_layer_scope_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, WeightFmt, ScaleFmt,
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_sum_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        L.sop_partition.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sop_pack_blocks.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, ScaleFmt, C.c_void_p, C.c_void_p, C.c_int,
+                                      C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                      C.POINTER(C.c_int), C.c_void_p]
         L.sop_layer_shift.argtypes = [C.POINTER(C.c_int64), C.c_int64, ScaleFmt, C.POINTER(C.c_int), C.POINTER(C.c_double)]
         _lib = L
     return _lib
@@ -310,6 +314,49 @@ class Context:
         _check(lib().sop_sum_f32(self._h, C.c_void_p(x.data_ptr()), x.numel(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
         return out
 
+    def partition(self, score, n_top: int, higher_is_better: bool = True, stream=None):
+        """sop_partition on a contiguous float32 CUDA tensor of per-block scores; returns device
+        tensors (pool_b [N_b] uint8, tau [1] float32, n_a [1] int64)."""
+        import torch
+        if not score.is_cuda or score.dtype != torch.float32 or not score.is_contiguous():
+            raise SopError(1, "score must be a contiguous float32 CUDA tensor")
+        n = score.numel()
+        pool_b = torch.empty(n, dtype=torch.uint8, device=score.device)
+        tau = torch.empty(1, dtype=torch.float32, device=score.device)
+        n_a = torch.empty(1, dtype=torch.int64, device=score.device)
+        st = torch.cuda.current_stream(score.device).cuda_stream if stream is None else stream
+        _check(lib().sop_partition(self._h, C.c_void_p(score.data_ptr()), n, n_top, 1 if higher_is_better else 0,
+                                   C.c_void_p(pool_b.data_ptr()), C.c_void_p(tau.data_ptr()), C.c_void_p(n_a.data_ptr()),
+                                   C.c_void_p(st)), self._h)
+        return pool_b, tau, n_a
+
+    def pack_blocks(self, out, M, K, g, fmt: ScaleFmt, a: int, b=None, pair_q: int = 0, stream=None):
+        """sop_pack_blocks on the outputs of an emitting pair_search: atom a alone (b None) or the
+        pair (a, b) with selector bit pair_q.  Returns (words [N_b] int16, payload [N_b, g*n/8] uint8, n)."""
+        import torch
+        if out.scale_code is None or out.code_planes is None:
+            raise SopError(1, "pack_blocks needs the scale codes and code planes of an emitting search")
+        two = b is not None
+        if two and out.sel_words is None:
+            raise SopError(1, "pack_blocks of a pair needs the selector words")
+        ents = self.n_entries
+        n = 1
+        while (1 << n) < (max(ents[a], ents[b]) if two else ents[a]):
+            n += 1
+        Nb = M * K // g
+        dev = out.scale_code.device
+        words = torch.empty(Nb, dtype=torch.int16, device=dev)
+        payload = torch.empty((Nb, g * n // 8), dtype=torch.uint8, device=dev)
+        nb = C.c_int(0)
+        st = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        ptr = lambda t: C.c_void_p(t.data_ptr())
+        _check(lib().sop_pack_blocks(self._h, M, K, g, fmt, ptr(out.scale_code[a]), ptr(out.code_planes[a]), ents[a],
+                                     ptr(out.scale_code[b]) if two else None, ptr(out.code_planes[b]) if two else None, ents[b] if two else 0,
+                                     ptr(out.sel_words) if two else None, out.sel_words.element_size() if two else 0, pair_q,
+                                     ptr(words), ptr(payload), C.byref(nb), C.c_void_p(st)), self._h)
+        assert nb.value == n
+        return words, payload, n
+
     def scale_histogram(self, W, g, t_pos: float, t_neg: float, fmt: ScaleFmt, stream=None):
         """sop_scale_histogram on a torch CUDA tensor; returns a [2, 320] int64 device tensor."""
         import torch
@@ -327,7 +374,7 @@ class Context:
                                          C.c_void_p(hist.data_ptr()), C.c_void_p(st)), self._h)
         return hist
 
-    def dd_histogram(self, W, c, g, n_bins: int = 1024, row_step: int = 1, stream=None):
+    def dd_histogram(self, W, c, g, n_bins: int = 1024, row_step: int = 1, block_mask=None, stream=None):
         """sop_dd_histogram on torch CUDA tensors; returns an [n_bins] int64 device tensor."""
         import torch
         if not W.is_cuda or (c is not None and not c.is_cuda):
@@ -341,8 +388,8 @@ class Context:
         hist = torch.empty(n_bins, dtype=torch.int64, device=W.device)
         st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
         _check(lib().sop_dd_histogram(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0),
-                                      None if c is None else C.c_void_p(c.data_ptr()), g, n_bins, row_step, C.c_void_p(hist.data_ptr()),
-                                      C.c_void_p(st)), self._h)
+                                      None if c is None else C.c_void_p(c.data_ptr()), g, n_bins, row_step, None if block_mask is None else C.c_void_p(block_mask.data_ptr()),
+                                      C.c_void_p(hist.data_ptr()), C.c_void_p(st)), self._h)
         return hist
 
     def pair_search(self, W, c, g, fmt: ScaleFmt, k: int = 0, metric: int = SEL_WSE, out: Outputs = None,

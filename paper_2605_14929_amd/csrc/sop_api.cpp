@@ -23,6 +23,8 @@ extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
 extern "C" hipError_t sopk_sum_launch(const LsParams* p, void* stream);
+extern "C" hipError_t sopk_sel_launch(const SelParams* p, int n_wg, void* stream);
+extern "C" hipError_t sopk_pack_launch(const PackParams* p, void* stream);
 
 namespace {
 
@@ -53,6 +55,7 @@ struct sop_ctx {
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
     unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and a finished-workgroup counter; zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
+    unsigned int* d_sel = nullptr;        // [3][SOP_K_SEL_BINS] digit counts of the block ranking, then its finished-workgroup counter; zero between calls
     unsigned long long* d_sums = nullptr; // [SOP_K_REPL][SOP_K_NCOL] layer sums, then the ticket counters; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
@@ -122,6 +125,12 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(partials)");
     }
+    if ((e = hipMalloc((void**)&c->d_sel, sizeof(unsigned int) * (3 * SOP_K_SEL_BINS + 1))) != hipSuccess ||
+        (e = hipMemset(c->d_sel, 0, sizeof(unsigned int) * (3 * SOP_K_SEL_BINS + 1))) != hipSuccess) {
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); if (c->d_sel) (void)hipFree(c->d_sel);
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(rank counts)");
+    }
     *out = c;
     return SOP_OK;
 }
@@ -135,6 +144,7 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_sums) (void)hipFree(c->d_sums);
         if (c->d_ddacc) (void)hipFree(c->d_ddacc);
         if (c->d_ls) (void)hipFree(c->d_ls);
+        if (c->d_sel) (void)hipFree(c->d_sel);
         for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
     }
     delete c;
@@ -627,7 +637,7 @@ extern "C" sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_dr
 static bool dd_bins_ok(int n_bins) { return n_bins >= 64 && n_bins <= SOP_K_DD_MAXBINS && (n_bins & (n_bins - 1)) == 0; }
 
 extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
-                                       const float* cn, int g, int n_bins, int64_t row_step, int64_t* hist, void* stream)
+                                       const float* cn, int g, int n_bins, int64_t row_step, const uint8_t* block_mask, int64_t* hist, void* stream)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !hist) return fail(c, SOP_EINVAL, "sop_dd_histogram: W and hist must not be NULL");
@@ -643,7 +653,7 @@ extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtyp
     const int epl = g < 16 ? g : 16;
     DdParams p;
     std::memset(&p, 0, sizeof(p));
-    p.W = W; p.c = cn; p.M = M; p.K = K; p.ldw = ldw;
+    p.W = W; p.c = cn; p.block_mask = block_mask; p.M = M; p.K = K; p.ldw = ldw; p.Bk = K / g;
     p.row_step = row_step; p.Ms = (M + row_step - 1) / row_step;
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * p.Ms;
@@ -844,6 +854,80 @@ extern "C" sop_status sop_sum_f32(sop_ctx* c, const float* x, int64_t n, double*
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = sopk_sum_launch(&p, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+// ------------------------------------------------------------------ block ranking and pools (step 2)
+extern "C" sop_status sop_partition(sop_ctx* c, const float* score, int64_t n_blocks, int64_t n_top, int higher_is_better,
+                                    uint8_t* pool_b, float* tau, int64_t* n_a, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!score || !pool_b || !tau || !n_a) return fail(c, SOP_EINVAL, "sop_partition: score, pool_b, tau and n_a must not be NULL");
+    if (n_blocks < 1 || n_blocks > 0x7FFFFFFFll) return fail(c, SOP_ESHAPE, "sop_partition: n_blocks must lie in 1 .. 2^31-1");
+    if (n_top < 0 || n_top > n_blocks) return fail(c, SOP_EINVAL, "sop_partition: n_top must lie in 0 .. n_blocks");
+    if (!aligned16(score)) return fail(c, SOP_EINVAL, "sop_partition: score must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(pool_b) & 3u) || (reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(n_a) & 7u))
+        return fail(c, SOP_EINVAL, "sop_partition: pool_b and tau must be 4-byte aligned, n_a 8-byte aligned");
+    SelParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.score = score; p.n = n_blocks; p.n_top = n_top; p.higher = higher_is_better ? 1 : 0; p.all_b = n_top == 0;
+    p.hist = c->d_sel; p.done = c->d_sel + 3 * SOP_K_SEL_BINS;
+    p.pool_b = pool_b; p.tau = tau; p.n_a = reinterpret_cast<long long*>(n_a);
+    const long long quads = std::max<long long>((n_blocks / 4 + SOP_K_SEL_THREADS - 1) / SOP_K_SEL_THREADS, 1);
+    const int n_wg = (int)std::min<long long>((long long)c->n_cu * 4, quads);
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_sel_launch(&p, n_wg, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+// ------------------------------------------------------------------ scale words and code payloads
+static int code_bits_of(int n_entries) { int n = 1; while ((1 << n) < n_entries) ++n; return n; }
+
+extern "C" sop_status sop_pack_blocks(sop_ctx* c, int64_t M, int64_t K, int g, sop_scale_fmt fmt,
+                                      const uint16_t* scale_a, const uint8_t* codes_a, int entries_a,
+                                      const uint16_t* scale_b, const uint8_t* codes_b, int entries_b,
+                                      const void* sel_words, int sel_word_bytes, int pair_q,
+                                      uint16_t* words, uint8_t* payload, int* n_bits_out, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (sop_status s = shape_check(c, M, K, g)) return s;
+    if (!scale_a || !codes_a || !words || !payload) return fail(c, SOP_EINVAL, "sop_pack_blocks: scale_a, codes_a, words and payload must not be NULL");
+    if (entries_a < 2 || entries_a > SOP_MAX_ENTRIES) return fail(c, SOP_EATOM, "sop_pack_blocks: entries_a out of range");
+    const bool two = scale_b || codes_b || sel_words;
+    if (two) {
+        if (!scale_b || !codes_b || !sel_words) return fail(c, SOP_EINVAL, "sop_pack_blocks: a second codebook needs scale_b, codes_b and sel_words");
+        if (entries_b < 2 || entries_b > SOP_MAX_ENTRIES) return fail(c, SOP_EATOM, "sop_pack_blocks: entries_b out of range");
+        if (sel_word_bytes != 2 && sel_word_bytes != 4) return fail(c, SOP_EINVAL, "sop_pack_blocks: selector words are 2 or 4 bytes wide");
+        if (pair_q < 0 || pair_q >= 8 * sel_word_bytes || pair_q >= SOP_K_MAXP) return fail(c, SOP_EINVAL, "sop_pack_blocks: pair index outside the selector word");
+        if (reinterpret_cast<uintptr_t>(sel_words) & (uintptr_t)(sel_word_bytes - 1)) return fail(c, SOP_EINVAL, "sop_pack_blocks: sel_words misaligned");
+    }
+    const int w = fmt.sign_bits, x = fmt.exp_bits, y = fmt.man_bits, b = fmt.container_bits;
+    if ((w != 0 && w != 1) || x < 1 || y < 0 || b < 1 || b > 16 || x + y > 15 || b - w - x - y < 0)
+        return fail(c, SOP_EFMT, "sop_pack_blocks: not a SwExMy word in a container of at most 16 bits");
+    const int m = b - w - x - y;
+    if (two && m == 0) return fail(c, SOP_EFMT, "sop_pack_blocks: the scale format has no metabit for the selector");
+    auto mis = [](const void* q, uintptr_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) != 0; };
+    if (mis(codes_a, 8) || (two && mis(codes_b, 8)) || mis(payload, 8) || mis(scale_a, 2) || (two && mis(scale_b, 2)) || mis(words, 2))
+        return fail(c, SOP_EINVAL, "sop_pack_blocks: code planes and payload must be 8-byte aligned, 16-bit arrays 2-byte aligned");
+    PackParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.M = M; p.K = K; p.g = g; p.Bk = K / g; p.Nb = M * (K / g);
+    p.n_bits = code_bits_of(two ? std::max(entries_a, entries_b) : entries_a);
+    p.wide_a = entries_a > 16; p.wide_b = two && entries_b > 16;
+    p.scale_a = scale_a; p.scale_b = two ? scale_b : nullptr;
+    p.codes_a = codes_a; p.codes_b = two ? codes_b : nullptr;
+    p.sel_words = two ? sel_words : nullptr; p.sel_u32 = sel_word_bytes == 4; p.pair_q = two ? pair_q : 0;
+    p.sign_pos = w ? b - 1 : -1;
+    p.mag_shift = w ? m : (m > 0 ? m - 1 : 0);
+    p.sel_pos = !two ? -1 : (w ? m - 1 : b - 1);
+    p.words = words; p.payload = payload;
+    if (n_bits_out) *n_bits_out = p.n_bits;
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_pack_launch(&p, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }

@@ -8,7 +8,8 @@
 //          bin    = clamp(floor(fl(fl(x * H/2) + H/2)), 0, H-1)         H bins over [-1, 1]
 //   hist[bin] += mass                                                   (64-bit integers)
 // Integer sums do not depend on the order of addition, so the histogram is reproducible bit for bit.
-// Only rows 0, row_step, 2*row_step, ... enter (row_step = 1: the whole layer).
+// Only rows 0, row_step, 2*row_step, ... enter (row_step = 1: the whole layer), and, when a block
+// mask is given, only blocks whose mask byte is non-zero.
 //
 // Work mapping as in the search kernel: a lane owns min(g,16) consecutive elements of a row, a
 // wavefront walks down the rows of a 64-lane strip.  Each workgroup (16 wavefronts, one per compute
@@ -104,7 +105,12 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
         for (int i = 0; i < EPL; ++i) a = fmaxf(a, fabsf(w[i]));
         if (LPB >= 2) a = fmaxf(a, __shfl_xor(a, 1, 64));
         if (LPB >= 4) a = fmaxf(a, __shfl_xor(a, 2, 64));
-        if (valid && a > 0.0f) {
+        bool take = valid && a > 0.0f;
+        if (p.block_mask && take) {                 // only the blocks of the pool enter
+            const long long blk = m * p.row_step * p.Bk + (strip * 64 + lane) / LPB;
+            take = p.block_mask[blk] != 0;
+        }
+        if (take) {
             const float r = 1.0f / a;
 #pragma unroll
             for (int i = 0; i < EPL; ++i) {

@@ -98,7 +98,8 @@ struct KParams {
 struct DdParams {
     const void*  W;
     const float* c;                  // null: uniform weights
-    long long M, K, ldw;
+    const unsigned char* block_mask; // null: every block; else [M*K/g], non-zero = the block enters
+    long long M, K, ldw, Bk;
     long long row_step, Ms;          // every row_step-th row is used: Ms = ceil(M / row_step) rows
     long long strips, total_units, n_waves;  // total_units = strips * Ms
     int n_bins;
@@ -137,5 +138,35 @@ struct LsParams {
     unsigned int* done;
     double* out;                     // [4] weighted error, plain error, ||W||_c^2, scale code   (sum kernel: [1])
     uint16_t* codes;                 // optional [M*K] index into the ascending signed grid
+};
+
+/* Ranking of the blocks by a per-block score (exact selection of the score of a given rank) */
+#define SOP_K_SEL_THREADS 256
+#define SOP_K_SEL_BINS 2048          /* 11 + 11 + 10 bits of the 32-bit key over three passes */
+struct SelParams {
+    const float* score;              // [n]
+    long long n, n_top;              // 1 <= n_top <= n (n_top == 0: all_b)
+    int higher;                      // 1: a larger score ranks better
+    int all_b;                       // 1: every block goes to the second pool
+    unsigned int* hist;              // [3][SOP_K_SEL_BINS] digit counts of the passes (zero between calls)
+    unsigned int* done;
+    unsigned char* pool_b;           // [n] 1 = ranked strictly worse than the threshold
+    float* tau;                      // [1] the threshold score
+    long long* n_a;                  // [1] blocks that stay in the first pool
+};
+
+/* Packing of scale words and code payloads */
+struct PackParams {
+    long long Nb, Bk;                // blocks, blocks per row
+    long long M, K;
+    int g, n_bits;
+    int wide_a, wide_b;              // 1: the atom's plane holds one byte per code (else two codes per byte)
+    const uint16_t* scale_a; const uint16_t* scale_b;   // [Nb] bit 15 = sign, low bits = magnitude code
+    const unsigned char* codes_a; const unsigned char* codes_b;
+    const void* sel_words;           // null: single codebook
+    int sel_u32, pair_q;
+    int sign_pos, mag_shift, sel_pos;   // bit positions inside the container (-1: absent)
+    uint16_t* words;                 // [Nb]
+    unsigned char* payload;          // [Nb][g*n_bits/8]
 };
 #endif

@@ -11,7 +11,7 @@ from gpu_util import run_gpu, compare, oracle_fmt, ctx
 pytestmark = pytest.mark.gpu
 
 
-def gpu_hist(W, c, g, H, bf16, ldw=None, row_step=1):
+def gpu_hist(W, c, g, H, bf16, ldw=None, row_step=1, mask=None):
     import torch
     Wt = torch.from_numpy(W).cuda()
     if bf16:
@@ -21,7 +21,8 @@ def gpu_hist(W, c, g, H, bf16, ldw=None, row_step=1):
         buf[:, :W.shape[1]] = Wt
         Wt = buf[:, :W.shape[1]]
     ct = None if c is None else torch.from_numpy(c).cuda()
-    h = ctx().dd_histogram(Wt, ct, g, H, row_step)
+    mt = None if mask is None else torch.from_numpy(mask).cuda()
+    h = ctx().dd_histogram(Wt, ct, g, H, row_step, block_mask=mt)
     torch.cuda.synchronize()
     return h.cpu().numpy()
 
@@ -91,3 +92,21 @@ def test_dd4_joins_the_alphabet_config5_shape():
     h16 = gpu_hist(W, c, g, H, True, row_step=16)
     assert np.array_equal(h16, DD.histogram(W[::16], c, g, H))
     assert np.max(np.abs(sop.sop_dd_fit(h16, 16, 20, init) - dd4)) < 4e-3
+
+
+@pytest.mark.parametrize("g", [8, 16, 32, 64])
+def test_histogram_of_a_pool_of_blocks(g):
+    M, K = 41, 1088
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 950 + g, row_sigma=0.5))
+    c = si.channel_norms(K, 1.0, 951)
+    rng = np.random.default_rng(952 + g)
+    mask = (rng.random(M * K // g) < 0.35).astype(np.uint8)
+    mask[mask == 1] = rng.integers(1, 256, int(mask.sum())).astype(np.uint8)      # any non-zero byte counts
+    for row_step in (1, 3):
+        ref_mask = mask.copy().reshape(M, K // g)
+        keep = np.zeros(M, bool); keep[::row_step] = True
+        ref_mask[~keep] = 0
+        ref = DD.histogram(W, c, g, 512, block_mask=ref_mask.reshape(-1))
+        got = gpu_hist(W, c, g, 512, True, row_step=row_step, mask=mask)
+        assert np.array_equal(got, ref)
+    assert gpu_hist(W, c, g, 512, True, mask=np.zeros_like(mask)).sum() == 0

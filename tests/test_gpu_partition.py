@@ -1,0 +1,110 @@
+"""GPU parity of the block ranking (step 2 of the pair search) and of steps 1-4 chained: threshold,
+pool mask and pool size bit-exact against the oracle; the refit on the pool and the final search
+equal to the oracle's chain."""
+import numpy as np
+import pytest
+
+import paper_2605_14929_amd as sop
+from oracle import atoms as OA, dd as DD, partition as PT, pairsearch as ops
+import sop_inputs as si
+from gpu_util import run_gpu, compare, oracle_fmt, ctx
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_partition(score, n_top, higher=True):
+    import torch
+    st = torch.from_numpy(np.ascontiguousarray(score, dtype=np.float32)).cuda()
+    pool_b, tau, n_a = ctx().partition(st, n_top, higher)
+    torch.cuda.synchronize()
+    return tau.cpu().numpy()[0], pool_b.cpu().numpy(), int(n_a.cpu().numpy()[0])
+
+
+def check(score, n_top, higher=True):
+    tau, pool_b, n_a = gpu_partition(score, n_top, higher)
+    rt, rp, rn = PT.partition(score, n_top, higher)
+    assert tau == rt or (tau == 0.0 and rt == 0.0), (tau, rt)
+    assert n_a == rn
+    assert np.array_equal(pool_b, rp)
+
+
+@pytest.mark.parametrize("higher", [True, False])
+def test_ranks_sizes_and_ties(higher):
+    rng = np.random.default_rng(11)
+    for N in (1, 2, 3, 5, 1023, 1024, 4099, 70001):                  # ragged tails, one and many workgroups
+        cosv = (1.0 - np.abs(rng.standard_normal(N)) * 0.01).astype(np.float32)     # block cosines crowd below 1
+        for n_top in sorted({0, 1, N // 3, N - 1, N} & set(range(N + 1))):
+            check(cosv, n_top, higher)
+    # heavy ties, both zeros, negative and huge values, subnormals
+    s = rng.integers(-4, 5, 50000).astype(np.float32) * np.float32(0.25)
+    s[::7] = -0.0
+    s[1::11] = np.float32(1e-42)
+    s[2::13] = np.float32(-3e38)
+    s[3::17] = np.float32(3e38)
+    for n_top in (1, 100, 25000, 49999, 50000):
+        check(s, n_top, higher)
+    # all equal
+    check(np.full(777, 0.5, np.float32), 5, higher)
+
+
+def test_calls_in_a_row_leave_no_state():
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal(30000).astype(np.float32)
+    b = rng.standard_normal(999).astype(np.float32)
+    for _ in range(2):
+        check(a, 12345)
+        check(b, 17, False)
+        check(b, 0)
+
+
+def test_argument_validation():
+    import torch
+    cx = ctx()
+    s = torch.zeros(16, dtype=torch.float32, device="cuda")
+    with pytest.raises(sop.SopError):
+        cx.partition(s, 17)
+    with pytest.raises(sop.SopError):
+        cx.partition(s, -1)
+    with pytest.raises(sop.SopError):
+        cx.partition(s[1:], 2)                                        # misaligned
+    with pytest.raises(sop.SopError):
+        cx.partition(s.double(), 2)
+
+
+def test_steps_one_to_four_chained():
+    import torch
+    M, K, g = 96, 2048, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 2100, row_sigma=0.4, outlier_frac=0.001))
+    c = si.channel_norms(K, 1.0, 2101)
+    fmt = sop.fmt_by_name("UE4M3")                                   # one metabit: the selector fits
+    La = OA.to_f32(OA.nf(4))
+    cx = ctx()
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    # steps 1 and 2 on the GPU
+    cx.set_alphabet([La]); cx.set_pairs(None)
+    o1 = cx.pair_search(Wt, ct, g, fmt, emit=True)
+    Nb = M * K // g
+    n_top = PT.top_count(70.0, Nb)
+    pool_b, tau, n_a = cx.partition(o1.blk_cos[0], n_top, True)
+    # step 3 on the GPU: histogram of the pool, fit on the host side of the library
+    hist = cx.dd_histogram(Wt, ct, g, 1024, 1, block_mask=pool_b)
+    torch.cuda.synchronize()
+    Lb = sop.sop_dd_fit(hist.cpu().numpy(), 16, 12, La)
+    # the oracle's chain
+    r1 = ops.pair_search(W, c, [La], g, oracle_fmt(fmt))
+    assert np.max(np.abs(o1.blk_cos[0].cpu().numpy() - r1.blk_cos[0])) < 2e-5
+    # rank on the GPU's own cosine plane (binary32 values differ in the last place between the two
+    # sides; the ranking itself is exact on whichever plane it is given)
+    gcos = o1.blk_cos[0].cpu().numpy()
+    rt, rp, rn = PT.partition(gcos, n_top, True)
+    assert tau.cpu().numpy()[0] == rt and int(n_a.cpu().numpy()[0]) == rn and np.array_equal(pool_b.cpu().numpy(), rp)
+    rh = DD.histogram(W, c, g, 1024, block_mask=rp)
+    assert np.array_equal(hist.cpu().numpy(), rh)
+    rLb = OA.to_f32(DD.fit(rh, 16, 12, OA.nf(4)))
+    assert np.array_equal(Lb, rLb)
+    # step 4: the search over (L_a, L_b) on both sides
+    gpu = run_gpu(W, c, [La, Lb], g, fmt, bf16=True)
+    ref = ops.pair_search(W, c, [La, rLb], g, oracle_fmt(fmt))
+    compare(gpu, ref, 1)
+    assert ref.acos_pair[0] > ref.acos_atom.max()
