@@ -225,6 +225,100 @@ def bench_ls(args):
     print(json.dumps(result))
 
 
+def bench_finish(args):
+    """Steps 2 and 3 of the pair search and the materialisation on the headline layer, after an
+    emitting search over (NF4, SH4) with a UE4M3 scale word (one metabit): rank the blocks by their
+    cosine under NF4 and split the pools (70% stay), histogram of the fitting pool, pack scale words
+    and code payloads of the pair."""
+    import numpy as np
+    import torch
+    import paper_2605_14929_amd as sop
+    import sop_inputs as si
+    W, c, cfg = si.make_config("C3_down")
+    M, K, g = cfg["M"], cfg["K"], cfg["g"]
+    Nb = M * K // g
+    fmt = sop.fmt_by_name("UE4M3")
+    tabs = sop.build_alphabet(["NF4", "SH4"])
+    dev = torch.device("cuda", 0)
+    wt = torch.from_numpy(W).to(dev).to(torch.bfloat16)
+    ct = torch.from_numpy(c).to(dev)
+    ctx = sop.Context(0)
+    ctx.set_alphabet(tabs)
+    out = ctx.pair_search(wt, ct, g, fmt, emit=True)
+    torch.cuda.synchronize()
+    n_top = int(np.floor(0.70 * Nb + 0.5))
+    score = out.blk_cos[0]
+
+    def step():
+        pool_b, tau, n_a = ctx.partition(score, n_top, True)
+        hist = ctx.dd_histogram(wt, ct, g, 1024, 1, block_mask=pool_b)
+        words, payload, n = ctx.pack_blocks(out, M, K, g, fmt, 0, 1, 0)
+        return pool_b, tau, n_a, hist, words, payload
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
+    # per-part latency with events on the launch stream
+    parts = {}
+    for name, fn in (("partition", lambda: ctx.partition(score, n_top, True)),
+                     ("masked_histogram", lambda: ctx.dd_histogram(wt, ct, g, 1024, 1, block_mask=step.pool)),
+                     ("pack", lambda: ctx.pack_blocks(out, M, K, g, fmt, 0, 1, 0))):
+        if name == "masked_histogram":
+            step.pool = ctx.partition(score, n_top, True)[0]
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for a, b in ev:
+            a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        parts[name] = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    alg = {"partition": 4 * 4 * Nb + Nb + 12,                         # the score plane is read by each of the four kernels
+           "masked_histogram": M * K * 2 + Nb + K * 4 + 8 * 1024,
+           "pack": Nb * (2 + 2 + g // 2) + Nb * (2 + g // 2)}
+    ev_ms = sum(parts.values())
+    alg_bytes = sum(alg.values())
+    result = {
+        "metric": "blocks finished/sec", "value": Nb / (ms_step * 1e-3), "unit": "blocks/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "steps 2-3 and packing after a (NF4, SH4) UE4M3 search of the C3 down-projection 4096x11008 bf16: "
+                               "rank 2.8 M block cosines, 70/30 pools, masked 1024-bin histogram, scale words + 8-byte payloads",
+                   "M": M, "K": K, "g": g, "n_top": n_top},
+        "part_latency_ms": parts,
+        "roofline": {"bound": "hbm", "achieved": alg_bytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_bytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "algorithmic_bytes_by_part": alg,
+                     "kernel": "sopk::rank_count_kernel x3 + sopk::rank_split_kernel + sopk::dd_hist_kernel + sopk::pack_kernel",
+                     "event_ms_per_launch": ev_ms},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import dd as DD, pack as PK, partition as PT, pairsearch as ops
+        Ms = 512                                                       # bounded sample: the first 512 rows
+        Ws = W[:Ms]
+        ref = ops.pair_search(Ws, c, tabs, g, ops.make_fmt(0, 4, 3))
+        t0 = time.perf_counter()
+        nbs = Ms * K // g
+        rt, rp, rn = PT.partition(ref.blk_cos[0], int(np.floor(0.70 * nbs + 0.5)), True)
+        rh = DD.histogram(Ws, c, g, 1024, block_mask=rp)
+        rw, rpl, _ = PK.materialise(ref, tabs, Ms, K, g, 0, 1, 0, 0, 4, 3, 8)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": nbs / dt, "unit": "blocks/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the first {Ms} rows of the layer ({nbs} blocks), numpy on one core, {dt:.2f} s wall"}
+        # parity in the run: the same rows through the library
+        o2 = ctx.pair_search(wt[:Ms], ct, g, fmt, emit=True)
+        pb, tau, n_a = ctx.partition(o2.blk_cos[0], int(np.floor(0.70 * nbs + 0.5)), True)
+        words, payload, _ = ctx.pack_blocks(o2, Ms, K, g, fmt, 0, 1, 0)
+        torch.cuda.synchronize()
+        gt, gp, gn = PT.partition(o2.blk_cos[0].cpu().numpy(), int(np.floor(0.70 * nbs + 0.5)), True)
+        result["parity_in_run"] = {"words_equal": bool(np.array_equal(words.cpu().numpy().view(np.uint16), rw)),
+                                   "payload_equal": bool(np.array_equal(payload.cpu().numpy(), rpl)),
+                                   "pool_equal_on_gpu_scores": bool(np.array_equal(pb.cpu().numpy(), gp) and int(n_a.item()) == gn)}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,10 +326,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope"],
+    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish"],
                     help="pair_search (default): the headline six-atom search; dd_histogram: the statistics pass of the "
                          "data-derived codebook on the same layer; scale_histogram: the statistics pass of the per-layer "
-                         "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer")
+                         "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer; finish: block ranking and pools, "
+                         "masked histogram and packing after a two-atom search")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (1 GiB read, 1 GiB written) a few times: the "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -255,6 +350,8 @@ def main():
         return bench_fl(args)
     if args.workload == "layer_scope":
         return bench_ls(args)
+    if args.workload == "finish":
+        return bench_finish(args)
 
     W, c, cfg = si.make_config("C3_down")
     M, K, g = cfg["M"], cfg["K"], cfg["g"]

@@ -23,7 +23,7 @@ extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
 extern "C" hipError_t sopk_sum_launch(const LsParams* p, void* stream);
-extern "C" hipError_t sopk_sel_launch(const SelParams* p, int n_wg, void* stream);
+extern "C" hipError_t sopk_sel_launch(const SelParams* p, int n_wg_count, int n_wg, void* stream);
 extern "C" hipError_t sopk_pack_launch(const PackParams* p, void* stream);
 
 namespace {
@@ -55,7 +55,8 @@ struct sop_ctx {
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
     unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and a finished-workgroup counter; zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
-    unsigned int* d_sel = nullptr;        // [3][SOP_K_SEL_BINS] digit counts of the block ranking, then its finished-workgroup counter; zero between calls
+    unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
+    int sel_set = 0;
     unsigned long long* d_sums = nullptr; // [SOP_K_REPL][SOP_K_NCOL] layer sums, then the ticket counters; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
@@ -125,8 +126,8 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(partials)");
     }
-    if ((e = hipMalloc((void**)&c->d_sel, sizeof(unsigned int) * (3 * SOP_K_SEL_BINS + 1))) != hipSuccess ||
-        (e = hipMemset(c->d_sel, 0, sizeof(unsigned int) * (3 * SOP_K_SEL_BINS + 1))) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_sel, sizeof(unsigned int) * (6 * SOP_K_SEL_BINS))) != hipSuccess ||
+        (e = hipMemset(c->d_sel, 0, sizeof(unsigned int) * (6 * SOP_K_SEL_BINS))) != hipSuccess) {
         (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); if (c->d_sel) (void)hipFree(c->d_sel);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(rank counts)");
@@ -872,14 +873,17 @@ extern "C" sop_status sop_partition(sop_ctx* c, const float* score, int64_t n_bl
     SelParams p;
     std::memset(&p, 0, sizeof(p));
     p.score = score; p.n = n_blocks; p.n_top = n_top; p.higher = higher_is_better ? 1 : 0; p.all_b = n_top == 0;
-    p.hist = c->d_sel; p.done = c->d_sel + 3 * SOP_K_SEL_BINS;
+    p.hist = c->d_sel + (c->sel_set ? 3 * SOP_K_SEL_BINS : 0); p.hist_other = c->d_sel + (c->sel_set ? 0 : 3 * SOP_K_SEL_BINS);
     p.pool_b = pool_b; p.tau = tau; p.n_a = reinterpret_cast<long long*>(n_a);
     const long long quads = std::max<long long>((n_blocks / 4 + SOP_K_SEL_THREADS - 1) / SOP_K_SEL_THREADS, 1);
     const int n_wg = (int)std::min<long long>((long long)c->n_cu * 4, quads);
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
-    hipError_t e = sopk_sel_launch(&p, n_wg, stream);
+    const long long cquads = std::max<long long>((n_blocks / 4 + SOP_K_CNT_THREADS - 1) / SOP_K_CNT_THREADS, 1);
+    const int n_wg_count = (int)std::min<long long>(std::max(c->n_cu / 2, 1), cquads);
+    hipError_t e = sopk_sel_launch(&p, n_wg_count, n_wg, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    if (!p.all_b) c->sel_set ^= 1;
     return SOP_OK;
 }
 

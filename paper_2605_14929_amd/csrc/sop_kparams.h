@@ -141,15 +141,16 @@ struct LsParams {
 };
 
 /* Ranking of the blocks by a per-block score (exact selection of the score of a given rank) */
-#define SOP_K_SEL_THREADS 256
+#define SOP_K_SEL_THREADS 256         /* pool-mask kernel */
+#define SOP_K_CNT_THREADS 1024        /* counting kernels */
 #define SOP_K_SEL_BINS 2048          /* 11 + 11 + 10 bits of the 32-bit key over three passes */
 struct SelParams {
     const float* score;              // [n]
     long long n, n_top;              // 1 <= n_top <= n (n_top == 0: all_b)
     int higher;                      // 1: a larger score ranks better
     int all_b;                       // 1: every block goes to the second pool
-    unsigned int* hist;              // [3][SOP_K_SEL_BINS] digit counts of the passes (zero between calls)
-    unsigned int* done;
+    unsigned int* hist;              // [3][SOP_K_SEL_BINS] digit counts of the passes (zero when the call starts)
+    unsigned int* hist_other;        // [3][SOP_K_SEL_BINS] the set the next call counts into: cleared by this call
     unsigned char* pool_b;           // [n] 1 = ranked strictly worse than the threshold
     float* tau;                      // [1] the threshold score
     long long* n_a;                  // [1] blocks that stay in the first pool

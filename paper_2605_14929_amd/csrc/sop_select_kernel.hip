@@ -9,8 +9,8 @@
 // counts, in a 2048-bin histogram, the digit of every key that agrees with the digits fixed so far;
 // the next kernel finds, from that histogram, the digit in which the wanted rank falls.  A last
 // kernel writes the pool mask, tau and the size of the first pool.  Counts are integers added with
-// atomics, so every result is exact and reproducible.  The histograms live in the context and are
-// left at zero by the last kernel.
+// atomics, so every result is exact and reproducible.  The context holds two sets of histograms:
+// a call counts into one and clears the other, which the next call then counts into.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -32,37 +32,43 @@ __device__ __forceinline__ float key_score(uint32_t k, bool higher)
     return __uint_as_float(u);
 }
 
-struct Found { int digit; unsigned long long rank_in, above; };
+struct Found { int digit; unsigned int rank_in, above; };
 
-// Wave 0 of the workgroup walks a histogram from its top bin down and finds the bin in which the
-// key of rank `rank` (1-based from the top) falls: `above` keys lie in higher bins and the wanted
-// key has rank `rank_in` inside the bin.  The result reaches every thread through LDS.
-__device__ Found find_digit(const unsigned int* hist, int nb, unsigned long long rank, Found* s_found)
+// The workgroup (at least 256 threads) walks a 2048-bin histogram from its top bin down and finds the bin in
+// which the key of rank `rank` (1-based from the top) falls: `above` keys lie in higher bins and the
+// wanted key has rank `rank_in` inside the bin.  Thread t holds the eight bins 2047-8t .. 2040-8t in
+// registers; a scan over the threads' sums names the one thread whose bins contain the rank.
+__device__ Found find_digit(const unsigned int* hist, unsigned int rank, Found* s_found, unsigned int* s_wave)
 {
-    if (threadIdx.x == 0) { s_found->digit = 0; s_found->rank_in = 1; s_found->above = 0; }   // histogram shorter than rank: stay in bounds
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        const int lane = threadIdx.x;
-        const int per = nb / 64;
-        const int top = nb - 1 - lane * per;
-        unsigned long long sum = 0;
-        for (int i = 0; i < per; ++i) sum += hist[top - i];
-        unsigned long long inc = sum;
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const bool on = t < SOP_K_SEL_BINS / 8;                         // the first 256 threads hold the bins
+    const int base = on ? SOP_K_SEL_BINS - 8 * (t + 1) : 0;
+    uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+    if (on) { lo = *reinterpret_cast<const uint4*>(hist + base); hi = *reinterpret_cast<const uint4*>(hist + base + 4); }
+    const unsigned int h[8] = {hi.w, hi.z, hi.y, hi.x, lo.w, lo.z, lo.y, lo.x};     // from the top bin down
+    const unsigned int sum = ((h[0] + h[1]) + (h[2] + h[3])) + ((h[4] + h[5]) + (h[6] + h[7]));
+    unsigned int inc = sum;
 #pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const unsigned long long t = __shfl_up(inc, st, 64);
-            if (lane >= st) inc += t;
-        }
-        const unsigned long long exc = inc - sum;
-        if (exc < rank && rank <= inc) {                            // exactly one lane
-            unsigned long long c = exc;
-            int d = top;
-            for (int i = 0; i < per; ++i) {
-                const unsigned long long h = hist[top - i];
-                if (c + h >= rank) { d = top - i; break; }
-                c += h;
+    for (int st = 1; st < 64; st <<= 1) {
+        const unsigned int v = __shfl_up(inc, st, 64);
+        if (lane >= st) inc += v;
+    }
+    if (t == 0) { s_found->digit = 0; s_found->rank_in = 1; s_found->above = 0; }   // histogram shorter than rank: stay in bounds
+    if (on && lane == 63) s_wave[wv] = inc;
+    __syncthreads();
+    if (on) {
+        for (int i = 0; i < wv; ++i) inc += s_wave[i];
+        const unsigned int exc = inc - sum;
+        if (exc < rank && rank <= inc) {                            // exactly one thread
+            unsigned int c = exc;
+            int d = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {                           // ci: keys above bin i of this thread
+                const unsigned int ci = exc + (i > 0 ? h[0] : 0u) + (i > 1 ? h[1] : 0u) + (i > 2 ? h[2] : 0u) + (i > 3 ? h[3] : 0u)
+                                      + (i > 4 ? h[4] : 0u) + (i > 5 ? h[5] : 0u) + (i > 6 ? h[6] : 0u);
+                if (ci < rank && rank <= ci + h[i]) { d = i; c = ci; }
             }
-            s_found->digit = d; s_found->rank_in = rank - c; s_found->above = c;
+            s_found->digit = base + 7 - d; s_found->rank_in = rank - c; s_found->above = c;
         }
     }
     __syncthreads();
@@ -71,22 +77,37 @@ __device__ Found find_digit(const unsigned int* hist, int nb, unsigned long long
     return f;
 }
 
+// one count into an LDS histogram for every active lane; lanes that share the first active lane's
+// digit are counted with one atomic (block cosines crowd into very few digits in the first pass)
+__device__ __forceinline__ void count_digit(unsigned int* s_hist, bool active, int digit)
+{
+    const unsigned long long act = __builtin_amdgcn_ballot_w64(active);
+    if (act == 0ull) return;
+    const int first = __builtin_ctzll(act);
+    const int lead = __builtin_amdgcn_readlane(digit, first);
+    const bool same = active && digit == lead;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(same);
+    if ((int)(threadIdx.x & 63) == first) atomicAdd(&s_hist[lead], (unsigned int)__builtin_popcountll(m));
+    if (active && !same) atomicAdd(&s_hist[digit], 1u);
+}
+
 // digits of a key: pass 0 bits 31..21, pass 1 bits 20..10, pass 2 bits 9..0
 __device__ __forceinline__ int digit_of(uint32_t k, int pass) { return pass == 0 ? (int)(k >> 21) : pass == 1 ? (int)((k >> 10) & 0x7FFu) : (int)(k & 0x3FFu); }
 
 template <int PASS>
-__global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_count_kernel(const SelParams p)
+__global__ __launch_bounds__(SOP_K_CNT_THREADS) void rank_count_kernel(const SelParams p)
 {
     __shared__ unsigned int s_hist[SOP_K_SEL_BINS];
     __shared__ Found s_found;
-    for (int i = threadIdx.x; i < SOP_K_SEL_BINS; i += SOP_K_SEL_THREADS) s_hist[i] = 0u;
+    __shared__ unsigned int s_wave[SOP_K_SEL_BINS / 8 / 64];
+    for (int i = threadIdx.x; i < SOP_K_SEL_BINS; i += SOP_K_CNT_THREADS) s_hist[i] = 0u;
     // the digits fixed by the earlier passes
     uint32_t prefix = 0, pmask = 0;
     if (PASS >= 1) {
-        const Found f0 = find_digit(p.hist, SOP_K_SEL_BINS, (unsigned long long)p.n_top, &s_found);
+        const Found f0 = find_digit(p.hist, (unsigned int)p.n_top, &s_found, s_wave);
         prefix = (uint32_t)f0.digit << 21; pmask = 0xFFE00000u;
         if (PASS >= 2) {
-            const Found f1 = find_digit(p.hist + SOP_K_SEL_BINS, SOP_K_SEL_BINS, f0.rank_in, &s_found);
+            const Found f1 = find_digit(p.hist + SOP_K_SEL_BINS, f0.rank_in, &s_found, s_wave);
             prefix |= (uint32_t)f1.digit << 10; pmask = 0xFFFFFC00u;
         }
     }
@@ -94,13 +115,13 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_count_kernel(const Sel
     const bool higher = p.higher != 0;
     const long long n4 = p.n >> 2;
     const float4* s4 = reinterpret_cast<const float4*>(p.score);
-    for (long long i = (long long)blockIdx.x * SOP_K_SEL_THREADS + threadIdx.x; i < n4; i += (long long)gridDim.x * SOP_K_SEL_THREADS) {
+    for (long long i = (long long)blockIdx.x * SOP_K_CNT_THREADS + threadIdx.x; i < n4; i += (long long)gridDim.x * SOP_K_CNT_THREADS) {
         const float4 v = s4[i];
         const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t k = rank_key(e[j], higher);
-            if ((k & pmask) == prefix) atomicAdd(&s_hist[digit_of(k, PASS)], 1u);
+            count_digit(s_hist, (k & pmask) == prefix, digit_of(k, PASS));
         }
     }
     if (blockIdx.x == 0 && (long long)threadIdx.x < (p.n & 3)) {     // ragged tail
@@ -109,7 +130,7 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_count_kernel(const Sel
     }
     __syncthreads();
     unsigned int* out = p.hist + PASS * SOP_K_SEL_BINS;
-    for (int i = threadIdx.x; i < SOP_K_SEL_BINS; i += SOP_K_SEL_THREADS) {
+    for (int i = threadIdx.x; i < SOP_K_SEL_BINS; i += SOP_K_CNT_THREADS) {
         const unsigned int v = s_hist[i];
         if (v) atomicAdd(out + i, v);
     }
@@ -118,15 +139,15 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_count_kernel(const Sel
 __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_split_kernel(const SelParams p)
 {
     __shared__ Found s_found;
-    __shared__ unsigned int s_flag;
+    __shared__ unsigned int s_wave[SOP_K_SEL_THREADS / 64];
     const bool higher = p.higher != 0;
     uint32_t tkey = 0xFFFFFFFFu;
-    unsigned long long n_a = 0;
+    unsigned int n_a = 0;
     float tau = higher ? __uint_as_float(0x7F800000u) : __uint_as_float(0xFF800000u);
     if (!p.all_b) {
-        const Found f0 = find_digit(p.hist, SOP_K_SEL_BINS, (unsigned long long)p.n_top, &s_found);
-        const Found f1 = find_digit(p.hist + SOP_K_SEL_BINS, SOP_K_SEL_BINS, f0.rank_in, &s_found);
-        const Found f2 = find_digit(p.hist + 2 * SOP_K_SEL_BINS, SOP_K_SEL_BINS, f1.rank_in, &s_found);
+        const Found f0 = find_digit(p.hist, (unsigned int)p.n_top, &s_found, s_wave);
+        const Found f1 = find_digit(p.hist + SOP_K_SEL_BINS, f0.rank_in, &s_found, s_wave);
+        const Found f2 = find_digit(p.hist + 2 * SOP_K_SEL_BINS, f1.rank_in, &s_found, s_wave);
         tkey = ((uint32_t)f0.digit << 21) | ((uint32_t)f1.digit << 10) | (uint32_t)f2.digit;
         tau = key_score(tkey, higher);
         // keys above tau's, plus every key equal to it
@@ -151,27 +172,26 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_split_kernel(const Sel
         p.pool_b[i] = p.all_b ? 1 : (rank_key(p.score[i], higher) < tkey ? 1 : 0);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) { *p.tau = tau; *p.n_a = (long long)n_a; }
-    // the workgroup that finishes last clears the histograms (every workgroup has read them by then)
-    __syncthreads();
-    if (threadIdx.x == 0) s_flag = atomicAdd(p.done, 1u) == gridDim.x - 1 ? 1u : 0u;
-    __syncthreads();
-    if (s_flag) {
-        for (int i = threadIdx.x; i < 3 * SOP_K_SEL_BINS; i += SOP_K_SEL_THREADS) atomicExch(p.hist + i, 0u);
-        if (threadIdx.x == 0) atomicExch(p.done, 0u);
-    }
+    // clear the other set of histograms (the one the previous call counted into; nothing reads it
+    // now) for the next call: no workgroup has to wait for the others
+    for (long long gi = (long long)blockIdx.x * SOP_K_SEL_THREADS + threadIdx.x; gi < 3 * SOP_K_SEL_BINS; gi += (long long)gridDim.x * SOP_K_SEL_THREADS)
+        p.hist_other[gi] = 0u;
 }
 
 }  // namespace sopk
 
-extern "C" hipError_t sopk_sel_launch(const SelParams* pp, int n_wg, void* stream)
+extern "C" hipError_t sopk_sel_launch(const SelParams* pp, int n_wg_count, int n_wg, void* stream)
 {
     const SelParams p = *pp;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((unsigned)n_wg), block(SOP_K_SEL_THREADS);
     if (!p.all_b) {
-        hipLaunchKernelGGL((sopk::rank_count_kernel<0>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((sopk::rank_count_kernel<1>), grid, block, 0, st, p);
-        hipLaunchKernelGGL((sopk::rank_count_kernel<2>), grid, block, 0, st, p);
+        // few, large workgroups: every workgroup adds its whole histogram to the layer's with
+        // same-address atomics, which serialise
+        const dim3 cgrid((unsigned)n_wg_count), cblock(SOP_K_CNT_THREADS);
+        hipLaunchKernelGGL((sopk::rank_count_kernel<0>), cgrid, cblock, 0, st, p);
+        hipLaunchKernelGGL((sopk::rank_count_kernel<1>), cgrid, cblock, 0, st, p);
+        hipLaunchKernelGGL((sopk::rank_count_kernel<2>), cgrid, cblock, 0, st, p);
     }
     hipLaunchKernelGGL(sopk::rank_split_kernel, grid, block, 0, st, p);
     return hipGetLastError();
