@@ -13,6 +13,7 @@ _SRC = os.path.join(_HERE, "sop_oracle.c")
 _LIB = os.path.join(_HERE, "libsop_oracle.so")
 
 WSE, COS, MSE = 0, 1, 2
+ABSMAX, ARGMAX = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -79,7 +80,8 @@ class Result:
 
 
 def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k: int = 0, metric: int = WSE,
-                pairs: np.ndarray | None = None, want_codes: bool = True, n_threads: int = 0) -> Result:
+                pairs: np.ndarray | None = None, want_codes: bool = True, n_threads: int = 0,
+                scale_rule: int = ABSMAX) -> Result:
     """Run the oracle on a layer.  W is fp32 [M,K] (bf16 data already widened); atoms is a list of
     ascending fp32 tables."""
     W = np.ascontiguousarray(W, dtype=np.float32)
@@ -111,7 +113,7 @@ def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k:
     rc = lib().sopo_pair_search(
         p(W, C.c_float), C.c_int64(M), C.c_int64(K), C.c_int64(K), p(c, C.c_float), C.c_int(g),
         C.c_int(A), p(n_entries, C.c_int), p(flat, C.c_float), C.c_int(P), p(pairs, C.c_int),
-        C.byref(fmt), C.c_int(k), C.c_int(metric),
+        C.byref(fmt), C.c_int(k), C.c_int(metric), C.c_int(scale_rule),
         p(acos_pair, C.c_double), p(acos_atom, C.c_double), p(sel, C.c_uint32), p(sc, C.c_uint16),
         p(codes, C.c_uint8), p(be, C.c_float), p(bc, C.c_float), C.c_int(n_threads))
     if rc != 0:

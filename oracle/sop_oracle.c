@@ -140,17 +140,36 @@ static int better(const cand* b, const cand* a, int metric)
     return metric == SOPO_COS ? cos_better(b, a) : (b->err < a->err);
 }
 
-/* One candidate: block w[g] with weights c[g], codebook L[N] (ascending) with midpoints mid[N-1],
- * scale sign sigma (+1/-1). */
-static void eval_candidate(const float* w, const float* c, int g, const float* L, const float* mid, int N,
-                           float pmax, float nmax, int sigma, const sopo_fmt* f, int k, int metric,
-                           const float* cw, double wn_d, cand* out)
+/* Ideal scale magnitude under the absmax rule (Section "Block Scaling", absmax scaling): no element
+ * lands beyond an endpoint.  A negative scale sign swaps the roles of the endpoints. */
+static float absmax_scale(const float* L, int N, float pmax, float nmax, int sigma)
 {
     float tp = L[N - 1], tn = -L[0];
-    /* absmax rule: no element beyond an endpoint.  A negative scale swaps the roles of the endpoints. */
     float s_pos = sigma > 0 ? pmax / tp : pmax / tn;
     float s_neg = sigma > 0 ? nmax / tn : nmax / tp;
-    float sstar = s_pos > s_neg ? s_pos : s_neg;
+    return s_pos > s_neg ? s_pos : s_neg;
+}
+
+/* Argmax rule (Section "Block Scaling", argmax scaling): the element of largest magnitude x* is
+ * mapped onto the endpoint of larger magnitude t*: s = x* / t*, so the scale's sign is that of x*
+ * when t* is the positive endpoint and the opposite otherwise.  Where the paper is silent: of two
+ * elements of equal magnitude and opposite sign the positive one is x*; of two endpoints of equal
+ * magnitude the positive one is t*. */
+static float argmax_scale(const float* L, int N, float pmax, float nmax, int* sigma)
+{
+    float tp = L[N - 1], tn = -L[0];
+    int x_pos = pmax >= nmax, t_pos = tp >= tn;
+    float amax = x_pos ? pmax : nmax;
+    *sigma = (x_pos == t_pos) ? +1 : -1;
+    return amax / (t_pos ? tp : tn);
+}
+
+/* One candidate: block w[g] with weights c[g], codebook L[N] (ascending) with midpoints mid[N-1],
+ * ideal scale magnitude sstar, scale sign sigma (+1/-1). */
+static void eval_candidate(const float* w, const float* c, int g, const float* L, const float* mid, int N,
+                           float sstar, int sigma, const sopo_fmt* f, int k, int metric,
+                           const float* cw, double wn_d, cand* out)
+{
     float sp = sstar * (float)ldexp(1.0, k);                         /* per-layer shift 2^k          */
     int q = sopo_scale_encode(f, sp);
     float s = (float)ldexp(sopo_scale_value(f, q), -k);              /* exact by validation          */
@@ -204,7 +223,7 @@ static void eval_candidate(const float* w, const float* c, int g, const float* L
 int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const float* c, int g,
                      int n_atoms, const int* n_entries, const float* atoms,
                      int n_pairs, const int* pair_ab,
-                     const sopo_fmt* fmt, int k, int metric,
+                     const sopo_fmt* fmt, int k, int metric, int scale_rule,
                      double* acos_pair, double* acos_atom, uint32_t* sel_words, uint16_t* scale_code,
                      uint8_t* codes, float* blk_err, float* blk_cos, int n_threads)
 {
@@ -214,6 +233,8 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
     int chunk = g < 8 ? g : 8;
     if (g % chunk != 0 || ((g / chunk) & (g / chunk - 1)) != 0) return -1;
     if (fmt->max_code < 1 || fmt->max_code >= (1 << (fmt->exp_bits + fmt->man_bits))) return -3;
+    if (scale_rule != 0 && scale_rule != 1) return -3;
+    if (scale_rule == 1 && fmt->sign_bits == 0) return -3;        /* the argmax scale carries a sign */
 
     const float* L[SOPO_MAX_ATOMS];
     float mid[SOPO_MAX_ATOMS][SOPO_MAX_ENTRIES];
@@ -265,11 +286,19 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
             }
             cand best[SOPO_MAX_ATOMS];
             for (int a = 0; a < n_atoms; ++a) {
-                eval_candidate(w, cb, g, L[a], mid[a], n_entries[a], pmax, nmax, +1, fmt, k, metric, cw, wn_d, &best[a]);
-                if (is_signed) {
-                    cand neg;
-                    eval_candidate(w, cb, g, L[a], mid[a], n_entries[a], pmax, nmax, -1, fmt, k, metric, cw, wn_d, &neg);
-                    if (better(&neg, &best[a], metric)) best[a] = neg;
+                if (scale_rule == 1) {                             /* argmax: the rule fixes the sign */
+                    int sigma;
+                    float sstar = argmax_scale(L[a], n_entries[a], pmax, nmax, &sigma);
+                    eval_candidate(w, cb, g, L[a], mid[a], n_entries[a], sstar, sigma, fmt, k, metric, cw, wn_d, &best[a]);
+                } else {
+                    eval_candidate(w, cb, g, L[a], mid[a], n_entries[a], absmax_scale(L[a], n_entries[a], pmax, nmax, +1), +1,
+                                   fmt, k, metric, cw, wn_d, &best[a]);
+                    if (is_signed) {
+                        cand neg;
+                        eval_candidate(w, cb, g, L[a], mid[a], n_entries[a], absmax_scale(L[a], n_entries[a], pmax, nmax, -1), -1,
+                                       fmt, k, metric, cw, wn_d, &neg);
+                        if (better(&neg, &best[a], metric)) best[a] = neg;
+                    }
                 }
                 int64_t blk = m * Bk + j;
                 rs[a] += best[a].cosv;
