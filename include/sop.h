@@ -114,6 +114,16 @@ sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int* n_bins, i
  * P = 0 (or pair_ab NULL) restores the default of all pairs.  Output index = position here. */
 sop_status sop_set_pairs(sop_ctx* ctx, const int* pair_ab, int n_pairs);
 
+/* Rule for the block scale (Section "Block Scaling").  SOP_SCALE_ABSMAX (default): the smallest scale
+ * that leaves no element beyond an endpoint, s = max(max_r x / t+, max_r (-x) / (-t-)); with a signed
+ * scale word the search evaluates both signs of it and keeps the better.  SOP_SCALE_ARGMAX: the
+ * element of largest magnitude x* is mapped onto the endpoint of larger magnitude t*, s = x* / t*; the
+ * rule fixes the sign (bit 15 of scale_code), so the scale word must have a sign bit (else SOP_EFMT
+ * from sop_pair_search).  Ties: of +a and -a the positive element is x*; of endpoints of equal
+ * magnitude the positive one is t*.  The rule stays set for later sop_pair_search() calls. */
+typedef enum { SOP_SCALE_ABSMAX = 0, SOP_SCALE_ARGMAX = 1 } sop_scale_rule;
+sop_status sop_set_scale_rule(sop_ctx* ctx, sop_scale_rule rule);
+
 /* Bytes of DEVICE workspace sop_pair_search() needs for this shape.  This version needs none and
  * reports 0 (the layer reduction keeps a few words inside the context); the workspace arguments of
  * sop_pair_search() are accepted for callers written against a version that did, and may be

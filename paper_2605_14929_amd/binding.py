@@ -9,6 +9,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 F32, BF16 = 0, 1
+SCALE_ABSMAX, SCALE_ARGMAX = 0, 1
 SEL_WSE, SEL_COS, SEL_MSE = 0, 1, 2
 MAX_ATOMS, MAX_ENTRIES = 8, 64
 _STATUS = {1: "SOP_EINVAL", 2: "SOP_ESHAPE", 3: "SOP_EATOM", 4: "SOP_EFMT", 5: "SOP_ENOMEM", 6: "SOP_EHIP"}
@@ -65,6 +66,7 @@ def lib():
         L.sop_set_alphabet.argtypes = [C.c_void_p, C.POINTER(_Atom), C.c_int]
         L.sop_check_alphabet.argtypes = [C.POINTER(_Atom), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.sop_set_pairs.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.c_int]
+        L.sop_set_scale_rule.argtypes = [C.c_void_p, C.c_int]
         L.sop_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
         L.sop_pair_search.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
                                       ScaleFmt, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(_Outputs), C.c_void_p]
@@ -313,6 +315,10 @@ class Context:
         st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
         _check(lib().sop_sum_f32(self._h, C.c_void_p(x.data_ptr()), x.numel(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
         return out
+
+    def set_scale_rule(self, rule: int):
+        """SCALE_ABSMAX (default) or SCALE_ARGMAX for later pair_search calls."""
+        _check(lib().sop_set_scale_rule(self._h, rule), self._h)
 
     def partition(self, score, n_top: int, higher_is_better: bool = True, stream=None):
         """sop_partition on a contiguous float32 CUDA tensor of per-block scores; returns device

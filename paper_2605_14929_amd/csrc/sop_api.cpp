@@ -16,8 +16,8 @@
 
 #include "sop_kparams.h"
 
-extern "C" const void* sopk_search_kernel(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
-extern "C" int sopk_variant_index(int is_bf16, int g, int is_signed, int metric, int emit, int na8);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na8);
+extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na8);
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
@@ -59,8 +59,9 @@ struct sop_ctx {
     int sel_set = 0;
     unsigned long long* d_sums = nullptr; // [SOP_K_REPL][SOP_K_NCOL] layer sums, then the ticket counters; zero between calls
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
-    int occ_blocks[192];                  // resident workgroups per CU of each kernel variant (0 = unknown)
-    size_t occ_lds[192];
+    int scale_rule = 0;                   // 0: absmax, 1: argmax
+    int occ_blocks[288];                  // resident workgroups per CU of each kernel variant (0 = unknown)
+    size_t occ_lds[288];
     long long waves_override = 0;
     std::string err;
 };
@@ -360,6 +361,14 @@ extern "C" sop_status sop_set_pairs(sop_ctx* c, const int* pair_ab, int n_pairs)
     return SOP_OK;
 }
 
+extern "C" sop_status sop_set_scale_rule(sop_ctx* c, sop_scale_rule rule)
+{
+    if (!c) return SOP_EINVAL;
+    if (rule != SOP_SCALE_ABSMAX && rule != SOP_SCALE_ARGMAX) return fail(c, SOP_EINVAL, "sop_set_scale_rule: unknown rule");
+    c->scale_rule = rule == SOP_SCALE_ARGMAX ? 1 : 0;
+    return SOP_OK;
+}
+
 static sop_status shape_check(sop_ctx* c, int64_t M, int64_t K, int g)
 {
     if (M <= 0 || K <= 0) return fail(c, SOP_ESHAPE, "M and K must be positive");
@@ -429,6 +438,7 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     const int x = fmt.exp_bits, y = fmt.man_bits, w = fmt.sign_bits;
     if ((w != 0 && w != 1) || x < 1 || x > 8 || y < 0 || y > 10 || x + y > 15) return fail(c, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15");
     if (fmt.container_bits != 0 && (fmt.container_bits < w + x + y || fmt.container_bits > 16)) return fail(c, SOP_EFMT, "scale format: container must hold w+x+y bits and be at most 16");
+    if (c->scale_rule == 1 && w == 0) return fail(c, SOP_EFMT, "the argmax scale rule needs a scale word with a sign bit");
     const int bias = fmt.bias < 0 ? (1 << (x - 1)) - 1 : fmt.bias;
     const int max_code = fmt.max_code < 0 ? (1 << (x + y)) - 1 : fmt.max_code;
     if (max_code < 1 || max_code >= (1 << (x + y))) return fail(c, SOP_EFMT, "scale format: max_code out of range");
@@ -499,8 +509,9 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
                            2 * SOP_K_MAXA * sizeof(float4) + 4 * SOP_K_NCOL * sizeof(float);
     const int na8 = A > 6 ? 1 : 0;
-    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, w, (int)metric, emit, na8);
-    const int vi = sopk_variant_index(dtype == SOP_BF16, g, w, (int)metric, emit, na8);
+    const int sign_mode = c->scale_rule == 1 ? 2 : w;
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8);
+    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8);
     hipError_t e = hipSuccess;
     if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
         if (dyn_lds > 48 * 1024) {

@@ -121,16 +121,27 @@ __device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, f
 // Scale of one (group, sign): code q, signed scale ss, scaled weights x and their bin offsets.
 // boff receives the LDS byte address of each element's bin record (lds_neg = table address minus the
 // product the 24-bit multiply adds for the constant's exponent bits).
-template <int EPL>
+// ARGMAX: the scale maps the block's largest-magnitude element onto the endpoint of larger magnitude
+// and its sign follows from the two signs (per lane, returned in neg_out); otherwise the absmax rule
+// for the sign given in `negative`.
+template <int EPL, bool ARGMAX>
 __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, float nmax, bool negative, int a,
                                              const KParams& p, const Switches& sw, const float2* __restrict__ s_tab,
                                              const float4* __restrict__ s_gpar, uint32_t lds_neg,
-                                             int& q, float& ss, bool& nonzero, float (&x)[EPL], uint32_t (&boff)[EPL])
+                                             int& q, float& ss, bool& nonzero, float (&x)[EPL], uint32_t (&boff)[EPL], bool& neg_out)
 {
     const float4 gp = s_gpar[2 * a];                   // (t+, -t-, bin scale, bin offset): same address in every lane
     const float tp = gp.x, tn = gp.y;
     const bool unit_p = (sw.unit_tpos >> a) & 1u, unit_n = (sw.unit_tneg >> a) & 1u;
-    const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp, unit_n, unit_p) : ideal_scale(pmax, nmax, tp, tn, unit_p, unit_n);
+    float sstar;
+    if constexpr (ARGMAX) {
+        const bool x_pos = pmax >= nmax, t_pos = tp >= tn;          // ties: the positive element, the positive endpoint
+        sstar = (x_pos ? pmax : nmax) / (t_pos ? tp : tn);
+        negative = x_pos != t_pos;
+    } else {
+        sstar = negative ? ideal_scale(pmax, nmax, tn, tp, unit_n, unit_p) : ideal_scale(pmax, nmax, tp, tn, unit_p, unit_n);
+    }
+    neg_out = negative;
     q = encode_scale(sstar * p.pow2k, p);
     float s, rinv;
     decode_scale(q, p, s_tab, s, rinv);
@@ -140,8 +151,9 @@ __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, 
     const float sc = gp.z, off = gp.w;
     // the table covers a scale rounded down by up to the factor SOP_K_BIN_SAFE; beyond it (the scale
     // word saturated) the whole wavefront clamps its scaled weights into the table's range
-    const bool beyond = !(sstar * rinv <= SOP_K_BIN_SAFE);
-    if (__builtin_expect(__any(beyond) != 0, 0)) {
+    // (the argmax rule lets elements pass the smaller endpoint by any factor: always clamp)
+    const bool beyond = ARGMAX || !(sstar * rinv <= SOP_K_BIN_SAFE);
+    if (__builtin_expect(ARGMAX || __any(beyond) != 0, ARGMAX ? 1 : 0)) {
         const float4 g2 = s_gpar[2 * a + 1];           // (table range low, high, -, -)
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
@@ -413,9 +425,12 @@ __device__ __forceinline__ void widen(const RawBlk<BF16, EPL>& r, float (&w)[EPL
 
 // NA: atoms the kernel is unrolled for (6 or 8).  OCC: resident workgroups per compute unit the
 // register budget is set for.
-template <bool BF16, int EPL, int LPB, bool SIGNED, int METRIC, bool EMIT, int NA, int OCC>
+// SIGNMODE 0: the scale is positive; 1: both signs of the scale are tried and the better one kept
+// (signed scale word, absmax rule); 2: argmax rule, the rule fixes the sign.
+template <bool BF16, int EPL, int LPB, int SIGNMODE, int METRIC, bool EMIT, int NA, int OCC>
 __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
 {
+    constexpr bool SIGNED = SIGNMODE == 1, ARGMAX = SIGNMODE == 2;
     extern __shared__ __align__(16) char s_mem[];
     // LDS: bin table | (scale, reciprocal) table | group parameters | reduction scratch
     char* s_bins = s_mem;                                                         // [n_bins] records of 33 words
@@ -514,7 +529,7 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
         // state of the current scale group: positive sign, and negative sign for signed scale words
         int gq = 0, gq2 = 0;
         float gss = 0.0f, gss2 = 0.0f;
-        bool gnz = false, gnz2 = false;
+        bool gnz = false, gnz2 = false, gneg = false, gneg2 = false;
         float gx[EPL], gx2[SIGNED ? EPL : 1];
         uint32_t gboff[EPL], gboff2[SIGNED ? EPL : 1];
 
@@ -523,14 +538,14 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
             score[a] = 0.0f; den[a] = 1.0f; dlt[a] = 0.0f;
             if (__builtin_expect(a < sw.A, 1)) {
                 if (a == 0 || ((sw.grp_first >> a) & 1u)) {       // atom 0 always opens a group
-                    prepare_sign<EPL>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff);
-                    if constexpr (SIGNED) prepare_sign<EPL>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, gq2, gss2, gnz2, gx2, gboff2);
+                    prepare_sign<EPL, ARGMAX>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff, gneg);
+                    if constexpr (SIGNED) prepare_sign<EPL, false>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, gq2, gss2, gnz2, gx2, gboff2, gneg2);
                 }
                 const bool wide = EMIT && ((sw.wide >> a) & 1u);
                 uint32_t codes[EPL / 4];
                 Cand best;
                 int q = gq;
-                bool neg = false;
+                bool neg = ARGMAX ? gneg : false;
                 if constexpr (METRIC == 1) {
                     best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, gx, gboff, gss, a, wide, codes));
                     float bq = best.dy > 0.0f ? best.ny * fabsf(best.ny) : 0.0f;
@@ -574,7 +589,7 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
                     // the block's norm; otherwise the whole wavefront recomputes this atom directly
                     if (__builtin_expect(__any(best.weak) != 0, 0)) {
                         float ny1, dy1;
-                        direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, false, a, ny1, dy1);
+                        direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, ARGMAX ? gneg : false, a, ny1, dy1);
                         if constexpr (SIGNED) {
                             float ny2, dy2;
                             direct_cosine_sums<EPL, LPB>(cb, w, gx2, gboff2, gnz2, true, a, ny2, dy2);
@@ -694,13 +709,14 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
 // ---- kernel table of this part ----
 namespace {
 template <bool BF16, int EPL, int LPB>
-const void* pick_geom(bool is_signed, bool emit, bool na8)
+const void* pick_geom(int sign_mode, bool emit, bool na8)
 {
     constexpr int MT = SOPK_PART_METRIC;
 #define SOPK_FN(S, E, NA, OCC) reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, OCC>)
-    if (emit) return is_signed ? SOPK_FN(true, true, 8, 1) : SOPK_FN(false, true, 8, 1);
-    if (is_signed) return na8 ? SOPK_FN(true, false, 8, 1) : SOPK_FN(true, false, 6, 2);
-    return na8 ? SOPK_FN(false, false, 8, 2) : SOPK_FN(false, false, 6, 3);
+    if (emit) return sign_mode == 1 ? SOPK_FN(1, true, 8, 1) : sign_mode == 2 ? SOPK_FN(2, true, 8, 1) : SOPK_FN(0, true, 8, 1);
+    if (sign_mode == 1) return na8 ? SOPK_FN(1, false, 8, 1) : SOPK_FN(1, false, 6, 2);
+    if (sign_mode == 2) return na8 ? SOPK_FN(2, false, 8, 2) : SOPK_FN(2, false, 6, 3);
+    return na8 ? SOPK_FN(0, false, 8, 2) : SOPK_FN(0, false, 6, 3);
 #undef SOPK_FN
 }
 }  // namespace
@@ -709,13 +725,13 @@ const void* pick_geom(bool is_signed, bool emit, bool na8)
 #define SOPK_CAT(a, b, c) SOPK_CAT2(a, b, c)
 
 // g: block size; na8: more than six atoms in the alphabet
-extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int is_signed, int emit, int na8)
+extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na8)
 {
     constexpr bool B = SOPK_PART_BF16 != 0;
     switch (g) {
-        case 8:  return pick_geom<B, 8, 1>(is_signed, emit, na8);
-        case 16: return pick_geom<B, 16, 1>(is_signed, emit, na8);
-        case 32: return pick_geom<B, 16, 2>(is_signed, emit, na8);
-        default: return pick_geom<B, 16, 4>(is_signed, emit, na8);
+        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na8);
+        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na8);
+        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na8);
+        default: return pick_geom<B, 16, 4>(sign_mode, emit, na8);
     }
 }

@@ -18,7 +18,7 @@ def oracle_fmt(f: sop.ScaleFmt):
     return ops.make_fmt(f.sign_bits, f.exp_bits, f.man_bits, f.container_bits, f.bias, f.max_code)
 
 
-def run_gpu(W, c, tabs, g, fmt, k=0, metric=0, pairs=None, bf16=False, emit=True, ldw=None):
+def run_gpu(W, c, tabs, g, fmt, k=0, metric=0, pairs=None, bf16=False, emit=True, ldw=None, scale_rule=0):
     """W fp32 numpy (already on the bf16 grid when bf16=True).  Returns dict of numpy arrays."""
     import torch
     cx = ctx()
@@ -32,8 +32,12 @@ def run_gpu(W, c, tabs, g, fmt, k=0, metric=0, pairs=None, bf16=False, emit=True
         buf[:, :W.shape[1]] = Wt
         Wt = buf[:, :W.shape[1]]
     ct = torch.from_numpy(c).cuda()
-    out = cx.pair_search(Wt, ct, g, fmt, k=k, metric=metric, emit=emit)
-    torch.cuda.synchronize()
+    cx.set_scale_rule(scale_rule)
+    try:
+        out = cx.pair_search(Wt, ct, g, fmt, k=k, metric=metric, emit=emit)
+        torch.cuda.synchronize()
+    finally:
+        cx.set_scale_rule(0)
     r = dict(acos_pair=out.acos_pair.cpu().numpy()[:cx.n_pairs], acos_atom=out.acos_atom.cpu().numpy())
     if out.sel_words is not None:
         sw = out.sel_words.cpu().numpy()
