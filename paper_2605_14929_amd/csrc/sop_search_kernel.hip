@@ -713,7 +713,7 @@ const void* pick_geom(int sign_mode, bool emit, bool na8)
 {
     constexpr int MT = SOPK_PART_METRIC;
 #define SOPK_FN(S, E, NA, OCC) reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, OCC>)
-    if (emit) return sign_mode == 1 ? SOPK_FN(1, true, 8, 1) : sign_mode == 2 ? SOPK_FN(2, true, 8, 1) : SOPK_FN(0, true, 8, 1);
+    if (emit) return sign_mode == 1 ? SOPK_FN(1, true, 8, 2) : sign_mode == 2 ? SOPK_FN(2, true, 8, 2) : SOPK_FN(0, true, 8, 2);
     if (sign_mode == 1) return na8 ? SOPK_FN(1, false, 8, 1) : SOPK_FN(1, false, 6, 2);
     if (sign_mode == 2) return na8 ? SOPK_FN(2, false, 8, 2) : SOPK_FN(2, false, 6, 3);
     return na8 ? SOPK_FN(0, false, 8, 2) : SOPK_FN(0, false, 6, 3);
