@@ -174,6 +174,25 @@ sop_status sop_lloyd_1d(const double* samples, const double* weights, int64_t n_
  * endpoints are set to -1 and +1 and the entry nearest zero to 0. */
 sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g, int iters, float* out);
 
+/* The search over the linear layers of a model in one call (Section "Per-Layer Pair Search": the pair is
+ * chosen per layer; the result is a table of per-layer ACos for every atom and pair, which the format
+ * allocation of the later pipeline steps reads).  layers: HOST array of n_layers descriptors of DEVICE
+ * tensors that share dtype, block size, scale format and metric; each has its own shape, channel norms
+ * and layer shift.  acos_pair_table_dev: DEVICE [n_layers][P] doubles (may be NULL), acos_atom_table_dev:
+ * DEVICE [n_layers][A] doubles (may be NULL; not both).  sel_words_dev of a layer may be NULL (search
+ * mode without selector words).  Every layer is validated before the first launch; an error names the
+ * layer in sop_last_error().  The launches go to hip_stream back to back; asynchronous. */
+typedef struct {
+    const void*  W_dev;
+    int64_t      M, K, ldw;
+    const float* c_dev;
+    int          layer_shift_k;
+    void*        sel_words_dev;
+} sop_layer;
+sop_status sop_pair_search_layers(sop_ctx* ctx, const sop_layer* layers, int n_layers, sop_dtype dtype, int g,
+                                  sop_scale_fmt fmt, sop_metric metric, double* acos_pair_table_dev,
+                                  double* acos_atom_table_dev, void* hip_stream);
+
 /* ---- data-derived codebook ("DD" atom; Section "Per-Layer Pair Search", steps 1 and 3: a
  * data-adaptive atom is fitted per layer from a histogram of the layer's weights; design axis (iii):
  * uniform or channel-norm-weighted updates).  Two steps: a statistics pass on the GPU and a

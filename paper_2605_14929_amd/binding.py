@@ -27,6 +27,12 @@ class ScaleFmt(C.Structure):
                 ("bias", C.c_int), ("max_code", C.c_int)]
 
 
+class _Layer(C.Structure):
+    """sop_layer: one linear layer of a model-wide search."""
+    _fields_ = [("W", C.c_void_p), ("M", C.c_int64), ("K", C.c_int64), ("ldw", C.c_int64), ("c", C.c_void_p),
+                ("k", C.c_int), ("sel_words", C.c_void_p)]
+
+
 class WeightFmt(C.Structure):
     """sop_weight_fmt: ExMy weight grid."""
     _fields_ = [("exp_bits", C.c_int), ("man_bits", C.c_int), ("bias", C.c_int), ("max_code", C.c_int)]
@@ -85,6 +91,8 @@ def lib():
         L.sop_layer_scope_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, WeightFmt, ScaleFmt,
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_sum_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        L.sop_pair_search_layers.argtypes = [C.c_void_p, C.POINTER(_Layer), C.c_int, C.c_int, C.c_int, ScaleFmt, C.c_int,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_partition.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_pack_blocks.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, ScaleFmt, C.c_void_p, C.c_void_p, C.c_int,
                                       C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -315,6 +323,39 @@ class Context:
         st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
         _check(lib().sop_sum_f32(self._h, C.c_void_p(x.data_ptr()), x.numel(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
         return out
+
+    def pair_search_layers(self, layers, g, fmt: ScaleFmt, metric: int = SEL_WSE, shifts=None, want_sel: bool = False, stream=None):
+        """sop_pair_search_layers: layers is a list of (W [M,K], c [K]) CUDA tensors of one dtype.  Returns
+        (acos_pair [L,P] float64, acos_atom [L,A] float64, list of selector-word tensors or None);
+        asynchronous on the current (or given) stream."""
+        import torch
+        if not layers:
+            raise SopError(1, "no layers")
+        dev = layers[0][0].device
+        dtypes = {W.dtype for W, _ in layers}
+        if dtypes not in ({torch.bfloat16}, {torch.float32}):
+            raise SopError(1, "all layers must be bfloat16, or all float32")
+        dt = BF16 if torch.bfloat16 in dtypes else F32
+        n = len(layers)
+        arr = (_Layer * n)()
+        sels = [] if want_sel else None
+        for i, (W, c) in enumerate(layers):
+            if not (W.is_cuda and c.is_cuda) or W.dim() != 2 or W.stride(1) != 1 or c.dtype != torch.float32 or not c.is_contiguous():
+                raise SopError(1, f"layer {i}: W must be a 2-D CUDA tensor with contiguous rows, c a contiguous float32 CUDA tensor")
+            M, K = W.shape
+            arr[i].W, arr[i].M, arr[i].K, arr[i].ldw, arr[i].c = W.data_ptr(), M, K, W.stride(0), c.data_ptr()
+            arr[i].k = 0 if shifts is None else int(shifts[i])
+            if want_sel:
+                sw = torch.empty(M * K // g, dtype=torch.int16 if self.n_pairs <= 16 else torch.int32, device=dev)
+                sels.append(sw)
+                arr[i].sel_words = sw.data_ptr()
+        tp = torch.empty((n, max(self.n_pairs, 1)), dtype=torch.float64, device=dev)
+        ta = torch.empty((n, self.n_atoms), dtype=torch.float64, device=dev)
+        st = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        _check(lib().sop_pair_search_layers(self._h, arr, n, dt, g, fmt, metric,
+                                            C.c_void_p(tp.data_ptr()) if self.n_pairs else None, C.c_void_p(ta.data_ptr()),
+                                            C.c_void_p(st)), self._h)
+        return tp[:, :self.n_pairs], ta, sels
 
     def set_scale_rule(self, rule: int):
         """SCALE_ABSMAX (default) or SCALE_ARGMAX for later pair_search calls."""

@@ -416,9 +416,10 @@ static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, 
     return SOP_OK;
 }
 
-extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
-                                      const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
-                                      void* ws, size_t ws_bytes, const sop_outputs* out, void* stream)
+// launch == false: validate everything and prepare the tables the call needs, but launch nothing
+static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                   const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
+                                   void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !cn || !out) return fail(c, SOP_EINVAL, "sop_pair_search: W, c and out must not be NULL");
@@ -530,8 +531,45 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
     wg = std::min(wg, (p.total_units + 3) / 4);
     wg = std::max<long long>(std::min(wg, max_workgroups(c)), 1);
     p.n_waves = wg * 4;
+    if (!launch) return SOP_OK;
     e = sopk_launch(fn, &p, dyn_lds, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                      const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
+                                      void* ws, size_t ws_bytes, const sop_outputs* out, void* stream)
+{
+    return pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, ws, ws_bytes, out, stream, true);
+}
+
+extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers, int n_layers, sop_dtype dtype, int g,
+                                             sop_scale_fmt fmt, sop_metric metric, double* acos_pair_table, double* acos_atom_table,
+                                             void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!layers || n_layers < 1) return fail(c, SOP_EINVAL, "sop_pair_search_layers: no layers");
+    if (!acos_pair_table && !acos_atom_table) return fail(c, SOP_EINVAL, "sop_pair_search_layers: no output table");
+    if ((reinterpret_cast<uintptr_t>(acos_pair_table) | reinterpret_cast<uintptr_t>(acos_atom_table)) & 7u)
+        return fail(c, SOP_EINVAL, "sop_pair_search_layers: tables must be 8-byte aligned");
+    // first pass validates every layer (nothing is launched when one of them is rejected), second pass launches
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int l = 0; l < n_layers; ++l) {
+            const sop_layer& L = layers[l];
+            sop_outputs o;
+            std::memset(&o, 0, sizeof(o));
+            o.acos_pair = acos_pair_table && c->n_pairs > 0 ? acos_pair_table + (size_t)l * c->n_pairs : nullptr;
+            o.acos_atom = acos_atom_table ? acos_atom_table + (size_t)l * c->n_atoms : nullptr;
+            o.sel_words = L.sel_words_dev;
+            const sop_status s = pair_search_impl(c, L.W_dev, dtype, L.M, L.K, L.ldw, L.c_dev, g, fmt, L.layer_shift_k, metric,
+                                                  nullptr, 0, &o, stream, pass == 1);
+            if (s != SOP_OK) {
+                c->err = "layer " + std::to_string(l) + ": " + c->err;
+                return s;
+            }
+        }
+    }
     return SOP_OK;
 }
 

@@ -120,3 +120,19 @@ def layer_shapes_7b():
     """The 7 linear layers of one 7B-shaped transformer block: (name, M, K)."""
     return [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096), ("o", 4096, 4096),
             ("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]
+
+
+def model_7b_layers(n_blocks: int, seed: int = 4001, rows: int | None = None):
+    """Configuration 4: the linear layers of a 7B-shaped model, block by block.  Yields
+    (name, W fp32 on the bf16 grid [M,K], c fp32 [K], nu): Student-t weights whose tail index nu is
+    drawn per layer from U(3, 8), one log-normal (sigma 1) channel-norm vector per layer.  `rows`
+    truncates every layer to its first rows (tests)."""
+    r = _rng(seed)
+    for b in range(n_blocks):
+        for i, (name, M, K) in enumerate(layer_shapes_7b()):
+            nu = float(r.uniform(3.0, 8.0))
+            s = seed + 1000 * (b + 1) + 10 * i
+            Mr = M if rows is None else min(M, int(rows))
+            W = bf16_round(student_t_weights(Mr, K, nu, s))
+            c = channel_norms(K, 1.0, s + 1)
+            yield f"block{b}.{name}", W, c, nu
