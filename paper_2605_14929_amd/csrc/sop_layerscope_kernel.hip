@@ -46,6 +46,36 @@ __device__ __forceinline__ float exmy_decode(int q, int y, int bias, int k)
     return e > 0 ? nrm : sub;
 }
 
+// value of the nearest ExMy grid point of a non-negative binary32 (same rounding as exmy_encode
+// followed by exmy_decode, without forming the code).  At and above the grid's smallest normal value
+// the grid point is the binary32 pattern rounded to y mantissa bits: add just under (or exactly) half
+// of the dropped field, clear it; a carry out of the mantissa lands on the next binade by itself.
+// Below it the grid is uniform with step 2^(1-bias-y); that branch is taken by few lanes.
+struct ExmyGrid {
+    int y, bias;
+    uint32_t half_m1;      // (1 << (22 - y)) - 1
+    uint32_t keep;         // ~((1 << (23 - y)) - 1)
+    float min_normal;      // 2^(1-bias)
+    float quantum;         // 2^(1-bias-y)
+    float vmax;            // value of max_code
+};
+__device__ __forceinline__ float exmy_round_value(float a, bool tie_up, const ExmyGrid& gd)
+{
+    const uint32_t u = __float_as_uint(a);
+    float v = __uint_as_float((u + gd.half_m1 + (tie_up ? 1u : 0u)) & gd.keep);
+    if (a < gd.min_normal) {
+        asm volatile("");                              // a real branch: skipped when no lane is this small
+        const int E = (int)(u >> 23);
+        const int Ee = E > 0 ? E : 1;
+        const uint32_t m = (u & 0x7FFFFFu) | (E > 0 ? 0x800000u : 0u);
+        int S = 151 - gd.bias - gd.y - Ee;
+        S = S > 31 ? 31 : S;
+        const uint32_t q = (m + ((1u << (S - 1)) - (tie_up ? 0u : 1u))) >> S;
+        v = (float)q * gd.quantum;
+    }
+    return fminf(v, gd.vmax);
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
 #pragma unroll
@@ -108,12 +138,21 @@ __global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
     const long long wave = (long long)blockIdx.x * 4 + wv;
     const long long u0 = p.total_units * wave / p.n_waves, u1 = p.total_units * (wave + 1) / p.n_waves;
     float pmax = 0.0f, nmin = 0.0f;
-    for (long long u = u0; u < u1; ++u) {
-        const long long row = u / p.strips, st = u - row * p.strips;
-        const long long col0 = (st * 64 + lane) * EPL;
-        if (col0 < p.K) {
-            const uint4 t = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4));
-            const uint32_t v[4] = {t.x, t.y, t.z, t.w};
+    // four steps in flight: the loads of a group are issued before any of them is used
+    for (long long ub = u0; ub < u1; ub += 4) {
+        uint4 t[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const long long u = ub + i;
+            const long long row = u / p.strips, st = u - row * p.strips;
+            const long long col0 = (st * 64 + lane) * EPL;
+            t[i] = make_uint4(0, 0, 0, 0);
+            if (u < u1 && col0 < p.K)
+                t[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t v[4] = {t[i].x, t[i].y, t[i].z, t[i].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float a = BF16 ? __uint_as_float(v[j] << 16) : __uint_as_float(v[j]);
@@ -157,25 +196,50 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
     const int q = exmy_encode(sstar * p.pow2k, p.s_man, p.s_bias, p.s_max_code, false);
     const float s = exmy_decode(q, p.s_man, p.s_bias, p.k);
     const float r = s > 0.0f ? 1.0f / s : 0.0f;
+    ExmyGrid gd;
+    gd.y = p.w_man; gd.bias = p.w_bias;
+    gd.half_m1 = (1u << (22 - p.w_man)) - 1u;
+    gd.keep = ~((1u << (23 - p.w_man)) - 1u);
+    gd.min_normal = __uint_as_float((uint32_t)(1 - p.w_bias + 127) << 23);
+    gd.quantum = __uint_as_float((uint32_t)(1 - p.w_bias - p.w_man + 127) << 23);
+    gd.vmax = tp;
 
     double acc_w = 0.0, acc_u = 0.0, acc_n = 0.0;
+    // a wavefront walks down the rows of one 64-lane strip (its channel norms stay in registers) and
+    // keeps the next row's load in flight while it works on the current one
+    long long st = u0 / p.M, row = u0 - st * p.M, cur_st = -1;
+    float c[EPL];
+    auto load_w = [&](long long r, long long sidx) {
+        const long long col = (sidx * 64 + lane) * EPL;
+        uint4 t = make_uint4(0, 0, 0, 0);
+        if (col < p.K) t = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (r * p.ldw + col) * (BF16 ? 2 : 4));
+        return t;
+    };
+    uint4 nxt = make_uint4(0, 0, 0, 0);
+    if (u0 < u1) nxt = load_w(row, st);
     for (long long u = u0; u < u1; ++u) {
-        const long long row = u / p.strips, st = u - row * p.strips;
+        const uint4 t = nxt;
         const long long col0 = (st * 64 + lane) * EPL;
-        if (col0 >= p.K) continue;
-        const uint4 t = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4));
+        const long long my_row = row;
+        const bool valid = col0 < p.K;
+        if (st != cur_st) {
+            cur_st = st;
+#pragma unroll
+            for (int j = 0; j < EPL; j += 4) {
+                float4 cc = make_float4(1.f, 1.f, 1.f, 1.f);
+                if (p.c && valid) cc = *reinterpret_cast<const float4*>(p.c + col0 + j);
+                c[j] = cc.x; c[j + 1] = cc.y; c[j + 2] = cc.z; c[j + 3] = cc.w;
+            }
+        }
+        if (++row == p.M) { row = 0; ++st; }
+        if (u + 1 < u1) nxt = load_w(row, st);
+        if (!valid) continue;
         const uint32_t v[4] = {t.x, t.y, t.z, t.w};
-        float w[EPL], c[EPL];
+        float w[EPL];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (BF16) { w[2 * j] = __uint_as_float(v[j] << 16); w[2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u); }
             else w[j] = __uint_as_float(v[j]);
-        }
-#pragma unroll
-        for (int j = 0; j < EPL; j += 4) {
-            float4 cc = make_float4(1.f, 1.f, 1.f, 1.f);
-            if (p.c) cc = *reinterpret_cast<const float4*>(p.c + col0 + j);
-            c[j] = cc.x; c[j + 1] = cc.y; c[j + 2] = cc.z; c[j + 3] = cc.w;
         }
         float ew = 0.0f, eu = 0.0f, wn = 0.0f;
         uint32_t packed[EPL / 2];
@@ -184,8 +248,14 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
             const float x = w[j] * r;
             const bool negv = x < 0.0f;
             // nearest grid value, ties to the lower value: for a negative x that is the larger magnitude
-            const int m = exmy_encode(fabsf(x), p.w_man, p.w_bias, p.w_max_code, negv);
-            const float ym = exmy_decode(m, p.w_man, p.w_bias, 0);
+            int m = 0;
+            float ym;
+            if (CODES) {
+                m = exmy_encode(fabsf(x), p.w_man, p.w_bias, p.w_max_code, negv);
+                ym = exmy_decode(m, p.w_man, p.w_bias, 0);
+            } else {
+                ym = exmy_round_value(fabsf(x), negv, gd);
+            }
             const float y = negv ? -ym : ym;
             const float d = __fmaf_rn(-s, y, w[j]);
             const float cd = c[j] * d;
@@ -199,7 +269,7 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
         }
         acc_w += (double)ew; acc_u += (double)eu; acc_n += (double)wn;
         if (CODES) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(p.codes + row * p.K + col0);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(p.codes + my_row * p.K + col0);
 #pragma unroll
             for (int j = 0; j < EPL / 2; ++j) dst[j] = packed[j];
         }
