@@ -108,3 +108,13 @@ def test_steps_one_to_four_chained():
     ref = ops.pair_search(W, c, [La, rLb], g, oracle_fmt(fmt))
     compare(gpu, ref, 1)
     assert ref.acos_pair[0] > ref.acos_atom.max()
+
+
+def test_block_counts_of_the_large_configurations():
+    # 2 818 048 blocks (4096 x 11008, g = 16) and 14 680 064 blocks (28672 x 8192, g = 16): scores shaped
+    # like block cosines (crowded just below 1), both directions
+    rng = np.random.default_rng(13)
+    for N in (4096 * 11008 // 16, 28672 * 8192 // 16):
+        s = (1.0 - np.abs(rng.standard_normal(N)).astype(np.float32) * np.float32(0.004)).astype(np.float32)
+        for p_percent, higher in ((70.0, True), (12.5, False)):
+            check(s, PT.top_count(p_percent, N), higher)
