@@ -63,6 +63,22 @@ def parse_traffic():
     return None
 
 
+def timed_region(step, steps):
+    """K calls back to back between one HIP event before and one after on the launch stream (events
+    inside the loop would put a marker between every two kernels).  Returns (wall ms per step, GPU ms
+    per step)."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3, e0.elapsed_time(e1) / steps
+
+
 def bench_dd(args):
     """Statistics pass of the data-derived codebook on the headline layer (whole layer, 4096 bins):
     every weight is read once and adds its channel norm to one histogram bin."""
@@ -80,15 +96,7 @@ def bench_dd(args):
     for i in range(args.warmup):
         ctx.dd_histogram(bufs[i % len(bufs)], ct, g, H)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        ev[i][0].record()
-        hist = ctx.dd_histogram(bufs[i % len(bufs)], ct, g, H)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
-    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ms_step, ev_ms = timed_region(lambda i: ctx.dd_histogram(bufs[i % len(bufs)], ct, g, H), args.steps)
     alg_bytes = M * K * 2 + K * 4 + H * 8
     result = {
         "metric": "weights histogrammed/sec", "value": M * K / (ms_step * 1e-3), "unit": "weights/s", "n_gpus": 1,
@@ -133,15 +141,7 @@ def bench_fl(args):
     for i in range(args.warmup):
         ctx.scale_histogram(bufs[i % len(bufs)], g, 1.0, 1.0, fmt)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        ev[i][0].record()
-        hist = ctx.scale_histogram(bufs[i % len(bufs)], g, 1.0, 1.0, fmt)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
-    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ms_step, ev_ms = timed_region(lambda i: ctx.scale_histogram(bufs[i % len(bufs)], g, 1.0, 1.0, fmt), args.steps)
     alg_bytes = M * K * 2 + 640 * 8
     result = {
         "metric": "blocks scanned/sec", "value": M * K // g / (ms_step * 1e-3), "unit": "blocks/s", "n_gpus": 1,
@@ -189,15 +189,7 @@ def bench_ls(args):
     for i in range(args.warmup):
         ctx.layer_scope_error(bufs[i % len(bufs)], ct, wf, sf)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        ev[i][0].record()
-        out, _ = ctx.layer_scope_error(bufs[i % len(bufs)], ct, wf, sf)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) / args.steps * 1e3
-    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    ms_step, ev_ms = timed_region(lambda i: ctx.layer_scope_error(bufs[i % len(bufs)], ct, wf, sf), args.steps)
     alg_bytes = 2 * (M * K * 2) + K * 4 + 32                        # the layer is read twice: maxima, then rounding
     result = {
         "metric": "weights rounded/sec", "value": M * K / (ms_step * 1e-3), "unit": "weights/s", "n_gpus": 1,
@@ -456,18 +448,18 @@ def main():
         ctx.pair_search(bufs[i % len(bufs)], ct, g, fmt, out=out)
     torch.cuda.synchronize()
 
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
+    ms_step, ev_ms = timed_region(lambda i: ctx.pair_search(bufs[i % len(bufs)], ct, g, fmt, out=out), args.steps)
+    last_pair = out.acos_pair.cpu().numpy()[:P].copy()
+    # outside the timed region: the latency of single calls, each between its own pair of events
+    n_lat = min(args.steps, 50)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
+    for i in range(n_lat):
         ev[i][0].record()
         ctx.pair_search(bufs[i % len(bufs)], ct, g, fmt, out=out)
         ev[i][1].record()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = wall / args.steps * 1e3
-    ev_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
-    ev_min_ms = float(np.min([a.elapsed_time(b) for a, b in ev]))
+    lat_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    lat_min_ms = float(np.min([a.elapsed_time(b) for a, b in ev]))
 
     # algorithmic HBM bytes of one launch: every weight once, the channel norms once, the
     # per-block selector words and the ACos vectors out
@@ -478,7 +470,6 @@ def main():
     alg_ops = algorithmic_lane_ops(M * K, g, A, n_groups, P)
 
     # last step ran on buffer (steps-1) % n: check it against the oracle when that is buffer 0
-    gpu_pair = out.acos_pair.cpu().numpy()[:P].copy()
     result = {
         "metric": "block x atom evaluations/sec", "value": Nb * A / (ms_step * 1e-3), "unit": "block*atom evals/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
@@ -486,7 +477,7 @@ def main():
         "config": {"workload": "C3 down-projection 4096x11008 bf16, g=16, UE4M4, 6 atoms (NF4,SH4,BOF4 and negations), 15 pairs, search mode",
                    "M": M, "K": K, "g": g, "scale_format": cfg["fmt"], "atoms": list(cfg["atoms"]), "pairs": P,
                    "weight_dtype": "bf16", "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
-        "layer_latency_ms": ev_ms, "layer_latency_min_ms": ev_min_ms,
+        "layer_latency_ms": lat_ms, "layer_latency_min_ms": lat_min_ms,
         # the six-atom search is bound by the plain vector ALUs; the HBM view of the
         # same launch is given beside it
         "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",
