@@ -376,6 +376,48 @@ def bench_model(args):
     print(json.dumps(result))
 
 
+def bench_layer_search(args):
+    """The whole per-layer procedure on the headline layer: all 15 pairs of the six fixed atoms, then for
+    every atom a sweep over p = 50, 70, 85, 95 % with a second codebook fitted on the blocks the atom serves
+    worst (24 rankings, 24 masked histograms and fits, 6 scoring calls), the winner packed."""
+    import numpy as np
+    import torch
+    import paper_2605_14929_amd as sop
+    from paper_2605_14929_amd import layer_search as LSR
+    import sop_inputs as si
+    W, c, cfg = si.make_config("C3_down")
+    M, K, g = cfg["M"], cfg["K"], cfg["g"]
+    tabs = sop.build_alphabet(cfg["atoms"], bof_draws=si.normal_draws(1 << 20, 4242))
+    fmt = sop.fmt_by_name("UE4M3")                                     # one metabit for the selector
+    dev = torch.device("cuda", 0)
+    wt = torch.from_numpy(W).to(dev).to(torch.bfloat16)
+    ct = torch.from_numpy(c).to(dev)
+    ctx = sop.Context(0)
+    p_grid = (50.0, 70.0, 85.0, 95.0)
+    steps = min(args.steps, 5)
+    LSR.search_layer(ctx, wt, ct, g, fmt, tabs, p_grid=p_grid, pack=True)          # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        res = LSR.search_layer(ctx, wt, ct, g, fmt, tabs, p_grid=p_grid, pack=True)
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) / steps * 1e3
+    Nb = M * K // g
+    evals = Nb * (6 + 6 * 5 + 2)                                       # block x atom evaluations of the scoring calls
+    result = {
+        "metric": "layer pair-search latency", "value": ms_step, "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": 1,
+        "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "full per-layer search of the C3 down-projection 4096x11008 bf16, g=16, UE4M3: 15 fixed pairs, "
+                               "6 atoms x 4 values of p with a fitted second codebook, winner packed", "M": M, "K": K, "g": g,
+                   "p_grid": list(p_grid)},
+        "block_atom_evals_per_second": evals / (ms_step * 1e-3),
+        "winner": {"kind": res.kind, "a": res.a, "b": res.b, "p_percent": res.p_percent, "acos": res.acos,
+                   "best_fixed_pair_acos": float(res.acos_fixed.max())},
+        "roofline": None,
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -383,12 +425,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish", "model"],
+    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish", "model", "layer_search"],
                     help="pair_search (default): the headline six-atom search; dd_histogram: the statistics pass of the "
                          "data-derived codebook on the same layer; scale_histogram: the statistics pass of the per-layer "
                          "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer; finish: block ranking and pools, "
                          "masked histogram and packing after a two-atom search; model: all 224 layers of a 7B-shaped "
-                         "model in one call")
+                         "model in one call; layer_search: the whole per-layer procedure with the sweep over p")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (1 GiB read, 1 GiB written) a few times: the "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -412,6 +454,8 @@ def main():
         return bench_finish(args)
     if args.workload == "model":
         return bench_model(args)
+    if args.workload == "layer_search":
+        return bench_layer_search(args)
 
     W, c, cfg = si.make_config("C3_down")
     M, K, g = cfg["M"], cfg["K"], cfg["g"]

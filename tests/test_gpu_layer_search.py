@@ -1,0 +1,60 @@
+"""The whole per-layer search (fixed pairs, and for every atom a sweep over p with a refit second
+codebook) driven through the library, against the same procedure written with the oracle's parts."""
+import numpy as np
+import pytest
+
+import paper_2605_14929_amd as sop
+from paper_2605_14929_amd import layer_search as LSR
+from oracle import atoms as OA, dd as DD, pack as PK, partition as PT, pairsearch as ops
+import sop_inputs as si
+from gpu_util import oracle_fmt, ctx
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_search(W, c, g, fmt, atoms, p_grid, entries, iters, bins):
+    A = len(atoms)
+    r = ops.pair_search(W, c, atoms, g, fmt, want_codes=False)
+    fixed = r.acos_pair.copy()
+    fitted = {}
+    Nb = W.size // g
+    for a in range(A):
+        for p in p_grid:
+            _, pool_b, _ = PT.partition(r.blk_cos[a], PT.top_count(p, Nb), True)
+            Lb = OA.to_f32(DD.fit(DD.histogram(W, c, g, bins, block_mask=pool_b), entries, iters, atoms[0].astype(np.float64)))
+            rr = ops.pair_search(W, c, [atoms[a], Lb], g, fmt, want_codes=False)
+            fitted[(a, p)] = (float(rr.acos_pair[0]), Lb)
+    return fixed, fitted
+
+
+def test_search_of_one_layer_matches_the_oracle_procedure():
+    import torch
+    M, K, g = 128, 2048, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 6100, row_sigma=0.5, outlier_frac=0.001))
+    c = si.channel_norms(K, 1.0, 6101)
+    atoms = [OA.to_f32(OA.nf(4)), OA.to_f32(OA.sh(4)), OA.to_f32(OA.negate(OA.sh(4)))]
+    fmt = sop.fmt_by_name("UE4M3")
+    p_grid = (50.0, 75.0, 90.0)
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    res = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=p_grid, fit_iters=12, pack=True)
+    fixed, fitted = oracle_search(W, c, g, oracle_fmt(fmt), atoms, p_grid, 16, 12, 1024)
+    assert np.max(np.abs(res.acos_fixed - fixed)) <= 1e-6
+    # the GPU ranks its own binary32 cosines, the oracle its own: a block at the threshold may change
+    # pools, which moves the fitted grid and the pair's ACos by a hair
+    for key, (v, Lb) in fitted.items():
+        assert abs(res.acos_fitted[key] - v) <= 2e-5, key
+    ref_best = max([("fixed", float(v)) for v in fixed] + [("fitted", v) for v, _ in fitted.values()], key=lambda t: t[1])
+    assert abs(res.acos - ref_best[1]) <= 2e-5 and res.kind == ref_best[0]
+    # a second codebook fitted on the worst blocks beats every fixed pair on this layer, and more so
+    # than any single atom
+    assert res.kind == "fitted" and res.acos > fixed.max()
+    # the packed result decodes to a layer whose cosine is the reported one
+    w_, x_, y_, b_ = 0, 4, 3, 8
+    What = PK.reconstruct(res.words.cpu().numpy().view(np.uint16), res.payload.cpu().numpy(), res.n_bits, g, M, K,
+                          res.table_a, res.table_b, oracle_fmt(fmt), 0, w_, x_, y_, b_)
+    cw = np.tile(c.astype(np.float64), M).reshape(-1, g)
+    wb, hb = W.astype(np.float64).reshape(-1, g), What.astype(np.float64).reshape(-1, g)
+    num = (cw * wb * hb).sum(1); den = np.sqrt((cw * wb * wb).sum(1) * (cw * hb * hb).sum(1))
+    cosv = np.where(den > 0, num / np.where(den > 0, den, 1), 1.0)
+    assert abs(cosv.mean() - res.acos) <= 1e-6
