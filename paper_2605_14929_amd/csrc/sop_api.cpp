@@ -16,9 +16,9 @@
 
 #include "sop_kparams.h"
 
-extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na8);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na8, int* occ);
 extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na8);
-extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, size_t dyn_lds, void* stream);
+extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int occ, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
@@ -62,7 +62,6 @@ struct sop_ctx {
     int scale_rule = 0;                   // 0: absmax, 1: argmax
     int occ_blocks[288];                  // resident workgroups per CU of each kernel variant (0 = unknown)
     size_t occ_lds[288];
-    long long waves_override = 0;
     std::string err;
 };
 
@@ -107,7 +106,6 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     hipDeviceProp_t prop;
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipGetDeviceProperties"); }
     c->n_cu = prop.multiProcessorCount;
-    if (const char* s = getenv("SOP_WAVES_PER_SIMD")) { long long v = atoll(s); if (v >= 1 && v <= 8) c->waves_override = v; }
     if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
     if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * (SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1))) != hipSuccess ||
         (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * (SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1))) != hipSuccess) {
@@ -378,7 +376,6 @@ static sop_status shape_check(sop_ctx* c, int64_t M, int64_t K, int g)
 }
 
 // upper bound of the workgroups one launch uses: 8 resident wavefronts per SIMD
-static long long max_workgroups(const sop_ctx* c) { return (long long)c->n_cu * 8; }
 
 extern "C" sop_status sop_workspace_bytes(sop_ctx* c, int64_t M, int64_t K, int g, size_t* bytes)
 {
@@ -507,12 +504,13 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
         p.stab = t.dev;
         p.n_tab_codes = t.n;
     }
-    const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
-                           2 * SOP_K_MAXA * sizeof(float4) + 4 * SOP_K_NCOL * sizeof(float);
     const int na8 = A > 6 ? 1 : 0;
     const int sign_mode = c->scale_rule == 1 ? 2 : w;
-    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8);
+    int occ = 1;
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8, &occ);
     const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8);
+    const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
+                           2 * SOP_K_MAXA * sizeof(float4) + (size_t)(4 * occ) * SOP_K_NCOL * sizeof(float);
     hipError_t e = hipSuccess;
     if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
         if (dyn_lds > 48 * 1024) {
@@ -520,19 +518,19 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
             if (e != hipSuccess) return hipfail(c, e, "hipFuncSetAttribute(dynamic LDS)");
         }
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256, dyn_lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256 * occ, dyn_lds);
         if (e != hipSuccess) return hipfail(c, e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
         if (nb < 1) return fail(c, SOP_EHIP, "the kernel does not fit on a compute unit with this alphabet and scale format");
-        c->occ_blocks[vi] = std::min(nb, 8);
+        c->occ_blocks[vi] = nb;
         c->occ_lds[vi] = dyn_lds;
     }
-    // one contiguous range of (strip,row) steps per resident wavefront
-    long long wg = (long long)c->n_cu * (c->waves_override ? std::min<long long>(c->waves_override, c->occ_blocks[vi]) : c->occ_blocks[vi]);
-    wg = std::min(wg, (p.total_units + 3) / 4);
-    wg = std::max<long long>(std::min(wg, max_workgroups(c)), 1);
-    p.n_waves = wg * 4;
+    // one workgroup of 4*occ wavefronts per compute unit; each takes a contiguous range of (strip,row) steps
+    const long long waves_per_wg = 4 * occ;
+    long long wg = std::min<long long>(c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    wg = std::max<long long>(wg, 1);
+    p.n_waves = wg * waves_per_wg;
     if (!launch) return SOP_OK;
-    e = sopk_launch(fn, &p, dyn_lds, stream);
+    e = sopk_launch(fn, &p, (int)wg, occ, dyn_lds, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }

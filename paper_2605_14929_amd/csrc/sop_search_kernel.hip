@@ -423,27 +423,31 @@ __device__ __forceinline__ void widen(const RawBlk<BF16, EPL>& r, float (&w)[EPL
     }
 }
 
-// NA: atoms the kernel is unrolled for (6 or 8).  OCC: resident workgroups per compute unit the
-// register budget is set for.
+// NA: atoms the kernel is unrolled for (6 or 8).  OCC: wavefronts per SIMD the register budget is set
+// for; a workgroup is 4*OCC wavefronts and fills one compute unit on its own (one copy of the tables in
+// LDS per compute unit, one ticket per compute unit in the layer reduction).
 // SIGNMODE 0: the scale is positive; 1: both signs of the scale are tried and the better one kept
 // (signed scale word, absmax rule); 2: argmax rule, the rule fixes the sign.
 template <bool BF16, int EPL, int LPB, int SIGNMODE, int METRIC, bool EMIT, int NA, int OCC>
-__global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
+__global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
 {
     constexpr bool SIGNED = SIGNMODE == 1, ARGMAX = SIGNMODE == 2;
+    constexpr int NT = 256 * OCC, NW = 4 * OCC;                                   // threads, wavefronts of the workgroup
     extern __shared__ __align__(16) char s_mem[];
     // LDS: bin table | (scale, reciprocal) table | group parameters | reduction scratch
     char* s_bins = s_mem;                                                         // [n_bins] records of 33 words
     const size_t bins_bytes = ((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15;
     float2* s_tab = reinterpret_cast<float2*>(s_mem + bins_bytes);
     float4* s_gpar = reinterpret_cast<float4*>(s_mem + bins_bytes + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15));
-    float* s_red = reinterpret_cast<float*>(s_gpar + 2 * SOP_K_MAXA);              // [4][SOP_K_NCOL]
+    float* s_red = reinterpret_cast<float*>(s_gpar + 2 * SOP_K_MAXA);              // [NW][SOP_K_NCOL]
+    unsigned int* s_slot = reinterpret_cast<unsigned int*>(s_red);                // [4] wavefronts seen per SIMD (before s_red is used)
     {
         const int nw = p.n_bins * (SOP_K_BIN_BYTES / 4);
         const uint32_t* src = reinterpret_cast<const uint32_t*>(p.bins);
         uint32_t* dst = reinterpret_cast<uint32_t*>(s_bins);
-        for (int i = threadIdx.x; i < nw; i += 256) dst[i] = src[i];
-        for (int i = threadIdx.x; i < p.n_tab_codes; i += 256) s_tab[i] = p.stab[i];
+        for (int i = threadIdx.x; i < nw; i += NT) dst[i] = src[i];
+        for (int i = threadIdx.x; i < p.n_tab_codes; i += NT) s_tab[i] = p.stab[i];
+        if (threadIdx.x < 4) s_slot[threadIdx.x] = 0u;
         // (static indices: a lane-dependent index into the kernel arguments would copy them to scratch memory)
 #pragma unroll
         for (int a = 0; a < SOP_K_MAXA; ++a)
@@ -459,9 +463,23 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
     // the wavefront's number is the same in all its lanes: saying so keeps the row loop's counters
     // and tests in scalar registers
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const long long wave = (long long)blockIdx.x * 4 + wv;
-    const long long u0 = p.total_units * wave / p.n_waves;
-    const long long u1 = p.total_units * (wave + 1) / p.n_waves;
+    // The workgroup's range of steps is cut into NW equal parts, handed out in the order (SIMD, arrival
+    // on that SIMD): the wavefronts that share a SIMD hold neighbouring parts, so every SIMD of the
+    // compute unit gets a quarter of the range to within one step whatever the number of steps is.
+    // (bits 5:4 of the hardware id register are the SIMD the wavefront runs on)
+    const int simd = (int)__builtin_amdgcn_s_getreg(4 | (4 << 6) | ((2 - 1) << 11)) & 3;   // register 4, offset 4, 2 bits
+    int slot = 0;
+    if (lane == 0) slot = (int)atomicAdd(&s_slot[simd], 1u);
+    slot = __builtin_amdgcn_readfirstlane(slot);
+    __syncthreads();
+    int order = slot;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) order += j < simd ? (int)s_slot[j] : 0;
+    order = __builtin_amdgcn_readfirstlane(order);
+    __syncthreads();                                   // s_slot shares its words with the reduction scratch
+    const long long g0 = p.total_units * blockIdx.x / gridDim.x, g1 = p.total_units * (blockIdx.x + 1) / gridDim.x;
+    const long long u0 = g0 + (g1 - g0) * order / NW;
+    const long long u1 = g0 + (g1 - g0) * (order + 1) / NW;
 
     // running sums of 1 - cos: atoms, pairs, and the count of lanes whose block has zero norm
     float acca[SOP_K_MAXA], accp[SOP_K_MAXP], accz = 0.0f;
@@ -635,11 +653,11 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
         }
     }
 
-    // ---- per-workgroup partial sums: lanes, then the four wavefronts in order ----
+    // ---- per-workgroup partial sums: lanes, then the wavefronts in order ----
     auto wave_sum = [&](float v, int col) {
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) v += __shfl_xor(v, st, 64);
-        if (lane == 0) s_red[wv * SOP_K_NCOL + col] = v;
+        if (lane == 0) s_red[order * SOP_K_NCOL + col] = v;       // by part, not by wavefront: the sums do not depend on which wavefront took which part
     };
 #pragma unroll
     for (int i = 0; i < SOP_K_MAXA; ++i) wave_sum(i < NA ? acca[i] : 0.0f, i);
@@ -649,7 +667,10 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
     __syncthreads();
     if ((int)threadIdx.x < SOP_K_NCOL) {
         const int i = threadIdx.x;
-        const float v = (s_red[i] + s_red[SOP_K_NCOL + i]) + (s_red[2 * SOP_K_NCOL + i] + s_red[3 * SOP_K_NCOL + i]);
+        float v = 0.0f;
+#pragma unroll
+        for (int w4 = 0; w4 < NW; w4 += 4)
+            v += (s_red[w4 * SOP_K_NCOL + i] + s_red[(w4 + 1) * SOP_K_NCOL + i]) + (s_red[(w4 + 2) * SOP_K_NCOL + i] + s_red[(w4 + 3) * SOP_K_NCOL + i]);
         // 2^32 * v is exact in binary32 and far inside the 64-bit range (a workgroup's share is < 2^20)
         if (v != 0.0f) {
             // Atomics to one address are served one after the other (about 20 ns each), so the sums
@@ -684,7 +705,7 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
         __syncthreads();
         if ((int)threadIdx.x < SOP_K_NCOL) s_tot[threadIdx.x] = 0ull;
         __syncthreads();
-        for (int idx = threadIdx.x; idx < SOP_K_REPL * SOP_K_NCOL; idx += 256) {
+        for (int idx = threadIdx.x; idx < SOP_K_REPL * SOP_K_NCOL; idx += NT) {
             const unsigned long long v = atomicExch(p.sums + idx, 0ull);
             if (v) atomicAdd(&s_tot[idx % SOP_K_NCOL], v);
         }
@@ -708,15 +729,29 @@ __global__ __launch_bounds__(256, OCC) void search_kernel(const KParams p)
 
 // ---- kernel table of this part ----
 namespace {
+// wavefronts per SIMD each variant is built for: the largest number its register need allows (a lane
+// owning 8 elements needs far fewer registers than one owning 16; trying both signs, emitting codes and
+// eight atoms each need more; measured on the 4096 x 11008 layer where two choices were close)
+constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
+{
+    if (epl == 8) {
+        if (sign_mode == 1) return emit ? 2 : 3;
+        return (emit || na == 8) ? 3 : 4;
+    }
+    if (sign_mode == 1) return emit ? 1 : 2;
+    if (emit) return 2;
+    return (na == 8 || metric == 1) ? 2 : 3;        // the cosine metric keeps two more sums per candidate alive
+}
+
 template <bool BF16, int EPL, int LPB>
-const void* pick_geom(int sign_mode, bool emit, bool na8)
+const void* pick_geom(int sign_mode, bool emit, bool na8, int* occ)
 {
     constexpr int MT = SOPK_PART_METRIC;
-#define SOPK_FN(S, E, NA, OCC) reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, OCC>)
-    if (emit) return sign_mode == 1 ? SOPK_FN(1, true, 8, 2) : sign_mode == 2 ? SOPK_FN(2, true, 8, 2) : SOPK_FN(0, true, 8, 2);
-    if (sign_mode == 1) return na8 ? SOPK_FN(1, false, 8, 1) : SOPK_FN(1, false, 6, 2);
-    if (sign_mode == 2) return na8 ? SOPK_FN(2, false, 8, 2) : SOPK_FN(2, false, 6, 3);
-    return na8 ? SOPK_FN(0, false, 8, 2) : SOPK_FN(0, false, 6, 3);
+#define SOPK_FN(S, E, NA) (*occ = occ_for(EPL, S, E, NA, MT), reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, occ_for(EPL, S, E, NA, MT)>))
+    if (emit) return sign_mode == 1 ? SOPK_FN(1, true, 8) : sign_mode == 2 ? SOPK_FN(2, true, 8) : SOPK_FN(0, true, 8);
+    if (sign_mode == 1) return na8 ? SOPK_FN(1, false, 8) : SOPK_FN(1, false, 6);
+    if (sign_mode == 2) return na8 ? SOPK_FN(2, false, 8) : SOPK_FN(2, false, 6);
+    return na8 ? SOPK_FN(0, false, 8) : SOPK_FN(0, false, 6);
 #undef SOPK_FN
 }
 }  // namespace
@@ -724,14 +759,15 @@ const void* pick_geom(int sign_mode, bool emit, bool na8)
 #define SOPK_CAT2(a, b, c) a##b##_##c
 #define SOPK_CAT(a, b, c) SOPK_CAT2(a, b, c)
 
-// g: block size; na8: more than six atoms in the alphabet
-extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na8)
+// g: block size; na8: more than six atoms in the alphabet; *occ receives the wavefronts per SIMD the
+// variant is built for (its workgroup has 256 * occ threads)
+extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na8, int* occ)
 {
     constexpr bool B = SOPK_PART_BF16 != 0;
     switch (g) {
-        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na8);
-        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na8);
-        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na8);
-        default: return pick_geom<B, 16, 4>(sign_mode, emit, na8);
+        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na8, occ);
+        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na8, occ);
+        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na8, occ);
+        default: return pick_geom<B, 16, 4>(sign_mode, emit, na8, occ);
     }
 }
