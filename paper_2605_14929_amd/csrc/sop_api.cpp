@@ -38,6 +38,8 @@ float funord(int64_t k) { return k < 0 ? u2f(0x80000000u | (uint32_t)(-k)) : u2f
 
 }  // namespace
 
+static constexpr size_t kSumsWords = SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1;   // one set of layer sums and tickets, in 64-bit words
+
 struct sop_ctx {
     int device = 0;
     int n_cu = 0;
@@ -57,7 +59,9 @@ struct sop_ctx {
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
     int sel_set = 0;
-    unsigned long long* d_sums = nullptr; // [SOP_K_REPL][SOP_K_NCOL] layer sums, then the ticket counters; zero between calls
+    unsigned long long* d_sums = nullptr; // two sets of [SOP_K_REPL][SOP_K_NCOL] layer sums followed by their ticket counters; zero between calls
+    hipStream_t lane_stream[2] = {nullptr, nullptr};   // sop_pair_search_layers alternates layers between two streams of its own
+    hipEvent_t lane_event[3] = {nullptr, nullptr, nullptr};
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int scale_rule = 0;                   // 0: absmax, 1: argmax
     int occ_blocks[288];                  // resident workgroups per CU of each kernel variant (0 = unknown)
@@ -107,8 +111,8 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipGetDeviceProperties"); }
     c->n_cu = prop.multiProcessorCount;
     if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
-    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * (SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1))) != hipSuccess ||
-        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * (SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1))) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * 2 * kSumsWords)) != hipSuccess ||
+        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * 2 * kSumsWords)) != hipSuccess) {
         (void)hipFree(c->d_bins); if (c->d_sums) (void)hipFree(c->d_sums);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(layer sums)");
@@ -145,6 +149,8 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_ddacc) (void)hipFree(c->d_ddacc);
         if (c->d_ls) (void)hipFree(c->d_ls);
         if (c->d_sel) (void)hipFree(c->d_sel);
+        for (hipStream_t s : c->lane_stream) if (s) (void)hipStreamDestroy(s);
+        for (hipEvent_t ev : c->lane_event) if (ev) (void)hipEventDestroy(ev);
         for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
     }
     delete c;
@@ -416,7 +422,7 @@ static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, 
 // launch == false: validate everything and prepare the tables the call needs, but launch nothing
 static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                                    const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
-                                   void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch)
+                                   void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch, int sums_set = 0)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !cn || !out) return fail(c, SOP_EINVAL, "sop_pair_search: W, c and out must not be NULL");
@@ -487,8 +493,8 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
         p.pair_slot_w[pi / 4] |= (unsigned)q << (8 * (pi % 4));
         p.pair_pi[q] = (unsigned char)pi;
     }
-    p.sums = c->d_sums;
-    p.done = reinterpret_cast<unsigned int*>(c->d_sums + SOP_K_REPL * SOP_K_NCOL);
+    p.sums = c->d_sums + (size_t)sums_set * kSumsWords;
+    p.done = reinterpret_cast<unsigned int*>(p.sums + SOP_K_REPL * SOP_K_NCOL);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
     p.acos_atom = out->acos_atom;
     p.sel_words = c->n_pairs ? out->sel_words : nullptr;
@@ -551,8 +557,27 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
     if (!acos_pair_table && !acos_atom_table) return fail(c, SOP_EINVAL, "sop_pair_search_layers: no output table");
     if ((reinterpret_cast<uintptr_t>(acos_pair_table) | reinterpret_cast<uintptr_t>(acos_atom_table)) & 7u)
         return fail(c, SOP_EINVAL, "sop_pair_search_layers: tables must be 8-byte aligned");
+    // Two streams of the library's own take the layers in turn (each with its own set of layer sums): a
+    // layer's kernel fills every compute unit, so the next layer's workgroups move in as the current
+    // one's finish, and its table load and first rows overlap the current layer's tail.  Both streams
+    // start after the work already queued on the caller's stream; the caller's stream continues after both.
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 2 && e == hipSuccess; ++i)
+        if (!c->lane_stream[i]) e = hipStreamCreateWithFlags(&c->lane_stream[i], hipStreamNonBlocking);
+    for (int i = 0; i < 3 && e == hipSuccess; ++i)
+        if (!c->lane_event[i]) e = hipEventCreateWithFlags(&c->lane_event[i], hipEventDisableTiming);
+    if (e != hipSuccess) return hipfail(c, e, "stream / event creation");
+    const bool two_lanes = n_layers > 1;
     // first pass validates every layer (nothing is launched when one of them is rejected), second pass launches
     for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1 && two_lanes) {
+            if ((e = hipEventRecord(c->lane_event[2], (hipStream_t)stream)) != hipSuccess ||
+                (e = hipStreamWaitEvent(c->lane_stream[0], c->lane_event[2], 0)) != hipSuccess ||
+                (e = hipStreamWaitEvent(c->lane_stream[1], c->lane_event[2], 0)) != hipSuccess)
+                return hipfail(c, e, "stream fork");
+        }
         for (int l = 0; l < n_layers; ++l) {
             const sop_layer& L = layers[l];
             sop_outputs o;
@@ -560,12 +585,25 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
             o.acos_pair = acos_pair_table && c->n_pairs > 0 ? acos_pair_table + (size_t)l * c->n_pairs : nullptr;
             o.acos_atom = acos_atom_table ? acos_atom_table + (size_t)l * c->n_atoms : nullptr;
             o.sel_words = L.sel_words_dev;
+            const int lane = two_lanes ? l & 1 : 0;
+            void* st = two_lanes ? (void*)c->lane_stream[lane] : stream;
             const sop_status s = pair_search_impl(c, L.W_dev, dtype, L.M, L.K, L.ldw, L.c_dev, g, fmt, L.layer_shift_k, metric,
-                                                  nullptr, 0, &o, stream, pass == 1);
+                                                  nullptr, 0, &o, st, pass == 1, lane);
             if (s != SOP_OK) {
                 c->err = "layer " + std::to_string(l) + ": " + c->err;
+                if (pass == 1 && two_lanes) {                                 // rejoin what was launched
+                    for (int i = 0; i < 2; ++i)
+                        if (hipEventRecord(c->lane_event[i], c->lane_stream[i]) == hipSuccess) (void)hipStreamWaitEvent((hipStream_t)stream, c->lane_event[i], 0);
+                }
                 return s;
             }
+        }
+    }
+    if (two_lanes) {
+        for (int i = 0; i < 2; ++i) {
+            if ((e = hipEventRecord(c->lane_event[i], c->lane_stream[i])) != hipSuccess ||
+                (e = hipStreamWaitEvent((hipStream_t)stream, c->lane_event[i], 0)) != hipSuccess)
+                return hipfail(c, e, "stream join");
         }
     }
     return SOP_OK;
