@@ -22,6 +22,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+CLOCK_RAMP_MS = 60.0            # untimed repetition of the call before the timed region (GPU clock ramp)
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # Plain vector-ALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 fp32 lane-operations per
 # second (one operation per lane per clock, an fma counted once).  The published 157.3 TFLOP/s is
@@ -68,6 +69,15 @@ def timed_region(step, steps):
     inside the loop would put a marker between every two kernels).  Returns (wall ms per step, GPU ms
     per step)."""
     import torch
+    # The GPU raises its clock over the first 20-30 ms of load.  Whatever --warmup says, the same call is
+    # repeated untimed for CLOCK_RAMP_MS first, so that a short run is not timed inside that ramp.
+    t_ramp = time.perf_counter()
+    j = 0
+    while (time.perf_counter() - t_ramp) * 1e3 < CLOCK_RAMP_MS:
+        for _ in range(20):
+            step(j)
+            j += 1
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -121,6 +131,7 @@ def bench_dd(args):
         chk = ctx.dd_histogram(torch.from_numpy(W[:rows]).to(dev).to(torch.bfloat16), ct, g, H)
         torch.cuda.synchronize()
         result["parity_in_run"] = {"histogram_equal": bool(np.array_equal(chk.cpu().numpy(), ref))}
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
@@ -168,6 +179,7 @@ def bench_fl(args):
         h = chk.cpu().numpy()
         result["parity_in_run"] = {"histogram_equal": bool(np.array_equal(h, ref)),
                                    "k_star": sop.sop_layer_shift(h, M * K // g, fmt)[0], "k_star_oracle": k_ref[0]}
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
@@ -214,6 +226,7 @@ def bench_ls(args):
         torch.cuda.synchronize()
         o = chk.cpu().numpy()
         result["parity_in_run"] = {"scale_code_equal": int(o[3]) == ref["q"], "rel_err_weighted_error": abs(o[0] - ref["err_w"]) / ref["err_w"]}
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
@@ -303,6 +316,7 @@ def bench_finish(args):
         result["parity_in_run"] = {"words_equal": bool(np.array_equal(words.cpu().numpy().view(np.uint16), rw)),
                                    "payload_equal": bool(np.array_equal(payload.cpu().numpy(), rpl)),
                                    "pool_equal_on_gpu_scores": bool(np.array_equal(pb.cpu().numpy(), gp) and int(n_a.item()) == gn)}
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
@@ -373,6 +387,7 @@ def bench_model(args):
                                   "sample": f"layer {name} (4096x4096) of the 224, whole layer, {dt:.2f} s wall"}
         result["parity_in_run"] = {"layer": name, "max_abs_dacos_pair": float(np.max(np.abs(tp[0].cpu().numpy() - ref.acos_pair))),
                                    "max_abs_dacos_atom": float(np.max(np.abs(ta[0].cpu().numpy() - ref.acos_atom)))}
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
@@ -415,6 +430,7 @@ def bench_layer_search(args):
                    "best_fixed_pair_acos": float(res.acos_fixed.max())},
         "roofline": None,
     }
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
@@ -544,6 +560,7 @@ def main():
         d_acos = float(np.max(np.abs(chk.acos_pair.cpu().numpy()[:P] - ref.acos_pair)))
         sel_ok = bool(np.array_equal(chk.sel_words.cpu().numpy().view(np.uint16).astype(np.uint32), ref.sel_words))
         result["parity_in_run"] = {"max_abs_dACos": d_acos, "selector_bits_equal": sel_ok}
+    result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
 
 
