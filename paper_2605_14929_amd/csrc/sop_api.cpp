@@ -16,8 +16,8 @@
 
 #include "sop_kparams.h"
 
-extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na8, int* occ);
-extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na8);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int* occ);
+extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class);
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int occ, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
@@ -64,8 +64,8 @@ struct sop_ctx {
     hipEvent_t lane_event[3] = {nullptr, nullptr, nullptr};
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int scale_rule = 0;                   // 0: absmax, 1: argmax
-    int occ_blocks[288];                  // resident workgroups per CU of each kernel variant (0 = unknown)
-    size_t occ_lds[288];
+    int occ_blocks[432];                  // resident workgroups per CU of each kernel variant (0 = unknown)
+    size_t occ_lds[432];
     std::string err;
 };
 
@@ -510,11 +510,11 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
         p.stab = t.dev;
         p.n_tab_codes = t.n;
     }
-    const int na8 = A > 6 ? 1 : 0;
+    const int na_class = A > 6 ? 2 : (A > 2 ? 1 : 0);
     const int sign_mode = c->scale_rule == 1 ? 2 : w;
     int occ = 1;
-    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8, &occ);
-    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na8);
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, &occ);
+    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class);
     const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
                            2 * SOP_K_MAXA * sizeof(float4) + (size_t)(4 * occ) * SOP_K_NCOL * sizeof(float);
     hipError_t e = hipSuccess;

@@ -423,7 +423,7 @@ __device__ __forceinline__ void widen(const RawBlk<BF16, EPL>& r, float (&w)[EPL
     }
 }
 
-// NA: atoms the kernel is unrolled for (6 or 8).  OCC: wavefronts per SIMD the register budget is set
+// NA: atoms the kernel is unrolled for (2, 6 or 8).  OCC: wavefronts per SIMD the register budget is set
 // for; a workgroup is 4*OCC wavefronts and fills one compute unit on its own (one copy of the tables in
 // LDS per compute unit, one ticket per compute unit in the layer reduction).
 // SIGNMODE 0: the scale is positive; 1: both signs of the scale are tried and the better one kept
@@ -734,6 +734,10 @@ namespace {
 // eight atoms each need more; measured on the 4096 x 11008 layer where two choices were close)
 constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
 {
+    if (na == 2) {                                   // one or two atoms: fewer registers
+        if (epl == 8) return (sign_mode == 1 && emit) ? 3 : 4;
+        return sign_mode == 1 ? 2 : 3;
+    }
     if (epl == 8) {
         if (sign_mode == 1) return emit ? 2 : 3;
         return (emit || na == 8) ? 3 : 4;
@@ -743,15 +747,18 @@ constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
     return (na == 8 || metric == 1) ? 2 : 3;        // the cosine metric keeps two more sums per candidate alive
 }
 
+// na_class: 0 = at most two atoms, 1 = at most six, 2 = up to eight
 template <bool BF16, int EPL, int LPB>
-const void* pick_geom(int sign_mode, bool emit, bool na8, int* occ)
+const void* pick_geom(int sign_mode, bool emit, int na_class, int* occ)
 {
     constexpr int MT = SOPK_PART_METRIC;
 #define SOPK_FN(S, E, NA) (*occ = occ_for(EPL, S, E, NA, MT), reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, occ_for(EPL, S, E, NA, MT)>))
-    if (emit) return sign_mode == 1 ? SOPK_FN(1, true, 8) : sign_mode == 2 ? SOPK_FN(2, true, 8) : SOPK_FN(0, true, 8);
-    if (sign_mode == 1) return na8 ? SOPK_FN(1, false, 8) : SOPK_FN(1, false, 6);
-    if (sign_mode == 2) return na8 ? SOPK_FN(2, false, 8) : SOPK_FN(2, false, 6);
-    return na8 ? SOPK_FN(0, false, 8) : SOPK_FN(0, false, 6);
+#define SOPK_BY_SIGN(E, NA) (sign_mode == 1 ? SOPK_FN(1, E, NA) : sign_mode == 2 ? SOPK_FN(2, E, NA) : SOPK_FN(0, E, NA))
+    if (emit) return na_class == 0 ? SOPK_BY_SIGN(true, 2) : SOPK_BY_SIGN(true, 8);
+    if (na_class == 0) return SOPK_BY_SIGN(false, 2);
+    if (na_class == 1) return SOPK_BY_SIGN(false, 6);
+    return SOPK_BY_SIGN(false, 8);
+#undef SOPK_BY_SIGN
 #undef SOPK_FN
 }
 }  // namespace
@@ -759,15 +766,15 @@ const void* pick_geom(int sign_mode, bool emit, bool na8, int* occ)
 #define SOPK_CAT2(a, b, c) a##b##_##c
 #define SOPK_CAT(a, b, c) SOPK_CAT2(a, b, c)
 
-// g: block size; na8: more than six atoms in the alphabet; *occ receives the wavefronts per SIMD the
+// g: block size; na_class: 0 / 1 / 2 for alphabets of at most 2 / 6 / 8 atoms; *occ receives the wavefronts per SIMD the
 // variant is built for (its workgroup has 256 * occ threads)
-extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na8, int* occ)
+extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na_class, int* occ)
 {
     constexpr bool B = SOPK_PART_BF16 != 0;
     switch (g) {
-        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na8, occ);
-        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na8, occ);
-        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na8, occ);
-        default: return pick_geom<B, 16, 4>(sign_mode, emit, na8, occ);
+        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na_class, occ);
+        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na_class, occ);
+        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na_class, occ);
+        default: return pick_geom<B, 16, 4>(sign_mode, emit, na_class, occ);
     }
 }
