@@ -75,25 +75,34 @@ def search_layer(ctx: B.Context, W, c, g: int, fmt: B.ScaleFmt, atoms: list, p_g
     # (2) fitted second codebooks: steps 2 and 3 per (a, p), step 4 for one atom's whole sweep at once
     acos_fitted = {}
     p_list = list(p_grid)
+    # steps 2 and 3 of every (a, p): rankings and masked histograms queued back to back (the stream orders
+    # them); one copy to the host then waits for all of them, and the fits follow on the host
+    hists = []
     for a in range(A):
-        fitted = []
         for p in p_list:
             pool_b, _, _ = ctx.partition(blk_cos[a], top_count(p, Nb), True)
-            hist = ctx.dd_histogram(W, c if weighted_fit else None, g, fit_bins, 1, block_mask=pool_b)
-            h = hist.cpu().numpy()                     # synchronises: 8 KB
-            fitted.append(B.sop_dd_fit(h, fit_entries, fit_iters, init) if h.sum() > 0 else init.copy())
+            hists.append(ctx.dd_histogram(W, c if weighted_fit else None, g, fit_bins, 1, block_mask=pool_b))
+    hs = torch.stack(hists).cpu().numpy().reshape(A, len(p_list), fit_bins)       # synchronises: 8 KB per (a, p)
+    fitted_all = [[B.sop_dd_fit(h, fit_entries, fit_iters, init) if h.sum() > 0 else init.copy() for h in hs[a]] for a in range(A)]
+    # step 4: one atom's whole sweep is scored by one call; the calls are queued, their tables read at the end
+    pending = []
+    for a in range(A):
+        fitted = fitted_all[a]
         for s0 in range(0, len(p_list), 7):            # at most eight atoms in an alphabet
             chunk = fitted[s0:s0 + 7]
+            torch.cuda.synchronize()                   # the alphabet's tables are replaced: nothing may still read them
             ctx.set_alphabet([atoms[a]] + chunk)
             ctx.set_pairs([(0, 1 + i) for i in range(len(chunk))])
             o = ctx.pair_search(W, c, g, fmt, k=k, metric=metric)
-            torch.cuda.synchronize()
-            ac = o.acos_pair.cpu().numpy()[:len(chunk)]
-            for i, v in enumerate(ac):
-                p = p_list[s0 + i]
-                acos_fitted[(a, p)] = float(v)
-                if best is None or v > best[4]:
-                    best = ("fitted", a, -1, p, float(v), chunk[i])
+            pending.append((a, s0, chunk, o))
+    torch.cuda.synchronize()
+    for a, s0, chunk, o in pending:
+        ac = o.acos_pair.cpu().numpy()[:len(chunk)]
+        for i, v in enumerate(ac):
+            p = p_list[s0 + i]
+            acos_fitted[(a, p)] = float(v)
+            if best is None or v > best[4]:
+                best = ("fitted", a, -1, p, float(v), chunk[i])
     kind, a, b, p, acos, tb = best
     table_b = atoms[b] if kind == "fixed" else tb
     res = LayerResult(kind, a, b, p, atoms[a], table_b, acos, acos_fixed, acos_fitted)
