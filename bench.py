@@ -64,6 +64,30 @@ def parse_traffic():
     return None
 
 
+def parse_valu_counters():
+    """Vector-ALU figures of the headline kernel from the committed rocprofv3 counter summary
+    (profiles/search_kernel_c3down_valu.txt): wavefront VALU instructions and busy cycles per launch."""
+    path = os.path.join(ROOT, "profiles", "search_kernel_c3down_valu.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        line = line.split("#", 1)[0]
+        if "=" in line:
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v)
+            except ValueError:
+                pass
+    if "SQ_INSTS_VALU" not in vals or "SQ_BUSY_CYCLES" not in vals:
+        return None
+    cycles = vals["SQ_BUSY_CYCLES"] / 32.0                               # the counter sums over 32 shader engines
+    return {"source": "profiles/search_kernel_c3down_valu.txt (rocprofv3 --pmc, same command)",
+            "wave_valu_instructions_per_launch": vals["SQ_INSTS_VALU"],
+            "valu_busy_frac": vals["SQ_INSTS_VALU"] / 1024.0 * 4.0 / cycles,   # 1024 SIMDs, 4 cycles per wavefront instruction
+            "executed_lane_ops_per_weight": vals["SQ_INSTS_VALU"] * 64.0 / (4096 * 11008)}
+
+
 def timed_region(step, steps):
     """K calls back to back between one HIP event before and one after on the launch stream (events
     inside the loop would put a marker between every two kernels).  Returns (wall ms per step, GPU ms
@@ -516,6 +540,7 @@ def main():
     torch.cuda.synchronize()
     lat_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
     lat_min_ms = float(np.min([a.elapsed_time(b) for a, b in ev]))
+    lat_med_ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
 
     # algorithmic HBM bytes of one launch: every weight once, the channel norms once, the
     # per-block selector words and the ACos vectors out
@@ -533,7 +558,8 @@ def main():
         "config": {"workload": "C3 down-projection 4096x11008 bf16, g=16, UE4M4, 6 atoms (NF4,SH4,BOF4 and negations), 15 pairs, search mode",
                    "M": M, "K": K, "g": g, "scale_format": cfg["fmt"], "atoms": list(cfg["atoms"]), "pairs": P,
                    "weight_dtype": "bf16", "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
-        "layer_latency_ms": lat_ms, "layer_latency_min_ms": lat_min_ms,
+        "layer_latency_ms": lat_ms, "layer_latency_median_ms": lat_med_ms, "layer_latency_min_ms": lat_min_ms,
+        "valu_counters": parse_valu_counters(),
         # the six-atom search is bound by the plain vector ALUs; the HBM view of the
         # same launch is given beside it
         "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",
@@ -554,6 +580,11 @@ def main():
         dt = time.perf_counter() - t0
         result["cpu_baseline"] = {"value": rows * (K // g) * A / dt, "unit": "block*atom evals/s", "cores": ops.num_threads(),
                                   "kind": "oracle", "sample": f"the whole layer ({rows} rows), OpenMP over rows, {dt:.2f} s wall"}
+        t0 = time.perf_counter()
+        ops.pair_search(W[:256], c, tabs, g, ofmt, want_codes=False, n_threads=1)
+        dt1 = time.perf_counter() - t0
+        result["cpu_baseline_one_thread"] = {"value": 256 * (K // g) * A / dt1, "unit": "block*atom evals/s", "cores": 1, "kind": "oracle",
+                                             "sample": f"the first 256 rows, one thread, {dt1:.2f} s wall"}
         # parity of the benchmarked configuration in the same run (buffer 0)
         chk = ctx.pair_search(bufs[0], ct, g, fmt, out=out)
         torch.cuda.synchronize()
