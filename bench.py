@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 VALU_PEAK_TLOPS = 39.3216
 
 
-def algorithmic_lane_ops(n_weights, g, n_atoms, n_groups, n_pairs):
+def algorithmic_lane_ops(n_weights, g, n_atoms, n_groups, n_pairs, signs=1):
     """Lane-operations the method needs per launch, counted from its arithmetic, not from the code:
     per weight: widen, max, min, c*w, ||w||^2 fma                                   = 5
     per weight and scale group: x = w*r, clamp, bin fma, table address               = 4
@@ -40,8 +40,10 @@ def algorithmic_lane_ops(n_weights, g, n_atoms, n_groups, n_pairs):
     per block and atom: chunk add 1, cosine 5, accumulate 2                          = 8
     per block and pair: compare, select, add, two moves for the selector bit         = 5
     (the kernel as profiled executes 69.5 lane-operations per weight against these 62.9)"""
-    per_weight = 5 + 4 * n_groups + 6 * n_atoms
-    per_block = 12 * n_groups + 8 * n_atoms + 5 * n_pairs
+    # a signed scale word doubles the group and atom work (both signs are evaluated) and adds three
+    # operations per block and atom for keeping the better sign
+    per_weight = 5 + signs * (4 * n_groups + 6 * n_atoms)
+    per_block = signs * (12 * n_groups + 8 * n_atoms) + (signs - 1) * 3 * n_atoms + 5 * n_pairs
     return n_weights * per_weight + (n_weights // g) * per_block
 
 
@@ -472,6 +474,8 @@ def main():
                          "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer; finish: block ranking and pools, "
                          "masked histogram and packing after a two-atom search; model: all 224 layers of a 7B-shaped "
                          "model in one call; layer_search: the whole per-layer procedure with the sweep over p")
+    ap.add_argument("--config", default="C3_down", choices=["C1", "C2", "C3_up", "C3_down", "C5"],
+                    help="layer of the pair_search workload (default: the headline down-projection)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain copy kernel of known size (1 GiB read, 1 GiB written) a few times: the "
                          "reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -498,16 +502,25 @@ def main():
     if args.workload == "layer_search":
         return bench_layer_search(args)
 
-    W, c, cfg = si.make_config("C3_down")
+    W, c, cfg = si.make_config(args.config)
     M, K, g = cfg["M"], cfg["K"], cfg["g"]
     A = len(cfg["atoms"])
     P = A * (A - 1) // 2
     Nb = M * K // g
     tabs = sop.build_alphabet(cfg["atoms"], bof_draws=si.normal_draws(1 << 20, 4242))
     fmt = sop.fmt_by_name(cfg["fmt"])
+    headline = args.config == "C3_down"
+    label = {"C1": "C1 layer 256x1024 fp32", "C2": "C2 attention projection 4096x4096 bf16 (outliers, row scales)",
+             "C3_up": "C3 up-projection 11008x4096 bf16", "C3_down": "C3 down-projection 4096x11008 bf16",
+             "C5": "C5 70B-shaped MLP layer 28672x8192 bf16"}[args.config]
 
     dev = torch.device("cuda", 0)
-    w0 = torch.from_numpy(W).to(dev).to(torch.bfloat16)
+    w0 = torch.from_numpy(W).to(dev)
+    if cfg["dtype"] == "bf16":
+        w0 = w0.to(torch.bfloat16)
+    esz = w0.element_size()
+    if args.config == "C5":
+        args.buffers = min(args.buffers, 2)
     bufs = [w0] + [torch.roll(w0, shifts=17 * i, dims=0).contiguous() for i in range(1, args.buffers)]
     ct = torch.from_numpy(c).to(dev)
     ctx = sop.Context(0)
@@ -545,25 +558,26 @@ def main():
     # algorithmic HBM bytes of one launch: every weight once, the channel norms once, the
     # per-block selector words and the ACos vectors out
     sel_bytes = 2 if P <= 16 else 4                                       # one selector word per block
-    alg_bytes = M * K * 2 + K * 4 + Nb * sel_bytes + (A + P) * 8
+    alg_bytes = M * K * esz + K * 4 + Nb * sel_bytes + (A + P) * 8
     achieved = alg_bytes / (ev_ms * 1e-3) / 1e9
     n_groups = len({(float(t[0]), float(t[-1])) for t in tabs})           # atoms with equal endpoints share a scale
-    alg_ops = algorithmic_lane_ops(M * K, g, A, n_groups, P)
+    alg_ops = algorithmic_lane_ops(M * K, g, A, n_groups, P, signs=2 if fmt.sign_bits else 1)
 
     # last step ran on buffer (steps-1) % n: check it against the oracle when that is buffer 0
     result = {
         "metric": "block x atom evaluations/sec", "value": Nb * A / (ms_step * 1e-3), "unit": "block*atom evals/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "C3 down-projection 4096x11008 bf16, g=16, UE4M4, 6 atoms (NF4,SH4,BOF4 and negations), 15 pairs, search mode",
+        "config": {"workload": f"{label}, g={g}, {cfg['fmt']}, {A} atoms ({','.join(cfg['atoms'])}), {P} pairs, search mode"
+                               + (" (both signs of the scale tried per atom; an atom counts once)" if fmt.sign_bits else ""),
                    "M": M, "K": K, "g": g, "scale_format": cfg["fmt"], "atoms": list(cfg["atoms"]), "pairs": P,
-                   "weight_dtype": "bf16", "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
+                   "weight_dtype": cfg["dtype"], "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
         "layer_latency_ms": lat_ms, "layer_latency_median_ms": lat_med_ms, "layer_latency_min_ms": lat_min_ms,
-        "valu_counters": parse_valu_counters(),
+        "valu_counters": parse_valu_counters() if headline else None,
         # the six-atom search is bound by the plain vector ALUs; the HBM view of the
         # same launch is given beside it
         "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",
-                     "frac": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_PEAK_TLOPS, "traffic": parse_traffic(),
+                     "frac": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_PEAK_TLOPS, "traffic": parse_traffic() if headline else None,
                      "op_definition": "fp32 lane-operations, an fma counted once; peak = 256 CU x 64 lanes x 2.4 GHz",
                      "algorithmic_lane_ops_per_launch": alg_ops, "algorithmic_lane_ops_per_weight": alg_ops / (M * K),
                      "kernel": "sopk::search_kernel", "event_ms_per_launch": ev_ms},

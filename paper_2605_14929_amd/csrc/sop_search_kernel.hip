@@ -36,6 +36,7 @@
 // subtracted at the end.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "sop_kparams.h"
 
@@ -442,11 +443,31 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     float* s_red = reinterpret_cast<float*>(s_gpar + 2 * SOP_K_MAXA);              // [NW][SOP_K_NCOL]
     unsigned int* s_slot = reinterpret_cast<unsigned int*>(s_red);                // [4] wavefronts seen per SIMD (before s_red is used)
     {
-        const int nw = p.n_bins * (SOP_K_BIN_BYTES / 4);
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(p.bins);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(s_bins);
-        for (int i = threadIdx.x; i < nw; i += NT) dst[i] = src[i];
-        for (int i = threadIdx.x; i < p.n_tab_codes; i += NT) s_tab[i] = p.stab[i];
+        // 16 bytes per lane and four loads in flight before the first LDS write: a loop of one load, wait,
+        // one write would spend a round trip to L2 per word and cost more than ten microseconds per launch
+        // (the table has a multiple of four bins, so its size is a multiple of 16 bytes)
+        const int n16 = p.n_bins * (SOP_K_BIN_BYTES / 4) / 4;
+        const uint4* src = reinterpret_cast<const uint4*>(p.bins);
+        uint4* dst = reinterpret_cast<uint4*>(s_bins);
+        for (int i0 = threadIdx.x; i0 < n16; i0 += 4 * NT) {
+            uint4 t[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[j] = i0 + j * NT < n16 ? src[i0 + j * NT] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (i0 + j * NT < n16) dst[i0 + j * NT] = t[j];
+        }
+        {
+            float2 t[3];                                // at most 2048 codes: three per thread are enough for 768 threads or more
+            const int nt = p.n_tab_codes;
+            for (int i0 = threadIdx.x; i0 < nt; i0 += 3 * NT) {
+#pragma unroll
+                for (int j = 0; j < 3; ++j) t[j] = i0 + j * NT < nt ? p.stab[i0 + j * NT] : make_float2(0.f, 0.f);
+#pragma unroll
+                for (int j = 0; j < 3; ++j)
+                    if (i0 + j * NT < nt) s_tab[i0 + j * NT] = t[j];
+            }
+        }
         if (threadIdx.x < 4) s_slot[threadIdx.x] = 0u;
         // (static indices: a lane-dependent index into the kernel arguments would copy them to scratch memory)
 #pragma unroll
@@ -654,10 +675,23 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     }
 
     // ---- per-workgroup partial sums: lanes, then the wavefronts in order ----
+    // Sum over the 64 lanes with data-parallel-primitive moves on the vector ALU (a shuffle goes through
+    // the LDS crossbar, and 37 columns x 6 shuffles x 12 wavefronts cost 5 us per launch): within quads,
+    // within rows of 16 lanes, then row 0 into row 1 and row 2 into row 3, then rows 0-1 into row 3; the
+    // total is in lane 63.  The order of the additions is fixed.
     auto wave_sum = [&](float v, int col) {
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) v += __shfl_xor(v, st, 64);
-        if (lane == 0) s_red[order * SOP_K_NCOL + col] = v;       // by part, not by wavefront: the sums do not depend on which wavefront took which part
+        auto dpp_add = [](float x, auto ctrl, auto row_mask) {
+            const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false);
+            return x + __int_as_float(t);
+        };
+        using std::integral_constant;
+        v = dpp_add(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});     // quad_perm [1,0,3,2]
+        v = dpp_add(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});     // quad_perm [2,3,0,1]
+        v = dpp_add(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});    // row_half_mirror
+        v = dpp_add(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});    // row_mirror
+        v = dpp_add(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});    // row_bcast15 into rows 1 and 3
+        v = dpp_add(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});    // row_bcast31 into rows 2 and 3
+        if (lane == 63) s_red[order * SOP_K_NCOL + col] = v;      // by part, not by wavefront: the sums do not depend on which wavefront took which part
     };
 #pragma unroll
     for (int i = 0; i < SOP_K_MAXA; ++i) wave_sum(i < NA ? acca[i] : 0.0f, i);
