@@ -693,10 +693,17 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         v = dpp_add(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});    // row_bcast31 into rows 2 and 3
         if (lane == 63) s_red[order * SOP_K_NCOL + col] = v;      // by part, not by wavefront: the sums do not depend on which wavefront took which part
     };
+    // (columns of atoms and pairs beyond the kernel's unrolling are never touched: plain zeros, stored without a sum)
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXA; ++i) wave_sum(i < NA ? acca[i] : 0.0f, i);
+    for (int i = 0; i < SOP_K_MAXA; ++i) {
+        if (i < NA) wave_sum(acca[i], i);
+        else if (lane == 63) s_red[order * SOP_K_NCOL + i] = 0.0f;
+    }
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXP; ++i) wave_sum(accp[i], SOP_K_MAXA + i);     // never-touched columns are plain zeros
+    for (int i = 0; i < SOP_K_MAXP; ++i) {
+        if (kPairTab.second[i] < NA) wave_sum(accp[i], SOP_K_MAXA + i);
+        else if (lane == 63) s_red[order * SOP_K_NCOL + SOP_K_MAXA + i] = 0.0f;
+    }
     wave_sum(accz, SOP_K_ZCOL);
     __syncthreads();
     if ((int)threadIdx.x < SOP_K_NCOL) {
