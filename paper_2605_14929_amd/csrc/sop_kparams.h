@@ -7,7 +7,7 @@
 #define SOP_K_MAXP 28                /* pairs i < j among SOP_K_MAXA atoms           */
 #define SOP_K_NCOL (SOP_K_MAXA + SOP_K_MAXP + 1)   /* sum columns: atoms, pairs, zero-norm lane count */
 #define SOP_K_ZCOL (SOP_K_MAXA + SOP_K_MAXP)
-#define SOP_K_REPL 32                /* replicas of the layer sums (spreads same-address atomics) */
+#define SOP_K_REPL 8                 /* replicas of the layer sums (spreads same-address atomics) */
 #define SOP_K_MAXBINS 1024           /* bins of the element-search table                        */
 #define SOP_K_MAXTABCODES 2048       /* scale codes whose (scale, reciprocal) pair is tabulated */
 #define SOP_K_BIN_WORDS (4 * SOP_K_MAXA + 1)   /* words of one bin record (odd: conflict-free banks)  */
