@@ -35,8 +35,18 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
     // cmax = max_k c_k (order-independent), found by every workgroup for itself
     float cmax = 1.0f;
     if (p.c) {
+        // 16 bytes per lane and four loads in flight (a loop of single dependent loads would spend a round
+        // trip to L2 per element); K is a multiple of 8 and c is 16-byte aligned
         float v = 0.0f;
-        for (long long k = threadIdx.x; k < p.K; k += SOP_K_DD_THREADS) v = fmaxf(v, p.c[k]);
+        const long long k4 = p.K >> 2;
+        const float4* c4 = reinterpret_cast<const float4*>(p.c);
+        for (long long k0 = threadIdx.x; k0 < k4; k0 += 4 * SOP_K_DD_THREADS) {
+            float4 t[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[j] = k0 + j * SOP_K_DD_THREADS < k4 ? c4[k0 + j * SOP_K_DD_THREADS] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v = fmaxf(fmaxf(fmaxf(v, t[j].x), fmaxf(t[j].y, t[j].z)), t[j].w);
+        }
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) v = fmaxf(v, __shfl_xor(v, st, 64));
         if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = v;
@@ -125,18 +135,36 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
     __syncthreads();
     // the workgroup's histogram joins the layer's through 64-bit integer atomics; their returned
     // values are consumed so that they have completed before the workgroup takes its ticket
-    for (int i = threadIdx.x; i < H; i += SOP_K_DD_THREADS) {
-        const unsigned long long v = s_hist[i];
-        if (v) {
-            const unsigned long long before = atomicAdd(p.acc + i, v);
-            asm volatile("" :: "v"(before) : "memory");
+    // (all of a thread's atomics are issued before the first returned value is looked at: one round trip)
+    {
+        unsigned long long before[SOP_K_DD_MAXBINS / SOP_K_DD_THREADS];
+#pragma unroll
+        for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) {
+            const int i = threadIdx.x + j * SOP_K_DD_THREADS;
+            before[j] = 0ull;
+            if (i < H) {
+                const unsigned long long v = s_hist[i];
+                if (v) before[j] = atomicAdd(p.acc + i, v);
+            }
         }
+#pragma unroll
+        for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) asm volatile("" :: "v"(before[j]) : "memory");
     }
     __syncthreads();
     if (threadIdx.x == 0) s_flag = atomicAdd(p.done, 1u) == gridDim.x - 1 ? 1u : 0u;
     __syncthreads();
     if (s_flag) {
-        for (int i = threadIdx.x; i < H; i += SOP_K_DD_THREADS) p.hist[i] = (long long)atomicExch(p.acc + i, 0ull);
+        unsigned long long got[SOP_K_DD_MAXBINS / SOP_K_DD_THREADS];
+#pragma unroll
+        for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) {
+            const int i = threadIdx.x + j * SOP_K_DD_THREADS;
+            got[j] = i < H ? atomicExch(p.acc + i, 0ull) : 0ull;
+        }
+#pragma unroll
+        for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) {
+            const int i = threadIdx.x + j * SOP_K_DD_THREADS;
+            if (i < H) p.hist[i] = (long long)got[j];
+        }
         if (threadIdx.x == 0) atomicExch(p.done, 0u);
     }
 }

@@ -114,18 +114,38 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < 2 * SOP_K_FL_BINS; i += SOP_K_FL_THREADS) {
-        const unsigned int v = s_hist[i];
-        if (v) {
-            const unsigned long long before = atomicAdd(p.acc + i, (unsigned long long)v);
-            asm volatile("" :: "v"(before) : "memory");     // completed before the ticket below
+    // (all of a thread's atomics are issued before the first returned value is looked at: one round
+    // trip; the values are consumed so that the adds have completed before the ticket below)
+    constexpr int PER = (2 * SOP_K_FL_BINS + SOP_K_FL_THREADS - 1) / SOP_K_FL_THREADS;
+    {
+        unsigned long long before[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = threadIdx.x + j * SOP_K_FL_THREADS;
+            before[j] = 0ull;
+            if (i < 2 * SOP_K_FL_BINS) {
+                const unsigned int v = s_hist[i];
+                if (v) before[j] = atomicAdd(p.acc + i, (unsigned long long)v);
+            }
         }
+#pragma unroll
+        for (int j = 0; j < PER; ++j) asm volatile("" :: "v"(before[j]) : "memory");
     }
     __syncthreads();
     if (threadIdx.x == 0) s_flag = atomicAdd(p.done, 1u) == gridDim.x - 1 ? 1u : 0u;
     __syncthreads();
     if (s_flag) {
-        for (int i = threadIdx.x; i < 2 * SOP_K_FL_BINS; i += SOP_K_FL_THREADS) p.hist[i] = (long long)atomicExch(p.acc + i, 0ull);
+        unsigned long long got[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = threadIdx.x + j * SOP_K_FL_THREADS;
+            got[j] = i < 2 * SOP_K_FL_BINS ? atomicExch(p.acc + i, 0ull) : 0ull;
+        }
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = threadIdx.x + j * SOP_K_FL_THREADS;
+            if (i < 2 * SOP_K_FL_BINS) p.hist[i] = (long long)got[j];
+        }
         if (threadIdx.x == 0) atomicExch(p.done, 0u);
     }
 }
