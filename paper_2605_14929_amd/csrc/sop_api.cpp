@@ -55,7 +55,7 @@ struct sop_ctx {
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
-    unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and a finished-workgroup counter; zero between calls
+    unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and 17 ticket counters (u32); zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
     int sel_set = 0;
@@ -123,8 +123,8 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(histogram)");
     }
-    if ((e = hipMalloc((void**)&c->d_ls, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2))) != hipSuccess ||
-        (e = hipMemset(c->d_ls, 0, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2))) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_ls, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2 + 9))) != hipSuccess ||
+        (e = hipMemset(c->d_ls, 0, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2 + 9))) != hipSuccess) {
         (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); if (c->d_ls) (void)hipFree(c->d_ls);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(partials)");

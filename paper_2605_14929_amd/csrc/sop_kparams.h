@@ -135,7 +135,7 @@ struct LsParams {
     float pow2k;
     unsigned int* maxbits;           // [2] bit patterns of the largest positive / negative weight (zero between calls)
     unsigned long long* part;        // [SOP_K_LS_MAXWG][3] workgroup partials (bit patterns of doubles)
-    unsigned int* done;
+    unsigned int* done;              // [17] tickets: over the groups, then per group of workgroups
     double* out;                     // [4] weighted error, plain error, ||W||_c^2, scale code   (sum kernel: [1])
     uint16_t* codes;                 // optional [M*K] index into the ascending signed grid
 };

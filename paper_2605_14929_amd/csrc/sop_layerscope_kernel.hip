@@ -105,7 +105,19 @@ __device__ __forceinline__ bool finish_sums(const double (&v)[NV], unsigned long
     }
     __syncthreads();
     unsigned int* s_flag = reinterpret_cast<unsigned int*>(s_buf + 4 * NV);
-    if (threadIdx.x == 0) *s_flag = atomicAdd(done, 1u) == gridDim.x - 1 ? 1u : 0u;
+    // tickets in two levels (16 groups by workgroup number, then over the groups): atomics to one address
+    // are served one after the other, and a thousand workgroups finish within a few microseconds
+    if (threadIdx.x == 0) {
+        const unsigned int r = blockIdx.x % 16u;
+        const unsigned int in_group = (gridDim.x - r + 15u) / 16u;
+        const unsigned int groups = gridDim.x < 16u ? gridDim.x : 16u;
+        unsigned int last = 0u;
+        if (atomicAdd(done + 1 + r, 1u) == in_group - 1) {
+            atomicExch(done + 1 + r, 0u);
+            if (atomicAdd(done, 1u) == groups - 1) last = 1u;
+        }
+        *s_flag = last;
+    }
     __syncthreads();
     if (!*s_flag) return false;
     // last workgroup: every thread adds the partials of workgroups t, t+256, ... in that order, then a
