@@ -553,7 +553,13 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             if (i < 8) wn0 = __fmaf_rn(cw, w[i], wn0); else wn1 = __fmaf_rn(cw, w[i], wn1);
         }
         pmax = group_max<LPB>(pmax);
-        const float nmax = group_max<LPB>(-nmin);
+        float nmax = group_max<LPB>(-nmin);
+        // Lanes past the end of a row hold zero weights.  Their scale would be zero, which sends the whole
+        // wavefront through the scale word's subnormal branch on every row of the last strip; a unit
+        // maximum keeps them on the common path.  Nothing of theirs is written, and with zero weights they
+        // still add exactly 1 to every sum and to the count column, as a zero block does.
+        pmax = valid ? pmax : 1.0f;
+        nmax = valid ? nmax : 1.0f;
         const float wn = group_sum<LPB>(EPL == 16 ? wn0 + wn1 : wn0);
         const float qwn = 0.25f * wn;
         accz += wn > 0.0f ? 0.0f : 1.0f;
