@@ -465,6 +465,9 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     p.Bk = K / g; p.Nb = M * p.Bk;
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * M;
+    if (p.total_units >= (1ll << 31) || M >= (1ll << 31)) return fail(c, SOP_ESHAPE, "the layer has more than 2^31 strip rows");
+    p.M32 = (unsigned int)M;
+    p.m_magic = M == 1 ? 0xFFFFFFFFu : (unsigned int)((1ull << 32) / (unsigned long long)M);
     p.A = A; p.P = c->n_pairs; p.lpb = lpb;
     p.n_bins = c->n_bins;
     p.man_bits = y; p.bias = bias; p.max_code = max_code; p.k = k;
@@ -516,7 +519,7 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, &occ);
     const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class);
     const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
-                           2 * SOP_K_MAXA * sizeof(float4) + (size_t)(4 * occ) * SOP_K_NCOL * sizeof(float);
+                           2 * SOP_K_MAXA * sizeof(float4) + (1 + 2 * SOP_K_NCOL) * sizeof(unsigned long long);
     hipError_t e = hipSuccess;
     if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
         if (dyn_lds > 48 * 1024) {

@@ -54,6 +54,7 @@ struct KParams {
     long long strips;                // 64-lane strips per row
     long long total_units;           // strips * M
     long long n_waves;               // wavefronts launched (multiple of 4)
+    unsigned int M32, m_magic;       // M, and floor(2^32 / M) (2^32 - 1 for M = 1): step number -> (strip, row)
     int A, P, lpb;
     int n_bins;
     int n_tab_codes;                 // 0: scale and reciprocal are computed arithmetically
@@ -77,7 +78,7 @@ struct KParams {
     unsigned int pair_slot_w[SOP_K_MAXP / 4];          // byte pi%4 of word pi/4: output index of pair pi = pair_index(i,j)
     alignas(8) unsigned char pair_pi[SOP_K_MAXP + 4];  // pair_index(i,j) of output o
     // outputs
-    // layer sums of 1-cos in fixed point (2^-32 units): every workgroup adds its share with integer
+    // layer sums of 1-cos in fixed point (2^-24 units): every workgroup adds its share with integer
     // atomics (order-independent, so the result is reproducible); the workgroup that finishes last
     // turns them into the ACos outputs and leaves sums and counter at zero for the next call
     unsigned long long* sums;        // [SOP_K_REPL][SOP_K_NCOL]

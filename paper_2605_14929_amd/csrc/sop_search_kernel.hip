@@ -358,8 +358,8 @@ template <int PI> struct PairOf { static constexpr int i = kPairTab.first[PI], j
 // block's selector word, and the chosen atom's deficit into the pair's running sum.
 template <int PI, int NA, int METRIC>
 __device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, const float (&score)[SOP_K_MAXA],
-                                          const float (&den)[SOP_K_MAXA], const float (&dlt)[SOP_K_MAXA],
-                                          float (&accp)[SOP_K_MAXP], uint32_t& bits)
+                                          const float (&den)[SOP_K_MAXA], const int (&dlt)[SOP_K_MAXA],
+                                          int (&accp)[SOP_K_MAXP], uint32_t& bits)
 {
     constexpr int i = PairOf<PI>::i, j = PairOf<PI>::j;
     static_assert(pair_index(i, j) == PI, "pair enumeration");
@@ -367,7 +367,8 @@ __device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, 
         if (__builtin_expect((sw.pair_mask >> PI) & 1u, 1)) {
             // caller's pair (a,b): selector = "b strictly better than a" (ties keep a).  The internal
             // order may have swapped the two (b is internal i): then internal j keeps the block on a tie.
-            const float si = score[i], sj = score[j], ni = den[i], nj = den[j], di = dlt[i], dj = dlt[j];
+            const float si = score[i], sj = score[j], ni = den[i], nj = den[j];
+            const int di = dlt[i], dj = dlt[j];
             const bool flip = (sw.flip_mask >> PI) & 1u;
             // both comparisons are formed as lane masks; the wave-uniform flag picks one of them in
             // scalar registers (no branch, no per-lane select of booleans)
@@ -375,7 +376,7 @@ __device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, 
             const unsigned long long lt = __builtin_amdgcn_ballot_w64(METRIC == 1 ? lhs > rhs : lhs < rhs);
             const unsigned long long le = __builtin_amdgcn_ballot_w64(METRIC == 1 ? lhs >= rhs : lhs <= rhs);
             const bool pick_j = __builtin_amdgcn_inverse_ballot_w64(flip ? le : lt);
-            const float chosen = pick_j ? dj : di;
+            const int chosen = pick_j ? dj : di;
             accp[PI] += chosen;
             // bit = "internal j taken"; for swapped pairs the caller's selector is its complement, put
             // right by one xor with the mask of swapped pairs after the last pair
@@ -440,8 +441,10 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     const size_t bins_bytes = ((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15;
     float2* s_tab = reinterpret_cast<float2*>(s_mem + bins_bytes);
     float4* s_gpar = reinterpret_cast<float4*>(s_mem + bins_bytes + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15));
-    float* s_red = reinterpret_cast<float*>(s_gpar + 2 * SOP_K_MAXA);              // [NW][SOP_K_NCOL]
-    unsigned int* s_slot = reinterpret_cast<unsigned int*>(s_red);                // [4] wavefronts seen per SIMD (before s_red is used)
+    // reduction scratch: flag word, the final gather's totals, the workgroup's own totals (64-bit integers)
+    unsigned long long* s_red = reinterpret_cast<unsigned long long*>(s_gpar + 2 * SOP_K_MAXA);
+    unsigned long long* s_acc = s_red + 1 + SOP_K_NCOL;                           // [SOP_K_NCOL] this workgroup's sums
+    __shared__ unsigned int s_next[4];                                            // next step of each SIMD's share
     {
         // 16 bytes per lane and four loads in flight before the first LDS write: a loop of one load, wait,
         // one write would spend a round trip to L2 per word and cost more than ten microseconds per launch
@@ -468,7 +471,8 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                     if (i0 + j * NT < nt) s_tab[i0 + j * NT] = t[j];
             }
         }
-        if (threadIdx.x < 4) s_slot[threadIdx.x] = 0u;
+        if (threadIdx.x < 4) s_next[threadIdx.x] = 0u;
+        if ((int)threadIdx.x < SOP_K_NCOL) s_acc[threadIdx.x] = 0ull;
         // (static indices: a lane-dependent index into the kernel arguments would copy them to scratch memory)
 #pragma unroll
         for (int a = 0; a < SOP_K_MAXA; ++a)
@@ -484,41 +488,78 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     // the wavefront's number is the same in all its lanes: saying so keeps the row loop's counters
     // and tests in scalar registers
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // The workgroup's range of steps is cut into NW equal parts, handed out in the order (SIMD, arrival
-    // on that SIMD): the wavefronts that share a SIMD hold neighbouring parts, so every SIMD of the
-    // compute unit gets a quarter of the range to within one step whatever the number of steps is.
-    // (bits 5:4 of the hardware id register are the SIMD the wavefront runs on)
+    // The workgroup's range of steps is cut into four equal shares, one per SIMD (bits 5:4 of the hardware
+    // id register name the SIMD a wavefront runs on).  The wavefronts of a SIMD take the steps of its share
+    // one at a time from a counter in LDS: the hardware favours the oldest wavefront of a SIMD, and with
+    // fixed parts the younger ones would run on alone, at a fraction of the SIMD's rate, for a fifth of the
+    // kernel.  Which wavefront takes which step does not change any result: all sums are integers.
     const int simd = (int)__builtin_amdgcn_s_getreg(4 | (4 << 6) | ((2 - 1) << 11)) & 3;   // register 4, offset 4, 2 bits
-    int slot = 0;
-    if (lane == 0) slot = (int)atomicAdd(&s_slot[simd], 1u);
-    slot = __builtin_amdgcn_readfirstlane(slot);
-    __syncthreads();
-    int order = slot;
-#pragma unroll
-    for (int j = 0; j < 3; ++j) order += j < simd ? (int)s_slot[j] : 0;
-    order = __builtin_amdgcn_readfirstlane(order);
-    __syncthreads();                                   // s_slot shares its words with the reduction scratch
     const long long g0 = p.total_units * blockIdx.x / gridDim.x, g1 = p.total_units * (blockIdx.x + 1) / gridDim.x;
-    const long long u0 = g0 + (g1 - g0) * order / NW;
-    const long long u1 = g0 + (g1 - g0) * (order + 1) / NW;
+    const unsigned int sb = (unsigned int)(g0 + (g1 - g0) * simd / 4);
+    const unsigned int cnt = (unsigned int)(g0 + (g1 - g0) * (simd + 1) / 4) - sb;
+    auto grab = [&]() -> unsigned int {
+        unsigned int v = 0u;
+        if (lane == 0) v = atomicAdd(&s_next[simd], 1u);
+        return (unsigned int)__builtin_amdgcn_readfirstlane((int)v);
+    };
+    // step number -> (strip, row): steps run down the rows of a strip; division by multiplication with
+    // floor(2^32 / M), one correction (scalar arithmetic)
+    auto locate = [&](unsigned int u, long long& st, long long& row) {
+        unsigned int q = __umulhi(u, p.m_magic);
+        unsigned int r = u - q * p.M32;
+        if (r >= p.M32) { ++q; r -= p.M32; }
+        st = q; row = r;
+    };
 
-    // running sums of 1 - cos: atoms, pairs, and the count of lanes whose block has zero norm
-    float acca[SOP_K_MAXA], accp[SOP_K_MAXP], accz = 0.0f;
+    // running sums of 1 - cos in units of 2^-24 (integers: exact, so their order does not matter): atoms,
+    // pairs, and the lanes whose block has zero norm
+    int acca[SOP_K_MAXA], accp[SOP_K_MAXP], accz = 0;
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXA; ++i) acca[i] = 0.0f;
+    for (int i = 0; i < SOP_K_MAXA; ++i) acca[i] = 0;
 #pragma unroll
-    for (int i = 0; i < SOP_K_MAXP; ++i) accp[i] = 0.0f;
+    for (int i = 0; i < SOP_K_MAXP; ++i) accp[i] = 0;
+    // Lane sums of a column, exact: a lane holds at most 32 steps x 2^25, so the value is split at bit 15
+    // and both halves are added over the 64 lanes with data-parallel-primitive moves on the vector ALU
+    // (quads, rows of 16 lanes, row 0 into 1 and 2 into 3, rows 0-1 into 3; total in lane 63), which then
+    // adds the 64-bit total to the workgroup's sum.
+    auto lane_sum_to = [&](int v, int col) {
+        auto dpp_add = [](int x, auto ctrl, auto row_mask) {
+            return x + __builtin_amdgcn_update_dpp(0, x, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false);
+        };
+        using std::integral_constant;
+        int lo = v & 0x7FFF, hi = v >> 15;
+#define SOPK_DPP6(x)                                                                        \
+        x = dpp_add(x, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});    /* quad_perm [1,0,3,2] */ \
+        x = dpp_add(x, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});    /* quad_perm [2,3,0,1] */ \
+        x = dpp_add(x, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});   /* row_half_mirror */     \
+        x = dpp_add(x, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});   /* row_mirror */          \
+        x = dpp_add(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});   /* row_bcast15 into rows 1, 3 */ \
+        x = dpp_add(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});   /* row_bcast31 into rows 2, 3 */
+        SOPK_DPP6(lo)
+        SOPK_DPP6(hi)
+#undef SOPK_DPP6
+        if (lane == 63) atomicAdd(&s_acc[col], (unsigned long long)(((long long)hi << 15) + (long long)lo));
+    };
+    auto flush = [&]() {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) { lane_sum_to(acca[i], i); acca[i] = 0; }
+#pragma unroll
+        for (int i = 0; i < SOP_K_MAXP; ++i)
+            if (kPairTab.second[i] < NA) { lane_sum_to(accp[i], SOP_K_MAXA + i); accp[i] = 0; }
+        lane_sum_to(accz, SOP_K_ZCOL); accz = 0;
+    };
 
-    long long strip = u0 / p.M;
-    long long m = u0 - strip * p.M;
+    long long strip = 0, m = 0;
     long long cur_strip = -1;
     float cb[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) cb[i] = 0.0f;
+    unsigned int i_cur = grab(), i_nxt = grab();
     RawBlk<BF16, EPL> nxt;
-    if (u0 < u1) nxt = load_raw<BF16, EPL>(p, strip, m, lane);
+    if (i_cur < cnt) { locate(sb + i_cur, strip, m); nxt = load_raw<BF16, EPL>(p, strip, m, lane); }
+    int since_flush = 0;
 
-    for (long long u = u0; u < u1; ++u) {
+    while (i_cur < cnt) {
         // The uniform switches below are re-read every row.  Left loop-invariant, each test would be
         // hoisted out of the loop as a 64-bit lane mask and the hundred-odd masks would spill.
         Switches sw = {p.A, p.pair_mask, p.flip_mask, p.grp_first_mask, p.unit_tpos, p.unit_tneg, p.wide_mask};
@@ -537,8 +578,8 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         // ---- the block: one read from HBM, requested one step ahead ----
         float w[EPL];
         widen<BF16, EPL>(nxt, w);
-        if (++m == p.M) { m = 0; ++strip; }
-        if (u + 1 < u1) nxt = load_raw<BF16, EPL>(p, strip, m, lane);
+        if (i_nxt < cnt) { locate(sb + i_nxt, strip, m); nxt = load_raw<BF16, EPL>(p, strip, m, lane); }
+        const unsigned int i_nn = grab();              // the step after the next one; used at the end of this step
 
         // ---- block statistics ----
         float pmax = 0.0f, nmin = 0.0f, wn0 = 0.0f, wn1 = 0.0f;
@@ -562,7 +603,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         nmax = valid ? nmax : 1.0f;
         const float wn = group_sum<LPB>(EPL == 16 ? wn0 + wn1 : wn0);
         const float qwn = 0.25f * wn;
-        accz += wn > 0.0f ? 0.0f : 1.0f;
+        accz += wn > 0.0f ? 0 : (1 << 24);
 
         const long long blk_in_row = (cs * 64 + lane) / LPB;
         const long long blk = cm * p.Bk + blk_in_row;
@@ -570,7 +611,8 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
 
         // per-block results of every atom that the pair stage needs: score = err (WSE / MSE) or
         // q = num*|num| (COS, 0 for a zero reconstruction), den (COS only, 1 for a zero reconstruction), 1 - cos
-        float score[SOP_K_MAXA], den[SOP_K_MAXA], dlt[SOP_K_MAXA];
+        float score[SOP_K_MAXA], den[SOP_K_MAXA];
+        int dlt[SOP_K_MAXA];
         // state of the current scale group: positive sign, and negative sign for signed scale words
         int gq = 0, gq2 = 0;
         float gss = 0.0f, gss2 = 0.0f;
@@ -580,7 +622,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
 
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
-            score[a] = 0.0f; den[a] = 1.0f; dlt[a] = 0.0f;
+            score[a] = 0.0f; den[a] = 1.0f; dlt[a] = 0;
             if (__builtin_expect(a < sw.A, 1)) {
                 if (a == 0 || ((sw.grp_first >> a) & 1u)) {       // atom 0 always opens a group
                     prepare_sign<EPL, ARGMAX>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff, gneg);
@@ -649,8 +691,9 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 // cosine value; a vanishing reconstruction has ny = 0 and gives cos 0; a zero-norm block
                 // gives exactly 1 - 0 here and is corrected through the count column
                 const float da = __fmaf_rn(-best.ny, __frsqrt_rn(__fmaf_rn(wn, best.dy, 1.0e-37f)), 1.0f);
-                dlt[a] = da;
-                acca[a] += da;
+                const int ia = __float2int_rn(da * 16777216.0f);       // units of 2^-24
+                dlt[a] = ia;
+                acca[a] += ia;
                 if (EMIT) {
                     const long long ua = p.uidx[a];
                     if (p.scale_code && leader) p.scale_code[ua * p.Nb + blk] = (uint16_t)(q | (neg ? 0x8000 : 0));
@@ -678,55 +721,24 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             if (p.sel_u32) reinterpret_cast<uint32_t*>(p.sel_words)[blk] = bits;
             else reinterpret_cast<uint16_t*>(p.sel_words)[blk] = (uint16_t)bits;
         }
+        i_cur = i_nxt;
+        i_nxt = i_nn;
+        if (++since_flush == 32) { flush(); since_flush = 0; }   // a lane's sums stay below 2^31
     }
 
-    // ---- per-workgroup partial sums: lanes, then the wavefronts in order ----
-    // Sum over the 64 lanes with data-parallel-primitive moves on the vector ALU (a shuffle goes through
-    // the LDS crossbar, and 37 columns x 6 shuffles x 12 wavefronts cost 5 us per launch): within quads,
-    // within rows of 16 lanes, then row 0 into row 1 and row 2 into row 3, then rows 0-1 into row 3; the
-    // total is in lane 63.  The order of the additions is fixed.
-    auto wave_sum = [&](float v, int col) {
-        auto dpp_add = [](float x, auto ctrl, auto row_mask) {
-            const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false);
-            return x + __int_as_float(t);
-        };
-        using std::integral_constant;
-        v = dpp_add(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});     // quad_perm [1,0,3,2]
-        v = dpp_add(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});     // quad_perm [2,3,0,1]
-        v = dpp_add(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});    // row_half_mirror
-        v = dpp_add(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});    // row_mirror
-        v = dpp_add(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});    // row_bcast15 into rows 1 and 3
-        v = dpp_add(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});    // row_bcast31 into rows 2 and 3
-        if (lane == 63) s_red[order * SOP_K_NCOL + col] = v;      // by part, not by wavefront: the sums do not depend on which wavefront took which part
-    };
-    // (columns of atoms and pairs beyond the kernel's unrolling are never touched: plain zeros, stored without a sum)
-#pragma unroll
-    for (int i = 0; i < SOP_K_MAXA; ++i) {
-        if (i < NA) wave_sum(acca[i], i);
-        else if (lane == 63) s_red[order * SOP_K_NCOL + i] = 0.0f;
-    }
-#pragma unroll
-    for (int i = 0; i < SOP_K_MAXP; ++i) {
-        if (kPairTab.second[i] < NA) wave_sum(accp[i], SOP_K_MAXA + i);
-        else if (lane == 63) s_red[order * SOP_K_NCOL + SOP_K_MAXA + i] = 0.0f;
-    }
-    wave_sum(accz, SOP_K_ZCOL);
+    // ---- per-workgroup sums: what the lanes still hold joins the workgroup's integer sums in LDS ----
+    flush();
     __syncthreads();
     if ((int)threadIdx.x < SOP_K_NCOL) {
         const int i = threadIdx.x;
-        float v = 0.0f;
-#pragma unroll
-        for (int w4 = 0; w4 < NW; w4 += 4)
-            v += (s_red[w4 * SOP_K_NCOL + i] + s_red[(w4 + 1) * SOP_K_NCOL + i]) + (s_red[(w4 + 2) * SOP_K_NCOL + i] + s_red[(w4 + 3) * SOP_K_NCOL + i]);
-        // 2^32 * v is exact in binary32 and far inside the 64-bit range (a workgroup's share is < 2^20)
-        if (v != 0.0f) {
+        const unsigned long long v = s_acc[i];
+        if (v != 0ull) {
             // Atomics to one address are served one after the other (about 20 ns each), so the sums
             // are kept in SOP_K_REPL replicas chosen by workgroup number.  The returned value is
             // consumed so that the add has completed at the memory side before this workgroup
             // announces itself below (all traffic here is atomic: no cache write-back, which a fence
             // would cost on every workgroup, is needed).
-            const unsigned long long before = atomicAdd(p.sums + (blockIdx.x % SOP_K_REPL) * SOP_K_NCOL + i,
-                                                        (unsigned long long)__float2ll_rn(v * 4294967296.0f));
+            const unsigned long long before = atomicAdd(p.sums + (blockIdx.x % SOP_K_REPL) * SOP_K_NCOL + i, v);
             asm volatile("" :: "v"(before) : "memory");
         }
     }
@@ -748,7 +760,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     __syncthreads();
     if (*s_flag) {
         // gather the replicas (exact integer adds in LDS; the exchanges leave zeros for the next call)
-        unsigned long long* s_tot = reinterpret_cast<unsigned long long*>(s_red) + 1;
+        unsigned long long* s_tot = s_red + 1;
         __syncthreads();
         if ((int)threadIdx.x < SOP_K_NCOL) s_tot[threadIdx.x] = 0ull;
         __syncthreads();
@@ -767,7 +779,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + p.uidx[o] : nullptr; }
             else { col = SOP_K_MAXA + p.pair_pi[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
             const long long t = (long long)s_tot[col];
-            if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 4294967296.0)) / ((double)p.Nb * (double)p.lpb);
+            if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 16777216.0)) / ((double)p.Nb * (double)p.lpb);
         }
     }
 }
