@@ -488,12 +488,15 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     // the wavefront's number is the same in all its lanes: saying so keeps the row loop's counters
     // and tests in scalar registers
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // The workgroup's range of steps is cut into four equal shares, one per SIMD (bits 5:4 of the hardware
-    // id register name the SIMD a wavefront runs on).  The wavefronts of a SIMD take the steps of its share
-    // one at a time from a counter in LDS: the hardware favours the oldest wavefront of a SIMD, and with
-    // fixed parts the younger ones would run on alone, at a fraction of the SIMD's rate, for a fifth of the
-    // kernel.  Which wavefront takes which step does not change any result: all sums are integers.
-    const int simd = (int)__builtin_amdgcn_s_getreg(4 | (4 << 6) | ((2 - 1) << 11)) & 3;   // register 4, offset 4, 2 bits
+    // The workgroup's range of steps is cut into four equal shares, one per SIMD.  The hardware deals the
+    // wavefronts of a workgroup out to the four SIMDs in turn, so wavefronts w, w+4, w+8, ... share a SIMD
+    // (checked against the hardware id register on this GPU) and work on share w mod 4; were they dealt out
+    // otherwise, only the balance would suffer: every share has wavefronts of its own.  The wavefronts of
+    // a share take its steps one at a time from a counter in LDS: the hardware favours the oldest
+    // wavefront of a SIMD, and with fixed parts the younger ones would run on alone, at a fraction of the
+    // SIMD's rate, for a fifth of the kernel.  Which wavefront takes which step does not change any
+    // result: all sums are integers.
+    const int simd = wv & 3;
     const long long g0 = p.total_units * blockIdx.x / gridDim.x, g1 = p.total_units * (blockIdx.x + 1) / gridDim.x;
     const unsigned int sb = (unsigned int)(g0 + (g1 - g0) * simd / 4);
     const unsigned int cnt = (unsigned int)(g0 + (g1 - g0) * (simd + 1) / 4) - sb;
