@@ -81,13 +81,23 @@ def parse_valu_counters():
                 vals[k.strip()] = float(v)
             except ValueError:
                 pass
-    if "SQ_INSTS_VALU" not in vals or "SQ_BUSY_CYCLES" not in vals:
+    if "SQ_INSTS_VALU" not in vals:
         return None
-    cycles = vals["SQ_BUSY_CYCLES"] / 32.0                               # the counter sums over 32 shader engines
     return {"source": "profiles/search_kernel_c3down_valu.txt (rocprofv3 --pmc, same command)",
             "wave_valu_instructions_per_launch": vals["SQ_INSTS_VALU"],
-            "valu_busy_frac": vals["SQ_INSTS_VALU"] / 1024.0 * 4.0 / cycles,   # 1024 SIMDs, 4 cycles per wavefront instruction
             "executed_lane_ops_per_weight": vals["SQ_INSTS_VALU"] * 64.0 / (4096 * 11008)}
+
+
+def valu_counters(ev_ms):
+    """The committed counters with the rate they mean at this run's time per launch: executed vector-ALU
+    lane-operations per second and their fraction of the plain (unpacked) peak."""
+    v = parse_valu_counters()
+    if v is None:
+        return None
+    rate = v["wave_valu_instructions_per_launch"] * 64.0 / (ev_ms * 1e-3) / 1e12
+    v["executed_T_lane_ops_per_second"] = rate
+    v["valu_utilisation_of_peak"] = rate / VALU_PEAK_TLOPS
+    return v
 
 
 def timed_region(step, steps):
@@ -573,7 +583,7 @@ def main():
                    "M": M, "K": K, "g": g, "scale_format": cfg["fmt"], "atoms": list(cfg["atoms"]), "pairs": P,
                    "weight_dtype": cfg["dtype"], "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
         "layer_latency_ms": lat_ms, "layer_latency_median_ms": lat_med_ms, "layer_latency_min_ms": lat_min_ms,
-        "valu_counters": parse_valu_counters() if headline else None,
+        "valu_counters": valu_counters(ev_ms) if headline else None,
         # the six-atom search is bound by the plain vector ALUs; the HBM view of the
         # same launch is given beside it
         "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",

@@ -833,7 +833,9 @@ extern "C" sop_status sop_scale_histogram(sop_ctx* c, const void* W, sop_dtype d
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * M;
     const long long waves_per_wg = SOP_K_FL_THREADS / 64;
-    long long wg = std::min<long long>((long long)c->n_cu * 4, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    // one large workgroup per compute unit: every workgroup adds its counts to the same few words of the
+    // running histogram, and atomics to one address are served one after the other
+    long long wg = std::min<long long>((long long)c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
     p.n_waves = std::max<long long>(wg, 1) * waves_per_wg;
     p.t_pos = t_pos; p.t_neg = t_neg;
     int e_top;

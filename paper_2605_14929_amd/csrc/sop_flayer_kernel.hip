@@ -45,6 +45,7 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
 #pragma unroll
         for (int i = 0; i < NV; ++i) raw[i] = valid ? reinterpret_cast<const uint4*>(src)[i] : make_uint4(0, 0, 0, 0);
     };
+    const bool unit_ends = p.t_pos == 1.0f && p.t_neg == 1.0f;      // uniform: a scalar branch
     uint4 nxt[UNR][NV];
     bool nxt_valid[UNR];
 #pragma unroll
@@ -91,7 +92,9 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
             float nmax = -nmin;
 #pragma unroll
             for (int st = 1; st < LPB; st <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, st, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, st, 64)); }
-            const float sc = fmaxf(pmax / p.t_pos, nmax / p.t_neg);
+            float sc;
+            if (unit_ends) sc = fmaxf(pmax, nmax);        // x / 1 = x exactly: the divisions are skipped
+            else sc = fmaxf(pmax / p.t_pos, nmax / p.t_neg);
             const bool counted = valid && (lane % LPB == 0) && sc > 0.0f && sc <= 3.4028235e38f;   // an overflowed quotient is not counted
             int e = 0;
             const float mant = frexpf(counted ? sc : 1.0f, &e);   // sc = mant * 2^e, 1/2 <= mant < 1 (subnormals included)

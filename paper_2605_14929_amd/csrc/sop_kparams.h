@@ -110,7 +110,7 @@ struct DdParams {
 };
 
 /* Statistics pass of the per-layer scale shift */
-#define SOP_K_FL_THREADS 256
+#define SOP_K_FL_THREADS 1024
 #define SOP_K_FL_BINS 320            /* binary exponents -160 .. 159 of sc = m * 2^e, 1/2 <= m < 1 */
 struct FlParams {
     const void* W;
