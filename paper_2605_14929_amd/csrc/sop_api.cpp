@@ -16,9 +16,9 @@
 
 #include "sop_kparams.h"
 
-extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int* occ);
-extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class);
-extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int occ, size_t dyn_lds, void* stream);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int small_wg, int* occ, int* wgw);
+extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int small_wg);
+extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int wgw, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
@@ -38,6 +38,7 @@ float funord(int64_t k) { return k < 0 ? u2f(0x80000000u | (uint32_t)(-k)) : u2f
 
 }  // namespace
 
+static constexpr int kLanes = 2;          // streams of its own that sop_pair_search_layers deals the layers out to
 static constexpr size_t kSumsWords = SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1;   // one set of layer sums and tickets, in 64-bit words
 
 struct sop_ctx {
@@ -60,12 +61,12 @@ struct sop_ctx {
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
     int sel_set = 0;
     unsigned long long* d_sums = nullptr; // two sets of [SOP_K_REPL][SOP_K_NCOL] layer sums followed by their ticket counters; zero between calls
-    hipStream_t lane_stream[2] = {nullptr, nullptr};   // sop_pair_search_layers alternates layers between two streams of its own
-    hipEvent_t lane_event[3] = {nullptr, nullptr, nullptr};
+    hipStream_t lane_stream[kLanes] = {};   // sop_pair_search_layers deals the layers out to streams of its own
+    hipEvent_t lane_event[kLanes + 1] = {};  // one per stream (join) and one for the fork
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int scale_rule = 0;                   // 0: absmax, 1: argmax
-    int occ_blocks[432];                  // resident workgroups per CU of each kernel variant (0 = unknown)
-    size_t occ_lds[432];
+    int occ_blocks[864];                  // resident workgroups per CU of each kernel variant (0 = unknown)
+    size_t occ_lds[864];
     std::string err;
 };
 
@@ -111,8 +112,8 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipGetDeviceProperties"); }
     c->n_cu = prop.multiProcessorCount;
     if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
-    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * 2 * kSumsWords)) != hipSuccess ||
-        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * 2 * kSumsWords)) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * kLanes * kSumsWords)) != hipSuccess ||
+        (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * kLanes * kSumsWords)) != hipSuccess) {
         (void)hipFree(c->d_bins); if (c->d_sums) (void)hipFree(c->d_sums);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(layer sums)");
@@ -422,7 +423,8 @@ static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, 
 // launch == false: validate everything and prepare the tables the call needs, but launch nothing
 static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                                    const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
-                                   void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch, int sums_set = 0)
+                                   void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch, int sums_set = 0,
+                                   bool small_wg = false)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !cn || !out) return fail(c, SOP_EINVAL, "sop_pair_search: W, c and out must not be NULL");
@@ -515,9 +517,12 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     }
     const int na_class = A > 6 ? 2 : (A > 2 ? 1 : 0);
     const int sign_mode = c->scale_rule == 1 ? 2 : w;
-    int occ = 1;
-    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, &occ);
-    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class);
+    // small_wg (a stream of layers): workgroups of four wavefronts, several resident per compute unit, where
+    // the variant exists; otherwise, and for a single call, one workgroup fills a compute unit
+    int occ = 1, wgw = 1;
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, small_wg ? 1 : 0, &occ, &wgw);
+    const bool small = wgw < occ;
+    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, small ? 1 : 0);
     const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
                            2 * SOP_K_MAXA * sizeof(float4) + (1 + 2 * SOP_K_NCOL) * sizeof(unsigned long long);
     hipError_t e = hipSuccess;
@@ -527,19 +532,21 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
             if (e != hipSuccess) return hipfail(c, e, "hipFuncSetAttribute(dynamic LDS)");
         }
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256 * occ, dyn_lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256 * wgw, dyn_lds);
         if (e != hipSuccess) return hipfail(c, e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
         if (nb < 1) return fail(c, SOP_EHIP, "the kernel does not fit on a compute unit with this alphabet and scale format");
         c->occ_blocks[vi] = nb;
         c->occ_lds[vi] = dyn_lds;
     }
-    // one workgroup of 4*occ wavefronts per compute unit; each takes a contiguous range of (strip,row) steps
-    const long long waves_per_wg = 4 * occ;
-    long long wg = std::min<long long>(c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    // one workgroup of 4*occ wavefronts per compute unit (small workgroups: as many of four wavefronts as stay
+    // resident together, at most occ); each takes a contiguous range of (strip,row) steps
+    const long long waves_per_wg = 4 * wgw;
+    const long long wg_per_cu = small ? std::min(occ, c->occ_blocks[vi]) : 1;
+    long long wg = std::min<long long>((long long)c->n_cu * wg_per_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
     wg = std::max<long long>(wg, 1);
     p.n_waves = wg * waves_per_wg;
     if (!launch) return SOP_OK;
-    e = sopk_launch(fn, &p, (int)wg, occ, dyn_lds, stream);
+    e = sopk_launch(fn, &p, (int)wg, wgw, dyn_lds, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }
@@ -560,26 +567,27 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
     if (!acos_pair_table && !acos_atom_table) return fail(c, SOP_EINVAL, "sop_pair_search_layers: no output table");
     if ((reinterpret_cast<uintptr_t>(acos_pair_table) | reinterpret_cast<uintptr_t>(acos_atom_table)) & 7u)
         return fail(c, SOP_EINVAL, "sop_pair_search_layers: tables must be 8-byte aligned");
-    // Two streams of the library's own take the layers in turn (each with its own set of layer sums): a
-    // layer's kernel fills every compute unit, so the next layer's workgroups move in as the current
-    // one's finish, and its table load and first rows overlap the current layer's tail.  Both streams
+    // Two streams of the library's own take the layers in turn (each with its own set of layer sums), and
+    // the kernels run with workgroups of four wavefronts, several resident per compute unit: when a
+    // workgroup of the current layer ends, one of the next layer takes its place while the others keep the
+    // SIMDs busy, so a workgroup's table load, first row and reduction cost next to nothing.  Both streams
     // start after the work already queued on the caller's stream; the caller's stream continues after both.
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = hipSuccess;
-    for (int i = 0; i < 2 && e == hipSuccess; ++i)
+    const int n_lanes = std::min(n_layers, kLanes);     // (three or four streams measured no faster than two)
+    for (int i = 0; i < n_lanes && e == hipSuccess; ++i)
         if (!c->lane_stream[i]) e = hipStreamCreateWithFlags(&c->lane_stream[i], hipStreamNonBlocking);
-    for (int i = 0; i < 3 && e == hipSuccess; ++i)
+    for (int i = 0; i <= kLanes && e == hipSuccess; ++i)
         if (!c->lane_event[i]) e = hipEventCreateWithFlags(&c->lane_event[i], hipEventDisableTiming);
     if (e != hipSuccess) return hipfail(c, e, "stream / event creation");
-    const bool two_lanes = n_layers > 1;
+    const bool lanes = n_lanes > 1;
     // first pass validates every layer (nothing is launched when one of them is rejected), second pass launches
     for (int pass = 0; pass < 2; ++pass) {
-        if (pass == 1 && two_lanes) {
-            if ((e = hipEventRecord(c->lane_event[2], (hipStream_t)stream)) != hipSuccess ||
-                (e = hipStreamWaitEvent(c->lane_stream[0], c->lane_event[2], 0)) != hipSuccess ||
-                (e = hipStreamWaitEvent(c->lane_stream[1], c->lane_event[2], 0)) != hipSuccess)
-                return hipfail(c, e, "stream fork");
+        if (pass == 1 && lanes) {
+            e = hipEventRecord(c->lane_event[kLanes], (hipStream_t)stream);
+            for (int i = 0; i < n_lanes && e == hipSuccess; ++i) e = hipStreamWaitEvent(c->lane_stream[i], c->lane_event[kLanes], 0);
+            if (e != hipSuccess) return hipfail(c, e, "stream fork");
         }
         for (int l = 0; l < n_layers; ++l) {
             const sop_layer& L = layers[l];
@@ -588,22 +596,22 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
             o.acos_pair = acos_pair_table && c->n_pairs > 0 ? acos_pair_table + (size_t)l * c->n_pairs : nullptr;
             o.acos_atom = acos_atom_table ? acos_atom_table + (size_t)l * c->n_atoms : nullptr;
             o.sel_words = L.sel_words_dev;
-            const int lane = two_lanes ? l & 1 : 0;
-            void* st = two_lanes ? (void*)c->lane_stream[lane] : stream;
+            const int lane = lanes ? l % n_lanes : 0;
+            void* st = lanes ? (void*)c->lane_stream[lane] : stream;
             const sop_status s = pair_search_impl(c, L.W_dev, dtype, L.M, L.K, L.ldw, L.c_dev, g, fmt, L.layer_shift_k, metric,
-                                                  nullptr, 0, &o, st, pass == 1, lane);
+                                                  nullptr, 0, &o, st, pass == 1, lane, lanes);
             if (s != SOP_OK) {
                 c->err = "layer " + std::to_string(l) + ": " + c->err;
-                if (pass == 1 && two_lanes) {                                 // rejoin what was launched
-                    for (int i = 0; i < 2; ++i)
+                if (pass == 1 && lanes) {                                     // rejoin what was launched
+                    for (int i = 0; i < n_lanes; ++i)
                         if (hipEventRecord(c->lane_event[i], c->lane_stream[i]) == hipSuccess) (void)hipStreamWaitEvent((hipStream_t)stream, c->lane_event[i], 0);
                 }
                 return s;
             }
         }
     }
-    if (two_lanes) {
-        for (int i = 0; i < 2; ++i) {
+    if (lanes) {
+        for (int i = 0; i < n_lanes; ++i) {
             if ((e = hipEventRecord(c->lane_event[i], c->lane_stream[i])) != hipSuccess ||
                 (e = hipStreamWaitEvent((hipStream_t)stream, c->lane_event[i], 0)) != hipSuccess)
                 return hipfail(c, e, "stream join");

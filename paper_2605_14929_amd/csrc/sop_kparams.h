@@ -78,7 +78,7 @@ struct KParams {
     unsigned int pair_slot_w[SOP_K_MAXP / 4];          // byte pi%4 of word pi/4: output index of pair pi = pair_index(i,j)
     alignas(8) unsigned char pair_pi[SOP_K_MAXP + 4];  // pair_index(i,j) of output o
     // outputs
-    // layer sums of 1-cos in fixed point (2^-24 units): every workgroup adds its share with integer
+    // layer sums of 1-cos in fixed point (2^-22 units): every workgroup adds its share with integer
     // atomics (order-independent, so the result is reproducible); the workgroup that finishes last
     // turns them into the ACos outputs and leaves sums and counter at zero for the next call
     unsigned long long* sums;        // [SOP_K_REPL][SOP_K_NCOL]

@@ -426,15 +426,19 @@ __device__ __forceinline__ void widen(const RawBlk<BF16, EPL>& r, float (&w)[EPL
 }
 
 // NA: atoms the kernel is unrolled for (2, 6 or 8).  OCC: wavefronts per SIMD the register budget is set
-// for; a workgroup is 4*OCC wavefronts and fills one compute unit on its own (one copy of the tables in
-// LDS per compute unit, one ticket per compute unit in the layer reduction).
+// for.  WGW: wavefronts per SIMD of one workgroup.  WGW == OCC: a workgroup of 4*OCC wavefronts fills one
+// compute unit on its own (one copy of the tables in LDS per compute unit, one ticket per compute unit in
+// the layer reduction): the shape of a single call.  WGW == 1: workgroups of four wavefronts, OCC of them
+// resident per compute unit, for a stream of layers on two streams: when a workgroup of one layer ends, one
+// of the next layer takes its place while the others keep the SIMDs busy, so table load, first row and
+// reduction of a workgroup are partly hidden behind its neighbours on the same compute unit.
 // SIGNMODE 0: the scale is positive; 1: both signs of the scale are tried and the better one kept
 // (signed scale word, absmax rule); 2: argmax rule, the rule fixes the sign.
-template <bool BF16, int EPL, int LPB, int SIGNMODE, int METRIC, bool EMIT, int NA, int OCC>
-__global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
+template <bool BF16, int EPL, int LPB, int SIGNMODE, int METRIC, bool EMIT, int NA, int OCC, int WGW>
+__global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel(const KParams p)
 {
     constexpr bool SIGNED = SIGNMODE == 1, ARGMAX = SIGNMODE == 2;
-    constexpr int NT = 256 * OCC, NW = 4 * OCC;                                   // threads, wavefronts of the workgroup
+    constexpr int NT = 256 * WGW, NW = 4 * WGW;                                   // threads, wavefronts of the workgroup
     extern __shared__ __align__(16) char s_mem[];
     // LDS: bin table | (scale, reciprocal) table | group parameters | reduction scratch
     char* s_bins = s_mem;                                                         // [n_bins] records of 33 words
@@ -490,7 +494,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     // The workgroup's range of steps is cut into four equal shares, one per SIMD.  The hardware deals the
     // wavefronts of a workgroup out to the four SIMDs in turn, so wavefronts w, w+4, w+8, ... share a SIMD
-    // (checked against the hardware id register on this GPU) and work on share w mod 4; were they dealt out
+    // (as measured on this GPU) and work on share w mod 4; were they dealt out
     // otherwise, only the balance would suffer: every share has wavefronts of its own.  The wavefronts of
     // a share take its steps one at a time from a counter in LDS: the hardware favours the oldest
     // wavefront of a SIMD, and with fixed parts the younger ones would run on alone, at a fraction of the
@@ -514,14 +518,14 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         st = q; row = r;
     };
 
-    // running sums of 1 - cos in units of 2^-24 (integers: exact, so their order does not matter): atoms,
+    // running sums of 1 - cos in units of 2^-22 (integers: exact, so their order does not matter): atoms,
     // pairs, and the lanes whose block has zero norm
     int acca[SOP_K_MAXA], accp[SOP_K_MAXP], accz = 0;
 #pragma unroll
     for (int i = 0; i < SOP_K_MAXA; ++i) acca[i] = 0;
 #pragma unroll
     for (int i = 0; i < SOP_K_MAXP; ++i) accp[i] = 0;
-    // Lane sums of a column, exact: a lane holds at most 32 steps x 2^25, so the value is split at bit 15
+    // Lane sums of a column, exact: a lane holds at most 128 steps x 2^23, so the value is split at bit 15
     // and both halves are added over the 64 lanes with data-parallel-primitive moves on the vector ALU
     // (quads, rows of 16 lanes, row 0 into 1 and 2 into 3, rows 0-1 into 3; total in lane 63), which then
     // adds the 64-bit total to the workgroup's sum.
@@ -606,7 +610,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         nmax = valid ? nmax : 1.0f;
         const float wn = group_sum<LPB>(EPL == 16 ? wn0 + wn1 : wn0);
         const float qwn = 0.25f * wn;
-        accz += wn > 0.0f ? 0 : (1 << 24);
+        accz += wn > 0.0f ? 0 : (1 << 22);
 
         const long long blk_in_row = (cs * 64 + lane) / LPB;
         const long long blk = cm * p.Bk + blk_in_row;
@@ -693,15 +697,18 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 }
                 // cosine value; a vanishing reconstruction has ny = 0 and gives cos 0; a zero-norm block
                 // gives exactly 1 - 0 here and is corrected through the count column
-                const float da = __fmaf_rn(-best.ny, __frsqrt_rn(__fmaf_rn(wn, best.dy, 1.0e-37f)), 1.0f);
-                const int ia = __float2int_rn(da * 16777216.0f);       // units of 2^-24
+                // 3 - cos lies in [2, 4], where binary32 values are 2^-22 apart and their bit patterns count
+                // those steps: the fma's own rounding (nearest, ties to even) rounds 1 - cos to the unit of
+                // the integer sums, and pattern minus pattern of 2.0 is that integer (no conversion)
+                const float rs = __frsqrt_rn(__fmaf_rn(wn, best.dy, 1.0e-37f));
+                const int ia = (int)__float_as_uint(__fmaf_rn(-best.ny, rs, 3.0f)) - 0x40000000;
                 dlt[a] = ia;
                 acca[a] += ia;
                 if (EMIT) {
                     const long long ua = p.uidx[a];
                     if (p.scale_code && leader) p.scale_code[ua * p.Nb + blk] = (uint16_t)(q | (neg ? 0x8000 : 0));
                     if (p.blk_err && leader) p.blk_err[ua * p.Nb + blk] = best.err;
-                    if (p.blk_cos && leader) p.blk_cos[ua * p.Nb + blk] = wn > 0.0f ? 1.0f - da : 1.0f;
+                    if (p.blk_cos && leader) p.blk_cos[ua * p.Nb + blk] = wn > 0.0f ? 1.0f - __fmaf_rn(-best.ny, rs, 1.0f) : 1.0f;
                     if (p.codes && valid) {
                         if (!wide) {
                             uint8_t* dst = p.codes + p.code_off[a] + (cm * p.K + col0) / 2;
@@ -726,7 +733,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         }
         i_cur = i_nxt;
         i_nxt = i_nn;
-        if (++since_flush == 32) { flush(); since_flush = 0; }   // a lane's sums stay below 2^31
+        if (++since_flush == 128) { flush(); since_flush = 0; }   // a step adds at most 2^23: a lane's sums stay below 2^31
     }
 
     // ---- per-workgroup sums: what the lanes still hold joins the workgroup's integer sums in LDS ----
@@ -782,7 +789,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             if (o < p.A) { col = o; dst = p.acos_atom ? p.acos_atom + p.uidx[o] : nullptr; }
             else { col = SOP_K_MAXA + p.pair_pi[o - p.A]; dst = p.acos_pair ? p.acos_pair + (o - p.A) : nullptr; }
             const long long t = (long long)s_tot[col];
-            if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 16777216.0)) / ((double)p.Nb * (double)p.lpb);
+            if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 4194304.0)) / ((double)p.Nb * (double)p.lpb);
         }
     }
 }
@@ -809,12 +816,29 @@ constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
     return (na == 8 || metric == 1) ? 2 : 3;        // the cosine metric keeps two more sums per candidate alive
 }
 
-// na_class: 0 = at most two atoms, 1 = at most six, 2 = up to eight
-template <bool BF16, int EPL, int LPB>
-const void* pick_geom(int sign_mode, bool emit, int na_class, int* occ)
+// one variant: *occ = wavefronts per SIMD its registers allow, *wgw = wavefronts per SIMD of one workgroup
+// (small workgroups exist for the searches of more than two atoms that write no per-block planes)
+template <bool BF16, int EPL, int LPB, int S, bool E, int NA>
+const void* variant(bool small_wg, int* occ, int* wgw)
 {
     constexpr int MT = SOPK_PART_METRIC;
-#define SOPK_FN(S, E, NA) (*occ = occ_for(EPL, S, E, NA, MT), reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, occ_for(EPL, S, E, NA, MT)>))
+    constexpr int O = occ_for(EPL, S, E, NA, MT);
+    *occ = O;
+    *wgw = O;
+    if constexpr (!E && NA != 2 && O > 1) {
+        if (small_wg) {
+            *wgw = 1;
+            return reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, O, 1>);
+        }
+    }
+    return reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, O, O>);
+}
+
+// na_class: 0 = at most two atoms, 1 = at most six, 2 = up to eight
+template <bool BF16, int EPL, int LPB>
+const void* pick_geom(int sign_mode, bool emit, int na_class, bool small_wg, int* occ, int* wgw)
+{
+#define SOPK_FN(S, E, NA) variant<BF16, EPL, LPB, S, E, NA>(small_wg, occ, wgw)
 #define SOPK_BY_SIGN(E, NA) (sign_mode == 1 ? SOPK_FN(1, E, NA) : sign_mode == 2 ? SOPK_FN(2, E, NA) : SOPK_FN(0, E, NA))
     if (emit) return na_class == 0 ? SOPK_BY_SIGN(true, 2) : SOPK_BY_SIGN(true, 8);
     if (na_class == 0) return SOPK_BY_SIGN(false, 2);
@@ -828,15 +852,17 @@ const void* pick_geom(int sign_mode, bool emit, int na_class, int* occ)
 #define SOPK_CAT2(a, b, c) a##b##_##c
 #define SOPK_CAT(a, b, c) SOPK_CAT2(a, b, c)
 
-// g: block size; na_class: 0 / 1 / 2 for alphabets of at most 2 / 6 / 8 atoms; *occ receives the wavefronts per SIMD the
-// variant is built for (its workgroup has 256 * occ threads)
-extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na_class, int* occ)
+// g: block size; na_class: 0 / 1 / 2 for alphabets of at most 2 / 6 / 8 atoms; small_wg: ask for the variant with
+// workgroups of four wavefronts (given where it exists).  *occ receives the wavefronts per SIMD the variant is built
+// for, *wgw those of one workgroup (256 * wgw threads)
+extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na_class, int small_wg, int* occ, int* wgw)
 {
     constexpr bool B = SOPK_PART_BF16 != 0;
+    const bool sm = small_wg != 0;
     switch (g) {
-        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na_class, occ);
-        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na_class, occ);
-        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na_class, occ);
-        default: return pick_geom<B, 16, 4>(sign_mode, emit, na_class, occ);
+        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na_class, sm, occ, wgw);
+        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na_class, sm, occ, wgw);
+        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na_class, sm, occ, wgw);
+        default: return pick_geom<B, 16, 4>(sign_mode, emit, na_class, sm, occ, wgw);
     }
 }
