@@ -16,9 +16,9 @@
 
 #include "sop_kparams.h"
 
-extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int small_wg, int* occ, int* wgw);
-extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int small_wg);
-extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int wgw, size_t dyn_lds, void* stream);
+extern "C" const void* sopk_search_kernel(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int mode, int* occ, int* mode_out);
+extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric, int emit, int na_class, int mode);
+extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int occ, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
@@ -39,11 +39,19 @@ float funord(int64_t k) { return k < 0 ? u2f(0x80000000u | (uint32_t)(-k)) : u2f
 }  // namespace
 
 static constexpr int kLanes = 2;          // streams of its own that sop_pair_search_layers deals the layers out to
+static constexpr int kMaxLayers = 1024;  // layers of one launch of the model-wide kernel (more are dealt with in several launches)
 static constexpr size_t kSumsWords = SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1;   // one set of layer sums and tickets, in 64-bit words
 
 struct sop_ctx {
     int device = 0;
     int n_cu = 0;
+    size_t lds_max = 0;                   // LDS one workgroup may use
+    LayerDesc* d_ldesc = nullptr;         // [kMaxLayers] layer list of the model-wide kernel
+    unsigned long long* d_msums = nullptr; // its sums [kMaxLayers][SOP_K_REPL][SOP_K_NCOL] and tickets (zero between calls)
+    LayerDesc* h_ldesc[2] = {nullptr, nullptr};   // pinned staging for the layer list, used in turn
+    hipEvent_t ldesc_copied[2] = {nullptr, nullptr};  // the copy out of each staging buffer has run
+    bool ldesc_pending[2] = {false, false};
+    int ldesc_turn = 0;
     int n_atoms = 0, n_pairs = 0;
     // caller's order
     std::vector<std::vector<float>> tables;
@@ -111,6 +119,7 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
     hipDeviceProp_t prop;
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipGetDeviceProperties"); }
     c->n_cu = prop.multiProcessorCount;
+    c->lds_max = prop.sharedMemPerBlock;
     if ((e = hipMalloc((void**)&c->d_bins, sizeof(BinRec) * SOP_K_MAXBINS)) != hipSuccess) { delete c; return hipfail(nullptr, e, "hipMalloc(table image)"); }
     if ((e = hipMalloc((void**)&c->d_sums, sizeof(unsigned long long) * kLanes * kSumsWords)) != hipSuccess ||
         (e = hipMemset(c->d_sums, 0, sizeof(unsigned long long) * kLanes * kSumsWords)) != hipSuccess) {
@@ -136,6 +145,20 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(rank counts)");
     }
+    const size_t msums_bytes = sizeof(unsigned long long) * ((size_t)kMaxLayers * SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1);
+    if ((e = hipMalloc((void**)&c->d_ldesc, sizeof(LayerDesc) * kMaxLayers)) != hipSuccess ||
+        (e = hipMalloc((void**)&c->d_msums, msums_bytes)) != hipSuccess || (e = hipMemset(c->d_msums, 0, msums_bytes)) != hipSuccess ||
+        (e = hipHostMalloc((void**)&c->h_ldesc[0], sizeof(LayerDesc) * kMaxLayers, hipHostMallocDefault)) != hipSuccess ||
+        (e = hipHostMalloc((void**)&c->h_ldesc[1], sizeof(LayerDesc) * kMaxLayers, hipHostMallocDefault)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&c->ldesc_copied[0], hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&c->ldesc_copied[1], hipEventDisableTiming)) != hipSuccess) {
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel);
+        if (c->d_ldesc) (void)hipFree(c->d_ldesc);
+        if (c->d_msums) (void)hipFree(c->d_msums);
+        for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(layer list)");
+    }
     *out = c;
     return SOP_OK;
 }
@@ -150,6 +173,9 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_ddacc) (void)hipFree(c->d_ddacc);
         if (c->d_ls) (void)hipFree(c->d_ls);
         if (c->d_sel) (void)hipFree(c->d_sel);
+        if (c->d_ldesc) (void)hipFree(c->d_ldesc);
+        if (c->d_msums) (void)hipFree(c->d_msums);
+        for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
         for (hipStream_t s : c->lane_stream) if (s) (void)hipStreamDestroy(s);
         for (hipEvent_t ev : c->lane_event) if (ev) (void)hipEventDestroy(ev);
         for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
@@ -424,7 +450,7 @@ static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, 
 static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                                    const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
                                    void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch, int sums_set = 0,
-                                   bool small_wg = false)
+                                   KParams* p_out = nullptr, size_t* lds_out = nullptr)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !cn || !out) return fail(c, SOP_EINVAL, "sop_pair_search: W, c and out must not be NULL");
@@ -517,14 +543,13 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     }
     const int na_class = A > 6 ? 2 : (A > 2 ? 1 : 0);
     const int sign_mode = c->scale_rule == 1 ? 2 : w;
-    // small_wg (a stream of layers): workgroups of four wavefronts, several resident per compute unit, where
-    // the variant exists; otherwise, and for a single call, one workgroup fills a compute unit
-    int occ = 1, wgw = 1;
-    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, small_wg ? 1 : 0, &occ, &wgw);
-    const bool small = wgw < occ;
-    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, small ? 1 : 0);
+    int occ = 1, mode = 0;
+    const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, 0, &occ, &mode);
+    const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, emit, na_class, 0);
     const size_t dyn_lds = (((size_t)p.n_bins * SOP_K_BIN_BYTES + 15) & ~(size_t)15) + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15) +
                            2 * SOP_K_MAXA * sizeof(float4) + (1 + 2 * SOP_K_NCOL) * sizeof(unsigned long long);
+    if (p_out) *p_out = p;
+    if (lds_out) *lds_out = dyn_lds;
     hipError_t e = hipSuccess;
     if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
         if (dyn_lds > 48 * 1024) {
@@ -532,21 +557,19 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
             if (e != hipSuccess) return hipfail(c, e, "hipFuncSetAttribute(dynamic LDS)");
         }
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256 * wgw, dyn_lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256 * occ, dyn_lds);
         if (e != hipSuccess) return hipfail(c, e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
         if (nb < 1) return fail(c, SOP_EHIP, "the kernel does not fit on a compute unit with this alphabet and scale format");
         c->occ_blocks[vi] = nb;
         c->occ_lds[vi] = dyn_lds;
     }
-    // one workgroup of 4*occ wavefronts per compute unit (small workgroups: as many of four wavefronts as stay
-    // resident together, at most occ); each takes a contiguous range of (strip,row) steps
-    const long long waves_per_wg = 4 * wgw;
-    const long long wg_per_cu = small ? std::min(occ, c->occ_blocks[vi]) : 1;
-    long long wg = std::min<long long>((long long)c->n_cu * wg_per_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
+    // one workgroup of 4*occ wavefronts per compute unit; each takes a contiguous range of (strip,row) steps
+    const long long waves_per_wg = 4 * occ;
+    long long wg = std::min<long long>(c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
     wg = std::max<long long>(wg, 1);
     p.n_waves = wg * waves_per_wg;
     if (!launch) return SOP_OK;
-    e = sopk_launch(fn, &p, (int)wg, wgw, dyn_lds, stream);
+    e = sopk_launch(fn, &p, (int)wg, occ, dyn_lds, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }
@@ -567,47 +590,130 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
     if (!acos_pair_table && !acos_atom_table) return fail(c, SOP_EINVAL, "sop_pair_search_layers: no output table");
     if ((reinterpret_cast<uintptr_t>(acos_pair_table) | reinterpret_cast<uintptr_t>(acos_atom_table)) & 7u)
         return fail(c, SOP_EINVAL, "sop_pair_search_layers: tables must be 8-byte aligned");
-    // Two streams of the library's own take the layers in turn (each with its own set of layer sums), and
-    // the kernels run with workgroups of four wavefronts, several resident per compute unit: when a
-    // workgroup of the current layer ends, one of the next layer takes its place while the others keep the
-    // SIMDs busy, so a workgroup's table load, first row and reduction cost next to nothing.  Both streams
-    // start after the work already queued on the caller's stream; the caller's stream continues after both.
+    // The layers go through the model-wide kernel: one launch works through a list of layers, its wavefronts
+    // passing from layer to layer without a pause (tables loaded once, tickets once), on the caller's stream.
+    // Layers are grouped by their layer shift (the scale table in LDS belongs to one shift): a launch per
+    // shift, and per kMaxLayers layers.  Where that kernel does not exist (alphabets of one or two atoms) or
+    // the tables leave no room in LDS for the layers' sums, there is one kernel per layer, dealt out to two
+    // streams of the library's own (each with its own set of layer sums) so that a layer's table load and
+    // first rows overlap its predecessor's tail; both streams start after the work already queued on the
+    // caller's stream, and the caller's stream continues after both.
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = hipSuccess;
+    // ---- every layer is validated before anything is launched (this also prepares the tables of the call);
+    //      the format part of the kernel parameters is kept per distinct shift ----
+    std::map<int, std::pair<KParams, size_t>> by_shift;
+    for (int l = 0; l < n_layers; ++l) {
+        const sop_layer& L = layers[l];
+        sop_outputs o;
+        std::memset(&o, 0, sizeof(o));
+        o.acos_atom = acos_atom_table;            // (any non-NULL output: nothing is written in this pass)
+        o.acos_pair = acos_pair_table;
+        o.sel_words = L.sel_words_dev;
+        KParams pk;
+        size_t ldsk = 0;
+        const sop_status s = pair_search_impl(c, L.W_dev, dtype, L.M, L.K, L.ldw, L.c_dev, g, fmt, L.layer_shift_k, metric,
+                                              nullptr, 0, &o, stream, false, 0, &pk, &ldsk);
+        if (s != SOP_OK) { c->err = "layer " + std::to_string(l) + ": " + c->err; return s; }
+        by_shift.emplace(L.layer_shift_k, std::make_pair(pk, ldsk));
+    }
+    if (n_layers > 1) {
+        const int na_class = c->n_atoms > 6 ? 2 : (c->n_atoms > 2 ? 1 : 0);
+        const int sign_mode = c->scale_rule == 1 ? 2 : fmt.sign_bits;
+        int occ = 1, mode = 0;
+        const void* fn = sopk_search_kernel(dtype == SOP_BF16, g, sign_mode, (int)metric, 0, na_class, 2, &occ, &mode);
+        const size_t lds0 = by_shift.begin()->second.second;          // (the same for every shift: table sizes do not depend on it)
+        const size_t per_layer = SOP_K_NCOL * sizeof(unsigned long long), slack = 256;     // (the kernel's few static words)
+        const long long room = c->lds_max > lds0 + slack ? (long long)((c->lds_max - lds0 - slack) / per_layer) : 0;
+        const int chunk = (int)std::min<long long>(kMaxLayers, room);
+        if (mode == 2 && chunk >= 2) {
+            const int vi = sopk_variant_index(dtype == SOP_BF16, g, sign_mode, (int)metric, 0, na_class, 2);
+            const int epl = g < 16 ? g : 16;
+            for (const auto& kv : by_shift) {
+                std::vector<int> idx;                                 // the layers of this shift, in the caller's order
+                for (int l = 0; l < n_layers; ++l) if (layers[l].layer_shift_k == kv.first) idx.push_back(l);
+                for (size_t i0 = 0; i0 < idx.size(); i0 += (size_t)chunk) {
+                    const int n = (int)std::min<size_t>((size_t)chunk, idx.size() - i0);
+                    const int turn = c->ldesc_turn;
+                    c->ldesc_turn ^= 1;
+                    if (c->ldesc_pending[turn]) {                              // the copy that last used this staging buffer has run?
+                        if ((e = hipEventSynchronize(c->ldesc_copied[turn])) != hipSuccess) return hipfail(c, e, "hipEventSynchronize(layer list)");
+                        c->ldesc_pending[turn] = false;
+                    }
+                    LayerDesc* h = c->h_ldesc[turn];
+                    for (int i = 0; i < n; ++i) {
+                        const int l = idx[i0 + i];
+                        const sop_layer& L = layers[l];
+                        LayerDesc& d = h[i];
+                        d.W = L.W_dev; d.c = L.c_dev; d.sel_words = c->n_pairs ? L.sel_words_dev : nullptr; d.ldw = L.ldw;
+                        d.Bk = (int)(L.K / g); d.Nb = L.M * (L.K / g);
+                        d.out_row = l;
+                        d.M32 = (unsigned int)L.M;
+                        d.m_magic = L.M == 1 ? 0xFFFFFFFFu : (unsigned int)((1ull << 32) / (unsigned long long)L.M);
+                        d.K = (int)L.K;
+                        d.total_units = (unsigned int)(((L.K / epl + 63) / 64) * L.M);
+                    }
+                    if ((e = hipMemcpyAsync(c->d_ldesc, h, sizeof(LayerDesc) * n, hipMemcpyHostToDevice, (hipStream_t)stream)) != hipSuccess ||
+                        (e = hipEventRecord(c->ldesc_copied[turn], (hipStream_t)stream)) != hipSuccess)
+                        return hipfail(c, e, "copy of the layer list");
+                    c->ldesc_pending[turn] = true;
+                    KParams p = kv.second.first;
+                    p.W = nullptr; p.c = nullptr; p.sel_words = nullptr;
+                    p.layers = c->d_ldesc;
+                    p.n_layers = n;
+                    p.sums = c->d_msums;
+                    p.done = reinterpret_cast<unsigned int*>(c->d_msums + (size_t)kMaxLayers * SOP_K_REPL * SOP_K_NCOL);
+                    p.acos_pair = c->n_pairs > 0 ? acos_pair_table : nullptr;
+                    p.acos_atom = acos_atom_table;
+                    const size_t dyn_lds = lds0 + (size_t)n * per_layer;
+                    if (c->occ_blocks[vi] == 0 || c->occ_lds[vi] != dyn_lds) {
+                        if (dyn_lds > 48 * 1024 && (e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds)) != hipSuccess)
+                            return hipfail(c, e, "hipFuncSetAttribute(dynamic LDS)");
+                        int nb = 0;
+                        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, 256 * occ, dyn_lds)) != hipSuccess)
+                            return hipfail(c, e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+                        if (nb < 1) return fail(c, SOP_EHIP, "the model-wide kernel does not fit on a compute unit with this alphabet and scale format");
+                        c->occ_blocks[vi] = nb;
+                        c->occ_lds[vi] = dyn_lds;
+                    }
+                    if ((e = sopk_launch(fn, &p, c->n_cu, occ, dyn_lds, stream)) != hipSuccess) return hipfail(c, e, "kernel launch");
+                }
+            }
+            return SOP_OK;
+        }
+    }
+    // ---- otherwise: one kernel per layer, dealt out to streams of the library's own ----
     const int n_lanes = std::min(n_layers, kLanes);     // (three or four streams measured no faster than two)
+    const bool lanes = n_lanes > 1;
     for (int i = 0; i < n_lanes && e == hipSuccess; ++i)
         if (!c->lane_stream[i]) e = hipStreamCreateWithFlags(&c->lane_stream[i], hipStreamNonBlocking);
     for (int i = 0; i <= kLanes && e == hipSuccess; ++i)
         if (!c->lane_event[i]) e = hipEventCreateWithFlags(&c->lane_event[i], hipEventDisableTiming);
     if (e != hipSuccess) return hipfail(c, e, "stream / event creation");
-    const bool lanes = n_lanes > 1;
-    // first pass validates every layer (nothing is launched when one of them is rejected), second pass launches
-    for (int pass = 0; pass < 2; ++pass) {
-        if (pass == 1 && lanes) {
-            e = hipEventRecord(c->lane_event[kLanes], (hipStream_t)stream);
-            for (int i = 0; i < n_lanes && e == hipSuccess; ++i) e = hipStreamWaitEvent(c->lane_stream[i], c->lane_event[kLanes], 0);
-            if (e != hipSuccess) return hipfail(c, e, "stream fork");
-        }
-        for (int l = 0; l < n_layers; ++l) {
-            const sop_layer& L = layers[l];
-            sop_outputs o;
-            std::memset(&o, 0, sizeof(o));
-            o.acos_pair = acos_pair_table && c->n_pairs > 0 ? acos_pair_table + (size_t)l * c->n_pairs : nullptr;
-            o.acos_atom = acos_atom_table ? acos_atom_table + (size_t)l * c->n_atoms : nullptr;
-            o.sel_words = L.sel_words_dev;
-            const int lane = lanes ? l % n_lanes : 0;
-            void* st = lanes ? (void*)c->lane_stream[lane] : stream;
-            const sop_status s = pair_search_impl(c, L.W_dev, dtype, L.M, L.K, L.ldw, L.c_dev, g, fmt, L.layer_shift_k, metric,
-                                                  nullptr, 0, &o, st, pass == 1, lane, lanes);
-            if (s != SOP_OK) {
-                c->err = "layer " + std::to_string(l) + ": " + c->err;
-                if (pass == 1 && lanes) {                                     // rejoin what was launched
-                    for (int i = 0; i < n_lanes; ++i)
-                        if (hipEventRecord(c->lane_event[i], c->lane_stream[i]) == hipSuccess) (void)hipStreamWaitEvent((hipStream_t)stream, c->lane_event[i], 0);
-                }
-                return s;
+    if (lanes) {
+        e = hipEventRecord(c->lane_event[kLanes], (hipStream_t)stream);
+        for (int i = 0; i < n_lanes && e == hipSuccess; ++i) e = hipStreamWaitEvent(c->lane_stream[i], c->lane_event[kLanes], 0);
+        if (e != hipSuccess) return hipfail(c, e, "stream fork");
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        const sop_layer& L = layers[l];
+        sop_outputs o;
+        std::memset(&o, 0, sizeof(o));
+        o.acos_pair = acos_pair_table && c->n_pairs > 0 ? acos_pair_table + (size_t)l * c->n_pairs : nullptr;
+        o.acos_atom = acos_atom_table ? acos_atom_table + (size_t)l * c->n_atoms : nullptr;
+        o.sel_words = L.sel_words_dev;
+        const int lane = lanes ? l % n_lanes : 0;
+        void* st = lanes ? (void*)c->lane_stream[lane] : stream;
+        const sop_status s = pair_search_impl(c, L.W_dev, dtype, L.M, L.K, L.ldw, L.c_dev, g, fmt, L.layer_shift_k, metric,
+                                              nullptr, 0, &o, st, true, lane);
+        if (s != SOP_OK) {
+            c->err = "layer " + std::to_string(l) + ": " + c->err;
+            if (lanes) {                                                  // rejoin what was launched
+                for (int i = 0; i < n_lanes; ++i)
+                    if (hipEventRecord(c->lane_event[i], c->lane_stream[i]) == hipSuccess) (void)hipStreamWaitEvent((hipStream_t)stream, c->lane_event[i], 0);
             }
+            return s;
         }
     }
     if (lanes) {

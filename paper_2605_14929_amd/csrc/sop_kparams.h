@@ -91,6 +91,24 @@ struct KParams {
     uint8_t*  codes;
     float*    blk_cos;
     float*    blk_err;
+    // model-wide kernel: the layers of one launch (W, c, M, K, ldw, Nb, sel_words above are then unused); sums is
+    // [n_layers][SOP_K_REPL][SOP_K_NCOL], acos_pair / acos_atom are tables with rows of P / A values (a layer names its row)
+    const struct LayerDesc* layers;
+    int n_layers;
+};
+
+/* One layer of a model-wide launch (64 bytes, read with scalar loads) */
+struct LayerDesc {
+    const void*  W;
+    const float* c;
+    void*        sel_words;          // or NULL
+    long long    ldw;
+    long long    Nb;
+    int          Bk;
+    int          out_row;            // row of the ACos tables this layer's results go to
+    unsigned int M32, m_magic;       // rows, floor(2^32 / rows)
+    int          K;
+    unsigned int total_units;        // strips * rows
 };
 
 /* Statistics pass of the data-derived codebook */

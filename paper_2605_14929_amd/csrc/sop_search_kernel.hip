@@ -391,16 +391,21 @@ __device__ __forceinline__ void all_pairs(const KParams& p, const Switches& sw, 
 template <bool BF16, int EPL> struct RawBlk { uint4 v[BF16 ? EPL / 8 : EPL / 4]; };
 
 template <bool BF16, int EPL>
-__device__ __forceinline__ RawBlk<BF16, EPL> load_raw(const KParams& p, long long strip, long long m, int lane)
+__device__ __forceinline__ RawBlk<BF16, EPL> load_raw(const void* W, long long ldw, long long K, long long strip, long long m, int lane)
 {
     RawBlk<BF16, EPL> r;
     const long long col0 = (strip * 64 + lane) * EPL;
-    const bool valid = col0 < p.K;
+    const bool valid = col0 < K;
     constexpr int NV = BF16 ? EPL / 8 : EPL / 4;
-    const char* src = reinterpret_cast<const char*>(p.W) + (m * p.ldw + col0) * (BF16 ? 2 : 4);
+    const char* src = reinterpret_cast<const char*>(W) + (m * ldw + col0) * (BF16 ? 2 : 4);
 #pragma unroll
     for (int i = 0; i < NV; ++i) r.v[i] = valid ? reinterpret_cast<const uint4*>(src)[i] : make_uint4(0, 0, 0, 0);
     return r;
+}
+template <bool BF16, int EPL>
+__device__ __forceinline__ RawBlk<BF16, EPL> load_raw(const KParams& p, long long strip, long long m, int lane)
+{
+    return load_raw<BF16, EPL>(p.W, p.ldw, p.K, strip, m, lane);
 }
 
 template <bool BF16, int EPL>
@@ -426,19 +431,21 @@ __device__ __forceinline__ void widen(const RawBlk<BF16, EPL>& r, float (&w)[EPL
 }
 
 // NA: atoms the kernel is unrolled for (2, 6 or 8).  OCC: wavefronts per SIMD the register budget is set
-// for.  WGW: wavefronts per SIMD of one workgroup.  WGW == OCC: a workgroup of 4*OCC wavefronts fills one
-// compute unit on its own (one copy of the tables in LDS per compute unit, one ticket per compute unit in
-// the layer reduction): the shape of a single call.  WGW == 1: workgroups of four wavefronts, OCC of them
-// resident per compute unit, for a stream of layers on two streams: when a workgroup of one layer ends, one
-// of the next layer takes its place while the others keep the SIMDs busy, so table load, first row and
-// reduction of a workgroup are partly hidden behind its neighbours on the same compute unit.
+// for; a workgroup is 4*OCC wavefronts and fills one compute unit on its own (one copy of the tables in
+// LDS per compute unit, one ticket per compute unit in the layer reduction).
+// MULTI: one launch works through a list of layers (model-wide call).  The workgroups stay, the tables are
+// loaded once, and every share's steps of all the layers form one sequence with one counter: a wavefront
+// passes from a layer to the next without waiting for anyone, adding what it holds to the finished layer's
+// sums in LDS on the way (one set of sums per layer of the launch); tickets and the conversion to ACos happen
+// once, at the end of the launch, for all its layers.
 // SIGNMODE 0: the scale is positive; 1: both signs of the scale are tried and the better one kept
 // (signed scale word, absmax rule); 2: argmax rule, the rule fixes the sign.
-template <bool BF16, int EPL, int LPB, int SIGNMODE, int METRIC, bool EMIT, int NA, int OCC, int WGW>
-__global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel(const KParams p)
+template <bool BF16, int EPL, int LPB, int SIGNMODE, int METRIC, bool EMIT, int NA, int OCC, bool MULTI>
+__global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
 {
+    static_assert(!MULTI || !EMIT, "the model-wide kernel searches only");
     constexpr bool SIGNED = SIGNMODE == 1, ARGMAX = SIGNMODE == 2;
-    constexpr int NT = 256 * WGW, NW = 4 * WGW;                                   // threads, wavefronts of the workgroup
+    constexpr int NT = 256 * OCC, NW = 4 * OCC;                                   // threads, wavefronts of the workgroup
     extern __shared__ __align__(16) char s_mem[];
     // LDS: bin table | (scale, reciprocal) table | group parameters | reduction scratch
     char* s_bins = s_mem;                                                         // [n_bins] records of 33 words
@@ -447,7 +454,8 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
     float4* s_gpar = reinterpret_cast<float4*>(s_mem + bins_bytes + (((size_t)p.n_tab_codes * sizeof(float2) + 15) & ~(size_t)15));
     // reduction scratch: flag word, the final gather's totals, the workgroup's own totals (64-bit integers)
     unsigned long long* s_red = reinterpret_cast<unsigned long long*>(s_gpar + 2 * SOP_K_MAXA);
-    unsigned long long* s_acc = s_red + 1 + SOP_K_NCOL;                           // [SOP_K_NCOL] this workgroup's sums
+    unsigned long long* s_acc = s_red + 1 + SOP_K_NCOL;                           // [SOP_K_NCOL] this workgroup's sums (MULTI: per layer)
+    const int n_acc = MULTI ? p.n_layers * SOP_K_NCOL : SOP_K_NCOL;
     __shared__ unsigned int s_next[4];                                            // next step of each SIMD's share
     {
         // 16 bytes per lane and four loads in flight before the first LDS write: a loop of one load, wait,
@@ -476,7 +484,7 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
             }
         }
         if (threadIdx.x < 4) s_next[threadIdx.x] = 0u;
-        if ((int)threadIdx.x < SOP_K_NCOL) s_acc[threadIdx.x] = 0ull;
+        for (int i = threadIdx.x; i < n_acc; i += NT) s_acc[i] = 0ull;
         // (static indices: a lane-dependent index into the kernel arguments would copy them to scratch memory)
 #pragma unroll
         for (int a = 0; a < SOP_K_MAXA; ++a)
@@ -501,9 +509,52 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
     // SIMD's rate, for a fifth of the kernel.  Which wavefront takes which step does not change any
     // result: all sums are integers.
     const int simd = wv & 3;
-    const long long g0 = p.total_units * blockIdx.x / gridDim.x, g1 = p.total_units * (blockIdx.x + 1) / gridDim.x;
-    const unsigned int sb = (unsigned int)(g0 + (g1 - g0) * simd / 4);
-    const unsigned int cnt = (unsigned int)(g0 + (g1 - g0) * (simd + 1) / 4) - sb;
+    // the share's range of steps in a layer of total_units steps
+    auto share_of = [&](long long total_units, unsigned int& first, unsigned int& count) {
+        const long long g0 = total_units * blockIdx.x / gridDim.x, g1 = total_units * (blockIdx.x + 1) / gridDim.x;
+        first = (unsigned int)(g0 + (g1 - g0) * simd / 4);
+        count = (unsigned int)(g0 + (g1 - g0) * (simd + 1) / 4) - first;
+    };
+    // Request side (the row loads run one step ahead of the arithmetic): the layer the next requested step
+    // lies in.  One layer: sb, cnt are the share's range.  MULTI: the shares of all layers follow one another
+    // in one sequence of step numbers; rq_base is the number of the first step of layer rq_l in it.
+    unsigned int sb, cnt;
+    int rq_l = 0;
+    unsigned int rq_base = 0u, rq_M32 = 0u, rq_magic = 0u;
+    const void* rq_W = nullptr;
+    long long rq_ldw = 0, rq_K = 0;
+    // (everything here is the same in all lanes; saying so keeps it in scalar registers: the range's
+    // divisions run on the vector unit, in 32 bits: T*b/G = (T/G)*b + (T%G)*b/G with G, b below 2^16)
+    auto uni = [](unsigned int x) { return (unsigned int)__builtin_amdgcn_readfirstlane((int)x); };
+    auto uni64 = [&](unsigned long long x) { return ((unsigned long long)uni((unsigned int)(x >> 32)) << 32) | uni((unsigned int)x); };
+    auto rq_enter = [&](int l) {
+        const LayerDesc& d = p.layers[l];
+        const unsigned int T = uni(d.total_units), G = gridDim.x, b = blockIdx.x;
+        const unsigned int tq = T / G, tr = T - tq * G;
+        const unsigned int g0 = tq * b + tr * b / G, g1 = tq * (b + 1u) + tr * (b + 1u) / G;
+        const unsigned int first = g0 + (g1 - g0) * (unsigned int)simd / 4u;
+        sb = uni(first);
+        cnt = uni(g0 + (g1 - g0) * (unsigned int)(simd + 1) / 4u - first);
+        rq_W = reinterpret_cast<const void*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(d.W)));
+        rq_ldw = (long long)uni64((unsigned long long)d.ldw);
+        rq_K = (long long)uni((unsigned int)d.K);
+        rq_M32 = uni(d.M32); rq_magic = uni(d.m_magic);
+    };
+    if constexpr (MULTI) rq_enter(0);
+    else share_of(p.total_units, sb, cnt);          // (the layer's own values are read from the kernel arguments where used)
+    // is step v of the sequence there?  (MULTI: moves the request side on to its layer; v never decreases)
+    auto seek = [&](unsigned int v) -> bool {
+        if constexpr (!MULTI) return v < cnt;
+        else {
+            if (rq_l >= p.n_layers) return false;
+            while (v - rq_base >= cnt) {
+                rq_base += cnt;
+                if (++rq_l >= p.n_layers) return false;
+                rq_enter(rq_l);
+            }
+            return true;
+        }
+    };
     auto grab = [&]() -> unsigned int {
         unsigned int v = 0u;
         if (lane == 0) v = atomicAdd(&s_next[simd], 1u);
@@ -512,9 +563,10 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
     // step number -> (strip, row): steps run down the rows of a strip; division by multiplication with
     // floor(2^32 / M), one correction (scalar arithmetic)
     auto locate = [&](unsigned int u, long long& st, long long& row) {
-        unsigned int q = __umulhi(u, p.m_magic);
-        unsigned int r = u - q * p.M32;
-        if (r >= p.M32) { ++q; r -= p.M32; }
+        const unsigned int magic = MULTI ? rq_magic : p.m_magic, rows = MULTI ? rq_M32 : p.M32;
+        unsigned int q = __umulhi(u, magic);
+        unsigned int r = u - q * rows;
+        if (r >= rows) { ++q; r -= rows; }
         st = q; row = r;
     };
 
@@ -547,14 +599,20 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
 #undef SOPK_DPP6
         if (lane == 63) atomicAdd(&s_acc[col], (unsigned long long)(((long long)hi << 15) + (long long)lo));
     };
-    auto flush = [&]() {
+    int cl = MULTI ? -1 : 0;                       // the layer the arithmetic is in
+    auto flush = [&](int layer) {
+        const int c0 = MULTI ? layer * SOP_K_NCOL : 0;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) { lane_sum_to(acca[i], i); acca[i] = 0; }
+        for (int i = 0; i < NA; ++i) { lane_sum_to(acca[i], c0 + i); acca[i] = 0; }
 #pragma unroll
         for (int i = 0; i < SOP_K_MAXP; ++i)
-            if (kPairTab.second[i] < NA) { lane_sum_to(accp[i], SOP_K_MAXA + i); accp[i] = 0; }
-        lane_sum_to(accz, SOP_K_ZCOL); accz = 0;
+            if (kPairTab.second[i] < NA) { lane_sum_to(accp[i], c0 + SOP_K_MAXA + i); accp[i] = 0; }
+        lane_sum_to(accz, c0 + SOP_K_ZCOL); accz = 0;
     };
+    // what the arithmetic needs of its layer
+    const float* lc_c = nullptr;
+    void* lc_sel = nullptr;
+    long long lc_K = 0, lc_Bk = 0;
 
     long long strip = 0, m = 0;
     long long cur_strip = -1;
@@ -563,29 +621,65 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
     for (int i = 0; i < EPL; ++i) cb[i] = 0.0f;
     unsigned int i_cur = grab(), i_nxt = grab();
     RawBlk<BF16, EPL> nxt;
-    if (i_cur < cnt) { locate(sb + i_cur, strip, m); nxt = load_raw<BF16, EPL>(p, strip, m, lane); }
+    bool ok_cur = seek(i_cur);
+    int l_nxt = rq_l;                              // layer of the row in nxt
+    if (ok_cur) { locate(sb + (i_cur - rq_base), strip, m); nxt = load_raw<BF16, EPL>(MULTI ? rq_W : p.W, MULTI ? rq_ldw : p.ldw, MULTI ? rq_K : p.K, strip, m, lane); }
     int since_flush = 0;
 
-    while (i_cur < cnt) {
+    while (ok_cur) {
+        if constexpr (MULTI) {
+            if (l_nxt != cl) {
+                // the arithmetic enters another layer: its channel norms are requested first, and while they
+                // travel the sums the lanes hold, which belong to the layer left, join that layer's
+                const int left = cl;
+                cl = l_nxt;
+                const LayerDesc& d = p.layers[cl];
+                lc_c = reinterpret_cast<const float*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(d.c)));
+                lc_sel = reinterpret_cast<void*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(d.sel_words)));
+                lc_K = (long long)uni((unsigned int)d.K); lc_Bk = (long long)uni((unsigned int)d.Bk);
+                cur_strip = strip;
+                const long long c0 = (strip * 64 + lane) * EPL;
+#pragma unroll
+                for (int i = 0; i < EPL; i += 4) {
+                    float4 t = c0 < lc_K ? *reinterpret_cast<const float4*>(lc_c + c0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    cb[i] = t.x; cb[i + 1] = t.y; cb[i + 2] = t.z; cb[i + 3] = t.w;
+                }
+                if (left >= 0) flush(left);
+                since_flush = 0;
+            }
+        }
         // The uniform switches below are re-read every row.  Left loop-invariant, each test would be
         // hoisted out of the loop as a 64-bit lane mask and the hundred-odd masks would spill.
         Switches sw = {p.A, p.pair_mask, p.flip_mask, p.grp_first_mask, p.unit_tpos, p.unit_tneg, p.wide_mask};
         asm volatile("" : "+s"(sw.A), "+s"(sw.pair_mask), "+s"(sw.flip_mask), "+s"(sw.grp_first), "+s"(sw.unit_tpos), "+s"(sw.unit_tneg), "+s"(sw.wide));
         const long long cm = m, cs = strip;
         const long long col0 = (cs * 64 + lane) * EPL;
-        const bool valid = col0 < p.K;
+        const bool valid = col0 < (MULTI ? lc_K : p.K);
         if (cs != cur_strip) {
             cur_strip = cs;
 #pragma unroll
             for (int i = 0; i < EPL; i += 4) {
-                float4 t = valid ? *reinterpret_cast<const float4*>(p.c + col0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                float4 t = valid ? *reinterpret_cast<const float4*>((MULTI ? lc_c : p.c) + col0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
                 cb[i] = t.x; cb[i + 1] = t.y; cb[i + 2] = t.z; cb[i + 3] = t.w;
             }
         }
         // ---- the block: one read from HBM, requested one step ahead ----
         float w[EPL];
         widen<BF16, EPL>(nxt, w);
-        if (i_nxt < cnt) { locate(sb + i_nxt, strip, m); nxt = load_raw<BF16, EPL>(p, strip, m, lane); }
+        const bool ok_nxt = seek(i_nxt);
+        l_nxt = rq_l;
+        if (ok_nxt) { locate(sb + (i_nxt - rq_base), strip, m); nxt = load_raw<BF16, EPL>(MULTI ? rq_W : p.W, MULTI ? rq_ldw : p.ldw, MULTI ? rq_K : p.K, strip, m, lane); }
+        // the next step opens another layer: its channel norms are asked for now (one word per lane brings
+        // every cache line of the strip's norms in), so that the loads at the top of that step find them
+        // near; the value is only held until the end of this step
+        float c_touch = 0.0f;
+        if constexpr (MULTI) {
+            if (ok_nxt && l_nxt != cl) {
+                const float* cn = reinterpret_cast<const float*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(p.layers[l_nxt].c)));
+                const long long tc = (strip * 64 + lane) * EPL;
+                if (tc < rq_K) c_touch = cn[tc];
+            }
+        }
         const unsigned int i_nn = grab();              // the step after the next one; used at the end of this step
 
         // ---- block statistics ----
@@ -613,7 +707,7 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
         accz += wn > 0.0f ? 0 : (1 << 22);
 
         const long long blk_in_row = (cs * 64 + lane) / LPB;
-        const long long blk = cm * p.Bk + blk_in_row;
+        const long long blk = cm * (MULTI ? lc_Bk : p.Bk) + blk_in_row;
         const bool leader = valid && (lane % LPB == 0);
 
         // per-block results of every atom that the pair stage needs: score = err (WSE / MSE) or
@@ -727,19 +821,40 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
         uint32_t bits = 0;
         all_pairs<0, NA, METRIC>(p, sw, score, den, dlt, accp, bits);
         bits ^= p.flip_slots;
-        if (p.sel_words && leader) {
-            if (p.sel_u32) reinterpret_cast<uint32_t*>(p.sel_words)[blk] = bits;
-            else reinterpret_cast<uint16_t*>(p.sel_words)[blk] = (uint16_t)bits;
+        void* const sel_words = MULTI ? lc_sel : p.sel_words;
+        if (sel_words && leader) {
+            if (p.sel_u32) reinterpret_cast<uint32_t*>(sel_words)[blk] = bits;
+            else reinterpret_cast<uint16_t*>(sel_words)[blk] = (uint16_t)bits;
         }
+        if constexpr (MULTI) asm volatile("" :: "v"(c_touch));
         i_cur = i_nxt;
+        ok_cur = ok_nxt;
         i_nxt = i_nn;
-        if (++since_flush == 128) { flush(); since_flush = 0; }   // a step adds at most 2^23: a lane's sums stay below 2^31
+        if (++since_flush == 128) { flush(cl); since_flush = 0; }   // a step adds at most 2^23: a lane's sums stay below 2^31
     }
 
     // ---- per-workgroup sums: what the lanes still hold joins the workgroup's integer sums in LDS ----
-    flush();
+    if (!MULTI || cl >= 0) flush(cl);
     __syncthreads();
-    if ((int)threadIdx.x < SOP_K_NCOL) {
+    if constexpr (MULTI) {
+        // every layer's sums of this workgroup join the layer's replica; eight adds of a thread are in
+        // flight before their returned values are consumed (see below for why they are consumed)
+        for (int base = 0; base < n_acc; base += 8 * NT) {
+            unsigned long long before[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int idx = base + j * NT + (int)threadIdx.x;
+                before[j] = 0ull;
+                if (idx < n_acc) {
+                    const unsigned long long v = s_acc[idx];
+                    const int layer = idx / SOP_K_NCOL, col = idx - layer * SOP_K_NCOL;
+                    if (v != 0ull) before[j] = atomicAdd(p.sums + ((size_t)layer * SOP_K_REPL + blockIdx.x % SOP_K_REPL) * SOP_K_NCOL + col, v);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) asm volatile("" :: "v"(before[j]) : "memory");
+        }
+    } else if ((int)threadIdx.x < SOP_K_NCOL) {
         const int i = threadIdx.x;
         const unsigned long long v = s_acc[i];
         if (v != 0ull) {
@@ -768,7 +883,37 @@ __global__ __launch_bounds__(256 * WGW, WGW == OCC ? 1 : OCC) void search_kernel
         *s_flag = last;
     }
     __syncthreads();
-    if (*s_flag) {
+    if constexpr (MULTI) {
+        if (*s_flag) {
+            // totals of every (layer, column) over the replicas into LDS, in place of the workgroup's own sums
+            // (the exchanges leave zeros for the next call), then one ACos per (layer, atom or pair)
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < n_acc; idx += NT) {
+                const int layer = idx / SOP_K_NCOL, col = idx - layer * SOP_K_NCOL;
+                unsigned long long* src = p.sums + (size_t)layer * SOP_K_REPL * SOP_K_NCOL + col;
+                unsigned long long part[SOP_K_REPL];
+#pragma unroll
+                for (int r = 0; r < SOP_K_REPL; ++r) part[r] = atomicExch(src + r * SOP_K_NCOL, 0ull);
+                unsigned long long tot = 0ull;
+#pragma unroll
+                for (int r = 0; r < SOP_K_REPL; ++r) tot += part[r];
+                s_acc[idx] = tot;
+            }
+            __syncthreads();
+            const int per = p.A + p.P;
+            for (int o = threadIdx.x; o < p.n_layers * per; o += NT) {
+                const int layer = o / per, q = o - layer * per;
+                int col;
+                double* dst;
+                const size_t row = (size_t)p.layers[layer].out_row;
+                if (q < p.A) { col = q; dst = p.acos_atom ? p.acos_atom + row * p.A + p.uidx[q] : nullptr; }
+                else { col = SOP_K_MAXA + p.pair_pi[q - p.A]; dst = p.acos_pair ? p.acos_pair + row * p.P + (q - p.A) : nullptr; }
+                const long long z = (long long)s_acc[layer * SOP_K_NCOL + SOP_K_ZCOL];
+                const long long t = (long long)s_acc[layer * SOP_K_NCOL + col];
+                if (dst) *dst = 1.0 - ((double)(t - z) * (1.0 / 4194304.0)) / ((double)p.layers[layer].Nb * (double)p.lpb);
+            }
+        }
+    } else if (*s_flag) {
         // gather the replicas (exact integer adds in LDS; the exchanges leave zeros for the next call)
         unsigned long long* s_tot = s_red + 1;
         __syncthreads();
@@ -816,29 +961,30 @@ constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
     return (na == 8 || metric == 1) ? 2 : 3;        // the cosine metric keeps two more sums per candidate alive
 }
 
-// one variant: *occ = wavefronts per SIMD its registers allow, *wgw = wavefronts per SIMD of one workgroup
-// (small workgroups exist for the searches of more than two atoms that write no per-block planes)
+// one variant: *occ = wavefronts per SIMD its registers allow (a workgroup has 4 * occ wavefronts).  mode 0: one
+// layer; 2: a list of layers, which exists for the searches of more than two atoms that write no per-block
+// planes; *mode_out tells which mode was given.
 template <bool BF16, int EPL, int LPB, int S, bool E, int NA>
-const void* variant(bool small_wg, int* occ, int* wgw)
+const void* variant(int mode, int* occ, int* mode_out)
 {
     constexpr int MT = SOPK_PART_METRIC;
     constexpr int O = occ_for(EPL, S, E, NA, MT);
     *occ = O;
-    *wgw = O;
-    if constexpr (!E && NA != 2 && O > 1) {
-        if (small_wg) {
-            *wgw = 1;
-            return reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, O, 1>);
+    *mode_out = 0;
+    if constexpr (!E && NA != 2) {
+        if (mode == 2) {
+            *mode_out = 2;
+            return reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, O, true>);
         }
     }
-    return reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, O, O>);
+    return reinterpret_cast<const void*>(&sopk::search_kernel<BF16, EPL, LPB, S, MT, E, NA, O, false>);
 }
 
 // na_class: 0 = at most two atoms, 1 = at most six, 2 = up to eight
 template <bool BF16, int EPL, int LPB>
-const void* pick_geom(int sign_mode, bool emit, int na_class, bool small_wg, int* occ, int* wgw)
+const void* pick_geom(int sign_mode, bool emit, int na_class, int mode, int* occ, int* mode_out)
 {
-#define SOPK_FN(S, E, NA) variant<BF16, EPL, LPB, S, E, NA>(small_wg, occ, wgw)
+#define SOPK_FN(S, E, NA) variant<BF16, EPL, LPB, S, E, NA>(mode, occ, mode_out)
 #define SOPK_BY_SIGN(E, NA) (sign_mode == 1 ? SOPK_FN(1, E, NA) : sign_mode == 2 ? SOPK_FN(2, E, NA) : SOPK_FN(0, E, NA))
     if (emit) return na_class == 0 ? SOPK_BY_SIGN(true, 2) : SOPK_BY_SIGN(true, 8);
     if (na_class == 0) return SOPK_BY_SIGN(false, 2);
@@ -852,17 +998,16 @@ const void* pick_geom(int sign_mode, bool emit, int na_class, bool small_wg, int
 #define SOPK_CAT2(a, b, c) a##b##_##c
 #define SOPK_CAT(a, b, c) SOPK_CAT2(a, b, c)
 
-// g: block size; na_class: 0 / 1 / 2 for alphabets of at most 2 / 6 / 8 atoms; small_wg: ask for the variant with
-// workgroups of four wavefronts (given where it exists).  *occ receives the wavefronts per SIMD the variant is built
-// for, *wgw those of one workgroup (256 * wgw threads)
-extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na_class, int small_wg, int* occ, int* wgw)
+// g: block size; na_class: 0 / 1 / 2 for alphabets of at most 2 / 6 / 8 atoms; mode: 0 one layer, 2 a list of layers
+// (*mode_out: the mode of the kernel returned, 0 where the one asked for does not exist).  *occ receives the
+// wavefronts per SIMD the variant is built for (its workgroup has 256 * occ threads)
+extern "C" const void* SOPK_CAT(sopk_part_, SOPK_PART_BF16, SOPK_PART_METRIC)(int g, int sign_mode, int emit, int na_class, int mode, int* occ, int* mode_out)
 {
     constexpr bool B = SOPK_PART_BF16 != 0;
-    const bool sm = small_wg != 0;
     switch (g) {
-        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na_class, sm, occ, wgw);
-        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na_class, sm, occ, wgw);
-        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na_class, sm, occ, wgw);
-        default: return pick_geom<B, 16, 4>(sign_mode, emit, na_class, sm, occ, wgw);
+        case 8:  return pick_geom<B, 8, 1>(sign_mode, emit, na_class, mode, occ, mode_out);
+        case 16: return pick_geom<B, 16, 1>(sign_mode, emit, na_class, mode, occ, mode_out);
+        case 32: return pick_geom<B, 16, 2>(sign_mode, emit, na_class, mode, occ, mode_out);
+        default: return pick_geom<B, 16, 4>(sign_mode, emit, na_class, mode, occ, mode_out);
     }
 }

@@ -61,3 +61,54 @@ def test_a_bad_layer_stops_the_call_before_any_launch():
     assert ei.value.status == 2 and "layer 2" in str(ei.value)
     with pytest.raises(sop.SopError):
         cx.pair_search_layers([good, (good[0].float(), good[1])], 16, sop.fmt_by_name("UE4M4"))
+
+
+def test_more_layers_than_one_launch_takes():
+    """1030 small layers (the model-wide kernel takes 1024 per launch): every row of the table equals the
+    single call's, a few are checked against the oracle."""
+    import torch
+    tabs = _alphabet()
+    fmt = sop.fmt_by_name("UE4M4")
+    cx = ctx()
+    cx.set_alphabet(tabs); cx.set_pairs(None)
+    rng = np.random.default_rng(77)
+    n = 1030
+    Ws = (rng.standard_t(4.0, size=(n, 8, 256)) * 0.05).astype(np.float32)
+    c = np.exp(rng.standard_normal(256)).astype(np.float32)
+    big = torch.from_numpy(Ws).cuda()
+    ct = torch.from_numpy(c).cuda()
+    layers = [(big[i], ct) for i in range(n)]
+    tp, ta, _ = cx.pair_search_layers(layers, 16, fmt)
+    torch.cuda.synchronize()
+    tp, ta = tp.cpu().numpy(), ta.cpu().numpy()
+    assert tp.shape == (n, 15) and ta.shape == (n, 6)
+    for i in (0, 1, 511, 1023, 1024, 1029):
+        o = cx.pair_search(big[i], ct, 16, fmt)
+        torch.cuda.synchronize()
+        assert np.array_equal(o.acos_pair.cpu().numpy()[:15], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i]), i
+    for i in (3, 1027):
+        ref = ops.pair_search(Ws[i], c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+        assert np.max(np.abs(tp[i] - ref.acos_pair)) <= 1e-6 and np.max(np.abs(ta[i] - ref.acos_atom)) <= 1e-6
+    assert np.all(np.isfinite(tp)) and np.all(tp <= 1.0 + 1e-9) and np.all(tp > 0.5)
+
+
+def test_two_atom_alphabet_goes_layer_by_layer():
+    """Alphabets of one or two atoms have no model-wide kernel: the call runs one kernel per layer on two
+    streams of its own; same table as single calls and as the oracle."""
+    import torch
+    tabs = _alphabet()[:2]
+    fmt = sop.fmt_by_name("UE4M3")
+    cx = ctx()
+    cx.set_alphabet(tabs); cx.set_pairs(None)
+    host = list(si.model_7b_layers(1, rows=64))[:5]
+    layers = [(torch.from_numpy(W).cuda().to(torch.bfloat16), torch.from_numpy(c).cuda()) for _, W, c, _ in host]
+    tp, ta, sels = cx.pair_search_layers(layers, 16, fmt, want_sel=True)
+    torch.cuda.synchronize()
+    tp, ta = tp.cpu().numpy(), ta.cpu().numpy()
+    for i, (name, W, c, _) in enumerate(host):
+        ref = ops.pair_search(W, c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+        assert np.max(np.abs(tp[i] - ref.acos_pair)) <= 1e-6 and np.max(np.abs(ta[i] - ref.acos_atom)) <= 1e-6, name
+        assert np.array_equal(sels[i].cpu().numpy().view(np.uint16).astype(np.uint32), ref.sel_words), name
+        o = cx.pair_search(layers[i][0], layers[i][1], 16, fmt)
+        torch.cuda.synchronize()
+        assert np.array_equal(o.acos_pair.cpu().numpy()[:1], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i])
