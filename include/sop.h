@@ -181,7 +181,12 @@ sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g,
  * and layer shift.  acos_pair_table_dev: DEVICE [n_layers][P] doubles (may be NULL), acos_atom_table_dev:
  * DEVICE [n_layers][A] doubles (may be NULL; not both).  sel_words_dev of a layer may be NULL (search
  * mode without selector words).  Every layer is validated before the first launch; an error names the
- * layer in sop_last_error().  The launches go to hip_stream back to back; asynchronous. */
+ * layer in sop_last_error().  Asynchronous on hip_stream.  Alphabets of more than two atoms are searched
+ * by one launch per distinct layer shift (and per 1024 layers) that works through the list; the results
+ * equal those of sop_pair_search on each layer bit for bit.  Smaller alphabets run one kernel per layer
+ * on two streams of the library's own, which start after the work already queued on hip_stream and
+ * which hip_stream waits for.  The call may wait on the host for the layer list of the call before last
+ * to have been copied to the device (two staging buffers), never for a kernel. */
 typedef struct {
     const void*  W_dev;
     int64_t      M, K, ldw;
