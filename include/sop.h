@@ -185,8 +185,9 @@ sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_draws, int g,
  * by one launch per distinct layer shift (and per 1024 layers) that works through the list; the results
  * equal those of sop_pair_search on each layer bit for bit.  Smaller alphabets run one kernel per layer
  * on two streams of the library's own, which start after the work already queued on hip_stream and
- * which hip_stream waits for.  The call may wait on the host for the layer list of the call before last
- * to have been copied to the device (two staging buffers), never for a kernel. */
+ * which hip_stream waits for.  The call may wait on the host until the layer list of the launch before
+ * last has been copied to the device (two pinned staging buffers are used in turn), i.e. the host runs
+ * at most two such launches ahead of the device. */
 typedef struct {
     const void*  W_dev;
     int64_t      M, K, ldw;
