@@ -599,9 +599,40 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
 #undef SOPK_DPP6
         if (lane == 63) atomicAdd(&s_acc[col], (unsigned long long)(((long long)hi << 15) + (long long)lo));
     };
+    // the sum of a lane's row of 16 lanes, in every lane of the row (32-bit: for values below 2^27)
+    auto row_sum = [](int x) {
+        x += __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
+        x += __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
+        x += __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);     // row_half_mirror
+        x += __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);     // row_mirror
+        return x;
+    };
     int cl = MULTI ? -1 : 0;                       // the layer the arithmetic is in
-    auto flush = [&](int layer) {
+    // few: the lanes hold at most 15 steps (a layer's share of a wavefront in the model-wide kernel, as a
+    // rule).  Then a lane holds at most 15 * 2^23 and a row of 16 lanes less than 2^31: one 32-bit pass over
+    // quads and rows, and the first lane of each row adds the row's sum to the workgroup's (a third of the
+    // instructions of the general form below)
+    auto flush = [&](int layer, bool few) {
         const int c0 = MULTI ? layer * SOP_K_NCOL : 0;
+        if (MULTI && few) {
+            int ra[NA], rp[SOP_K_MAXP];
+#pragma unroll
+            for (int i = 0; i < NA; ++i) { ra[i] = row_sum(acca[i]); acca[i] = 0; }
+#pragma unroll
+            for (int i = 0; i < SOP_K_MAXP; ++i)
+                if (kPairTab.second[i] < NA) { rp[i] = row_sum(accp[i]); accp[i] = 0; }
+            const int rz = row_sum(accz);
+            accz = 0;
+            if ((lane & 15) == 0) {
+#pragma unroll
+                for (int i = 0; i < NA; ++i) atomicAdd(&s_acc[c0 + i], (unsigned long long)(long long)ra[i]);
+#pragma unroll
+                for (int i = 0; i < SOP_K_MAXP; ++i)
+                    if (kPairTab.second[i] < NA) atomicAdd(&s_acc[c0 + SOP_K_MAXA + i], (unsigned long long)(long long)rp[i]);
+                atomicAdd(&s_acc[c0 + SOP_K_ZCOL], (unsigned long long)(long long)rz);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NA; ++i) { lane_sum_to(acca[i], c0 + i); acca[i] = 0; }
 #pragma unroll
@@ -644,7 +675,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                     float4 t = c0 < lc_K ? *reinterpret_cast<const float4*>(lc_c + c0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
                     cb[i] = t.x; cb[i + 1] = t.y; cb[i + 2] = t.z; cb[i + 3] = t.w;
                 }
-                if (left >= 0) flush(left);
+                if (left >= 0) flush(left, since_flush <= 15);
                 since_flush = 0;
             }
         }
@@ -830,11 +861,11 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         i_cur = i_nxt;
         ok_cur = ok_nxt;
         i_nxt = i_nn;
-        if (++since_flush == 128) { flush(cl); since_flush = 0; }   // a step adds at most 2^23: a lane's sums stay below 2^31
+        if (++since_flush == 128) { flush(cl, false); since_flush = 0; }   // a step adds at most 2^23: a lane's sums stay below 2^31
     }
 
     // ---- per-workgroup sums: what the lanes still hold joins the workgroup's integer sums in LDS ----
-    if (!MULTI || cl >= 0) flush(cl);
+    if (!MULTI || cl >= 0) flush(cl, since_flush <= 15);
     __syncthreads();
     if constexpr (MULTI) {
         // every layer's sums of this workgroup join the layer's replica; eight adds of a thread are in
