@@ -78,3 +78,33 @@ def test_config5_shape_row_sample():
     ref = ops.pair_search(W[rows], c, tabs, 16, oracle_fmt(fmt), want_codes=False)
     assert np.max(np.abs(gpu["acos_pair"] - ref.acos_pair)) < 2e-4
     assert np.all((gpu["acos_pair"] > 0.99) & (gpu["acos_pair"] <= 1.0))
+
+
+def test_config4_one_block_full_size_through_the_model_wide_call():
+    """The seven layers of a 7B-shaped block at their full sizes in one model-wide call (the launch
+    bench.py --workload model times, on one block): the ACos table equals the single calls' bit for bit,
+    the selector words of sampled rows equal the oracle's, the ACos of one layer the oracle's."""
+    import torch
+    host = list(si.model_7b_layers(1))
+    tabs = _alphabet(["NF4", "SH4", "BOF4", "-NF4", "-SH4", "-BOF4"])
+    fmt = sop.fmt_by_name("UE4M4")
+    cx = sop.Context(0)
+    cx.set_alphabet(tabs); cx.set_pairs(None)
+    layers = [(torch.from_numpy(W).cuda().to(torch.bfloat16), torch.from_numpy(c).cuda()) for _, W, c, _ in host]
+    tp, ta, sels = cx.pair_search_layers(layers, 16, fmt, want_sel=True)
+    torch.cuda.synchronize()
+    tp, ta = tp.cpu().numpy(), ta.cpu().numpy()
+    rng = np.random.default_rng(9)
+    for i, (name, W, c, _) in enumerate(host):
+        o = cx.pair_search(layers[i][0], layers[i][1], 16, fmt)
+        torch.cuda.synchronize()
+        assert np.array_equal(o.acos_pair.cpu().numpy()[:15], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i]), name
+        assert torch.equal(o.sel_words, sels[i]), name
+        M, K = W.shape
+        rows = np.sort(rng.choice(M, size=24, replace=False))
+        ref = ops.pair_search(W[rows], c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+        got = sels[i].cpu().numpy().view(np.uint16).astype(np.uint32).reshape(M, K // 16)[rows].reshape(-1)
+        assert np.array_equal(got, ref.sel_words), name
+    name, W, c, _ = host[0]                                          # 4096 x 4096: the oracle on the whole layer
+    ref = ops.pair_search(W, c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+    assert np.max(np.abs(tp[0] - ref.acos_pair)) <= 1e-6 and np.max(np.abs(ta[0] - ref.acos_atom)) <= 1e-6
