@@ -599,38 +599,36 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
 #undef SOPK_DPP6
         if (lane == 63) atomicAdd(&s_acc[col], (unsigned long long)(((long long)hi << 15) + (long long)lo));
     };
-    // the sum of a lane's row of 16 lanes, in every lane of the row (32-bit: for values below 2^27)
-    auto row_sum = [](int x) {
+    // the sum over the wavefront of lane values below 2^27, as a scalar: every row of 16 lanes is added up in
+    // 32 bits on the vector ALU (quads, half rows, rows), the four row sums in 64 bits on the scalar unit
+    auto wave_sum_small = [](int x) -> long long {
         x += __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
         x += __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
         x += __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);     // row_half_mirror
         x += __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);     // row_mirror
-        return x;
+        return (long long)__builtin_amdgcn_readlane(x, 0) + (long long)__builtin_amdgcn_readlane(x, 16) +
+               (long long)__builtin_amdgcn_readlane(x, 32) + (long long)__builtin_amdgcn_readlane(x, 48);
     };
     int cl = MULTI ? -1 : 0;                       // the layer the arithmetic is in
     // few: the lanes hold at most 15 steps (a layer's share of a wavefront in the model-wide kernel, as a
     // rule).  Then a lane holds at most 15 * 2^23 and a row of 16 lanes less than 2^31: one 32-bit pass over
-    // quads and rows, and the first lane of each row adds the row's sum to the workgroup's (a third of the
-    // instructions of the general form below)
+    // quads and rows, the four row sums added on the scalar unit, and one lane adds the total to the
+    // workgroup's (half the vector instructions of the general form below).  At the end of a single call the
+    // short form measured slower (2 us per launch) and is not used.
     auto flush = [&](int layer, bool few) {
         const int c0 = MULTI ? layer * SOP_K_NCOL : 0;
         if (MULTI && few) {
-            int ra[NA], rp[SOP_K_MAXP];
+            auto add_small = [&](int v, int col) {
+                const long long t = wave_sum_small(v);
+                if (lane == 0) atomicAdd(&s_acc[col], (unsigned long long)t);
+            };
 #pragma unroll
-            for (int i = 0; i < NA; ++i) { ra[i] = row_sum(acca[i]); acca[i] = 0; }
+            for (int i = 0; i < NA; ++i) { add_small(acca[i], c0 + i); acca[i] = 0; }
 #pragma unroll
             for (int i = 0; i < SOP_K_MAXP; ++i)
-                if (kPairTab.second[i] < NA) { rp[i] = row_sum(accp[i]); accp[i] = 0; }
-            const int rz = row_sum(accz);
+                if (kPairTab.second[i] < NA) { add_small(accp[i], c0 + SOP_K_MAXA + i); accp[i] = 0; }
+            add_small(accz, c0 + SOP_K_ZCOL);
             accz = 0;
-            if ((lane & 15) == 0) {
-#pragma unroll
-                for (int i = 0; i < NA; ++i) atomicAdd(&s_acc[c0 + i], (unsigned long long)(long long)ra[i]);
-#pragma unroll
-                for (int i = 0; i < SOP_K_MAXP; ++i)
-                    if (kPairTab.second[i] < NA) atomicAdd(&s_acc[c0 + SOP_K_MAXA + i], (unsigned long long)(long long)rp[i]);
-                atomicAdd(&s_acc[c0 + SOP_K_ZCOL], (unsigned long long)(long long)rz);
-            }
             return;
         }
 #pragma unroll
@@ -865,7 +863,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     }
 
     // ---- per-workgroup sums: what the lanes still hold joins the workgroup's integer sums in LDS ----
-    if (!MULTI || cl >= 0) flush(cl, since_flush <= 15);
+    if (!MULTI || cl >= 0) flush(cl, since_flush <= 15);      // (since_flush: steps since the last flush)
     __syncthreads();
     if constexpr (MULTI) {
         // every layer's sums of this workgroup join the layer's replica; eight adds of a thread are in
