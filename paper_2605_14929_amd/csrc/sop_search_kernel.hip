@@ -610,14 +610,15 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                (long long)__builtin_amdgcn_readlane(x, 32) + (long long)__builtin_amdgcn_readlane(x, 48);
     };
     int cl = MULTI ? -1 : 0;                       // the layer the arithmetic is in
-    // few: the lanes hold at most 15 steps (a layer's share of a wavefront in the model-wide kernel, as a
-    // rule).  Then a lane holds at most 15 * 2^23 and a row of 16 lanes less than 2^31: one 32-bit pass over
-    // quads and rows, the four row sums added on the scalar unit, and one lane adds the total to the
-    // workgroup's (half the vector instructions of the general form below).  At the end of a single call the
-    // short form measured slower (2 us per launch) and is not used.
+    // few: the lanes hold at most 15 steps (a wavefront's share of a layer of a few thousand rows: the rule at
+    // a change of layer in the model-wide kernel, and at the end of a single call on such a layer).  Then a
+    // lane holds at most 15 * 2^23 and a row of 16 lanes less than 2^31: one 32-bit pass over quads and rows,
+    // the four row sums added on the scalar unit, and one lane adds the total to the workgroup's (half the
+    // vector instructions of the general form below).  (Four lanes adding their row sums to one LDS word
+    // instead made a single call 2 us slower.)
     auto flush = [&](int layer, bool few) {
         const int c0 = MULTI ? layer * SOP_K_NCOL : 0;
-        if (MULTI && few) {
+        if (few) {
             auto add_small = [&](int v, int col) {
                 const long long t = wave_sum_small(v);
                 if (lane == 0) atomicAdd(&s_acc[col], (unsigned long long)t);
