@@ -85,7 +85,7 @@ def lib():
         L.sop_atom_bof.argtypes = [C.c_int, C.POINTER(C.c_double), C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float)]
         L.sop_dd_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_int,
                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.sop_dd_fit.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        L.sop_dd_fit.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]     # (host arrays by address: the fit is called in loops)
         L.sop_scale_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_float,
                                           ScaleFmt, C.c_void_p, C.c_void_p]
         L.sop_layer_scope_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, WeightFmt, ScaleFmt,
@@ -151,7 +151,7 @@ def sop_dd_fit(hist: np.ndarray, n_entries: int, iters: int, init: np.ndarray) -
     h = np.ascontiguousarray(hist, dtype=np.int64).reshape(-1)
     ini = np.ascontiguousarray(init, dtype=np.float32)
     out = np.empty(n_entries, dtype=np.float32)
-    _check(lib().sop_dd_fit(_fp(h, C.c_int64), h.size, n_entries, iters, _fp(ini), _fp(out)))
+    _check(lib().sop_dd_fit(h.ctypes.data, h.size, n_entries, iters, ini.ctypes.data, out.ctypes.data))
     return out
 
 

@@ -882,22 +882,35 @@ extern "C" sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries,
     std::vector<double> cent(init, init + n_entries), mids(n_entries - 1);
     for (int j = 0; j + 1 < n_entries; ++j)
         if (!(cent[j] < cent[j + 1])) return fail(nullptr, SOP_EATOM, "sop_dd_fit: the start grid must be strictly ascending");
-    std::vector<unsigned __int128> mass(n_entries), first(n_entries);
+    // A bin stands for its centre -1 + (2b+1)/H and goes, whole, to that centre's cell (cell = number of
+    // midpoints strictly below the centre).  The centres ascend with b, so a cell is a run of bins and its
+    // mass and first moment are differences of prefix sums (exact integers); the run's end for a midpoint is
+    // found by bisection on the same binary64 expression of the centre that defines the cell.
+    std::vector<unsigned __int128> pm(n_bins + 1), pf(n_bins + 1);
+    pm[0] = 0; pf[0] = 0;
+    for (int b = 0; b < n_bins; ++b) {
+        pm[b + 1] = pm[b] + (unsigned __int128)hist[b];
+        pf[b + 1] = pf[b] + (unsigned __int128)hist[b] * (unsigned)(2 * b + 1);
+    }
+    auto centre = [n_bins](int b) { return -1.0 + (2.0 * (double)b + 1.0) / (double)n_bins; };
     for (int it = 0; it < iters; ++it) {
         for (int j = 0; j + 1 < n_entries; ++j) mids[j] = 0.5 * (cent[j] + cent[j + 1]);
-        std::fill(mass.begin(), mass.end(), (unsigned __int128)0);
-        std::fill(first.begin(), first.end(), (unsigned __int128)0);
-        int cell = 0;
-        for (int b = 0; b < n_bins; ++b) {
-            // a bin stands for its centre -1 + (2b+1)/H and goes, whole, to that centre's cell
-            // (cell = number of midpoints strictly below the centre)
-            const double xc = -1.0 + (2.0 * (double)b + 1.0) / (double)n_bins;
-            while (cell < n_entries - 1 && mids[cell] < xc) ++cell;
-            mass[cell] += (unsigned __int128)hist[b];
-            first[cell] += (unsigned __int128)hist[b] * (unsigned)(2 * b + 1);
+        int lo_bin = 0;                               // first bin of the current cell
+        for (int j = 0; j < n_entries; ++j) {
+            int end = n_bins;                         // one past the last bin of cell j
+            if (j + 1 < n_entries) {
+                // smallest b >= lo_bin with mids[j] < centre(b): those bins belong to later cells
+                int lo = lo_bin, hi = n_bins;
+                while (lo < hi) {
+                    const int mid = (lo + hi) / 2;
+                    if (mids[j] < centre(mid)) hi = mid; else lo = mid + 1;
+                }
+                end = lo;
+            }
+            const unsigned __int128 mass = pm[end] - pm[lo_bin], first = pf[end] - pf[lo_bin];
+            if (mass > 0) cent[j] = ((double)first / (double)mass) / (double)n_bins - 1.0;
+            lo_bin = end;
         }
-        for (int j = 0; j < n_entries; ++j)
-            if (mass[j] > 0) cent[j] = ((double)first[j] / (double)mass[j]) / (double)n_bins - 1.0;
         std::sort(cent.begin(), cent.end());
     }
     for (int j = 0; j < n_entries; ++j) out[j] = (float)cent[j];

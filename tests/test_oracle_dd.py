@@ -125,6 +125,37 @@ def test_library_host_fit_equals_the_oracle_fit():
         mine = sop.sop_dd_fit(h, 2 ** n_bits, iters, init)
         ref = DD.fit(h, 2 ** n_bits, iters, init.astype(np.float64))
         assert np.array_equal(mine, ref.astype(np.float32))
+    # histograms with empty stretches, clusters and few samples (cells that stay empty, midpoints that fall on
+    # bin centres), random start grids and round counts: same grid, or both reject
+    rng = np.random.default_rng(52)
+    for trial in range(120):
+        H = int(rng.choice([64, 256, 1024, 4096]))
+        if trial % 3 == 0:
+            x = rng.standard_t(3, size=4000)
+            x = x / np.abs(x).max()
+        elif trial % 3 == 1:
+            x = rng.uniform(-1, 1, size=int(rng.integers(40, 400)))
+        else:
+            x = np.concatenate([rng.normal(-0.5, 0.05, 500), rng.normal(0.6, 0.02, 500), [-1.0, 1.0]]).clip(-1, 1)
+        h = np.histogram(x, bins=H, range=(-1, 1))[0].astype(np.int64) * int(rng.integers(1, 1 << 20))
+        n = int(rng.choice([4, 16, 32]))
+        init = np.sort(rng.uniform(-1, 1, n)).astype(np.float32)
+        if np.unique(init).size < n:
+            continue
+        iters = int(rng.integers(0, 25))
+        try:
+            ref = DD.fit(h, n, iters, init.astype(np.float64)).astype(np.float32)
+        except Exception:
+            ref = None
+        if ref is not None and not (np.all(np.diff(ref) > 0) and ref[0] < 0 < ref[-1]):
+            ref = None                                                # the library rejects what cannot be an atom
+        try:
+            mine = sop.sop_dd_fit(h, n, iters, init)
+        except sop.SopError:
+            mine = None
+        assert (mine is None) == (ref is None), trial
+        if mine is not None:
+            assert np.array_equal(mine, ref), trial
     with pytest.raises(sop.SopError) as e:                            # a one-sided result cannot be an atom
         hh = np.zeros(256, dtype=np.int64)
         hh[200:] = 5
