@@ -584,8 +584,8 @@ def main():
                    "weight_dtype": cfg["dtype"], "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
         "layer_latency_ms": lat_ms, "layer_latency_median_ms": lat_med_ms, "layer_latency_min_ms": lat_min_ms,
         "valu_counters": valu_counters(ev_ms) if headline else None,
-        # the six-atom search is bound by the plain vector ALUs; the HBM view of the
-        # same launch is given beside it
+        # the six-atom search is bound by the plain vector ALUs (72 us of algorithmic lane-operations
+        # against 12 us of algorithmic HBM traffic per launch); the HBM view of the same launch is given beside it
         "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",
                      "frac": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_PEAK_TLOPS, "traffic": parse_traffic() if headline else None,
                      "op_definition": "fp32 lane-operations, an fma counted once; peak = 256 CU x 64 lanes x 2.4 GHz",

@@ -19,6 +19,14 @@ grid trained per layer).  The paper gives no recipe beyond that; the reading tak
 Parity unpinned for the choice of recipe (the paper prints no DD4 table); the arithmetic of the
 recipe is pinned against scikit-learn's weighted k-means on the raw samples, against the plain
 Lloyd iteration of oracle/atoms.py and by exact-recovery cases (tests/test_oracle_dd.py).
+
+Grid-constrained construction (Section "Per-Layer Pair Search", step 1: a data-adaptive codebook
+is selected from the grid points of the deployed LUT value format by a dynamic programme on the
+histogram, so that no snap-to-grid displacement is paid afterwards): fit_grid() below.  The problem
+has a plain definition, which grid_cost() writes out: among all ways to pick n_entries of the given
+candidate values, the one whose nearest-entry quantisation of the histogram (a bin stands for its
+centre) has the least summed mass * squared distance.  Pinned by exhaustive search over all
+subsets on small cases and by the comparison with "free Lloyd fit, then snap to the grid".
 """
 from __future__ import annotations
 
@@ -118,3 +126,65 @@ def samples(W: np.ndarray, c: np.ndarray | None, g: int):
     wt = np.broadcast_to(cv.reshape(1, K // g, g), x.shape)
     sel = np.broadcast_to(live[:, :, None], x.shape)
     return x[sel].astype(np.float64), wt[sel].astype(np.float64)
+
+
+def bin_centres(n_bins: int) -> np.ndarray:
+    """Centre of bin b of the histogram over [-1, 1]: -1 + (2b+1)/H."""
+    return -1.0 + (2.0 * np.arange(n_bins, dtype=np.float64) + 1.0) / n_bins
+
+
+def grid_cost(hist: np.ndarray, values: np.ndarray) -> float:
+    """Distortion of a codebook on the histogram, by definition: every bin goes, whole, to the entry
+    nearest its centre (ties to the lower entry, which does not change the sum), and pays its mass
+    times the squared distance.  Units: histogram mass times squared domain units."""
+    h = np.asarray(hist, dtype=np.float64).reshape(-1)
+    x = bin_centres(h.size)
+    L = np.sort(np.asarray(values, dtype=np.float64).reshape(-1))
+    d2 = (x[:, None] - L[None, :]) ** 2
+    return float((h * d2.min(axis=1)).sum())
+
+
+def fit_grid(hist: np.ndarray, cand: np.ndarray, n_entries: int):
+    """Best n_entries-subset of the ascending candidate values `cand` for the histogram:
+    returns (indices into cand, ascending; distortion as grid_cost() defines it).
+
+    Dynamic programme over "the k-th chosen entry is candidate c".  With entries chosen in ascending
+    order, the bins at or below the first entry pay to the first entry, the bins above the last pay to
+    the last, and the bins between two neighbouring chosen entries a < b pay to the nearer one (centre
+    <= (a+b)/2: the lower).  Hence
+        best[1][c] = below(c),   best[k][c] = min over c' < c of best[k-1][c'] + between(c', c),
+        answer     = min over c of best[n][c] + above(c),
+    every term a plain sum over the bins concerned.  Equal sums: the lower candidate index wins."""
+    h = np.asarray(hist, dtype=np.float64).reshape(-1)
+    x = bin_centres(h.size)
+    G = np.asarray(cand, dtype=np.float64).reshape(-1)
+    n = int(n_entries)
+    assert 1 <= n <= G.size and np.all(np.diff(G) > 0)
+    nG = G.size
+    below = np.array([(h[x <= G[c]] * (x[x <= G[c]] - G[c]) ** 2).sum() for c in range(nG)])
+    above = np.array([(h[x > G[c]] * (x[x > G[c]] - G[c]) ** 2).sum() for c in range(nG)])
+    between = np.full((nG, nG), np.inf)
+    for a in range(nG):
+        for b in range(a + 1, nG):
+            sel = (x > G[a]) & (x <= G[b])
+            xs, hs = x[sel], h[sel]
+            to_a = xs <= 0.5 * (G[a] + G[b])
+            between[a, b] = (hs * np.where(to_a, (xs - G[a]) ** 2, (xs - G[b]) ** 2)).sum()
+    best = np.full((n + 1, nG), np.inf)
+    prev = np.full((n + 1, nG), -1, dtype=np.int64)
+    best[1] = below
+    for k in range(2, n + 1):
+        for c in range(k - 1, nG):
+            for cp in range(k - 2, c):
+                v = best[k - 1][cp] + between[cp, c]
+                if v < best[k][c]:
+                    best[k][c], prev[k][c] = v, cp
+    total = best[n] + above
+    total[: n - 1] = np.inf
+    c = int(np.argmin(total))                                        # first minimum: lowest index
+    cost = float(total[c])
+    chosen = []
+    for k in range(n, 0, -1):
+        chosen.append(c)
+        c = int(prev[k][c])
+    return np.array(chosen[::-1], dtype=np.int64), cost
