@@ -32,6 +32,7 @@ extern "C" {
 
 #define SOP_MAX_ATOMS   8     /* atoms in one alphabet                       */
 #define SOP_MAX_ENTRIES 64    /* entries in one atom (n <= 6 bits)           */
+#define SOP_DD_MAX_CANDIDATES 2047  /* grid points sop_dd_fit_grid() selects from */
 
 typedef enum {
     SOP_OK = 0,
@@ -232,6 +233,24 @@ sop_status sop_dd_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, in
  * atom). */
 sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries, int iters, const float* init, float* out);
 
+/* Grid-constrained data-derived codebook (Section "Per-Layer Pair Search", step 1: the entries of a
+ * data-adaptive codebook are selected among the grid points of the deployed LUT value format by a
+ * dynamic programme on the histogram, so that no snap-to-grid displacement follows the fit; step 3
+ * uses the same construction on the fitting pool).  All HOST memory.
+ *   hist, n_bins   as sop_dd_histogram() writes them (bin b stands for its centre -1 + (2b+1)/H)
+ *   cand           n_cand candidate values in the histogram's domain, strictly ascending, within
+ *                  [-4, 4] (grid value / normalisation target; sop_weight_grid() lists a format's values)
+ *   chosen         receives n_entries ascending indices into cand: the selection with the least
+ *                  sum over bins of mass * (centre - nearest chosen value)^2 (a bin goes, whole, to
+ *                  the value nearest its centre, ties to the lower value); among selections whose
+ *                  costs agree to rounding (about 1e-14 relative) the one found first is returned
+ *   cost           HOST or NULL: receives that sum (mass units times squared domain units)
+ * Exact optimum by dynamic programming over (number of values chosen, last value chosen):
+ * O(n_entries * n_cand^2) operations.  SOP_EATOM when the candidates are not ascending or the
+ * selection is not two-sided (it could not serve as an atom). */
+sop_status sop_dd_fit_grid(const int64_t* hist, int n_bins, const double* cand, int n_cand, int n_entries,
+                           int* chosen, double* cost);
+
 /* ---- per-layer scale shift (Section "Scale Format and Metabit Allocation", paragraph "Per-layer
  * scale shift": all block scales of a layer are multiplied by 2^k before they are rounded into the
  * scale word, k* maximising the fraction of block scales in the format's normal range).  Two steps:
@@ -263,6 +282,13 @@ sop_status sop_layer_shift(const int64_t* hist, int64_t n_blocks, sop_scale_fmt 
 /* An ExMy weight grid: magnitudes value(q), q = 0..max_code (bias < 0: 2^(x-1)-1; max_code < 0:
  * 2^(x+y)-1, every code finite), both signs, one zero: 2*max_code+1 values. */
 typedef struct { int exp_bits, man_bits, bias, max_code; } sop_weight_fmt;
+
+/* The distinct values of an ExMy weight grid, ascending, both signs and one zero (Section "SOP
+ * Methodology", paragraph "LUT value format": LUT entries live on a small floating-point grid such
+ * as E2M3 or E4M3).  top > 0 keeps only magnitudes up to top (a normalisation target below the
+ * format's largest value); top <= 0 keeps all.  values: HOST, room for 2*max_code+1 doubles;
+ * n_values receives the count.  x + y <= 10. */
+sop_status sop_weight_grid(sop_weight_fmt wfmt, double top, double* values, int* n_values);
 
 /* One scale for the whole layer by the block rule with the layer as the block: s* = max(pmax, nmax)
  * / value(max_code), times 2^k, rounded into the scale word `sfmt` (nearest, ties to the lower

@@ -6,6 +6,6 @@ There is no CPU fallback: importing works anywhere, calling needs the built libr
 """
 from .binding import (  # noqa: F401
     SopError, lib, lib_path, Context, ScaleFmt, WeightFmt, Outputs,
-    sop_check_alphabet, sop_atom_nf, sop_atom_sh, sop_atom_negate, sop_atom_bof, sop_lloyd_1d, sop_dd_fit, sop_layer_shift,
+    sop_check_alphabet, sop_atom_nf, sop_atom_sh, sop_atom_negate, sop_atom_bof, sop_lloyd_1d, sop_dd_fit, sop_dd_fit_grid, sop_weight_grid, sop_layer_shift,
     F32, BF16, SEL_WSE, SEL_COS, SEL_MSE, SCALE_ABSMAX, SCALE_ARGMAX, fmt_by_name, build_alphabet,
 )

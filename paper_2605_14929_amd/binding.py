@@ -86,6 +86,8 @@ def lib():
         L.sop_dd_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_int,
                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_dd_fit.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]     # (host arrays by address: the fit is called in loops)
+        L.sop_dd_fit_grid.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.sop_weight_grid.argtypes = [WeightFmt, C.c_double, C.c_void_p, C.c_void_p]
         L.sop_scale_histogram.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_float,
                                           ScaleFmt, C.c_void_p, C.c_void_p]
         L.sop_layer_scope_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, WeightFmt, ScaleFmt,
@@ -153,6 +155,25 @@ def sop_dd_fit(hist: np.ndarray, n_entries: int, iters: int, init: np.ndarray) -
     out = np.empty(n_entries, dtype=np.float32)
     _check(lib().sop_dd_fit(h.ctypes.data, h.size, n_entries, iters, ini.ctypes.data, out.ctypes.data))
     return out
+
+
+def sop_dd_fit_grid(hist: np.ndarray, cand: np.ndarray, n_entries: int):
+    """Best n_entries of the ascending candidate values for an [H] int64 histogram (host):
+    (indices into cand, cost)."""
+    h = np.ascontiguousarray(hist, dtype=np.int64).reshape(-1)
+    g = np.ascontiguousarray(cand, dtype=np.float64).reshape(-1)
+    chosen = np.empty(n_entries, dtype=np.int32)
+    cost = C.c_double(0.0)
+    _check(lib().sop_dd_fit_grid(h.ctypes.data, h.size, g.ctypes.data, g.size, n_entries, chosen.ctypes.data, C.byref(cost)))
+    return chosen.astype(np.int64), cost.value
+
+
+def sop_weight_grid(wfmt: "WeightFmt", top: float = 0.0) -> np.ndarray:
+    """Distinct values of an ExMy weight grid, ascending (host)."""
+    out = np.empty(2 * (1 << (wfmt.exp_bits + wfmt.man_bits)) + 1, dtype=np.float64)
+    n = C.c_int(0)
+    _check(lib().sop_weight_grid(wfmt, C.c_double(top), out.ctypes.data, C.byref(n)))
+    return out[:n.value].copy()
 
 
 def sop_layer_shift(hist: np.ndarray, n_blocks: int, fmt: "ScaleFmt"):

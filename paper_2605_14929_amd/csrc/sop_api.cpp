@@ -938,6 +938,117 @@ extern "C" sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries,
     return SOP_OK;
 }
 
+extern "C" sop_status sop_weight_grid(sop_weight_fmt wfmt, double top, double* values, int* n_values)
+{
+    if (!values || !n_values) return fail(nullptr, SOP_EINVAL, "sop_weight_grid: NULL argument");
+    const int x = wfmt.exp_bits, y = wfmt.man_bits;
+    if (x < 1 || x > 8 || y < 0 || y > 10 || x + y > 10) return fail(nullptr, SOP_EFMT, "sop_weight_grid: need 1<=x<=8, 0<=y<=10, x+y<=10");
+    const int bias = wfmt.bias < 0 ? (1 << (x - 1)) - 1 : wfmt.bias;
+    const int max_code = wfmt.max_code < 0 ? (1 << (x + y)) - 1 : wfmt.max_code;
+    if (max_code < 1 || max_code >= (1 << (x + y)) || bias > 127) return fail(nullptr, SOP_EFMT, "sop_weight_grid: bad bias or max_code");
+    if (top != top) return fail(nullptr, SOP_EINVAL, "sop_weight_grid: top is NaN");
+    // magnitudes ascend with the code; a format without mantissa bits has no subnormal step above zero
+    std::vector<double> mag;
+    for (int q = 0; q <= max_code; ++q) {
+        const int e = q >> y, f = q & ((1 << y) - 1);
+        const double v = e == 0 ? std::ldexp((double)f, 1 - bias - y) : std::ldexp((double)((1 << y) + f), e - bias - y);
+        if (top > 0.0 && v > top) break;
+        if (mag.empty() || v > mag.back()) mag.push_back(v);
+    }
+    if (mag.size() < 2) return fail(nullptr, SOP_EINVAL, "sop_weight_grid: top leaves no value besides zero");
+    int n = 0;
+    for (size_t i = mag.size(); i-- > 1;) values[n++] = -mag[i];
+    for (size_t i = 0; i < mag.size(); ++i) values[n++] = mag[i];
+    *n_values = n;
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_dd_fit_grid(const int64_t* hist, int n_bins, const double* cand, int n_cand, int n_entries,
+                                      int* chosen, double* cost)
+{
+    if (!hist || !cand || !chosen) return fail(nullptr, SOP_EINVAL, "sop_dd_fit_grid: NULL argument");
+    if (!dd_bins_ok(n_bins)) return fail(nullptr, SOP_EINVAL, "sop_dd_fit_grid: n_bins must be a power of two within 64..8192");
+    if (n_entries < 2 || n_entries > SOP_MAX_ENTRIES || n_cand < n_entries || n_cand > SOP_DD_MAX_CANDIDATES)
+        return fail(nullptr, SOP_EINVAL, "sop_dd_fit_grid: need 2 <= n_entries <= 64 and n_entries <= n_cand <= 2047");
+    for (int b = 0; b < n_bins; ++b) if (hist[b] < 0) return fail(nullptr, SOP_EINVAL, "sop_dd_fit_grid: negative histogram entry");
+    for (int c = 0; c < n_cand; ++c) {
+        if (!std::isfinite(cand[c]) || std::fabs(cand[c]) > 4.0) return fail(nullptr, SOP_EATOM, "sop_dd_fit_grid: candidates must be finite and within [-4, 4]");
+        if (c > 0 && !(cand[c - 1] < cand[c])) return fail(nullptr, SOP_EATOM, "sop_dd_fit_grid: candidates must be strictly ascending");
+    }
+    const int H = n_bins, G = n_cand, N = n_entries;
+    // Bin b stands for its centre, numerator u_b = 2b+1-H in units of 1/H.  Prefix sums of the mass and of
+    // its first and second moments in these integer units are exact in 128 bits (mass < 2^63, |u| < 2^13);
+    // they are rounded once to the x87 extended format (64-bit significand), so the cost of sending a run of
+    // bins to one value, (S2 - 2a*S1 + a*a*S0) / H^2 with a = value * H (exact: H is a power of two), keeps
+    // some 15 digits after the cancellation between its terms.
+    std::vector<long double> p0(H + 1), p1(H + 1), p2(H + 1);
+    {
+        __int128 s0 = 0, s1 = 0, s2 = 0;
+        p0[0] = p1[0] = p2[0] = 0.0L;
+        for (int b = 0; b < H; ++b) {
+            const __int128 m = hist[b], u = 2 * b + 1 - H;
+            s0 += m; s1 += m * u; s2 += m * u * u;
+            p0[b + 1] = (long double)s0; p1[b + 1] = (long double)s1; p2[b + 1] = (long double)s2;
+        }
+    }
+    std::vector<long double> a(G);
+    for (int c = 0; c < G; ++c) a[c] = (long double)cand[c] * (long double)H;
+    auto run = [&](int c, int lo, int hi) -> double {              // bins [lo, hi) sent to candidate c, times H^2
+        if (hi <= lo) return 0.0;
+        const long double v = (p2[hi] - p2[lo]) - 2.0L * a[c] * (p1[hi] - p1[lo]) + a[c] * a[c] * (p0[hi] - p0[lo]);
+        return v > 0.0L ? (double)v : 0.0;
+    };
+    std::vector<double> centre(H);
+    for (int b = 0; b < H; ++b) centre[b] = -1.0 + (2.0 * (double)b + 1.0) / (double)H;
+    std::vector<int> upto(G);                                      // number of bins with centre <= candidate
+    {
+        int j = 0;
+        for (int c = 0; c < G; ++c) { while (j < H && centre[j] <= cand[c]) ++j; upto[c] = j; }
+    }
+    // Cost of two neighbouring chosen values c' < c: the bins above c' up to c go to the nearer of the two
+    // (centre <= midpoint: the lower):
+    //   pair(c', c) = run(c'; first bin above c', split) + run(c; split, first bin above c),
+    // split = number of bins whose centre is at most the midpoint; for a fixed c' it rises with c, so one
+    // sweep over the bins serves a whole row.  Stored with c as the row: the search below reads a row in order.
+    std::vector<double> pair_cost((size_t)G * G);
+    for (int cp = 0; cp < G; ++cp) {
+        int j = upto[cp];
+        for (int c = cp + 1; c < G; ++c) {
+            const double mid = 0.5 * (cand[cp] + cand[c]);
+            while (j < H && centre[j] <= mid) ++j;
+            pair_cost[(size_t)c * G + cp] = run(cp, upto[cp], j) + run(c, j, upto[c]);
+        }
+    }
+    // best[k][c]: least cost of the bins at or below candidate c when c is the k-th chosen value;
+    //   best[1][c] = all those bins sent to c,  best[k][c] = min over c' < c of best[k-1][c'] + pair(c', c);
+    // the bins above the last chosen value are added at the end.
+    std::vector<double> best((size_t)(N + 1) * G, HUGE_VAL);
+    std::vector<int> from((size_t)(N + 1) * G, -1);
+    for (int c = 0; c < G; ++c) best[(size_t)1 * G + c] = run(c, 0, upto[c]);
+    for (int k = 2; k <= N; ++k) {
+        const double* prev = &best[(size_t)(k - 1) * G];
+        for (int c = k - 1; c < G; ++c) {
+            const double* pc = &pair_cost[(size_t)c * G];
+            double bv = HUGE_VAL; int bp = -1;
+            for (int cp = k - 2; cp < c; ++cp) {
+                const double v = prev[cp] + pc[cp];
+                if (v < bv) { bv = v; bp = cp; }                  // equal sums: the lower candidate stays
+            }
+            best[(size_t)k * G + c] = bv; from[(size_t)k * G + c] = bp;
+        }
+    }
+    double total = HUGE_VAL; int last = -1;
+    for (int c = N - 1; c < G; ++c) {
+        const double v = best[(size_t)N * G + c] + run(c, upto[c], H);
+        if (v < total) { total = v; last = c; }
+    }
+    if (last < 0) return fail(nullptr, SOP_EINVAL, "sop_dd_fit_grid: no selection found");
+    for (int k = N, c = last; k >= 1; --k) { chosen[k - 1] = c; c = from[(size_t)k * G + c]; }
+    if (cost) *cost = total / ((double)H * (double)H);
+    if (!(cand[chosen[0]] < 0.0 && cand[chosen[N - 1]] > 0.0)) return fail(nullptr, SOP_EATOM, "sop_dd_fit_grid: the selected grid is one-sided");
+    return SOP_OK;
+}
+
 // ------------------------------------------------------------------ per-layer scale shift
 namespace {
 struct FmtRange { int x, y, bias, max_code; double lo, hi; };

@@ -5,7 +5,8 @@ Every pass over the weights runs in the HIP kernels: scoring every block against
 finishing reassignment (sop_pair_search), ranking the blocks and splitting the pools (sop_partition),
 the histogram of the fitting pool (sop_dd_histogram with a block mask), packing the result
 (sop_pack_blocks).  The host does what the paper leaves to the host: the loop over candidates, the
-Lloyd fit on the 1024-bin histogram (sop_dd_fit, microseconds) and the comparison of layer ACos values.
+fit on the 1024-bin histogram (sop_dd_fit: free Lloyd rounds, microseconds; or sop_dd_fit_grid: the
+selection among the grid points of an LUT value format) and the comparison of layer ACos values.
 
 Candidates examined for a layer:
   (1) every pair of fixed atoms of the alphabet (one search call);
@@ -46,8 +47,13 @@ def top_count(p_percent: float, n_blocks: int) -> int:
 
 def search_layer(ctx: B.Context, W, c, g: int, fmt: B.ScaleFmt, atoms: list, p_grid=(50.0, 70.0, 85.0, 95.0),
                  k: int = 0, metric: int = B.SEL_WSE, fit_entries: int = 16, fit_iters: int = 20, fit_bins: int = 1024,
-                 fit_init: np.ndarray | None = None, weighted_fit: bool = True, pack: bool = False) -> LayerResult:
-    """Run the search on one layer (W [M,K] bf16/fp32 and c [K] fp32 on the GPU)."""
+                 fit_init: np.ndarray | None = None, weighted_fit: bool = True, pack: bool = False,
+                 fit_grid: np.ndarray | None = None) -> LayerResult:
+    """Run the search on one layer (W [M,K] bf16/fp32 and c [K] fp32 on the GPU).
+
+    fit_grid: ascending candidate values in the atoms' units (largest magnitude 1, e.g. the E2M3 grid
+    divided by 7.5): the second codebook is then selected among them (grid-constrained construction)
+    instead of being fitted freely; fit_iters and fit_init are not used."""
     import torch
     M, K = W.shape
     Nb = M * K // g
@@ -83,7 +89,15 @@ def search_layer(ctx: B.Context, W, c, g: int, fmt: B.ScaleFmt, atoms: list, p_g
             pool_b, _, _ = ctx.partition(blk_cos[a], top_count(p, Nb), True)
             hists.append(ctx.dd_histogram(W, c if weighted_fit else None, g, fit_bins, 1, block_mask=pool_b))
     hs = torch.stack(hists).cpu().numpy().reshape(A, len(p_list), fit_bins)       # synchronises: 8 KB per (a, p)
-    fitted_all = [[B.sop_dd_fit(h, fit_entries, fit_iters, init) if h.sum() > 0 else init.copy() for h in hs[a]] for a in range(A)]
+    if fit_grid is None:
+        def fit(h):
+            return B.sop_dd_fit(h, fit_entries, fit_iters, init)
+    else:
+        cand = np.ascontiguousarray(fit_grid, dtype=np.float64)
+
+        def fit(h):
+            return cand[B.sop_dd_fit_grid(h, cand, fit_entries)[0]].astype(np.float32)
+    fitted_all = [[fit(h) if h.sum() > 0 else init.copy() for h in hs[a]] for a in range(A)]
     # step 4: one atom's whole sweep is scored by one call; the calls are queued, their tables read at the end
     pending = []
     for a in range(A):

@@ -110,3 +110,36 @@ def test_histogram_of_a_pool_of_blocks(g):
         got = gpu_hist(W, c, g, 512, True, row_step=row_step, mask=mask)
         assert np.array_equal(got, ref)
     assert gpu_hist(W, c, g, 512, True, mask=np.zeros_like(mask)).sum() == 0
+
+
+def test_grid_constrained_dd4_joins_the_alphabet():
+    # the codebook selected among the E4M3 grid's values (step 1 of the pair search, data-adaptive atom)
+    # from the GPU's histogram: same selection as the oracle's, and as an atom it serves the layer better
+    # than the free fit or NF4 snapped to the same grid
+    M, K, g, H = 512, 4096, 16, 1024
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 7300, row_sigma=0.5, outlier_frac=0.001))
+    c = si.channel_norms(K, 1.0, 7301)
+    hist = gpu_hist(W, c, g, H, True)
+    assert np.array_equal(hist, DD.histogram(W, c, g, H))
+    grid = sop.sop_weight_grid(sop.WeightFmt(4, 3, -1, -1))
+    cand = grid / grid[-1]
+    idx, cost = sop.sop_dd_fit_grid(hist, cand, 16)
+    ridx, rcost = DD.fit_grid(hist, cand, 16)
+    assert abs(cost - rcost) <= 1e-11 * rcost and np.array_equal(idx, ridx)
+    dd_grid = cand[idx].astype(np.float32)
+    free = sop.sop_dd_fit(hist, 16, 20, sop.sop_atom_nf(4)).astype(np.float64)
+    snapped = np.unique(cand[np.abs(cand[None, :] - free[:, None]).argmin(axis=1)]).astype(np.float32)
+    nf = sop.sop_atom_nf(4).astype(np.float64)
+    nf_snapped = np.unique(cand[np.abs(cand[None, :] - nf[:, None]).argmin(axis=1)]).astype(np.float32)
+    assert snapped.size == 16 and nf_snapped.size == 16
+    tabs = [sop.sop_atom_nf(4), dd_grid, snapped, nf_snapped]
+    fmt = sop.fmt_by_name("UE4M4")
+    gpu = run_gpu(W, c, tabs, g, fmt, bf16=True, emit=True)
+    ref = ops.pair_search(W, c, tabs, g, oracle_fmt(fmt))
+    assert np.array_equal(gpu["sel_words"], ref.sel_words) and np.array_equal(gpu["scale_code"], ref.scale_code)
+    for a in range(4):
+        assert np.array_equal(gpu["codes"][a], ref.codes[a])
+    assert np.max(np.abs(gpu["acos_atom"] - ref.acos_atom)) <= 1e-6
+    # among codebooks that live on the E4M3 grid, the one selected on the grid serves the layer best
+    # (the unconstrained NF4 table, which no E4M3 LUT can hold, is better still)
+    assert gpu["acos_atom"][1] > gpu["acos_atom"][2] and gpu["acos_atom"][1] > gpu["acos_atom"][3]

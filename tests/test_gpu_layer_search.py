@@ -12,7 +12,7 @@ from gpu_util import oracle_fmt, ctx
 pytestmark = pytest.mark.gpu
 
 
-def oracle_search(W, c, g, fmt, atoms, p_grid, entries, iters, bins):
+def oracle_search(W, c, g, fmt, atoms, p_grid, entries, iters, bins, grid=None):
     A = len(atoms)
     r = ops.pair_search(W, c, atoms, g, fmt, want_codes=False)
     fixed = r.acos_pair.copy()
@@ -21,7 +21,11 @@ def oracle_search(W, c, g, fmt, atoms, p_grid, entries, iters, bins):
     for a in range(A):
         for p in p_grid:
             _, pool_b, _ = PT.partition(r.blk_cos[a], PT.top_count(p, Nb), True)
-            Lb = OA.to_f32(DD.fit(DD.histogram(W, c, g, bins, block_mask=pool_b), entries, iters, atoms[0].astype(np.float64)))
+            h = DD.histogram(W, c, g, bins, block_mask=pool_b)
+            if grid is None:
+                Lb = OA.to_f32(DD.fit(h, entries, iters, atoms[0].astype(np.float64)))
+            else:
+                Lb = OA.to_f32(grid[DD.fit_grid(h, grid, entries)[0]])
             rr = ops.pair_search(W, c, [atoms[a], Lb], g, fmt, want_codes=False)
             fitted[(a, p)] = (float(rr.acos_pair[0]), Lb)
     return fixed, fitted
@@ -58,3 +62,27 @@ def test_search_of_one_layer_matches_the_oracle_procedure():
     num = (cw * wb * hb).sum(1); den = np.sqrt((cw * wb * wb).sum(1) * (cw * hb * hb).sum(1))
     cosv = np.where(den > 0, num / np.where(den > 0, den, 1), 1.0)
     assert abs(cosv.mean() - res.acos) <= 1e-6
+
+
+def test_search_with_the_second_codebook_selected_on_an_lut_grid():
+    """Step 3 with the grid-constrained construction: L_b is chosen among the E2M3 grid's values."""
+    import torch
+    M, K, g = 96, 1024, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 6200, row_sigma=0.5, outlier_frac=0.001))
+    c = si.channel_norms(K, 1.0, 6201)
+    atoms = [OA.to_f32(OA.nf(4)), OA.to_f32(OA.sh(4))]
+    fmt = sop.fmt_by_name("UE4M3")
+    p_grid = (60.0, 90.0)
+    grid = OA.exmy_grid(2, 3) / 7.5
+    assert np.array_equal(grid, sop.sop_weight_grid(sop.WeightFmt(2, 3, -1, -1)) / 7.5)
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    res = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=p_grid, fit_grid=grid)
+    fixed, fitted = oracle_search(W, c, g, oracle_fmt(fmt), atoms, p_grid, 16, 0, 1024, grid=grid)
+    assert np.max(np.abs(res.acos_fixed - fixed)) <= 1e-6
+    for key, (v, Lb) in fitted.items():
+        assert abs(res.acos_fitted[key] - v) <= 2e-5, key
+    ref_best = max([("fixed", float(v)) for v in fixed] + [("fitted", v) for v, _ in fitted.values()], key=lambda t: t[1])
+    assert abs(res.acos - ref_best[1]) <= 2e-5 and res.kind == ref_best[0]
+    if res.kind == "fitted":
+        assert np.all(np.isin(res.table_b.astype(np.float64), grid.astype(np.float32).astype(np.float64)))   # every entry is a grid value
