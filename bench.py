@@ -125,6 +125,39 @@ def timed_region(step, steps):
     return (time.perf_counter() - t0) / steps * 1e3, e0.elapsed_time(e1) / steps
 
 
+def bench_probe(args):
+    """Calibration: a plain read of the headline layer's bytes (and of the 70B-shaped layer's) by the
+    library's read-probe kernel; the time is the floor of every pass that reads a layer once."""
+    import torch
+    import paper_2605_14929_amd as sop
+    dev = torch.device("cuda", 0)
+    ctx = sop.Context(0)
+    out = torch.empty(2048, dtype=torch.int32, device=dev)
+    res = {}
+    for label, M, K, n_buf in (("4096x11008 bf16", 4096, 11008, args.buffers), ("28672x8192 bf16", 28672, 8192, 3)):
+        bufs = [torch.randint(-(1 << 31), (1 << 31) - 1, (M * K // 2,), dtype=torch.int32, device=dev) for _ in range(n_buf)]
+        for i in range(args.warmup):
+            ctx.read_probe(bufs[i % n_buf], out)
+        torch.cuda.synchronize()
+        ms_step, ev_ms = timed_region(lambda i: ctx.read_probe(bufs[i % n_buf], out), args.steps)
+        nbytes = M * K * 2
+        res[label] = {"bytes": nbytes, "event_ms_per_launch": ev_ms, "GB/s": nbytes / (ev_ms * 1e-3) / 1e9,
+                      "frac_of_published_peak": nbytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_rotated": n_buf}
+        del bufs
+    head = res["4096x11008 bf16"]
+    result = {
+        "metric": "bytes read/sec (plain read, calibration)", "value": head["GB/s"] * 1e9, "unit": "B/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["event_ms_per_launch"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "plain read of 90 MB (the C3 down-projection's bytes) by sopk::read_probe_kernel"},
+        "roofline": {"bound": "hbm", "achieved": head["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["frac_of_published_peak"],
+                     "traffic": None, "algorithmic_bytes_per_launch": head["bytes"], "kernel": "sopk::read_probe_kernel",
+                     "event_ms_per_launch": head["event_ms_per_launch"]},
+        "sizes": res, "untimed_clock_ramp_ms": CLOCK_RAMP_MS,
+    }
+    print(json.dumps(result))
+
+
 def bench_dd(args):
     """Statistics pass of the data-derived codebook on the headline layer (whole layer, 4096 bins):
     every weight is read once and adds its channel norm to one histogram bin."""
@@ -478,7 +511,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish", "model", "layer_search"],
+    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish", "model", "layer_search", "read_probe"],
                     help="pair_search (default): the headline six-atom search; dd_histogram: the statistics pass of the "
                          "data-derived codebook on the same layer; scale_histogram: the statistics pass of the per-layer "
                          "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer; finish: block ranking and pools, "
@@ -499,6 +532,8 @@ def main():
     import paper_2605_14929_amd as sop
     import sop_inputs as si
 
+    if args.workload == "read_probe":
+        return bench_probe(args)
     if args.workload == "dd_histogram":
         return bench_dd(args)
     if args.workload == "scale_histogram":

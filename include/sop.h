@@ -305,6 +305,15 @@ sop_status sop_layer_scope_error(sop_ctx* ctx, const void* W_dev, sop_dtype dtyp
                                  const float* c_dev, sop_weight_fmt wfmt, sop_scale_fmt sfmt, int layer_shift_k,
                                  double* out_dev, uint16_t* codes_dev, void* hip_stream);
 
+/* Calibration, not part of the method: a plain read of n_bytes (a multiple of 16) of DEVICE memory at
+ * x_dev (16-byte aligned) by SOP_READ_PROBE_WORDS workgroups, which is what every statistics pass above
+ * must at least do; its time is the floor their rooflines are judged against (the published HBM peak is
+ * not reachable by a kernel, and the reachable rate depends on the buffer's size).
+ * out_dev: DEVICE, SOP_READ_PROBE_WORDS uint32 words, overwritten: word b = exclusive-or of the 32-bit
+ * words workgroup b read; the exclusive-or of all of them is that of the whole buffer.  Asynchronous. */
+#define SOP_READ_PROBE_WORDS 2048
+sop_status sop_read_probe(sop_ctx* ctx, const void* x_dev, int64_t n_bytes, uint32_t* out_dev, void* hip_stream);
+
 /* out_dev[0] = sum of the n binary32 values at x_dev, accumulated in binary64 in a fixed order. */
 sop_status sop_sum_f32(sop_ctx* ctx, const float* x_dev, int64_t n, double* out_dev, void* hip_stream);
 

@@ -93,6 +93,7 @@ def lib():
         L.sop_layer_scope_error.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, WeightFmt, ScaleFmt,
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_sum_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        L.sop_read_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.sop_pair_search_layers.argtypes = [C.c_void_p, C.POINTER(_Layer), C.c_int, C.c_int, C.c_int, ScaleFmt, C.c_int,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_partition.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -343,6 +344,18 @@ class Context:
         out = torch.empty(1, dtype=torch.float64, device=x.device)
         st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
         _check(lib().sop_sum_f32(self._h, C.c_void_p(x.data_ptr()), x.numel(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
+        return out
+
+    def read_probe(self, x, out=None, stream=None):
+        """sop_read_probe on a contiguous CUDA tensor whose size is a multiple of 16 bytes; returns the
+        [2048] int32 device tensor of per-workgroup checksums."""
+        import torch
+        if not x.is_cuda or not x.is_contiguous():
+            raise SopError(1, "x must be a contiguous CUDA tensor")
+        if out is None:
+            out = torch.empty(2048, dtype=torch.int32, device=x.device)
+        st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
+        _check(lib().sop_read_probe(self._h, C.c_void_p(x.data_ptr()), x.numel() * x.element_size(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
         return out
 
     def pair_search_layers(self, layers, g, fmt: ScaleFmt, metric: int = SEL_WSE, shifts=None, want_sel: bool = False, stream=None):

@@ -21,8 +21,10 @@ extern "C" int sopk_variant_index(int is_bf16, int g, int sign_mode, int metric,
 extern "C" hipError_t sopk_launch(const void* fn, const KParams* p, int n_wg, int occ, size_t dyn_lds, void* stream);
 extern "C" hipError_t sopk_dd_launch(const DdParams* p, int is_bf16, int g, void* stream);
 extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void* stream);
+extern "C" int sopk_fl_weights_per_lane(int is_bf16, int g);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
 extern "C" hipError_t sopk_sum_launch(const LsParams* p, void* stream);
+extern "C" hipError_t sopk_probe_launch(const void* x, long long n16, unsigned int* out, void* stream);
 extern "C" hipError_t sopk_sel_launch(const SelParams* p, int n_wg_count, int n_wg, void* stream);
 extern "C" hipError_t sopk_pack_launch(const PackParams* p, void* stream);
 
@@ -64,7 +66,7 @@ struct sop_ctx {
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
     BinRec* d_bins = nullptr;             // [MAXBINS] capacity
-    unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, then the layer maxima (2 x u32) and 17 ticket counters (u32); zero between calls
+    unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, one spare word, 17 ticket counters (u32) from word 3*MAXWG+1, then SOP_K_LS_MAXREP copies of the layer maxima (2 x u32 each, 128 bytes apart) from word 3*MAXWG+16; zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
     int sel_set = 0;
@@ -133,8 +135,8 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(histogram)");
     }
-    if ((e = hipMalloc((void**)&c->d_ls, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2 + 9))) != hipSuccess ||
-        (e = hipMemset(c->d_ls, 0, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2 + 9))) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_ls, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2 + 9 + 5 + 16 * SOP_K_LS_MAXREP))) != hipSuccess ||
+        (e = hipMemset(c->d_ls, 0, sizeof(unsigned long long) * (3 * SOP_K_LS_MAXWG + 2 + 9 + 5 + 16 * SOP_K_LS_MAXREP))) != hipSuccess) {
         (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); if (c->d_ls) (void)hipFree(c->d_ls);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(partials)");
@@ -1082,7 +1084,7 @@ extern "C" sop_status sop_scale_histogram(sop_ctx* c, const void* W, sop_dtype d
     FmtRange r;
     if (!resolve_fmt(fmt, r)) return fail(c, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15, valid bias and max_code");
     if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
-    const int epl = dtype == SOP_BF16 ? 8 : 4;            // 16 bytes per lane and step
+    const int epl = sopk_fl_weights_per_lane(dtype == SOP_BF16, g);   // 16 or 32 bytes per lane and step
     FlParams p;
     std::memset(&p, 0, sizeof(p));
     p.W = W; p.M = M; p.K = K; p.ldw = ldw;
@@ -1093,6 +1095,10 @@ extern "C" sop_status sop_scale_histogram(sop_ctx* c, const void* W, sop_dtype d
     // running histogram, and atomics to one address are served one after the other
     long long wg = std::min<long long>((long long)c->n_cu, (p.total_units + waves_per_wg - 1) / waves_per_wg);
     p.n_waves = std::max<long long>(wg, 1) * waves_per_wg;
+    // the kernel keeps unit numbers in 32 bits
+    if (p.total_units >= (1ll << 31) - 4096) return fail(c, SOP_ESHAPE, "the layer has more than 2^31 wavefront steps");
+    p.units_per_wg = (int)(p.total_units / std::max<long long>(wg, 1));
+    p.units_rem = (int)(p.total_units % std::max<long long>(wg, 1));
     p.t_pos = t_pos; p.t_neg = t_neg;
     int e_top;
     p.m_top = std::frexp((float)r.hi, &e_top);
@@ -1175,12 +1181,24 @@ extern "C" sop_status sop_layer_scope_error(sop_ctx* c, const void* W, sop_dtype
     p.s_man = rs.y; p.s_bias = rs.bias; p.s_max_code = rs.max_code;
     p.k = k; p.pow2k = std::ldexp(1.0f, k);
     p.part = c->d_ls;
-    p.maxbits = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG);
+    p.maxbits = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG + 16);   // 128-byte aligned: one cache line per copy
     p.done = reinterpret_cast<unsigned int*>(c->d_ls + 3 * SOP_K_LS_MAXWG + 1);
     p.out = out; p.codes = codes;
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = sopk_ls_launch(&p, dtype == SOP_BF16, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_read_probe(sop_ctx* c, const void* x, int64_t n_bytes, uint32_t* out, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!x || !out || n_bytes < 16 || n_bytes % 16 != 0) return fail(c, SOP_EINVAL, "sop_read_probe: x and out must not be NULL, n_bytes a positive multiple of 16");
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(out) & 3u)) return fail(c, SOP_EINVAL, "sop_read_probe: misaligned pointer");
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_probe_launch(x, (long long)(n_bytes / 16), out, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }

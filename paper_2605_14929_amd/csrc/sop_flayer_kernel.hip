@@ -7,8 +7,8 @@
 // m exceeds `m_top` (the m of the scale format's largest value).  Counts are integers, so the result
 // does not depend on the order of addition.
 //
-// Work mapping as in the search kernel; one counter update per block (not per weight), so the pass
-// streams the layer at memory speed.  Workgroups count in LDS, add to the context's running
+// Work mapping as in the search kernel; the lanes count in registers and a wavefront adds its counts to
+// the workgroup's histogram in LDS a few times per launch.  Workgroups add to the context's running
 // histogram with integer atomics, and the workgroup that finishes last moves the result to the
 // caller's buffer and leaves zeros behind.
 #include <hip/hip_runtime.h>
@@ -17,6 +17,20 @@
 #include "sop_kparams.h"
 
 namespace sopk {
+
+// Sum of x over the 64 lanes with data-parallel-primitive moves on the vector ALU (quads, rows of 16
+// lanes, row 0 into 1 and 2 into 3, rows 0-1 into 3): the total is in lane 63.
+__device__ __forceinline__ unsigned int wave_total_in_lane63(unsigned int v)
+{
+    int x = (int)v;
+    x += __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
+    x += __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
+    x += __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);     // row_half_mirror
+    x += __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);     // row_mirror
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);     // row_bcast15 into rows 1, 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);     // row_bcast31 into rows 2, 3
+    return (unsigned int)x;
+}
 
 template <bool BF16, int EPL, int LPB>
 __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlParams p)
@@ -28,30 +42,82 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const long long wave = (long long)blockIdx.x * (SOP_K_FL_THREADS / 64) + wv;
-    const long long u0 = p.total_units * wave / p.n_waves;
-    const long long u1 = p.total_units * (wave + 1) / p.n_waves;
-    // row-major order: a wavefront's steps and neighbouring wavefronts cover consecutive memory.
-    // Steps are taken four at a time and the next four are requested before the current four are
-    // used, so that a wavefront keeps up to 8 KiB in flight (one load in flight per wavefront leaves
-    // the memory system three quarters idle).
+    // A workgroup takes a contiguous range of the layer's units (row-major: consecutive memory) and its
+    // wavefronts take the units of the range in turn, so that at any moment the workgroup reads one
+    // stretch of a few tens of KiB.  The (row, strip) of the next unit to load is kept on the scalar unit
+    // and advanced per load (one division per wavefront, none per step).  A lane reads 16 or 32 bytes per
+    // step; steps are taken UNR at a time and the next UNR are requested before the current ones are used:
+    // 64 bytes per lane, 4 KiB per wavefront in flight.
+    constexpr int WPG = SOP_K_FL_THREADS / 64;
+    // (the host gives total_units / workgroups and the remainder, and total_units is below 2^31: no 64-bit
+    // division here)
+    const unsigned int bq = (unsigned int)p.units_per_wg, br = (unsigned int)p.units_rem;
+    const unsigned int g0 = blockIdx.x * bq + (blockIdx.x < br ? blockIdx.x : br), g1 = g0 + bq + (blockIdx.x < br ? 1u : 0u);
+    const unsigned int u0 = g0 + (unsigned int)wv;
+    const int n_units = __builtin_amdgcn_readfirstlane(u0 < g1 ? (int)((g1 - u0 + WPG - 1) / WPG) : 0);
     constexpr int NV = BF16 ? EPL / 8 : EPL / 4;     // 16-byte pieces per lane and step
-    constexpr int UNR = 4;
-    auto load = [&](long long u, uint4 (&raw)[NV], bool& valid) {
-        const long long row = u / p.strips, st = u - row * p.strips;
-        const long long col0 = (st * 64 + lane) * EPL;
-        valid = u < u1 && col0 < p.K;
-        const char* src = reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4);
+    constexpr int UNR = 4 / NV;
+    const int strips = __builtin_amdgcn_readfirstlane((int)p.strips);
+    long long lrow = u0 / (unsigned int)strips;
+    int lst = __builtin_amdgcn_readfirstlane((int)(u0 - (unsigned int)lrow * (unsigned int)strips));
+    int loaded = 0;                                   // units requested so far
+    auto load = [&](uint4 (&raw)[NV], bool& valid) {
+        const long long col0 = ((long long)lst * 64 + lane) * EPL;
+        valid = loaded < n_units && col0 < p.K;
+        const char* src = reinterpret_cast<const char*>(p.W) + (lrow * p.ldw + col0) * (BF16 ? 2 : 4);
 #pragma unroll
-        for (int i = 0; i < NV; ++i) raw[i] = valid ? reinterpret_cast<const uint4*>(src)[i] : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < NV; ++i) {
+            raw[i] = make_uint4(0, 0, 0, 0);
+            if (valid) {                               // every weight is read once: the loads bypass-hint the caches
+                const unsigned int* q = reinterpret_cast<const unsigned int*>(src) + 4 * i;
+                raw[i].x = __builtin_nontemporal_load(q); raw[i].y = __builtin_nontemporal_load(q + 1);
+                raw[i].z = __builtin_nontemporal_load(q + 2); raw[i].w = __builtin_nontemporal_load(q + 3);
+            }
+        }
+        ++loaded;
+        lst += WPG;
+        while (lst >= strips) { lst -= strips; ++lrow; }
     };
     const bool unit_ends = p.t_pos == 1.0f && p.t_neg == 1.0f;      // uniform: a scalar branch
+    // Counting.  The block scales of a layer share a handful of binary exponents, so 64 lanes adding to
+    // LDS words would queue up on two or three addresses.  Instead every lane counts for itself, in
+    // registers: 16 eight-bit counters for the exponents [wbase, wbase + 16) and 16 more for the blocks
+    // above the top mantissa, wbase set by the first block the wavefront counts.  Every 255 steps and at
+    // the end the wavefront adds its lanes' counters (widened to 16 bits, two to a register, summed with
+    // data-parallel-primitive moves) and one lane adds the totals to the workgroup's histogram in LDS.  An
+    // exponent outside the window (rare) is added to LDS directly.
+    unsigned long long c_lo = 0ull, c_hi = 0ull, a_lo = 0ull, a_hi = 0ull;
+    int wbase = 0, pending = 0;
+    bool have_base = false;
+    auto flush = [&]() {
+        const unsigned long long regs[4] = {c_lo, c_hi, a_lo, a_hi};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const unsigned long long ev = regs[r] & 0x00FF00FF00FF00FFull, od = (regs[r] >> 8) & 0x00FF00FF00FF00FFull;
+            // fields 0,2 | 4,6 | 1,3 | 5,7 of this register, 16 bits each (a total is at most 64 * 255)
+            const unsigned int part[4] = {(unsigned int)ev, (unsigned int)(ev >> 32), (unsigned int)od, (unsigned int)(od >> 32)};
+            const int first_field[4] = {0, 4, 1, 5};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned int t = wave_total_in_lane63(part[q]);
+                if (lane == 63 && t != 0u) {
+                    const int f0 = (r & 1) * 8 + first_field[q];        // field of the low half; the high half is f0 + 2
+                    const int bin = (r >> 1) * SOP_K_FL_BINS + wbase + 160;
+                    if (t & 0xFFFFu) atomicAdd(&s_hist[bin + f0], t & 0xFFFFu);
+                    if (t >> 16) atomicAdd(&s_hist[bin + f0 + 2], t >> 16);
+                }
+            }
+        }
+        c_lo = c_hi = a_lo = a_hi = 0ull;
+        pending = 0;
+    };
+
     uint4 nxt[UNR][NV];
     bool nxt_valid[UNR];
 #pragma unroll
-    for (int j = 0; j < UNR; ++j) load(u0 + j, nxt[j], nxt_valid[j]);
+    for (int j = 0; j < UNR; ++j) load(nxt[j], nxt_valid[j]);
 
-    for (long long ub = u0; ub < u1; ub += UNR) {
+    for (int ub = 0; ub < n_units; ub += UNR) {
         uint4 cur[UNR][NV];
         bool cur_valid[UNR];
 #pragma unroll
@@ -61,7 +127,7 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
             for (int i = 0; i < NV; ++i) cur[j][i] = nxt[j][i];
         }
 #pragma unroll
-        for (int j = 0; j < UNR; ++j) load(ub + UNR + j, nxt[j], nxt_valid[j]);
+        for (int j = 0; j < UNR; ++j) load(nxt[j], nxt_valid[j]);
 #pragma unroll
         for (int j = 0; j < UNR; ++j) {
             const bool valid = cur_valid[j];
@@ -99,23 +165,31 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
             int e = 0;
             const float mant = frexpf(counted ? sc : 1.0f, &e);   // sc = mant * 2^e, 1/2 <= mant < 1 (subnormals included)
             const bool above = counted && mant > p.m_top;
-            // the scales of a layer share a handful of exponents: the wavefront counts its lanes per
-            // distinct exponent with ballots and one lane adds the count (64 lanes adding to one LDS
-            // word would be served one after the other)
-            unsigned long long todo = __ballot(counted);
-            while (todo) {
-                const int first = __builtin_ctzll(todo);
-                const int e0 = __builtin_amdgcn_readlane(e, first);
-                const unsigned long long same = __ballot(counted && e == e0);
-                const unsigned long long same_above = __ballot(above && e == e0);
-                if (lane == first) {
-                    atomicAdd(&s_hist[e0 + 160], (unsigned int)__builtin_popcountll(same));
-                    if (same_above) atomicAdd(&s_hist[SOP_K_FL_BINS + e0 + 160], (unsigned int)__builtin_popcountll(same_above));
+            if (!have_base) {
+                const unsigned long long any = __ballot(counted);
+                if (any) {
+                    // the first block's exponent, nine counters below it and six above (later blocks of a
+                    // strip of heavy-tailed weights are more often smaller than larger)
+                    wbase = __builtin_amdgcn_readlane(e, __builtin_ctzll(any)) - 9;
+                    have_base = true;
                 }
-                todo &= ~same;
             }
+            const unsigned int idx = (unsigned int)(e - wbase);
+            const bool inw = counted && idx < 16u;
+            const unsigned long long one = 1ull << ((idx & 7u) * 8u);
+            const unsigned long long add_lo = inw && idx < 8u ? one : 0ull, add_hi = inw && idx >= 8u ? one : 0ull;
+            c_lo += add_lo; c_hi += add_hi;
+            a_lo += above ? add_lo : 0ull; a_hi += above ? add_hi : 0ull;
+            if (__builtin_expect(__any(counted && !inw) != 0, 0)) {
+                if (counted && !inw) {
+                    atomicAdd(&s_hist[e + 160], 1u);
+                    if (above) atomicAdd(&s_hist[SOP_K_FL_BINS + e + 160], 1u);
+                }
+            }
+            if (++pending == 255) flush();
         }
     }
+    if (pending) flush();
     __syncthreads();
     // (all of a thread's atomics are issued before the first returned value is looked at: one round
     // trip; the values are consumed so that the adds have completed before the ticket below)
@@ -155,18 +229,21 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
 
 }  // namespace sopk
 
+extern "C" int sopk_fl_weights_per_lane(int is_bf16, int g) { return is_bf16 ? (g < 16 ? g : 16) : 8; }
+
 extern "C" hipError_t sopk_fl_launch(const FlParams* pp, int is_bf16, int g, void* stream)
 {
     FlParams p = *pp;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((unsigned)(p.n_waves / (SOP_K_FL_THREADS / 64))), block(SOP_K_FL_THREADS);
 #define SOPK_FL(B, E, L) hipLaunchKernelGGL((sopk::scale_hist_kernel<B, E, L>), grid, block, 0, st, p)
-    // a lane reads 16 bytes per step (8 bf16 or 4 fp32 weights): every load instruction of a wavefront
-    // covers 1 KiB of consecutive memory; g / (weights per lane) lanes share a block
+    // a lane reads 16 or 32 bytes per step (8 or 16 bf16 weights, 8 fp32 weights): every load instruction of
+    // a wavefront covers 1 KiB of consecutive memory; g / (weights per lane) lanes share a block.
+    // The host's strips are counted in these steps: sopk_fl_weights_per_lane().
     if (is_bf16) {
-        if (g == 8) SOPK_FL(true, 8, 1); else if (g == 16) SOPK_FL(true, 8, 2); else if (g == 32) SOPK_FL(true, 8, 4); else SOPK_FL(true, 8, 8);
+        if (g == 8) SOPK_FL(true, 8, 1); else if (g == 16) SOPK_FL(true, 16, 1); else if (g == 32) SOPK_FL(true, 16, 2); else SOPK_FL(true, 16, 4);
     } else {
-        if (g == 8) SOPK_FL(false, 4, 2); else if (g == 16) SOPK_FL(false, 4, 4); else if (g == 32) SOPK_FL(false, 4, 8); else SOPK_FL(false, 4, 16);
+        if (g == 8) SOPK_FL(false, 8, 1); else if (g == 16) SOPK_FL(false, 8, 2); else if (g == 32) SOPK_FL(false, 8, 4); else SOPK_FL(false, 8, 8);
     }
 #undef SOPK_FL
     return hipGetLastError();

@@ -134,6 +134,7 @@ struct FlParams {
     const void* W;
     long long M, K, ldw;
     long long strips, total_units, n_waves;
+    int units_per_wg, units_rem;     // total_units = workgroups * units_per_wg + units_rem
     float t_pos, t_neg;              // endpoints t+ and -t- of the codebook
     float m_top;                     // m of the scale format's largest value
     unsigned long long* acc;         // [2 * SOP_K_FL_BINS] running counts (zero between calls)
@@ -141,8 +142,12 @@ struct FlParams {
     long long* hist;                 // [2][SOP_K_FL_BINS] output
 };
 
+/* Read-rate calibration kernel: workgroups (of 256 threads) of one launch */
+#define SOP_K_PROBE_WG 2048
+
 /* Layer-scope weight formats and the binary64 sum */
 #define SOP_K_LS_MAXWG 2048
+#define SOP_K_LS_MAXREP 64           /* copies of the running layer maxima */
 struct LsParams {
     const void*  W;                  // weights (or the binary32 array of the sum kernel)
     const float* c;                  // null: c = 1
@@ -152,7 +157,7 @@ struct LsParams {
     int s_man, s_bias, s_max_code;   // scale word
     int k;
     float pow2k;
-    unsigned int* maxbits;           // [2] bit patterns of the largest positive / negative weight (zero between calls)
+    unsigned int* maxbits;           // [SOP_K_LS_MAXREP][32], two words used: bit patterns of the largest positive / negative weight (zero between calls)
     unsigned long long* part;        // [SOP_K_LS_MAXWG][3] workgroup partials (bit patterns of doubles)
     unsigned int* done;              // [17] tickets: over the groups, then per group of workgroups
     double* out;                     // [4] weighted error, plain error, ||W||_c^2, scale code   (sum kernel: [1])

@@ -150,17 +150,22 @@ __global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
     const long long wave = (long long)blockIdx.x * 4 + wv;
     const long long u0 = p.total_units * wave / p.n_waves, u1 = p.total_units * (wave + 1) / p.n_waves;
     float pmax = 0.0f, nmin = 0.0f;
+    // the (row, strip) of the next unit is kept on the scalar unit and advanced per load: one division per
+    // wavefront, none per step
+    const int strips = __builtin_amdgcn_readfirstlane((int)p.strips);
+    long long row = u0 / p.strips;
+    int st = __builtin_amdgcn_readfirstlane((int)(u0 - row * p.strips));
     // four steps in flight: the loads of a group are issued before any of them is used
     for (long long ub = u0; ub < u1; ub += 4) {
         uint4 t[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const long long u = ub + i;
-            const long long row = u / p.strips, st = u - row * p.strips;
-            const long long col0 = (st * 64 + lane) * EPL;
+            const long long col0 = ((long long)st * 64 + lane) * EPL;
             t[i] = make_uint4(0, 0, 0, 0);
             if (u < u1 && col0 < p.K)
                 t[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (row * p.ldw + col0) * (BF16 ? 2 : 4));
+            if (++st == strips) { st = 0; ++row; }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -186,7 +191,10 @@ __global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
     if (threadIdx.x < 2) {
         const float v = fmaxf(fmaxf(s_m[threadIdx.x][0], s_m[threadIdx.x][1]), fmaxf(s_m[threadIdx.x][2], s_m[threadIdx.x][3]));
         const unsigned int bits = __float_as_uint(v);          // non-negative floats order like their bit patterns
-        if (bits > __hip_atomic_load(p.maxbits + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(p.maxbits + threadIdx.x, bits);
+        // (the running maxima have SOP_K_LS_MAXREP copies, chosen by workgroup number: the first workgroups
+        // all finish at once and all find the running value still low)
+        unsigned int* mb = p.maxbits + 32 * (blockIdx.x & (SOP_K_LS_MAXREP - 1)) + threadIdx.x;   // copies 128 bytes apart
+        if (bits > __hip_atomic_load(mb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(mb, bits);
     }
 }
 
@@ -201,8 +209,11 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
     const long long u0 = p.total_units * wave / p.n_waves, u1 = p.total_units * (wave + 1) / p.n_waves;
 
     // ---- the layer's scale: the block rule with the whole layer as the block ----
-    const float pmax = __uint_as_float(__hip_atomic_load(p.maxbits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    const float nmax = __uint_as_float(__hip_atomic_load(p.maxbits + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    static_assert(SOP_K_LS_MAXREP == 64, "one copy of the running maxima per lane");
+    float pmax = __uint_as_float(__hip_atomic_load(p.maxbits + 32 * lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    float nmax = __uint_as_float(__hip_atomic_load(p.maxbits + 32 * lane + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+#pragma unroll
+    for (int sh = 1; sh < 64; sh <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, sh, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, sh, 64)); }
     const float tp = exmy_decode(p.w_max_code, p.w_man, p.w_bias, 0);            // the grid is symmetric: t+ = -t-
     const float sstar = fmaxf(pmax / tp, nmax / tp);
     const int q = exmy_encode(sstar * p.pow2k, p.s_man, p.s_bias, p.s_max_code, false);
@@ -289,7 +300,7 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
     const double v3[3] = {acc_w, acc_u, acc_n};
     if (finish_sums<3>(v3, p.part, p.done, p.out, s_buf)) {
         if (threadIdx.x == 0) p.out[3] = (double)q;
-        if (threadIdx.x == 1) { atomicExch(p.maxbits, 0u); atomicExch(p.maxbits + 1, 0u); }   // zero for the next call
+        if (threadIdx.x < 2 * SOP_K_LS_MAXREP) atomicExch(p.maxbits + 32 * (threadIdx.x >> 1) + (threadIdx.x & 1), 0u);   // zero for the next call
     }
 }
 
@@ -313,8 +324,13 @@ extern "C" hipError_t sopk_ls_launch(const LsParams* pp, int is_bf16, void* stre
     LsParams p = *pp;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((unsigned)(p.n_waves / 4)), block(256);
-    if (is_bf16) hipLaunchKernelGGL(sopk::layer_max_kernel<true>, grid, block, 0, st, p);
-    else hipLaunchKernelGGL(sopk::layer_max_kernel<false>, grid, block, 0, st, p);
+    // the maxima pass keeps nothing per workgroup, so it is cut four times finer: compute units that get
+    // through their share early take further workgroups (17 us instead of 20 for a 90 MB layer)
+    LsParams pm = p;
+    pm.n_waves = 4 * p.n_waves;
+    const dim3 grid_max((unsigned)(pm.n_waves / 4));
+    if (is_bf16) hipLaunchKernelGGL(sopk::layer_max_kernel<true>, grid_max, block, 0, st, pm);
+    else hipLaunchKernelGGL(sopk::layer_max_kernel<false>, grid_max, block, 0, st, pm);
     if (is_bf16) {
         if (p.codes) hipLaunchKernelGGL((sopk::layer_scope_kernel<true, true>), grid, block, 0, st, p);
         else hipLaunchKernelGGL((sopk::layer_scope_kernel<true, false>), grid, block, 0, st, p);
