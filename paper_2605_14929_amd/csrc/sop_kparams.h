@@ -82,7 +82,7 @@ struct KParams {
     // atomics (order-independent, so the result is reproducible); the workgroup that finishes last
     // turns them into the ACos outputs and leaves sums and counter at zero for the next call
     unsigned long long* sums;        // [SOP_K_REPL][SOP_K_NCOL]
-    unsigned int* done;              // [1 + SOP_K_REPL] tickets: over the replicas, then per replica
+    unsigned int* done;              // workgroups finished (zero between calls; room for 1 + SOP_K_REPL words)
     double*   acos_pair;
     double*   acos_atom;
     void*     sel_words;             // [Nb] selector word of every block

@@ -897,19 +897,14 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             asm volatile("" :: "v"(before) : "memory");
         }
     }
-    // ---- layer reduction: tickets in two levels (per replica, then over the replicas); the
-    //      workgroup that takes the very last ticket finishes the layer ----
+    // ---- layer reduction: every workgroup takes a ticket; the one that takes the last finishes the
+    //      layer.  (One counter: the workgroups do not end at the same instant, and a second level of
+    //      counters only put one more round trip to memory on the last workgroup's path.) ----
     __syncthreads();
     unsigned int* s_flag = reinterpret_cast<unsigned int*>(s_red);
     if (threadIdx.x == 0) {
-        const unsigned int r = blockIdx.x % SOP_K_REPL;
-        const unsigned int in_group = (gridDim.x - r + SOP_K_REPL - 1) / SOP_K_REPL;
-        const unsigned int groups = gridDim.x < SOP_K_REPL ? gridDim.x : SOP_K_REPL;
         unsigned int last = 0u;
-        if (atomicAdd(p.done + 1 + r, 1u) == in_group - 1) {
-            atomicExch(p.done + 1 + r, 0u);
-            if (atomicAdd(p.done, 1u) == groups - 1) { atomicExch(p.done, 0u); last = 1u; }
-        }
+        if (atomicAdd(p.done, 1u) == gridDim.x - 1) { atomicExch(p.done, 0u); last = 1u; }
         *s_flag = last;
     }
     __syncthreads();
