@@ -209,11 +209,19 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
     const long long u0 = p.total_units * wave / p.n_waves, u1 = p.total_units * (wave + 1) / p.n_waves;
 
     // ---- the layer's scale: the block rule with the whole layer as the block ----
+    // (the copies of the running maxima sit in 64 lines: one wavefront of the workgroup reads them, the
+    // others take the result from LDS; every wavefront reading them cost the pass 3 us)
     static_assert(SOP_K_LS_MAXREP == 64, "one copy of the running maxima per lane");
-    float pmax = __uint_as_float(__hip_atomic_load(p.maxbits + 32 * lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    float nmax = __uint_as_float(__hip_atomic_load(p.maxbits + 32 * lane + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    __shared__ float s_mx[2];
+    if (wv == 0) {
+        float a = __uint_as_float(__hip_atomic_load(p.maxbits + 32 * lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        float b = __uint_as_float(__hip_atomic_load(p.maxbits + 32 * lane + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 #pragma unroll
-    for (int sh = 1; sh < 64; sh <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, sh, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, sh, 64)); }
+        for (int sh = 1; sh < 64; sh <<= 1) { a = fmaxf(a, __shfl_xor(a, sh, 64)); b = fmaxf(b, __shfl_xor(b, sh, 64)); }
+        if (lane == 0) { s_mx[0] = a; s_mx[1] = b; }
+    }
+    __syncthreads();
+    const float pmax = s_mx[0], nmax = s_mx[1];
     const float tp = exmy_decode(p.w_max_code, p.w_man, p.w_bias, 0);            // the grid is symmetric: t+ = -t-
     const float sstar = fmaxf(pmax / tp, nmax / tp);
     const int q = exmy_encode(sstar * p.pow2k, p.s_man, p.s_bias, p.s_max_code, false);
