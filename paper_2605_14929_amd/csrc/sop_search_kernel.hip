@@ -577,67 +577,63 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     for (int i = 0; i < SOP_K_MAXA; ++i) acca[i] = 0;
 #pragma unroll
     for (int i = 0; i < SOP_K_MAXP; ++i) accp[i] = 0;
-    // Lane sums of a column, exact: a lane holds at most 128 steps x 2^23, so the value is split at bit 15
-    // and both halves are added over the 64 lanes with data-parallel-primitive moves on the vector ALU
-    // (quads, rows of 16 lanes, row 0 into 1 and 2 into 3, rows 0-1 into 3; total in lane 63), which then
-    // adds the 64-bit total to the workgroup's sum.
-    auto lane_sum_to = [&](int v, int col) {
-        auto dpp_add = [](int x, auto ctrl, auto row_mask) {
-            return x + __builtin_amdgcn_update_dpp(0, x, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false);
-        };
-        using std::integral_constant;
-        int lo = v & 0x7FFF, hi = v >> 15;
-#define SOPK_DPP6(x)                                                                        \
-        x = dpp_add(x, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});    /* quad_perm [1,0,3,2] */ \
-        x = dpp_add(x, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});    /* quad_perm [2,3,0,1] */ \
-        x = dpp_add(x, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});   /* row_half_mirror */     \
-        x = dpp_add(x, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});   /* row_mirror */          \
-        x = dpp_add(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});   /* row_bcast15 into rows 1, 3 */ \
-        x = dpp_add(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});   /* row_bcast31 into rows 2, 3 */
-        SOPK_DPP6(lo)
-        SOPK_DPP6(hi)
-#undef SOPK_DPP6
-        if (lane == 63) atomicAdd(&s_acc[col], (unsigned long long)(((long long)hi << 15) + (long long)lo));
-    };
-    // the sum over the wavefront of lane values below 2^27, as a scalar: every row of 16 lanes is added up in
-    // 32 bits on the vector ALU (quads, half rows, rows), the four row sums in 64 bits on the scalar unit
-    auto wave_sum_small = [](int x) -> long long {
+    // Lane sums of a column, exact.  A row of 16 lanes is added up with data-parallel-primitive moves on the
+    // vector ALU (quads, half rows, rows: every lane of the row then holds the row's sum), and the first lane
+    // of each row adds its row's sum to the workgroup's 64-bit sum in LDS: four lanes to one word per column.
+    // (This translation unit is compiled
+    // with the compiler's atomic optimizer off: it would turn each of these adds into a loop over the
+    // active lanes.)
+    auto row_sum = [](int x) -> int {
         x += __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
         x += __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
         x += __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);     // row_half_mirror
         x += __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);     // row_mirror
-        return (long long)__builtin_amdgcn_readlane(x, 0) + (long long)__builtin_amdgcn_readlane(x, 16) +
-               (long long)__builtin_amdgcn_readlane(x, 32) + (long long)__builtin_amdgcn_readlane(x, 48);
+        return x;
     };
     int cl = MULTI ? -1 : 0;                       // the layer the arithmetic is in
     // few: the lanes hold at most 15 steps (a wavefront's share of a layer of a few thousand rows: the rule at
     // a change of layer in the model-wide kernel, and at the end of a single call on such a layer).  Then a
-    // lane holds at most 15 * 2^23 and a row of 16 lanes less than 2^31: one 32-bit pass over quads and rows,
-    // the four row sums added on the scalar unit, and one lane adds the total to the workgroup's (half the
-    // vector instructions of the general form below).  (Four lanes adding their row sums to one LDS word
-    // instead made a single call 2 us slower.)
+    // lane holds at most 15 * 2^23 and a row of 16 lanes less than 2^31: one 32-bit pass per column.  In
+    // general a lane holds at most 128 steps x 2^23 < 2^31: the value is split at bit 15 and both halves are
+    // added over the row (below 2^19 and 2^20), then joined in 64 bits.
     auto flush = [&](int layer, bool few) {
         const int c0 = MULTI ? layer * SOP_K_NCOL : 0;
+        const bool row_lead = (lane & 15) == 0;
+        constexpr int NCOLS = SOP_K_MAXA + SOP_K_MAXP + 1;
+        int col_of[NCOLS], val[NCOLS], n = 0;        // the live columns of this variant (compile-time list)
+#pragma unroll
+        for (int i = 0; i < NA; ++i) { col_of[n] = i; val[n] = acca[i]; acca[i] = 0; ++n; }
+#pragma unroll
+        for (int i = 0; i < SOP_K_MAXP; ++i)
+            if (kPairTab.second[i] < NA) { col_of[n] = SOP_K_MAXA + i; val[n] = accp[i]; accp[i] = 0; ++n; }
+        col_of[n] = SOP_K_ZCOL; val[n] = accz; accz = 0; ++n;
+        // four columns at a time: their chains of moves are independent and fill each other's wait states,
+        // and few values are live at once
+        constexpr int B = 4;
         if (few) {
-            auto add_small = [&](int v, int col) {
-                const long long t = wave_sum_small(v);
-                if (lane == 0) atomicAdd(&s_acc[col], (unsigned long long)t);
-            };
 #pragma unroll
-            for (int i = 0; i < NA; ++i) { add_small(acca[i], c0 + i); acca[i] = 0; }
+            for (int j0 = 0; j0 < NCOLS; j0 += B) {
+                int rs[B];
 #pragma unroll
-            for (int i = 0; i < SOP_K_MAXP; ++i)
-                if (kPairTab.second[i] < NA) { add_small(accp[i], c0 + SOP_K_MAXA + i); accp[i] = 0; }
-            add_small(accz, c0 + SOP_K_ZCOL);
-            accz = 0;
+                for (int j = 0; j < B; ++j) if (j0 + j < n) rs[j] = row_sum(val[j0 + j]);
+                if (row_lead) {
+#pragma unroll
+                    for (int j = 0; j < B; ++j) if (j0 + j < n) atomicAdd(&s_acc[c0 + col_of[j0 + j]], (unsigned long long)(long long)rs[j]);   // (a lane's sum can be a few units below zero: sign-extended)
+                }
+            }
             return;
         }
 #pragma unroll
-        for (int i = 0; i < NA; ++i) { lane_sum_to(acca[i], c0 + i); acca[i] = 0; }
+        for (int j0 = 0; j0 < NCOLS; j0 += B) {
+            int rl[B], rh[B];
 #pragma unroll
-        for (int i = 0; i < SOP_K_MAXP; ++i)
-            if (kPairTab.second[i] < NA) { lane_sum_to(accp[i], c0 + SOP_K_MAXA + i); accp[i] = 0; }
-        lane_sum_to(accz, c0 + SOP_K_ZCOL); accz = 0;
+            for (int j = 0; j < B; ++j) if (j0 + j < n) { rl[j] = row_sum(val[j0 + j] & 0x7FFF); rh[j] = row_sum(val[j0 + j] >> 15); }
+            if (row_lead) {
+#pragma unroll
+                for (int j = 0; j < B; ++j)
+                    if (j0 + j < n) atomicAdd(&s_acc[c0 + col_of[j0 + j]], (unsigned long long)(((long long)rh[j] << 15) + (long long)rl[j]));
+            }
+        }
     };
     // what the arithmetic needs of its layer
     const float* lc_c = nullptr;
