@@ -18,17 +18,15 @@
 
 namespace sopk {
 
-// Sum of x over the 64 lanes with data-parallel-primitive moves on the vector ALU (quads, rows of 16
-// lanes, row 0 into 1 and 2 into 3, rows 0-1 into 3): the total is in lane 63.
-__device__ __forceinline__ unsigned int wave_total_in_lane63(unsigned int v)
+// Sum of x over every row of 16 lanes with data-parallel-primitive moves on the vector ALU (quads, half
+// rows, rows): every lane of a row then holds the row's sum.
+__device__ __forceinline__ unsigned int row_total(unsigned int v)
 {
     int x = (int)v;
     x += __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
     x += __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
     x += __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);     // row_half_mirror
     x += __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);     // row_mirror
-    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);     // row_bcast15 into rows 1, 3
-    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);     // row_bcast31 into rows 2, 3
     return (unsigned int)x;
 }
 
@@ -83,28 +81,33 @@ __global__ __launch_bounds__(SOP_K_FL_THREADS) void scale_hist_kernel(const FlPa
     // LDS words would queue up on two or three addresses.  Instead every lane counts for itself, in
     // registers: 16 eight-bit counters for the exponents [wbase, wbase + 16) and 16 more for the blocks
     // above the top mantissa, wbase set by the first block the wavefront counts.  Every 255 steps and at
-    // the end the wavefront adds its lanes' counters (widened to 16 bits, two to a register, summed with
-    // data-parallel-primitive moves) and one lane adds the totals to the workgroup's histogram in LDS.  An
+    // the end the wavefront adds its lanes' counters over every row of 16 lanes (widened to 16 bits, two to a
+    // register, summed with data-parallel-primitive moves) and the first lane of each row adds the row's totals
+    // to the workgroup's histogram in LDS (compiled with the compiler's atomic optimizer off, which would wrap
+    // each of these adds in a scan over the active lanes).  An
     // exponent outside the window (rare) is added to LDS directly.
     unsigned long long c_lo = 0ull, c_hi = 0ull, a_lo = 0ull, a_hi = 0ull;
     int wbase = 0, pending = 0;
     bool have_base = false;
     auto flush = [&]() {
         const unsigned long long regs[4] = {c_lo, c_hi, a_lo, a_hi};
+        const bool row_lead = (lane & 15) == 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const unsigned long long ev = regs[r] & 0x00FF00FF00FF00FFull, od = (regs[r] >> 8) & 0x00FF00FF00FF00FFull;
-            // fields 0,2 | 4,6 | 1,3 | 5,7 of this register, 16 bits each (a total is at most 64 * 255)
+            // fields 0,2 | 4,6 | 1,3 | 5,7 of this register, 16 bits each (a row's total is at most 16 * 255)
             const unsigned int part[4] = {(unsigned int)ev, (unsigned int)(ev >> 32), (unsigned int)od, (unsigned int)(od >> 32)};
             const int first_field[4] = {0, 4, 1, 5};
+            unsigned int t[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const unsigned int t = wave_total_in_lane63(part[q]);
-                if (lane == 63 && t != 0u) {
-                    const int f0 = (r & 1) * 8 + first_field[q];        // field of the low half; the high half is f0 + 2
-                    const int bin = (r >> 1) * SOP_K_FL_BINS + wbase + 160;
-                    if (t & 0xFFFFu) atomicAdd(&s_hist[bin + f0], t & 0xFFFFu);
-                    if (t >> 16) atomicAdd(&s_hist[bin + f0 + 2], t >> 16);
+            for (int q = 0; q < 4; ++q) t[q] = row_total(part[q]);      // four independent chains
+            if (row_lead) {                                               // four lanes add their rows' totals
+                const int bin = (r >> 1) * SOP_K_FL_BINS + wbase + 160 + (r & 1) * 8;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int f0 = first_field[q];                        // field of the low half; the high half is f0 + 2
+                    if (t[q] & 0xFFFFu) atomicAdd(&s_hist[bin + f0], t[q] & 0xFFFFu);
+                    if (t[q] >> 16) atomicAdd(&s_hist[bin + f0 + 2], t[q] >> 16);
                 }
             }
         }
