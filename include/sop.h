@@ -263,7 +263,9 @@ sop_status sop_dd_fit_grid(const int64_t* hist, int n_bins, const double* cand, 
  * sc = m * 2^e with 1/2 <= m < 1, hist[e + 160] counts the blocks with that e, and
  * hist[320 + e + 160] those among them whose m exceeds the m of the format's largest value.
  * Blocks with sc = 0 are not counted.  hist_dev: DEVICE, 640 64-bit integers, overwritten.
- * Asynchronous; needs no workspace; calls on one context must not overlap on the GPU. */
+ * SOP_ESHAPE for a layer of 2^31 or more wavefront steps (a step is 64 lanes x 8 or 16 weights:
+ * about 10^12 weights).  Asynchronous; needs no workspace; calls on one context must not overlap on
+ * the GPU. */
 sop_status sop_scale_histogram(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw, int g,
                                float t_pos, float t_neg, sop_scale_fmt fmt, int64_t* hist_dev, void* hip_stream);
 
