@@ -151,6 +151,27 @@ sop_status sop_pair_search(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int
                            const float* c_dev, int g, sop_scale_fmt fmt, int layer_shift_k, sop_metric metric,
                            void* workspace_dev, size_t workspace_bytes, const sop_outputs* out, void* hip_stream);
 
+/* sop_pair_search() for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (without the workspace), same kernels, same results bit
+ * for bit; the call itself calls no hipMalloc / hipFree and no allocating library routine.  What
+ * sop_pair_search() keeps in memory of the context allocated on demand (the running sums and ticket
+ * counters of the layer reduction, the table of (scale, reciprocal) per scale code) lives here in a
+ * statically allocated device array of SOP_STATIC_SCRATCH_BYTES bytes that is part of the library's device
+ * image: every GPU the library runs on holds one copy until the process ends.  A small kernel at the start
+ * of the call clears the sums and writes the scale table for (fmt, layer_shift_k); it is launched on
+ * hip_stream before the search kernel (no memset node, so the pair may be captured into a graph).
+ * Limit: the scale word may have at most SOP_STATIC_MAX_CODES magnitude codes (max_code < 2048, i.e.
+ * x + y <= 11); a wider word is refused with SOP_EFMT (sop_pair_search() decodes such words arithmetically).
+ * The context must have been created and given its alphabet beforehand (those calls allocate).  All static
+ * calls on one GPU share the one array, whatever the context or stream: calls that overlap on a GPU race;
+ * issue them on one stream or order them with events.  The first call of a kernel variant on a context
+ * queries its occupancy (no allocation). */
+#define SOP_STATIC_MAX_CODES     2048
+#define SOP_STATIC_SCRATCH_BYTES (2560 + 8 * SOP_STATIC_MAX_CODES)
+sop_status sop_pair_search_static(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                  const float* c_dev, int g, sop_scale_fmt fmt, int layer_shift_k, sop_metric metric,
+                                  const sop_outputs* out, void* hip_stream);
+
 /* Text of the last error on this context (or of the last failed sop_create when ctx is NULL). */
 const char* sop_last_error(sop_ctx* ctx);
 

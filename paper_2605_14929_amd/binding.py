@@ -76,6 +76,8 @@ def lib():
         L.sop_workspace_bytes.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
         L.sop_pair_search.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
                                       ScaleFmt, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(_Outputs), C.c_void_p]
+        L.sop_pair_search_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
+                                             ScaleFmt, C.c_int, C.c_int, C.POINTER(_Outputs), C.c_void_p]
         L.sop_last_error.argtypes = [C.c_void_p]
         L.sop_last_error.restype = C.c_char_p
         L.sop_atom_nf.argtypes = [C.c_int, C.POINTER(C.c_float)]
@@ -474,9 +476,10 @@ class Context:
         return hist
 
     def pair_search(self, W, c, g, fmt: ScaleFmt, k: int = 0, metric: int = SEL_WSE, out: Outputs = None,
-                    emit: bool = False, stream=None) -> Outputs:
+                    emit: bool = False, stream=None, static: bool = False) -> Outputs:
         """sop_pair_search on torch CUDA tensors: W [M,K] float32 or bfloat16 (row stride = W.stride(0)),
-        c [K] float32.  Asynchronous on the current (or given) stream."""
+        c [K] float32.  Asynchronous on the current (or given) stream.  static=True calls
+        sop_pair_search_static (the caller then passes `out`, so that nothing is allocated)."""
         import torch
         if not (W.is_cuda and c.is_cuda):
             raise SopError(1, "W and c must be CUDA tensors (no CPU fallback)")
@@ -503,6 +506,10 @@ class Context:
 
         o = _Outputs(ptr(out.acos_pair), ptr(out.acos_atom), ptr(out.sel_words), ptr(out.scale_code), ptr(out.codes),
                      ptr(out.blk_cos), ptr(out.blk_err))
+        if static:
+            _check(lib().sop_pair_search_static(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
+                                                fmt, k, metric, C.byref(o), C.c_void_p(st)), self._h)
+            return out
         _check(lib().sop_pair_search(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
                                      fmt, k, metric, None if self._ws is None else C.c_void_p(self._ws.data_ptr()),
                                      0 if self._ws is None else self._ws.numel(), C.byref(o),

@@ -44,6 +44,48 @@ static constexpr int kLanes = 2;          // streams of its own that sop_pair_se
 static constexpr int kMaxLayers = 1024;  // layers of one launch of the model-wide kernel (more are dealt with in several launches)
 static constexpr size_t kSumsWords = SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1;   // one set of layer sums and tickets, in 64-bit words
 
+// ---- scratch of the entry point that allocates nothing (sop_pair_search_static) ----
+// One set of layer sums with its ticket counters, then the (scale, reciprocal) table of the call's scale
+// word.  The array lives in the library's device image: every GPU the library runs on holds its own copy
+// at its own address until the process ends.  Host code never uses the array's name as an address: the
+// address on a device comes from hipGetSymbolAddress (static_scratch_of) and is what kernels are given.
+static constexpr size_t kStaticSumsBytes = (kSumsWords * sizeof(unsigned long long) + 255) & ~(size_t)255;
+static constexpr size_t kStaticBytes = kStaticSumsBytes + (size_t)SOP_STATIC_MAX_CODES * sizeof(float2);
+static_assert(kStaticBytes == SOP_STATIC_SCRATCH_BYTES, "the header states the size of the static scratch");
+static __device__ __align__(256) unsigned char sop_static_scratch[kStaticBytes];
+static constexpr int kMaxDevices = 64;
+static unsigned char* g_static_ptr[kMaxDevices] = {nullptr};   // per device, filled once by static_scratch_of()
+
+// Address of this device's copy of the scratch array (the device must be current).
+static hipError_t static_scratch_of(int device, unsigned char** out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_static_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(sop_static_scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_static_ptr[device] = static_cast<unsigned char*>(ptr);
+    }
+    *out = g_static_ptr[device];
+    return hipSuccess;
+}
+
+// Start of a static call: the sums and tickets are cleared (an earlier call that did not finish may have left
+// anything there) and the scale table of this call's scale word and layer shift is written:
+// value(q) * 2^-k (exact) and its IEEE reciprocal, the same values the host builds for sop_pair_search.
+__global__ void static_prologue_kernel(unsigned long long* sums, int n_words, float2* tab, int n_codes, int y, int bias, int k)
+{
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < n_words) sums[i] = 0ull;
+    if (i < n_codes) {
+        const int e = i >> y, f = i & ((1 << y) - 1);
+        const float s = e == 0 ? ldexpf((float)f, 1 - bias - y - k) : ldexpf((float)((1 << y) + f), e - bias - y - k);
+        tab[i] = make_float2(s, s > 0.0f ? 1.0f / s : 0.0f);
+    }
+}
+
 struct sop_ctx {
     int device = 0;
     int n_cu = 0;
@@ -75,6 +117,7 @@ struct sop_ctx {
     hipEvent_t lane_event[kLanes + 1] = {};  // one per stream (join) and one for the fork
     std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
     int scale_rule = 0;                   // 0: absmax, 1: argmax
+    unsigned char* static_scratch = nullptr;   // this device's copy of sop_static_scratch (looked up by sop_create)
     int occ_blocks[864];                  // resident workgroups per CU of each kernel variant (0 = unknown)
     size_t occ_lds[864];
     std::string err;
@@ -160,6 +203,11 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
         delete c;
         return hipfail(nullptr, e, "hipMalloc(layer list)");
+    }
+    if ((e = static_scratch_of(device, &c->static_scratch)) != hipSuccess) {
+        hipError_t keep = e;
+        sop_destroy(c);
+        return hipfail(nullptr, keep, "hipGetSymbolAddress(static scratch)");
     }
     *out = c;
     return SOP_OK;
@@ -470,7 +518,7 @@ static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, 
 static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                                    const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
                                    void* ws, size_t ws_bytes, const sop_outputs* out, void* stream, bool launch, int sums_set = 0,
-                                   KParams* p_out = nullptr, size_t* lds_out = nullptr)
+                                   KParams* p_out = nullptr, size_t* lds_out = nullptr, bool use_static = false)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !cn || !out) return fail(c, SOP_EINVAL, "sop_pair_search: W, c and out must not be NULL");
@@ -502,6 +550,11 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
         return fail(c, SOP_EFMT, "scale format with this layer shift leaves binary32's normal range (choose bias / max_code / k accordingly)");
 
     (void)ws; (void)ws_bytes;         // no workspace is needed (sop_workspace_bytes reports 0)
+    if (use_static) {
+        if (max_code >= SOP_STATIC_MAX_CODES)
+            return fail(c, SOP_EFMT, "sop_pair_search_static: the scale word has more magnitude codes than the static scale table holds (2048); use sop_pair_search");
+        if (!c->static_scratch) return fail(c, SOP_EHIP, "sop_pair_search_static: the static scratch of this device was not found");
+    }
 
     const int epl = g < 16 ? g : 16, lpb = g / epl;
     const int A = c->n_atoms;
@@ -544,7 +597,7 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
         p.pair_slot_w[pi / 4] |= (unsigned)q << (8 * (pi % 4));
         p.pair_pi[q] = (unsigned char)pi;
     }
-    p.sums = c->d_sums + (size_t)sums_set * kSumsWords;
+    p.sums = use_static ? reinterpret_cast<unsigned long long*>(c->static_scratch) : c->d_sums + (size_t)sums_set * kSumsWords;
     p.done = reinterpret_cast<unsigned int*>(p.sums + SOP_K_REPL * SOP_K_NCOL);
     p.acos_pair = c->n_pairs ? out->acos_pair : nullptr;
     p.acos_atom = out->acos_atom;
@@ -555,7 +608,10 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
 
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
-    if (max_code < SOP_K_MAXTABCODES) {
+    if (use_static) {
+        p.stab = reinterpret_cast<const float2*>(c->static_scratch + kStaticSumsBytes);
+        p.n_tab_codes = max_code + 1;
+    } else if (max_code < SOP_K_MAXTABCODES) {
         ScaleTab t;
         if (sop_status s = scale_table(c, x, y, bias, max_code, k, &t)) return s;
         p.stab = t.dev;
@@ -589,6 +645,12 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     wg = std::max<long long>(wg, 1);
     p.n_waves = wg * waves_per_wg;
     if (!launch) return SOP_OK;
+    if (use_static) {
+        const int n_words = (int)kSumsWords, n_thr = std::max(n_words, p.n_tab_codes);
+        static_prologue_kernel<<<dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+            p.sums, n_words, reinterpret_cast<float2*>(c->static_scratch + kStaticSumsBytes), p.n_tab_codes, y, bias, k);
+        if ((e = hipGetLastError()) != hipSuccess) return hipfail(c, e, "kernel launch (static prologue)");
+    }
     e = sopk_launch(fn, &p, (int)wg, occ, dyn_lds, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
@@ -599,6 +661,13 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
                                       void* ws, size_t ws_bytes, const sop_outputs* out, void* stream)
 {
     return pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, ws, ws_bytes, out, stream, true);
+}
+
+extern "C" sop_status sop_pair_search_static(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                             const float* cn, int g, sop_scale_fmt fmt, int k, sop_metric metric,
+                                             const sop_outputs* out, void* stream)
+{
+    return pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, nullptr, 0, out, stream, true, 0, nullptr, nullptr, true);
 }
 
 extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers, int n_layers, sop_dtype dtype, int g,
