@@ -77,6 +77,7 @@ class Result:
     codes: list              # per atom: packed code plane (u8)
     blk_err: np.ndarray      # [A][M*K/g] f32
     blk_cos: np.ndarray      # [A][M*K/g] f32
+    blk_rank: np.ndarray = None   # [A][M*K/g] f32: ranking score of step 2 (signed squared block cosine, binary32)
 
 
 def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k: int = 0, metric: int = WSE,
@@ -106,6 +107,7 @@ def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k:
     codes = np.zeros(sum(plane), dtype=np.uint8) if want_codes else None
     be = np.zeros((A, Nb), dtype=np.float32)
     bc = np.zeros((A, Nb), dtype=np.float32)
+    br = np.zeros((A, Nb), dtype=np.float32)
 
     def p(a, t):
         return a.ctypes.data_as(C.POINTER(t)) if a is not None else None
@@ -115,14 +117,14 @@ def pair_search(W: np.ndarray, c: np.ndarray, atoms: list, g: int, fmt: _Fmt, k:
         C.c_int(A), p(n_entries, C.c_int), p(flat, C.c_float), C.c_int(P), p(pairs, C.c_int),
         C.byref(fmt), C.c_int(k), C.c_int(metric), C.c_int(scale_rule),
         p(acos_pair, C.c_double), p(acos_atom, C.c_double), p(sel, C.c_uint32), p(sc, C.c_uint16),
-        p(codes, C.c_uint8), p(be, C.c_float), p(bc, C.c_float), C.c_int(n_threads))
+        p(codes, C.c_uint8), p(be, C.c_float), p(bc, C.c_float), p(br, C.c_float), C.c_int(n_threads))
     if rc != 0:
         raise ValueError(f"oracle rejected the arguments (code {rc})")
     code_list = None
     if codes is not None:
         offs = np.concatenate([[0], np.cumsum(plane)])
         code_list = [codes[offs[a]:offs[a + 1]] for a in range(A)]
-    return Result(acos_pair[:P], acos_atom, sel, sc, code_list, be, bc)
+    return Result(acos_pair[:P], acos_atom, sel, sc, code_list, be, bc, br)
 
 
 def unpack_codes(plane: np.ndarray, n_entries: int, M: int, K: int) -> np.ndarray:

@@ -125,6 +125,24 @@ typedef struct {
     uint8_t code[64];
 } cand;
 
+/* Ranking score of step 2 of the per-layer pair search (Section "Per-Layer Pair Search", step 2: every
+ * block is scored against L_a under its own scale and the blocks are ranked; design axis (i): the
+ * ranking score is the block cosine).  The ranking decides which pool a block goes to, so the score is
+ * a decision quantity and is formed in binary32, one rounding per operation, from the block's binary32
+ * tree sums: with num = <w,w^>_c, den = ||w^||_c^2, wn = ||w||_c^2 it is
+ *     fl( fl(num / wn) * fl(|num| / den) ),
+ * the block cosine squared with the cosine's sign, which ranks blocks as the cosine does.  Both
+ * quotients are of the order of one whatever the block's magnitude.  A block without weighted norm has
+ * cosine 1 (score 1), a zero reconstruction of a non-zero block cosine 0 (score 0). */
+static float rank_score(float num, float den, float wn)
+{
+    if (!(wn > 0.0f)) return 1.0f;
+    if (!(den > 0.0f)) return 0.0f;
+    float a = num / wn;
+    float b = fabsf(num) / den;
+    return a * b;
+}
+
 /* cosine-mode comparison: is candidate b strictly better than candidate a?  cos = num/sqrt(wn*den);
  * wn is common, so compare num*|num|/den by cross-multiplication; a zero reconstruction has
  * cosine 0. */
@@ -218,6 +236,7 @@ static void eval_candidate(const float* w, const float* c, int g, const float* L
  *              codes per byte, even element in the low nibble), otherwise M*K bytes
  *   blk_err    [A][M*K/g] binary32 decision score (c-weighted error; unweighted in mode MSE)
  *   blk_cos    [A][M*K/g] binary32 rounding of the block cosine
+ *   blk_rank   [A][M*K/g] binary32 ranking score of step 2 (rank_score above) of the candidate kept
  * Returns 0, or a negative number for an invalid argument.
  */
 int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const float* c, int g,
@@ -225,7 +244,7 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
                      int n_pairs, const int* pair_ab,
                      const sopo_fmt* fmt, int k, int metric, int scale_rule,
                      double* acos_pair, double* acos_atom, uint32_t* sel_words, uint16_t* scale_code,
-                     uint8_t* codes, float* blk_err, float* blk_cos, int n_threads)
+                     uint8_t* codes, float* blk_err, float* blk_cos, float* blk_rank, int n_threads)
 {
     if (M <= 0 || K <= 0 || g <= 0 || g > 64 || K % g != 0 || ldw < K) return -1;
     if (n_atoms < 1 || n_atoms > SOPO_MAX_ATOMS) return -2;
@@ -305,6 +324,7 @@ int sopo_pair_search(const float* W, int64_t M, int64_t K, int64_t ldw, const fl
                 if (scale_code) scale_code[(int64_t)a * Nb + blk] = (uint16_t)(best[a].q | (best[a].neg ? 0x8000 : 0));
                 if (blk_err) blk_err[(int64_t)a * Nb + blk] = best[a].err;
                 if (blk_cos) blk_cos[(int64_t)a * Nb + blk] = (float)best[a].cosv;
+                if (blk_rank) blk_rank[(int64_t)a * Nb + blk] = rank_score(best[a].num, best[a].den, tree_dot(cw, w, g));
                 if (codes) {
                     if (n_entries[a] <= 16) {
                         uint8_t* o = codes + code_off[a] + (m * K + j * g) / 2;

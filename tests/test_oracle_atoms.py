@@ -113,3 +113,41 @@ def test_lloyd_fixed_point_and_bof_invariants():
     a = A.lloyd_1d(xs, wts, A.nf(4), 5)
     b = A.lloyd_1d(np.repeat(xs, wts.astype(int)), None, A.nf(4), 5)
     assert np.allclose(a, b, atol=1e-12)
+
+
+def test_lloyd_on_cases_the_mathematics_fixes():
+    # (1) Uniform mass on [0,1): the optimal n-level quantiser of a uniform density has equally spaced
+    #     levels (2j+1)/(2n) (the Lloyd-Max conditions: each level is its cell's mean, each boundary the
+    #     midpoint of its levels).  A fine regular grid of samples stands for the density; the fixed point
+    #     is then exact up to the grid's spacing.
+    n, N = 8, 1 << 16
+    x = (np.arange(N) + 0.5) / N
+    start = np.sort(np.random.default_rng(3).uniform(0, 1, n))
+    cent = A.lloyd_1d(x, None, start, 4000)
+    assert np.max(np.abs(cent - (2 * np.arange(n) + 1) / (2 * n))) < 2e-4
+    # (2) Point masses: with as many centroids as distinct points, each centroid ends on a point (zero
+    #     distortion is reachable and is a fixed point); with weights, a centroid shared by two points
+    #     sits at their weighted mean.
+    pts = np.array([-3.0, -1.0, 0.5, 2.0])
+    xs = np.repeat(pts, [5, 1, 7, 2])
+    cent = A.lloyd_1d(xs, None, np.array([-2.5, -0.5, 0.4, 1.0]), 3)
+    assert np.array_equal(cent, pts)
+    cent = A.lloyd_1d(np.array([0.0, 1.0, 10.0]), np.array([3.0, 1.0, 2.0]), np.array([0.2, 9.0]), 5)
+    assert np.array_equal(cent, np.array([0.25, 10.0]))               # (3*0 + 1*1) / 4, and the lone point
+    # (3) one step, by hand: samples 0,1,2,3 with centroids (0.4, 2.1): midpoint 1.25 -> cells {0,1} and
+    #     {2,3} -> (0.5, 2.5); a sample on a midpoint goes to the lower centroid
+    assert np.array_equal(A.lloyd_1d(np.arange(4.0), None, np.array([0.4, 2.1]), 1), np.array([0.5, 2.5]))
+    assert np.array_equal(A.lloyd_1d(np.array([0.0, 1.0, 2.0]), None, np.array([0.0, 2.0]), 1), np.array([0.5, 2.0]))
+    # (4) an empty cell keeps its centroid
+    assert np.array_equal(A.lloyd_1d(np.array([0.0, 0.1]), None, np.array([0.0, 5.0]), 2), np.array([0.05, 5.0]))
+
+
+def test_block_normalise_hand_worked():
+    # blocks of 4: (1, -2, 0.5, 1.5) has signed absmax -2 -> (-0.5, 1, -0.25, -0.75);
+    #              (3, 1, -1, 0) has signed absmax 3 -> (1, 1/3, -1/3, 0); the trailing partial block is dropped
+    x = A.block_normalise(np.array([1, -2, 0.5, 1.5, 3, 1, -1, 0, 9, 9], dtype=np.float64), 4)
+    assert np.array_equal(x, np.array([-0.5, 1, -0.25, -0.75, 1, 1 / 3, -1 / 3, 0]))
+    # every block holds +1 exactly once it has a unique largest magnitude, and nothing exceeds 1
+    d = si.normal_draws(1 << 12, 5)
+    xb = A.block_normalise(d, 16).reshape(-1, 16)
+    assert np.all(xb.max(axis=1) == 1.0) and np.all(np.abs(xb) <= 1.0)

@@ -335,3 +335,63 @@ def test_argument_validation():
         ps.pair_search(W, c, [L[::-1].copy()], 16, UE4M4)           # unsorted atom
     with pytest.raises(ValueError):
         ps.pair_search(W, c, [np.abs(L) + 1], 16, UE4M4)            # one-sided atom
+
+
+# ---------------------------------------------------------------- ranking score of step 2
+def test_rank_score_hand_worked_block():
+    # L = {-1,0,1}, c = 1, block (1, 0.5, -1, 0.25, 0, 0, 0, 0): s = 1 (representable), x = w, midpoints
+    # -0.5 / +0.5 (0.5 is a tie and goes down): w_hat = (1, 0, -1, 0, 0...).
+    # num = 1 + 1 = 2, den = 2, wn = 1 + 1/4 + 1 + 1/16 = 37/16: every sum exact in binary32.
+    # score = fl(fl(2 / (37/16)) * fl(2 / 2)) = fl(32/37) = cos^2 = 4 / (37/16 * 2)
+    L = f32([-1, 0, 1])
+    W = f32([[1.0, 0.5, -1.0, 0.25, 0, 0, 0, 0]])
+    r = ps.pair_search(W, np.ones(8, dtype=np.float32), [L], 8, WIDE_U)
+    assert ps.unpack_codes(r.codes[0], 3, 1, 8).tolist() == [[2, 1, 0, 1, 1, 1, 1, 1]]
+    want = np.float32(Fr(32, 37))                                     # one rounding of the exact quotient
+    assert r.blk_rank[0, 0] == want
+    assert abs(float(r.blk_rank[0, 0]) - float(r.blk_cos[0, 0]) ** 2) < 2e-7
+    # channel norms weigh linearly: c = (4,1,1,1,...) gives num = 5, den = 5, wn = 4 + 21/16 = 85/16
+    c = np.ones(8, dtype=np.float32); c[0] = 4
+    r = ps.pair_search(W, c, [L], 8, WIDE_U)
+    assert r.blk_rank[0, 0] == np.float32(Fr(80, 85))
+
+
+def test_rank_score_conventions_and_sign():
+    L = f32(A.nf(4))
+    W = np.zeros((1, 48), dtype=np.float32)
+    W[0, 16] = 1e-12                                  # second block: the scale underflows, reconstruction 0
+    W[0, 32:48] = si.student_t_weights(1, 16, 5.0, 77)[0]
+    r = ps.pair_search(W, np.ones(48, dtype=np.float32), [L], 16, UE4M4)
+    assert r.blk_rank[0, 0] == 1.0 and r.blk_rank[0, 1] == 0.0        # no norm: 1; nothing reconstructed: 0
+    assert 0.9 < r.blk_rank[0, 2] <= 1.0
+    # a negative cosine keeps its sign: a one-entry-per-side codebook whose reconstruction points away
+    # cannot be built with the absmax rule, so plant it through the channel norms instead: c = 0 on
+    # the elements that match, so only the mismatching element counts
+    L3 = f32([-1, 0.25, 1])
+    Wb = f32([[1.0, -0.1]])                           # -0.1 -> nearest entry 0.25 (midpoint -0.375): w * w_hat < 0
+    r = ps.pair_search(Wb, f32([0.0, 1.0]), [L3], 2, WIDE_U)
+    assert r.blk_rank[0, 0] < 0 and r.blk_cos[0, 0] < 0
+    assert abs(float(r.blk_rank[0, 0]) + float(r.blk_cos[0, 0]) ** 2) < 1e-6
+
+
+@pytest.mark.parametrize("fmt,g", [(UE4M4, 16), (E4M3, 32), (WIDE, 8), (UE4M4, 64)])
+def test_rank_score_is_the_signed_squared_cosine_and_ranks_like_it(fmt, g):
+    W = si.bf16_round(si.student_t_weights(48, 1024, 4.0, 810 + g, row_sigma=0.5, outlier_frac=0.002))
+    c = si.channel_norms(1024, 1.0, 811)
+    tabs = [f32(A.nf(4)), f32(A.sh(4)), f32(A.negate(A.sh(4)))]
+    r = ps.pair_search(W, c, tabs, g, fmt)
+    # value: against exact rational arithmetic on the reconstruction the oracle reports (codes, scale code)
+    cos = r.blk_cos.astype(np.float64)
+    assert np.max(np.abs(r.blk_rank.astype(np.float64) - np.sign(cos) * cos * cos)) < 1e-6
+    # ranking: wherever two blocks' cosines differ by more than the binary32 resolution, the score orders
+    # them the same way
+    for a in range(3):
+        order = np.argsort(r.blk_rank[a], kind="stable")
+        cs = cos[a][order]
+        assert np.all(np.diff(cs) > -1e-6)
+    # scaling the layer by a power of two (and the layer shift with it) changes no score: the two
+    # quotients are formed of sums that scale together
+    r2 = ps.pair_search(W * np.float32(2.0 ** -20), c, tabs, g, fmt, k=20)
+    assert np.array_equal(r.blk_rank, r2.blk_rank)
+    r3 = ps.pair_search(W, c * np.float32(2.0 ** 30), tabs, g, fmt)
+    assert np.array_equal(r.blk_rank, r3.blk_rank)
