@@ -88,6 +88,14 @@ typedef struct {
     float*    blk_cos;     /* [A][N_b]  per-block weighted cosine (value, fp32 accuracy)        */
     float*    blk_err;     /* [A][N_b]  per-block decision score (weighted error; unweighted in
                               mode SOP_SEL_MSE)                                                 */
+    float*    blk_rank;    /* [A][N_b]  ranking score of step 2 of the per-layer search (Section
+                              "Per-Layer Pair Search", step 2; design axis (i): block cosine): the
+                              block cosine squared, with the cosine's sign, formed in binary32 from the
+                              block's binary32 sums (chunks of 8 consecutive elements, sequential fma,
+                              balanced tree) num = <w,w^>_c, den = ||w^||_c^2, wn = ||w||_c^2 as
+                              fl(fl(num / wn) * fl(|num| / den)); 1 when wn = 0, 0 when den = 0.  It
+                              orders blocks as blk_cos does but is reproducible bit for bit, so pools
+                              derived from it (sop_partition) are too                            */
 } sop_outputs;
 
 typedef struct sop_ctx sop_ctx;

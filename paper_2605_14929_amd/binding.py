@@ -44,7 +44,8 @@ class _Atom(C.Structure):
 
 class _Outputs(C.Structure):
     _fields_ = [("acos_pair", C.c_void_p), ("acos_atom", C.c_void_p), ("sel_words", C.c_void_p),
-                ("scale_code", C.c_void_p), ("codes", C.c_void_p), ("blk_cos", C.c_void_p), ("blk_err", C.c_void_p)]
+                ("scale_code", C.c_void_p), ("codes", C.c_void_p), ("blk_cos", C.c_void_p), ("blk_err", C.c_void_p),
+                ("blk_rank", C.c_void_p)]
 
 
 def lib_path() -> str:
@@ -247,6 +248,7 @@ class Outputs:
     code_planes: list = None
     blk_cos: object = None
     blk_err: object = None
+    blk_rank: object = None
 
 
 class Context:
@@ -317,6 +319,7 @@ class Context:
             o.code_planes = [o.codes[int(offs[a]):int(offs[a + 1])] for a in range(A)]
             o.blk_cos = torch.empty((A, Nb), dtype=torch.float32, device=dev)
             o.blk_err = torch.empty((A, Nb), dtype=torch.float32, device=dev)
+            o.blk_rank = torch.empty((A, Nb), dtype=torch.float32, device=dev)
         return o
 
     def layer_scope_error(self, W, c, wfmt: WeightFmt, sfmt: ScaleFmt, k: int = 0, want_codes: bool = False, stream=None):
@@ -505,7 +508,7 @@ class Context:
             return None if t is None else C.c_void_p(t.data_ptr())
 
         o = _Outputs(ptr(out.acos_pair), ptr(out.acos_atom), ptr(out.sel_words), ptr(out.scale_code), ptr(out.codes),
-                     ptr(out.blk_cos), ptr(out.blk_err))
+                     ptr(out.blk_cos), ptr(out.blk_err), ptr(out.blk_rank))
         if static:
             _check(lib().sop_pair_search_static(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
                                                 fmt, k, metric, C.byref(o), C.c_void_p(st)), self._h)

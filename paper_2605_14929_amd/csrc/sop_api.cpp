@@ -531,7 +531,8 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
     if (!aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
     if ((out->sel_words && (reinterpret_cast<uintptr_t>(out->sel_words) & 3u)) || (out->codes && (reinterpret_cast<uintptr_t>(out->codes) & 3u)) ||
-        (out->scale_code && (reinterpret_cast<uintptr_t>(out->scale_code) & 1u)))
+        (out->scale_code && (reinterpret_cast<uintptr_t>(out->scale_code) & 1u)) ||
+        ((reinterpret_cast<uintptr_t>(out->blk_cos) | reinterpret_cast<uintptr_t>(out->blk_err) | reinterpret_cast<uintptr_t>(out->blk_rank)) & 3u))
         return fail(c, SOP_EINVAL, "output buffers must be naturally aligned");
 
     // ---- scale format ----
@@ -603,8 +604,8 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     p.acos_atom = out->acos_atom;
     p.sel_words = c->n_pairs ? out->sel_words : nullptr;
     p.sel_u32 = c->n_pairs > 16 ? 1 : 0;
-    p.scale_code = out->scale_code; p.codes = out->codes; p.blk_cos = out->blk_cos; p.blk_err = out->blk_err;
-    const int emit = (p.scale_code || p.codes || p.blk_cos || p.blk_err) ? 1 : 0;
+    p.scale_code = out->scale_code; p.codes = out->codes; p.blk_cos = out->blk_cos; p.blk_err = out->blk_err; p.blk_rank = out->blk_rank;
+    const int emit = (p.scale_code || p.codes || p.blk_cos || p.blk_err || p.blk_rank) ? 1 : 0;
 
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");

@@ -91,6 +91,7 @@ struct KParams {
     uint8_t*  codes;
     float*    blk_cos;
     float*    blk_err;
+    float*    blk_rank;              // [A][Nb] ranking score of step 2 (signed squared block cosine, binary32 decision quantity)
     // model-wide kernel: the layers of one launch (W, c, M, K, ldw, Nb, sel_words above are then unused); sums is
     // [n_layers][SOP_K_REPL][SOP_K_NCOL], acos_pair / acos_atom are tables with rows of P / A values (a layer names its row)
     const struct LayerDesc* layers;

@@ -829,6 +829,24 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                     if (p.scale_code && leader) p.scale_code[ua * p.Nb + blk] = (uint16_t)(q | (neg ? 0x8000 : 0));
                     if (p.blk_err && leader) p.blk_err[ua * p.Nb + blk] = best.err;
                     if (p.blk_cos && leader) p.blk_cos[ua * p.Nb + blk] = wn > 0.0f ? 1.0f - __fmaf_rn(-best.ny, rs, 1.0f) : 1.0f;
+                    if (p.blk_rank) {
+                        // ranking score of step 2 of the per-layer search: a decision quantity, formed in binary32 from
+                        // the block's tree sums num = <w,w^>_c, den = ||w^||_c^2 (chunks of 8, balanced tree) and wn:
+                        // fl(fl(num / wn) * fl(|num| / den)), 1 for a block without weighted norm, 0 for a zero reconstruction
+                        float num, dn;
+                        if constexpr (METRIC == 1) { num = best.ny; dn = best.dy; }
+                        else {
+                            uint32_t nocodes[EPL / 4];
+                            const Cand c1 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx, gboff, gss, a, false, nocodes));
+                            num = c1.ny; dn = c1.dy;
+                            if constexpr (SIGNED) {
+                                const Cand c2 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx2, gboff2, gss2, a, false, nocodes));
+                                num = neg ? c2.ny : num; dn = neg ? c2.dy : dn;
+                            }
+                        }
+                        const float rank = wn > 0.0f ? (dn > 0.0f ? (num / wn) * (fabsf(num) / dn) : 0.0f) : 1.0f;
+                        if (leader) p.blk_rank[ua * p.Nb + blk] = rank;
+                    }
                     if (p.codes && valid) {
                         if (!wide) {
                             uint8_t* dst = p.codes + p.code_off[a] + (cm * p.K + col0) / 2;

@@ -67,7 +67,7 @@ def search_layer(ctx: B.Context, W, c, g: int, fmt: B.ScaleFmt, atoms: list, p_g
     ctx.set_alphabet(atoms)
     ctx.set_pairs(None)
     out = ctx.alloc_outputs(M, K, g, emit=False, sel=False)
-    out.blk_cos = torch.empty((A, Nb), dtype=torch.float32, device=W.device)    # the only per-block plane step 2 needs
+    out.blk_rank = torch.empty((A, Nb), dtype=torch.float32, device=W.device)   # the only per-block plane step 2 needs
     ctx.pair_search(W, c, g, fmt, k=k, metric=metric, out=out)
     torch.cuda.synchronize()
     acos_fixed = out.acos_pair.cpu().numpy()[:ctx.n_pairs].copy()
@@ -76,7 +76,7 @@ def search_layer(ctx: B.Context, W, c, g: int, fmt: B.ScaleFmt, atoms: list, p_g
     if pairs:
         q = int(np.argmax(acos_fixed))
         best = ("fixed", pairs[q][0], pairs[q][1], float("nan"), float(acos_fixed[q]), None)
-    blk_cos = out.blk_cos                              # [A, Nb]
+    blk_rank = out.blk_rank                            # [A, Nb]
 
     # (2) fitted second codebooks: steps 2 and 3 per (a, p), step 4 for one atom's whole sweep at once
     acos_fitted = {}
@@ -86,7 +86,7 @@ def search_layer(ctx: B.Context, W, c, g: int, fmt: B.ScaleFmt, atoms: list, p_g
     hists = []
     for a in range(A):
         for p in p_list:
-            pool_b, _, _ = ctx.partition(blk_cos[a], top_count(p, Nb), True)
+            pool_b, _, _ = ctx.partition(blk_rank[a], top_count(p, Nb), True)
             hists.append(ctx.dd_histogram(W, c if weighted_fit else None, g, fit_bins, 1, block_mask=pool_b))
     hs = torch.stack(hists).cpu().numpy().reshape(A, len(p_list), fit_bins)       # synchronises: 8 KB per (a, p)
     if fit_grid is None:

@@ -46,6 +46,7 @@ def run_gpu(W, c, tabs, g, fmt, k=0, metric=0, pairs=None, bf16=False, emit=True
         r["scale_code"] = out.scale_code.cpu().numpy().view(np.uint16)
         r["codes"] = [p.cpu().numpy() for p in out.code_planes]
         r["blk_err"] = out.blk_err.cpu().numpy()
+        r["blk_rank"] = out.blk_rank.cpu().numpy()
         r["blk_cos"] = out.blk_cos.cpu().numpy()
     return r
 
@@ -61,4 +62,5 @@ def compare(gpu, ref, n_pairs, emit=True, acos_tol=1e-6, cos_tol=2e-5):
         for a, (x, y) in enumerate(zip(gpu["codes"], ref.codes)):
             assert np.array_equal(x, y), f"codes of atom {a} differ at {np.flatnonzero(x != y)[:8]}"
         assert np.array_equal(gpu["blk_err"], ref.blk_err), "block scores differ"
+        assert np.array_equal(gpu["blk_rank"].view(np.uint32), ref.blk_rank.view(np.uint32)), "ranking scores differ"
         assert np.max(np.abs(gpu["blk_cos"] - ref.blk_cos)) <= cos_tol

@@ -86,7 +86,7 @@ def test_steps_one_to_four_chained():
     o1 = cx.pair_search(Wt, ct, g, fmt, emit=True)
     Nb = M * K // g
     n_top = PT.top_count(70.0, Nb)
-    pool_b, tau, n_a = cx.partition(o1.blk_cos[0], n_top, True)
+    pool_b, tau, n_a = cx.partition(o1.blk_rank[0], n_top, True)
     # step 3 on the GPU: histogram of the pool, fit on the host side of the library
     hist = cx.dd_histogram(Wt, ct, g, 1024, 1, block_mask=pool_b)
     torch.cuda.synchronize()
@@ -94,10 +94,10 @@ def test_steps_one_to_four_chained():
     # the oracle's chain
     r1 = ops.pair_search(W, c, [La], g, oracle_fmt(fmt))
     assert np.max(np.abs(o1.blk_cos[0].cpu().numpy() - r1.blk_cos[0])) < 2e-5
-    # rank on the GPU's own cosine plane (binary32 values differ in the last place between the two
-    # sides; the ranking itself is exact on whichever plane it is given)
-    gcos = o1.blk_cos[0].cpu().numpy()
-    rt, rp, rn = PT.partition(gcos, n_top, True)
+    # the ranking score is a binary32 decision quantity: both sides hold the same bits, and the oracle
+    # ranks its own plane
+    assert np.array_equal(o1.blk_rank[0].cpu().numpy().view(np.uint32), r1.blk_rank[0].view(np.uint32))
+    rt, rp, rn = PT.partition(r1.blk_rank[0], n_top, True)
     assert tau.cpu().numpy()[0] == rt and int(n_a.cpu().numpy()[0]) == rn and np.array_equal(pool_b.cpu().numpy(), rp)
     rh = DD.histogram(W, c, g, 1024, block_mask=rp)
     assert np.array_equal(hist.cpu().numpy(), rh)

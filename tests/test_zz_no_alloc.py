@@ -17,7 +17,7 @@ def _both(cx, W, c, g, fmt, k, emit):
     res = []
     for static in (False, True):
         out = cx.alloc_outputs(M, K, g, emit=emit)
-        for t in (out.acos_pair, out.acos_atom, out.sel_words, out.scale_code, out.codes, out.blk_cos, out.blk_err):
+        for t in (out.acos_pair, out.acos_atom, out.sel_words, out.scale_code, out.codes, out.blk_cos, out.blk_err, out.blk_rank):
             if t is not None:
                 t.fill_(-3 if t.dtype != torch.uint8 else 0xEE)   # so that an output left unwritten differs
         cx.pair_search(W, c, g, fmt, k=k, out=out, static=static)
@@ -27,7 +27,7 @@ def _both(cx, W, c, g, fmt, k, emit):
 
 
 def _equal(a, b, n_pairs):
-    names = ("acos_atom", "sel_words", "scale_code", "codes", "blk_cos", "blk_err")
+    names = ("acos_atom", "sel_words", "scale_code", "codes", "blk_cos", "blk_err", "blk_rank")
     assert np.array_equal(a.acos_pair.cpu().numpy()[:n_pairs], b.acos_pair.cpu().numpy()[:n_pairs]), "acos_pair"
     for nm in names:
         x, y = getattr(a, nm), getattr(b, nm)
