@@ -9,5 +9,5 @@ which these inputs stand in for.
 """
 from .generate import (  # noqa: F401
     bf16_round, bf16_bits, bf16_bits_to_f32, student_t_weights, channel_norms,
-    normal_draws, CONFIGS, make_config, layer_shapes_7b, model_7b_layers,
+    normal_draws, CONFIGS, make_config, layer_shapes_7b, model_7b_layers, model_7b_layer,
 )

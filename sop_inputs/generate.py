@@ -136,3 +136,16 @@ def model_7b_layers(n_blocks: int, seed: int = 4001, rows: int | None = None):
             W = bf16_round(student_t_weights(Mr, K, nu, s))
             c = channel_norms(K, 1.0, s + 1)
             yield f"block{b}.{name}", W, c, nu
+
+
+def model_7b_layer(block: int, index: int, seed: int = 4001, rows: int | None = None):
+    """Layer `index` (0..6 in the order of layer_shapes_7b) of block `block` of configuration 4, as
+    model_7b_layers() yields it, without drawing the layers before it."""
+    r = _rng(seed)
+    nu = 0.0
+    for _ in range(7 * block + index + 1):                 # the tail indices are drawn in layer order
+        nu = float(r.uniform(3.0, 8.0))
+    name, M, K = layer_shapes_7b()[index]
+    s = seed + 1000 * (block + 1) + 10 * index
+    Mr = M if rows is None else min(M, int(rows))
+    return f"block{block}.{name}", bf16_round(student_t_weights(Mr, K, nu, s)), channel_norms(K, 1.0, s + 1), nu

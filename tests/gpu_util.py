@@ -5,6 +5,16 @@ import paper_2605_14929_amd as sop
 from oracle import pairsearch as ops
 
 _ctx = None
+_cfg_cache = {}
+
+
+def cached_config(name):
+    """A benchmark configuration's tensors, drawn once per test session (the 70B-shaped layer takes a
+    while to draw and several tests use it)."""
+    import sop_inputs as si
+    if name not in _cfg_cache:
+        _cfg_cache[name] = si.make_config(name)
+    return _cfg_cache[name]
 
 
 def ctx():

@@ -6,7 +6,7 @@ import pytest
 import paper_2605_14929_amd as sop
 from oracle import flayer as FL, pairsearch as ops
 import sop_inputs as si
-from gpu_util import run_gpu, compare, oracle_fmt, ctx
+from gpu_util import run_gpu, compare, oracle_fmt, ctx, cached_config
 
 pytestmark = pytest.mark.gpu
 
@@ -60,7 +60,7 @@ def test_shift_feeds_the_pair_search():
 
 def test_full_layer_and_errors():
     import torch
-    W, c, cfg = si.make_config("C3_down")
+    W, c, cfg = cached_config("C3_down")
     f = sop.fmt_by_name("UE4M4")
     sc = FL.block_scales(W, 16, 1.0, 1.0)
     got = gpu_hist(W, 16, 1.0, 1.0, f, True)

@@ -6,7 +6,7 @@ import pytest
 import paper_2605_14929_amd as sop
 from oracle import pairsearch as ops
 import sop_inputs as si
-from gpu_util import run_gpu, compare, oracle_fmt
+from gpu_util import run_gpu, compare, oracle_fmt, cached_config
 
 pytestmark = pytest.mark.gpu
 
@@ -47,7 +47,7 @@ def test_config2_full_signed():
 
 @pytest.mark.parametrize("name", ["C3_down", "C3_up"])
 def test_config3_headline_full(name):
-    W, c, cfg = si.make_config(name)
+    W, c, cfg = cached_config(name)
     tabs = _alphabet(cfg["atoms"])
     fmt = sop.fmt_by_name(cfg["fmt"])
     gpu = run_gpu(W, c, tabs, 16, fmt, bf16=True, emit=False)        # the configuration bench.py times
@@ -55,56 +55,85 @@ def test_config3_headline_full(name):
     compare(gpu, ref, 15, emit=False)
 
 
-@pytest.mark.parametrize("g,fmt", [(8, "E4M5"), (32, "UE5M7"), (64, "S1E5M5")])
-def test_config3_sweep_samples(g, fmt):
-    W, c, cfg = si.make_config("C3_down", rows=512)
-    tabs = _alphabet(["NF5", "SH5", "BOF5", "-NF5", "-SH5", "-BOF5"])
-    f = sop.fmt_by_name(fmt)
-    gpu = run_gpu(W, c, tabs, g, f, bf16=True, emit=True)
-    ref = ops.pair_search(W, c, tabs, g, oracle_fmt(f))
-    compare(gpu, ref, 15)
-
-
-def test_config5_shape_row_sample():
-    # 70B-shaped MLP layer 28672 x 8192: search mode on the full layer, oracle on sampled rows and
-    # on the layer mean through the property  mean over rows of sampled per-row results
-    W, c, cfg = si.make_config("C5", rows=28672)
+def test_config5_whole_layer_against_the_oracle():
+    # 70B-shaped MLP layer 28672 x 8192 in the launch configuration bench.py times (search mode): every
+    # selector word and every ACos against the oracle on the whole layer
+    W, c, cfg = cached_config("C5")
     tabs = _alphabet(cfg["atoms"])
     fmt = sop.fmt_by_name(cfg["fmt"])
     gpu = run_gpu(W, c, tabs, 16, fmt, bf16=True, emit=False)
-    rows = np.sort(np.random.default_rng(5).choice(W.shape[0], 256, replace=False))
-    _sample_rows_check(W, c, tabs, 16, fmt, gpu, rows, True)
-    # the sampled rows' ACos is an unbiased estimate of the layer's: agree to sampling accuracy
-    ref = ops.pair_search(W[rows], c, tabs, 16, oracle_fmt(fmt), want_codes=False)
-    assert np.max(np.abs(gpu["acos_pair"] - ref.acos_pair)) < 2e-4
+    ref = ops.pair_search(W, c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+    compare(gpu, ref, 15, emit=False)
     assert np.all((gpu["acos_pair"] > 0.99) & (gpu["acos_pair"] <= 1.0))
 
 
-def test_config4_one_block_full_size_through_the_model_wide_call():
-    """The seven layers of a 7B-shaped block at their full sizes in one model-wide call (the launch
-    bench.py --workload model times, on one block): the ACos table equals the single calls' bit for bit,
-    the selector words of sampled rows equal the oracle's, the ACos of one layer the oracle's."""
+def test_headline_layer_repeat_runs_are_bit_equal():
+    # the sums of the layer reduction are integers: which wavefront took which step, and in what order
+    # the workgroups finished, cannot change a bit of the result
     import torch
-    host = list(si.model_7b_layers(1))
+    W, c, cfg = cached_config("C3_down")
+    tabs = _alphabet(cfg["atoms"])
+    fmt = sop.fmt_by_name(cfg["fmt"])
+    cx = sop.Context(0)
+    cx.set_alphabet(tabs)
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    runs = []
+    for i in range(4):
+        o = cx.pair_search(Wt, ct, 16, fmt, static=(i == 3), out=cx.alloc_outputs(W.shape[0], W.shape[1], 16))
+        torch.cuda.synchronize()
+        runs.append((o.acos_pair.cpu().numpy().copy(), o.acos_atom.cpu().numpy().copy(), o.sel_words.cpu().numpy().copy()))
+    for r in runs[1:]:
+        assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(runs[0], r))
+
+
+# the scale words of the sweep: the 8-, 10-, 12- and 16-bit formats of the paper's scale-format tables
+SWEEP_FORMATS = ["UE4M4", "E4M3", "UE4M6", "E4M5", "UE5M7", "E5M6", "E4M7", "S1E5M5", "E8M7"]
+
+
+@pytest.mark.parametrize("layer", ["C3_down", "C3_up"])
+@pytest.mark.parametrize("n", [4, 5])
+def test_config3_sweep_block_sizes_by_scale_formats(layer, n):
+    """The sweep of configuration 3 on the first 256 rows of both MLP layers: block sizes 8, 16, 32, 64 by
+    nine scale words, for the six four-bit atoms and the six five-bit atoms; every output against the oracle
+    (codes, scale codes, selector words, block errors and ranking scores bit for bit, ACos at 1e-6)."""
+    W, c, cfg = cached_config(layer)
+    W = W[:256]
+    tabs = _alphabet([f"NF{n}", f"SH{n}", f"BOF{n}", f"-NF{n}", f"-SH{n}", f"-BOF{n}"])
+    for g in (8, 16, 32, 64):
+        for name in SWEEP_FORMATS:
+            f = sop.fmt_by_name(name)
+            gpu = run_gpu(W, c, tabs, g, f, bf16=True, emit=True)
+            ref = ops.pair_search(W, c, tabs, g, oracle_fmt(f))
+            try:
+                compare(gpu, ref, 15)
+            except AssertionError as e:
+                raise AssertionError(f"{layer} n={n} g={g} {name}: {e}") from e
+
+
+def test_config4_fourteen_layers_full_size_through_the_model_wide_call():
+    """Fourteen layers of the 7B-shaped model at their full sizes in one model-wide call (the launch
+    bench.py --workload model times): the seven layers of block 0 and one layer of each type from seven
+    other blocks.  Every row of the ACos tables and every selector word against the oracle on the whole
+    layer; the tables also equal the single calls' bit for bit."""
+    import torch
+    picks = [(0, i) for i in range(7)] + [(3, 4), (7, 0), (12, 6), (18, 2), (21, 5), (27, 1), (31, 3)]
     tabs = _alphabet(["NF4", "SH4", "BOF4", "-NF4", "-SH4", "-BOF4"])
     fmt = sop.fmt_by_name("UE4M4")
     cx = sop.Context(0)
     cx.set_alphabet(tabs); cx.set_pairs(None)
+    host = [si.model_7b_layer(b, i) for b, i in picks]
+    assert len({nu for _, _, _, nu in host}) == 14
     layers = [(torch.from_numpy(W).cuda().to(torch.bfloat16), torch.from_numpy(c).cuda()) for _, W, c, _ in host]
     tp, ta, sels = cx.pair_search_layers(layers, 16, fmt, want_sel=True)
     torch.cuda.synchronize()
     tp, ta = tp.cpu().numpy(), ta.cpu().numpy()
-    rng = np.random.default_rng(9)
     for i, (name, W, c, _) in enumerate(host):
-        o = cx.pair_search(layers[i][0], layers[i][1], 16, fmt)
-        torch.cuda.synchronize()
-        assert np.array_equal(o.acos_pair.cpu().numpy()[:15], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i]), name
-        assert torch.equal(o.sel_words, sels[i]), name
-        M, K = W.shape
-        rows = np.sort(rng.choice(M, size=24, replace=False))
-        ref = ops.pair_search(W[rows], c, tabs, 16, oracle_fmt(fmt), want_codes=False)
-        got = sels[i].cpu().numpy().view(np.uint16).astype(np.uint32).reshape(M, K // 16)[rows].reshape(-1)
-        assert np.array_equal(got, ref.sel_words), name
-    name, W, c, _ = host[0]                                          # 4096 x 4096: the oracle on the whole layer
-    ref = ops.pair_search(W, c, tabs, 16, oracle_fmt(fmt), want_codes=False)
-    assert np.max(np.abs(tp[0] - ref.acos_pair)) <= 1e-6 and np.max(np.abs(ta[0] - ref.acos_atom)) <= 1e-6
+        ref = ops.pair_search(W, c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+        assert np.max(np.abs(tp[i] - ref.acos_pair)) <= 1e-6 and np.max(np.abs(ta[i] - ref.acos_atom)) <= 1e-6, name
+        assert np.array_equal(sels[i].cpu().numpy().view(np.uint16).astype(np.uint32), ref.sel_words), name
+        if i < 7:
+            o = cx.pair_search(layers[i][0], layers[i][1], 16, fmt)
+            torch.cuda.synchronize()
+            assert np.array_equal(o.acos_pair.cpu().numpy()[:15], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i]), name
+            assert torch.equal(o.sel_words, sels[i]), name

@@ -7,7 +7,7 @@ import pytest
 import paper_2605_14929_amd as sop
 from oracle import layerscope as LS, pairsearch as ops
 import sop_inputs as si
-from gpu_util import run_gpu, oracle_fmt, ctx
+from gpu_util import run_gpu, oracle_fmt, ctx, cached_config
 
 pytestmark = pytest.mark.gpu
 
@@ -85,7 +85,7 @@ def test_fp6_block_scaled_versus_fp8_layer_scaled_full_layer():
     # the paper's operating-point comparison on the 70B-shaped layer of configuration 5:
     # E2M3sUE4M4 (g = 16, 6.5 bpw) against E4M3^0sUE8M0 (8.0 bpw), weighted reconstruction error
     import torch
-    W, c, cfg = si.make_config("C5")
+    W, c, cfg = cached_config("C5")
     g = 16
     e2m3 = LS.exmy_table(2, 3).astype(np.float32)
     ue4m4 = sop.fmt_by_name("UE4M4")
