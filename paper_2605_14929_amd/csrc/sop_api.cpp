@@ -102,7 +102,9 @@ struct sop_ctx {
     int pairs[2 * SOP_K_MAXP] = {0};
     // internal order: atoms of one scale group (equal endpoints) adjacent
     int order[SOP_K_MAXA] = {0};          // internal index -> caller's index
-    int grp_first[SOP_K_MAXA] = {0};
+    int gid[SOP_K_MAXA] = {0};            // scale group of the internal atom
+    int mirror[SOP_K_MAXA] = {0};         // 1: the internal atom is the sign-negated copy of the one before it
+    int selfsym[SOP_K_MAXA] = {0};        // 1: the atom is its own sign-negated copy
     float tpos[SOP_K_MAXA] = {0}, tneg[SOP_K_MAXA] = {0}, bin_sc[SOP_K_MAXA] = {0}, bin_off[SOP_K_MAXA] = {0};
     float bin_lo[SOP_K_MAXA] = {0}, bin_hi[SOP_K_MAXA] = {0};
     int nent[SOP_K_MAXA] = {0};
@@ -317,7 +319,7 @@ namespace {
 struct AlphabetPlan {
     std::vector<std::vector<float>> tabs;      // caller's order
     int n_atoms = 0;
-    int order[SOP_K_MAXA] = {0}, grp_first[SOP_K_MAXA] = {0};
+    int order[SOP_K_MAXA] = {0}, gid[SOP_K_MAXA] = {0}, mirror[SOP_K_MAXA] = {0}, selfsym[SOP_K_MAXA] = {0};
     float sc[SOP_K_MAXA] = {0}, off[SOP_K_MAXA] = {0}, lo[SOP_K_MAXA] = {0}, hi[SOP_K_MAXA] = {0};
     int n_bins = 0;
     std::vector<BinRec> img;
@@ -343,15 +345,51 @@ static sop_status plan_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms, 
         if (!(L[0] < 0.0f && L[N - 1] > 0.0f)) return fail(c, SOP_EATOM, "an atom must have a negative first and a positive last entry");
         pl.tabs[a].assign(L, L + N);
     }
-    // scale groups: equal endpoints; internal order = groups by first appearance
-    int n = 0;
+    // Scale groups: equal endpoints; internal order = groups by first appearance.  An atom that is the
+    // sign-negated copy of another (L'[k] = -L[N-1-k]) is placed directly after it where it can be: inside a
+    // group with symmetric endpoints, and at the seam between a group and the group of mirrored endpoints,
+    // which then follows it.  Under a signed scale word such a copy needs no evaluation of its own.
+    auto same_ends = [&](int a, int b) { return pl.tabs[a].front() == pl.tabs[b].front() && pl.tabs[a].back() == pl.tabs[b].back(); };
+    auto is_copy = [&](int a, int b) {                       // b is the sign-negated copy of a
+        const std::vector<float>&A = pl.tabs[a], &B = pl.tabs[b];
+        if (A.size() != B.size()) return false;
+        for (size_t k = 0; k < A.size(); ++k) if (B[k] != -A[A.size() - 1 - k]) return false;
+        // (the kernel finds a scaled weight on a code boundary by comparing bit patterns, which tells -0 from +0:
+        // a codebook with a boundary at zero takes no copies)
+        for (size_t k = 0; k + 1 < A.size(); ++k) if ((float)(((double)A[k] + (double)A[k + 1]) * 0.5) == 0.0f) return false;
+        return true;
+    };
+    int n = 0, n_groups = 0;
     bool used[SOP_K_MAXA] = {false};
+    auto place = [&](int a, int g, int mir) { used[a] = true; pl.order[n] = a; pl.gid[n] = g; pl.mirror[n] = mir; pl.selfsym[n] = is_copy(a, a); ++n; };
+    auto copy_of = [&](int a, bool same_group) {             // an unused sign-negated copy of a, inside or outside a's group
+        for (int b = 0; b < n_atoms; ++b)
+            if (!used[b] && b != a && same_ends(a, b) == same_group && is_copy(a, b)) return b;
+        return -1;
+    };
     for (int a = 0; a < n_atoms; ++a) {
         if (used[a]) continue;
-        for (int b = a; b < n_atoms; ++b)
-            if (!used[b] && pl.tabs[b].front() == pl.tabs[a].front() && pl.tabs[b].back() == pl.tabs[a].back()) {
-                used[b] = true; pl.grp_first[n] = (b == a); pl.order[n++] = b;
+        const int g = n_groups++;
+        std::vector<int> members;
+        for (int b = a; b < n_atoms; ++b) if (!used[b] && same_ends(a, b)) members.push_back(b);
+        // the member placed last is one whose copy lives in the group of mirrored endpoints (if there is one)
+        int seam = -1, seam_copy = -1;
+        for (int b : members) { const int cb = copy_of(b, false); if (cb >= 0) { seam = b; seam_copy = cb; break; } }
+        for (int b : members) {
+            if (used[b] || b == seam) continue;
+            place(b, g, 0);
+            if (!pl.selfsym[n - 1]) { const int cb = copy_of(b, true); if (cb >= 0) place(cb, g, 1); }
+        }
+        if (seam >= 0) {
+            place(seam, g, 0);
+            const int g2 = n_groups++;
+            place(seam_copy, g2, 1);
+            for (int b = 0; b < n_atoms; ++b) {               // the rest of the mirrored group
+                if (used[b] || !same_ends(seam_copy, b)) continue;
+                place(b, g2, 0);
+                if (!pl.selfsym[n - 1]) { const int cb = copy_of(b, true); if (cb >= 0) place(cb, g2, 1); }
             }
+        }
     }
     // smallest bin count for which every bin of every atom holds at most one code boundary.  The
     // table spans SOP_K_BIN_EXT times the atom's range, so that a block whose scale was rounded down
@@ -392,7 +430,7 @@ extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_
     c->n_bins = pl.n_bins;
     for (int i = 0; i < n_atoms; ++i) {
         const std::vector<float>& L = c->tables[pl.order[i]];
-        c->order[i] = pl.order[i]; c->grp_first[i] = pl.grp_first[i];
+        c->order[i] = pl.order[i]; c->gid[i] = pl.gid[i]; c->mirror[i] = pl.mirror[i]; c->selfsym[i] = pl.selfsym[i];
         c->tpos[i] = L.back(); c->tneg[i] = -L.front(); c->nent[i] = (int)L.size();
         c->bin_sc[i] = pl.sc[i]; c->bin_off[i] = pl.off[i]; c->bin_lo[i] = pl.lo[i]; c->bin_hi[i] = pl.hi[i];
     }
@@ -582,7 +620,10 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     for (int i = 0; i < A; ++i) {
         p.tpos[i] = c->tpos[i]; p.tneg[i] = c->tneg[i]; p.bin_sc[i] = c->bin_sc[i]; p.bin_off[i] = c->bin_off[i];
         p.bin_lo[i] = c->bin_lo[i]; p.bin_hi[i] = c->bin_hi[i];
-        if (c->grp_first[i]) p.grp_first_mask |= 1u << i;
+        p.gid_w |= (unsigned)c->gid[i] << (4 * i);
+        if (c->mirror[i]) p.mirror_mask |= 1u << i;
+        if (c->selfsym[i]) p.selfsym_mask |= 1u << i;
+        p.nent[i] = (unsigned char)c->nent[i];
         if (c->tpos[i] == 1.0f) p.unit_tpos |= 1u << i;
         if (c->tneg[i] == 1.0f) p.unit_tneg |= 1u << i;
         if (c->nent[i] > 16) p.wide_mask |= 1u << i;

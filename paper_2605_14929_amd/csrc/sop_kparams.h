@@ -41,7 +41,8 @@ struct BinRec {
 };
 
 /* Atoms are handled in an internal order in which atoms with equal endpoints (one "scale group":
- * same ideal scale, same scale code, same scaled weights) are adjacent. */
+ * same ideal scale, same scale code, same scaled weights) are adjacent, and an atom that is the
+ * sign-negated copy of another follows it directly where the grouping allows. */
 struct KParams {
     // inputs
     const void*   W;
@@ -66,7 +67,10 @@ struct KParams {
     float tpos[SOP_K_MAXA], tneg[SOP_K_MAXA];      // t+ and -t-
     float bin_sc[SOP_K_MAXA], bin_off[SOP_K_MAXA]; // bin = bits(fma(x, sc, off)) - bits(magic)
     float bin_lo[SOP_K_MAXA], bin_hi[SOP_K_MAXA];  // range of x the table covers (clamped path)
-    unsigned int grp_first_mask;                   // bit a: first atom of its scale group
+    unsigned int gid_w;                            // 4 bits per atom: its scale group (atoms of a group are adjacent)
+    unsigned int mirror_mask;                      // bit a: atom a is the sign-negated copy of atom a-1 (signed scale words take its candidates over)
+    unsigned int selfsym_mask;                     // bit a: atom a is its own sign-negated copy
+    alignas(8) unsigned char nent[SOP_K_MAXA];     // entries of the atom
     unsigned int unit_tpos, unit_tneg;             // bit a: the endpoint is exactly 1 (no division needed)
     unsigned int wide_mask;                        // bit a: more than 16 entries (one byte per code)
     alignas(8) unsigned char uidx[SOP_K_MAXA];     // caller's index of the atom

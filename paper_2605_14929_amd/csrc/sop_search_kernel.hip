@@ -66,7 +66,7 @@ template <int LPB> __device__ __forceinline__ float group_sum(float v)
 // wave-uniform switches of the row loop
 struct Switches {
     int A;
-    uint32_t pair_mask, flip_mask, grp_first, unit_tpos, unit_tneg, wide;
+    uint32_t pair_mask, flip_mask, gid, unit_tpos, unit_tneg, wide, mirror, tiechk, selfsym;
 };
 
 // round a non-negative fp32 to the scale word: nearest, ties to the lower code, saturating
@@ -210,10 +210,14 @@ __device__ __forceinline__ void put_code(uint32_t (&codes)[EPL / 4], int i, uint
 // which shares c*d with the error sum.  The form cancels when the reconstruction is much smaller
 // than the block (saturated or vanished scale); the caller checks that and falls back to
 // direct_cosine_sums() for the wavefront.
-template <int EPL, int METRIC, bool CODES>
+// TIES: `tie` becomes zero in the lanes that hold a scaled weight exactly on a code boundary (the one place
+// where a codebook under the negative scale sign and its sign-negated copy under the positive sign part ways):
+// it is the running minimum of the exclusive-or of the two bit patterns (a boundary at +0 would miss a weight
+// of -0: the host marks no copies for a codebook with such a boundary).
+template <int EPL, int METRIC, bool CODES, bool TIES = false>
 __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float (&cb)[EPL], const float (&x)[EPL],
                                               const uint32_t (&boff)[EPL], float ss, int a,
-                                              bool wide_codes, uint32_t (&codes)[EPL / 4])
+                                              bool wide_codes, uint32_t (&codes)[EPL / 4], uint32_t* tie = nullptr)
 {
     float e0 = 0.0f, e1 = 0.0f, wd = 0.0f, ew = 0.0f;
     if (CODES) {
@@ -229,6 +233,7 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
         for (int j = 0; j < 4; ++j) {
             const int i = i0 + j;
             const bool up = x[i] > r[j].thr;
+            if constexpr (TIES) *tie = min(*tie, __float_as_uint(x[i]) ^ __float_as_uint(r[j].thr));
             const float yv = up ? r[j].yhi : r[j].ylo;
             const float d = __fmaf_rn(-ss, yv, w[i]);
             const float cd = cb[i] * d;
@@ -249,10 +254,10 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
 // Element pass, DIRECT form with the decision sums of metric COS:
 //   w^ = fl(ss*y), num = sum fma(fl(c*w), w^), den = sum fma(fl(c*w^), w^), chunks of 8 and the tree;
 // err is formed as well when WANT_ERR (the blk_err output).
-template <int EPL, bool CODES, bool WANT_ERR>
+template <int EPL, bool CODES, bool WANT_ERR, bool TIES = false>
 __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (&cb)[EPL], const float (&x)[EPL],
                                             const uint32_t (&boff)[EPL], float ss, int a,
-                                            bool wide_codes, uint32_t (&codes)[EPL / 4])
+                                            bool wide_codes, uint32_t (&codes)[EPL / 4], uint32_t* tie = nullptr)
 {
     float e0 = 0.0f, e1 = 0.0f, n0 = 0.0f, n1 = 0.0f, d0 = 0.0f, d1 = 0.0f;
     if (CODES) {
@@ -268,6 +273,7 @@ __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (
         for (int j = 0; j < 4; ++j) {
             const int i = i0 + j;
             const bool up = x[i] > r[j].thr;
+            if constexpr (TIES) *tie = min(*tie, __float_as_uint(x[i]) ^ __float_as_uint(r[j].thr));
             const float yv = up ? r[j].yhi : r[j].ylo;
             const float what = ss * yv;
             const float cw = cb[i] * w[i];
@@ -317,16 +323,23 @@ struct Cand {
     bool weak;    // residual form not trustworthy for this block
 };
 
+// The cosine is a ratio of sums that all scale with the square of the block's magnitude; formed of the raw
+// sums, the product ||w||^2 ||w^||^2 would leave binary32's range for blocks of very small or very large
+// weights.  The value path therefore works on sums multiplied by a power of two, sc = 2^-e with
+// ||w||_c^2 = m 2^e (exact, and the same bits as before wherever nothing over- or underflowed):
+// wns = sc ||w||^2 lies in [1, 2), and the residual form yields sc <w,w^> and sc ||w^||^2 directly.
+struct NormScale { float wns, qwns, sc, sc2; };      // sc ||w||^2, a quarter of it, sc, 2 sc
+
 template <int LPB, int METRIC>
-__device__ __forceinline__ Cand finish_residual(const Sums& s, float wn, float qwn)
+__device__ __forceinline__ Cand finish_residual(const Sums& s, const NormScale& n)
 {
     Cand c;
     c.err = group_sum<LPB>(s.err);
     const float wd = group_sum<LPB>(s.wd);
     const float errw = METRIC == 2 ? group_sum<LPB>(s.ew) : c.err;
-    c.ny = wn - wd;
-    c.dy = __fmaf_rn(-2.0f, wd, wn) + errw;
-    c.weak = !(c.dy >= qwn);
+    c.ny = __fmaf_rn(-wd, n.sc, n.wns);
+    c.dy = __fmaf_rn(errw, n.sc, __fmaf_rn(-n.sc2, wd, n.wns));
+    c.weak = !(c.dy >= n.qwns);
     return c;
 }
 
@@ -676,8 +689,9 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         }
         // The uniform switches below are re-read every row.  Left loop-invariant, each test would be
         // hoisted out of the loop as a 64-bit lane mask and the hundred-odd masks would spill.
-        Switches sw = {p.A, p.pair_mask, p.flip_mask, p.grp_first_mask, p.unit_tpos, p.unit_tneg, p.wide_mask};
-        asm volatile("" : "+s"(sw.A), "+s"(sw.pair_mask), "+s"(sw.flip_mask), "+s"(sw.grp_first), "+s"(sw.unit_tpos), "+s"(sw.unit_tneg), "+s"(sw.wide));
+        Switches sw = {p.A, p.pair_mask, p.flip_mask, p.gid_w, p.unit_tpos, p.unit_tneg, p.wide_mask, p.mirror_mask, 0u, p.selfsym_mask};
+        asm volatile("" : "+s"(sw.A), "+s"(sw.pair_mask), "+s"(sw.flip_mask), "+s"(sw.gid), "+s"(sw.unit_tpos), "+s"(sw.unit_tneg), "+s"(sw.wide));
+        if constexpr (SIGNED) asm volatile("" : "+s"(sw.mirror), "+s"(sw.selfsym));
         const long long cm = m, cs = strip;
         const long long col0 = (cs * 64 + lane) * EPL;
         const bool valid = col0 < (MULTI ? lc_K : p.K);
@@ -729,8 +743,16 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         pmax = valid ? pmax : 1.0f;
         nmax = valid ? nmax : 1.0f;
         const float wn = group_sum<LPB>(EPL == 16 ? wn0 + wn1 : wn0);
-        const float qwn = 0.25f * wn;
         accz += wn > 0.0f ? 0 : (1 << 22);
+        // power of two that brings ||w||^2 into [1, 2) (exponent fields 1 .. 253: norms within 2^-126 .. 2^126)
+        NormScale nsc;
+        {
+            const uint32_t eb = min(max(__float_as_uint(wn) >> 23, 1u), 253u);
+            nsc.sc = __uint_as_float((254u - eb) << 23);
+            nsc.sc2 = nsc.sc + nsc.sc;
+            nsc.wns = wn * nsc.sc;
+            nsc.qwns = 0.25f * nsc.wns;
+        }
 
         const long long blk_in_row = (cs * 64 + lane) / LPB;
         const long long blk = cm * (MULTI ? lc_Bk : p.Bk) + blk_in_row;
@@ -746,12 +768,29 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         bool gnz = false, gnz2 = false, gneg = false, gneg2 = false;
         float gx[EPL], gx2[SIGNED ? EPL : 1];
         uint32_t gboff[EPL], gboff2[SIGNED ? EPL : 1];
+        int cur_gid = -1;                              // scale group the state above belongs to (wave-uniform)
+        // Signed scale word: both candidates (positive, negative scale sign) of the atom before, kept for an atom
+        // that is its sign-negated copy.  Codebook -a under the positive sign reconstructs what a does under the
+        // negative sign, and the other way round (same scale code, same residuals bit for bit, codes k <-> N-1-k),
+        // unless a scaled weight lies exactly on a code boundary: there the two resolve the tie differently.  So
+        // the copy takes over the kept candidates with their roles exchanged, unless some lane of the wavefront
+        // saw such a tie, in which case the copy is evaluated like any other atom.
+        // (plain scalars: copying the candidate structs would drag their padding bytes through scratch memory)
+        float pv_errP = 0.0f, pv_nyP = 0.0f, pv_dyP = 0.0f, pv_errM = 0.0f, pv_nyM = 0.0f, pv_dyM = 0.0f;
+        int pv_qp = 0, pv_qm = 0;
+        uint32_t pv_codesP[EPL / 4], pv_codesM[EPL / 4];
+        bool pv_tie = true;                            // wave-uniform: the kept candidates may not be taken over
+        bool pv_raw = false;                           // wave-uniform: the kept cosine sums are the direct ones (not scaled)
 
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
             score[a] = 0.0f; den[a] = 1.0f; dlt[a] = 0;
             if (__builtin_expect(a < sw.A, 1)) {
-                if (a == 0 || ((sw.grp_first >> a) & 1u)) {       // atom 0 always opens a group
+                bool derived = false;
+                if constexpr (SIGNED) derived = ((sw.mirror >> a) & 1u) && !pv_tie;
+                const int gid = (int)((sw.gid >> (4 * a)) & 15u);
+                if (!derived && gid != cur_gid) {
+                    cur_gid = gid;
                     prepare_sign<EPL, ARGMAX>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff, gneg);
                     if constexpr (SIGNED) prepare_sign<EPL, false>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, gq2, gss2, gnz2, gx2, gboff2, gneg2);
                 }
@@ -760,58 +799,98 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 Cand best;
                 int q = gq;
                 bool neg = ARGMAX ? gneg : false;
-                if constexpr (METRIC == 1) {
+                bool raw = false;                      // wave-uniform: best.ny, best.dy are raw sums (else multiplied by nsc.sc)
+                if constexpr (SIGNED) {
+                    // ---- both signs of the scale: candidate P (positive) and candidate M (negative) ----
+                    float errP, nyP, dyP, errM, nyM, dyM;
+                    int qp, qm;
+                    uint32_t codesP[EPL / 4], codesM[EPL / 4];
+                    // codes of the mirrored codebook: N-1-k in every field (no borrows: every field holds at most N-1)
+                    const uint32_t cmask = (uint32_t)(p.nent[a] - 1) * (wide ? 0x01010101u : 0x11111111u);
+                    if (derived) {
+                        errP = pv_errM; nyP = pv_nyM; dyP = pv_dyM;
+                        errM = pv_errP; nyM = pv_nyP; dyM = pv_dyP;
+                        qp = pv_qm; qm = pv_qp;
+                        if (EMIT) {
+#pragma unroll
+                            for (int j = 0; j < EPL / 4; ++j) { codesP[j] = cmask - pv_codesM[j]; codesM[j] = cmask - pv_codesP[j]; }
+                        }
+                    } else {
+                        uint32_t tie = 0xFFFFFFFFu;
+                        bool weakP, weakM;
+                        qp = gq; qm = gq2;
+                        {
+                            Cand t;
+                            if constexpr (METRIC == 1) t = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT, true>(w, cb, gx, gboff, gss, a, wide, codesP, &tie));
+                            else t = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT, true>(w, cb, gx, gboff, gss, a, wide, codesP, &tie), nsc);
+                            errP = t.err; nyP = t.ny; dyP = t.dy; weakP = t.weak;
+                        }
+                        // a codebook that is its own sign-negated copy reconstructs the same under both signs (away
+                        // from ties), and an equal candidate never replaces the positive sign
+                        if (((sw.selfsym >> a) & 1u) && !__any(tie == 0u && valid)) {
+                            errM = errP; nyM = nyP; dyM = dyP; weakM = weakP;
+                            if (EMIT) {
+#pragma unroll
+                                for (int j = 0; j < EPL / 4; ++j) codesM[j] = cmask - codesP[j];
+                            }
+                        } else {
+                            Cand t;
+                            if constexpr (METRIC == 1) t = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT, true>(w, cb, gx2, gboff2, gss2, a, wide, codesM, &tie));
+                            else t = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT, true>(w, cb, gx2, gboff2, gss2, a, wide, codesM, &tie), nsc);
+                            errM = t.err; nyM = t.ny; dyM = t.dy; weakM = t.weak;
+                        }
+                        pv_tie = __any(tie == 0u && valid) != 0;
+                        if constexpr (METRIC != 1) {
+                            // the residual form is accurate while the reconstruction carries a fair share of the
+                            // block's norm; otherwise the whole wavefront recomputes both candidates' cosine sums directly
+                            if (__builtin_expect(__any(weakP || weakM) != 0, 0)) {
+                                direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, false, a, nyP, dyP);
+                                direct_cosine_sums<EPL, LPB>(cb, w, gx2, gboff2, gnz2, true, a, nyM, dyM);
+                                pv_raw = true;
+                            } else pv_raw = false;
+                        }
+                    }
+                    pv_errP = errP; pv_nyP = nyP; pv_dyP = dyP; pv_errM = errM; pv_nyM = nyM; pv_dyM = dyM;
+                    pv_qp = qp; pv_qm = qm;
+                    if (EMIT) {
+#pragma unroll
+                        for (int j = 0; j < EPL / 4; ++j) { pv_codesP[j] = codesP[j]; pv_codesM[j] = codesM[j]; }
+                    }
+                    if constexpr (METRIC == 1) {
+                        const float bqp = dyP > 0.0f ? nyP * fabsf(nyP) : 0.0f, bdp = dyP > 0.0f ? dyP : 1.0f;
+                        const float bqm = dyM > 0.0f ? nyM * fabsf(nyM) : 0.0f, bdm = dyM > 0.0f ? dyM : 1.0f;
+                        neg = bqm * bdp > bqp * bdm;
+                        score[a] = neg ? bqm : bqp;
+                        den[a] = neg ? bdm : bdp;
+                    } else {
+                        neg = errM < errP;
+                        score[a] = neg ? errM : errP;
+                    }
+                    best.err = neg ? errM : errP;
+                    best.ny = neg ? nyM : nyP;
+                    best.dy = neg ? dyM : dyP;
+                    best.weak = false;
+                    raw = METRIC == 1 || pv_raw;
+                    q = neg ? qm : qp;
+                    if (EMIT) {
+#pragma unroll
+                        for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codesM[j] : codesP[j];
+                    }
+                } else if constexpr (METRIC == 1) {
                     best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, gx, gboff, gss, a, wide, codes));
-                    float bq = best.dy > 0.0f ? best.ny * fabsf(best.ny) : 0.0f;
-                    float bd = best.dy > 0.0f ? best.dy : 1.0f;
-                    if constexpr (SIGNED) {
-                        uint32_t codes2[EPL / 4];
-                        const Cand c2 = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, gx2, gboff2, gss2, a, wide, codes2));
-                        const float q2 = c2.dy > 0.0f ? c2.ny * fabsf(c2.ny) : 0.0f;
-                        const float d2 = c2.dy > 0.0f ? c2.dy : 1.0f;
-                        neg = q2 * bd > bq * d2;
-                        best.err = neg ? c2.err : best.err;
-                        best.ny = neg ? c2.ny : best.ny;
-                        best.dy = neg ? c2.dy : best.dy;
-                        bq = neg ? q2 : bq;
-                        bd = neg ? d2 : bd;
-                        q = neg ? gq2 : q;
-                        if (EMIT) {
-#pragma unroll
-                            for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codes2[j] : codes[j];
-                        }
-                    }
-                    score[a] = bq;
-                    den[a] = bd;
+                    score[a] = best.dy > 0.0f ? best.ny * fabsf(best.ny) : 0.0f;
+                    den[a] = best.dy > 0.0f ? best.dy : 1.0f;
+                    raw = true;
                 } else {
-                    best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, gx, gboff, gss, a, wide, codes), wn, qwn);
-                    if constexpr (SIGNED) {
-                        uint32_t codes2[EPL / 4];
-                        const Cand c2 = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, gx2, gboff2, gss2, a, wide, codes2), wn, qwn);
-                        neg = c2.err < best.err;
-                        best.err = neg ? c2.err : best.err;
-                        best.ny = neg ? c2.ny : best.ny;
-                        best.dy = neg ? c2.dy : best.dy;
-                        best.weak = neg ? c2.weak : best.weak;
-                        q = neg ? gq2 : q;
-                        if (EMIT) {
-#pragma unroll
-                            for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codes2[j] : codes[j];
-                        }
-                    }
+                    best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, gx, gboff, gss, a, wide, codes), nsc);
                     // the residual form is accurate while the reconstruction carries a fair share of
                     // the block's norm; otherwise the whole wavefront recomputes this atom directly
                     if (__builtin_expect(__any(best.weak) != 0, 0)) {
                         float ny1, dy1;
                         direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, ARGMAX ? gneg : false, a, ny1, dy1);
-                        if constexpr (SIGNED) {
-                            float ny2, dy2;
-                            direct_cosine_sums<EPL, LPB>(cb, w, gx2, gboff2, gnz2, true, a, ny2, dy2);
-                            ny1 = neg ? ny2 : ny1;
-                            dy1 = neg ? dy2 : dy1;
-                        }
                         best.ny = ny1;
                         best.dy = dy1;
+                        raw = true;
                     }
                     score[a] = best.err;
                 }
@@ -820,7 +899,11 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 // 3 - cos lies in [2, 4], where binary32 values are 2^-22 apart and their bit patterns count
                 // those steps: the fma's own rounding (nearest, ties to even) rounds 1 - cos to the unit of
                 // the integer sums, and pattern minus pattern of 2.0 is that integer (no conversion)
-                const float rs = __frsqrt_rn(__fmaf_rn(wn, best.dy, 1.0e-37f));
+                // (direct sums come with the codebook's own magnitude: paired with the raw norm, as they were formed;
+                // the COS metric's decision sums are raw sums of w^ and are brought to the scaled norm's units)
+                const float ny_raw = best.ny, dy_raw = best.dy;
+                if constexpr (METRIC == 1) { best.ny *= nsc.sc; best.dy *= nsc.sc; }
+                const float rs = __frsqrt_rn(__fmaf_rn((raw && METRIC != 1) ? wn : nsc.wns, best.dy, 1.0e-37f));
                 const int ia = (int)__float_as_uint(__fmaf_rn(-best.ny, rs, 3.0f)) - 0x40000000;
                 dlt[a] = ia;
                 acca[a] += ia;
@@ -834,14 +917,17 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                         // the block's tree sums num = <w,w^>_c, den = ||w^||_c^2 (chunks of 8, balanced tree) and wn:
                         // fl(fl(num / wn) * fl(|num| / den)), 1 for a block without weighted norm, 0 for a zero reconstruction
                         float num, dn;
-                        if constexpr (METRIC == 1) { num = best.ny; dn = best.dy; }
+                        if constexpr (METRIC == 1) { num = ny_raw; dn = dy_raw; }
                         else {
                             uint32_t nocodes[EPL / 4];
-                            const Cand c1 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx, gboff, gss, a, false, nocodes));
+                            const int slot = derived ? a - 1 : a;            // a copy reads its original's table entries
+                            const Cand c1 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx, gboff, gss, slot, false, nocodes));
                             num = c1.ny; dn = c1.dy;
                             if constexpr (SIGNED) {
-                                const Cand c2 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx2, gboff2, gss2, a, false, nocodes));
-                                num = neg ? c2.ny : num; dn = neg ? c2.dy : dn;
+                                // (for a copy the positive sign is the original's negative one)
+                                const Cand c2 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx2, gboff2, gss2, slot, false, nocodes));
+                                const bool second = neg != derived;
+                                num = second ? c2.ny : num; dn = second ? c2.dy : dn;
                             }
                         }
                         const float rank = wn > 0.0f ? (dn > 0.0f ? (num / wn) * (fabsf(num) / dn) : 0.0f) : 1.0f;
@@ -989,7 +1075,7 @@ constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
 {
     if (na == 2) {                                   // one or two atoms: fewer registers
         if (epl == 8) return (sign_mode == 1 && emit) ? 3 : 4;
-        return sign_mode == 1 ? 2 : 3;
+        return (sign_mode == 1 || emit) ? 2 : 3;       // (with the per-block planes a lane of 16 elements needs more than 168 registers)
     }
     if (epl == 8) {
         if (sign_mode == 1) return emit ? 2 : 3;
