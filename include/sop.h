@@ -367,6 +367,26 @@ sop_status sop_sum_f32(sop_ctx* ctx, const float* x_dev, int64_t n, double* out_
 sop_status sop_partition(sop_ctx* ctx, const float* score_dev, int64_t n_blocks, int64_t n_top, int higher_is_better,
                          uint8_t* pool_b_dev, float* tau_dev, int64_t* n_a_dev, void* hip_stream);
 
+/* The same ranking for several sizes of the first pool at once (Section "Per-Layer Pair Search": the search
+ * sweeps the partition parameter p; steps 2 and 3 for every p of the sweep from one ranking and one pass over
+ * the weights).  n_top: HOST, n_levels (1..8) non-decreasing sizes of the first pool, so that the fitting pools
+ * are nested: pool j = the blocks ranked strictly worse than tau_j, pool 0 the largest.
+ *   level_dev   DEVICE, n_blocks bytes, 4-byte aligned: the number of pools the block belongs to
+ *               (0 .. n_levels); block b is in pool j exactly when level[b] > j
+ *   tau_dev     DEVICE, n_levels floats; n_a_dev  DEVICE, n_levels int64: as in sop_partition(), per threshold
+ * Each (tau_j, n_a_j, pool j) equals what sop_partition() returns for n_top[j].  Exact, asynchronous, no
+ * workspace; calls on one context must not overlap on the GPU. */
+sop_status sop_partition_levels(sop_ctx* ctx, const float* score_dev, int64_t n_blocks, const int64_t* n_top, int n_levels,
+                                int higher_is_better, uint8_t* level_dev, float* tau_dev, int64_t* n_a_dev, void* hip_stream);
+
+/* sop_dd_histogram() for nested pools: level_dev as sop_partition_levels() writes it; hist_dev: DEVICE,
+ * [n_levels][n_bins] 64-bit integers, overwritten: row j is the histogram of pool j (the blocks of level > j),
+ * equal to sop_dd_histogram() with pool j as block mask.  One pass over the weights.  n_levels * n_bins must
+ * not exceed 8192. */
+sop_status sop_dd_histogram_levels(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                   const float* c_dev, int g, int n_bins, int64_t row_step, const uint8_t* level_dev, int n_levels,
+                                   int64_t* hist_dev, void* hip_stream);
+
 /* ---- materialisation (Section "Scale Format and Metabit Allocation", paragraphs "The SwExMy
  * notation", "Bit placement" and "Worked examples"; Section "Per-Layer Pair Search": one metabit per
  * block names the codebook; introduction: a block of g n-bit codes is g*n/8 bytes). ----

@@ -100,6 +100,10 @@ def lib():
         L.sop_pair_search_layers.argtypes = [C.c_void_p, C.POINTER(_Layer), C.c_int, C.c_int, C.c_int, ScaleFmt, C.c_int,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_partition.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sop_partition_levels.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p]
+        L.sop_dd_histogram_levels.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_int,
+                                              C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.sop_pack_blocks.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, ScaleFmt, C.c_void_p, C.c_void_p, C.c_int,
                                       C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                       C.POINTER(C.c_int), C.c_void_p]
@@ -415,6 +419,37 @@ class Context:
                                    C.c_void_p(pool_b.data_ptr()), C.c_void_p(tau.data_ptr()), C.c_void_p(n_a.data_ptr()),
                                    C.c_void_p(st)), self._h)
         return pool_b, tau, n_a
+
+    def partition_levels(self, score, n_tops, higher_is_better: bool = True, stream=None):
+        """sop_partition_levels on a contiguous float32 CUDA tensor of per-block scores; returns device tensors
+        (level [N_b] uint8, tau [L] float32, n_a [L] int64)."""
+        import torch
+        if not score.is_cuda or score.dtype != torch.float32 or not score.is_contiguous():
+            raise SopError(1, "score must be a contiguous float32 CUDA tensor")
+        n, L = score.numel(), len(n_tops)
+        level = torch.empty(n, dtype=torch.uint8, device=score.device)
+        tau = torch.empty(L, dtype=torch.float32, device=score.device)
+        n_a = torch.empty(L, dtype=torch.int64, device=score.device)
+        tops = (C.c_int64 * L)(*[int(t) for t in n_tops])
+        st = torch.cuda.current_stream(score.device).cuda_stream if stream is None else stream
+        _check(lib().sop_partition_levels(self._h, C.c_void_p(score.data_ptr()), n, tops, L, 1 if higher_is_better else 0,
+                                          C.c_void_p(level.data_ptr()), C.c_void_p(tau.data_ptr()), C.c_void_p(n_a.data_ptr()),
+                                          C.c_void_p(st)), self._h)
+        return level, tau, n_a
+
+    def dd_histogram_levels(self, W, c, g, level, n_levels: int, n_bins: int = 1024, row_step: int = 1, stream=None):
+        """sop_dd_histogram_levels on torch CUDA tensors; returns an [n_levels, n_bins] int64 device tensor."""
+        import torch
+        dt = BF16 if W.dtype == torch.bfloat16 else (F32 if W.dtype == torch.float32 else None)
+        if dt is None or not W.is_cuda or W.dim() != 2 or W.stride(1) != 1:
+            raise SopError(1, "W must be a 2-D float32 or bfloat16 CUDA tensor with contiguous rows")
+        M, K = W.shape
+        hist = torch.empty((n_levels, n_bins), dtype=torch.int64, device=W.device)
+        st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
+        _check(lib().sop_dd_histogram_levels(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0),
+                                             None if c is None else C.c_void_p(c.data_ptr()), g, n_bins, row_step,
+                                             C.c_void_p(level.data_ptr()), n_levels, C.c_void_p(hist.data_ptr()), C.c_void_p(st)), self._h)
+        return hist
 
     def pack_blocks(self, out, M, K, g, fmt: ScaleFmt, a: int, b=None, pair_q: int = 0, stream=None):
         """sop_pack_blocks on the outputs of an emitting pair_search: atom a alone (b None) or the

@@ -26,6 +26,7 @@ extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* strea
 extern "C" hipError_t sopk_sum_launch(const LsParams* p, void* stream);
 extern "C" hipError_t sopk_probe_launch(const void* x, long long n16, unsigned int* out, void* stream);
 extern "C" hipError_t sopk_sel_launch(const SelParams* p, int n_wg_count, int n_wg, void* stream);
+extern "C" hipError_t sopk_selm_launch(const SelMParams* p, int n_wg_count, int n_wg, void* stream);
 extern "C" hipError_t sopk_pack_launch(const PackParams* p, void* stream);
 
 namespace {
@@ -114,6 +115,8 @@ struct sop_ctx {
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
     int sel_set = 0;
+    unsigned int* d_selm = nullptr;       // [2][SOP_K_SELM_WORDS] two sets of digit counts of the ranking with several thresholds
+    int selm_set = 0;
     unsigned long long* d_sums = nullptr; // two sets of [SOP_K_REPL][SOP_K_NCOL] layer sums followed by their ticket counters; zero between calls
     hipStream_t lane_stream[kLanes] = {};   // sop_pair_search_layers deals the layers out to streams of its own
     hipEvent_t lane_event[kLanes + 1] = {};  // one per stream (join) and one for the fork
@@ -192,6 +195,12 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(rank counts)");
     }
+    if ((e = hipMalloc((void**)&c->d_selm, sizeof(unsigned int) * 2 * SOP_K_SELM_WORDS)) != hipSuccess ||
+        (e = hipMemset(c->d_selm, 0, sizeof(unsigned int) * 2 * SOP_K_SELM_WORDS)) != hipSuccess) {
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); if (c->d_selm) (void)hipFree(c->d_selm);
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(rank counts of the sweep)");
+    }
     const size_t msums_bytes = sizeof(unsigned long long) * ((size_t)kMaxLayers * SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1);
     if ((e = hipMalloc((void**)&c->d_ldesc, sizeof(LayerDesc) * kMaxLayers)) != hipSuccess ||
         (e = hipMalloc((void**)&c->d_msums, msums_bytes)) != hipSuccess || (e = hipMemset(c->d_msums, 0, msums_bytes)) != hipSuccess ||
@@ -199,7 +208,7 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         (e = hipHostMalloc((void**)&c->h_ldesc[1], sizeof(LayerDesc) * kMaxLayers, hipHostMallocDefault)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&c->ldesc_copied[0], hipEventDisableTiming)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&c->ldesc_copied[1], hipEventDisableTiming)) != hipSuccess) {
-        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel);
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); (void)hipFree(c->d_selm);
         if (c->d_ldesc) (void)hipFree(c->d_ldesc);
         if (c->d_msums) (void)hipFree(c->d_msums);
         for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
@@ -225,6 +234,7 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_ddacc) (void)hipFree(c->d_ddacc);
         if (c->d_ls) (void)hipFree(c->d_ls);
         if (c->d_sel) (void)hipFree(c->d_sel);
+        if (c->d_selm) (void)hipFree(c->d_selm);
         if (c->d_ldesc) (void)hipFree(c->d_ldesc);
         if (c->d_msums) (void)hipFree(c->d_msums);
         for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
@@ -970,8 +980,9 @@ extern "C" sop_status sop_atom_bof(int n_bits, const double* draws, int64_t n_dr
 // ------------------------------------------------------------------ data-derived codebook (DD atom)
 static bool dd_bins_ok(int n_bins) { return n_bins >= 64 && n_bins <= SOP_K_DD_MAXBINS && (n_bins & (n_bins - 1)) == 0; }
 
-extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
-                                       const float* cn, int g, int n_bins, int64_t row_step, const uint8_t* block_mask, int64_t* hist, void* stream)
+static sop_status dd_histogram_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                    const float* cn, int g, int n_bins, int64_t row_step, const uint8_t* block_mask, int n_levels,
+                                    int64_t* hist, void* stream)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !hist) return fail(c, SOP_EINVAL, "sop_dd_histogram: W and hist must not be NULL");
@@ -982,12 +993,15 @@ extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtyp
     if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
     if (cn && !aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
     if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..8192");
+    if (n_levels < 0 || n_levels > 255 || (long long)std::max(n_levels, 1) * n_bins > SOP_K_DD_MAXBINS)
+        return fail(c, SOP_EINVAL, "sop_dd_histogram_levels: n_levels * n_bins must not exceed 8192");
+    if (n_levels > 0 && !block_mask) return fail(c, SOP_EINVAL, "sop_dd_histogram_levels: level_dev must not be NULL");
     if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
     if (row_step < 1) return fail(c, SOP_EINVAL, "row_step must be at least 1");
     const int epl = g < 16 ? g : 16;
     DdParams p;
     std::memset(&p, 0, sizeof(p));
-    p.W = W; p.c = cn; p.block_mask = block_mask; p.M = M; p.K = K; p.ldw = ldw; p.Bk = K / g;
+    p.W = W; p.c = cn; p.block_mask = block_mask; p.n_levels = n_levels; p.M = M; p.K = K; p.ldw = ldw; p.Bk = K / g;
     p.row_step = row_step; p.Ms = (M + row_step - 1) / row_step;
     p.strips = (K / epl + 63) / 64;
     p.total_units = p.strips * p.Ms;
@@ -1003,6 +1017,20 @@ extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtyp
     hipError_t e = sopk_dd_launch(&p, dtype == SOP_BF16, g, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
+}
+
+extern "C" sop_status sop_dd_histogram(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                       const float* cn, int g, int n_bins, int64_t row_step, const uint8_t* block_mask, int64_t* hist, void* stream)
+{
+    return dd_histogram_impl(c, W, dtype, M, K, ldw, cn, g, n_bins, row_step, block_mask, 0, hist, stream);
+}
+
+extern "C" sop_status sop_dd_histogram_levels(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
+                                              const float* cn, int g, int n_bins, int64_t row_step, const uint8_t* level, int n_levels,
+                                              int64_t* hist, void* stream)
+{
+    if (c && n_levels < 1) return fail(c, SOP_EINVAL, "sop_dd_histogram_levels: n_levels must be at least 1");
+    return dd_histogram_impl(c, W, dtype, M, K, ldw, cn, g, n_bins, row_step, level, n_levels, hist, stream);
 }
 
 extern "C" sop_status sop_dd_fit(const int64_t* hist, int n_bins, int n_entries, int iters, const float* init, float* out)
@@ -1359,6 +1387,39 @@ extern "C" sop_status sop_partition(sop_ctx* c, const float* score, int64_t n_bl
     hipError_t e = sopk_sel_launch(&p, n_wg_count, n_wg, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     if (!p.all_b) c->sel_set ^= 1;
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_partition_levels(sop_ctx* c, const float* score, int64_t n_blocks, const int64_t* n_top, int n_levels,
+                                           int higher_is_better, uint8_t* level, float* tau, int64_t* n_a, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!score || !n_top || !level || !tau || !n_a) return fail(c, SOP_EINVAL, "sop_partition_levels: score, n_top, level_dev, tau and n_a must not be NULL");
+    if (n_blocks < 1 || n_blocks > 0x7FFFFFFFll) return fail(c, SOP_ESHAPE, "sop_partition_levels: n_blocks must lie in 1 .. 2^31-1");
+    if (n_levels < 1 || n_levels > SOP_K_SEL_MAXLEV) return fail(c, SOP_EINVAL, "sop_partition_levels: 1 .. 8 thresholds");
+    for (int j = 0; j < n_levels; ++j) {
+        if (n_top[j] < 0 || n_top[j] > n_blocks) return fail(c, SOP_EINVAL, "sop_partition_levels: n_top must lie in 0 .. n_blocks");
+        if (j && n_top[j] < n_top[j - 1]) return fail(c, SOP_EINVAL, "sop_partition_levels: n_top must not decrease (the pools are nested)");
+    }
+    if (!aligned16(score)) return fail(c, SOP_EINVAL, "sop_partition_levels: score must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(level) & 3u) || (reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(n_a) & 7u))
+        return fail(c, SOP_EINVAL, "sop_partition_levels: level_dev and tau must be 4-byte aligned, n_a 8-byte aligned");
+    SelMParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.score = score; p.n = n_blocks; p.higher = higher_is_better ? 1 : 0; p.n_levels = n_levels;
+    bool any = false;
+    for (int j = 0; j < n_levels; ++j) { p.n_top[j] = n_top[j]; any = any || n_top[j] != 0; }
+    p.hist = c->d_selm + (c->selm_set ? SOP_K_SELM_WORDS : 0); p.hist_other = c->d_selm + (c->selm_set ? 0 : SOP_K_SELM_WORDS);
+    p.level = level; p.tau = tau; p.n_a = reinterpret_cast<long long*>(n_a);
+    const long long quads = std::max<long long>((n_blocks / 4 + SOP_K_SEL_THREADS - 1) / SOP_K_SEL_THREADS, 1);
+    const int n_wg = (int)std::min<long long>((long long)c->n_cu * 4, quads);
+    const long long cquads = std::max<long long>((n_blocks / 4 + SOP_K_CNT_THREADS - 1) / SOP_K_CNT_THREADS, 1);
+    const int n_wg_count = (int)std::min<long long>(std::max(c->n_cu / 2, 1), cquads);
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = sopk_selm_launch(&p, n_wg_count, n_wg, stream);
+    if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    if (any) c->selm_set ^= 1;
     return SOP_OK;
 }
 

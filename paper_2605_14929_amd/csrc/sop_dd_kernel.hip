@@ -9,7 +9,9 @@
 //   hist[bin] += mass                                                   (64-bit integers)
 // Integer sums do not depend on the order of addition, so the histogram is reproducible bit for bit.
 // Only rows 0, row_step, 2*row_step, ... enter (row_step = 1: the whole layer), and, when a block
-// mask is given, only blocks whose mask byte is non-zero.
+// mask is given, only blocks whose mask byte is non-zero.  With levels (the sweep over the partition
+// parameter of the per-layer search: nested fitting pools) the mask byte names one of L histograms, and
+// the result holds the L pool histograms: one pass over the weights serves every pool of the sweep.
 //
 // Work mapping as in the search kernel: a lane owns min(g,16) consecutive elements of a row, a
 // wavefront walks down the rows of a 64-lane strip.  Each workgroup (16 wavefronts, one per compute
@@ -30,7 +32,8 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
     extern __shared__ __align__(16) unsigned long long s_hist[];      // [H]
     __shared__ float s_max[SOP_K_DD_THREADS / 64];
     __shared__ unsigned int s_flag;
-    const int H = p.n_bins;
+    const int HB = p.n_bins;                                          // bins of one histogram
+    const int H = p.n_bins * (p.n_levels > 0 ? p.n_levels : 1);       // words of all the histograms of the call
     for (int i = threadIdx.x; i < H; i += SOP_K_DD_THREADS) s_hist[i] = 0ull;
     // cmax = max_k c_k (order-independent), found by every workgroup for itself
     float cmax = 1.0f;
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
     const long long u0 = p.total_units * wave / p.n_waves;
     const long long u1 = p.total_units * (wave + 1) / p.n_waves;
     const float cs = cmax > 0.0f ? 1048576.0f / cmax : 0.0f;      // all-zero channel norms: an empty histogram
-    const float half = 0.5f * (float)H;
+    const float half = 0.5f * (float)HB;
 
     long long strip = u0 / p.Ms;
     long long m = u0 - strip * p.Ms;              // index among the sampled rows
@@ -116,9 +119,12 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
         if (LPB >= 2) a = fmaxf(a, __shfl_xor(a, 1, 64));
         if (LPB >= 4) a = fmaxf(a, __shfl_xor(a, 2, 64));
         bool take = valid && a > 0.0f;
+        int hbase = 0;                              // first word of the block's histogram
         if (p.block_mask && take) {                 // only the blocks of the pool enter
             const long long blk = m * p.row_step * p.Bk + (strip * 64 + lane) / LPB;
-            take = p.block_mask[blk] != 0;
+            const int lv = p.block_mask[blk];
+            take = lv != 0;
+            if (p.n_levels > 0) hbase = (min(lv, p.n_levels) - 1) * HB;
         }
         if (take) {
             const float r = 1.0f / a;
@@ -126,8 +132,8 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
             for (int i = 0; i < EPL; ++i) {
                 const float x = w[i] * r;
                 int bin = (int)floorf(x * half + half);          // x*half is exact: the sum rounds once
-                bin = bin < 0 ? 0 : (bin > H - 1 ? H - 1 : bin);
-                atomicAdd(&s_hist[bin], (unsigned long long)mass[i]);
+                bin = bin < 0 ? 0 : (bin > HB - 1 ? HB - 1 : bin);
+                atomicAdd(&s_hist[hbase + bin], (unsigned long long)mass[i]);
             }
         }
         if (++m == p.Ms) { m = 0; ++strip; }
@@ -160,10 +166,25 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
             const int i = threadIdx.x + j * SOP_K_DD_THREADS;
             got[j] = i < H ? atomicExch(p.acc + i, 0ull) : 0ull;
         }
+        if (p.n_levels > 1) {
+            // nested pools: histogram j of the result is the sum of the level histograms j .. L-1
+            __syncthreads();
 #pragma unroll
-        for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) {
-            const int i = threadIdx.x + j * SOP_K_DD_THREADS;
-            if (i < H) p.hist[i] = (long long)got[j];
+            for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) {
+                const int i = threadIdx.x + j * SOP_K_DD_THREADS;
+                if (i < H) s_hist[i] = got[j];
+            }
+            __syncthreads();
+            for (int b = threadIdx.x; b < HB; b += SOP_K_DD_THREADS) {
+                unsigned long long run = 0ull;
+                for (int l = p.n_levels - 1; l >= 0; --l) { run += s_hist[l * HB + b]; p.hist[l * HB + b] = (long long)run; }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < SOP_K_DD_MAXBINS / SOP_K_DD_THREADS; ++j) {
+                const int i = threadIdx.x + j * SOP_K_DD_THREADS;
+                if (i < H) p.hist[i] = (long long)got[j];
+            }
         }
         if (threadIdx.x == 0) atomicExch(p.done, 0u);
     }
@@ -175,7 +196,7 @@ extern "C" hipError_t sopk_dd_launch(const DdParams* pp, int is_bf16, int g, voi
 {
     DdParams p = *pp;
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = (size_t)p.n_bins * sizeof(unsigned long long);
+    const size_t lds = (size_t)p.n_bins * (size_t)(p.n_levels > 0 ? p.n_levels : 1) * sizeof(unsigned long long);
     const dim3 grid((unsigned)(p.n_waves / (SOP_K_DD_THREADS / 64))), block(SOP_K_DD_THREADS);
 #define SOPK_DD(B, E, L) hipLaunchKernelGGL((sopk::dd_hist_kernel<B, E, L>), grid, block, lds, st, p)
     if (is_bf16) {

@@ -123,6 +123,9 @@ struct DdParams {
     const void*  W;
     const float* c;                  // null: uniform weights
     const unsigned char* block_mask; // null: every block; else [M*K/g], non-zero = the block enters
+    int n_levels;                    // 0: plain mask.  L >= 1: the mask byte is a level 0..L; a block of level l >= 1 enters
+                                     // histogram l-1 of L (n_bins bins each), and the result holds, for every j, the sum of
+                                     // the histograms j .. L-1 (the pool of every block of level > j)
     long long M, K, ldw, Bk;
     long long row_step, Ms;          // every row_step-th row is used: Ms = ceil(M / row_step) rows
     long long strips, total_units, n_waves;  // total_units = strips * Ms
@@ -183,6 +186,22 @@ struct SelParams {
     unsigned char* pool_b;           // [n] 1 = ranked strictly worse than the threshold
     float* tau;                      // [1] the threshold score
     long long* n_a;                  // [1] blocks that stay in the first pool
+};
+
+/* Ranking with several thresholds at once (the sweep over the partition parameter p): nested pools */
+#define SOP_K_SEL_MAXLEV 8
+#define SOP_K_SELM_WORDS ((1 + 2 * SOP_K_SEL_MAXLEV) * SOP_K_SEL_BINS)   /* one set of digit counts */
+struct SelMParams {
+    const float* score;              // [n]
+    long long n;
+    int higher;                      // 1: a larger score ranks better
+    int n_levels;                    // thresholds, 1 .. SOP_K_SEL_MAXLEV
+    long long n_top[SOP_K_SEL_MAXLEV];   // non-decreasing sizes of the first pool (0: every block goes to the second pool)
+    unsigned int* hist;              // pass 0: [SOP_K_SEL_BINS]; pass 1: [MAXLEV][BINS]; pass 2: [MAXLEV][BINS] (zero when the call starts)
+    unsigned int* hist_other;        // the set the next call counts into: cleared by this call
+    unsigned char* level;            // [n] number of thresholds the block ranks strictly worse than
+    float* tau;                      // [n_levels] threshold scores
+    long long* n_a;                  // [n_levels] blocks at least as good as the threshold
 };
 
 /* Packing of scale words and code payloads */

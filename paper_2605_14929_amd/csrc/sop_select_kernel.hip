@@ -178,7 +178,165 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_split_kernel(const Sel
         p.hist_other[gi] = 0u;
 }
 
+// ---- several thresholds at once (the sweep over the partition parameter: nested pools) ----
+// The first counting pass is shared by all thresholds; in the second and third pass every threshold counts
+// the keys that agree with its own digits so far, in a histogram of its own.  Thresholds whose digits so
+// far coincide share one histogram (the one of the first of them).  A last kernel writes, per block, the
+// number of thresholds it ranks strictly worse than: the pools are nested, pool j holds the blocks of
+// level > j.
+struct MultiPrefix {
+    uint32_t prefix[SOP_K_SEL_MAXLEV];       // digits fixed so far
+    unsigned int rank_in[SOP_K_SEL_MAXLEV];  // rank wanted among the keys with those digits
+    unsigned int above[SOP_K_SEL_MAXLEV];    // keys above those digits
+    int alias[SOP_K_SEL_MAXLEV];             // first threshold with the same digits so far
+};
+
+// digits of every threshold after `passes` passes (1 or 2), from the histograms of those passes
+__device__ void multi_prefix(const SelMParams& p, int passes, MultiPrefix& mp, Found* s_found, unsigned int* s_wave)
+{
+    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
+        mp.prefix[j] = 0; mp.rank_in[j] = 1; mp.above[j] = 0; mp.alias[j] = j;
+        if (j >= p.n_levels || p.n_top[j] == 0) continue;
+        const Found f0 = find_digit(p.hist, (unsigned int)p.n_top[j], s_found, s_wave);
+        mp.prefix[j] = (uint32_t)f0.digit << 21; mp.rank_in[j] = f0.rank_in; mp.above[j] = f0.above;
+    }
+    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j)
+        _Pragma("unroll") for (int i = j - 1; i >= 0; --i)
+            if (j < p.n_levels && p.n_top[i] != 0 && p.n_top[j] != 0 && mp.prefix[i] == mp.prefix[j]) mp.alias[j] = mp.alias[i];
+    if (passes >= 2) {
+        uint32_t pre2[SOP_K_SEL_MAXLEV];
+        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
+            pre2[j] = mp.prefix[j];
+            if (j >= p.n_levels || p.n_top[j] == 0) continue;
+            const Found f1 = find_digit(p.hist + (1 + mp.alias[j]) * SOP_K_SEL_BINS, mp.rank_in[j], s_found, s_wave);
+            pre2[j] |= (uint32_t)f1.digit << 10; mp.rank_in[j] = f1.rank_in; mp.above[j] += f1.above;
+        }
+        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
+            mp.prefix[j] = pre2[j]; mp.alias[j] = j;
+        }
+        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j)
+            _Pragma("unroll") for (int i = j - 1; i >= 0; --i)
+                if (j < p.n_levels && p.n_top[i] != 0 && p.n_top[j] != 0 && mp.prefix[i] == mp.prefix[j]) mp.alias[j] = mp.alias[i];
+    }
+}
+
+template <int PASS>
+__global__ __launch_bounds__(SOP_K_CNT_THREADS) void rank_count_multi_kernel(const SelMParams p)
+{
+    extern __shared__ unsigned int s_mh[];                          // pass 0: [BINS]; else [n_levels][BINS]
+    __shared__ Found s_found;
+    __shared__ unsigned int s_wave[SOP_K_SEL_BINS / 8 / 64];
+    const int L = PASS == 0 ? 1 : p.n_levels;
+    for (int i = threadIdx.x; i < L * SOP_K_SEL_BINS; i += SOP_K_CNT_THREADS) s_mh[i] = 0u;
+    MultiPrefix mp;
+    const uint32_t pmask = PASS == 0 ? 0u : PASS == 1 ? 0xFFE00000u : 0xFFFFFC00u;
+    if (PASS >= 1) multi_prefix(p, PASS, mp, &s_found, s_wave);
+    __syncthreads();
+    const bool higher = p.higher != 0;
+    const long long n4 = p.n >> 2;
+    const float4* s4 = reinterpret_cast<const float4*>(p.score);
+    for (long long i = (long long)blockIdx.x * SOP_K_CNT_THREADS + threadIdx.x; i < n4; i += (long long)gridDim.x * SOP_K_CNT_THREADS) {
+        const float4 v = s4[i];
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t k = rank_key(e[j], higher);
+            if (PASS == 0) count_digit(s_mh, true, digit_of(k, 0));
+            else
+                _Pragma("unroll") for (int t = 0; t < SOP_K_SEL_MAXLEV; ++t)
+                    if (t < p.n_levels && p.n_top[t] != 0 && mp.alias[t] == t) count_digit(s_mh + t * SOP_K_SEL_BINS, (k & pmask) == mp.prefix[t], digit_of(k, PASS));
+        }
+    }
+    if (blockIdx.x == 0 && (long long)threadIdx.x < (p.n & 3)) {     // ragged tail
+        const uint32_t k = rank_key(p.score[(n4 << 2) + threadIdx.x], higher);
+        if (PASS == 0) atomicAdd(&s_mh[digit_of(k, 0)], 1u);
+        else
+            _Pragma("unroll") for (int t = 0; t < SOP_K_SEL_MAXLEV; ++t)
+                if (t < p.n_levels && p.n_top[t] != 0 && mp.alias[t] == t && (k & pmask) == mp.prefix[t]) atomicAdd(&s_mh[t * SOP_K_SEL_BINS + digit_of(k, PASS)], 1u);
+    }
+    __syncthreads();
+    unsigned int* out = p.hist + (PASS == 0 ? 0 : PASS == 1 ? SOP_K_SEL_BINS : (1 + SOP_K_SEL_MAXLEV) * SOP_K_SEL_BINS);
+    for (int i = threadIdx.x; i < L * SOP_K_SEL_BINS; i += SOP_K_CNT_THREADS) {
+        const unsigned int v = s_mh[i];
+        if (v) atomicAdd(out + i, v);
+    }
+}
+
+__global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_level_kernel(const SelMParams p)
+{
+    __shared__ Found s_found;
+    __shared__ unsigned int s_wave[SOP_K_SEL_THREADS / 64];
+    const bool higher = p.higher != 0;
+    MultiPrefix mp;
+    multi_prefix(p, 2, mp, &s_found, s_wave);
+    // a key of 2^32 stands for "every block ranks worse" (a first pool of size zero)
+    unsigned long long tkey[SOP_K_SEL_MAXLEV];
+    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
+        tkey[j] = 0ull;                                            // (thresholds beyond n_levels: no block ranks worse)
+        if (j >= p.n_levels) continue;
+        tkey[j] = 1ull << 32;
+        float tau = higher ? __uint_as_float(0x7F800000u) : __uint_as_float(0xFF800000u);
+        unsigned int n_a = 0;
+        if (p.n_top[j] != 0) {
+            const unsigned int* h2 = p.hist + (1 + SOP_K_SEL_MAXLEV + mp.alias[j]) * SOP_K_SEL_BINS;
+            const Found f2 = find_digit(h2, mp.rank_in[j], &s_found, s_wave);
+            const uint32_t tk = mp.prefix[j] | (uint32_t)f2.digit;
+            tkey[j] = tk;
+            tau = key_score(tk, higher);
+            n_a = mp.above[j] + f2.above + h2[f2.digit];          // keys above tau's, plus every key equal to it
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) { p.tau[j] = tau; p.n_a[j] = (long long)n_a; }
+    }
+    const long long n4 = p.n >> 2;
+    const float4* s4 = reinterpret_cast<const float4*>(p.score);
+    uint32_t* m4 = reinterpret_cast<uint32_t*>(p.level);
+    for (long long i = (long long)blockIdx.x * SOP_K_SEL_THREADS + threadIdx.x; i < n4; i += (long long)gridDim.x * SOP_K_SEL_THREADS) {
+        const float4 v = s4[i];
+        const float e[4] = {v.x, v.y, v.z, v.w};
+        uint32_t w = 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned long long k = rank_key(e[j], higher);
+            uint32_t lv = 0u;
+            _Pragma("unroll") for (int t = 0; t < SOP_K_SEL_MAXLEV; ++t) lv += k < tkey[t] ? 1u : 0u;
+            w |= lv << (8 * j);
+        }
+        m4[i] = w;
+    }
+    if (blockIdx.x == 0 && (long long)threadIdx.x < (p.n & 3)) {
+        const long long i = (n4 << 2) + threadIdx.x;
+        const unsigned long long k = rank_key(p.score[i], higher);
+        unsigned int lv = 0u;
+        _Pragma("unroll") for (int t = 0; t < SOP_K_SEL_MAXLEV; ++t) lv += k < tkey[t] ? 1u : 0u;
+        p.level[i] = (unsigned char)lv;
+    }
+    for (long long gi = (long long)blockIdx.x * SOP_K_SEL_THREADS + threadIdx.x; gi < SOP_K_SELM_WORDS; gi += (long long)gridDim.x * SOP_K_SEL_THREADS)
+        p.hist_other[gi] = 0u;
+}
+
 }  // namespace sopk
+
+extern "C" hipError_t sopk_selm_launch(const SelMParams* pp, int n_wg_count, int n_wg, void* stream)
+{
+    const SelMParams p = *pp;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((unsigned)n_wg), block(SOP_K_SEL_THREADS), cgrid((unsigned)n_wg_count), cblock(SOP_K_CNT_THREADS);
+    bool any = false;
+    for (int j = 0; j < p.n_levels; ++j) any = any || p.n_top[j] != 0;
+    if (any) {
+        const size_t lds0 = SOP_K_SEL_BINS * sizeof(unsigned int), ldsL = (size_t)p.n_levels * lds0;
+        if (ldsL > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sopk::rank_count_multi_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsL);
+            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sopk::rank_count_multi_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsL);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL((sopk::rank_count_multi_kernel<0>), cgrid, cblock, lds0, st, p);
+        hipLaunchKernelGGL((sopk::rank_count_multi_kernel<1>), cgrid, cblock, ldsL, st, p);
+        hipLaunchKernelGGL((sopk::rank_count_multi_kernel<2>), cgrid, cblock, ldsL, st, p);
+    }
+    hipLaunchKernelGGL(sopk::rank_level_kernel, grid, block, 0, st, p);
+    return hipGetLastError();
+}
 
 extern "C" hipError_t sopk_sel_launch(const SelParams* pp, int n_wg_count, int n_wg, void* stream)
 {

@@ -118,3 +118,44 @@ def test_block_counts_of_the_large_configurations():
         s = (1.0 - np.abs(rng.standard_normal(N)).astype(np.float32) * np.float32(0.004)).astype(np.float32)
         for p_percent, higher in ((70.0, True), (12.5, False)):
             check(s, PT.top_count(p_percent, N), higher)
+
+
+@pytest.mark.parametrize("higher", [True, False])
+def test_several_thresholds_at_once_equal_single_rankings(higher):
+    """sop_partition_levels / sop_dd_histogram_levels (the sweep over p from one ranking and one pass over the
+    weights) against the oracle's ranking and masked histogram, threshold by threshold."""
+    import torch
+    M, K, g = 96, 2048, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 7700, row_sigma=0.5))
+    c = si.channel_norms(K, 1.0, 7701)
+    Nb = M * K // g
+    rng = np.random.default_rng(77)
+    # scores crowded like block cosines, with ties, zeros of both signs and a ragged length for the pure ranking
+    s = (1.0 - np.abs(rng.standard_normal(Nb)).astype(np.float32) * np.float32(0.004)).astype(np.float32)
+    s[rng.integers(0, Nb, 500)] = s[7]
+    s[:5] = [0.0, -0.0, 1.0, 1.0, -1.0]
+    cx = ctx()
+    for tops in ([PT.top_count(p, Nb) for p in (50.0, 70.0, 85.0, 95.0)], [0, 0, 17, Nb // 3, Nb // 3, Nb - 1, Nb, Nb], [Nb // 2], [0]):
+        level, tau, n_a = cx.partition_levels(torch.from_numpy(s).cuda(), tops, higher)
+        hist = cx.dd_histogram_levels(torch.from_numpy(W).cuda().to(torch.bfloat16), torch.from_numpy(c).cuda(), g, level, len(tops), 512)
+        torch.cuda.synchronize()
+        level, tau, n_a, hist = level.cpu().numpy(), tau.cpu().numpy(), n_a.cpu().numpy(), hist.cpu().numpy()
+        want_level = np.zeros(Nb, dtype=np.int64)
+        for j, t in enumerate(tops):
+            rt, rp, rn = PT.partition(s, t, higher)
+            assert tau[j] == rt and n_a[j] == rn, (tops, j)
+            assert np.array_equal((level > j).astype(np.uint8), rp), (tops, j)
+            assert np.array_equal(hist[j], DD.histogram(W, c, g, 512, block_mask=rp)), (tops, j)
+            want_level += rp
+        assert np.array_equal(level, want_level)
+    # a ragged number of scores (not a multiple of four), ranking only
+    s2 = s[:Nb - 3]
+    tops = [10, 1000, Nb // 2]
+    level, tau, n_a = cx.partition_levels(torch.from_numpy(s2).cuda(), tops, higher)
+    torch.cuda.synchronize()
+    for j, t in enumerate(tops):
+        rt, rp, rn = PT.partition(s2, t, higher)
+        assert tau.cpu().numpy()[j] == rt and int(n_a.cpu().numpy()[j]) == rn
+        assert np.array_equal((level.cpu().numpy() > j).astype(np.uint8), rp)
+    with pytest.raises(sop.SopError):
+        cx.partition_levels(torch.from_numpy(s).cuda(), [100, 50], higher)          # pools must be nested
