@@ -13,8 +13,8 @@
  *     non-zero status sop_last_error() returns a text describing it.
  *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are memory of the GPU the
  *     context was created on.  The library never allocates or frees memory the caller sees; it
- *     owns only a small image of the codebook tables and the layer reduction's sums inside the
- *     context (allocated by sop_create, scale tables on first use of a scale format).
+ *     owns only a small image of the codebook tables, the layer reduction's sums and a slab of
+ *     scale tables inside the context, all allocated by sop_create.
  *   - sop_pair_search() is asynchronous on the given HIP stream and does no host synchronisation.
  *     Inputs are read-only; requested outputs are completely overwritten.
  *   - Block index: block j of row m has index m*(K/g) + j.
@@ -158,6 +158,14 @@ sop_status sop_workspace_bytes(sop_ctx* ctx, int64_t M, int64_t K, int g, size_t
 sop_status sop_pair_search(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                            const float* c_dev, int g, sop_scale_fmt fmt, int layer_shift_k, sop_metric metric,
                            void* workspace_dev, size_t workspace_bytes, const sop_outputs* out, void* hip_stream);
+
+/* The table of (scale, reciprocal) per scale code that sop_pair_search() reads for (fmt, layer_shift_k),
+ * written ahead of time.  Optional: a call that finds the table missing writes it itself with one small
+ * kernel on its stream before its search kernel (the tables live in memory the context allocated at its
+ * creation, 160 of them, the least recently used one is replaced; nothing is allocated or copied from the host,
+ * and the host never waits).  Asynchronous on hip_stream; the search calls that use the table must be ordered
+ * after it (same stream, or an event). */
+sop_status sop_prepare_scale(sop_ctx* ctx, sop_scale_fmt fmt, int layer_shift_k, void* hip_stream);
 
 /* sop_pair_search() for callers that cannot allocate: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments (without the workspace), same kernels, same results bit
@@ -408,6 +416,60 @@ sop_status sop_pack_blocks(sop_ctx* ctx, int64_t M, int64_t K, int g, sop_scale_
                            const uint16_t* scale_b_dev, const uint8_t* codes_b_dev, int entries_b,
                            const void* sel_words_dev, int sel_word_bytes, int pair_q,
                            uint16_t* words_dev, uint8_t* payload_dev, int* n_bits_out, void* hip_stream);
+
+/* ---- the per-layer pair search as one call (Section "Per-Layer Pair Search": step 1 per-atom scoring, step 2
+ * block ranking and the top-p% pool, step 3 the second codebook fitted on the rest, step 4 the finishing
+ * reassignment; the search sweeps the atoms and the partition parameter p and keeps the best (L_a, p, L_b)). ----
+ * Candidates examined: every pair of atoms of the given alphabet; and, for every atom a and every p of the sweep,
+ * the pair (a, L_b) with L_b fitted on the blocks that a serves worst (the ranking score is blk_rank, the pool
+ * the blocks ranked strictly worse than the block of rank round(p * N_b / 100), halves up; the fit is
+ * sop_dd_fit() on sop_dd_histogram() of that pool, or sop_dd_fit_grid() when a grid is given; an empty pool
+ * leaves the start grid).  The winner has the largest layer ACos under step 4's reassignment; among equal
+ * values the first in this order wins: pairs of atoms in lexicographic order, then atom by atom, p by p.
+ * A fitted codebook that cannot serve as an atom (SOP_EATOM from the fit or from the table construction) drops
+ * its candidate (NaN in acos_fitted). */
+#define SOP_LAYER_MAX_P 7
+typedef struct {
+    int           n_p;                         /* values of p in the sweep, 0..7 (0: pairs of atoms only)            */
+    double        p_percent[SOP_LAYER_MAX_P];  /* non-decreasing, each within [0, 100]                               */
+    int           fit_entries, fit_iters;      /* entries of L_b (2..64), Lloyd rounds of the free fit                */
+    int           fit_bins;                    /* histogram bins (power of two, n_p * fit_bins <= 8192)               */
+    const float*  fit_init;                    /* HOST, fit_entries ascending values: start grid (NULL: the first atom) */
+    int           weighted_fit;                /* non-zero: channel-norm-weighted histogram (design axis (iii))       */
+    const double* fit_grid;                    /* HOST or NULL: ascending candidate values, L_b is selected among them */
+    int           n_fit_grid;
+    int           pack;                        /* non-zero: the winner is searched once more and packed               */
+} sop_layer_opts;
+typedef struct {
+    int    kind;                               /* 0: both codebooks are atoms of the alphabet; 1: L_b was fitted      */
+    int    a, b;                               /* atom indices (b = -1 when fitted)                                   */
+    int    j;                                  /* index of the winner's p in the sweep (fitted only)                  */
+    double p_percent;                          /* the winner's p (0 for kind 0)                                       */
+    double acos;                               /* its layer ACos                                                      */
+    int    n_entries_b;
+    float  table_b[SOP_MAX_ENTRIES];           /* the second codebook                                                 */
+    double acos_fixed[28];                     /* every pair of atoms, lexicographic; NaN beyond the alphabet's pairs */
+    double acos_atom[SOP_MAX_ATOMS];           /* every atom alone                                                    */
+    double acos_fitted[SOP_MAX_ATOMS][SOP_LAYER_MAX_P];   /* (a, p_j); NaN: not examined or dropped                   */
+    int    n_bits;                             /* bits per code of the packed payload (pack only)                     */
+} sop_layer_result;
+
+/* Bytes of DEVICE workspace sop_search_layer() needs (the ranking scores of every atom, A * N_b floats, make up
+ * most of it). */
+sop_status sop_search_layer_workspace(sop_ctx* ctx, int64_t M, int64_t K, int g, int n_atoms, const sop_layer_opts* opts, size_t* bytes);
+
+/* W_dev, dtype, M, K, ldw, c_dev, g, fmt, layer_shift_k, metric as in sop_pair_search(); atoms: HOST, n_atoms
+ * (1..8) codebooks; workspace_dev: DEVICE, 256-byte aligned, at least sop_search_layer_workspace() bytes;
+ * result: HOST; words_dev / payload_dev: DEVICE outputs of the packing as in sop_pack_blocks() (pack only: N_b
+ * uint16 and N_b * g*n/8 bytes with n = bits of the larger of the two codebooks; the scale word needs a metabit).
+ * The call queues its kernels on hip_stream and waits for the stream twice (the pool histograms are fitted on the
+ * host; the ACos values decide the winner); the packing is queued and not waited for.  It replaces the context's
+ * alphabet and pair list: afterwards the context has no alphabet set.  The first call on a context allocates
+ * pinned host staging (a few MB).  Calls on one context must not overlap. */
+sop_status sop_search_layer(sop_ctx* ctx, const void* W_dev, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw, const float* c_dev,
+                            int g, sop_scale_fmt fmt, int layer_shift_k, sop_metric metric, const sop_atom* atoms, int n_atoms,
+                            const sop_layer_opts* opts, void* workspace_dev, size_t workspace_bytes, sop_layer_result* result,
+                            uint16_t* words_dev, uint8_t* payload_dev, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -42,6 +42,23 @@ class _Atom(C.Structure):
     _fields_ = [("n_entries", C.c_int), ("values", C.POINTER(C.c_float))]
 
 
+LAYER_MAX_P = 7
+
+
+class _LayerOpts(C.Structure):
+    """sop_layer_opts"""
+    _fields_ = [("n_p", C.c_int), ("p_percent", C.c_double * LAYER_MAX_P), ("fit_entries", C.c_int), ("fit_iters", C.c_int),
+                ("fit_bins", C.c_int), ("fit_init", C.POINTER(C.c_float)), ("weighted_fit", C.c_int),
+                ("fit_grid", C.POINTER(C.c_double)), ("n_fit_grid", C.c_int), ("pack", C.c_int)]
+
+
+class _LayerResult(C.Structure):
+    """sop_layer_result"""
+    _fields_ = [("kind", C.c_int), ("a", C.c_int), ("b", C.c_int), ("j", C.c_int), ("p_percent", C.c_double), ("acos", C.c_double),
+                ("n_entries_b", C.c_int), ("table_b", C.c_float * MAX_ENTRIES), ("acos_fixed", C.c_double * 28),
+                ("acos_atom", C.c_double * MAX_ATOMS), ("acos_fitted", (C.c_double * LAYER_MAX_P) * MAX_ATOMS), ("n_bits", C.c_int)]
+
+
 class _Outputs(C.Structure):
     _fields_ = [("acos_pair", C.c_void_p), ("acos_atom", C.c_void_p), ("sel_words", C.c_void_p),
                 ("scale_code", C.c_void_p), ("codes", C.c_void_p), ("blk_cos", C.c_void_p), ("blk_err", C.c_void_p),
@@ -79,6 +96,11 @@ def lib():
                                       ScaleFmt, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(_Outputs), C.c_void_p]
         L.sop_pair_search_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
                                              ScaleFmt, C.c_int, C.c_int, C.POINTER(_Outputs), C.c_void_p]
+        L.sop_search_layer_workspace.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.POINTER(_LayerOpts), C.POINTER(C.c_size_t)]
+        L.sop_search_layer.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, ScaleFmt, C.c_int,
+                                       C.c_int, C.POINTER(_Atom), C.c_int, C.POINTER(_LayerOpts), C.c_void_p, C.c_size_t,
+                                       C.POINTER(_LayerResult), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sop_prepare_scale.argtypes = [C.c_void_p, ScaleFmt, C.c_int, C.c_void_p]
         L.sop_last_error.argtypes = [C.c_void_p]
         L.sop_last_error.restype = C.c_char_p
         L.sop_atom_nf.argtypes = [C.c_int, C.POINTER(C.c_float)]
@@ -400,6 +422,61 @@ class Context:
                                             C.c_void_p(st)), self._h)
         return tp[:, :self.n_pairs], ta, sels
 
+    def search_layer(self, W, c, g, fmt: ScaleFmt, atoms, p_grid=(), k: int = 0, metric: int = SEL_WSE, fit_entries: int = 16,
+                     fit_iters: int = 20, fit_bins: int = 1024, fit_init=None, weighted_fit: bool = True, fit_grid=None,
+                     pack: bool = False, stream=None):
+        """sop_search_layer on torch CUDA tensors.  Returns (result structure, words or None, payload or None); the
+        workspace is a torch tensor kept by the context and grown on demand."""
+        import torch
+        dt = BF16 if W.dtype == torch.bfloat16 else (F32 if W.dtype == torch.float32 else None)
+        if dt is None or not (W.is_cuda and c.is_cuda) or W.dim() != 2 or W.stride(1) != 1:
+            raise SopError(1, "W must be a 2-D float32 or bfloat16 CUDA tensor with contiguous rows, c a CUDA tensor")
+        M, K = W.shape
+        tabs = [np.ascontiguousarray(t, dtype=np.float32) for t in atoms]
+        arr = (_Atom * len(tabs))()
+        for i, t in enumerate(tabs):
+            arr[i].n_entries = t.size
+            arr[i].values = _fp(t)
+        o = _LayerOpts()
+        o.n_p = len(p_grid)
+        for i, p in enumerate(list(p_grid)[:LAYER_MAX_P]):
+            o.p_percent[i] = float(p)
+        o.fit_entries, o.fit_iters, o.fit_bins, o.weighted_fit, o.pack = fit_entries, fit_iters, fit_bins, int(bool(weighted_fit)), int(bool(pack))
+        keep = []
+        if fit_init is not None:
+            ini = np.ascontiguousarray(fit_init, dtype=np.float32); keep.append(ini)
+            o.fit_init = _fp(ini)
+        if fit_grid is not None:
+            gr = np.ascontiguousarray(fit_grid, dtype=np.float64); keep.append(gr)
+            o.fit_grid = _fp(gr, C.c_double); o.n_fit_grid = gr.size
+        need = C.c_size_t()
+        _check(lib().sop_search_layer_workspace(self._h, M, K, g, len(tabs), C.byref(o), C.byref(need)), self._h)
+        if self._ws is None or self._ws.numel() < need.value:
+            self._ws = torch.empty(need.value, dtype=torch.uint8, device=W.device)
+        words = payload = None
+        if pack:
+            n = 1
+            while (1 << n) < max(max(t.size for t in tabs), fit_entries if len(p_grid) else 0):
+                n += 1                                          # room for the widest codebook that can win
+            words = torch.empty(M * K // g, dtype=torch.int16, device=W.device)
+            payload = torch.empty((M * K // g, g * n // 8), dtype=torch.uint8, device=W.device)
+        res = _LayerResult()
+        st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
+        _check(lib().sop_search_layer(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g, fmt, k, metric,
+                                      arr, len(tabs), C.byref(o), C.c_void_p(self._ws.data_ptr()), self._ws.numel(), C.byref(res),
+                                      None if words is None else C.c_void_p(words.data_ptr()),
+                                      None if payload is None else C.c_void_p(payload.data_ptr()), C.c_void_p(st)), self._h)
+        self.n_atoms = 0
+        if pack and payload.shape[1] != g * res.n_bits // 8:
+            payload = payload.reshape(-1)[:M * K // g * (g * res.n_bits // 8)].reshape(M * K // g, g * res.n_bits // 8)
+        return res, words, payload
+
+    def prepare_scale(self, fmt: ScaleFmt, k: int = 0, stream=None):
+        """sop_prepare_scale: write the scale table of (fmt, k) ahead of the searches that use it."""
+        import torch
+        st = torch.cuda.current_stream(self.device).cuda_stream if stream is None else stream
+        _check(lib().sop_prepare_scale(self._h, fmt, k, C.c_void_p(st)), self._h)
+
     def set_scale_rule(self, rule: int):
         """SCALE_ABSMAX (default) or SCALE_ARGMAX for later pair_search calls."""
         _check(lib().sop_set_scale_rule(self._h, rule), self._h)
@@ -534,9 +611,6 @@ class Context:
         M, K = W.shape
         if out is None:
             out = self.alloc_outputs(M, K, g, emit=emit)
-        need = self.workspace_bytes(M, K, g)
-        if need and (self._ws is None or self._ws.numel() < need):
-            self._ws = torch.empty(need, dtype=torch.uint8, device=W.device)
         st = torch.cuda.current_stream(W.device).cuda_stream if stream is None else stream
 
         def ptr(t):
@@ -549,7 +623,6 @@ class Context:
                                                 fmt, k, metric, C.byref(o), C.c_void_p(st)), self._h)
             return out
         _check(lib().sop_pair_search(self._h, C.c_void_p(W.data_ptr()), dt, M, K, W.stride(0), C.c_void_p(c.data_ptr()), g,
-                                     fmt, k, metric, None if self._ws is None else C.c_void_p(self._ws.data_ptr()),
-                                     0 if self._ws is None else self._ws.numel(), C.byref(o),
+                                     fmt, k, metric, None, 0, C.byref(o),
                                      C.c_void_p(st)), self._h)
         return out

@@ -32,6 +32,7 @@ extern "C" hipError_t sopk_pack_launch(const PackParams* p, void* stream);
 namespace {
 
 struct ScaleTab { float2* dev = nullptr; int n = 0; };
+struct ScaleSlot { std::tuple<int, int, int, int, int> key; bool used = false; unsigned long long age = 0; };
 
 uint32_t f2u(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 float u2f(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
@@ -43,6 +44,7 @@ float funord(int64_t k) { return k < 0 ? u2f(0x80000000u | (uint32_t)(-k)) : u2f
 
 static constexpr int kLanes = 2;          // streams of its own that sop_pair_search_layers deals the layers out to
 static constexpr int kMaxLayers = 1024;  // layers of one launch of the model-wide kernel (more are dealt with in several launches)
+static constexpr int kStabSlots = 160;   // (scale, reciprocal) tables kept on the device: more than the layer shifts one call can name (129)
 static constexpr size_t kSumsWords = SOP_K_REPL * SOP_K_NCOL + SOP_K_REPL + 1;   // one set of layer sums and tickets, in 64-bit words
 
 // ---- scratch of the entry point that allocates nothing (sop_pair_search_static) ----
@@ -110,7 +112,12 @@ struct sop_ctx {
     float bin_lo[SOP_K_MAXA] = {0}, bin_hi[SOP_K_MAXA] = {0};
     int nent[SOP_K_MAXA] = {0};
     int n_bins = 0;
-    BinRec* d_bins = nullptr;             // [MAXBINS] capacity
+    BinRec* d_bins = nullptr;             // [MAXBINS] capacity: the context's own image of the element-search table
+    BinRec* d_bins_cur = nullptr;         // the image the searches read (d_bins, or an image inside a caller's workspace during sop_search_layer)
+    BinRec* h_bins = nullptr;             // pinned staging for table images of sop_search_layer (allocated at its first call)
+    char* h_res = nullptr;                // pinned staging for its results
+    hipEvent_t stage_done = nullptr;      // the last copy out of h_bins has run
+    bool stage_pending = false;
     unsigned long long* d_ls = nullptr;   // [3*SOP_K_LS_MAXWG] workgroup partials, one spare word, 17 ticket counters (u32) from word 3*MAXWG+1, then SOP_K_LS_MAXREP copies of the layer maxima (2 x u32 each, 128 bytes apart) from word 3*MAXWG+16; zero between calls
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
@@ -120,7 +127,9 @@ struct sop_ctx {
     unsigned long long* d_sums = nullptr; // two sets of [SOP_K_REPL][SOP_K_NCOL] layer sums followed by their ticket counters; zero between calls
     hipStream_t lane_stream[kLanes] = {};   // sop_pair_search_layers deals the layers out to streams of its own
     hipEvent_t lane_event[kLanes + 1] = {};  // one per stream (join) and one for the fork
-    std::map<std::tuple<int, int, int, int, int>, ScaleTab> stabs;   // (x, y, bias, max_code, k) -> device table
+    float2* d_stab = nullptr;             // [kStabSlots][SOP_K_MAXTABCODES] (scale * 2^-k, reciprocal) tables, written by a kernel on first use
+    ScaleSlot stab_slot[kStabSlots];      // what each slot holds: (x, y, bias, max_code, k); the least recently used one is replaced
+    unsigned long long stab_clock = 0;
     int scale_rule = 0;                   // 0: absmax, 1: argmax
     unsigned char* static_scratch = nullptr;   // this device's copy of sop_static_scratch (looked up by sop_create)
     int occ_blocks[864];                  // resident workgroups per CU of each kernel variant (0 = unknown)
@@ -195,9 +204,14 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(rank counts)");
     }
+    if ((e = hipMalloc((void**)&c->d_stab, sizeof(float2) * (size_t)kStabSlots * SOP_K_MAXTABCODES)) != hipSuccess) {
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel);
+        delete c;
+        return hipfail(nullptr, e, "hipMalloc(scale tables)");
+    }
     if ((e = hipMalloc((void**)&c->d_selm, sizeof(unsigned int) * 2 * SOP_K_SELM_WORDS)) != hipSuccess ||
         (e = hipMemset(c->d_selm, 0, sizeof(unsigned int) * 2 * SOP_K_SELM_WORDS)) != hipSuccess) {
-        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); if (c->d_selm) (void)hipFree(c->d_selm);
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); (void)hipFree(c->d_stab); if (c->d_selm) (void)hipFree(c->d_selm);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(rank counts of the sweep)");
     }
@@ -208,7 +222,7 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         (e = hipHostMalloc((void**)&c->h_ldesc[1], sizeof(LayerDesc) * kMaxLayers, hipHostMallocDefault)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&c->ldesc_copied[0], hipEventDisableTiming)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&c->ldesc_copied[1], hipEventDisableTiming)) != hipSuccess) {
-        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); (void)hipFree(c->d_selm);
+        (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); (void)hipFree(c->d_selm); (void)hipFree(c->d_stab);
         if (c->d_ldesc) (void)hipFree(c->d_ldesc);
         if (c->d_msums) (void)hipFree(c->d_msums);
         for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
@@ -238,9 +252,12 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_ldesc) (void)hipFree(c->d_ldesc);
         if (c->d_msums) (void)hipFree(c->d_msums);
         for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
+        if (c->h_bins) (void)hipHostFree(c->h_bins);
+        if (c->h_res) (void)hipHostFree(c->h_res);
+        if (c->stage_done) (void)hipEventDestroy(c->stage_done);
         for (hipStream_t s : c->lane_stream) if (s) (void)hipStreamDestroy(s);
         for (hipEvent_t ev : c->lane_event) if (ev) (void)hipEventDestroy(ev);
-        for (auto& kv : c->stabs) if (kv.second.dev) (void)hipFree(kv.second.dev);
+        if (c->d_stab) (void)hipFree(c->d_stab);
     }
     delete c;
     return SOP_OK;
@@ -424,17 +441,25 @@ static sop_status plan_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms, 
     return SOP_OK;
 }
 
-extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms)
+// Plan the alphabet and make it the context's current one.  d_img == nullptr: the context's own image, copied
+// synchronously.  Otherwise the image goes through the pinned buffer h_stage to d_img with a copy on `st`
+// (the host does not wait), and the searches launched from now on read d_img.
+static sop_status install_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms, BinRec* d_img, BinRec* h_stage, hipStream_t st)
 {
-    if (!c) return SOP_EINVAL;
     AlphabetPlan pl;
     if (sop_status s = plan_alphabet(c, atoms, n_atoms, pl)) return s;
     {
         DeviceGuard guard(c->device);
         hipError_t e = guard.err;
-        if (e == hipSuccess) e = hipMemcpy(c->d_bins, pl.img.data(), pl.img.size() * sizeof(BinRec), hipMemcpyHostToDevice);
+        if (e == hipSuccess) {
+            if (d_img) {
+                std::memcpy(h_stage, pl.img.data(), pl.img.size() * sizeof(BinRec));
+                e = hipMemcpyAsync(d_img, h_stage, pl.img.size() * sizeof(BinRec), hipMemcpyHostToDevice, st);
+            } else e = hipMemcpy(c->d_bins, pl.img.data(), pl.img.size() * sizeof(BinRec), hipMemcpyHostToDevice);
+        }
         if (e != hipSuccess) return hipfail(c, e, "upload of the table image");
     }
+    c->d_bins_cur = d_img ? d_img : c->d_bins;
     c->tables.swap(pl.tabs);
     c->n_atoms = n_atoms;
     c->n_bins = pl.n_bins;
@@ -444,9 +469,14 @@ extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_
         c->tpos[i] = L.back(); c->tneg[i] = -L.front(); c->nent[i] = (int)L.size();
         c->bin_sc[i] = pl.sc[i]; c->bin_off[i] = pl.off[i]; c->bin_lo[i] = pl.lo[i]; c->bin_hi[i] = pl.hi[i];
     }
-    std::memset(c->occ_blocks, 0, sizeof(c->occ_blocks));
-    default_pairs(c);
+    default_pairs(c);                      // (the occupancy cache is keyed by variant and LDS size: it stays valid)
     return SOP_OK;
+}
+
+extern "C" sop_status sop_set_alphabet(sop_ctx* c, const sop_atom* atoms, int n_atoms)
+{
+    if (!c) return SOP_EINVAL;
+    return install_alphabet(c, atoms, n_atoms, nullptr, nullptr, nullptr);
 }
 
 extern "C" sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int* n_bins, int64_t* n_checked)
@@ -537,28 +567,43 @@ extern "C" sop_status sop_workspace_bytes(sop_ctx* c, int64_t M, int64_t K, int 
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// (scale * 2^-k, reciprocal) of every code of a scale word; built and uploaded on first use
-static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, int k, ScaleTab* out)
+// (scale * 2^-k, reciprocal) of every code of a scale word: value(q) * 2^-k (exact) and its IEEE reciprocal.
+// The tables live in a slab the context allocated at its creation; a table that is not there yet is written
+// by a small kernel on the caller's stream ahead of the kernel that reads it (no allocation, no copy from the
+// host, no synchronisation), into the slot that was used longest ago.
+__global__ void scale_table_kernel(float2* tab, int n_codes, int y, int bias, int k)
+{
+    const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (i < n_codes) {
+        const int e = i >> y, f = i & ((1 << y) - 1);
+        const float s = e == 0 ? ldexpf((float)f, 1 - bias - y - k) : ldexpf((float)((1 << y) + f), e - bias - y - k);
+        tab[i] = make_float2(s, s > 0.0f ? 1.0f / s : 0.0f);
+    }
+}
+
+static sop_status scale_table(sop_ctx* c, int x, int y, int bias, int max_code, int k, void* stream, ScaleTab* out)
 {
     const auto key = std::make_tuple(x, y, bias, max_code, k);
-    auto it = c->stabs.find(key);
-    if (it != c->stabs.end()) { *out = it->second; return SOP_OK; }
-    const int n = max_code + 1;
-    std::vector<float2> img(n);
-    for (int q = 0; q < n; ++q) {
-        const int e = q >> y, f = q & ((1 << y) - 1);
-        const double v = e == 0 ? std::ldexp((double)f, 1 - bias - y) : std::ldexp((double)((1 << y) + f), e - bias - y);
-        const float s = (float)std::ldexp(v, -k);
-        img[q].x = s;
-        img[q].y = s > 0.0f ? 1.0f / s : 0.0f;
+    int slot = -1, oldest = -1;
+    for (int i = 0; i < kStabSlots && slot < 0; ++i)
+        if (c->stab_slot[i].used && c->stab_slot[i].key == key) slot = i;
+    for (int i = 0; i < kStabSlots && slot < 0; ++i) {            // a free slot, else the one used longest ago
+        if (!c->stab_slot[i].used) { oldest = i; break; }
+        if (oldest < 0 || c->stab_slot[i].age < c->stab_slot[oldest].age) oldest = i;
     }
-    ScaleTab t;
-    t.n = n;
-    hipError_t e = hipMalloc((void**)&t.dev, sizeof(float2) * n);
-    if (e == hipSuccess) e = hipMemcpy(t.dev, img.data(), sizeof(float2) * n, hipMemcpyHostToDevice);
-    if (e != hipSuccess) return hipfail(c, e, "upload of the scale table");
-    c->stabs[key] = t;
-    *out = t;
+    const int n = max_code + 1;
+    if (slot < 0) {
+        slot = oldest;
+        float2* dst = c->d_stab + (size_t)slot * SOP_K_MAXTABCODES;
+        scale_table_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(dst, n, y, bias, k);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hipfail(c, e, "kernel launch (scale table)");
+        c->stab_slot[slot].key = key;
+        c->stab_slot[slot].used = true;
+    }
+    c->stab_slot[slot].age = ++c->stab_clock;
+    out->dev = c->d_stab + (size_t)slot * SOP_K_MAXTABCODES;
+    out->n = n;
     return SOP_OK;
 }
 
@@ -610,7 +655,7 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     KParams p;
     std::memset(&p, 0, sizeof(p));
     p.W = W; p.c = cn;
-    p.bins = c->d_bins;
+    p.bins = c->d_bins_cur;
     p.M = M; p.K = K; p.ldw = ldw;
     p.Bk = K / g; p.Nb = M * p.Bk;
     p.strips = (K / epl + 63) / 64;
@@ -665,7 +710,7 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
         p.n_tab_codes = max_code + 1;
     } else if (max_code < SOP_K_MAXTABCODES) {
         ScaleTab t;
-        if (sop_status s = scale_table(c, x, y, bias, max_code, k, &t)) return s;
+        if (sop_status s = scale_table(c, x, y, bias, max_code, k, stream, &t)) return s;
         p.stab = t.dev;
         p.n_tab_codes = t.n;
     }
@@ -713,6 +758,24 @@ extern "C" sop_status sop_pair_search(sop_ctx* c, const void* W, sop_dtype dtype
                                       void* ws, size_t ws_bytes, const sop_outputs* out, void* stream)
 {
     return pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, ws, ws_bytes, out, stream, true);
+}
+
+extern "C" sop_status sop_prepare_scale(sop_ctx* c, sop_scale_fmt fmt, int k, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    const int x = fmt.exp_bits, y = fmt.man_bits, w = fmt.sign_bits;
+    if ((w != 0 && w != 1) || x < 1 || x > 8 || y < 0 || y > 10 || x + y > 15) return fail(c, SOP_EFMT, "scale format: need w in {0,1}, 1<=x<=8, 0<=y<=10, x+y<=15");
+    const int bias = fmt.bias < 0 ? (1 << (x - 1)) - 1 : fmt.bias;
+    const int max_code = fmt.max_code < 0 ? (1 << (x + y)) - 1 : fmt.max_code;
+    if (max_code < 1 || max_code >= (1 << (x + y))) return fail(c, SOP_EFMT, "scale format: max_code out of range");
+    if (k < -64 || k > 64 || bias < 0 || bias > 127) return fail(c, SOP_EFMT, "layer shift k must be within [-64, 64], bias within [0, 127]");
+    if (1 - bias - y - k < -126 || 1 - bias - k > 126 || std::max(max_code >> y, 1) - bias - k > 125)
+        return fail(c, SOP_EFMT, "scale format with this layer shift leaves binary32's normal range (choose bias / max_code / k accordingly)");
+    if (max_code >= SOP_K_MAXTABCODES) return SOP_OK;            // such words are decoded arithmetically: nothing to prepare
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    ScaleTab t;
+    return scale_table(c, x, y, bias, max_code, k, stream, &t);
 }
 
 extern "C" sop_status sop_pair_search_static(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
@@ -1469,5 +1532,242 @@ extern "C" sop_status sop_pack_blocks(sop_ctx* c, int64_t M, int64_t K, int g, s
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = sopk_pack_launch(&p, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
+    return SOP_OK;
+}
+
+// ------------------------------------------------------------------ the per-layer procedure (steps 1 to 4 and the sweep over p)
+namespace {
+constexpr size_t kImgBytes = sizeof(BinRec) * SOP_K_MAXBINS;
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+struct LayerWs {
+    size_t rank, level, hist, tau, na, acos, bins, sc, codes, sel, total;
+    int n_img;
+};
+// acos region, in doubles: [0,28) fixed pairs, [28,36) fixed atoms, then per atom a: 8 pairs (a, L_b(p_j))
+constexpr int kAcosFit = SOP_K_MAXP + SOP_K_MAXA;
+LayerWs layer_ws(int64_t M, int64_t K, int g, int A, int n_p, int bins, int pack)
+{
+    const size_t Nb = (size_t)(M * (K / g));
+    LayerWs w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
+    w.rank = take((size_t)A * Nb * sizeof(float));
+    w.level = take(Nb);
+    w.hist = take((size_t)A * std::max(n_p, 1) * bins * sizeof(long long));
+    w.tau = take(SOP_K_SEL_MAXLEV * sizeof(float));
+    w.na = take(SOP_K_SEL_MAXLEV * sizeof(long long));
+    w.acos = take((size_t)(kAcosFit + SOP_K_MAXA * 8) * sizeof(double));
+    w.n_img = A + 3;                                   // fixed alphabet, one per atom's sweep, one spare, the winner
+    w.bins = take((size_t)w.n_img * kImgBytes);
+    w.sc = take(pack ? 2 * Nb * sizeof(uint16_t) : 0);
+    w.codes = take(pack ? 2 * (size_t)(M * K) : 0);
+    w.sel = take(pack ? Nb * sizeof(uint16_t) : 0);
+    w.total = off;
+    return w;
+}
+sop_status layer_opts_check(sop_ctx* c, int n_atoms, const sop_layer_opts* o)
+{
+    if (!o) return fail(c, SOP_EINVAL, "sop_search_layer: opts is NULL");
+    if (n_atoms < 1 || n_atoms > SOP_K_MAXA) return fail(c, SOP_EATOM, "sop_search_layer: 1..8 atoms");
+    if (o->n_p < 0 || o->n_p > SOP_LAYER_MAX_P) return fail(c, SOP_EINVAL, "sop_search_layer: at most 7 values of p (the atom and its fitted codebooks form one alphabet of 8)");
+    for (int j = 0; j < o->n_p; ++j) {
+        if (!(o->p_percent[j] >= 0.0 && o->p_percent[j] <= 100.0)) return fail(c, SOP_EINVAL, "sop_search_layer: p must lie in [0, 100]");
+        if (j && o->p_percent[j] < o->p_percent[j - 1]) return fail(c, SOP_EINVAL, "sop_search_layer: the values of p must not decrease");
+    }
+    if (o->n_p > 0) {
+        if (o->fit_entries < 2 || o->fit_entries > SOP_MAX_ENTRIES || o->fit_iters < 0) return fail(c, SOP_EINVAL, "sop_search_layer: fit_entries within 2..64, fit_iters >= 0");
+        if (!dd_bins_ok(o->fit_bins) || (long long)o->fit_bins * o->n_p > SOP_K_DD_MAXBINS) return fail(c, SOP_EINVAL, "sop_search_layer: fit_bins a power of two within 64..8192 with n_p * fit_bins <= 8192");
+        if (o->fit_grid && (o->n_fit_grid < o->fit_entries || o->n_fit_grid > SOP_DD_MAX_CANDIDATES)) return fail(c, SOP_EINVAL, "sop_search_layer: the grid needs fit_entries .. 2047 candidates");
+    }
+    return SOP_OK;
+}
+}  // namespace
+
+extern "C" sop_status sop_search_layer_workspace(sop_ctx* c, int64_t M, int64_t K, int g, int n_atoms, const sop_layer_opts* o, size_t* bytes)
+{
+    if (!c) return SOP_EINVAL;
+    if (!bytes) return fail(c, SOP_EINVAL, "sop_search_layer_workspace: bytes is NULL");
+    if (sop_status s = shape_check(c, M, K, g)) return s;
+    if (sop_status s = layer_opts_check(c, n_atoms, o)) return s;
+    *bytes = layer_ws(M, K, g, n_atoms, o->n_p, o->n_p ? o->fit_bins : 64, o->pack).total;
+    return SOP_OK;
+}
+
+extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw, const float* cn, int g,
+                                       sop_scale_fmt fmt, int k, sop_metric metric, const sop_atom* atoms, int n_atoms,
+                                       const sop_layer_opts* o, void* ws, size_t ws_bytes, sop_layer_result* res,
+                                       uint16_t* words, uint8_t* payload, void* stream)
+{
+    if (!c) return SOP_EINVAL;
+    if (!res || !atoms) return fail(c, SOP_EINVAL, "sop_search_layer: atoms and result must not be NULL");
+    if (sop_status s = shape_check(c, M, K, g)) return s;
+    if (sop_status s = layer_opts_check(c, n_atoms, o)) return s;
+    const int A = n_atoms, n_p = o->n_p, bins = n_p ? o->fit_bins : 64;
+    if (A < 2 && n_p == 0) return fail(c, SOP_EINVAL, "sop_search_layer: one atom and no sweep leave no pair to examine");
+    if (o->pack && (!words || !payload)) return fail(c, SOP_EINVAL, "sop_search_layer: packing needs words_dev and payload_dev");
+    const LayerWs L = layer_ws(M, K, g, A, n_p, bins, o->pack);
+    if (!ws || ws_bytes < L.total) return fail(c, SOP_ENOMEM, "sop_search_layer: workspace too small (see sop_search_layer_workspace)");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(c, SOP_EINVAL, "sop_search_layer: workspace must be 256-byte aligned");
+    for (int a = 0; a < A; ++a)
+        if (!atoms[a].values || atoms[a].n_entries < 2 || atoms[a].n_entries > SOP_MAX_ENTRIES) return fail(c, SOP_EATOM, "sop_search_layer: an atom needs 2..64 entries");
+    std::vector<float> init;
+    if (n_p) {
+        if (o->fit_init) init.assign(o->fit_init, o->fit_init + o->fit_entries);
+        else {
+            if (atoms[0].n_entries != o->fit_entries) return fail(c, SOP_EINVAL, "sop_search_layer: without fit_init the first atom is the start grid and must have fit_entries values");
+            init.assign(atoms[0].values, atoms[0].values + o->fit_entries);
+        }
+    }
+    const int64_t Nb = M * (K / g);
+    char* base = static_cast<char*>(ws);
+    hipStream_t st = (hipStream_t)stream;
+    DeviceGuard guard(c->device);
+    if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
+    hipError_t e = hipSuccess;
+    // pinned staging, allocated once per context
+    const size_t res_bytes = (size_t)SOP_K_MAXA * SOP_K_DD_MAXBINS * sizeof(long long) + (size_t)(kAcosFit + SOP_K_MAXA * 8) * sizeof(double);
+    if (!c->h_bins) {
+        if ((e = hipHostMalloc((void**)&c->h_bins, (size_t)(SOP_K_MAXA + 3) * kImgBytes, hipHostMallocDefault)) != hipSuccess ||
+            (e = hipHostMalloc((void**)&c->h_res, res_bytes, hipHostMallocDefault)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&c->stage_done, hipEventDisableTiming)) != hipSuccess)
+            return hipfail(c, e, "pinned staging of sop_search_layer");
+    }
+    if (c->stage_pending) {                            // an earlier call's copies out of the staging buffers have run?
+        if ((e = hipEventSynchronize(c->stage_done)) != hipSuccess) return hipfail(c, e, "hipEventSynchronize(staging)");
+        c->stage_pending = false;
+    }
+    // whatever happens below, the context ends up reading its own image again, with no alphabet set
+    struct Restore { sop_ctx* c; ~Restore() { c->d_bins_cur = c->d_bins; c->n_atoms = 0; c->n_pairs = 0; } } restore{c};
+    auto img = [&](int i) { return reinterpret_cast<BinRec*>(base + L.bins + (size_t)i * kImgBytes); };
+    auto himg = [&](int i) { return reinterpret_cast<BinRec*>(reinterpret_cast<char*>(c->h_bins) + (size_t)i * kImgBytes); };
+    double* d_acos = reinterpret_cast<double*>(base + L.acos);
+    float* d_rank = reinterpret_cast<float*>(base + L.rank);
+
+    // ---- step 1 for every atom, and every pair of fixed atoms: one search with the ranking scores out ----
+    if (sop_status s = install_alphabet(c, atoms, A, img(0), himg(0), st)) return s;
+    {
+        sop_outputs out;
+        std::memset(&out, 0, sizeof(out));
+        out.acos_pair = d_acos; out.acos_atom = d_acos + SOP_K_MAXP;
+        out.blk_rank = n_p ? d_rank : nullptr;
+        if (sop_status s = pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, nullptr, 0, &out, stream, true)) return s;
+    }
+    const int P = c->n_pairs;
+    // ---- steps 2 and 3 for every atom and every p: one ranking with n_p thresholds, one pass over the weights ----
+    int64_t tops[SOP_K_SEL_MAXLEV] = {0};
+    for (int j = 0; j < n_p; ++j) {
+        const double v = std::floor(o->p_percent[j] * (double)Nb / 100.0 + 0.5);      // nearest count, halves up
+        tops[j] = v < 0.0 ? 0 : (v > (double)Nb ? Nb : (int64_t)v);
+    }
+    long long* d_hist = reinterpret_cast<long long*>(base + L.hist);
+    for (int a = 0; a < A && n_p; ++a) {
+        if (sop_status s = sop_partition_levels(c, d_rank + (size_t)a * Nb, Nb, tops, n_p, 1, reinterpret_cast<uint8_t*>(base + L.level),
+                                                reinterpret_cast<float*>(base + L.tau), reinterpret_cast<int64_t*>(base + L.na), stream)) return s;
+        if (sop_status s = dd_histogram_impl(c, W, dtype, M, K, ldw, o->weighted_fit ? cn : nullptr, g, bins, 1, reinterpret_cast<uint8_t*>(base + L.level), n_p,
+                                             reinterpret_cast<int64_t*>(d_hist + (size_t)a * n_p * bins), stream)) return s;
+    }
+    long long* h_hist = reinterpret_cast<long long*>(c->h_res);
+    double* h_acos = reinterpret_cast<double*>(c->h_res + (size_t)SOP_K_MAXA * SOP_K_DD_MAXBINS * sizeof(long long));
+    if (n_p) {
+        if ((e = hipMemcpyAsync(h_hist, d_hist, (size_t)A * n_p * bins * sizeof(long long), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+            (e = hipStreamSynchronize(st)) != hipSuccess) return hipfail(c, e, "copy of the pool histograms");
+    }
+    // ---- the fits (host), and step 4 for one atom's whole sweep per search: alphabet (a, L_b(p_0), L_b(p_1), ...) ----
+    std::vector<std::vector<float>> fitted((size_t)A * std::max(n_p, 1));
+    std::vector<int> slot_of((size_t)A * std::max(n_p, 1), -1);       // position of (a, j) in the acos region, -1: candidate dropped
+    int spare_uses = 0;
+    auto score = [&](int a, const std::vector<int>& js, int image, int out_base) -> sop_status {
+        std::vector<sop_atom> al(1 + js.size());
+        al[0] = atoms[a];
+        for (size_t i = 0; i < js.size(); ++i) { al[1 + i].n_entries = o->fit_entries; al[1 + i].values = fitted[(size_t)a * n_p + js[i]].data(); }
+        if (sop_status s = install_alphabet(c, al.data(), (int)al.size(), img(image), himg(image), st)) return s;
+        int pr[2 * SOP_K_MAXA];
+        for (size_t i = 0; i < js.size(); ++i) { pr[2 * i] = 0; pr[2 * i + 1] = 1 + (int)i; }
+        if (sop_status s = sop_set_pairs(c, pr, (int)js.size())) return s;
+        sop_outputs out;
+        std::memset(&out, 0, sizeof(out));
+        out.acos_pair = d_acos + out_base;
+        if (sop_status s = pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, nullptr, 0, &out, stream, true)) return s;
+        for (size_t i = 0; i < js.size(); ++i) slot_of[(size_t)a * n_p + js[i]] = out_base + (int)i;
+        return SOP_OK;
+    };
+    for (int a = 0; a < A && n_p; ++a) {
+        std::vector<int> js;
+        for (int j = 0; j < n_p; ++j) {
+            const long long* h = h_hist + ((size_t)a * n_p + j) * bins;
+            bool any = false;
+            for (int b = 0; b < bins && !any; ++b) any = h[b] != 0;
+            std::vector<float>& Lb = fitted[(size_t)a * n_p + j];
+            Lb.assign(o->fit_entries, 0.0f);
+            sop_status fs = SOP_OK;
+            if (!any) Lb = init;                                   // an empty pool: the start grid stands in
+            else if (o->fit_grid) {
+                std::vector<int> chosen(o->fit_entries);
+                fs = sop_dd_fit_grid(reinterpret_cast<const int64_t*>(h), bins, o->fit_grid, o->n_fit_grid, o->fit_entries, chosen.data(), nullptr);
+                if (fs == SOP_OK) for (int t = 0; t < o->fit_entries; ++t) Lb[t] = (float)o->fit_grid[chosen[t]];
+            } else fs = sop_dd_fit(reinterpret_cast<const int64_t*>(h), bins, o->fit_entries, o->fit_iters, init.data(), Lb.data());
+            if (fs == SOP_OK) js.push_back(j);
+            else if (fs != SOP_EATOM) return fail(c, fs, std::string("sop_search_layer: fit: ") + g_create_err);
+        }
+        if (js.empty()) continue;
+        sop_status s = score(a, js, 1 + a, kAcosFit + 8 * a);
+        if (s == SOP_EATOM && js.size() > 1) {
+            // some fitted codebook cannot be searched next to the others (entries too closely spaced for the
+            // element-search table): the candidates are scored one by one, through one spare image, and
+            // those that fail alone are dropped
+            for (size_t i = 0; i < js.size(); ++i) {
+                if (spare_uses++ && (e = hipStreamSynchronize(st)) != hipSuccess) return hipfail(c, e, "hipStreamSynchronize");
+                s = score(a, std::vector<int>(1, js[i]), A + 1, kAcosFit + 8 * a + (int)i);
+                if (s != SOP_OK && s != SOP_EATOM) return s;
+            }
+        } else if (s != SOP_OK && s != SOP_EATOM) return s;
+    }
+    if ((e = hipMemcpyAsync(h_acos, d_acos, (size_t)(kAcosFit + 8 * A) * sizeof(double), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+        (e = hipStreamSynchronize(st)) != hipSuccess) return hipfail(c, e, "copy of the ACos values");
+    // ---- the best (L_a, p, L_b): the largest layer ACos, the first one among equals (fixed pairs in their
+    //      order, then atom by atom, p by p) ----
+    std::memset(res, 0, sizeof(*res));
+    res->a = -1; res->b = -1;
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    for (int q = 0; q < SOP_K_MAXP; ++q) res->acos_fixed[q] = q < P ? h_acos[q] : nan;
+    for (int a = 0; a < SOP_K_MAXA; ++a) {
+        res->acos_atom[a] = a < A ? h_acos[SOP_K_MAXP + a] : nan;
+        for (int j = 0; j < SOP_LAYER_MAX_P; ++j) {
+            const int sl = (a < A && j < n_p) ? slot_of[(size_t)a * n_p + j] : -1;
+            res->acos_fitted[a][j] = sl >= 0 ? h_acos[sl] : nan;
+        }
+    }
+    bool have = false;
+    {
+        int q = 0;
+        for (int a = 0; a < A; ++a)
+            for (int b = a + 1; b < A; ++b, ++q)
+                if (!have || res->acos_fixed[q] > res->acos) { have = true; res->kind = 0; res->a = a; res->b = b; res->p_percent = 0.0; res->acos = res->acos_fixed[q]; }
+    }
+    for (int a = 0; a < A; ++a)
+        for (int j = 0; j < n_p; ++j) {
+            const double v = res->acos_fitted[a][j];
+            if (v == v && (!have || v > res->acos)) { have = true; res->kind = 1; res->a = a; res->b = -1; res->j = j; res->p_percent = o->p_percent[j]; res->acos = v; }
+        }
+    if (!have) return fail(c, SOP_EATOM, "sop_search_layer: no candidate could be scored");
+    const float* tb = res->kind == 0 ? atoms[res->b].values : fitted[(size_t)res->a * n_p + res->j].data();
+    res->n_entries_b = res->kind == 0 ? atoms[res->b].n_entries : o->fit_entries;
+    std::memcpy(res->table_b, tb, sizeof(float) * res->n_entries_b);
+    // ---- materialisation of the winner ----
+    if (o->pack) {
+        sop_atom two[2] = {atoms[res->a], {res->n_entries_b, res->table_b}};
+        if (sop_status s = install_alphabet(c, two, 2, img(A + 2), himg(A + 2), st)) return s;
+        uint16_t* sc = reinterpret_cast<uint16_t*>(base + L.sc);
+        uint8_t* codes = reinterpret_cast<uint8_t*>(base + L.codes);
+        const size_t plane_a = two[0].n_entries <= 16 ? (size_t)(M * K / 2) : (size_t)(M * K);
+        sop_outputs out;
+        std::memset(&out, 0, sizeof(out));
+        out.acos_pair = d_acos; out.scale_code = sc; out.codes = codes; out.sel_words = base + L.sel;
+        if (sop_status s = pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, nullptr, 0, &out, stream, true)) return s;
+        if (sop_status s = sop_pack_blocks(c, M, K, g, fmt, sc, codes, two[0].n_entries, sc + Nb, codes + plane_a, two[1].n_entries,
+                                           base + L.sel, 2, 0, words, payload, &res->n_bits, stream)) return s;
+    }
+    if ((e = hipEventRecord(c->stage_done, st)) != hipSuccess) return hipfail(c, e, "hipEventRecord");
+    c->stage_pending = true;
     return SOP_OK;
 }
