@@ -122,8 +122,9 @@ struct sop_ctx {
     unsigned long long* d_ddacc = nullptr; // [SOP_K_DD_MAXBINS] running DD histogram + (one word further) its finished-workgroup counter; zero between calls
     unsigned int* d_sel = nullptr;        // [2][3][SOP_K_SEL_BINS] two sets of digit counts of the block ranking: a call counts into set sel_set and clears the other
     int sel_set = 0;
-    unsigned int* d_selm = nullptr;       // [2][SOP_K_SELM_WORDS] two sets of digit counts of the ranking with several thresholds
+    unsigned int* d_selm = nullptr;       // [2][SOP_K_MAXA][SOP_K_SELM_WORDS] two sets of digit counts of the ranking with several thresholds (one per score plane of a launch)
     int selm_set = 0;
+    SelMState* d_selstate = nullptr;      // [SOP_K_MAXA] what the passes of that ranking hand on, per score plane
     unsigned long long* d_sums = nullptr; // two sets of [SOP_K_REPL][SOP_K_NCOL] layer sums followed by their ticket counters; zero between calls
     hipStream_t lane_stream[kLanes] = {};   // sop_pair_search_layers deals the layers out to streams of its own
     hipEvent_t lane_event[kLanes + 1] = {};  // one per stream (join) and one for the fork
@@ -209,8 +210,9 @@ extern "C" sop_status sop_create(sop_ctx** out, int device)
         delete c;
         return hipfail(nullptr, e, "hipMalloc(scale tables)");
     }
-    if ((e = hipMalloc((void**)&c->d_selm, sizeof(unsigned int) * 2 * SOP_K_SELM_WORDS)) != hipSuccess ||
-        (e = hipMemset(c->d_selm, 0, sizeof(unsigned int) * 2 * SOP_K_SELM_WORDS)) != hipSuccess) {
+    if ((e = hipMalloc((void**)&c->d_selm, sizeof(unsigned int) * 2 * SOP_K_MAXA * SOP_K_SELM_WORDS)) != hipSuccess ||
+        (e = hipMemset(c->d_selm, 0, sizeof(unsigned int) * 2 * SOP_K_MAXA * SOP_K_SELM_WORDS)) != hipSuccess ||
+        (e = hipMalloc((void**)&c->d_selstate, sizeof(SelMState) * SOP_K_MAXA)) != hipSuccess) {
         (void)hipFree(c->d_bins); (void)hipFree(c->d_sums); (void)hipFree(c->d_ddacc); (void)hipFree(c->d_ls); (void)hipFree(c->d_sel); (void)hipFree(c->d_stab); if (c->d_selm) (void)hipFree(c->d_selm);
         delete c;
         return hipfail(nullptr, e, "hipMalloc(rank counts of the sweep)");
@@ -249,6 +251,7 @@ extern "C" sop_status sop_destroy(sop_ctx* c)
         if (c->d_ls) (void)hipFree(c->d_ls);
         if (c->d_sel) (void)hipFree(c->d_sel);
         if (c->d_selm) (void)hipFree(c->d_selm);
+        if (c->d_selstate) (void)hipFree(c->d_selstate);
         if (c->d_ldesc) (void)hipFree(c->d_ldesc);
         if (c->d_msums) (void)hipFree(c->d_msums);
         for (int i = 0; i < 2; ++i) { if (c->h_ldesc[i]) (void)hipHostFree(c->h_ldesc[i]); if (c->ldesc_copied[i]) (void)hipEventDestroy(c->ldesc_copied[i]); }
@@ -1453,8 +1456,11 @@ extern "C" sop_status sop_partition(sop_ctx* c, const float* score, int64_t n_bl
     return SOP_OK;
 }
 
-extern "C" sop_status sop_partition_levels(sop_ctx* c, const float* score, int64_t n_blocks, const int64_t* n_top, int n_levels,
-                                           int higher_is_better, uint8_t* level, float* tau, int64_t* n_a, void* stream)
+// n_planes score planes of n_blocks scores each, back to back, ranked in the same launches (the per-layer
+// procedure ranks the blocks under every atom at once): level, tau and n_a hold one row per plane
+// (tau / n_a rows of SOP_K_SEL_MAXLEV entries)
+static sop_status partition_levels_impl(sop_ctx* c, const float* score, int64_t n_blocks, const int64_t* n_top, int n_levels,
+                                        int higher_is_better, uint8_t* level, float* tau, int64_t* n_a, int n_planes, void* stream)
 {
     if (!c) return SOP_EINVAL;
     if (!score || !n_top || !level || !tau || !n_a) return fail(c, SOP_EINVAL, "sop_partition_levels: score, n_top, level_dev, tau and n_a must not be NULL");
@@ -1472,8 +1478,11 @@ extern "C" sop_status sop_partition_levels(sop_ctx* c, const float* score, int64
     p.score = score; p.n = n_blocks; p.higher = higher_is_better ? 1 : 0; p.n_levels = n_levels;
     bool any = false;
     for (int j = 0; j < n_levels; ++j) { p.n_top[j] = n_top[j]; any = any || n_top[j] != 0; }
-    p.hist = c->d_selm + (c->selm_set ? SOP_K_SELM_WORDS : 0); p.hist_other = c->d_selm + (c->selm_set ? 0 : SOP_K_SELM_WORDS);
+    p.hist = c->d_selm + (c->selm_set ? (size_t)SOP_K_MAXA * SOP_K_SELM_WORDS : 0); p.hist_other = c->d_selm + (c->selm_set ? 0 : (size_t)SOP_K_MAXA * SOP_K_SELM_WORDS);
     p.level = level; p.tau = tau; p.n_a = reinterpret_cast<long long*>(n_a);
+    p.n_planes = n_planes;
+    p.state = c->d_selstate;
+    if (n_planes > 1 && (n_blocks & 3)) return fail(c, SOP_EINVAL, "ranking of several planes: the number of blocks must be a multiple of four");
     const long long quads = std::max<long long>((n_blocks / 4 + SOP_K_SEL_THREADS - 1) / SOP_K_SEL_THREADS, 1);
     const int n_wg = (int)std::min<long long>((long long)c->n_cu * 4, quads);
     const long long cquads = std::max<long long>((n_blocks / 4 + SOP_K_CNT_THREADS - 1) / SOP_K_CNT_THREADS, 1);
@@ -1484,6 +1493,12 @@ extern "C" sop_status sop_partition_levels(sop_ctx* c, const float* score, int64
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     if (any) c->selm_set ^= 1;
     return SOP_OK;
+}
+
+extern "C" sop_status sop_partition_levels(sop_ctx* c, const float* score, int64_t n_blocks, const int64_t* n_top, int n_levels,
+                                           int higher_is_better, uint8_t* level, float* tau, int64_t* n_a, void* stream)
+{
+    return partition_levels_impl(c, score, n_blocks, n_top, n_levels, higher_is_better, level, tau, n_a, 1, stream);
 }
 
 // ------------------------------------------------------------------ scale words and code payloads
@@ -1552,10 +1567,10 @@ LayerWs layer_ws(int64_t M, int64_t K, int g, int A, int n_p, int bins, int pack
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
     w.rank = take((size_t)A * Nb * sizeof(float));
-    w.level = take(Nb);
+    w.level = take((size_t)A * up256(Nb));
     w.hist = take((size_t)A * std::max(n_p, 1) * bins * sizeof(long long));
-    w.tau = take(SOP_K_SEL_MAXLEV * sizeof(float));
-    w.na = take(SOP_K_SEL_MAXLEV * sizeof(long long));
+    w.tau = take((size_t)SOP_K_MAXA * SOP_K_SEL_MAXLEV * sizeof(float));
+    w.na = take((size_t)SOP_K_MAXA * SOP_K_SEL_MAXLEV * sizeof(long long));
     w.acos = take((size_t)(kAcosFit + SOP_K_MAXA * 8) * sizeof(double));
     w.n_img = A + 3;                                   // fixed alphabet, one per atom's sweep, one spare, the winner
     w.bins = take((size_t)w.n_img * kImgBytes);
@@ -1660,11 +1675,23 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
         tops[j] = v < 0.0 ? 0 : (v > (double)Nb ? Nb : (int64_t)v);
     }
     long long* d_hist = reinterpret_cast<long long*>(base + L.hist);
-    for (int a = 0; a < A && n_p; ++a) {
-        if (sop_status s = sop_partition_levels(c, d_rank + (size_t)a * Nb, Nb, tops, n_p, 1, reinterpret_cast<uint8_t*>(base + L.level),
-                                                reinterpret_cast<float*>(base + L.tau), reinterpret_cast<int64_t*>(base + L.na), stream)) return s;
-        if (sop_status s = dd_histogram_impl(c, W, dtype, M, K, ldw, o->weighted_fit ? cn : nullptr, g, bins, 1, reinterpret_cast<uint8_t*>(base + L.level), n_p,
-                                             reinterpret_cast<int64_t*>(d_hist + (size_t)a * n_p * bins), stream)) return s;
+    if (n_p) {
+        // all atoms' planes are ranked by the same four launches when they lie back to back with whole float4s (N_b
+        // a multiple of four); the level planes are N_b bytes apart then
+        const bool batch = (Nb & 3) == 0;
+        const size_t lstride = batch ? (size_t)Nb : up256((size_t)Nb);
+        uint8_t* d_level = reinterpret_cast<uint8_t*>(base + L.level);
+        if (batch) {
+            if (sop_status s = partition_levels_impl(c, d_rank, Nb, tops, n_p, 1, d_level, reinterpret_cast<float*>(base + L.tau),
+                                                     reinterpret_cast<int64_t*>(base + L.na), A, stream)) return s;
+        }
+        for (int a = 0; a < A; ++a) {
+            if (!batch)
+                if (sop_status s = partition_levels_impl(c, d_rank + (size_t)a * Nb, Nb, tops, n_p, 1, d_level + a * lstride, reinterpret_cast<float*>(base + L.tau),
+                                                         reinterpret_cast<int64_t*>(base + L.na), 1, stream)) return s;
+            if (sop_status s = dd_histogram_impl(c, W, dtype, M, K, ldw, o->weighted_fit ? cn : nullptr, g, bins, 1, d_level + a * lstride, n_p,
+                                                 reinterpret_cast<int64_t*>(d_hist + (size_t)a * n_p * bins), stream)) return s;
+        }
     }
     long long* h_hist = reinterpret_cast<long long*>(c->h_res);
     double* h_acos = reinterpret_cast<double*>(c->h_res + (size_t)SOP_K_MAXA * SOP_K_DD_MAXBINS * sizeof(long long));

@@ -191,6 +191,14 @@ struct SelParams {
 /* Ranking with several thresholds at once (the sweep over the partition parameter p): nested pools */
 #define SOP_K_SEL_MAXLEV 8
 #define SOP_K_SELM_WORDS ((1 + 2 * SOP_K_SEL_MAXLEV) * SOP_K_SEL_BINS)   /* one set of digit counts */
+/* what the passes of such a ranking hand on, per score plane (written by a one-workgroup kernel after each counting pass) */
+struct SelMState {
+    unsigned int prefix[SOP_K_SEL_MAXLEV];       // digits of every threshold's key fixed so far
+    unsigned int rank_in[SOP_K_SEL_MAXLEV];      // rank wanted among the keys with those digits
+    unsigned int above[SOP_K_SEL_MAXLEV];        // keys above those digits
+    int alias[SOP_K_SEL_MAXLEV];                 // first threshold with the same digits so far (its histogram is the one used)
+    unsigned long long tkey[SOP_K_SEL_MAXLEV];   // after the last pass: the threshold's key (2^32: every block ranks worse)
+};
 struct SelMParams {
     const float* score;              // [n]
     long long n;
@@ -202,6 +210,10 @@ struct SelMParams {
     unsigned char* level;            // [n] number of thresholds the block ranks strictly worse than
     float* tau;                      // [n_levels] threshold scores
     long long* n_a;                  // [n_levels] blocks at least as good as the threshold
+    SelMState* state;                // [n_planes]
+    // several score planes in one launch (blockIdx.y names the plane): plane q reads score + q * n, counts into
+    // hist + q * SOP_K_SELM_WORDS and writes level + q * n, tau / n_a + q * SOP_K_SEL_MAXLEV
+    int n_planes;
 };
 
 /* Packing of scale words and code payloads */

@@ -1111,7 +1111,7 @@ const void* pick_geom(int sign_mode, bool emit, int na_class, int mode, int* occ
 {
 #define SOPK_FN(S, E, NA) variant<BF16, EPL, LPB, S, E, NA>(mode, occ, mode_out)
 #define SOPK_BY_SIGN(E, NA) (sign_mode == 1 ? SOPK_FN(1, E, NA) : sign_mode == 2 ? SOPK_FN(2, E, NA) : SOPK_FN(0, E, NA))
-    if (emit) return na_class == 0 ? SOPK_BY_SIGN(true, 2) : SOPK_BY_SIGN(true, 8);
+    if (emit) return na_class == 0 ? SOPK_BY_SIGN(true, 2) : na_class == 1 ? SOPK_BY_SIGN(true, 6) : SOPK_BY_SIGN(true, 8);
     if (na_class == 0) return SOPK_BY_SIGN(false, 2);
     if (na_class == 1) return SOPK_BY_SIGN(false, 6);
     return SOPK_BY_SIGN(false, 8);

@@ -181,56 +181,40 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_split_kernel(const Sel
 // ---- several thresholds at once (the sweep over the partition parameter: nested pools) ----
 // The first counting pass is shared by all thresholds; in the second and third pass every threshold counts
 // the keys that agree with its own digits so far, in a histogram of its own.  Thresholds whose digits so
-// far coincide share one histogram (the one of the first of them).  A last kernel writes, per block, the
-// number of thresholds it ranks strictly worse than: the pools are nested, pool j holds the blocks of
-// level > j.
-struct MultiPrefix {
-    uint32_t prefix[SOP_K_SEL_MAXLEV];       // digits fixed so far
-    unsigned int rank_in[SOP_K_SEL_MAXLEV];  // rank wanted among the keys with those digits
-    unsigned int above[SOP_K_SEL_MAXLEV];    // keys above those digits
-    int alias[SOP_K_SEL_MAXLEV];             // first threshold with the same digits so far
-};
+// far coincide share one histogram (the one of the first of them).  After each counting pass a kernel of one
+// workgroup per plane walks the histograms and hands the digits on (were every counting workgroup to walk
+// them itself, the walk's chain of loads and barriers would cost more than the counting).  A last kernel
+// writes, per block, the number of thresholds it ranks strictly worse than: the pools are nested, pool j
+// holds the blocks of level > j.
+// After counting pass PASS a single workgroup per plane finds, for every threshold, the digit of that pass in
+// which the wanted rank falls, and hands the digits so far on to the next pass (or, after the last pass, the
+// thresholds' keys, scores and first-pool sizes to the level kernel and the caller).
+template <int PASS>
+__global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_find_kernel(const SelMParams pp);
 
-// digits of every threshold after `passes` passes (1 or 2), from the histograms of those passes
-__device__ void multi_prefix(const SelMParams& p, int passes, MultiPrefix& mp, Found* s_found, unsigned int* s_wave)
+// the parameters of one plane of a launch over several score planes
+__device__ __forceinline__ SelMParams plane_of(SelMParams p, unsigned int q)
 {
-    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
-        mp.prefix[j] = 0; mp.rank_in[j] = 1; mp.above[j] = 0; mp.alias[j] = j;
-        if (j >= p.n_levels || p.n_top[j] == 0) continue;
-        const Found f0 = find_digit(p.hist, (unsigned int)p.n_top[j], s_found, s_wave);
-        mp.prefix[j] = (uint32_t)f0.digit << 21; mp.rank_in[j] = f0.rank_in; mp.above[j] = f0.above;
-    }
-    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j)
-        _Pragma("unroll") for (int i = j - 1; i >= 0; --i)
-            if (j < p.n_levels && p.n_top[i] != 0 && p.n_top[j] != 0 && mp.prefix[i] == mp.prefix[j]) mp.alias[j] = mp.alias[i];
-    if (passes >= 2) {
-        uint32_t pre2[SOP_K_SEL_MAXLEV];
-        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
-            pre2[j] = mp.prefix[j];
-            if (j >= p.n_levels || p.n_top[j] == 0) continue;
-            const Found f1 = find_digit(p.hist + (1 + mp.alias[j]) * SOP_K_SEL_BINS, mp.rank_in[j], s_found, s_wave);
-            pre2[j] |= (uint32_t)f1.digit << 10; mp.rank_in[j] = f1.rank_in; mp.above[j] += f1.above;
-        }
-        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
-            mp.prefix[j] = pre2[j]; mp.alias[j] = j;
-        }
-        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j)
-            _Pragma("unroll") for (int i = j - 1; i >= 0; --i)
-                if (j < p.n_levels && p.n_top[i] != 0 && p.n_top[j] != 0 && mp.prefix[i] == mp.prefix[j]) mp.alias[j] = mp.alias[i];
-    }
+    p.score += (size_t)q * (size_t)p.n;
+    p.hist += (size_t)q * SOP_K_SELM_WORDS;
+    p.hist_other += (size_t)q * SOP_K_SELM_WORDS;
+    p.level += (size_t)q * (size_t)p.n;
+    p.tau += q * SOP_K_SEL_MAXLEV;
+    p.n_a += q * SOP_K_SEL_MAXLEV;
+    p.state += q;
+    return p;
 }
 
 template <int PASS>
-__global__ __launch_bounds__(SOP_K_CNT_THREADS) void rank_count_multi_kernel(const SelMParams p)
+__global__ __launch_bounds__(SOP_K_CNT_THREADS) void rank_count_multi_kernel(const SelMParams pp)
 {
+    const SelMParams p = plane_of(pp, blockIdx.y);
     extern __shared__ unsigned int s_mh[];                          // pass 0: [BINS]; else [n_levels][BINS]
-    __shared__ Found s_found;
-    __shared__ unsigned int s_wave[SOP_K_SEL_BINS / 8 / 64];
     const int L = PASS == 0 ? 1 : p.n_levels;
     for (int i = threadIdx.x; i < L * SOP_K_SEL_BINS; i += SOP_K_CNT_THREADS) s_mh[i] = 0u;
-    MultiPrefix mp;
     const uint32_t pmask = PASS == 0 ? 0u : PASS == 1 ? 0xFFE00000u : 0xFFFFFC00u;
-    if (PASS >= 1) multi_prefix(p, PASS, mp, &s_found, s_wave);
+    SelMState mp;                                                    // (same values in every lane: scalar loads)
+    if (PASS >= 1) mp = *p.state;
     __syncthreads();
     const bool higher = p.higher != 0;
     const long long n4 = p.n >> 2;
@@ -262,31 +246,12 @@ __global__ __launch_bounds__(SOP_K_CNT_THREADS) void rank_count_multi_kernel(con
     }
 }
 
-__global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_level_kernel(const SelMParams p)
+__global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_level_kernel(const SelMParams pp)
 {
-    __shared__ Found s_found;
-    __shared__ unsigned int s_wave[SOP_K_SEL_THREADS / 64];
+    const SelMParams p = plane_of(pp, blockIdx.y);
     const bool higher = p.higher != 0;
-    MultiPrefix mp;
-    multi_prefix(p, 2, mp, &s_found, s_wave);
-    // a key of 2^32 stands for "every block ranks worse" (a first pool of size zero)
     unsigned long long tkey[SOP_K_SEL_MAXLEV];
-    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
-        tkey[j] = 0ull;                                            // (thresholds beyond n_levels: no block ranks worse)
-        if (j >= p.n_levels) continue;
-        tkey[j] = 1ull << 32;
-        float tau = higher ? __uint_as_float(0x7F800000u) : __uint_as_float(0xFF800000u);
-        unsigned int n_a = 0;
-        if (p.n_top[j] != 0) {
-            const unsigned int* h2 = p.hist + (1 + SOP_K_SEL_MAXLEV + mp.alias[j]) * SOP_K_SEL_BINS;
-            const Found f2 = find_digit(h2, mp.rank_in[j], &s_found, s_wave);
-            const uint32_t tk = mp.prefix[j] | (uint32_t)f2.digit;
-            tkey[j] = tk;
-            tau = key_score(tk, higher);
-            n_a = mp.above[j] + f2.above + h2[f2.digit];          // keys above tau's, plus every key equal to it
-        }
-        if (blockIdx.x == 0 && threadIdx.x == 0) { p.tau[j] = tau; p.n_a[j] = (long long)n_a; }
-    }
+    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) tkey[j] = j < p.n_levels ? p.state->tkey[j] : 0ull;   // (beyond n_levels: no block ranks worse)
     const long long n4 = p.n >> 2;
     const float4* s4 = reinterpret_cast<const float4*>(p.score);
     uint32_t* m4 = reinterpret_cast<uint32_t*>(p.level);
@@ -314,15 +279,56 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_level_kernel(const Sel
         p.hist_other[gi] = 0u;
 }
 
+template <int PASS>
+__global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_find_kernel(const SelMParams pp)
+{
+    const SelMParams p = plane_of(pp, blockIdx.y);
+    __shared__ Found s_found;
+    __shared__ unsigned int s_wave[SOP_K_SEL_THREADS / 64];
+    const bool higher = p.higher != 0;
+    SelMState st;
+    if (PASS >= 1) st = *p.state;
+    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
+        if (PASS == 0) { st.prefix[j] = 0u; st.rank_in[j] = 1u; st.above[j] = 0u; st.alias[j] = j; }
+        st.tkey[j] = 1ull << 32;
+        if (j >= p.n_levels || p.n_top[j] == 0) continue;
+        const unsigned int* h = PASS == 0 ? p.hist : p.hist + ((PASS == 1 ? 1 : 1 + SOP_K_SEL_MAXLEV) + st.alias[j]) * SOP_K_SEL_BINS;
+        const Found f = find_digit(h, PASS == 0 ? (unsigned int)p.n_top[j] : st.rank_in[j], &s_found, s_wave);
+        st.prefix[j] |= (uint32_t)f.digit << (PASS == 0 ? 21 : PASS == 1 ? 10 : 0);
+        st.rank_in[j] = f.rank_in;
+        if (PASS == 2) {
+            st.tkey[j] = st.prefix[j];
+            if (threadIdx.x == 0) { p.tau[j] = key_score(st.prefix[j], higher); p.n_a[j] = (long long)(st.above[j] + f.above + h[f.digit]); }   // keys above tau's, plus every key equal to it
+        }
+        st.above[j] += f.above;
+    }
+    if (PASS == 2) {
+        _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j)
+            if (j < p.n_levels && p.n_top[j] == 0 && threadIdx.x == 0) {
+                p.tau[j] = higher ? __uint_as_float(0x7F800000u) : __uint_as_float(0xFF800000u);
+                p.n_a[j] = 0;
+            }
+    }
+    // thresholds whose digits so far coincide share the histogram of the first of them in the next pass
+    _Pragma("unroll") for (int j = 0; j < SOP_K_SEL_MAXLEV; ++j) {
+        st.alias[j] = j;
+        _Pragma("unroll") for (int i = j - 1; i >= 0; --i)
+            if (j < p.n_levels && p.n_top[i] != 0 && p.n_top[j] != 0 && st.prefix[i] == st.prefix[j]) st.alias[j] = st.alias[i];
+    }
+    if (threadIdx.x == 0) *p.state = st;
+}
+
 }  // namespace sopk
 
 extern "C" hipError_t sopk_selm_launch(const SelMParams* pp, int n_wg_count, int n_wg, void* stream)
 {
     const SelMParams p = *pp;
     hipStream_t st = (hipStream_t)stream;
-    const dim3 grid((unsigned)n_wg), block(SOP_K_SEL_THREADS), cgrid((unsigned)n_wg_count), cblock(SOP_K_CNT_THREADS);
+    const unsigned planes = (unsigned)(p.n_planes > 0 ? p.n_planes : 1);
+    const dim3 grid((unsigned)n_wg, planes), block(SOP_K_SEL_THREADS), cgrid((unsigned)n_wg_count, planes), cblock(SOP_K_CNT_THREADS);
     bool any = false;
     for (int j = 0; j < p.n_levels; ++j) any = any || p.n_top[j] != 0;
+    const dim3 fgrid(1, planes);
     if (any) {
         const size_t lds0 = SOP_K_SEL_BINS * sizeof(unsigned int), ldsL = (size_t)p.n_levels * lds0;
         if (ldsL > 48 * 1024) {
@@ -331,9 +337,12 @@ extern "C" hipError_t sopk_selm_launch(const SelMParams* pp, int n_wg_count, int
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL((sopk::rank_count_multi_kernel<0>), cgrid, cblock, lds0, st, p);
+        hipLaunchKernelGGL((sopk::rank_find_kernel<0>), fgrid, block, 0, st, p);
         hipLaunchKernelGGL((sopk::rank_count_multi_kernel<1>), cgrid, cblock, ldsL, st, p);
+        hipLaunchKernelGGL((sopk::rank_find_kernel<1>), fgrid, block, 0, st, p);
         hipLaunchKernelGGL((sopk::rank_count_multi_kernel<2>), cgrid, cblock, ldsL, st, p);
     }
+    hipLaunchKernelGGL((sopk::rank_find_kernel<2>), fgrid, block, 0, st, p);      // (with every first pool empty it only writes the defaults)
     hipLaunchKernelGGL(sopk::rank_level_kernel, grid, block, 0, st, p);
     return hipGetLastError();
 }
