@@ -22,10 +22,11 @@
 #define SOP_K_BIN_EXT 1.5625f
 #define SOP_K_BIN_SAFE 1.55f
 
-#if defined(__HIPCC__)
+#if defined(__HIPCC__) || defined(__HIP__)
 #define SOP_K_HD __host__ __device__
 #else
 #define SOP_K_HD
+struct float2 { float x, y; };       /* (host-only translation units see the launch parameters' layout without a HIP header) */
 #endif
 
 /* position of (i,j), i < j, in the lexicographic list of all pairs of SOP_K_MAXA atoms */
