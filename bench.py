@@ -30,20 +30,21 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 VALU_PEAK_TLOPS = 39.3216
 
 
-def algorithmic_lane_ops(n_weights, g, n_atoms, n_groups, n_pairs, signs=1):
-    """Lane-operations the method needs per launch, counted from its arithmetic, not from the code:
-    per weight: widen, max, min, c*w, ||w||^2 fma                                   = 5
-    per weight and scale group: x = w*r, clamp, bin fma, table address               = 4
-    per weight and atom: compare with the bin's boundary, select the entry, residual
-        fma, c*d, error fma, cosine-sum fma                                          = 6
+def algorithmic_lane_ops(n_weights, g, n_atoms, n_groups, n_pairs, signs=1, n_copies=0):
+    """Lane-operations of the method's own arithmetic per launch (an fma counted once), not of the code:
+    per weight: widen, max, min, c*w, ||w||^2 fma                                    = 5
+    per weight and scale group: x = w*r, the two operations that locate x's code     = 3
+    per weight and evaluated (atom, sign): compare with the code boundary, select
+        the entry, residual fma, c*d, error fma, cosine-sum fma                      = 6
     per block and scale group: ideal scale 3, shift 1, encode 5, decode+reciprocal 3 = 12
     per block and atom: chunk add 1, cosine 5, accumulate 2                          = 8
-    per block and pair: compare, select, add, two moves for the selector bit         = 5
-    (the kernel as profiled executes 69.5 lane-operations per weight against these 62.9)"""
-    # a signed scale word doubles the group and atom work (both signs are evaluated) and adds three
-    # operations per block and atom for keeping the better sign
-    per_weight = 5 + signs * (4 * n_groups + 6 * n_atoms)
-    per_block = signs * (12 * n_groups + 8 * n_atoms) + (signs - 1) * 3 * n_atoms + 5 * n_pairs
+    per block and pair: compare, select, add, two operations for the selector bit    = 5
+    A signed scale word evaluates both signs of every atom (groups and atoms count twice, three more
+    operations per block and atom keep the better sign), except that an atom that is the sign-negated copy
+    of another (n_copies of the n_atoms) takes its candidates over from it and is not evaluated."""
+    evaluated = n_atoms - (n_copies if signs == 2 else 0)
+    per_weight = 5 + signs * (3 * n_groups + 6 * evaluated)
+    per_block = signs * 12 * n_groups + 8 * n_atoms + (signs - 1) * (8 * evaluated + 3 * n_atoms) + 5 * n_pairs
     return n_weights * per_weight + (n_weights // g) * per_block
 
 
@@ -66,9 +67,10 @@ def parse_traffic():
     return None
 
 
-def parse_valu_counters():
-    """Vector-ALU figures of the headline kernel from the committed rocprofv3 counter summary
-    (profiles/search_kernel_c3down_valu.txt): wavefront VALU instructions and busy cycles per launch."""
+def counters_from_file():
+    """Figures of the headline kernel that this run does NOT measure: they are read from the committed rocprofv3
+    counter summary (profiles/search_kernel_c3down_valu.txt, taken with `rocprofv3 --pmc` on this workload) and
+    are labelled as such in the bench line."""
     path = os.path.join(ROOT, "profiles", "search_kernel_c3down_valu.txt")
     if not os.path.exists(path):
         return None
@@ -83,21 +85,13 @@ def parse_valu_counters():
                 pass
     if "SQ_INSTS_VALU" not in vals:
         return None
-    return {"source": "profiles/search_kernel_c3down_valu.txt (rocprofv3 --pmc, same command)",
-            "wave_valu_instructions_per_launch": vals["SQ_INSTS_VALU"],
-            "executed_lane_ops_per_weight": vals["SQ_INSTS_VALU"] * 64.0 / (4096 * 11008)}
-
-
-def valu_counters(ev_ms):
-    """The committed counters with the rate they mean at this run's time per launch: executed vector-ALU
-    lane-operations per second and their fraction of the plain (unpacked) peak."""
-    v = parse_valu_counters()
-    if v is None:
-        return None
-    rate = v["wave_valu_instructions_per_launch"] * 64.0 / (ev_ms * 1e-3) / 1e12
-    v["executed_T_lane_ops_per_second"] = rate
-    v["valu_utilisation_of_peak"] = rate / VALU_PEAK_TLOPS
-    return v
+    out = {"from_file": "profiles/search_kernel_c3down_valu.txt", "measured_in_this_run": False,
+           "wave_valu_instructions_per_launch": vals["SQ_INSTS_VALU"]}
+    if "weights_per_launch" in vals:
+        out["executed_lane_ops_per_weight"] = vals["SQ_INSTS_VALU"] * 64.0 / vals["weights_per_launch"]
+    if "observed_clock_ghz" in vals:
+        out["observed_clock_ghz"] = vals["observed_clock_ghz"]
+    return out
 
 
 def timed_region(step, steps):
@@ -606,7 +600,15 @@ def main():
     alg_bytes = M * K * esz + K * 4 + Nb * sel_bytes + (A + P) * 8
     achieved = alg_bytes / (ev_ms * 1e-3) / 1e9
     n_groups = len({(float(t[0]), float(t[-1])) for t in tabs})           # atoms with equal endpoints share a scale
-    alg_ops = algorithmic_lane_ops(M * K, g, A, n_groups, P, signs=2 if fmt.sign_bits else 1)
+    n_copies = 0                                                          # atoms that are the sign-negated copy of an earlier atom
+    for i, t in enumerate(tabs):
+        if any(t.size == u.size and np.array_equal(t, -u[::-1]) for u in tabs[:i]):
+            n_copies += 1
+    if fmt.sign_bits:                                                     # a copy's group of mirrored endpoints is not prepared either
+        n_groups = len({tuple(sorted((abs(float(t[0])), abs(float(t[-1]))))) for t in tabs})
+    alg_ops = algorithmic_lane_ops(M * K, g, A, n_groups, P, signs=2 if fmt.sign_bits else 1, n_copies=n_copies)
+    cff = counters_from_file() if headline else None
+    clock = cff.get("observed_clock_ghz") if cff else None
 
     # last step ran on buffer (steps-1) % n: check it against the oracle when that is buffer 0
     result = {
@@ -618,16 +620,18 @@ def main():
                    "M": M, "K": K, "g": g, "scale_format": cfg["fmt"], "atoms": list(cfg["atoms"]), "pairs": P,
                    "weight_dtype": cfg["dtype"], "buffers_rotated": len(bufs), "alphabet_upload_ms_once": alphabet_upload_ms},
         "layer_latency_ms": lat_ms, "layer_latency_median_ms": lat_med_ms, "layer_latency_min_ms": lat_min_ms,
-        "valu_counters": valu_counters(ev_ms) if headline else None,
+        "counters_from_file": cff,
         # the six-atom search is bound by the plain vector ALUs (72 us of algorithmic lane-operations
         # against 12 us of algorithmic HBM traffic per launch); the HBM view of the same launch is given beside it
         "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",
                      "frac": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_PEAK_TLOPS, "traffic": parse_traffic() if headline else None,
-                     "op_definition": "fp32 lane-operations, an fma counted once; peak = 256 CU x 64 lanes x 2.4 GHz",
+                     "traffic_source": "profiles/search_kernel_c3down_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)" if headline else None,
+                     "frac_at_observed_clock": (alg_ops / (ev_ms * 1e-3) / 1e12 / (VALU_PEAK_TLOPS * clock / 2.4)) if clock else None,
+                     "op_definition": "fp32 lane-operations of the method's arithmetic, an fma counted once; peak = 256 CU x 64 lanes x 2.4 GHz (published clock)",
                      "algorithmic_lane_ops_per_launch": alg_ops, "algorithmic_lane_ops_per_weight": alg_ops / (M * K),
                      "kernel": "sopk::search_kernel", "event_ms_per_launch": ev_ms},
         "roofline_hbm": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": alg_bytes},
+                         "frac": achieved / HBM_PEAK_GBS, "target_frac": 0.60, "algorithmic_bytes_per_launch": alg_bytes},
     }
 
     if not args.no_cpu_baseline:
@@ -652,6 +656,8 @@ def main():
         result["parity_in_run"] = {"max_abs_dACos": d_acos, "selector_bits_equal": sel_ok}
     result["untimed_clock_ramp_ms"] = CLOCK_RAMP_MS
     print(json.dumps(result))
+    sys.stdout.flush()
+    ctx.close()
 
 
 if __name__ == "__main__":
