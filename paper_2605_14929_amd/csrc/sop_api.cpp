@@ -365,6 +365,21 @@ extern "C" sop_status sop_workspace_bytes(sop_ctx* c, int64_t M, int64_t K, int 
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Rows folded into one for the search kernel (see KParams::Kc): the power of two f <= 64 dividing M that leaves
+// the fewest idle lanes in the last 64-lane strip of a row of f*K columns; 1 when the rows do not lie back to back.
+static int row_fold(int64_t M, int64_t K, int64_t ldw, int epl)
+{
+    if (ldw != K) return 1;
+    int best = 1;
+    double best_waste = 1e9;
+    for (int f = 1; f <= 64 && M % f == 0 && K * f < (1ll << 24); f *= 2) {
+        const int64_t lanes = K * f / epl, strips = (lanes + 63) / 64;
+        const double waste = (double)(strips * 64 - lanes) / (double)lanes;
+        if (waste < best_waste - 1e-12) { best_waste = waste; best = f; }
+    }
+    return best;
+}
+
 // (scale * 2^-k, reciprocal) of every code of a scale word: value(q) * 2^-k (exact) and its IEEE reciprocal.
 // The tables live in a slab the context allocated at its creation; a table that is not there yet is written
 // by a small kernel on the caller's stream ahead of the kernel that reads it (no allocation, no copy from the
@@ -454,6 +469,10 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     std::memset(&p, 0, sizeof(p));
     p.W = W; p.c = cn;
     p.bins = c->d_bins_cur;
+    const int64_t Mu = M, Ku = K;                       // the caller's shape (output planes are laid out by it)
+    const int fold = row_fold(M, K, ldw, epl);
+    p.Kc = K;
+    M /= fold; K *= fold; ldw = fold > 1 ? K : ldw;     // from here on: the shape the kernel walks
     p.M = M; p.K = K; p.ldw = ldw;
     p.Bk = K / g; p.Nb = M * p.Bk;
     p.strips = (K / epl + 63) / 64;
@@ -468,7 +487,7 @@ static sop_status pair_search_impl(sop_ctx* c, const void* W, sop_dtype dtype, i
     p.sub_quantum = std::ldexp(1.0f, 1 - bias - y - k);
     // code planes are laid out in the caller's atom order
     long long plane_off[SOP_K_MAXA], off = 0;
-    for (int a = 0; a < A; ++a) { plane_off[a] = off; off += c->tables[a].size() <= 16 ? M * K / 2 : M * K; }
+    for (int a = 0; a < A; ++a) { plane_off[a] = off; off += c->tables[a].size() <= 16 ? Mu * Ku / 2 : Mu * Ku; }
     int internal_of[SOP_K_MAXA];
     for (int i = 0; i < A; ++i) {
         p.tpos[i] = c->tpos[i]; p.tneg[i] = c->tneg[i]; p.bin_sc[i] = c->bin_sc[i]; p.bin_off[i] = c->bin_off[i];
@@ -648,13 +667,15 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
                         const int l = idx[i0 + i];
                         const sop_layer& L = layers[l];
                         LayerDesc& d = h[i];
-                        d.W = L.W_dev; d.c = L.c_dev; d.sel_words = c->n_pairs ? L.sel_words_dev : nullptr; d.ldw = L.ldw;
-                        d.Bk = (int)(L.K / g); d.Nb = L.M * (L.K / g);
+                        const int fold = row_fold(L.M, L.K, L.ldw, epl);
+                        const int64_t Mf = L.M / fold, Kf = L.K * fold;
+                        d.W = L.W_dev; d.c = L.c_dev; d.sel_words = c->n_pairs ? L.sel_words_dev : nullptr; d.ldw = fold > 1 ? Kf : L.ldw;
+                        d.Bk = (int)(Kf / g); d.Nb = L.M * (L.K / g);
                         d.out_row = l;
-                        d.M32 = (unsigned int)L.M;
-                        d.m_magic = L.M == 1 ? 0xFFFFFFFFu : (unsigned int)((1ull << 32) / (unsigned long long)L.M);
-                        d.K = (int)L.K;
-                        d.total_units = (unsigned int)(((L.K / epl + 63) / 64) * L.M);
+                        d.M32 = (unsigned int)Mf;
+                        d.m_magic = Mf == 1 ? 0xFFFFFFFFu : (unsigned int)((1ull << 32) / (unsigned long long)Mf);
+                        d.K = (int)Kf; d.Kc = (int)L.K; d.pad = 0;
+                        d.total_units = (unsigned int)(((Kf / epl + 63) / 64) * Mf);
                     }
                     if ((e = hipMemcpyAsync(c->d_ldesc, h, sizeof(LayerDesc) * n, hipMemcpyHostToDevice, (hipStream_t)stream)) != hipSuccess ||
                         (e = hipEventRecord(c->ldesc_copied[turn], (hipStream_t)stream)) != hipSuccess)

@@ -50,7 +50,11 @@ struct KParams {
     const float*  c;
     const BinRec* bins;              // [n_bins], atoms in internal order
     const float2* stab;              // [n_tab_codes] (scale * 2^-k, its reciprocal), or null
-    long long M, K, ldw;
+    long long M, K, ldw;             // as the kernel walks the layer: rows may be folded (see Kc)
+    long long Kc;                    // true row length.  When the rows lie back to back (ldw == K) and 64 lanes do not divide a
+                                     // row's lanes, the host folds f rows into one of f*K columns (M/f rows): the last strip of
+                                     // every row then wastes fewer lanes (none when 64 divides f*K/EPL).  Block and element
+                                     // indices are unchanged by this; only the channel of a column becomes its index modulo Kc.
     long long Bk;                    // blocks per row
     long long Nb;                    // blocks in the layer
     long long strips;                // 64-lane strips per row
@@ -103,7 +107,7 @@ struct KParams {
     int n_layers;
 };
 
-/* One layer of a model-wide launch (64 bytes, read with scalar loads) */
+/* One layer of a model-wide launch (72 bytes, read with scalar loads) */
 struct LayerDesc {
     const void*  W;
     const float* c;
@@ -115,6 +119,8 @@ struct LayerDesc {
     unsigned int M32, m_magic;       // rows, floor(2^32 / rows)
     int          K;
     unsigned int total_units;        // strips * rows
+    int          Kc;                 // true row length (rows may be folded as in KParams)
+    int          pad;
 };
 
 /* Statistics pass of the data-derived codebook */

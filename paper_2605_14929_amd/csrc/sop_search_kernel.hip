@@ -652,6 +652,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
     const float* lc_c = nullptr;
     void* lc_sel = nullptr;
     long long lc_K = 0, lc_Bk = 0;
+    unsigned int lc_Kc = 1u;
 
     long long strip = 0, m = 0;
     long long cur_strip = -1;
@@ -676,11 +677,12 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 lc_c = reinterpret_cast<const float*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(d.c)));
                 lc_sel = reinterpret_cast<void*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(d.sel_words)));
                 lc_K = (long long)uni((unsigned int)d.K); lc_Bk = (long long)uni((unsigned int)d.Bk);
+                lc_Kc = uni((unsigned int)d.Kc);
                 cur_strip = strip;
                 const long long c0 = (strip * 64 + lane) * EPL;
 #pragma unroll
                 for (int i = 0; i < EPL; i += 4) {
-                    float4 t = c0 < lc_K ? *reinterpret_cast<const float4*>(lc_c + c0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    float4 t = c0 < lc_K ? *reinterpret_cast<const float4*>(lc_c + (unsigned int)c0 % lc_Kc + i) : make_float4(0.f, 0.f, 0.f, 0.f);
                     cb[i] = t.x; cb[i + 1] = t.y; cb[i + 2] = t.z; cb[i + 3] = t.w;
                 }
                 if (left >= 0) flush(left, since_flush <= 15);
@@ -699,7 +701,8 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             cur_strip = cs;
 #pragma unroll
             for (int i = 0; i < EPL; i += 4) {
-                float4 t = valid ? *reinterpret_cast<const float4*>((MULTI ? lc_c : p.c) + col0 + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+                // (rows may have been folded, see KParams::Kc: the channel of a column is its index modulo the true row length)
+                float4 t = valid ? *reinterpret_cast<const float4*>((MULTI ? lc_c : p.c) + (unsigned int)col0 % (MULTI ? lc_Kc : (unsigned int)p.Kc) + i) : make_float4(0.f, 0.f, 0.f, 0.f);
                 cb[i] = t.x; cb[i + 1] = t.y; cb[i + 2] = t.z; cb[i + 3] = t.w;
             }
         }
@@ -717,7 +720,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
             if (ok_nxt && l_nxt != cl) {
                 const float* cn = reinterpret_cast<const float*>(uni64((unsigned long long)reinterpret_cast<uintptr_t>(p.layers[l_nxt].c)));
                 const long long tc = (strip * 64 + lane) * EPL;
-                if (tc < rq_K) c_touch = cn[tc];
+                if (tc < rq_K) c_touch = cn[(unsigned int)tc % uni((unsigned int)p.layers[l_nxt].Kc)];
             }
         }
         const unsigned int i_nn = grab();              // the step after the next one; used at the end of this step
