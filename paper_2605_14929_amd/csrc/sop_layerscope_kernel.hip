@@ -76,6 +76,28 @@ __device__ __forceinline__ float exmy_round_value(float a, bool tie_up, const Ex
     return fminf(v, gd.vmax);
 }
 
+// the same grid point for a signed x, sign included: ties go to the lower value, which for a negative x is
+// the larger magnitude, so the sign bit itself is the tie increment; the sign bit rides through the
+// rounding untouched (a finite value never carries out of the exponent), and the clamp to +-vmax is one
+// median-of-three.
+__device__ __forceinline__ float exmy_round_signed(float x, const ExmyGrid& gd)
+{
+    const uint32_t xb = __float_as_uint(x);
+    float v = __uint_as_float((xb + gd.half_m1 + (xb >> 31)) & gd.keep);
+    if (fabsf(x) < gd.min_normal) {
+        asm volatile("");                              // a real branch: skipped when no lane is this small
+        const uint32_t u = xb & 0x7FFFFFFFu;
+        const int E = (int)(u >> 23);
+        const int Ee = E > 0 ? E : 1;
+        const uint32_t m = (u & 0x7FFFFFu) | (E > 0 ? 0x800000u : 0u);
+        int S = 151 - gd.bias - gd.y - Ee;
+        S = S > 31 ? 31 : S;
+        const uint32_t q = (m + ((1u << (S - 1)) - 1u + (xb >> 31))) >> S;
+        v = __uint_as_float(__float_as_uint((float)q * gd.quantum) | (xb & 0x80000000u));
+    }
+    return __builtin_amdgcn_fmed3f(v, -gd.vmax, gd.vmax);
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
 #pragma unroll
@@ -236,74 +258,96 @@ __global__ __launch_bounds__(256) void layer_scope_kernel(const LsParams p)
     gd.vmax = tp;
 
     double acc_w = 0.0, acc_u = 0.0, acc_n = 0.0;
-    // a wavefront walks down the rows of one 64-lane strip (its channel norms stay in registers) and
-    // keeps the next row's load in flight while it works on the current one
-    long long st = u0 / p.M, row = u0 - st * p.M, cur_st = -1;
-    float c[EPL];
-    auto load_w = [&](long long r, long long sidx) {
-        const long long col = (sidx * 64 + lane) * EPL;
-        uint4 t = make_uint4(0, 0, 0, 0);
-        if (col < p.K) t = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.W) + (r * p.ldw + col) * (BF16 ? 2 : 4));
-        return t;
-    };
-    uint4 nxt = make_uint4(0, 0, 0, 0);
-    if (u0 < u1) nxt = load_w(row, st);
-    for (long long u = u0; u < u1; ++u) {
-        const uint4 t = nxt;
+    // A wavefront walks down the rows of a 64-lane strip, its channel norms in registers.  Its share of the
+    // steps is cut at the strip boundaries into segments; within a segment the loads of four rows are in
+    // flight at any time, in four buffers taken in turn.  No load of the inner loop sits under a branch (a
+    // lane past the end of the row reads the row's last columns and uses nothing of them; past the last row
+    // of the segment the last row is read again), so the count of loads in flight is known where a buffer is
+    // waited for and the wait leaves the three younger loads in flight.
+    const int esz = BF16 ? 2 : 4;
+    long long u = u0;
+    while (u < u1) {
+        const long long st = u / p.M;
+        const long long row0 = u - st * p.M;
+        const long long seg_end = (st + 1) * p.M < u1 ? (st + 1) * p.M : u1;
+        const long long n = seg_end - u;
         const long long col0 = (st * 64 + lane) * EPL;
-        const long long my_row = row;
         const bool valid = col0 < p.K;
-        if (st != cur_st) {
-            cur_st = st;
+        const long long colc = valid ? col0 : p.K - EPL;
+        float c[EPL];
 #pragma unroll
-            for (int j = 0; j < EPL; j += 4) {
-                float4 cc = make_float4(1.f, 1.f, 1.f, 1.f);
-                if (p.c && valid) cc = *reinterpret_cast<const float4*>(p.c + col0 + j);
-                c[j] = cc.x; c[j + 1] = cc.y; c[j + 2] = cc.z; c[j + 3] = cc.w;
+        for (int j = 0; j < EPL; j += 4) {
+            float4 cc = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (p.c) cc = *reinterpret_cast<const float4*>(p.c + colc + j);
+            c[j] = cc.x; c[j + 1] = cc.y; c[j + 2] = cc.z; c[j + 3] = cc.w;
+        }
+        const char* lp = reinterpret_cast<const char*>(p.W) + (row0 * p.ldw + colc) * esz;
+        const long long row_bytes = p.ldw * esz;
+        long long left = n;
+        auto issue = [&]() {
+            const uint4 t = *reinterpret_cast<const uint4*>(lp);
+            if (--left > 0) lp += row_bytes;
+            return t;
+        };
+        auto step = [&](const uint4 t, const long long my_row) {
+            if (!valid) return;
+            const uint32_t v[4] = {t.x, t.y, t.z, t.w};
+            float w[EPL];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (BF16) { w[2 * j] = __uint_as_float(v[j] << 16); w[2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u); }
+                else w[j] = __uint_as_float(v[j]);
             }
-        }
-        if (++row == p.M) { row = 0; ++st; }
-        if (u + 1 < u1) nxt = load_w(row, st);
-        if (!valid) continue;
-        const uint32_t v[4] = {t.x, t.y, t.z, t.w};
-        float w[EPL];
+            float ew = 0.0f, eu = 0.0f, wn = 0.0f;
+            uint32_t packed[EPL / 2];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (BF16) { w[2 * j] = __uint_as_float(v[j] << 16); w[2 * j + 1] = __uint_as_float(v[j] & 0xFFFF0000u); }
-            else w[j] = __uint_as_float(v[j]);
-        }
-        float ew = 0.0f, eu = 0.0f, wn = 0.0f;
-        uint32_t packed[EPL / 2];
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const float x = w[j] * r;
-            const bool negv = x < 0.0f;
-            // nearest grid value, ties to the lower value: for a negative x that is the larger magnitude
-            int m = 0;
-            float ym;
+            for (int j = 0; j < EPL; ++j) {
+                const float x = w[j] * r;
+                // nearest grid value, ties to the lower value: for a negative x that is the larger magnitude
+                float y;
+                if (CODES) {
+                    const bool negv = x < 0.0f;
+                    const int m = exmy_encode(fabsf(x), p.w_man, p.w_bias, p.w_max_code, negv);
+                    const float ym = exmy_decode(m, p.w_man, p.w_bias, 0);
+                    y = negv ? -ym : ym;
+                    const uint32_t idx = (uint32_t)(negv ? p.w_max_code - m : p.w_max_code + m);   // index in the ascending signed grid
+                    if (j % 2 == 0) packed[j / 2] = idx; else packed[j / 2] |= idx << 16;
+                } else {
+                    y = exmy_round_signed(x, gd);
+                }
+                const float d = __fmaf_rn(-s, y, w[j]);
+                const float cd = c[j] * d;
+                ew = __fmaf_rn(cd, d, ew);
+                eu = __fmaf_rn(d, d, eu);
+                wn = __fmaf_rn(c[j] * w[j], w[j], wn);
+            }
+            acc_w += (double)ew; acc_u += (double)eu; acc_n += (double)wn;
             if (CODES) {
-                m = exmy_encode(fabsf(x), p.w_man, p.w_bias, p.w_max_code, negv);
-                ym = exmy_decode(m, p.w_man, p.w_bias, 0);
-            } else {
-                ym = exmy_round_value(fabsf(x), negv, gd);
-            }
-            const float y = negv ? -ym : ym;
-            const float d = __fmaf_rn(-s, y, w[j]);
-            const float cd = c[j] * d;
-            ew = __fmaf_rn(cd, d, ew);
-            eu = __fmaf_rn(d, d, eu);
-            wn = __fmaf_rn(c[j] * w[j], w[j], wn);
-            if (CODES) {
-                const uint32_t idx = (uint32_t)(negv ? p.w_max_code - m : p.w_max_code + m);   // index in the ascending signed grid
-                if (j % 2 == 0) packed[j / 2] = idx; else packed[j / 2] |= idx << 16;
-            }
-        }
-        acc_w += (double)ew; acc_u += (double)eu; acc_n += (double)wn;
-        if (CODES) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(p.codes + my_row * p.K + col0);
+                uint32_t* dst = reinterpret_cast<uint32_t*>(p.codes + my_row * p.K + col0);
 #pragma unroll
-            for (int j = 0; j < EPL / 2; ++j) dst[j] = packed[j];
+                for (int j = 0; j < EPL / 2; ++j) dst[j] = packed[j];
+            }
+        };
+        // (issued in the order the loop takes them: the waits count the loads issued after the one waited for)
+        uint4 q0 = issue();
+        __builtin_amdgcn_sched_barrier(0);
+        uint4 q1 = issue();
+        __builtin_amdgcn_sched_barrier(0);
+        uint4 q2 = issue();
+        __builtin_amdgcn_sched_barrier(0);
+        uint4 q3 = issue();
+        __builtin_amdgcn_sched_barrier(0);
+        for (long long i = 0; i < n; i += 4) {
+            step(q0, row0 + i);
+            q0 = issue();
+            if (i + 1 < n) step(q1, row0 + i + 1);
+            q1 = issue();
+            if (i + 2 < n) step(q2, row0 + i + 2);
+            q2 = issue();
+            if (i + 3 < n) step(q3, row0 + i + 3);
+            q3 = issue();
         }
+        u = seg_end;
     }
     const double v3[3] = {acc_w, acc_u, acc_n};
     if (finish_sums<3>(v3, p.part, p.done, p.out, s_buf)) {
