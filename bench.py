@@ -152,6 +152,50 @@ def bench_probe(args):
     print(json.dumps(result))
 
 
+def bench_issue(args):
+    """Calibration: the rate at which the vector ALUs take instructions of one kind, by the number of wavefronts
+    a SIMD holds (the library's issue-probe kernel: no memory traffic, eight independent chains per lane)."""
+    import torch
+    import paper_2605_14929_amd as sop
+    dev = torch.device("cuda", 0)
+    ctx = sop.Context(0)
+    n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+    kinds = ["v_fmac_f32 (registers only)", "v_max_f32", "v_fma_f32 with a scalar-register operand", "v_cmp_lt_f32 + v_cndmask_b32",
+             "v_mul_f32", "v_mad_u32_u24", "v_fma_f32 + v_max_f32 alternating"]
+    iters = 4000
+    out = torch.empty(n_cu * 8 * 256, dtype=torch.float32, device=dev)
+    table = {}
+    for kind, name in enumerate(kinds):
+        row = {}
+        for wps in (1, 2, 3, 4, 6, 8):
+            for _ in range(3):
+                ctx.issue_probe(kind, wps, iters, 1.0, 0.125, out)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            reps = 5
+            for _ in range(reps):
+                ctx.issue_probe(kind, wps, iters, 1.0, 0.125, out)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            wave_instr = n_cu * 4 * wps * iters * 64.0
+            row[str(wps)] = {"ms": ms, "T_lane_ops_per_s": wave_instr * 64 / (ms * 1e-3) / 1e12,
+                             "cycles_per_instruction_per_simd_at_2.4GHz": ms * 1e-3 * 2.4e9 * n_cu * 4 / wave_instr}
+        table[name] = row
+    best = table[kinds[0]]["8"]["T_lane_ops_per_s"]
+    result = {
+        "metric": "vector-ALU lane-operations/sec (issue-rate calibration)", "value": best * 1e12, "unit": "lane-ops/s", "n_gpus": 1,
+        "steps": 5, "warmup": 3, "ms_per_step": table[kinds[0]]["8"]["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "sopk::issue_probe_kernel: 64 instructions of one kind per lane and iteration, by kind and by wavefronts per SIMD"},
+        "roofline": {"bound": "alu", "achieved": best, "peak": VALU_PEAK_TLOPS, "unit": "T lane-ops/s", "frac": best / VALU_PEAK_TLOPS,
+                     "traffic": None, "kernel": "sopk::issue_probe_kernel<0>"},
+        "by_kind_and_wavefronts_per_simd": table,
+    }
+    print(json.dumps(result))
+
+
 def bench_dd(args):
     """Statistics pass of the data-derived codebook on the headline layer (whole layer, 4096 bins):
     every weight is read once and adds its channel norm to one histogram bin."""
@@ -505,7 +549,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish", "model", "layer_search", "read_probe"],
+    ap.add_argument("--workload", default="pair_search", choices=["pair_search", "dd_histogram", "scale_histogram", "layer_scope", "finish", "model", "layer_search", "read_probe", "issue_probe"],
                     help="pair_search (default): the headline six-atom search; dd_histogram: the statistics pass of the "
                          "data-derived codebook on the same layer; scale_histogram: the statistics pass of the per-layer "
                          "scale shift on the same layer; layer_scope: E4M3 weights with one power-of-two scale for the layer; finish: block ranking and pools, "
@@ -528,6 +572,8 @@ def main():
 
     if args.workload == "read_probe":
         return bench_probe(args)
+    if args.workload == "issue_probe":
+        return bench_issue(args)
     if args.workload == "dd_histogram":
         return bench_dd(args)
     if args.workload == "scale_histogram":

@@ -119,6 +119,7 @@ def lib():
                                             C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_sum_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.sop_read_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        L.sop_issue_probe.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float, C.c_void_p, C.POINTER(C.c_int), C.c_void_p]
         L.sop_pair_search_layers.argtypes = [C.c_void_p, C.POINTER(_Layer), C.c_int, C.c_int, C.c_int, ScaleFmt, C.c_int,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.sop_partition.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -387,6 +388,23 @@ class Context:
             out = torch.empty(2048, dtype=torch.int32, device=x.device)
         st = torch.cuda.current_stream(x.device).cuda_stream if stream is None else stream
         _check(lib().sop_read_probe(self._h, C.c_void_p(x.data_ptr()), x.numel() * x.element_size(), C.c_void_p(out.data_ptr()), C.c_void_p(st)), self._h)
+        return out
+
+    def issue_probe(self, kind: int, waves_per_simd: int, iters: int, a: float = 0.5, b: float = 0.25, out=None, stream=None):
+        """sop_issue_probe: returns the [workgroups * 256] float32 device tensor of per-lane chain sums."""
+        import torch
+        dev = torch.device("cuda", self.device)
+        n = torch.cuda.get_device_properties(dev).multi_processor_count * int(waves_per_simd) * 256
+        if out is None:
+            out = torch.empty(n, dtype=torch.float32, device=dev)
+        elif out.numel() < n or out.dtype != torch.float32 or not out.is_cuda:
+            raise SopError(1, "out must be a CUDA float32 tensor of workgroups * 256 elements")
+        st = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        nwg = C.c_int(0)
+        _check(lib().sop_issue_probe(self._h, int(kind), int(waves_per_simd), int(iters), float(a), float(b),
+                                     C.c_void_p(out.data_ptr()), C.byref(nwg), C.c_void_p(st)), self._h)
+        if nwg.value * 256 != n:
+            raise SopError(6, "the library counts another number of compute units than PyTorch")
         return out
 
     def pair_search_layers(self, layers, g, fmt: ScaleFmt, metric: int = SEL_WSE, shifts=None, want_sel: bool = False, stream=None):
