@@ -125,6 +125,27 @@ __device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, f
 // ARGMAX: the scale maps the block's largest-magnitude element onto the endpoint of larger magnitude
 // and its sign follows from the two signs (per lane, returned in neg_out); otherwise the absmax rule
 // for the sign given in `negative`.
+// Scale of one (group, sign) without the scaled weights: code q, signed scale ss, signed reciprocal rr, and whether the
+// scaled weights may leave the bin table (see prepare_sign).
+struct ScalePrep { int q; float ss, rr; bool nonzero, beyond; };
+__device__ __forceinline__ ScalePrep prepare_scale(float pmax, float nmax, bool negative, int a, const KParams& p, const Switches& sw,
+                                                   const float2* __restrict__ s_tab, const float4* __restrict__ s_gpar)
+{
+    const float4 gp = s_gpar[2 * a];                   // (t+, -t-, bin scale, bin offset): same address in every lane
+    const float tp = gp.x, tn = gp.y;
+    const bool unit_p = (sw.unit_tpos >> a) & 1u, unit_n = (sw.unit_tneg >> a) & 1u;
+    const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp, unit_n, unit_p) : ideal_scale(pmax, nmax, tp, tn, unit_p, unit_n);
+    ScalePrep r;
+    r.q = encode_scale(sstar * p.pow2k, p);
+    float s, rinv;
+    decode_scale(r.q, p, s_tab, s, rinv);
+    r.ss = negative ? -s : s;
+    r.nonzero = s > 0.0f;
+    r.rr = negative ? -rinv : rinv;
+    r.beyond = !(sstar * rinv <= SOP_K_BIN_SAFE);
+    return r;
+}
+
 template <int EPL, bool ARGMAX>
 __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, float nmax, bool negative, int a,
                                              const KParams& p, const Switches& sw, const float2* __restrict__ s_tab,
@@ -173,6 +194,29 @@ __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, 
     }
 }
 
+// Where an element pass takes a scaled weight and the LDS address of its bin record from: arrays filled by
+// prepare_sign (a scale group's atoms share them), or formed on the spot from the weight and the scale's reciprocal
+// (signed scale words: the arrays of two signs would cost a wavefront per SIMD in registers, and with every atom
+// evaluated under two scales there is little left to share).  Same arithmetic either way.
+template <int EPL>
+struct ArrSrc {
+    const float (&x)[EPL];
+    const uint32_t (&boff)[EPL];
+    __device__ __forceinline__ void get(int i, float& xo, uint32_t& bo) const { xo = x[i]; bo = boff[i]; }
+};
+template <int EPL, bool CLAMP>
+struct FlySrc {
+    const float (&w)[EPL];
+    float rr, sc, off, lo, hi;
+    uint32_t lds_neg;
+    __device__ __forceinline__ void get(int i, float& xo, uint32_t& bo) const
+    {
+        xo = w[i] * rr;
+        const float xc = CLAMP ? __builtin_amdgcn_fmed3f(xo, lo, hi) : xo;
+        bo = __umul24(__float_as_uint(__fmaf_rn(xc, sc, off)), SOP_K_BIN_BYTES) + lds_neg;
+    }
+};
+
 // Sums of one (atom, sign) candidate over the lane's elements, before the cross-lane tree.
 struct Sums {
     float err;    // decision score of metrics WSE / MSE (and the blk_err output)
@@ -214,9 +258,8 @@ __device__ __forceinline__ void put_code(uint32_t (&codes)[EPL / 4], int i, uint
 // where a codebook under the negative scale sign and its sign-negated copy under the positive sign part ways):
 // it is the running minimum of the exclusive-or of the two bit patterns (a boundary at +0 would miss a weight
 // of -0: the host marks no copies for a codebook with such a boundary).
-template <int EPL, int METRIC, bool CODES, bool TIES = false>
-__device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float (&cb)[EPL], const float (&x)[EPL],
-                                              const uint32_t (&boff)[EPL], float ss, int a,
+template <int EPL, int METRIC, bool CODES, bool TIES = false, class SRC>
+__device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float (&cb)[EPL], const SRC& src, float ss, int a,
                                               bool wide_codes, uint32_t (&codes)[EPL / 4], uint32_t* tie = nullptr)
 {
     float e0 = 0.0f, e1 = 0.0f, wd = 0.0f, ew = 0.0f;
@@ -227,13 +270,18 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
 #pragma unroll
     for (int i0 = 0; i0 < EPL; i0 += 4) {
         Rec r[4];
+        float xe[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = read_rec<CODES>(boff[i0 + j], a);
+        for (int j = 0; j < 4; ++j) {
+            uint32_t bo;
+            src.get(i0 + j, xe[j], bo);
+            r[j] = read_rec<CODES>(bo, a);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int i = i0 + j;
-            const bool up = x[i] > r[j].thr;
-            if constexpr (TIES) *tie = min(*tie, __float_as_uint(x[i]) ^ __float_as_uint(r[j].thr));
+            const bool up = xe[j] > r[j].thr;
+            if constexpr (TIES) *tie = min(*tie, __float_as_uint(xe[j]) ^ __float_as_uint(r[j].thr));
             const float yv = up ? r[j].yhi : r[j].ylo;
             const float d = __fmaf_rn(-ss, yv, w[i]);
             const float cd = cb[i] * d;
@@ -254,9 +302,8 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
 // Element pass, DIRECT form with the decision sums of metric COS:
 //   w^ = fl(ss*y), num = sum fma(fl(c*w), w^), den = sum fma(fl(c*w^), w^), chunks of 8 and the tree;
 // err is formed as well when WANT_ERR (the blk_err output).
-template <int EPL, bool CODES, bool WANT_ERR, bool TIES = false>
-__device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (&cb)[EPL], const float (&x)[EPL],
-                                            const uint32_t (&boff)[EPL], float ss, int a,
+template <int EPL, bool CODES, bool WANT_ERR, bool TIES = false, class SRC>
+__device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (&cb)[EPL], const SRC& src, float ss, int a,
                                             bool wide_codes, uint32_t (&codes)[EPL / 4], uint32_t* tie = nullptr)
 {
     float e0 = 0.0f, e1 = 0.0f, n0 = 0.0f, n1 = 0.0f, d0 = 0.0f, d1 = 0.0f;
@@ -267,13 +314,18 @@ __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (
 #pragma unroll
     for (int i0 = 0; i0 < EPL; i0 += 4) {
         Rec r[4];
+        float xe[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = read_rec<CODES>(boff[i0 + j], a);
+        for (int j = 0; j < 4; ++j) {
+            uint32_t bo;
+            src.get(i0 + j, xe[j], bo);
+            r[j] = read_rec<CODES>(bo, a);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int i = i0 + j;
-            const bool up = x[i] > r[j].thr;
-            if constexpr (TIES) *tie = min(*tie, __float_as_uint(x[i]) ^ __float_as_uint(r[j].thr));
+            const bool up = xe[j] > r[j].thr;
+            if constexpr (TIES) *tie = min(*tie, __float_as_uint(xe[j]) ^ __float_as_uint(r[j].thr));
             const float yv = up ? r[j].yhi : r[j].ylo;
             const float what = ss * yv;
             const float cw = cb[i] * w[i];
@@ -297,16 +349,18 @@ __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (
 
 // Cosine inputs straight from the codebook values in the scaled domain, where the block scale
 // cancels: cos = sign(s) <w,y>_c / sqrt(||w||_c^2 ||y||_c^2).  Used when the residual form would cancel.
-template <int EPL, int LPB>
-__device__ __forceinline__ void direct_cosine_sums(const float (&cb)[EPL], const float (&w)[EPL], const float (&x)[EPL],
-                                                   const uint32_t (&boff)[EPL], bool nonzero, bool negative,
+template <int EPL, int LPB, class SRC>
+__device__ __forceinline__ void direct_cosine_sums(const float (&cb)[EPL], const float (&w)[EPL], const SRC& src, bool nonzero, bool negative,
                                                    int a, float& ny_out, float& dy_out)
 {
     float ny = 0.0f, dy = 0.0f;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        const Rec r = read_rec<false>(boff[i], a);
-        const float yv = x[i] > r.thr ? r.yhi : r.ylo;
+        float xe;
+        uint32_t bo;
+        src.get(i, xe, bo);
+        const Rec r = read_rec<false>(bo, a);
+        const float yv = xe > r.thr ? r.yhi : r.ylo;
         ny = __fmaf_rn(cb[i] * w[i], yv, ny);
         dy = __fmaf_rn(cb[i], yv * yv, dy);
     }
@@ -765,25 +819,31 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         // q = num*|num| (COS, 0 for a zero reconstruction), den (COS only, 1 for a zero reconstruction), 1 - cos
         float score[SOP_K_MAXA], den[SOP_K_MAXA];
         int dlt[SOP_K_MAXA];
-        // state of the current scale group: positive sign, and negative sign for signed scale words
-        int gq = 0, gq2 = 0;
-        float gss = 0.0f, gss2 = 0.0f;
-        bool gnz = false, gnz2 = false, gneg = false, gneg2 = false;
-        float gx[EPL], gx2[SIGNED ? EPL : 1];
-        uint32_t gboff[EPL], gboff2[SIGNED ? EPL : 1];
+        // state of the current scale group: scale code, scale, scaled weights and the addresses of their bin records.
+        // A signed scale word keeps the scale of both signs instead and forms scaled weights and addresses inside the
+        // element pass (FlySrc): the arrays of two signs would cost 64 registers and with them a wavefront per SIMD.
+        int gq = 0;
+        float gss = 0.0f;
+        bool gnz = false, gneg = false;
+        float gx[SIGNED ? 1 : EPL];
+        uint32_t gboff[SIGNED ? 1 : EPL];
+        ScalePrep spP = {0, 0.0f, 0.0f, false, false}, spM = {0, 0.0f, 0.0f, false, false};
         int cur_gid = -1;                              // scale group the state above belongs to (wave-uniform)
-        // Signed scale word: both candidates (positive, negative scale sign) of the atom before, kept for an atom
-        // that is its sign-negated copy.  Codebook -a under the positive sign reconstructs what a does under the
+        // Signed scale word: the two candidates of the atom before (0: positive scale sign, 1: negative), kept for an
+        // atom that is its sign-negated copy.  Codebook -a under the positive sign reconstructs what a does under the
         // negative sign, and the other way round (same scale code, same residuals bit for bit, codes k <-> N-1-k),
         // unless a scaled weight lies exactly on a code boundary: there the two resolve the tie differently.  So
-        // the copy takes over the kept candidates with their roles exchanged, unless some lane of the wavefront
-        // saw such a tie, in which case the copy is evaluated like any other atom.
-        // (plain scalars: copying the candidate structs would drag their padding bytes through scratch memory)
-        float pv_errP = 0.0f, pv_nyP = 0.0f, pv_dyP = 0.0f, pv_errM = 0.0f, pv_nyM = 0.0f, pv_dyM = 0.0f;
-        int pv_qp = 0, pv_qm = 0;
-        uint32_t pv_codesP[EPL / 4], pv_codesM[EPL / 4];
+        // the copy takes over the kept candidates with their roles exchanged (the wave-uniform flag f0neg: candidate
+        // 0 is the negative sign), unless some lane of the wavefront saw such a tie, in which case the copy is
+        // evaluated like any other atom.
+        // (plain scalars: copying candidate structs would drag their padding bytes through scratch memory)
+        float pv_err0 = 0.0f, pv_ny0 = 0.0f, pv_dy0 = 0.0f, pv_err1 = 0.0f, pv_ny1 = 0.0f, pv_dy1 = 0.0f;
+        float pv_rn0 = 0.0f, pv_rd0 = 0.0f, pv_rn1 = 0.0f, pv_rd1 = 0.0f;   // sums of the ranking score (emit mode)
+        int pv_q0 = 0, pv_q1 = 0;
+        uint32_t pv_codes0[EPL / 4], pv_codes1[EPL / 4];
+        bool pv_f0neg = false;                         // wave-uniform: the kept candidate 0 is the negative sign (it was kept by a copy)
         bool pv_tie = true;                            // wave-uniform: the kept candidates may not be taken over
-        bool pv_raw = false;                           // wave-uniform: the kept cosine sums are the direct ones (not scaled)
+        bool pv_raw0 = false, pv_raw1 = false;         // wave-uniform: the kept cosine sums are the direct ones (not scaled)
 
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
@@ -794,103 +854,142 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 const int gid = (int)((sw.gid >> (4 * a)) & 15u);
                 if (!derived && gid != cur_gid) {
                     cur_gid = gid;
-                    prepare_sign<EPL, ARGMAX>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff, gneg);
-                    if constexpr (SIGNED) prepare_sign<EPL, false>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, gq2, gss2, gnz2, gx2, gboff2, gneg2);
+                    if constexpr (SIGNED) {
+                        spP = prepare_scale(pmax, nmax, false, a, p, sw, s_tab, s_gpar);
+                        spM = prepare_scale(pmax, nmax, true, a, p, sw, s_tab, s_gpar);
+                    } else {
+                        prepare_sign<EPL, ARGMAX>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff, gneg);
+                    }
                 }
                 const bool wide = EMIT && ((sw.wide >> a) & 1u);
                 uint32_t codes[EPL / 4];
                 Cand best;
                 int q = gq;
                 bool neg = ARGMAX ? gneg : false;
-                bool raw = false;                      // wave-uniform: best.ny, best.dy are raw sums (else multiplied by nsc.sc)
+                bool raw = false;                      // best.ny, best.dy are raw sums (else multiplied by nsc.sc); per lane for signed words
+                float rk_num = 0.0f, rk_dn = 0.0f;     // sums of the ranking score of the chosen sign (signed words, emit mode)
                 if constexpr (SIGNED) {
-                    // ---- both signs of the scale: candidate P (positive) and candidate M (negative) ----
-                    float errP, nyP, dyP, errM, nyM, dyM;
-                    int qp, qm;
-                    uint32_t codesP[EPL / 4], codesM[EPL / 4];
+                    // ---- both signs of the scale: candidate 0 (the positive sign; the negative one when f0neg) and candidate 1 ----
+                    float err0, ny0, dy0, err1, ny1, dy1, rn0 = 0.0f, rd0 = 0.0f, rn1 = 0.0f, rd1 = 0.0f;
+                    int q0, q1;
+                    bool raw0, raw1, f0neg;
+                    uint32_t codes0[EPL / 4], codes1[EPL / 4];
                     // codes of the mirrored codebook: N-1-k in every field (no borrows: every field holds at most N-1)
                     const uint32_t cmask = (uint32_t)(p.nent[a] - 1) * (wide ? 0x01010101u : 0x11111111u);
                     if (derived) {
-                        errP = pv_errM; nyP = pv_nyM; dyP = pv_dyM;
-                        errM = pv_errP; nyM = pv_nyP; dyM = pv_dyP;
-                        qp = pv_qm; qm = pv_qp;
+                        err0 = pv_err0; ny0 = pv_ny0; dy0 = pv_dy0; err1 = pv_err1; ny1 = pv_ny1; dy1 = pv_dy1;
+                        rn0 = pv_rn0; rd0 = pv_rd0; rn1 = pv_rn1; rd1 = pv_rd1;
+                        q0 = pv_q0; q1 = pv_q1; raw0 = pv_raw0; raw1 = pv_raw1;
+                        f0neg = !pv_f0neg;                 // what was the original's negative sign is the copy's positive one
                         if (EMIT) {
 #pragma unroll
-                            for (int j = 0; j < EPL / 4; ++j) { codesP[j] = cmask - pv_codesM[j]; codesM[j] = cmask - pv_codesP[j]; }
+                            for (int j = 0; j < EPL / 4; ++j) { codes0[j] = cmask - pv_codes0[j]; codes1[j] = cmask - pv_codes1[j]; }
                         }
                     } else {
                         uint32_t tie = 0xFFFFFFFFu;
-                        bool weakP, weakM;
-                        qp = gq; qm = gq2;
-                        {
-                            Cand t;
-                            if constexpr (METRIC == 1) t = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT, true>(w, cb, gx, gboff, gss, a, wide, codesP, &tie));
-                            else t = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT, true>(w, cb, gx, gboff, gss, a, wide, codesP, &tie), nsc);
-                            errP = t.err; nyP = t.ny; dyP = t.dy; weakP = t.weak;
-                        }
+                        f0neg = false;
+                        // one sign of the scale: the atom's element pass with scaled weights formed on the spot
+                        const float4 gpar = s_gpar[2 * a];             // (t+, -t-, bin scale, bin offset): same address in every lane
+                        auto eval_sign = [&](const ScalePrep& sp, const bool sgn, float& err, float& ny, float& dy, int& qq, bool& rawf,
+                                             uint32_t (&cds)[EPL / 4], float& rn, float& rd) {
+                            qq = sp.q;
+                            auto run = [&](const auto& src) {
+                                Cand t;
+                                if constexpr (METRIC == 1) t = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT, true>(w, cb, src, sp.ss, a, wide, cds, &tie));
+                                else t = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT, true>(w, cb, src, sp.ss, a, wide, cds, &tie), nsc);
+                                err = t.err; ny = t.ny; dy = t.dy;
+                                rawf = METRIC == 1;
+                                if constexpr (METRIC != 1) {
+                                    // the residual form is accurate while the reconstruction carries a fair share of the block's
+                                    // norm; otherwise the whole wavefront recomputes this candidate's cosine sums directly
+                                    if (__builtin_expect(__any(t.weak) != 0, 0)) {
+                                        direct_cosine_sums<EPL, LPB>(cb, w, src, sp.nonzero, sgn, a, ny, dy);
+                                        rawf = true;
+                                    }
+                                }
+                                if constexpr (EMIT) {
+                                    if (p.blk_rank) {
+                                        if constexpr (METRIC == 1) { rn = t.ny; rd = t.dy; }
+                                        else {
+                                            uint32_t nocodes[EPL / 4];
+                                            const Cand c1 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, src, sp.ss, a, false, nocodes));
+                                            rn = c1.ny; rd = c1.dy;
+                                        }
+                                    }
+                                }
+                            };
+                            // the table covers a scale rounded down by up to the factor SOP_K_BIN_SAFE; beyond it (the scale word
+                            // saturated) the whole wavefront clamps its scaled weights into the table's range
+                            if (__builtin_expect(__any(sp.beyond) != 0, 0)) {
+                                const float4 g2 = s_gpar[2 * a + 1];       // (table range low, high, -, -)
+                                run(FlySrc<EPL, true>{w, sp.rr, gpar.z, gpar.w, g2.x, g2.y, lds_neg});
+                            } else {
+                                run(FlySrc<EPL, false>{w, sp.rr, gpar.z, gpar.w, 0.0f, 0.0f, lds_neg});
+                            }
+                        };
+                        eval_sign(spP, false, err0, ny0, dy0, q0, raw0, codes0, rn0, rd0);
                         // a codebook that is its own sign-negated copy reconstructs the same under both signs (away
                         // from ties), and an equal candidate never replaces the positive sign
                         if (((sw.selfsym >> a) & 1u) && !__any(tie == 0u && valid)) {
-                            errM = errP; nyM = nyP; dyM = dyP; weakM = weakP;
+                            err1 = err0; ny1 = ny0; dy1 = dy0; q1 = spM.q; raw1 = raw0; rn1 = rn0; rd1 = rd0;
                             if (EMIT) {
 #pragma unroll
-                                for (int j = 0; j < EPL / 4; ++j) codesM[j] = cmask - codesP[j];
+                                for (int j = 0; j < EPL / 4; ++j) codes1[j] = cmask - codes0[j];
                             }
                         } else {
-                            Cand t;
-                            if constexpr (METRIC == 1) t = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT, true>(w, cb, gx2, gboff2, gss2, a, wide, codesM, &tie));
-                            else t = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT, true>(w, cb, gx2, gboff2, gss2, a, wide, codesM, &tie), nsc);
-                            errM = t.err; nyM = t.ny; dyM = t.dy; weakM = t.weak;
+                            eval_sign(spM, true, err1, ny1, dy1, q1, raw1, codes1, rn1, rd1);
                         }
                         pv_tie = __any(tie == 0u && valid) != 0;
-                        if constexpr (METRIC != 1) {
-                            // the residual form is accurate while the reconstruction carries a fair share of the
-                            // block's norm; otherwise the whole wavefront recomputes both candidates' cosine sums directly
-                            if (__builtin_expect(__any(weakP || weakM) != 0, 0)) {
-                                direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, false, a, nyP, dyP);
-                                direct_cosine_sums<EPL, LPB>(cb, w, gx2, gboff2, gnz2, true, a, nyM, dyM);
-                                pv_raw = true;
-                            } else pv_raw = false;
-                        }
                     }
-                    pv_errP = errP; pv_nyP = nyP; pv_dyP = dyP; pv_errM = errM; pv_nyM = nyM; pv_dyM = dyM;
-                    pv_qp = qp; pv_qm = qm;
+                    pv_err0 = err0; pv_ny0 = ny0; pv_dy0 = dy0; pv_err1 = err1; pv_ny1 = ny1; pv_dy1 = dy1;
+                    pv_q0 = q0; pv_q1 = q1; pv_raw0 = raw0; pv_raw1 = raw1; pv_f0neg = f0neg;
                     if (EMIT) {
+                        pv_rn0 = rn0; pv_rd0 = rd0; pv_rn1 = rn1; pv_rd1 = rd1;
 #pragma unroll
-                        for (int j = 0; j < EPL / 4; ++j) { pv_codesP[j] = codesP[j]; pv_codesM[j] = codesM[j]; }
+                        for (int j = 0; j < EPL / 4; ++j) { pv_codes0[j] = codes0[j]; pv_codes1[j] = codes1[j]; }
                     }
+                    // the negative sign only when strictly better: candidate 1 is taken when it is strictly better, or, if it
+                    // is the positive sign (f0neg), when it is at least as good.  Both comparisons are formed as lane masks
+                    // and the wave-uniform flag picks one of them in scalar registers.
+                    bool pick1;
                     if constexpr (METRIC == 1) {
-                        const float bqp = dyP > 0.0f ? nyP * fabsf(nyP) : 0.0f, bdp = dyP > 0.0f ? dyP : 1.0f;
-                        const float bqm = dyM > 0.0f ? nyM * fabsf(nyM) : 0.0f, bdm = dyM > 0.0f ? dyM : 1.0f;
-                        neg = bqm * bdp > bqp * bdm;
-                        score[a] = neg ? bqm : bqp;
-                        den[a] = neg ? bdm : bdp;
+                        const float bq0 = dy0 > 0.0f ? ny0 * fabsf(ny0) : 0.0f, bd0 = dy0 > 0.0f ? dy0 : 1.0f;
+                        const float bq1 = dy1 > 0.0f ? ny1 * fabsf(ny1) : 0.0f, bd1 = dy1 > 0.0f ? dy1 : 1.0f;
+                        const unsigned long long gt = __builtin_amdgcn_ballot_w64(bq1 * bd0 > bq0 * bd1);
+                        const unsigned long long ge = __builtin_amdgcn_ballot_w64(!(bq0 * bd1 > bq1 * bd0));
+                        pick1 = __builtin_amdgcn_inverse_ballot_w64(f0neg ? ge : gt);
+                        score[a] = pick1 ? bq1 : bq0;
+                        den[a] = pick1 ? bd1 : bd0;
                     } else {
-                        neg = errM < errP;
-                        score[a] = neg ? errM : errP;
+                        const unsigned long long lt = __builtin_amdgcn_ballot_w64(err1 < err0);
+                        const unsigned long long le = __builtin_amdgcn_ballot_w64(!(err0 < err1));
+                        pick1 = __builtin_amdgcn_inverse_ballot_w64(f0neg ? le : lt);
+                        score[a] = pick1 ? err1 : err0;
                     }
-                    best.err = neg ? errM : errP;
-                    best.ny = neg ? nyM : nyP;
-                    best.dy = neg ? dyM : dyP;
+                    neg = pick1 != f0neg;
+                    best.err = pick1 ? err1 : err0;
+                    best.ny = pick1 ? ny1 : ny0;
+                    best.dy = pick1 ? dy1 : dy0;
                     best.weak = false;
-                    raw = METRIC == 1 || pv_raw;
-                    q = neg ? qm : qp;
+                    raw = pick1 ? raw1 : raw0;
+                    q = pick1 ? q1 : q0;
                     if (EMIT) {
+                        rk_num = pick1 ? rn1 : rn0; rk_dn = pick1 ? rd1 : rd0;
 #pragma unroll
-                        for (int j = 0; j < EPL / 4; ++j) codes[j] = neg ? codesM[j] : codesP[j];
+                        for (int j = 0; j < EPL / 4; ++j) codes[j] = pick1 ? codes1[j] : codes0[j];
                     }
                 } else if constexpr (METRIC == 1) {
-                    best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, gx, gboff, gss, a, wide, codes));
+                    best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes));
                     score[a] = best.dy > 0.0f ? best.ny * fabsf(best.ny) : 0.0f;
                     den[a] = best.dy > 0.0f ? best.dy : 1.0f;
                     raw = true;
                 } else {
-                    best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, gx, gboff, gss, a, wide, codes), nsc);
+                    best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes), nsc);
                     // the residual form is accurate while the reconstruction carries a fair share of
                     // the block's norm; otherwise the whole wavefront recomputes this atom directly
                     if (__builtin_expect(__any(best.weak) != 0, 0)) {
                         float ny1, dy1;
-                        direct_cosine_sums<EPL, LPB>(cb, w, gx, gboff, gnz, ARGMAX ? gneg : false, a, ny1, dy1);
+                        direct_cosine_sums<EPL, LPB>(cb, w, ArrSrc<EPL>{gx, gboff}, gnz, ARGMAX ? gneg : false, a, ny1, dy1);
                         best.ny = ny1;
                         best.dy = dy1;
                         raw = true;
@@ -920,18 +1019,12 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                         // the block's tree sums num = <w,w^>_c, den = ||w^||_c^2 (chunks of 8, balanced tree) and wn:
                         // fl(fl(num / wn) * fl(|num| / den)), 1 for a block without weighted norm, 0 for a zero reconstruction
                         float num, dn;
-                        if constexpr (METRIC == 1) { num = ny_raw; dn = dy_raw; }
+                        if constexpr (SIGNED) { num = rk_num; dn = rk_dn; }
+                        else if constexpr (METRIC == 1) { num = ny_raw; dn = dy_raw; }
                         else {
                             uint32_t nocodes[EPL / 4];
-                            const int slot = derived ? a - 1 : a;            // a copy reads its original's table entries
-                            const Cand c1 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx, gboff, gss, slot, false, nocodes));
+                            const Cand c1 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, false, nocodes));
                             num = c1.ny; dn = c1.dy;
-                            if constexpr (SIGNED) {
-                                // (for a copy the positive sign is the original's negative one)
-                                const Cand c2 = finish_direct<LPB>(eval_direct<EPL, false, false>(w, cb, gx2, gboff2, gss2, slot, false, nocodes));
-                                const bool second = neg != derived;
-                                num = second ? c2.ny : num; dn = second ? c2.dy : dn;
-                            }
                         }
                         const float rank = wn > 0.0f ? (dn > 0.0f ? (num / wn) * (fabsf(num) / dn) : 0.0f) : 1.0f;
                         if (leader) p.blk_rank[ua * p.Nb + blk] = rank;
@@ -1078,13 +1171,13 @@ constexpr int occ_for(int epl, int sign_mode, bool emit, int na, int metric)
 {
     if (na == 2) {                                   // one or two atoms: fewer registers
         if (epl == 8) return (sign_mode == 1 && emit) ? 3 : 4;
-        return (sign_mode == 1 || emit) ? 2 : 3;       // (with the per-block planes a lane of 16 elements needs more than 168 registers)
+        return emit ? 2 : 3;                           // (with the per-block planes a lane of 16 elements needs more than 168 registers)
     }
     if (epl == 8) {
         if (sign_mode == 1) return emit ? 2 : 3;
         return (emit || na == 8) ? 3 : 4;
     }
-    if (sign_mode == 1) return emit ? 1 : 2;
+    if (sign_mode == 1) return emit ? (na == 8 ? 1 : 2) : (na == 8 ? 2 : 3);
     if (emit) return 2;
     return (na == 8 || metric == 1) ? 2 : 3;        // the cosine metric keeps two more sums per candidate alive
 }
