@@ -825,8 +825,9 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         int gq = 0;
         float gss = 0.0f;
         bool gnz = false, gneg = false;
-        float gx[SIGNED ? 1 : EPL];
-        uint32_t gboff[SIGNED ? 1 : EPL];
+        constexpr bool FLY = SIGNED && EPL == 16;       // (a lane of 8 elements has the registers for both signs' arrays)
+        float gx[FLY ? 1 : EPL], gx2[(SIGNED && !FLY) ? EPL : 1];
+        uint32_t gboff[FLY ? 1 : EPL], gboff2[(SIGNED && !FLY) ? EPL : 1];
         ScalePrep spP = {0, 0.0f, 0.0f, false, false}, spM = {0, 0.0f, 0.0f, false, false};
         int cur_gid = -1;                              // scale group the state above belongs to (wave-uniform)
         // Signed scale word: the two candidates of the atom before (0: positive scale sign, 1: negative), kept for an
@@ -854,9 +855,13 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                 const int gid = (int)((sw.gid >> (4 * a)) & 15u);
                 if (!derived && gid != cur_gid) {
                     cur_gid = gid;
-                    if constexpr (SIGNED) {
+                    if constexpr (FLY) {
                         spP = prepare_scale(pmax, nmax, false, a, p, sw, s_tab, s_gpar);
                         spM = prepare_scale(pmax, nmax, true, a, p, sw, s_tab, s_gpar);
+                    } else if constexpr (SIGNED) {
+                        bool unused;
+                        prepare_sign<EPL, false>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, spP.q, spP.ss, spP.nonzero, gx, gboff, unused);
+                        prepare_sign<EPL, false>(w, pmax, nmax, true, a, p, sw, s_tab, s_gpar, lds_neg, spM.q, spM.ss, spM.nonzero, gx2, gboff2, unused);
                     } else {
                         prepare_sign<EPL, ARGMAX>(w, pmax, nmax, false, a, p, sw, s_tab, s_gpar, lds_neg, gq, gss, gnz, gx, gboff, gneg);
                     }
@@ -890,7 +895,8 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                         f0neg = false;
                         // one sign of the scale: the atom's element pass with scaled weights formed on the spot
                         const float4 gpar = s_gpar[2 * a];             // (t+, -t-, bin scale, bin offset): same address in every lane
-                        auto eval_sign = [&](const ScalePrep& sp, const bool sgn, float& err, float& ny, float& dy, int& qq, bool& rawf,
+                        auto eval_sign = [&](const ScalePrep& sp, const bool sgn, const auto& xarr, const auto& barr,
+                                             float& err, float& ny, float& dy, int& qq, bool& rawf,
                                              uint32_t (&cds)[EPL / 4], float& rn, float& rd) {
                             qq = sp.q;
                             auto run = [&](const auto& src) {
@@ -920,14 +926,16 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                             };
                             // the table covers a scale rounded down by up to the factor SOP_K_BIN_SAFE; beyond it (the scale word
                             // saturated) the whole wavefront clamps its scaled weights into the table's range
-                            if (__builtin_expect(__any(sp.beyond) != 0, 0)) {
+                            if constexpr (!FLY) {
+                                run(ArrSrc<EPL>{xarr, barr});
+                            } else if (__builtin_expect(__any(sp.beyond) != 0, 0)) {
                                 const float4 g2 = s_gpar[2 * a + 1];       // (table range low, high, -, -)
                                 run(FlySrc<EPL, true>{w, sp.rr, gpar.z, gpar.w, g2.x, g2.y, lds_neg});
                             } else {
                                 run(FlySrc<EPL, false>{w, sp.rr, gpar.z, gpar.w, 0.0f, 0.0f, lds_neg});
                             }
                         };
-                        eval_sign(spP, false, err0, ny0, dy0, q0, raw0, codes0, rn0, rd0);
+                        eval_sign(spP, false, gx, gboff, err0, ny0, dy0, q0, raw0, codes0, rn0, rd0);
                         // a codebook that is its own sign-negated copy reconstructs the same under both signs (away
                         // from ties), and an equal candidate never replaces the positive sign
                         if (((sw.selfsym >> a) & 1u) && !__any(tie == 0u && valid)) {
@@ -937,7 +945,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                                 for (int j = 0; j < EPL / 4; ++j) codes1[j] = cmask - codes0[j];
                             }
                         } else {
-                            eval_sign(spM, true, err1, ny1, dy1, q1, raw1, codes1, rn1, rd1);
+                            eval_sign(spM, true, gx2, gboff2, err1, ny1, dy1, q1, raw1, codes1, rn1, rd1);
                         }
                         pv_tie = __any(tie == 0u && valid) != 0;
                     }
