@@ -164,13 +164,14 @@ def bench_issue(args):
     ctx = sop.Context(0)
     n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
     kinds = ["v_fmac_f32 (registers only)", "v_max_f32", "v_fma_f32 with a scalar-register operand", "v_cmp_lt_f32 + v_cndmask_b32",
-             "v_mul_f32", "v_mad_u32_u24", "v_fma_f32 + v_max_f32 alternating"]
+             "v_mul_f32", "v_mad_u32_u24", "v_fma_f32 + v_max_f32 alternating", "v_add_f32", "v_and_b32", "v_add_u32", "v_lshrrev_b32",
+             "v_lshlrev_b32", "v_cvt_i32_f32", "v_med3_f32", "v_rcp_f32"]
     iters = 4000
     out = torch.empty(n_cu * 8 * 256, dtype=torch.float32, device=dev)
     table = {}
     for kind, name in enumerate(kinds):
         row = {}
-        for wps in (1, 2, 3, 4, 6, 8):
+        for wps in ((1, 2, 3, 4, 6, 8) if kind < 7 else (8,)):          # kinds 7..: the class only
             for _ in range(3):
                 ctx.issue_probe(kind, wps, iters, 1.0, 0.125, out)
             torch.cuda.synchronize()

@@ -907,7 +907,7 @@ extern "C" sop_status sop_issue_probe(sop_ctx* c, int kind, int waves_per_simd, 
 {
     if (!c) return SOP_EINVAL;
     if (kind < 0 || kind >= SOP_ISSUE_PROBE_KINDS || waves_per_simd < 1 || waves_per_simd > 8 || iters < 1 || iters > (1 << 20) || !out)
-        return fail(c, SOP_EINVAL, "sop_issue_probe: kind 0..6, waves_per_simd 1..8, iters 1..2^20, out not NULL");
+        return fail(c, SOP_EINVAL, "sop_issue_probe: kind 0..14, waves_per_simd 1..8, iters 1..2^20, out not NULL");
     if (reinterpret_cast<uintptr_t>(out) & 3u) return fail(c, SOP_EINVAL, "sop_issue_probe: misaligned pointer");
     const int n_wg = c->n_cu * waves_per_simd;
     if (n_wg_out) *n_wg_out = n_wg;

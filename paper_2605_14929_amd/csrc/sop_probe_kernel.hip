@@ -44,6 +44,8 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const uint4* __restrict
 //   kind 4  v_mul_f32   x, x, a
 //   kind 5  v_mad_u32_u24 x, x, a, b
 //   kind 6  v_fma_f32 then v_max_f32 on the same chain (one of each class, alternating)
+//   kinds 7..14  v_add_f32, v_and_b32, v_add_u32, v_lshrrev_b32, v_lshlrev_b32, v_cvt_i32_f32, v_med3_f32, v_rcp_f32
+//           (which class an instruction belongs to; their chain values are not meant to be checked)
 #define SOPK_ISSUE8(INS) \
     asm volatile(INS : "+v"(x0) : "v"(a), "v"(b), "s"(sa) : "vcc"); asm volatile(INS : "+v"(x1) : "v"(a), "v"(b), "s"(sa) : "vcc"); \
     asm volatile(INS : "+v"(x2) : "v"(a), "v"(b), "s"(sa) : "vcc"); asm volatile(INS : "+v"(x3) : "v"(a), "v"(b), "s"(sa) : "vcc"); \
@@ -67,7 +69,15 @@ __global__ __launch_bounds__(256) void issue_probe_kernel(float* __restrict__ ou
     else if (KIND == 3) { SOPK_ISSUE_BODY("v_cmp_lt_f32 vcc, %0, %1", "v_cndmask_b32 %0, %0, %2, vcc") }
     else if (KIND == 4) { SOPK_ISSUE_BODY("v_mul_f32 %0, %0, %1", "v_mul_f32 %0, %0, %1") }
     else if (KIND == 5) { SOPK_ISSUE_BODY("v_mad_u32_u24 %0, %0, %1, %2", "v_mad_u32_u24 %0, %0, %1, %2") }
-    else { SOPK_ISSUE_BODY("v_fma_f32 %0, %0, %1, %2", "v_max_f32 %0, %0, %2") }
+    else if (KIND == 6) { SOPK_ISSUE_BODY("v_fma_f32 %0, %0, %1, %2", "v_max_f32 %0, %0, %2") }
+    else if (KIND == 7) { SOPK_ISSUE_BODY("v_add_f32 %0, %0, %1", "v_add_f32 %0, %0, %2") }
+    else if (KIND == 8) { SOPK_ISSUE_BODY("v_and_b32 %0, %0, %1", "v_and_b32 %0, %0, %2") }
+    else if (KIND == 9) { SOPK_ISSUE_BODY("v_add_u32 %0, %0, %1", "v_add_u32 %0, %0, %2") }
+    else if (KIND == 10) { SOPK_ISSUE_BODY("v_lshrrev_b32 %0, 1, %0", "v_lshrrev_b32 %0, 1, %0") }
+    else if (KIND == 11) { SOPK_ISSUE_BODY("v_lshlrev_b32 %0, 1, %0", "v_lshlrev_b32 %0, 1, %0") }
+    else if (KIND == 12) { SOPK_ISSUE_BODY("v_cvt_i32_f32 %0, %0", "v_cvt_i32_f32 %0, %0") }
+    else if (KIND == 13) { SOPK_ISSUE_BODY("v_med3_f32 %0, %0, %1, %2", "v_med3_f32 %0, %0, %1, %2") }
+    else { SOPK_ISSUE_BODY("v_rcp_f32 %0, %0", "v_rcp_f32 %0, %0") }
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
 }
 
@@ -85,7 +95,15 @@ extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int iters, flo
     case 3: SOPK_IP(3); break;
     case 4: SOPK_IP(4); break;
     case 5: SOPK_IP(5); break;
-    default: SOPK_IP(6); break;
+    case 6: SOPK_IP(6); break;
+    case 7: SOPK_IP(7); break;
+    case 8: SOPK_IP(8); break;
+    case 9: SOPK_IP(9); break;
+    case 10: SOPK_IP(10); break;
+    case 11: SOPK_IP(11); break;
+    case 12: SOPK_IP(12); break;
+    case 13: SOPK_IP(13); break;
+    default: SOPK_IP(14); break;
     }
 #undef SOPK_IP
     return hipGetLastError();

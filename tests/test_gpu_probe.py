@@ -67,7 +67,7 @@ def test_issue_probe_values(kind, a, b):
 
 
 def test_issue_probe_argument_errors():
-    for bad in ((7, 1, 1), (-1, 1, 1), (0, 0, 1), (0, 9, 1), (0, 1, 0)):
+    for bad in ((15, 1, 1), (-1, 1, 1), (0, 0, 1), (0, 9, 1), (0, 1, 0)):
         with pytest.raises(sop.SopError) as e:
             ctx().issue_probe(*bad)
         assert e.value.status == 1
