@@ -38,7 +38,8 @@ typedef enum {
     SOP_OK = 0,
     SOP_EINVAL = 1,   /* null pointer, bad enum, misaligned buffer, bad pair list            */
     SOP_ESHAPE = 2,   /* M or K <= 0, g not in {8,16,32,64}, g does not divide K, ldw < K    */
-    SOP_EATOM  = 3,   /* atom not strictly ascending, < 2 or > 64 entries, not two-sided, NaN*/
+    SOP_EATOM  = 3,   /* atom not strictly ascending, < 2 or > 64 entries, not two-sided, NaN,
+                         or two code boundaries closer than 1/650 of the atom's range          */
     SOP_EFMT   = 4,   /* scale format or layer shift outside the supported range             */
     SOP_ENOMEM = 5,   /* workspace too small                                                 */
     SOP_EHIP   = 6    /* a HIP runtime call failed; see sop_last_error()                     */
@@ -109,6 +110,11 @@ sop_status sop_destroy(sop_ctx* ctx);
  * candidate codebooks, each atom and its sign negation being separate candidates).  atoms is a
  * HOST array of n_atoms <= SOP_MAX_ATOMS descriptors.  Builds value and midpoint tables (midpoint
  * = binary64 mean of neighbours rounded once to binary32) and uploads them synchronously.
+ * The kernel finds an element's code through a table over at most 1024 uniform bins of the scaled
+ * weight with at most one code boundary per bin: an atom with two boundaries (midpoints of
+ * neighbouring entries) closer than about 1/650 of its range is refused with SOP_EATOM.
+ * Weights and channel norms must be finite; per-block results are exact for weighted block norms
+ * sum(c w^2) within 2^-126 .. 2^126 (the cosine's value path rescales by the norm's exponent).
  * Resets the pair list to all pairs a < b in lexicographic order. */
 sop_status sop_set_alphabet(sop_ctx* ctx, const sop_atom* atoms, int n_atoms);
 
