@@ -673,7 +673,7 @@ def main():
         # the six-atom search is bound by vector-ALU instruction issue (the method's lane-operations take 34 us per launch
         # at the full-rate peak and twice that at the rate three wavefronts per SIMD reach, against 12 us of algorithmic
         # HBM traffic); the HBM view of the same launch is given beside it
-        "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "TFLOP/s",
+        "roofline": {"bound": "alu", "achieved": alg_ops / (ev_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TLOPS, "unit": "T lane-ops/s",
                      "frac": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_PEAK_TLOPS, "traffic": parse_traffic() if headline else None,
                      "traffic_source": "profiles/search_kernel_c3down_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)" if headline else None,
                      "frac_of_half_rate_class_peak": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_HALF_RATE_TLOPS,
