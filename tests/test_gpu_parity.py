@@ -110,6 +110,25 @@ def test_row_stride():
     check(W, c, tabs_for(["NF4", "SH4"]), 16, sop.fmt_by_name("UE4M4"), ldw=K + 64)
 
 
+@pytest.mark.parametrize("M,K,g,bf16", [(192, 1040, 16, True),    # 65 lanes a row: 64 rows walked as one fill 65 strips
+                                         (6, 1040, 16, False),     # 6 rows: two rows at a time at most
+                                         (7, 1040, 16, True),      # an odd number of rows: no folding
+                                         (48, 1032, 8, False),     # lanes of 8 elements, 129 a row
+                                         (40, 2112, 32, True),     # two lanes a block, 132 lanes a row
+                                         (16, 4160, 64, True)])    # four lanes a block, 260 lanes a row
+def test_rows_walked_as_one(M, K, g, bf16):
+    """Rows that lie back to back are walked several at a time where that fills the last 64-lane strip of a row better;
+    every per-block output keeps its place and the channel norm of a column is the one of its index within the true row."""
+    W = si.student_t_weights(M, K, 4.0, 9100 + M)
+    if bf16:
+        W = si.bf16_round(W)
+    c = si.channel_norms(K, 1.0, 9200 + K)
+    tabs = tabs_for(["NF4", "SH4", "-NF4"])
+    check(W, c, tabs, g, sop.fmt_by_name("UE4M4"), bf16=bf16)
+    check(W, c, tabs, g, sop.fmt_by_name("E4M3"), bf16=bf16)
+    check(W, c, tabs, g, sop.fmt_by_name("UE4M4"), bf16=bf16, ldw=K + 32)      # rows apart: no folding, same results
+
+
 def test_degenerate_blocks():
     rng = np.random.default_rng(9)
     M, K, g = 8, 512, 16
