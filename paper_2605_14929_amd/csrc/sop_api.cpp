@@ -753,7 +753,7 @@ extern "C" sop_status sop_pair_search_layers(sop_ctx* c, const sop_layer* layers
 // ------------------------------------------------------------------ data-derived codebook (DD atom)
 static sop_status dd_histogram_impl(sop_ctx* c, const void* W, sop_dtype dtype, int64_t M, int64_t K, int64_t ldw,
                                     const float* cn, int g, int n_bins, int64_t row_step, const uint8_t* block_mask, int n_levels,
-                                    int64_t* hist, void* stream)
+                                    int64_t* hist, void* stream, int n_planes = 1, int64_t plane_stride = 0)
 {
     if (!c) return SOP_EINVAL;
     if (!W || !hist) return fail(c, SOP_EINVAL, "sop_dd_histogram: W and hist must not be NULL");
@@ -764,7 +764,8 @@ static sop_status dd_histogram_impl(sop_ctx* c, const void* W, sop_dtype dtype, 
     if (!aligned16(W) || (ldw * esz) % 16 != 0) return fail(c, SOP_EINVAL, "W and its row stride must be multiples of 16 bytes");
     if (cn && !aligned16(cn)) return fail(c, SOP_EINVAL, "c must be 16-byte aligned");
     if (!dd_bins_ok(n_bins)) return fail(c, SOP_EINVAL, "n_bins must be a power of two within 64..8192");
-    if (n_levels < 0 || n_levels > 255 || (long long)std::max(n_levels, 1) * n_bins > SOP_K_DD_MAXBINS)
+    if (n_planes < 1 || (n_planes > 1 && n_levels < 1)) return fail(c, SOP_EINVAL, "several level planes need levels");
+    if (n_levels < 0 || n_levels > 255 || (long long)std::max(n_levels, 1) * n_planes * n_bins > SOP_K_DD_MAXBINS)
         return fail(c, SOP_EINVAL, "sop_dd_histogram_levels: n_levels * n_bins must not exceed 8192");
     if (n_levels > 0 && !block_mask) return fail(c, SOP_EINVAL, "sop_dd_histogram_levels: level_dev must not be NULL");
     if (reinterpret_cast<uintptr_t>(hist) & 7u) return fail(c, SOP_EINVAL, "hist must be 8-byte aligned");
@@ -772,6 +773,7 @@ static sop_status dd_histogram_impl(sop_ctx* c, const void* W, sop_dtype dtype, 
     const int epl = g < 16 ? g : 16;
     DdParams p;
     std::memset(&p, 0, sizeof(p));
+    p.n_planes = n_planes; p.plane_stride = plane_stride;
     p.W = W; p.c = cn; p.block_mask = block_mask; p.n_levels = n_levels; p.M = M; p.K = K; p.ldw = ldw; p.Bk = K / g;
     p.row_step = row_step; p.Ms = (M + row_step - 1) / row_step;
     p.strips = (K / epl + 63) / 64;
@@ -1195,12 +1197,16 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
             if (sop_status s = partition_levels_impl(c, d_rank, Nb, tops, n_p, 1, d_level, reinterpret_cast<float*>(base + L.tau),
                                                      reinterpret_cast<int64_t*>(base + L.na), A, stream)) return s;
         }
-        for (int a = 0; a < A; ++a) {
+        // one pass over the weights fills the pool histograms of as many atoms as the histogram pass has room for
+        const int per_pass = std::max(1, SOP_K_DD_MAXBINS / (n_p * bins));
+        for (int a = 0; a < A; a += per_pass) {
+            const int na = std::min(per_pass, A - a);
             if (!batch)
-                if (sop_status s = partition_levels_impl(c, d_rank + (size_t)a * Nb, Nb, tops, n_p, 1, d_level + a * lstride, reinterpret_cast<float*>(base + L.tau),
-                                                         reinterpret_cast<int64_t*>(base + L.na), 1, stream)) return s;
+                for (int b = a; b < a + na; ++b)
+                    if (sop_status s = partition_levels_impl(c, d_rank + (size_t)b * Nb, Nb, tops, n_p, 1, d_level + b * lstride, reinterpret_cast<float*>(base + L.tau),
+                                                             reinterpret_cast<int64_t*>(base + L.na), 1, stream)) return s;
             if (sop_status s = dd_histogram_impl(c, W, dtype, M, K, ldw, o->weighted_fit ? cn : nullptr, g, bins, 1, d_level + a * lstride, n_p,
-                                                 reinterpret_cast<int64_t*>(d_hist + (size_t)a * n_p * bins), stream)) return s;
+                                                 reinterpret_cast<int64_t*>(d_hist + (size_t)a * n_p * bins), stream, na, (int64_t)lstride)) return s;
         }
     }
     long long* h_hist = reinterpret_cast<long long*>(c->h_res);

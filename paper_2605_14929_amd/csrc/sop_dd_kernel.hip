@@ -11,7 +11,9 @@
 // Only rows 0, row_step, 2*row_step, ... enter (row_step = 1: the whole layer), and, when a block
 // mask is given, only blocks whose mask byte is non-zero.  With levels (the sweep over the partition
 // parameter of the per-layer search: nested fitting pools) the mask byte names one of L histograms, and
-// the result holds the L pool histograms: one pass over the weights serves every pool of the sweep.
+// the result holds the L pool histograms: one pass over the weights serves every pool of the sweep.  With several
+// level planes (one per codebook of the search: each ranks the blocks its own way) the same pass fills every
+// plane's histograms: the weights are read, normalised and binned once.
 //
 // Work mapping as in the search kernel: a lane owns min(g,16) consecutive elements of a row, a
 // wavefront walks down the rows of a 64-lane strip.  Each workgroup (16 wavefronts, one per compute
@@ -33,7 +35,8 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
     __shared__ float s_max[SOP_K_DD_THREADS / 64];
     __shared__ unsigned int s_flag;
     const int HB = p.n_bins;                                          // bins of one histogram
-    const int H = p.n_bins * (p.n_levels > 0 ? p.n_levels : 1);       // words of all the histograms of the call
+    const int NP = p.n_levels > 0 ? p.n_planes : 1;                   // level planes
+    const int H = p.n_bins * (p.n_levels > 0 ? p.n_levels : 1) * NP;  // words of all the histograms of the call
     for (int i = threadIdx.x; i < H; i += SOP_K_DD_THREADS) s_hist[i] = 0ull;
     // cmax = max_k c_k (order-independent), found by every workgroup for itself
     float cmax = 1.0f;
@@ -119,6 +122,30 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
         if (LPB >= 2) a = fmaxf(a, __shfl_xor(a, 1, 64));
         if (LPB >= 4) a = fmaxf(a, __shfl_xor(a, 2, 64));
         bool take = valid && a > 0.0f;
+        if (NP > 1) {
+            // several level planes: the bins are found once, every plane adds the block to the histogram of its level
+            if (take) {
+                const float r = 1.0f / a;
+                int bin[EPL];
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) {
+                    const float x = w[i] * r;
+                    const int b = (int)floorf(x * half + half);
+                    bin[i] = b < 0 ? 0 : (b > HB - 1 ? HB - 1 : b);
+                }
+                const long long blk = m * p.row_step * p.Bk + (strip * 64 + lane) / LPB;
+                for (int pl = 0; pl < NP; ++pl) {
+                    const int lv = p.block_mask[(long long)pl * p.plane_stride + blk];
+                    if (lv != 0) {
+                        const int hb = (pl * p.n_levels + min(lv, p.n_levels) - 1) * HB;
+#pragma unroll
+                        for (int i = 0; i < EPL; ++i) atomicAdd(&s_hist[hb + bin[i]], (unsigned long long)mass[i]);
+                    }
+                }
+            }
+            if (++m == p.Ms) { m = 0; ++strip; }
+            continue;
+        }
         int hbase = 0;                              // first word of the block's histogram
         if (p.block_mask && take) {                 // only the blocks of the pool enter
             const long long blk = m * p.row_step * p.Bk + (strip * 64 + lane) / LPB;
@@ -166,7 +193,7 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
             const int i = threadIdx.x + j * SOP_K_DD_THREADS;
             got[j] = i < H ? atomicExch(p.acc + i, 0ull) : 0ull;
         }
-        if (p.n_levels > 1) {
+        if (p.n_levels > 1 || NP > 1) {
             // nested pools: histogram j of the result is the sum of the level histograms j .. L-1
             __syncthreads();
 #pragma unroll
@@ -175,9 +202,11 @@ __global__ __launch_bounds__(SOP_K_DD_THREADS) void dd_hist_kernel(const DdParam
                 if (i < H) s_hist[i] = got[j];
             }
             __syncthreads();
-            for (int b = threadIdx.x; b < HB; b += SOP_K_DD_THREADS) {
+            for (int b = threadIdx.x; b < HB * NP; b += SOP_K_DD_THREADS) {
+                const int pl = b / HB, bb = b - pl * HB;
+                const int base = pl * p.n_levels * HB + bb;
                 unsigned long long run = 0ull;
-                for (int l = p.n_levels - 1; l >= 0; --l) { run += s_hist[l * HB + b]; p.hist[l * HB + b] = (long long)run; }
+                for (int l = p.n_levels - 1; l >= 0; --l) { run += s_hist[base + l * HB]; p.hist[base + l * HB] = (long long)run; }
             }
         } else {
 #pragma unroll
@@ -196,7 +225,7 @@ extern "C" hipError_t sopk_dd_launch(const DdParams* pp, int is_bf16, int g, voi
 {
     DdParams p = *pp;
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = (size_t)p.n_bins * (size_t)(p.n_levels > 0 ? p.n_levels : 1) * sizeof(unsigned long long);
+    const size_t lds = (size_t)p.n_bins * (size_t)(p.n_levels > 0 ? p.n_levels * p.n_planes : 1) * sizeof(unsigned long long);
     const dim3 grid((unsigned)(p.n_waves / (SOP_K_DD_THREADS / 64))), block(SOP_K_DD_THREADS);
 #define SOPK_DD(B, E, L) hipLaunchKernelGGL((sopk::dd_hist_kernel<B, E, L>), grid, block, lds, st, p)
     if (is_bf16) {

@@ -133,6 +133,8 @@ struct DdParams {
     int n_levels;                    // 0: plain mask.  L >= 1: the mask byte is a level 0..L; a block of level l >= 1 enters
                                      // histogram l-1 of L (n_bins bins each), and the result holds, for every j, the sum of
                                      // the histograms j .. L-1 (the pool of every block of level > j)
+    int n_planes;                    // levels only: P >= 1 level planes, plane_stride bytes apart (one per codebook whose pools are
+    long long plane_stride;          // wanted): one pass over the weights fills P * L histograms, laid out [plane][level][bin]
     long long M, K, ldw, Bk;
     long long row_step, Ms;          // every row_step-th row is used: Ms = ceil(M / row_step) rows
     long long strips, total_units, n_waves;  // total_units = strips * Ms
