@@ -39,7 +39,8 @@ typedef enum {
     SOP_EINVAL = 1,   /* null pointer, bad enum, misaligned buffer, bad pair list            */
     SOP_ESHAPE = 2,   /* M or K <= 0, g not in {8,16,32,64}, g does not divide K, ldw < K    */
     SOP_EATOM  = 3,   /* atom not strictly ascending, < 2 or > 64 entries, not two-sided, NaN,
-                         or two code boundaries closer than 1/650 of the atom's range          */
+                         two code boundaries closer than 1/650 of the atom's range, or a
+                         non-zero entry below 2^-125 in magnitude                              */
     SOP_EFMT   = 4,   /* scale format or layer shift outside the supported range             */
     SOP_ENOMEM = 5,   /* workspace too small                                                 */
     SOP_EHIP   = 6    /* a HIP runtime call failed; see sop_last_error()                     */
@@ -113,6 +114,8 @@ sop_status sop_destroy(sop_ctx* ctx);
  * The kernel finds an element's code through a table over at most 1024 uniform bins of the scaled
  * weight with at most one code boundary per bin: an atom with two boundaries (midpoints of
  * neighbouring entries) closer than about 1/650 of its range is refused with SOP_EATOM.
+ * The table holds half of every entry (the element passes multiply by twice the block scale: the
+ * same product), so a non-zero entry must be at least 2^-125 in magnitude (SOP_EATOM otherwise).
  * Weights and channel norms must be finite; per-block results are exact for weighted block norms
  * sum(c w^2) within 2^-126 .. 2^126 (the cosine's value path rescales by the norm's exponent).
  * Resets the pair list to all pairs a < b in lexicographic order. */

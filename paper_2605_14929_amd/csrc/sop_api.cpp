@@ -86,7 +86,7 @@ __global__ void static_prologue_kernel(unsigned long long* sums, int n_words, fl
     if (i < n_codes) {
         const int e = i >> y, f = i & ((1 << y) - 1);
         const float s = e == 0 ? ldexpf((float)f, 1 - bias - y - k) : ldexpf((float)((1 << y) + f), e - bias - y - k);
-        tab[i] = make_float2(s, s > 0.0f ? 1.0f / s : 0.0f);
+        tab[i] = make_float2(s + s, s > 0.0f ? 1.0f / s : 0.0f);      // (twice the scale, its reciprocal)
     }
 }
 
@@ -381,7 +381,7 @@ static int row_fold(int64_t M, int64_t K, int64_t ldw, int epl)
     return best;
 }
 
-// (scale * 2^-k, reciprocal) of every code of a scale word: value(q) * 2^-k (exact) and its IEEE reciprocal.
+// (twice the scale, reciprocal) of every code of a scale word: 2 * value(q) * 2^-k (exact; the table of codebook values holds halves) and the IEEE reciprocal of value(q) * 2^-k.
 // The tables live in a slab the context allocated at its creation; a table that is not there yet is written
 // by a small kernel on the caller's stream ahead of the kernel that reads it (no allocation, no copy from the
 // host, no synchronisation), into the slot that was used longest ago.
@@ -391,7 +391,7 @@ __global__ void scale_table_kernel(float2* tab, int n_codes, int y, int bias, in
     if (i < n_codes) {
         const int e = i >> y, f = i & ((1 << y) - 1);
         const float s = e == 0 ? ldexpf((float)f, 1 - bias - y - k) : ldexpf((float)((1 << y) + f), e - bias - y - k);
-        tab[i] = make_float2(s, s > 0.0f ? 1.0f / s : 0.0f);
+        tab[i] = make_float2(s + s, s > 0.0f ? 1.0f / s : 0.0f);      // (twice the scale, its reciprocal)
     }
 }
 

@@ -91,8 +91,8 @@ static bool build_bins(const std::vector<float>& L, float xl, float xh, float sc
         }
         if (c1 - c0 > 1) return false;
         rec[j].thr[ia] = c1 > c0 ? mid[c0] : inf;
-        rec[j].ylo[ia] = L[c0];
-        rec[j].yhi[ia] = L[c1];
+        rec[j].ylo[ia] = 0.5f * L[c0];               // halves (exact: plan_alphabet refuses entries whose half is not)
+        rec[j].yhi[ia] = 0.5f * L[c1];
         rec[j].code_lo[ia] = c0;
     }
     return true;
@@ -116,6 +116,19 @@ sop_status soph::plan_alphabet(std::string* err, const sop_atom* atoms, int n_at
             if (j && !(L[j - 1] < L[j])) return planfail(err, SOP_EATOM, "atom entries must be strictly ascending");
         }
         if (!(L[0] < 0.0f && L[N - 1] > 0.0f)) return planfail(err, SOP_EATOM, "an atom must have a negative first and a positive last entry");
+        // the table holds half of every entry, exactly
+        for (int j = 0; j < N; ++j) {
+            const volatile float h = 0.5f * L[j];
+            if (h + h != L[j]) return planfail(err, SOP_EATOM, "atom entry too small: a non-zero entry must be at least 2^-125 in magnitude");
+        }
+        // The search kernels that write no codes form a code boundary as the binary32 sum of its neighbours' halves
+        // instead of reading it.  That sum is the boundary (the binary64 mean rounded once to binary32): both round the
+        // same real number once, the binary64 mean being exact whenever its low bits can matter.  Checked, not assumed:
+        for (int j = 0; j + 1 < N; ++j) {
+            const volatile float hs = 0.5f * L[j] + 0.5f * L[j + 1];
+            if (hs != (float)(((double)L[j] + (double)L[j + 1]) * 0.5))
+                return planfail(err, SOP_EATOM, "atom entries whose code boundary is not the sum of their halves (not expected for finite entries)");
+        }
         pl.tabs[a].assign(L, L + N);
     }
     // Scale groups: equal endpoints; internal order = groups by first appearance.  An atom that is the
@@ -215,7 +228,12 @@ extern "C" sop_status sop_check_alphabet(const sop_atom* atoms, int n_atoms, int
             const BinRec& r = pl.img[b];
             const bool up = x > r.thr[i];
             ++checked;
-            return r.code_lo[i] + (up ? 1 : 0) == code && (up ? r.yhi[i] : r.ylo[i]) == L[code];
+            // (the table holds halves; the boundary formed as their sum must choose the same value wherever it is used)
+            const volatile float thr2 = r.ylo[i] + r.yhi[i];
+            const float v_up = x > thr2 ? r.yhi[i] : r.ylo[i];
+            if (v_up + v_up != L[code]) return false;
+            const float v = up ? r.yhi[i] : r.ylo[i];
+            return r.code_lo[i] + (up ? 1 : 0) == code && v + v == L[code];
         };
         bool ok = true;
         // every float within 64 steps of a code boundary or of an endpoint, a uniform sweep, and

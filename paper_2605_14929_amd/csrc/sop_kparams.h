@@ -32,11 +32,14 @@ struct float2 { float x, y; };       /* (host-only translation units see the lau
 /* position of (i,j), i < j, in the lexicographic list of all pairs of SOP_K_MAXA atoms */
 SOP_K_HD constexpr int pair_index(int i, int j) { return i * (2 * SOP_K_MAXA - i - 1) / 2 + (j - i - 1); }
 
-/* One bin of the element-search table.  For every atom the bin holds at most one code boundary. */
+/* One bin of the element-search table.  For every atom the bin holds at most one code boundary.
+ * The two values are stored HALVED (exactly; the element passes multiply by twice the block scale): the boundary
+ * between two neighbouring entries then equals the binary32 sum of the two stored values, and the passes that only
+ * choose between the values form it with one addition instead of reading it. */
 struct BinRec {
     float thr[SOP_K_MAXA];      // the boundary inside the bin (+inf when there is none)
-    float ylo[SOP_K_MAXA];      // codebook value at and below the boundary
-    float yhi[SOP_K_MAXA];      // codebook value above the boundary
+    float ylo[SOP_K_MAXA];      // half of the codebook value at and below the boundary
+    float yhi[SOP_K_MAXA];      // half of the codebook value above the boundary
     int   code_lo[SOP_K_MAXA];  // code at and below the boundary
     int   pad;
 };
@@ -49,7 +52,7 @@ struct KParams {
     const void*   W;
     const float*  c;
     const BinRec* bins;              // [n_bins], atoms in internal order
-    const float2* stab;              // [n_tab_codes] (scale * 2^-k, its reciprocal), or null
+    const float2* stab;              // [n_tab_codes] (twice the scale value(q) * 2^-k, the scale's reciprocal), or null
     long long M, K, ldw;             // as the kernel walks the layer: rows may be folded (see Kc)
     long long Kc;                    // true row length.  When the rows lie back to back (ldw == K) and 64 lanes do not divide a
                                      // row's lanes, the host folds f rows into one of f*K columns (M/f rows): the last strip of

@@ -23,7 +23,8 @@
 //   scale      s* = max(pmax/t+, nmax/-t-)  (IEEE division), times 2^k, rounded to the scale word
 //              (nearest, ties to the lower code, saturating), s = value(q) * 2^-k, r = 1/s (IEEE)
 //   element    x = fl(w*r); code = number of midpoints strictly below x
-//   error      d = fma(-s, L[code], w);  err = sum fma(fl(c*d), d, .) over chunks of 8 consecutive
+//   error      d = fma(-s, L[code], w) (evaluated as fma(-2s, L[code]/2, w): the same product, both factors exact);
+//              err = sum fma(fl(c*d), d, .) over chunks of 8 consecutive
 //              elements, chunk partials added in a balanced tree in index order
 //   cosine     (metric COS only) w^ = fl(s*L[code]); num = sum fma(fl(c*w), w^, .),
 //              den = sum fma(fl(c*w^), w^, .), same chunks and tree
@@ -91,19 +92,21 @@ __device__ __forceinline__ int encode_scale(float sp, const KParams& p)
     return (int)(q > (uint32_t)p.max_code ? (uint32_t)p.max_code : q);
 }
 
-// value(q) * 2^-k (exact) and its IEEE reciprocal (0 for the zero scale)
-__device__ __forceinline__ void decode_scale(int q, const KParams& p, const float2* __restrict__ s_tab, float& s, float& rinv)
+// TWICE value(q) * 2^-k (exact; the element passes multiply it with the halved codebook values of the table) and the
+// IEEE reciprocal of value(q) * 2^-k (0 for the zero scale); the tabulated pair holds the doubled scale already
+__device__ __forceinline__ void decode_scale(int q, const KParams& p, const float2* __restrict__ s_tab, float& s2, float& rinv)
 {
     if (p.n_tab_codes) {
         const float2 t = s_tab[q];
-        s = t.x;
+        s2 = t.x;
         rinv = t.y;
     } else {
         const int y = p.man_bits;
         const int e = q >> y, f = q & ((1 << y) - 1);
         const float nrm = __uint_as_float(((uint32_t)(e - p.bias - p.k + 127) << 23) | ((uint32_t)f << (23 - y)));
         const float sub = (float)f * p.sub_quantum;
-        s = e > 0 ? nrm : sub;
+        const float s = e > 0 ? nrm : sub;
+        s2 = s + s;
         rinv = s > 0.0f ? 1.0f / s : 0.0f;
     }
 }
@@ -119,14 +122,15 @@ __device__ __forceinline__ float ideal_scale(float pmax, float nmax, float tp, f
     return fmaxf(s1, s2);
 }
 
-// Scale of one (group, sign): code q, signed scale ss, scaled weights x and their bin offsets.
+// Scale of one (group, sign): code q, twice the signed scale in ss, scaled weights x and their bin offsets.
 // boff receives the LDS byte address of each element's bin record (lds_neg = table address minus the
 // product the 24-bit multiply adds for the constant's exponent bits).
 // ARGMAX: the scale maps the block's largest-magnitude element onto the endpoint of larger magnitude
 // and its sign follows from the two signs (per lane, returned in neg_out); otherwise the absmax rule
 // for the sign given in `negative`.
-// Scale of one (group, sign) without the scaled weights: code q, signed scale ss, signed reciprocal rr, and whether the
-// scaled weights may leave the bin table (see prepare_sign).
+// Scale of one (group, sign) without the scaled weights: code q, TWICE the signed scale in ss (the table holds half of
+// every codebook value, see read_rec: 2s * L/2 is the product s * L), signed reciprocal rr, and whether the scaled
+// weights may leave the bin table (see prepare_sign).
 struct ScalePrep { int q; float ss, rr; bool nonzero, beyond; };
 __device__ __forceinline__ ScalePrep prepare_scale(float pmax, float nmax, bool negative, int a, const KParams& p, const Switches& sw,
                                                    const float2* __restrict__ s_tab, const float4* __restrict__ s_gpar)
@@ -137,10 +141,10 @@ __device__ __forceinline__ ScalePrep prepare_scale(float pmax, float nmax, bool 
     const float sstar = negative ? ideal_scale(pmax, nmax, tn, tp, unit_n, unit_p) : ideal_scale(pmax, nmax, tp, tn, unit_p, unit_n);
     ScalePrep r;
     r.q = encode_scale(sstar * p.pow2k, p);
-    float s, rinv;
-    decode_scale(r.q, p, s_tab, s, rinv);
-    r.ss = negative ? -s : s;
-    r.nonzero = s > 0.0f;
+    float s2, rinv;
+    decode_scale(r.q, p, s_tab, s2, rinv);
+    r.ss = negative ? -s2 : s2;
+    r.nonzero = s2 > 0.0f;
     r.rr = negative ? -rinv : rinv;
     r.beyond = !(sstar * rinv <= SOP_K_BIN_SAFE);
     return r;
@@ -165,10 +169,10 @@ __device__ __forceinline__ void prepare_sign(const float (&w)[EPL], float pmax, 
     }
     neg_out = negative;
     q = encode_scale(sstar * p.pow2k, p);
-    float s, rinv;
-    decode_scale(q, p, s_tab, s, rinv);
-    ss = negative ? -s : s;
-    nonzero = s > 0.0f;
+    float s2, rinv;
+    decode_scale(q, p, s_tab, s2, rinv);             // (twice the scale: the element passes multiply it with half of the codebook value)
+    ss = negative ? -s2 : s2;
+    nonzero = s2 > 0.0f;
     const float rr = negative ? -rinv : rinv;
     const float sc = gp.z, off = gp.w;
     // the table covers a scale rounded down by up to the factor SOP_K_BIN_SAFE; beyond it (the scale
@@ -225,17 +229,27 @@ struct Sums {
 };
 
 // One bin record read: boundary, value below, value above (and the lower code when codes are wanted).
-// `addr` is the LDS byte address of the record and A the atom's slot in it: all four reads are
-// register + immediate offset.
+// `addr` is the LDS byte address of the record and A the atom's slot in it: all reads are register + immediate offset.
+// The table holds HALF of each codebook value (exact: the host refuses entries whose half is not), and every
+// element pass multiplies by twice the block scale, which is the same product.  What that buys: the boundary
+// between two neighbouring entries, the binary64 mean rounded once to binary32, equals the binary32 sum of their
+// halves (one rounding of the same real number; the host checks it entry by entry), so a pass that needs the
+// boundary only to choose between the two values forms it with one addition instead of reading it.  LDS serves
+// 128 bytes a clock to the four SIMDs of a compute unit: with 12 bytes per weight and codebook the element passes
+// were bound by that, with 8 they are bound by the vector ALUs.  In a bin without a boundary both values are the
+// same entry, so the choice does not matter there; passes that form codes or look for scaled weights exactly on a
+// boundary (THR) read the stored boundary, which is +infinity in such bins.
 typedef __attribute__((address_space(3))) const float lds_cfloat;
 typedef __attribute__((address_space(3))) const int lds_cint;
 struct Rec { float thr, ylo, yhi; int clo; };
-template <bool CODES>
+template <bool THR, bool CODES>
 __device__ __forceinline__ Rec read_rec(uint32_t addr, int a)
 {
     lds_cfloat* rp = (lds_cfloat*)(size_t)addr;
     Rec r;
-    r.thr = rp[a]; r.ylo = rp[SOP_K_MAXA + a]; r.yhi = rp[2 * SOP_K_MAXA + a];
+    if (THR) r.thr = rp[a];
+    r.ylo = rp[SOP_K_MAXA + a]; r.yhi = rp[2 * SOP_K_MAXA + a];
+    if (!THR) r.thr = r.ylo + r.yhi;
     r.clo = CODES ? ((lds_cint*)(size_t)addr)[3 * SOP_K_MAXA + a] : 0;
     return r;
 }
@@ -275,7 +289,7 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
         for (int j = 0; j < 4; ++j) {
             uint32_t bo;
             src.get(i0 + j, xe[j], bo);
-            r[j] = read_rec<CODES>(bo, a);
+            r[j] = read_rec<CODES || TIES, CODES>(bo, a);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -319,7 +333,7 @@ __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (
         for (int j = 0; j < 4; ++j) {
             uint32_t bo;
             src.get(i0 + j, xe[j], bo);
-            r[j] = read_rec<CODES>(bo, a);
+            r[j] = read_rec<CODES || TIES, CODES>(bo, a);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -349,7 +363,8 @@ __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (
 
 // Cosine inputs straight from the codebook values in the scaled domain, where the block scale
 // cancels: cos = sign(s) <w,y>_c / sqrt(||w||_c^2 ||y||_c^2).  Used when the residual form would cancel.
-template <int EPL, int LPB, class SRC>
+// (y is read as the table holds it, halved: the ratio does not change.)
+template <int EPL, int LPB, bool THR, class SRC>
 __device__ __forceinline__ void direct_cosine_sums(const float (&cb)[EPL], const float (&w)[EPL], const SRC& src, bool nonzero, bool negative,
                                                    int a, float& ny_out, float& dy_out)
 {
@@ -359,7 +374,7 @@ __device__ __forceinline__ void direct_cosine_sums(const float (&cb)[EPL], const
         float xe;
         uint32_t bo;
         src.get(i, xe, bo);
-        const Rec r = read_rec<false>(bo, a);
+        const Rec r = read_rec<THR, false>(bo, a);
         const float yv = xe > r.thr ? r.yhi : r.ylo;
         ny = __fmaf_rn(cb[i] * w[i], yv, ny);
         dy = __fmaf_rn(cb[i], yv * yv, dy);
@@ -823,7 +838,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         // A signed scale word keeps the scale of both signs instead and forms scaled weights and addresses inside the
         // element pass (FlySrc): the arrays of two signs would cost 64 registers and with them a wavefront per SIMD.
         int gq = 0;
-        float gss = 0.0f;
+        float gss = 0.0f;                              // twice the scale (the table holds halved codebook values)
         bool gnz = false, gneg = false;
         constexpr bool FLY = SIGNED && EPL == 16;       // (a lane of 8 elements has the registers for both signs' arrays)
         float gx[FLY ? 1 : EPL], gx2[(SIGNED && !FLY) ? EPL : 1];
@@ -909,7 +924,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                                     // the residual form is accurate while the reconstruction carries a fair share of the block's
                                     // norm; otherwise the whole wavefront recomputes this candidate's cosine sums directly
                                     if (__builtin_expect(__any(t.weak) != 0, 0)) {
-                                        direct_cosine_sums<EPL, LPB>(cb, w, src, sp.nonzero, sgn, a, ny, dy);
+                                        direct_cosine_sums<EPL, LPB, true>(cb, w, src, sp.nonzero, sgn, a, ny, dy);
                                         rawf = true;
                                     }
                                 }
@@ -997,7 +1012,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                     // the block's norm; otherwise the whole wavefront recomputes this atom directly
                     if (__builtin_expect(__any(best.weak) != 0, 0)) {
                         float ny1, dy1;
-                        direct_cosine_sums<EPL, LPB>(cb, w, ArrSrc<EPL>{gx, gboff}, gnz, ARGMAX ? gneg : false, a, ny1, dy1);
+                        direct_cosine_sums<EPL, LPB, EMIT>(cb, w, ArrSrc<EPL>{gx, gboff}, gnz, ARGMAX ? gneg : false, a, ny1, dy1);
                         best.ny = ny1;
                         best.dy = dy1;
                         raw = true;

@@ -82,3 +82,26 @@ def test_search_table_matches_direct_search():
     with pytest.raises(sop.SopError) as e:                            # boundaries closer than the finest table
         sop.sop_check_alphabet([np.array([-1.0, 0.0, 1e-4, 2e-4, 1.0], dtype=np.float32)])
     assert e.value.status == 3
+
+
+def test_halved_table_values_and_entry_magnitudes():
+    # The table holds half of every entry and the search kernels form a code boundary as the sum of two halves.
+    # Host logic: (1) entries whose half is not exact are refused; (2) codebooks with entries of very different
+    # magnitudes (where a binary64 mean could be rounded twice) and entries around binade boundaries still pass the
+    # table self-check, which replays the summed-halves boundary against the midpoint count.
+    with pytest.raises(sop.SopError) as e:
+        sop.sop_check_alphabet([np.array([-1.0, 1e-44, 1.0], dtype=np.float32)])      # a subnormal entry: its half is not exact
+    assert e.value.status == 3
+    sop.sop_check_alphabet([np.array([-1.0, 0.0, 1.0], dtype=np.float32)])
+    rng = np.random.default_rng(77)
+    for _ in range(20):
+        n = int(rng.integers(3, 17))
+        mags = np.sort(np.exp(rng.uniform(np.log(1e-3), 0.0, size=n)).astype(np.float32))
+        L = np.unique(np.concatenate([-mags[: n // 2 + 1][::-1], mags[n // 2:]])).astype(np.float32)
+        try:
+            sop.sop_check_alphabet([L])
+        except sop.SopError as err:                                                   # only the spacing rule may refuse these
+            assert "closely" in str(err)
+    # neighbours more than 2^29 apart in magnitude, and entries exactly on powers of two
+    sop.sop_check_alphabet([np.array([-1.0, -2.0 ** -31, 2.0 ** -3, 0.5], dtype=np.float32),
+                            np.array([-1.0, -0.5, np.float32(0.5) + np.float32(2.0 ** -24), 1.0], dtype=np.float32)])
