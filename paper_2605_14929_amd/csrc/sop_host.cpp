@@ -140,9 +140,8 @@ sop_status soph::plan_alphabet(std::string* err, const sop_atom* atoms, int n_at
         const std::vector<float>&A = pl.tabs[a], &B = pl.tabs[b];
         if (A.size() != B.size()) return false;
         for (size_t k = 0; k < A.size(); ++k) if (B[k] != -A[A.size() - 1 - k]) return false;
-        // (the kernel finds a scaled weight on a code boundary by comparing bit patterns, which tells -0 from +0:
-        // a codebook with a boundary at zero takes no copies)
-        for (size_t k = 0; k + 1 < A.size(); ++k) if ((float)(((double)A[k] + (double)A[k + 1]) * 0.5) == 0.0f) return false;
+        // (a boundary at zero is no obstacle: the kernel finds a scaled weight on a code boundary by a floating-point
+        // comparison, under which -0 and +0 are equal)
         return true;
     };
     int n = 0, n_groups = 0;

@@ -268,13 +268,13 @@ __device__ __forceinline__ void put_code(uint32_t (&codes)[EPL / 4], int i, uint
 // which shares c*d with the error sum.  The form cancels when the reconstruction is much smaller
 // than the block (saturated or vanished scale); the caller checks that and falls back to
 // direct_cosine_sums() for the wavefront.
-// TIES: `tie` becomes zero in the lanes that hold a scaled weight exactly on a code boundary (the one place
-// where a codebook under the negative scale sign and its sign-negated copy under the positive sign part ways):
-// it is the running minimum of the exclusive-or of the two bit patterns (a boundary at +0 would miss a weight
-// of -0: the host marks no copies for a codebook with such a boundary).
+// TIES: `tie` collects, as a lane mask, the lanes that hold a scaled weight exactly on a code boundary (the one place
+// where a codebook under the negative scale sign and its sign-negated copy under the positive sign part ways).  The
+// comparison writes a scalar lane mask and the masks are joined on the scalar unit: one vector instruction per
+// element.  (-0 and +0 compare equal, so a boundary at zero is seen from either side.)
 template <int EPL, int METRIC, bool CODES, bool TIES = false, class SRC>
 __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float (&cb)[EPL], const SRC& src, float ss, int a,
-                                              bool wide_codes, uint32_t (&codes)[EPL / 4], uint32_t* tie = nullptr)
+                                              bool wide_codes, uint32_t (&codes)[EPL / 4], unsigned long long* tie = nullptr)
 {
     float e0 = 0.0f, e1 = 0.0f, wd = 0.0f, ew = 0.0f;
     if (CODES) {
@@ -295,7 +295,7 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
         for (int j = 0; j < 4; ++j) {
             const int i = i0 + j;
             const bool up = xe[j] > r[j].thr;
-            if constexpr (TIES) *tie = min(*tie, __float_as_uint(xe[j]) ^ __float_as_uint(r[j].thr));
+            if constexpr (TIES) *tie |= __builtin_amdgcn_ballot_w64(xe[j] == r[j].thr);
             const float yv = up ? r[j].yhi : r[j].ylo;
             const float d = __fmaf_rn(-ss, yv, w[i]);
             const float cd = cb[i] * d;
@@ -318,7 +318,7 @@ __device__ __forceinline__ Sums eval_residual(const float (&w)[EPL], const float
 // err is formed as well when WANT_ERR (the blk_err output).
 template <int EPL, bool CODES, bool WANT_ERR, bool TIES = false, class SRC>
 __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (&cb)[EPL], const SRC& src, float ss, int a,
-                                            bool wide_codes, uint32_t (&codes)[EPL / 4], uint32_t* tie = nullptr)
+                                            bool wide_codes, uint32_t (&codes)[EPL / 4], unsigned long long* tie = nullptr)
 {
     float e0 = 0.0f, e1 = 0.0f, n0 = 0.0f, n1 = 0.0f, d0 = 0.0f, d1 = 0.0f;
     if (CODES) {
@@ -339,7 +339,7 @@ __device__ __forceinline__ Sums eval_direct(const float (&w)[EPL], const float (
         for (int j = 0; j < 4; ++j) {
             const int i = i0 + j;
             const bool up = xe[j] > r[j].thr;
-            if constexpr (TIES) *tie = min(*tie, __float_as_uint(xe[j]) ^ __float_as_uint(r[j].thr));
+            if constexpr (TIES) *tie |= __builtin_amdgcn_ballot_w64(xe[j] == r[j].thr);
             const float yv = up ? r[j].yhi : r[j].ylo;
             const float what = ss * yv;
             const float cw = cb[i] * w[i];
@@ -906,7 +906,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                             for (int j = 0; j < EPL / 4; ++j) { codes0[j] = cmask - pv_codes0[j]; codes1[j] = cmask - pv_codes1[j]; }
                         }
                     } else {
-                        uint32_t tie = 0xFFFFFFFFu;
+                        unsigned long long tie = 0ull;          // lanes that saw a scaled weight exactly on a code boundary
                         f0neg = false;
                         // one sign of the scale: the atom's element pass with scaled weights formed on the spot
                         const float4 gpar = s_gpar[2 * a];             // (t+, -t-, bin scale, bin offset): same address in every lane
@@ -953,7 +953,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                         eval_sign(spP, false, gx, gboff, err0, ny0, dy0, q0, raw0, codes0, rn0, rd0);
                         // a codebook that is its own sign-negated copy reconstructs the same under both signs (away
                         // from ties), and an equal candidate never replaces the positive sign
-                        if (((sw.selfsym >> a) & 1u) && !__any(tie == 0u && valid)) {
+                        if (((sw.selfsym >> a) & 1u) && (tie & __builtin_amdgcn_ballot_w64(valid)) == 0ull) {
                             err1 = err0; ny1 = ny0; dy1 = dy0; q1 = spM.q; raw1 = raw0; rn1 = rn0; rd1 = rd0;
                             if (EMIT) {
 #pragma unroll
@@ -962,7 +962,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                         } else {
                             eval_sign(spM, true, gx2, gboff2, err1, ny1, dy1, q1, raw1, codes1, rn1, rd1);
                         }
-                        pv_tie = __any(tie == 0u && valid) != 0;
+                        pv_tie = (tie & __builtin_amdgcn_ballot_w64(valid)) != 0ull;
                     }
                     pv_err0 = err0; pv_ny0 = ny0; pv_dy0 = dy0; pv_err1 = err1; pv_ny1 = ny1; pv_dy1 = dy1;
                     pv_q0 = q0; pv_q1 = q1; pv_raw0 = raw0; pv_raw1 = raw1; pv_f0neg = f0neg;

@@ -81,8 +81,9 @@ def test_ties_on_code_boundaries_send_a_wavefront_the_long_way():
             _check(W, c, [L, neg(L), sh, neg(sh)], g, fmt, metric=metric)
     # zero weights on an atom with a boundary at zero: -0 and +0 tie with it
     two = np.array([-1.0, 1.0], dtype=np.float32)
-    W2 = W.copy(); W2[5, 64:512] = 0.0
+    W2 = W.copy(); W2[5, 64:512] = 0.0; W2[6, 0:256] = -0.0; W2[7, 100:700:3] = -0.0
     _check(W2, c, [two, L, neg(L)], g, "E4M3")
+    _check(W2, c, [two, neg(two), sh], g, "E4M3", bf16=False)
 
 
 def test_degenerate_blocks_under_a_signed_word():
