@@ -452,8 +452,14 @@ sop_status sop_pack_blocks(sop_ctx* ctx, int64_t M, int64_t K, int g, sop_scale_
  * leaves the start grid).  The winner has the largest layer ACos under step 4's reassignment; among equal
  * values the first in this order wins: pairs of atoms in lexicographic order, then atom by atom, p by p.
  * A fitted codebook that cannot serve as an atom (SOP_EATOM from the fit or from the table construction) drops
- * its candidate (NaN in acos_fitted). */
+ * its candidate (NaN in acos_fitted).
+ * An alphabet of more than SOP_MAX_ATOMS atoms (at most SOP_LAYER_MAX_ATOMS) is covered by several searches of at
+ * most eight atoms each: the halves [0, 8) and [8, A) whole (every atom's own ACos and ranking plane, the pairs inside
+ * a half) and the pairs across the halves four atoms against four, at most six searches; every pair is scored in exactly
+ * one of them, with the arithmetic of a search that holds both atoms. */
 #define SOP_LAYER_MAX_P 7
+#define SOP_LAYER_MAX_ATOMS 16
+#define SOP_LAYER_MAX_PAIRS 120
 typedef struct {
     int           n_p;                         /* values of p in the sweep, 0..7 (0: pairs of atoms only)            */
     double        p_percent[SOP_LAYER_MAX_P];  /* non-decreasing, each within [0, 100]                               */
@@ -473,9 +479,9 @@ typedef struct {
     double acos;                               /* its layer ACos                                                      */
     int    n_entries_b;
     float  table_b[SOP_MAX_ENTRIES];           /* the second codebook                                                 */
-    double acos_fixed[28];                     /* every pair of atoms, lexicographic; NaN beyond the alphabet's pairs */
-    double acos_atom[SOP_MAX_ATOMS];           /* every atom alone                                                    */
-    double acos_fitted[SOP_MAX_ATOMS][SOP_LAYER_MAX_P];   /* (a, p_j); NaN: not examined or dropped                   */
+    double acos_fixed[SOP_LAYER_MAX_PAIRS];    /* every pair of atoms, lexicographic; NaN beyond the alphabet's pairs */
+    double acos_atom[SOP_LAYER_MAX_ATOMS];     /* every atom alone                                                    */
+    double acos_fitted[SOP_LAYER_MAX_ATOMS][SOP_LAYER_MAX_P];   /* (a, p_j); NaN: not examined or dropped             */
     int    n_bits;                             /* bits per code of the packed payload (pack only)                     */
 } sop_layer_result;
 
@@ -484,7 +490,7 @@ typedef struct {
 sop_status sop_search_layer_workspace(sop_ctx* ctx, int64_t M, int64_t K, int g, int n_atoms, const sop_layer_opts* opts, size_t* bytes);
 
 /* W_dev, dtype, M, K, ldw, c_dev, g, fmt, layer_shift_k, metric as in sop_pair_search(); atoms: HOST, n_atoms
- * (1..8) codebooks; workspace_dev: DEVICE, 256-byte aligned, at least sop_search_layer_workspace() bytes;
+ * (1..16) codebooks; workspace_dev: DEVICE, 256-byte aligned, at least sop_search_layer_workspace() bytes;
  * result: HOST; words_dev / payload_dev: DEVICE outputs of the packing as in sop_pack_blocks() (pack only: N_b
  * uint16 and N_b * g*n/8 bytes with n = bits of the larger of the two codebooks; the scale word needs a metabit).
  * The call queues its kernels on hip_stream and waits for the stream twice (the pool histograms are fitted on the

@@ -43,6 +43,8 @@ class _Atom(C.Structure):
 
 
 LAYER_MAX_P = 7
+LAYER_MAX_ATOMS = 16
+LAYER_MAX_PAIRS = 120
 
 
 class _LayerOpts(C.Structure):
@@ -55,8 +57,8 @@ class _LayerOpts(C.Structure):
 class _LayerResult(C.Structure):
     """sop_layer_result"""
     _fields_ = [("kind", C.c_int), ("a", C.c_int), ("b", C.c_int), ("j", C.c_int), ("p_percent", C.c_double), ("acos", C.c_double),
-                ("n_entries_b", C.c_int), ("table_b", C.c_float * MAX_ENTRIES), ("acos_fixed", C.c_double * 28),
-                ("acos_atom", C.c_double * MAX_ATOMS), ("acos_fitted", (C.c_double * LAYER_MAX_P) * MAX_ATOMS), ("n_bits", C.c_int)]
+                ("n_entries_b", C.c_int), ("table_b", C.c_float * MAX_ENTRIES), ("acos_fixed", C.c_double * LAYER_MAX_PAIRS),
+                ("acos_atom", C.c_double * LAYER_MAX_ATOMS), ("acos_fitted", (C.c_double * LAYER_MAX_P) * LAYER_MAX_ATOMS), ("n_bits", C.c_int)]
 
 
 class _Outputs(C.Structure):

@@ -125,6 +125,7 @@ struct sop_ctx {
     int sel_set = 0;
     unsigned int* d_selm = nullptr;       // [2][SOP_K_MAXA][SOP_K_SELM_WORDS] two sets of digit counts of the ranking with several thresholds (one per score plane of a launch)
     int selm_set = 0;
+    int selm_dirty[2] = {0, 0};           // planes of each set of the batched ranking's digit counts that hold counts
     SelMState* d_selstate = nullptr;      // [SOP_K_MAXA] what the passes of that ranking hand on, per score plane
     unsigned long long* d_sums = nullptr; // two sets of [SOP_K_REPL][SOP_K_NCOL] layer sums followed by their ticket counters; zero between calls
     hipStream_t lane_stream[kLanes] = {};   // sop_pair_search_layers deals the layers out to streams of its own
@@ -993,6 +994,7 @@ static sop_status partition_levels_impl(sop_ctx* c, const float* score, int64_t 
     p.hist = c->d_selm + (c->selm_set ? (size_t)SOP_K_MAXA * SOP_K_SELM_WORDS : 0); p.hist_other = c->d_selm + (c->selm_set ? 0 : (size_t)SOP_K_MAXA * SOP_K_SELM_WORDS);
     p.level = level; p.tau = tau; p.n_a = reinterpret_cast<long long*>(n_a);
     p.n_planes = n_planes;
+    p.n_clear = c->selm_dirty[c->selm_set ^ 1];
     p.state = c->d_selstate;
     if (n_planes > 1 && (n_blocks & 3)) return fail(c, SOP_EINVAL, "ranking of several planes: the number of blocks must be a multiple of four");
     const long long quads = std::max<long long>((n_blocks / 4 + SOP_K_SEL_THREADS - 1) / SOP_K_SEL_THREADS, 1);
@@ -1003,7 +1005,8 @@ static sop_status partition_levels_impl(sop_ctx* c, const float* score, int64_t 
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = sopk_selm_launch(&p, n_wg_count, n_wg, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
-    if (any) c->selm_set ^= 1;
+    c->selm_dirty[c->selm_set ^ 1] = 0;
+    if (any) { c->selm_dirty[c->selm_set] = std::max(c->selm_dirty[c->selm_set], n_planes); c->selm_set ^= 1; }
     return SOP_OK;
 }
 
@@ -1070,8 +1073,14 @@ struct LayerWs {
     size_t rank, level, hist, tau, na, acos, bins, sc, codes, sel, total;
     int n_img;
 };
-// acos region, in doubles: [0,28) fixed pairs, [28,36) fixed atoms, then per atom a: 8 pairs (a, L_b(p_j))
-constexpr int kAcosFit = SOP_K_MAXP + SOP_K_MAXA;
+// An alphabet of more than eight atoms is covered by several searches of at most eight atoms each (the kernel unrolls over
+// eight): the two halves [0, 8) and [8, A) whole, which also gives every atom's own ACos and ranking plane, and the pairs
+// across the halves by quarters (four atoms of one half with four of the other): at most six searches.
+constexpr int kFixedMax = 6;
+constexpr int kAcosPer = SOP_K_MAXP + SOP_K_MAXA;          // doubles per such search: its pairs, then its atoms
+// acos region, in doubles: kFixedMax searches of the fixed alphabet, then per atom a: 8 pairs (a, L_b(p_j))
+constexpr int kAcosFit = kFixedMax * kAcosPer;
+constexpr int kAcosAll = kAcosFit + SOP_LAYER_MAX_ATOMS * 8;
 LayerWs layer_ws(int64_t M, int64_t K, int g, int A, int n_p, int bins, int pack)
 {
     const size_t Nb = (size_t)(M * (K / g));
@@ -1081,10 +1090,10 @@ LayerWs layer_ws(int64_t M, int64_t K, int g, int A, int n_p, int bins, int pack
     w.rank = take((size_t)A * Nb * sizeof(float));
     w.level = take((size_t)A * up256(Nb));
     w.hist = take((size_t)A * std::max(n_p, 1) * bins * sizeof(long long));
-    w.tau = take((size_t)SOP_K_MAXA * SOP_K_SEL_MAXLEV * sizeof(float));
-    w.na = take((size_t)SOP_K_MAXA * SOP_K_SEL_MAXLEV * sizeof(long long));
-    w.acos = take((size_t)(kAcosFit + SOP_K_MAXA * 8) * sizeof(double));
-    w.n_img = A + 3;                                   // fixed alphabet, one per atom's sweep, one spare, the winner
+    w.tau = take((size_t)SOP_LAYER_MAX_ATOMS * SOP_K_SEL_MAXLEV * sizeof(float));
+    w.na = take((size_t)SOP_LAYER_MAX_ATOMS * SOP_K_SEL_MAXLEV * sizeof(long long));
+    w.acos = take((size_t)kAcosAll * sizeof(double));
+    w.n_img = kFixedMax + A + 2;                       // the searches of the fixed alphabet, one per atom's sweep, one spare, the winner
     w.bins = take((size_t)w.n_img * kImgBytes);
     w.sc = take(pack ? 2 * Nb * sizeof(uint16_t) : 0);
     w.codes = take(pack ? 2 * (size_t)(M * K) : 0);
@@ -1095,7 +1104,7 @@ LayerWs layer_ws(int64_t M, int64_t K, int g, int A, int n_p, int bins, int pack
 sop_status layer_opts_check(sop_ctx* c, int n_atoms, const sop_layer_opts* o)
 {
     if (!o) return fail(c, SOP_EINVAL, "sop_search_layer: opts is NULL");
-    if (n_atoms < 1 || n_atoms > SOP_K_MAXA) return fail(c, SOP_EATOM, "sop_search_layer: 1..8 atoms");
+    if (n_atoms < 1 || n_atoms > SOP_LAYER_MAX_ATOMS) return fail(c, SOP_EATOM, "sop_search_layer: 1..16 atoms");
     if (o->n_p < 0 || o->n_p > SOP_LAYER_MAX_P) return fail(c, SOP_EINVAL, "sop_search_layer: at most 7 values of p (the atom and its fitted codebooks form one alphabet of 8)");
     for (int j = 0; j < o->n_p; ++j) {
         if (!(o->p_percent[j] >= 0.0 && o->p_percent[j] <= 100.0)) return fail(c, SOP_EINVAL, "sop_search_layer: p must lie in [0, 100]");
@@ -1152,9 +1161,9 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
     hipError_t e = hipSuccess;
     // pinned staging, allocated once per context
-    const size_t res_bytes = (size_t)SOP_K_MAXA * SOP_K_DD_MAXBINS * sizeof(long long) + (size_t)(kAcosFit + SOP_K_MAXA * 8) * sizeof(double);
+    const size_t res_bytes = (size_t)SOP_LAYER_MAX_ATOMS * SOP_K_DD_MAXBINS * sizeof(long long) + (size_t)kAcosAll * sizeof(double);
     if (!c->h_bins) {
-        if ((e = hipHostMalloc((void**)&c->h_bins, (size_t)(SOP_K_MAXA + 3) * kImgBytes, hipHostMallocDefault)) != hipSuccess ||
+        if ((e = hipHostMalloc((void**)&c->h_bins, (size_t)(kFixedMax + SOP_LAYER_MAX_ATOMS + 2) * kImgBytes, hipHostMallocDefault)) != hipSuccess ||
             (e = hipHostMalloc((void**)&c->h_res, res_bytes, hipHostMallocDefault)) != hipSuccess ||
             (e = hipEventCreateWithFlags(&c->stage_done, hipEventDisableTiming)) != hipSuccess)
             return hipfail(c, e, "pinned staging of sop_search_layer");
@@ -1170,16 +1179,43 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
     double* d_acos = reinterpret_cast<double*>(base + L.acos);
     float* d_rank = reinterpret_cast<float*>(base + L.rank);
 
-    // ---- step 1 for every atom, and every pair of fixed atoms: one search with the ranking scores out ----
-    if (sop_status s = install_alphabet(c, atoms, A, img(0), himg(0), st)) return s;
+    // ---- step 1 for every atom, and every pair of fixed atoms: searches of at most eight atoms each, those of the two
+    //      halves with the ranking scores out ----
+    struct Fixed { int n, atom[SOP_K_MAXA], n_pairs, pr[2 * SOP_K_MAXP]; bool whole; };
+    std::vector<Fixed> fx;
     {
+        auto add = [&](int lo0, int hi0, int lo1, int hi1) {       // atoms [lo0, hi0) and [lo1, hi1); the second range empty: all pairs of the first
+            Fixed f;
+            std::memset(&f, 0, sizeof(f));
+            for (int a = lo0; a < hi0; ++a) f.atom[f.n++] = a;
+            const int n0 = f.n;
+            for (int a = lo1; a < hi1; ++a) f.atom[f.n++] = a;
+            f.whole = lo1 >= hi1;
+            if (f.whole) { for (int i = 0; i < n0; ++i) for (int j = i + 1; j < n0; ++j) { f.pr[2 * f.n_pairs] = i; f.pr[2 * f.n_pairs + 1] = j; ++f.n_pairs; } }
+            else for (int i = 0; i < n0; ++i) for (int j = n0; j < f.n; ++j) { f.pr[2 * f.n_pairs] = i; f.pr[2 * f.n_pairs + 1] = j; ++f.n_pairs; }
+            fx.push_back(f);
+        };
+        if (A <= SOP_K_MAXA) add(0, A, 0, 0);
+        else {
+            add(0, SOP_K_MAXA, 0, 0);
+            add(SOP_K_MAXA, A, 0, 0);
+            for (int q0 = 0; q0 < SOP_K_MAXA; q0 += 4)
+                for (int q1 = SOP_K_MAXA; q1 < A; q1 += 4) add(q0, q0 + 4, q1, std::min(q1 + 4, A));
+        }
+    }
+    for (size_t i = 0; i < fx.size(); ++i) {
+        const Fixed& f = fx[i];
+        sop_atom sub[SOP_K_MAXA];
+        for (int t = 0; t < f.n; ++t) sub[t] = atoms[f.atom[t]];
+        if (sop_status s = install_alphabet(c, sub, f.n, img((int)i), himg((int)i), st)) return s;
+        if (f.n_pairs) { if (sop_status s = sop_set_pairs(c, f.pr, f.n_pairs)) return s; }
         sop_outputs out;
         std::memset(&out, 0, sizeof(out));
-        out.acos_pair = d_acos; out.acos_atom = d_acos + SOP_K_MAXP;
-        out.blk_rank = n_p ? d_rank : nullptr;
+        out.acos_pair = d_acos + i * kAcosPer;
+        out.acos_atom = d_acos + i * kAcosPer + SOP_K_MAXP;
+        out.blk_rank = (n_p && f.whole) ? d_rank + (size_t)f.atom[0] * Nb : nullptr;      // (a half's atoms are consecutive: so are their planes)
         if (sop_status s = pair_search_impl(c, W, dtype, M, K, ldw, cn, g, fmt, k, metric, nullptr, 0, &out, stream, true)) return s;
     }
-    const int P = c->n_pairs;
     // ---- steps 2 and 3 for every atom and every p: one ranking with n_p thresholds, one pass over the weights ----
     int64_t tops[SOP_K_SEL_MAXLEV] = {0};
     for (int j = 0; j < n_p; ++j) {
@@ -1193,10 +1229,10 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
         const bool batch = (Nb & 3) == 0;
         const size_t lstride = batch ? (size_t)Nb : up256((size_t)Nb);
         uint8_t* d_level = reinterpret_cast<uint8_t*>(base + L.level);
-        if (batch) {
-            if (sop_status s = partition_levels_impl(c, d_rank, Nb, tops, n_p, 1, d_level, reinterpret_cast<float*>(base + L.tau),
-                                                     reinterpret_cast<int64_t*>(base + L.na), A, stream)) return s;
-        }
+        for (int a0 = 0; batch && a0 < A; a0 += SOP_K_MAXA)           // (the batched ranking takes eight planes a call)
+            if (sop_status s = partition_levels_impl(c, d_rank + (size_t)a0 * Nb, Nb, tops, n_p, 1, d_level + (size_t)a0 * lstride,
+                                                     reinterpret_cast<float*>(base + L.tau) + a0 * SOP_K_SEL_MAXLEV,
+                                                     reinterpret_cast<int64_t*>(base + L.na) + a0 * SOP_K_SEL_MAXLEV, std::min(SOP_K_MAXA, A - a0), stream)) return s;
         // one pass over the weights fills the pool histograms of as many atoms as the histogram pass has room for
         const int per_pass = std::max(1, SOP_K_DD_MAXBINS / (n_p * bins));
         for (int a = 0; a < A; a += per_pass) {
@@ -1210,7 +1246,7 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
         }
     }
     long long* h_hist = reinterpret_cast<long long*>(c->h_res);
-    double* h_acos = reinterpret_cast<double*>(c->h_res + (size_t)SOP_K_MAXA * SOP_K_DD_MAXBINS * sizeof(long long));
+    double* h_acos = reinterpret_cast<double*>(c->h_res + (size_t)SOP_LAYER_MAX_ATOMS * SOP_K_DD_MAXBINS * sizeof(long long));
     if (n_p) {
         if ((e = hipMemcpyAsync(h_hist, d_hist, (size_t)A * n_p * bins * sizeof(long long), hipMemcpyDeviceToHost, st)) != hipSuccess ||
             (e = hipStreamSynchronize(st)) != hipSuccess) return hipfail(c, e, "copy of the pool histograms");
@@ -1253,14 +1289,14 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
             else if (fs != SOP_EATOM) return fail(c, fs, std::string("sop_search_layer: fit: ") + soph::host_last_error());
         }
         if (js.empty()) continue;
-        sop_status s = score(a, js, 1 + a, kAcosFit + 8 * a);
+        sop_status s = score(a, js, kFixedMax + a, kAcosFit + 8 * a);
         if (s == SOP_EATOM && js.size() > 1) {
             // some fitted codebook cannot be searched next to the others (entries too closely spaced for the
             // element-search table): the candidates are scored one by one, through one spare image, and
             // those that fail alone are dropped
             for (size_t i = 0; i < js.size(); ++i) {
                 if (spare_uses++ && (e = hipStreamSynchronize(st)) != hipSuccess) return hipfail(c, e, "hipStreamSynchronize");
-                s = score(a, std::vector<int>(1, js[i]), A + 1, kAcosFit + 8 * a + (int)i);
+                s = score(a, std::vector<int>(1, js[i]), kFixedMax + A, kAcosFit + 8 * a + (int)i);
                 if (s != SOP_OK && s != SOP_EATOM) return s;
             }
         } else if (s != SOP_OK && s != SOP_EATOM) return s;
@@ -1272,9 +1308,17 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
     std::memset(res, 0, sizeof(*res));
     res->a = -1; res->b = -1;
     const double nan = std::numeric_limits<double>::quiet_NaN();
-    for (int q = 0; q < SOP_K_MAXP; ++q) res->acos_fixed[q] = q < P ? h_acos[q] : nan;
-    for (int a = 0; a < SOP_K_MAXA; ++a) {
-        res->acos_atom[a] = a < A ? h_acos[SOP_K_MAXP + a] : nan;
+    for (int q = 0; q < SOP_LAYER_MAX_PAIRS; ++q) res->acos_fixed[q] = nan;
+    for (int a = 0; a < SOP_LAYER_MAX_ATOMS; ++a) res->acos_atom[a] = nan;
+    for (size_t i = 0; i < fx.size(); ++i) {
+        const Fixed& f = fx[i];
+        for (int t = 0; t < f.n_pairs; ++t) {
+            const int a = f.atom[f.pr[2 * t]], b = f.atom[f.pr[2 * t + 1]];
+            res->acos_fixed[a * (2 * A - a - 1) / 2 + (b - a - 1)] = h_acos[i * kAcosPer + t];
+        }
+        if (f.whole) for (int t = 0; t < f.n; ++t) res->acos_atom[f.atom[t]] = h_acos[i * kAcosPer + SOP_K_MAXP + t];
+    }
+    for (int a = 0; a < SOP_LAYER_MAX_ATOMS; ++a) {
         for (int j = 0; j < SOP_LAYER_MAX_P; ++j) {
             const int sl = (a < A && j < n_p) ? slot_of[(size_t)a * n_p + j] : -1;
             res->acos_fitted[a][j] = sl >= 0 ? h_acos[sl] : nan;
@@ -1299,7 +1343,7 @@ extern "C" sop_status sop_search_layer(sop_ctx* c, const void* W, sop_dtype dtyp
     // ---- materialisation of the winner ----
     if (o->pack) {
         sop_atom two[2] = {atoms[res->a], {res->n_entries_b, res->table_b}};
-        if (sop_status s = install_alphabet(c, two, 2, img(A + 2), himg(A + 2), st)) return s;
+        if (sop_status s = install_alphabet(c, two, 2, img(kFixedMax + A + 1), himg(kFixedMax + A + 1), st)) return s;
         uint16_t* sc = reinterpret_cast<uint16_t*>(base + L.sc);
         uint8_t* codes = reinterpret_cast<uint8_t*>(base + L.codes);
         const size_t plane_a = two[0].n_entries <= 16 ? (size_t)(M * K / 2) : (size_t)(M * K);

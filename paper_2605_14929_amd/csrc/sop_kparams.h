@@ -226,6 +226,8 @@ struct SelMParams {
     // several score planes in one launch (blockIdx.y names the plane): plane q reads score + q * n, counts into
     // hist + q * SOP_K_SELM_WORDS and writes level + q * n, tau / n_a + q * SOP_K_SEL_MAXLEV
     int n_planes;
+    int n_clear;                     // planes of hist_other that hold counts (the calls that counted into that set may have
+                                     // had more planes than this one): all of them are cleared
 };
 
 /* Packing of scale words and code payloads */

@@ -275,8 +275,13 @@ __global__ __launch_bounds__(SOP_K_SEL_THREADS) void rank_level_kernel(const Sel
         _Pragma("unroll") for (int t = 0; t < SOP_K_SEL_MAXLEV; ++t) lv += k < tkey[t] ? 1u : 0u;
         p.level[i] = (unsigned char)lv;
     }
-    for (long long gi = (long long)blockIdx.x * SOP_K_SEL_THREADS + threadIdx.x; gi < SOP_K_SELM_WORDS; gi += (long long)gridDim.x * SOP_K_SEL_THREADS)
-        p.hist_other[gi] = 0u;
+    // the other set of digit counts is cleared for the next call: every plane that holds counts, which can be more
+    // planes than this launch has (a launch over fewer planes follows one over more)
+    for (unsigned int cq = blockIdx.y; cq < (unsigned int)pp.n_clear; cq += gridDim.y) {
+        unsigned int* dst = pp.hist_other + (size_t)cq * SOP_K_SELM_WORDS;
+        for (long long gi = (long long)blockIdx.x * SOP_K_SEL_THREADS + threadIdx.x; gi < SOP_K_SELM_WORDS; gi += (long long)gridDim.x * SOP_K_SEL_THREADS)
+            dst[gi] = 0u;
+    }
 }
 
 template <int PASS>

@@ -88,3 +88,62 @@ def test_search_with_the_second_codebook_selected_on_an_lut_grid():
     assert abs(res.acos - ref_best[1]) <= 1e-6 and res.kind == ref_best[0]
     if res.kind == "fitted":
         assert np.all(np.isin(res.table_b.astype(np.float64), grid.astype(np.float32).astype(np.float64)))   # every entry is a grid value
+
+
+@pytest.mark.parametrize("A", [9, 10, 16])
+def test_alphabets_of_more_than_eight_atoms(A):
+    """Alphabets above the kernel's eight atoms are covered by several searches inside the one call: every pair of
+    atoms, every atom alone and the sweep over p against the oracle (which takes sixteen atoms at once)."""
+    import torch
+    M, K, g = 64, 2048, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 6300 + A, row_sigma=0.5, outlier_frac=0.001))
+    c = si.channel_norms(K, 1.0, 6301)
+    draws = si.normal_draws(1 << 16, 4242)
+    base = [OA.nf(4), OA.sh(4), OA.bof(4, draws), OA.sh(4, 1.2, 0.01), OA.sh(4, 2.0, -0.03), OA.nf(3), OA.sh(5), OA.nf(5)]
+    atoms = [OA.to_f32(t) for t in base] + [OA.to_f32(OA.negate(t)) for t in base]
+    order = [0, 8, 1, 9, 2, 10, 3, 11, 4, 12, 5, 13, 6, 14, 7, 15][:A]
+    atoms = [atoms[i] for i in order]
+    fmt = sop.fmt_by_name("UE4M3")
+    p_grid = (60.0, 90.0)
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    res = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=p_grid, fit_iters=8, fit_init=atoms[0])
+    ofmt = oracle_fmt(fmt)
+    pairs = np.array([(a, b) for a in range(A) for b in range(a + 1, A)], dtype=np.int32)
+    fixed = np.zeros(len(pairs))
+    r = None
+    for i0 in range(0, len(pairs), 28):                                   # the oracle's selector word holds 32 pairs
+        r = ops.pair_search(W, c, atoms, g, ofmt, pairs=pairs[i0:i0 + 28], want_codes=False)
+        fixed[i0:i0 + 28] = r.acos_pair[:len(pairs[i0:i0 + 28])]
+    assert res.acos_fixed.shape == fixed.shape and np.max(np.abs(res.acos_fixed - fixed)) <= 1e-6
+    Nb = W.size // g
+    best = ("fixed", fixed.max())
+    for a in range(A):
+        for p in p_grid:
+            _, pool_b, _ = PT.partition(r.blk_rank[a], PT.top_count(p, Nb), True)
+            h = DD.histogram(W, c, g, 1024, block_mask=pool_b)
+            Lb = OA.to_f32(DD.fit(h, 16, 8, atoms[0].astype(np.float64)))
+            v = float(ops.pair_search(W, c, [atoms[a], Lb], g, ofmt, want_codes=False).acos_pair[0])
+            assert abs(res.acos_fitted[(a, p)] - v) <= 1e-6, (a, p)
+            if v > best[1]: best = ("fitted", v)
+    assert abs(res.acos - best[1]) <= 1e-6 and res.kind == best[0]
+
+
+def test_calls_with_fewer_and_then_more_atoms_leave_no_state():
+    """The batched ranking keeps digit counts per score plane in the context: a call over fewer planes between
+    two calls over more must leave nothing behind (the third call equals the first bit for bit)."""
+    import torch
+    M, K, g = 64, 1024, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 6400, row_sigma=0.5))
+    c = si.channel_norms(K, 1.0, 6401)
+    atoms = [OA.to_f32(OA.nf(4)), OA.to_f32(OA.sh(4)), OA.to_f32(OA.negate(OA.sh(4))), OA.to_f32(OA.negate(OA.nf(4)))]
+    fmt = sop.fmt_by_name("UE4M3")
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    cx = sop.Context(0)
+    run = lambda n: LSR.search_layer(cx, Wt, ct, g, fmt, atoms[:n], p_grid=(50.0, 80.0), fit_iters=6)
+    first = run(4)
+    for n in (2, 4, 3, 1, 4):
+        r = run(n)
+        if n == 4:
+            assert r.acos_fitted == first.acos_fitted and np.array_equal(r.acos_fixed, first.acos_fixed) and r.acos == first.acos
