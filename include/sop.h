@@ -364,9 +364,10 @@ sop_status sop_layer_scope_error(sop_ctx* ctx, const void* W_dev, sop_dtype dtyp
 sop_status sop_read_probe(sop_ctx* ctx, const void* x_dev, int64_t n_bytes, uint32_t* out_dev, void* hip_stream);
 
 /* Calibration: the rate at which the vector ALUs take one kind of instruction (not part of the method; it
- * is what the "alu" roofline of the search kernel is read against).  Launches n_cu * waves_per_simd
- * workgroups of 256 threads (four wavefronts, one per SIMD); every lane executes iters * 64 instructions of
- * the kind on eight independent chains, without memory traffic:
+ * is what the "alu" roofline of the search kernel is read against).  Launches n_cu * waves_per_simd * 256
+ * threads so that every SIMD holds waves_per_simd wavefronts (one workgroup per compute unit up to four
+ * wavefronts per SIMD, two for six and eight, workgroups of four wavefronts for five and seven); every lane
+ * executes iters * 64 instructions of the kind on eight independent chains, without memory traffic:
  *   kind 0 v_fmac_f32 (registers only)   1 v_max_f32   2 v_fma_f32 with a scalar-register operand
  *        3 v_cmp_lt_f32 + v_cndmask_b32  4 v_mul_f32   5 v_mad_u32_u24   6 v_fma_f32 + v_max_f32 alternating
  *        7 v_add_f32  8 v_and_b32  9 v_add_u32  10 v_lshrrev_b32  11 v_lshlrev_b32  12 v_cvt_i32_f32  13 v_med3_f32
@@ -374,10 +375,10 @@ sop_status sop_read_probe(sop_ctx* ctx, const void* x_dev, int64_t n_bytes, uint
  * a, b: the two operand values (chains start at (thread % 8) / 8 + chain number).
  * out_dev: DEVICE, n_cu * waves_per_simd * 256 floats, overwritten: the sum ((x0+x1)+(x2+x3))+((x4+x5)+(x6+x7))
  * of the lane's chain values.  waves_per_simd 1..8, iters 1..2^20.  Asynchronous.
- * *n_wg_out (HOST, may be NULL) receives the number of workgroups launched. */
+ * *n_out (HOST, may be NULL) receives the number of floats written (threads launched). */
 #define SOP_ISSUE_PROBE_KINDS 15
 sop_status sop_issue_probe(sop_ctx* ctx, int kind, int waves_per_simd, int iters, float a, float b,
-                           float* out_dev, int* n_wg_out, void* hip_stream);
+                           float* out_dev, int* n_out, void* hip_stream);
 
 /* out_dev[0] = sum of the n binary32 values at x_dev, accumulated in binary64 in a fixed order. */
 sop_status sop_sum_f32(sop_ctx* ctx, const float* x_dev, int64_t n, double* out_dev, void* hip_stream);

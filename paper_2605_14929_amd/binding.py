@@ -393,19 +393,19 @@ class Context:
         return out
 
     def issue_probe(self, kind: int, waves_per_simd: int, iters: int, a: float = 0.5, b: float = 0.25, out=None, stream=None):
-        """sop_issue_probe: returns the [workgroups * 256] float32 device tensor of per-lane chain sums."""
+        """sop_issue_probe: returns the [compute units * waves_per_simd * 256] float32 device tensor of per-lane chain sums."""
         import torch
         dev = torch.device("cuda", self.device)
         n = torch.cuda.get_device_properties(dev).multi_processor_count * int(waves_per_simd) * 256
         if out is None:
             out = torch.empty(n, dtype=torch.float32, device=dev)
         elif out.numel() < n or out.dtype != torch.float32 or not out.is_cuda:
-            raise SopError(1, "out must be a CUDA float32 tensor of workgroups * 256 elements")
+            raise SopError(1, "out must be a CUDA float32 tensor of compute units * waves_per_simd * 256 elements")
         st = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
         nwg = C.c_int(0)
         _check(lib().sop_issue_probe(self._h, int(kind), int(waves_per_simd), int(iters), float(a), float(b),
                                      C.c_void_p(out.data_ptr()), C.byref(nwg), C.c_void_p(st)), self._h)
-        if nwg.value * 256 != n:
+        if nwg.value != n:
             raise SopError(6, "the library counts another number of compute units than PyTorch")
         return out
 

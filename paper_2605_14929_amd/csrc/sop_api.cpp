@@ -30,7 +30,7 @@ extern "C" hipError_t sopk_fl_launch(const FlParams* p, int is_bf16, int g, void
 extern "C" int sopk_fl_weights_per_lane(int is_bf16, int g);
 extern "C" hipError_t sopk_ls_launch(const LsParams* p, int is_bf16, void* stream);
 extern "C" hipError_t sopk_sum_launch(const LsParams* p, void* stream);
-extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int iters, float a, float b, float* out, void* stream);
+extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int n_threads, int iters, float a, float b, float* out, void* stream);
 extern "C" hipError_t sopk_probe_launch(const void* x, long long n16, unsigned int* out, void* stream);
 extern "C" hipError_t sopk_sel_launch(const SelParams* p, int n_wg_count, int n_wg, void* stream);
 extern "C" hipError_t sopk_selm_launch(const SelMParams* p, int n_wg_count, int n_wg, void* stream);
@@ -906,17 +906,21 @@ extern "C" sop_status sop_read_probe(sop_ctx* c, const void* x, int64_t n_bytes,
     return SOP_OK;
 }
 
-extern "C" sop_status sop_issue_probe(sop_ctx* c, int kind, int waves_per_simd, int iters, float a, float b, float* out, int* n_wg_out, void* stream)
+extern "C" sop_status sop_issue_probe(sop_ctx* c, int kind, int waves_per_simd, int iters, float a, float b, float* out, int* n_out, void* stream)
 {
     if (!c) return SOP_EINVAL;
     if (kind < 0 || kind >= SOP_ISSUE_PROBE_KINDS || waves_per_simd < 1 || waves_per_simd > 8 || iters < 1 || iters > (1 << 20) || !out)
         return fail(c, SOP_EINVAL, "sop_issue_probe: kind 0..14, waves_per_simd 1..8, iters 1..2^20, out not NULL");
     if (reinterpret_cast<uintptr_t>(out) & 3u) return fail(c, SOP_EINVAL, "sop_issue_probe: misaligned pointer");
-    const int n_wg = c->n_cu * waves_per_simd;
-    if (n_wg_out) *n_wg_out = n_wg;
+    // every SIMD is to hold exactly waves_per_simd wavefronts: one workgroup per compute unit with that many wavefronts
+    // per SIMD (up to four), two such workgroups for six and eight, else workgroups of four wavefronts
+    int n_wg = c->n_cu * waves_per_simd, n_threads = 256;
+    if (waves_per_simd <= 4) { n_wg = c->n_cu; n_threads = 256 * waves_per_simd; }
+    else if (waves_per_simd % 2 == 0) { n_wg = 2 * c->n_cu; n_threads = 128 * waves_per_simd; }
+    if (n_out) *n_out = n_wg * n_threads;
     DeviceGuard guard(c->device);
     if (guard.err != hipSuccess) return hipfail(c, guard.err, "hipSetDevice");
-    hipError_t e = sopk_issue_probe_launch(kind, n_wg, iters, a, b, out, stream);
+    hipError_t e = sopk_issue_probe_launch(kind, n_wg, n_threads, iters, a, b, out, stream);
     if (e != hipSuccess) return hipfail(c, e, "kernel launch");
     return SOP_OK;
 }

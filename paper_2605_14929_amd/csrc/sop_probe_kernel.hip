@@ -46,47 +46,84 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const uint4* __restrict
 //   kind 6  v_fma_f32 then v_max_f32 on the same chain (one of each class, alternating)
 //   kinds 7..14  v_add_f32, v_and_b32, v_add_u32, v_lshrrev_b32, v_lshlrev_b32, v_cvt_i32_f32, v_med3_f32, v_rcp_f32
 //           (which class an instruction belongs to; their chain values are not meant to be checked)
-#define SOPK_ISSUE8(INS) \
-    asm volatile(INS : "+v"(x0) : "v"(a), "v"(b), "s"(sa) : "vcc"); asm volatile(INS : "+v"(x1) : "v"(a), "v"(b), "s"(sa) : "vcc"); \
-    asm volatile(INS : "+v"(x2) : "v"(a), "v"(b), "s"(sa) : "vcc"); asm volatile(INS : "+v"(x3) : "v"(a), "v"(b), "s"(sa) : "vcc"); \
-    asm volatile(INS : "+v"(x4) : "v"(a), "v"(b), "s"(sa) : "vcc"); asm volatile(INS : "+v"(x5) : "v"(a), "v"(b), "s"(sa) : "vcc"); \
-    asm volatile(INS : "+v"(x6) : "v"(a), "v"(b), "s"(sa) : "vcc"); asm volatile(INS : "+v"(x7) : "v"(a), "v"(b), "s"(sa) : "vcc");
-// (two instructions per statement: the compiler separates inline-assembly statements by a no-op, which would
-// take one of the wavefront's issue slots per instruction measured)
-#define SOPK_ISSUE_BODY(I1, I2) for (int it = 0; it < iters; ++it) { SOPK_ISSUE8(I1 "\n" I2) SOPK_ISSUE8(I1 "\n" I2) SOPK_ISSUE8(I1 "\n" I2) SOPK_ISSUE8(I1 "\n" I2) }
+// One statement holds the sixteen instructions of a round over the eight chains (the compiler separates inline-assembly
+// statements by a no-op, which takes an issue slot of the wavefront: one per sixteen instructions measured here).
+// I1, I2: the two instructions applied to a chain, with X for the chain's register and %8, %9, %10 for a, b, sa.
+#define SOPK_R8(I) I("%0") "\n" I("%1") "\n" I("%2") "\n" I("%3") "\n" I("%4") "\n" I("%5") "\n" I("%6") "\n" I("%7") "\n"
+#define SOPK_P(I1, I2, X) I1(X) "\n" I2(X) "\n"
+#define SOPK_OPS : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7) : "v"(a), "v"(b), "s"(sa) : "vcc"
+// the first instruction on every chain, then the second on every chain: neighbours in the stream are independent
+#define SOPK_ISSUE16(I1, I2) asm volatile(SOPK_R8(I1) SOPK_R8(I2) SOPK_OPS);
+// compare and select stay together (the select reads the mask the compare before it wrote)
+#define SOPK_ISSUE16P(I1, I2) \
+    asm volatile(SOPK_P(I1, I2, "%0") SOPK_P(I1, I2, "%1") SOPK_P(I1, I2, "%2") SOPK_P(I1, I2, "%3") \
+                 SOPK_P(I1, I2, "%4") SOPK_P(I1, I2, "%5") SOPK_P(I1, I2, "%6") SOPK_P(I1, I2, "%7") SOPK_OPS);
+#define SOPK_ISSUE_BODY(I1, I2) for (int it = 0; it < iters; ++it) { SOPK_ISSUE16(I1, I2) SOPK_ISSUE16(I1, I2) SOPK_ISSUE16(I1, I2) SOPK_ISSUE16(I1, I2) }
+#define SOPK_ISSUE_BODYP(I1, I2) for (int it = 0; it < iters; ++it) { SOPK_ISSUE16P(I1, I2) SOPK_ISSUE16P(I1, I2) SOPK_ISSUE16P(I1, I2) SOPK_ISSUE16P(I1, I2) }
+
+#define SOPK_K0A(X) "v_fmac_f32 " X ", %8, %9"
+#define SOPK_K0B(X) "v_fmac_f32 " X ", %8, %9"
+#define SOPK_K1A(X) "v_max_f32 " X ", " X ", %8"
+#define SOPK_K1B(X) "v_max_f32 " X ", " X ", %9"
+#define SOPK_K2A(X) "v_fma_f32 " X ", " X ", %10, %9"
+#define SOPK_K2B(X) "v_fma_f32 " X ", " X ", %10, %9"
+#define SOPK_K3A(X) "v_cmp_lt_f32 vcc, " X ", %8"
+#define SOPK_K3B(X) "v_cndmask_b32 " X ", " X ", %9, vcc"
+#define SOPK_K4A(X) "v_mul_f32 " X ", " X ", %8"
+#define SOPK_K4B(X) "v_mul_f32 " X ", " X ", %8"
+#define SOPK_K5A(X) "v_mad_u32_u24 " X ", " X ", %8, %9"
+#define SOPK_K5B(X) "v_mad_u32_u24 " X ", " X ", %8, %9"
+#define SOPK_K6A(X) "v_fma_f32 " X ", " X ", %8, %9"
+#define SOPK_K6B(X) "v_max_f32 " X ", " X ", %9"
+#define SOPK_K7A(X) "v_add_f32 " X ", " X ", %8"
+#define SOPK_K7B(X) "v_add_f32 " X ", " X ", %9"
+#define SOPK_K8A(X) "v_and_b32 " X ", " X ", %8"
+#define SOPK_K8B(X) "v_and_b32 " X ", " X ", %9"
+#define SOPK_K9A(X) "v_add_u32 " X ", " X ", %8"
+#define SOPK_K9B(X) "v_add_u32 " X ", " X ", %9"
+#define SOPK_K10A(X) "v_lshrrev_b32 " X ", 1, " X
+#define SOPK_K10B(X) "v_lshrrev_b32 " X ", 1, " X
+#define SOPK_K11A(X) "v_lshlrev_b32 " X ", 1, " X
+#define SOPK_K11B(X) "v_lshlrev_b32 " X ", 1, " X
+#define SOPK_K12A(X) "v_cvt_i32_f32 " X ", " X
+#define SOPK_K12B(X) "v_cvt_i32_f32 " X ", " X
+#define SOPK_K13A(X) "v_med3_f32 " X ", " X ", %8, %9"
+#define SOPK_K13B(X) "v_med3_f32 " X ", " X ", %8, %9"
+#define SOPK_K14A(X) "v_rcp_f32 " X ", " X
+#define SOPK_K14B(X) "v_rcp_f32 " X ", " X
 
 template <int KIND>
-__global__ __launch_bounds__(256) void issue_probe_kernel(float* __restrict__ out, int iters, float fa, float fb)
+__global__ __launch_bounds__(1024) void issue_probe_kernel(float* __restrict__ out, int iters, float fa, float fb)
 {
     float x0 = (float)(threadIdx.x & 7) * 0.125f, x1 = x0 + 1.0f, x2 = x0 + 2.0f, x3 = x0 + 3.0f, x4 = x0 + 4.0f, x5 = x0 + 5.0f, x6 = x0 + 6.0f, x7 = x0 + 7.0f;
     float a = fa, b = fb;
     const float sa = fa;
     // the operands must sit in vector registers for the kinds that name registers only
     asm volatile("" : "+v"(a), "+v"(b));
-    if (KIND == 0) { SOPK_ISSUE_BODY("v_fmac_f32 %0, %1, %2", "v_fmac_f32 %0, %1, %2") }
-    else if (KIND == 1) { SOPK_ISSUE_BODY("v_max_f32 %0, %0, %1", "v_max_f32 %0, %0, %2") }
-    else if (KIND == 2) { SOPK_ISSUE_BODY("v_fma_f32 %0, %0, %3, %2", "v_fma_f32 %0, %0, %3, %2") }
-    else if (KIND == 3) { SOPK_ISSUE_BODY("v_cmp_lt_f32 vcc, %0, %1", "v_cndmask_b32 %0, %0, %2, vcc") }
-    else if (KIND == 4) { SOPK_ISSUE_BODY("v_mul_f32 %0, %0, %1", "v_mul_f32 %0, %0, %1") }
-    else if (KIND == 5) { SOPK_ISSUE_BODY("v_mad_u32_u24 %0, %0, %1, %2", "v_mad_u32_u24 %0, %0, %1, %2") }
-    else if (KIND == 6) { SOPK_ISSUE_BODY("v_fma_f32 %0, %0, %1, %2", "v_max_f32 %0, %0, %2") }
-    else if (KIND == 7) { SOPK_ISSUE_BODY("v_add_f32 %0, %0, %1", "v_add_f32 %0, %0, %2") }
-    else if (KIND == 8) { SOPK_ISSUE_BODY("v_and_b32 %0, %0, %1", "v_and_b32 %0, %0, %2") }
-    else if (KIND == 9) { SOPK_ISSUE_BODY("v_add_u32 %0, %0, %1", "v_add_u32 %0, %0, %2") }
-    else if (KIND == 10) { SOPK_ISSUE_BODY("v_lshrrev_b32 %0, 1, %0", "v_lshrrev_b32 %0, 1, %0") }
-    else if (KIND == 11) { SOPK_ISSUE_BODY("v_lshlrev_b32 %0, 1, %0", "v_lshlrev_b32 %0, 1, %0") }
-    else if (KIND == 12) { SOPK_ISSUE_BODY("v_cvt_i32_f32 %0, %0", "v_cvt_i32_f32 %0, %0") }
-    else if (KIND == 13) { SOPK_ISSUE_BODY("v_med3_f32 %0, %0, %1, %2", "v_med3_f32 %0, %0, %1, %2") }
-    else { SOPK_ISSUE_BODY("v_rcp_f32 %0, %0", "v_rcp_f32 %0, %0") }
-    out[(size_t)blockIdx.x * 256 + threadIdx.x] = ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
+    if (KIND == 0) { SOPK_ISSUE_BODY(SOPK_K0A, SOPK_K0B) }
+    else if (KIND == 1) { SOPK_ISSUE_BODY(SOPK_K1A, SOPK_K1B) }
+    else if (KIND == 2) { SOPK_ISSUE_BODY(SOPK_K2A, SOPK_K2B) }
+    else if (KIND == 3) { SOPK_ISSUE_BODYP(SOPK_K3A, SOPK_K3B) }
+    else if (KIND == 4) { SOPK_ISSUE_BODY(SOPK_K4A, SOPK_K4B) }
+    else if (KIND == 5) { SOPK_ISSUE_BODY(SOPK_K5A, SOPK_K5B) }
+    else if (KIND == 6) { SOPK_ISSUE_BODY(SOPK_K6A, SOPK_K6B) }
+    else if (KIND == 7) { SOPK_ISSUE_BODY(SOPK_K7A, SOPK_K7B) }
+    else if (KIND == 8) { SOPK_ISSUE_BODY(SOPK_K8A, SOPK_K8B) }
+    else if (KIND == 9) { SOPK_ISSUE_BODY(SOPK_K9A, SOPK_K9B) }
+    else if (KIND == 10) { SOPK_ISSUE_BODY(SOPK_K10A, SOPK_K10B) }
+    else if (KIND == 11) { SOPK_ISSUE_BODY(SOPK_K11A, SOPK_K11B) }
+    else if (KIND == 12) { SOPK_ISSUE_BODY(SOPK_K12A, SOPK_K12B) }
+    else if (KIND == 13) { SOPK_ISSUE_BODY(SOPK_K13A, SOPK_K13B) }
+    else { SOPK_ISSUE_BODY(SOPK_K14A, SOPK_K14B) }
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
 }
 
 }  // namespace sopk
 
-extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int iters, float a, float b, float* out, void* stream)
+extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int n_threads, int iters, float a, float b, float* out, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const dim3 grid((unsigned)n_wg), block(256);
+    const dim3 grid((unsigned)n_wg), block((unsigned)n_threads);
 #define SOPK_IP(K) hipLaunchKernelGGL(sopk::issue_probe_kernel<K>, grid, block, 0, st, out, iters, a, b)
     switch (kind) {
     case 0: SOPK_IP(0); break;
