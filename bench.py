@@ -25,12 +25,13 @@ sys.path.insert(0, ROOT)
 CLOCK_RAMP_MS = 60.0            # untimed repetition of the call before the timed region (GPU clock ramp)
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # Plain vector-ALU peak: the published fp32 vector rate, 157.3 TFLOP/s, counts an fma as two: 78.6e12 fp32
-# lane-operations per second with an fma counted once = 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz.  A SIMD reaches
-# that rate (measured: 65-70e12, `--workload issue_probe`) only on plain two-operand arithmetic on vector registers
-# (fma, multiply, add, logic, integer add) and with four or more wavefronts per SIMD; compares, selects' compares,
-# minima and maxima, conversions, left shifts, three-operand integer forms and anything with a scalar-register
-# operand issue at half of it (VALU_HALF_RATE_TLOPS), and one wavefront issues at most one instruction (of any kind,
-# scalar and LDS included) about every 4.2 cycles.  Packed fp32 (two operations per lane) is not used in this build.
+# lane-operations per second with an fma counted once = 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz.  A SIMD takes
+# plain two-operand arithmetic on vector registers (fma, multiply, add, logic, integer add) from two wavefronts at a
+# time (measured: 70e12 with four or more wavefronts per SIMD, 2.3 cycles an instruction; 2.8 cycles with three,
+# where one wavefront goes alone; `--workload issue_probe`); compares, selects, minima and maxima, conversions, left
+# shifts, three-operand integer forms and anything with a scalar-register operand are taken at half that rate
+# (VALU_HALF_RATE_TLOPS) but leave the other slot to the first class, so a mixed stream runs at the first rate.
+# Packed fp32 (two operations per lane) is not used in this build.
 VALU_PEAK_TLOPS = 78.6432
 VALU_HALF_RATE_TLOPS = 39.3216
 
@@ -41,6 +42,7 @@ def algorithmic_lane_ops(n_weights, g, n_atoms, n_groups, n_pairs, signs=1, n_co
     per weight and scale group: x = w*r, the two operations that locate x's code     = 3
     per weight and evaluated (atom, sign): compare with the code boundary, select
         the entry, residual fma, c*d, error fma, cosine-sum fma                      = 6
+        (the kernel spends a seventh, forming the boundary from the table's two values: not the method's)
     per block and scale group: ideal scale 3, shift 1, encode 5, decode+reciprocal 3 = 12
     per block and atom: chunk add 1, cosine 5, accumulate 2                          = 8
     per block and pair: compare, select, add, two operations for the selector bit    = 5
@@ -678,8 +680,8 @@ def main():
                      "traffic_source": "profiles/search_kernel_c3down_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)" if headline else None,
                      "frac_of_half_rate_class_peak": alg_ops / (ev_ms * 1e-3) / 1e12 / VALU_HALF_RATE_TLOPS,
                      "op_definition": "fp32 lane-operations of the method's arithmetic, an fma counted once; peak = the published 157.3 TFLOP/s / 2 "
-                                      "= 256 CU x 4 SIMD x 32 lanes/clock x 2.4 GHz, reached only by plain register-operand arithmetic; compares, "
-                                      "min/max, conversions, 3-operand integer forms and scalar-operand forms issue at half of it (39.3)",
+                                      "= 256 CU x 4 SIMD x 32 lanes/clock x 2.4 GHz (a SIMD takes plain register-operand arithmetic from two wavefronts at a "
+                                      "time; compares, min/max, conversions, 3-operand integer forms and scalar-operand forms go one at a time, 39.3)",
                      "algorithmic_lane_ops_per_launch": alg_ops, "algorithmic_lane_ops_per_weight": alg_ops / (M * K),
                      "kernel": "sopk::search_kernel", "event_ms_per_launch": ev_ms},
         "roofline_hbm": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
