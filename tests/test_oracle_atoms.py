@@ -151,3 +151,25 @@ def test_block_normalise_hand_worked():
     d = si.normal_draws(1 << 12, 5)
     xb = A.block_normalise(d, 16).reshape(-1, 16)
     assert np.all(xb.max(axis=1) == 1.0) and np.all(np.abs(xb) <= 1.0)
+
+
+def test_midpoint_is_the_sum_of_the_halves():
+    """A code boundary is the binary64 mean of two neighbouring entries rounded once to binary32 (the oracle's definition).
+    It equals the binary32 sum of the entries' halves, which is how the GPU kernels form it: both are one rounding of
+    the same real number, because the binary64 mean is exact whenever its low bits can change the binary32 result.
+    Checked on random pairs of every relative magnitude, on neighbours in the last place and around powers of two."""
+    rng = np.random.default_rng(5)
+    n = 400000
+    a = (rng.standard_normal(n) * np.exp2(rng.integers(-40, 40, n))).astype(np.float32)
+    b = (rng.standard_normal(n) * np.exp2(rng.integers(-40, 40, n))).astype(np.float32)
+    # pairs a few units in the last place apart, and pairs straddling a power of two
+    c = np.nextafter(a, np.float32(np.inf), dtype=np.float32)
+    for k in range(3): c = np.nextafter(c, np.float32(np.inf), dtype=np.float32)
+    p2 = np.exp2(rng.integers(-30, 30, n)).astype(np.float32)
+    lo = np.nextafter(p2, np.float32(0), dtype=np.float32)
+    hi = np.nextafter(p2, np.float32(np.inf), dtype=np.float32)
+    for x, y in ((a, b), (a, c), (lo, hi), (lo, p2), (-a, b), (a, np.float32(2.0 ** -31) * b)):
+        mid = ((x.astype(np.float64) + y.astype(np.float64)) * 0.5).astype(np.float32)
+        half = np.float32(0.5)
+        summed = (half * x) + (half * y)                       # binary32 throughout
+        assert summed.dtype == np.float32 and np.array_equal(mid.view(np.uint32), summed.view(np.uint32))
