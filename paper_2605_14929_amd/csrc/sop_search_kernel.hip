@@ -1002,12 +1002,17 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
                         for (int j = 0; j < EPL / 4; ++j) codes[j] = pick1 ? codes1[j] : codes0[j];
                     }
                 } else if constexpr (METRIC == 1) {
-                    best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes));
+                    // (emit mode without a code plane, as when only the ranking scores are wanted: the pass that forms no codes)
+                    if (!EMIT || p.codes) best = finish_direct<LPB>(eval_direct<EPL, EMIT, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes));
+                    else best = finish_direct<LPB>(eval_direct<EPL, false, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes));
                     score[a] = best.dy > 0.0f ? best.ny * fabsf(best.ny) : 0.0f;
                     den[a] = best.dy > 0.0f ? best.dy : 1.0f;
                     raw = true;
                 } else {
-                    best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes), nsc);
+                    // (emit mode without a code plane, as when only the ranking scores are wanted: the pass that forms no codes
+                    // and reads no boundaries)
+                    if (!EMIT || p.codes) best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, EMIT>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes), nsc);
+                    else best = finish_residual<LPB, METRIC>(eval_residual<EPL, METRIC, false>(w, cb, ArrSrc<EPL>{gx, gboff}, gss, a, wide, codes), nsc);
                     // the residual form is accurate while the reconstruction carries a fair share of
                     // the block's norm; otherwise the whole wavefront recomputes this atom directly
                     if (__builtin_expect(__any(best.weak) != 0, 0)) {
