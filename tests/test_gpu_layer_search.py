@@ -127,6 +127,17 @@ def test_alphabets_of_more_than_eight_atoms(A):
             assert abs(res.acos_fitted[(a, p)] - v) <= 1e-6, (a, p)
             if v > best[1]: best = ("fitted", v)
     assert abs(res.acos - best[1]) <= 1e-6 and res.kind == best[0]
+    if A == 10:
+        # pairs of atoms only, the winner packed: the packed layer decodes to the reported cosine
+        r2 = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=(), pack=True)
+        assert r2.kind == "fixed" and np.array_equal(r2.acos_fixed, res.acos_fixed) and abs(r2.acos - fixed.max()) <= 1e-6
+        assert (r2.a, r2.b) == tuple(pairs[int(np.argmax(fixed))])
+        What = PK.reconstruct(r2.words.cpu().numpy().view(np.uint16), r2.payload.cpu().numpy(), r2.n_bits, g, M, K,
+                              r2.table_a, r2.table_b, ofmt, 0, 0, 4, 3, 8)
+        cw = np.tile(c.astype(np.float64), M).reshape(-1, g)
+        wb, hb = W.astype(np.float64).reshape(-1, g), What.astype(np.float64).reshape(-1, g)
+        num = (cw * wb * hb).sum(1); den = np.sqrt((cw * wb * wb).sum(1) * (cw * hb * hb).sum(1))
+        assert abs(np.where(den > 0, num / np.where(den > 0, den, 1), 1.0).mean() - r2.acos) <= 1e-6
 
 
 def test_calls_with_fewer_and_then_more_atoms_leave_no_state():
