@@ -167,13 +167,16 @@ def bench_issue(args):
     n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
     kinds = ["v_fmac_f32 (registers only)", "v_max_f32", "v_fma_f32 with a scalar-register operand", "v_cmp_lt_f32 + v_cndmask_b32",
              "v_mul_f32", "v_mad_u32_u24", "v_fma_f32 + v_max_f32 alternating", "v_add_f32", "v_and_b32", "v_add_u32", "v_lshrrev_b32",
-             "v_lshlrev_b32", "v_cvt_i32_f32", "v_med3_f32", "v_rcp_f32"]
-    iters = 4000
+             "v_lshlrev_b32", "v_cvt_i32_f32", "v_med3_f32", "v_rcp_f32",
+             "element pass, 12-byte look-ups (6 instructions per element)", "element pass, 8-byte look-ups (7 instructions per element)",
+             "element pass, no look-ups (7 instructions per element)", "element pass, no look-ups (6 instructions per element)"]
+    per_iter = {15: 96 * 6, 16: 96 * 7, 17: 96 * 7, 18: 96 * 6}          # vector instructions per lane and iteration (the other kinds: 64)
     out = torch.empty(n_cu * 8 * 256, dtype=torch.float32, device=dev)
     table = {}
     for kind, name in enumerate(kinds):
         row = {}
-        for wps in ((1, 2, 3, 4, 6, 8) if kind < 7 else (8,)):          # kinds 7..: the class only
+        iters = 4000 if kind < 15 else 400
+        for wps in ((1, 2, 3, 4, 6, 8) if kind < 7 else ((1, 2, 3, 4) if kind >= 15 else (8,))):     # kinds 7..14: the class only
             for _ in range(3):
                 ctx.issue_probe(kind, wps, iters, 1.0, 0.125, out)
             torch.cuda.synchronize()
@@ -185,9 +188,11 @@ def bench_issue(args):
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / reps
-            wave_instr = n_cu * 4 * wps * iters * 64.0
+            wave_instr = n_cu * 4 * wps * iters * float(per_iter.get(kind, 64))
             row[str(wps)] = {"ms": ms, "T_lane_ops_per_s": wave_instr * 64 / (ms * 1e-3) / 1e12,
                              "cycles_per_instruction_per_simd_at_2.4GHz": ms * 1e-3 * 2.4e9 * n_cu * 4 / wave_instr}
+            if kind >= 15:      # SIMD cycles per element of a pass (per weight and codebook in the search kernel)
+                row[str(wps)]["cycles_per_element_per_simd_at_2.4GHz"] = ms * 1e-3 * 2.4e9 * n_cu * 4 / (n_cu * 4 * wps * iters * 96.0)
         table[name] = row
     best = table[kinds[0]]["8"]["T_lane_ops_per_s"]
     result = {

@@ -372,11 +372,17 @@ sop_status sop_read_probe(sop_ctx* ctx, const void* x_dev, int64_t n_bytes, uint
  *        3 v_cmp_lt_f32 + v_cndmask_b32  4 v_mul_f32   5 v_mad_u32_u24   6 v_fma_f32 + v_max_f32 alternating
  *        7 v_add_f32  8 v_and_b32  9 v_add_u32  10 v_lshrrev_b32  11 v_lshlrev_b32  12 v_cvt_i32_f32  13 v_med3_f32
  *        14 v_rcp_f32  (7..14 tell an instruction's class; their values are not meant to be checked)
+ *   kinds 15..18: the element pass of the search kernel on its own (per iteration six passes over 16 elements: a
+ *        table look-up in LDS at a bin that differs from lane to lane, the choice between the two values, residual
+ *        fma, c*d, error fma, cosine-sum fma; iters * 96 elements per lane): 15 with 12-byte look-ups (boundary and
+ *        two values, 6 vector instructions per element), 16 with 8-byte look-ups (two values, the boundary is their
+ *        sum: 7 instructions; what the search kernel does), 17 and 18 the arithmetic of 16 and 15 on register values
+ *        without look-ups.  What LDS costs beside the arithmetic (values not meant to be checked).
  * a, b: the two operand values (chains start at (thread % 8) / 8 + chain number).
  * out_dev: DEVICE, n_cu * waves_per_simd * 256 floats, overwritten: the sum ((x0+x1)+(x2+x3))+((x4+x5)+(x6+x7))
  * of the lane's chain values.  waves_per_simd 1..8, iters 1..2^20.  Asynchronous.
  * *n_out (HOST, may be NULL) receives the number of floats written (threads launched). */
-#define SOP_ISSUE_PROBE_KINDS 15
+#define SOP_ISSUE_PROBE_KINDS 19
 sop_status sop_issue_probe(sop_ctx* ctx, int kind, int waves_per_simd, int iters, float a, float b,
                            float* out_dev, int* n_out, void* hip_stream);
 

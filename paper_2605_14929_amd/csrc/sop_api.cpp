@@ -910,7 +910,7 @@ extern "C" sop_status sop_issue_probe(sop_ctx* c, int kind, int waves_per_simd, 
 {
     if (!c) return SOP_EINVAL;
     if (kind < 0 || kind >= SOP_ISSUE_PROBE_KINDS || waves_per_simd < 1 || waves_per_simd > 8 || iters < 1 || iters > (1 << 20) || !out)
-        return fail(c, SOP_EINVAL, "sop_issue_probe: kind 0..14, waves_per_simd 1..8, iters 1..2^20, out not NULL");
+        return fail(c, SOP_EINVAL, "sop_issue_probe: kind 0..18, waves_per_simd 1..8, iters 1..2^20, out not NULL");
     if (reinterpret_cast<uintptr_t>(out) & 3u) return fail(c, SOP_EINVAL, "sop_issue_probe: misaligned pointer");
     // every SIMD is to hold exactly waves_per_simd wavefronts: one workgroup per compute unit with that many wavefronts
     // per SIMD (up to four), two such workgroups for six and eight, else workgroups of four wavefronts

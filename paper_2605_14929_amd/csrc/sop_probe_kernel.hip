@@ -118,6 +118,74 @@ __global__ __launch_bounds__(1024) void issue_probe_kernel(float* __restrict__ o
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
 }
 
+
+// Calibration kernel: the element pass of the search kernel on its own (kinds 15..18 of the issue probe).  Per
+// iteration a lane runs six passes ("atoms") over 16 elements held in registers: a table look-up in LDS at a bin that
+// differs from lane to lane (records of 33 words as in the search kernel, 256 bins), the choice between the two values
+// read, residual fma, c*d, error fma, cosine-sum fma.  It tells what the look-ups cost beside the arithmetic: LDS serves
+// 128 bytes a clock to the four SIMDs of a compute unit.
+//   MODE 0  12-byte look-up: boundary, value below, value above            (6 vector instructions per element)
+//   MODE 1   8-byte look-up: the two values, boundary = their sum          (7; what the search kernel does)
+//   MODE 2  no look-up, the arithmetic of MODE 1 on register values        (7)
+//   MODE 3  no look-up, the arithmetic of MODE 0 on register values        (6)
+// out[thread] = the three running sums added up (not meant to be checked: the table holds a pattern, not a codebook).
+#define SOPK_EP_BINS 256
+#define SOPK_EP_WORDS 33
+template <int MODE>
+__global__ __launch_bounds__(1024) void elem_probe_kernel(float* __restrict__ out, int iters, float fa, float fb)
+{
+    extern __shared__ float s_ep[];
+    for (int i = threadIdx.x; i < SOPK_EP_BINS * SOPK_EP_WORDS; i += blockDim.x) s_ep[i] = 0.25f + 0.001f * (float)(i % 97);
+    __syncthreads();
+    typedef __attribute__((address_space(3))) const float lds_cf;
+    const int lane = threadIdx.x & 63;
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)s_ep + 4u * SOPK_EP_WORDS * (uint32_t)((lane * 7) & 127);
+    float x[16], w[16], c[16];
+    uint32_t addr[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        x[i] = fa + 0.001f * (float)lane + 0.01f * (float)i; w[i] = x[i] + 0.5f; c[i] = fb;
+        addr[i] = base + 4u * SOPK_EP_WORDS * (uint32_t)((i * 37) & 63);          // bins (lane*7 & 127) + (i*37 & 63) < 256
+    }
+    const float ss = -fb;
+    float e0 = 0.0f, e1 = 0.0f, wd = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+        // (nothing below may be moved out of the loop: the compiler is told that the operands have changed)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(x[i]), "+v"(w[i]), "+v"(addr[i]));
+#pragma unroll
+        for (int a = 0; a < 6; ++a) {
+#pragma unroll
+            for (int i0 = 0; i0 < 16; i0 += 4) {
+                float thr[4], ylo[4], yhi[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = i0 + j;
+                    if (MODE <= 1) {
+                        lds_cf* rp = (lds_cf*)(size_t)addr[i];
+                        if (MODE == 0) thr[j] = rp[a];
+                        ylo[j] = rp[8 + a]; yhi[j] = rp[16 + a];
+                        if (MODE == 1) thr[j] = ylo[j] + yhi[j];
+                    } else {
+                        ylo[j] = c[i]; yhi[j] = w[(i + a + 1) & 15];
+                        thr[j] = MODE == 2 ? ylo[j] + yhi[j] : x[(i + a + 5) & 15];
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = i0 + j;
+                    const float yv = x[i] > thr[j] ? yhi[j] : ylo[j];
+                    const float d = __fmaf_rn(ss, yv, w[i]);
+                    const float cd = c[i] * d;
+                    if (i < 8) e0 = __fmaf_rn(cd, d, e0); else e1 = __fmaf_rn(cd, d, e1);
+                    wd = __fmaf_rn(cd, w[i], wd);
+                }
+            }
+        }
+    }
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = (e0 + e1) + wd;
+}
+
 }  // namespace sopk
 
 extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int n_threads, int iters, float a, float b, float* out, void* stream)
@@ -125,6 +193,16 @@ extern "C" hipError_t sopk_issue_probe_launch(int kind, int n_wg, int n_threads,
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((unsigned)n_wg), block((unsigned)n_threads);
 #define SOPK_IP(K) hipLaunchKernelGGL(sopk::issue_probe_kernel<K>, grid, block, 0, st, out, iters, a, b)
+    if (kind >= 15) {
+        const size_t lds = (size_t)SOPK_EP_BINS * SOPK_EP_WORDS * sizeof(float);
+        switch (kind) {
+        case 15: hipLaunchKernelGGL(sopk::elem_probe_kernel<0>, grid, block, lds, st, out, iters, a, b); break;
+        case 16: hipLaunchKernelGGL(sopk::elem_probe_kernel<1>, grid, block, lds, st, out, iters, a, b); break;
+        case 17: hipLaunchKernelGGL(sopk::elem_probe_kernel<2>, grid, block, lds, st, out, iters, a, b); break;
+        default: hipLaunchKernelGGL(sopk::elem_probe_kernel<3>, grid, block, lds, st, out, iters, a, b); break;
+        }
+        return hipGetLastError();
+    }
     switch (kind) {
     case 0: SOPK_IP(0); break;
     case 1: SOPK_IP(1); break;

@@ -11,10 +11,10 @@
 //
 // Every block is read from HBM exactly once.  LDS holds a table over uniform bins of the scaled
 // weight x: for every atom each bin contains at most one code boundary, so the nearest entry is a
-// table read and one compare.  A bin is a record of 33 words (boundary, lower value, upper value
-// and lower code of each of the 8 atoms, one word of padding): the odd stride puts the same field
-// of 32 consecutive bins into 32 different banks.  For scale words of up to 11 magnitude bits LDS
-// also holds the (scale, reciprocal) pair of every scale code.
+// table read and one compare.  A bin is a record of 33 words (boundary, half the lower value, half the
+// upper value and lower code of each of the 8 atoms, one word of padding; see read_rec for the halves):
+// the odd stride puts the same field of 32 consecutive bins into 32 different banks.  For scale words of
+// up to 11 magnitude bits LDS also holds (twice the scale, the scale's reciprocal) of every scale code.
 //
 // Atoms with equal endpoints form a scale group: they share the ideal scale, the scale code and the
 // scaled weights, which are computed once per group.

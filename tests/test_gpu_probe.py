@@ -67,7 +67,17 @@ def test_issue_probe_values(kind, a, b):
 
 
 def test_issue_probe_argument_errors():
-    for bad in ((15, 1, 1), (-1, 1, 1), (0, 0, 1), (0, 9, 1), (0, 1, 0)):
+    for bad in ((19, 1, 1), (-1, 1, 1), (0, 0, 1), (0, 9, 1), (0, 1, 0)):
         with pytest.raises(sop.SopError) as e:
             ctx().issue_probe(*bad)
         assert e.value.status == 1
+
+
+@pytest.mark.parametrize("kind", [15, 16, 17, 18])
+def test_element_pass_probe_runs_and_repeats(kind):
+    # the element-pass kinds hold a pattern, not a codebook: their sums are finite and the same on every run
+    import torch
+    a = ctx().issue_probe(kind, 3, 3, 0.3, 1.25).clone()
+    b = ctx().issue_probe(kind, 3, 3, 0.3, 1.25)
+    torch.cuda.synchronize()
+    assert torch.isfinite(a).all() and torch.equal(a, b)
