@@ -158,3 +158,50 @@ def test_calls_with_fewer_and_then_more_atoms_leave_no_state():
         r = run(n)
         if n == 4:
             assert r.acos_fitted == first.acos_fitted and np.array_equal(r.acos_fixed, first.acos_fixed) and r.acos == first.acos
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("SOP_RANDOM_LAYER_SEARCHES", "8"))))
+def test_random_layer_searches_on_one_context(seed):
+    """Random shapes, alphabets (1 to 12 atoms), sweeps, block sizes and scale words through sop_search_layer on the shared
+    context, each against the oracle's parts chained."""
+    import torch
+    rng = np.random.default_rng(6500 + seed)
+    g = int(rng.choice([8, 16, 32]))
+    M, K = int(rng.integers(4, 40)), g * int(rng.integers(8, 80))
+    if (M * (K // g)) % 4: M += 4 - M % 4                      # (whole float4s of scores: the batched ranking)
+    W = si.bf16_round(si.student_t_weights(M, K, float(rng.uniform(3, 8)), 6600 + seed, row_sigma=0.5, outlier_frac=0.001))
+    c = si.channel_norms(K, 1.0, 6700 + seed)
+    pool = [OA.nf(4), OA.sh(4), OA.sh(4, 1.2, 0.01), OA.nf(3), OA.sh(5), OA.negate(OA.nf(4)), OA.negate(OA.sh(4)), OA.sh(4, 2.0, -0.03),
+            OA.nf(5), OA.negate(OA.sh(5)), OA.negate(OA.nf(3)), OA.sh(3)]
+    A = int(rng.choice([1, 2, 3, 4, 6, 8, 9, 12]))
+    atoms = [OA.to_f32(pool[i]) for i in rng.permutation(len(pool))[:A]]
+    fmt = sop.fmt_by_name(str(rng.choice(["UE4M3", "S1E5M5", "E4M5", "UE5M7"])))
+    n_p = int(rng.integers(1 if A == 1 else 0, 4))
+    p_grid = tuple(sorted(float(x) for x in rng.choice([0.0, 30.0, 50.0, 70.0, 85.0, 95.0, 100.0], size=n_p, replace=False)))
+    bins = int(rng.choice([256, 1024]))
+    init = OA.to_f32(OA.nf(4))
+    Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    ct = torch.from_numpy(c).cuda()
+    res = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=p_grid, fit_iters=5, fit_bins=bins, fit_init=init)
+    ofmt = oracle_fmt(fmt)
+    pairs = np.array([(a, b) for a in range(A) for b in range(a + 1, A)], dtype=np.int32).reshape(-1, 2)
+    fixed = np.zeros(len(pairs))
+    r = ops.pair_search(W, c, atoms, g, ofmt, pairs=pairs[:1] if len(pairs) else None, want_codes=False)
+    for i0 in range(0, len(pairs), 28):
+        rr = ops.pair_search(W, c, atoms, g, ofmt, pairs=pairs[i0:i0 + 28], want_codes=False)
+        fixed[i0:i0 + 28] = rr.acos_pair[:len(pairs[i0:i0 + 28])]
+    assert np.max(np.abs(res.acos_fixed - fixed), initial=0.0) <= 1e-6
+    Nb = W.size // g
+    cands = [("fixed", float(v)) for v in fixed]
+    for a in range(A):
+        for p in p_grid:
+            _, pool_b, _ = PT.partition(r.blk_rank[a], PT.top_count(p, Nb), True)
+            h = DD.histogram(W, c, g, bins, block_mask=pool_b)
+            Lb = OA.to_f32(DD.fit(h, 16, 5, init.astype(np.float64))) if h.any() else init
+            if (a, p) not in res.acos_fitted:                  # dropped: the fitted codebook cannot serve as an atom
+                continue
+            v = float(ops.pair_search(W, c, [atoms[a], Lb], g, ofmt, want_codes=False).acos_pair[0])
+            assert abs(res.acos_fitted[(a, p)] - v) <= 1e-6, (a, p)
+            cands.append(("fitted", v))
+    best = max(cands, key=lambda t: t[1])
+    assert abs(res.acos - best[1]) <= 1e-6

@@ -2,6 +2,8 @@
 block sizes, scale words, codebooks of random sizes and values beside the named ones, metrics, pair subsets, layer
 shifts, both scale rules, search and emit mode, all on one context in a row (so that nothing a call leaves behind
 can change the next)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -35,7 +37,7 @@ def _random_codebook(rng):
     return OA.to_f32(L)
 
 
-@pytest.mark.parametrize("seed", range(36))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("SOP_RANDOM_CONFIGS", "36"))))     # (more seeds for a longer hunt)
 def test_random_configuration(seed):
     rng = np.random.default_rng(9000 + seed)
     g = int(rng.choice([8, 16, 16, 32, 64]))
