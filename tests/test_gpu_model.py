@@ -112,3 +112,52 @@ def test_two_atom_alphabet_goes_layer_by_layer():
         o = cx.pair_search(layers[i][0], layers[i][1], 16, fmt)
         torch.cuda.synchronize()
         assert np.array_equal(o.acos_pair.cpu().numpy()[:1], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i])
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("SOP_RANDOM_MODELS", "6"))))
+def test_random_lists_of_layers(seed):
+    """Random lists of layers (shapes with ragged strips, row strides, 1 to 40 layers, several layer shifts), alphabets of 1 to
+    8 atoms, block sizes, signed and unsigned scale words, metrics: every row of the table and every selector word against the
+    oracle, and bit for bit against the single call."""
+    import torch
+    rng = np.random.default_rng(7700 + seed)
+    pool = _alphabet() + [OA.to_f32(t) for t in (OA.nf(3), OA.sh(5), OA.negate(OA.sh(5)), OA.nf(5), np.array([-1.0, 0.0, 1.0]))]
+    A = int(rng.integers(1, 9))
+    tabs = [pool[i] for i in rng.permutation(len(pool))[:A]]
+    g = int(rng.choice([8, 16, 16, 32, 64]))
+    fmt = sop.fmt_by_name(str(rng.choice(["UE4M4", "E4M3", "UE4M6", "S1E5M5", "UE5M7"])))
+    metric = int(rng.choice([0, 0, 1, 2]))
+    bf16 = bool(rng.random() < 0.7)
+    cx = ctx()
+    cx.set_alphabet(tabs); cx.set_pairs(None)
+    P = A * (A - 1) // 2
+    n = int(rng.integers(1, 41))
+    host, layers, shifts = [], [], []
+    for l in range(n):
+        M, K = int(rng.integers(1, 24)), g * int(rng.integers(1, 40))
+        while K % 8: K += g
+        W = si.student_t_weights(M, K, float(rng.uniform(3, 8)), 7800 + 100 * seed + l, row_sigma=0.5)
+        if rng.random() < 0.1: W[:] = 0.0
+        if bf16: W = si.bf16_round(W)
+        c = si.channel_norms(K, 1.0, 7900 + 100 * seed + l)
+        Wt = torch.from_numpy(W).cuda()
+        if bf16: Wt = Wt.to(torch.bfloat16)
+        if rng.random() < 0.3:                                        # a row stride larger than K
+            buf = torch.zeros((M, K + 16), dtype=Wt.dtype, device="cuda")
+            buf[:, :K] = Wt
+            Wt = buf[:, :K]
+        host.append((W, c)); layers.append((Wt, torch.from_numpy(c).cuda())); shifts.append(int(rng.choice([0, 0, 1, -2, 3])))
+    tp, ta, sels = cx.pair_search_layers(layers, g, fmt, metric=metric, shifts=shifts, want_sel=P > 0)
+    torch.cuda.synchronize()
+    tp, ta = tp.cpu().numpy(), ta.cpu().numpy()
+    for l, (W, c) in enumerate(host):
+        ref = ops.pair_search(W, c, tabs, g, oracle_fmt(fmt), k=shifts[l], metric=metric, want_codes=False)
+        assert np.max(np.abs(ta[l] - ref.acos_atom)) <= 1e-6, l
+        if P:
+            assert np.max(np.abs(tp[l] - ref.acos_pair)) <= 1e-6, l
+            sw = sels[l].cpu().numpy()
+            assert np.array_equal(sw.view(np.uint16 if sw.dtype == np.int16 else np.uint32).astype(np.uint32), ref.sel_words), l
+        if l % 7 == 0:
+            o = cx.pair_search(layers[l][0], layers[l][1], g, fmt, k=shifts[l], metric=metric)
+            torch.cuda.synchronize()
+            assert np.array_equal(o.acos_atom.cpu().numpy(), ta[l]) and (P == 0 or np.array_equal(o.acos_pair.cpu().numpy()[:P], tp[l])), l
