@@ -105,3 +105,37 @@ def test_halved_table_values_and_entry_magnitudes():
     # neighbours more than 2^29 apart in magnitude, and entries exactly on powers of two
     sop.sop_check_alphabet([np.array([-1.0, -2.0 ** -31, 2.0 ** -3, 0.5], dtype=np.float32),
                             np.array([-1.0, -0.5, np.float32(0.5) + np.float32(2.0 ** -24), 1.0], dtype=np.float32)])
+
+
+def test_binding_structures_match_the_header(tmp_path):
+    """The ctypes mirrors of the header's structures have the header's sizes and field offsets (a C program that
+    includes include/sop.h prints them)."""
+    import subprocess
+    from paper_2605_14929_amd import binding as B
+    fields = {
+        "sop_scale_fmt": (B.ScaleFmt, ["sign_bits", "exp_bits", "man_bits", "container_bits", "bias", "max_code"]),
+        "sop_atom": (B._Atom, ["n_entries", "values"]),
+        "sop_outputs": (B._Outputs, ["acos_pair", "acos_atom", "sel_words", "scale_code", "codes", "blk_cos", "blk_err", "blk_rank"]),
+        "sop_layer": (B._Layer, None),
+        "sop_weight_fmt": (B.WeightFmt, ["exp_bits", "man_bits", "bias", "max_code"]),
+        "sop_layer_opts": (B._LayerOpts, ["n_p", "p_percent", "fit_entries", "fit_iters", "fit_bins", "fit_init", "weighted_fit", "fit_grid", "n_fit_grid", "pack"]),
+        "sop_layer_result": (B._LayerResult, ["kind", "a", "b", "j", "p_percent", "acos", "n_entries_b", "table_b", "acos_fixed", "acos_atom", "acos_fitted", "n_bits"]),
+    }
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sop.h"', 'int main(void) {']
+    for name, (_, fl) in fields.items():
+        lines.append(f'printf("{name} %zu\\n", sizeof({name}));')
+        for f in fl or []:
+            lines.append(f'printf("{name}.{f} %zu\\n", offsetof({name}, {f}));')
+    lines += ['printf("SOP_MAX_ATOMS %d\\nSOP_MAX_ENTRIES %d\\nSOP_LAYER_MAX_P %d\\nSOP_LAYER_MAX_ATOMS %d\\nSOP_LAYER_MAX_PAIRS %d\\n", '
+              'SOP_MAX_ATOMS, SOP_MAX_ENTRIES, SOP_LAYER_MAX_P, SOP_LAYER_MAX_ATOMS, SOP_LAYER_MAX_PAIRS);', 'return 0; }']
+    src = tmp_path / "sizes.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "sizes"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = dict(l.split() for l in subprocess.check_output([str(exe)], text=True).splitlines())
+    for name, (cls, fl) in fields.items():
+        assert int(got[name]) == C.sizeof(cls), name
+        for f in fl or []:
+            assert int(got[f"{name}.{f}"]) == getattr(cls, f).offset, (name, f)
+    assert (int(got["SOP_MAX_ATOMS"]), int(got["SOP_MAX_ENTRIES"]), int(got["SOP_LAYER_MAX_P"])) == (B.MAX_ATOMS, B.MAX_ENTRIES, B.LAYER_MAX_P)
+    assert (int(got["SOP_LAYER_MAX_ATOMS"]), int(got["SOP_LAYER_MAX_PAIRS"])) == (B.LAYER_MAX_ATOMS, B.LAYER_MAX_PAIRS)
