@@ -67,7 +67,7 @@ template <int LPB> __device__ __forceinline__ float group_sum(float v)
 // wave-uniform switches of the row loop
 struct Switches {
     int A;
-    uint32_t pair_mask, flip_mask, gid, unit_tpos, unit_tneg, wide, mirror, tiechk, selfsym;
+    uint32_t pair_mask, flip_mask, gid, unit_tpos, unit_tneg, wide, mirror, selfsym;
 };
 
 // round a non-negative fp32 to the scale word: nearest, ties to the lower code, saturating
@@ -760,7 +760,7 @@ __global__ __launch_bounds__(256 * OCC, 1) void search_kernel(const KParams p)
         }
         // The uniform switches below are re-read every row.  Left loop-invariant, each test would be
         // hoisted out of the loop as a 64-bit lane mask and the hundred-odd masks would spill.
-        Switches sw = {p.A, p.pair_mask, p.flip_mask, p.gid_w, p.unit_tpos, p.unit_tneg, p.wide_mask, p.mirror_mask, 0u, p.selfsym_mask};
+        Switches sw = {p.A, p.pair_mask, p.flip_mask, p.gid_w, p.unit_tpos, p.unit_tneg, p.wide_mask, p.mirror_mask, p.selfsym_mask};
         asm volatile("" : "+s"(sw.A), "+s"(sw.pair_mask), "+s"(sw.flip_mask), "+s"(sw.gid), "+s"(sw.unit_tpos), "+s"(sw.unit_tneg), "+s"(sw.wide));
         if constexpr (SIGNED) asm volatile("" : "+s"(sw.mirror), "+s"(sw.selfsym));
         const long long cm = m, cs = strip;
