@@ -201,7 +201,9 @@ __global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
             }
         }
     }
-    float nmax = -nmin;
+    // (0 - nmin, not -nmin: a wavefront without negative weights, or without work, must hand on +0; the bit pattern of -0
+    // would rank above every positive value in the unsigned maximum below and erase the copy's running value)
+    float nmax = 0.0f - nmin;
 #pragma unroll
     for (int st = 1; st < 64; st <<= 1) { pmax = fmaxf(pmax, __shfl_xor(pmax, st, 64)); nmax = fmaxf(nmax, __shfl_xor(nmax, st, 64)); }
     // workgroup maximum in LDS, then at most one atomic per workgroup and value, and only when it
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(256) void layer_max_kernel(const LsParams p)
     __syncthreads();
     if (threadIdx.x < 2) {
         const float v = fmaxf(fmaxf(s_m[threadIdx.x][0], s_m[threadIdx.x][1]), fmaxf(s_m[threadIdx.x][2], s_m[threadIdx.x][3]));
-        const unsigned int bits = __float_as_uint(v);          // non-negative floats order like their bit patterns
+        const unsigned int bits = __float_as_uint(v) & 0x7FFFFFFFu;   // non-negative floats order like their bit patterns
         // (the running maxima have SOP_K_LS_MAXREP copies, chosen by workgroup number: the first workgroups
         // all finish at once and all find the running value still low)
         unsigned int* mb = p.maxbits + 32 * (blockIdx.x & (SOP_K_LS_MAXREP - 1)) + threadIdx.x;   // copies 128 bytes apart

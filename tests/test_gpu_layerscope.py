@@ -113,3 +113,17 @@ def test_fp6_block_scaled_versus_fp8_layer_scaled_full_layer():
     full6 = float(o.blk_err.cpu().numpy().astype(np.float64).sum())
     assert abs(fp6 - full6) <= 1e-12 * full6
     assert fp6 < fp8[0]                                               # block-scaled FP6 wins at 1.5 bpw less
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_one_negative_weight_in_a_small_layer(bf16):
+    """A layer so small that many wavefronts of the maxima pass have no work, and whose weights are all positive but one:
+    the largest negative magnitude must reach the layer's scale wherever that weight sits (a wavefront without negative
+    weights once handed on -0, whose bit pattern erased the running maximum it was joined with)."""
+    M, K = 27, 1408
+    base = np.full((M, K), 1.0 / 1024, np.float32)
+    for r, c0 in ((0, 0), (5, 700), (13, 64), (26, 933), (26, 1407), (20, 3)):
+        W = base.copy(); W[r, c0] = -0.5
+        check(W, None, (3, 4, -1, -1), sop.fmt_by_name("UE4M4"), k=3, bf16=bf16)
+        check(-W, None, (4, 3, -1, -1), UE8M0, bf16=bf16)
+    check(base, None, (3, 4, -1, -1), sop.fmt_by_name("UE4M4"), k=3, bf16=bf16)          # no negative weight at all
