@@ -86,3 +86,23 @@ def test_random_configuration(seed):
                           pairs=None if pairs is None else np.asarray(pairs, dtype=np.int32), scale_rule=rule, want_codes=emit)
     P = len(all_pairs) if pairs is None else len(pairs)
     compare(gpu, ref, P, emit=emit)
+
+
+def test_more_scale_tables_than_the_context_keeps():
+    """The context keeps the (scale, reciprocal) tables of the 160 (format, shift) pairs used last; 420 distinct pairs in a
+    row, the first ones used again at the end: every search against the oracle."""
+    import torch
+    rng = np.random.default_rng(4711)
+    M, K, g = 6, 512, 16
+    W = si.bf16_round(si.student_t_weights(M, K, 4.0, 4712, row_sigma=0.5) * np.float32(0.25))
+    c = si.channel_norms(K, 1.0, 4713)
+    tabs = [OA.to_f32(OA.nf(4)), OA.to_f32(OA.sh(4)), OA.to_f32(OA.negate(OA.sh(4)))]
+    combos = [(w, x, y, bias, k) for w in (0, 1) for x in (4, 5) for y in (3, 4, 5) for bias in (5, 6, 7, 8, 9) for k in (-2, -1, 0, 1, 2, 3, 4)]
+    order = [combos[i] for i in rng.permutation(len(combos))]
+    order = order + order[:25]
+    assert len(set(order)) == 420
+    for (w, x, y, bias, k) in order:
+        fmt = sop.ScaleFmt(w, x, y, 16, bias, -1)
+        gpu = run_gpu(W, c, tabs, g, fmt, k=k, bf16=True, emit=False)
+        ref = ops.pair_search(W, c, tabs, g, oracle_fmt(fmt), k=k, want_codes=False)
+        compare(gpu, ref, 3, emit=False)
