@@ -6,7 +6,7 @@ import pytest
 import paper_2605_14929_amd as sop
 from oracle import pairsearch as ops
 import sop_inputs as si
-from gpu_util import run_gpu, compare, oracle_fmt, cached_config
+from gpu_util import run_gpu, compare, oracle_fmt, cached_config, ctx
 
 pytestmark = pytest.mark.gpu
 
@@ -137,3 +137,25 @@ def test_config4_fourteen_layers_full_size_through_the_model_wide_call():
             torch.cuda.synchronize()
             assert np.array_equal(o.acos_pair.cpu().numpy()[:15], tp[i]) and np.array_equal(o.acos_atom.cpu().numpy(), ta[i]), name
             assert torch.equal(o.sel_words, sels[i]), name
+
+
+def test_layer_of_more_than_128_steps_per_wavefront():
+    """A wavefront adds its lanes' sums to the workgroup's every 128 steps (a lane's 32-bit sums would overflow beyond);
+    no layer of the configurations is large enough to get there (it takes more than 403 M weights).  805 M weights
+    (49152 x 16384: twelve row-rotated, rescaled copies of one drawn block): every selector word and ACos against the oracle."""
+    import torch
+    K, Mb, reps = 16384, 4096, 12
+    base = si.bf16_round(si.student_t_weights(Mb, K, 4.0, 15001, row_sigma=0.5))
+    W = np.concatenate([np.roll(base, 7 * r, axis=0) * np.float32(2.0 ** (r % 3 - 1)) for r in range(reps)], axis=0)
+    c = si.channel_norms(K, 1.0, 15002)
+    tabs = sop.build_alphabet(["NF4", "SH4", "BOF4", "-NF4", "-SH4", "-BOF4"], bof_draws=si.normal_draws(1 << 18, 4242))
+    cx = ctx()
+    cx.set_alphabet(tabs); cx.set_pairs(None)
+    fmt = sop.fmt_by_name("UE4M4")
+    out = cx.pair_search(torch.from_numpy(W).cuda().to(torch.bfloat16), torch.from_numpy(c).cuda(), 16, fmt)
+    torch.cuda.synchronize()
+    assert W.size / 1024 / (torch.cuda.get_device_properties(0).multi_processor_count * 12) > 128
+    ref = ops.pair_search(W, c, tabs, 16, oracle_fmt(fmt), want_codes=False)
+    assert np.array_equal(out.sel_words.cpu().numpy().view(np.uint16).astype(np.uint32), ref.sel_words)
+    assert np.max(np.abs(out.acos_pair.cpu().numpy()[:15] - ref.acos_pair)) <= 1e-6
+    assert np.max(np.abs(out.acos_atom.cpu().numpy() - ref.acos_atom)) <= 1e-6
