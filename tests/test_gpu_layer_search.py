@@ -180,15 +180,22 @@ def test_random_layer_searches_on_one_context(seed):
     p_grid = tuple(sorted(float(x) for x in rng.choice([0.0, 30.0, 50.0, 70.0, 85.0, 95.0, 100.0], size=n_p, replace=False)))
     bins = int(rng.choice([256, 1024]))
     init = OA.to_f32(OA.nf(4))
+    metric = int(rng.choice([0, 0, 1, 2]))
+    weighted = bool(rng.random() < 0.7)
+    grid = None
+    if rng.random() < 0.35:
+        gv = OA.exmy_grid(*[(2, 3), (3, 3), (3, 2)][int(rng.integers(0, 3))])
+        grid = gv / np.abs(gv).max()
     Wt = torch.from_numpy(W).cuda().to(torch.bfloat16)
     ct = torch.from_numpy(c).cuda()
-    res = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=p_grid, fit_iters=5, fit_bins=bins, fit_init=init)
+    res = LSR.search_layer(ctx(), Wt, ct, g, fmt, atoms, p_grid=p_grid, fit_iters=5, fit_bins=bins, fit_init=init, metric=metric,
+                           weighted_fit=weighted, fit_grid=grid)
     ofmt = oracle_fmt(fmt)
     pairs = np.array([(a, b) for a in range(A) for b in range(a + 1, A)], dtype=np.int32).reshape(-1, 2)
     fixed = np.zeros(len(pairs))
-    r = ops.pair_search(W, c, atoms, g, ofmt, pairs=pairs[:1] if len(pairs) else None, want_codes=False)
+    r = ops.pair_search(W, c, atoms, g, ofmt, metric=metric, pairs=pairs[:1] if len(pairs) else None, want_codes=False)
     for i0 in range(0, len(pairs), 28):
-        rr = ops.pair_search(W, c, atoms, g, ofmt, pairs=pairs[i0:i0 + 28], want_codes=False)
+        rr = ops.pair_search(W, c, atoms, g, ofmt, metric=metric, pairs=pairs[i0:i0 + 28], want_codes=False)
         fixed[i0:i0 + 28] = rr.acos_pair[:len(pairs[i0:i0 + 28])]
     assert np.max(np.abs(res.acos_fixed - fixed), initial=0.0) <= 1e-6
     Nb = W.size // g
@@ -196,11 +203,13 @@ def test_random_layer_searches_on_one_context(seed):
     for a in range(A):
         for p in p_grid:
             _, pool_b, _ = PT.partition(r.blk_rank[a], PT.top_count(p, Nb), True)
-            h = DD.histogram(W, c, g, bins, block_mask=pool_b)
-            Lb = OA.to_f32(DD.fit(h, 16, 5, init.astype(np.float64))) if h.any() else init
+            h = DD.histogram(W, c if weighted else None, g, bins, block_mask=pool_b)
+            if not h.any(): Lb = init
+            elif grid is None: Lb = OA.to_f32(DD.fit(h, 16, 5, init.astype(np.float64)))
+            else: Lb = OA.to_f32(grid[DD.fit_grid(h, grid, 16)[0]])
             if (a, p) not in res.acos_fitted:                  # dropped: the fitted codebook cannot serve as an atom
                 continue
-            v = float(ops.pair_search(W, c, [atoms[a], Lb], g, ofmt, want_codes=False).acos_pair[0])
+            v = float(ops.pair_search(W, c, [atoms[a], Lb], g, ofmt, metric=metric, want_codes=False).acos_pair[0])
             assert abs(res.acos_fitted[(a, p)] - v) <= 1e-6, (a, p)
             cands.append(("fitted", v))
     best = max(cands, key=lambda t: t[1])
